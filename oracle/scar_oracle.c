@@ -1,0 +1,341 @@
+/*
+ * CPU oracle for the five steps of SCAR's checkpoint path.
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is the plain, slow statement of what each step
+ * computes, used only to check the GPU library (tests, the smoke check and the
+ * benchmark's CPU-baseline leg).  It shares no code, header or table with the GPU
+ * library and the GPU library never calls it.
+ *
+ * Notation follows the paper: x = live parameters, c (the paper's z) = running
+ * checkpoint, both cut into n_blocks blocks of block_len elements (the last block
+ * may be short); a block is one "parameter" of Section 4.3 / 5.1 (a matrix row, a
+ * shard).  K = blocks chosen for a checkpoint, S = blocks lost in a failure.
+ *
+ * Arithmetic: floating data are widened to double and everything is accumulated in
+ * double; integer tables are widened to int64 and results are exact.
+ *
+ * Every loop is over whole blocks in index order; the only threading is an OpenMP
+ * "parallel for" over independent blocks (thread count set by
+ * oracle_set_num_threads, default 1).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_I32 = 2 };
+enum { ORACLE_OK = 0, ORACLE_ERR_ARG = -1, ORACLE_ERR_INDEX = -2, ORACLE_ERR_NOMEM = -3 };
+
+typedef struct {
+  double sum;   /* float data: sum of squared differences; integer: (double)isum */
+  double norm;  /* float data: sqrt(sum) (Euclidean norm); integer: (double)isum */
+  int64_t isum; /* integer data: sum of absolute differences; float data: 0      */
+} oracle_norm;
+
+static int g_threads = 1;
+
+void oracle_set_num_threads(int n) { g_threads = n > 0 ? n : 1; }
+
+int oracle_get_num_threads(void) {
+#ifdef _OPENMP
+  return g_threads;
+#else
+  return 1;
+#endif
+}
+
+static size_t elem_size(int dtype) { return dtype == ORACLE_BF16 ? 2 : 4; }
+
+static int dtype_ok(int dtype) {
+  return dtype == ORACLE_F32 || dtype == ORACLE_BF16 || dtype == ORACLE_I32;
+}
+
+static uint64_t count_blocks(uint64_t n_elems, uint32_t block_len) {
+  return (n_elems + block_len - 1) / block_len;
+}
+
+/* Element j of a float-typed store, widened exactly to double.  bfloat16 is the
+ * upper half of an IEEE binary32, so its value is that of the float whose bit
+ * pattern is the 16 stored bits followed by 16 zero bits. */
+static double load_real(int dtype, const void *p, uint64_t j) {
+  if (dtype == ORACLE_F32) return (double)((const float *)p)[j];
+  uint32_t bits = (uint32_t)((const uint16_t *)p)[j] << 16;
+  float f;
+  memcpy(&f, &bits, sizeof f);
+  return (double)f;
+}
+
+/* [lo, hi) element range of block b. */
+static void block_range(uint64_t b, uint64_t n_elems, uint32_t block_len, uint64_t *lo,
+                        uint64_t *hi) {
+  *lo = b * (uint64_t)block_len;
+  *hi = *lo + block_len;
+  if (*hi > n_elems) *hi = n_elems;
+}
+
+/* Squared Euclidean distance between block b of x and of c (Appendix A.3 uses the
+ * Euclidean norm; squaring keeps the order of distances). */
+static double block_sqdist(int dtype, const void *x, const void *c, uint64_t lo, uint64_t hi) {
+  double s = 0.0;
+  for (uint64_t j = lo; j < hi; ++j) {
+    double d = load_real(dtype, x, j) - load_real(dtype, c, j);
+    s += d * d;
+  }
+  return s;
+}
+
+/* L1 distance between block b of two integer count tables.  For a row of topic
+ * counts whose total N is unchanged this is 2 * N * TV(x/N, c/N): twice the
+ * document-length-scaled total variation of Appendix C. */
+static int64_t block_l1(const int32_t *x, const int32_t *c, uint64_t lo, uint64_t hi) {
+  int64_t s = 0;
+  for (uint64_t j = lo; j < hi; ++j) {
+    int64_t d = (int64_t)x[j] - (int64_t)c[j];
+    s += d < 0 ? -d : d;
+  }
+  return s;
+}
+
+/* Index lists must be in range and without repeats (a repeat would count a block
+ * twice in the norm). */
+static int check_indices(const uint32_t *idx, uint32_t n_idx, uint64_t n_blocks) {
+  if (n_idx == 0) return ORACLE_OK;
+  if (!idx) return ORACLE_ERR_ARG;
+  uint8_t *seen = (uint8_t *)calloc(n_blocks ? n_blocks : 1, 1);
+  if (!seen) return ORACLE_ERR_NOMEM;
+  int rc = ORACLE_OK;
+  for (uint32_t i = 0; i < n_idx; ++i) {
+    if (idx[i] >= n_blocks || seen[idx[i]]) {
+      rc = ORACLE_ERR_INDEX;
+      break;
+    }
+    seen[idx[i]] = 1;
+  }
+  free(seen);
+  return rc;
+}
+
+/* Checkpoint step 1 (Section 4.3): distance of every block from its value in the
+ * running checkpoint.  scores: double[n_blocks] for float data (squared L2),
+ * int64_t[n_blocks] for integer tables (L1). */
+int oracle_block_scores(int dtype, const void *x, const void *c, uint64_t n_elems,
+                        uint32_t block_len, void *scores) {
+  if (!dtype_ok(dtype) || block_len == 0) return ORACLE_ERR_ARG;
+  if (n_elems == 0) return ORACLE_OK;
+  if (!x || !c || !scores) return ORACLE_ERR_ARG;
+  int64_t n_blocks = (int64_t)count_blocks(n_elems, block_len);
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+  for (int64_t b = 0; b < n_blocks; ++b) {
+    uint64_t lo, hi;
+    block_range((uint64_t)b, n_elems, block_len, &lo, &hi);
+    if (dtype == ORACLE_I32)
+      ((int64_t *)scores)[b] = block_l1((const int32_t *)x, (const int32_t *)c, lo, hi);
+    else
+      ((double *)scores)[b] = block_sqdist(dtype, x, c, lo, hi);
+  }
+  return ORACLE_OK;
+}
+
+/* ---- checkpoint step 3: the k blocks with the largest distances -------------- */
+
+typedef struct {
+  double f;
+  int64_t i;
+  uint32_t idx;
+} keyed;
+
+/* Larger score first; NaN counts as larger than every number; equal scores go to
+ * the lower block index. */
+static int cmp_real_desc(const void *pa, const void *pb) {
+  const keyed *a = (const keyed *)pa, *b = (const keyed *)pb;
+  int an = isnan(a->f), bn = isnan(b->f);
+  if (an != bn) return an ? -1 : 1;
+  if (!an) {
+    if (a->f > b->f) return -1;
+    if (a->f < b->f) return 1;
+  }
+  return a->idx < b->idx ? -1 : (a->idx > b->idx ? 1 : 0);
+}
+
+static int cmp_int_desc(const void *pa, const void *pb) {
+  const keyed *a = (const keyed *)pa, *b = (const keyed *)pb;
+  if (a->i > b->i) return -1;
+  if (a->i < b->i) return 1;
+  return a->idx < b->idx ? -1 : (a->idx > b->idx ? 1 : 0);
+}
+
+static int cmp_u32_asc(const void *pa, const void *pb) {
+  uint32_t a = *(const uint32_t *)pa, b = *(const uint32_t *)pb;
+  return a < b ? -1 : (a > b ? 1 : 0);
+}
+
+/* scores: double[n_blocks] (scores_are_int == 0) or int64_t[n_blocks].
+ * out_idx: k block indices, ascending. */
+int oracle_select_topk(int scores_are_int, const void *scores, uint32_t n_blocks, uint32_t k,
+                       uint32_t *out_idx) {
+  if (k > n_blocks) return ORACLE_ERR_ARG;
+  if (k == 0) return ORACLE_OK;
+  if (!scores || !out_idx) return ORACLE_ERR_ARG;
+  keyed *all = (keyed *)malloc((size_t)n_blocks * sizeof(keyed));
+  if (!all) return ORACLE_ERR_NOMEM;
+  for (uint32_t b = 0; b < n_blocks; ++b) {
+    all[b].idx = b;
+    all[b].f = scores_are_int ? 0.0 : ((const double *)scores)[b];
+    all[b].i = scores_are_int ? ((const int64_t *)scores)[b] : 0;
+  }
+  qsort(all, n_blocks, sizeof(keyed), scores_are_int ? cmp_int_desc : cmp_real_desc);
+  for (uint32_t i = 0; i < k; ++i) out_idx[i] = all[i].idx;
+  qsort(out_idx, k, sizeof(uint32_t), cmp_u32_asc);
+  free(all);
+  return ORACLE_OK;
+}
+
+/* Test helper: the largest total score any k-subset of n (n <= 24) blocks can have,
+ * found by trying every subset.  result: double (real scores) or int64_t. */
+int oracle_brute_force_topk(int scores_are_int, const void *scores, uint32_t n, uint32_t k,
+                            void *result) {
+  if (n > 24 || k > n || !scores || !result) return ORACLE_ERR_ARG;
+  double best_f = -INFINITY;
+  int64_t best_i = INT64_MIN;
+  for (uint32_t mask = 0; mask < (1u << n); ++mask) {
+    if ((uint32_t)__builtin_popcount(mask) != k) continue;
+    double sf = 0.0;
+    int64_t si = 0;
+    for (uint32_t b = 0; b < n; ++b)
+      if (mask >> b & 1u) {
+        if (scores_are_int)
+          si += ((const int64_t *)scores)[b];
+        else
+          sf += ((const double *)scores)[b];
+      }
+    if (sf > best_f) best_f = sf;
+    if (si > best_i) best_i = si;
+  }
+  if (scores_are_int)
+    *(int64_t *)result = best_i;
+  else
+    *(double *)result = best_f;
+  return ORACLE_OK;
+}
+
+/* Checkpoint step 4, the in-memory part: c_b <- x_b for b in K.  If staging is not
+ * NULL, row i of staging (block_len elements per row) also receives block idx[i]
+ * (the rows that would go to persistent storage). */
+int oracle_checkpoint_commit(int dtype, const void *x, void *c, uint64_t n_elems,
+                             uint32_t block_len, const uint32_t *idx, uint32_t n_idx,
+                             void *staging) {
+  if (!dtype_ok(dtype) || block_len == 0) return ORACLE_ERR_ARG;
+  if (n_idx == 0) return ORACLE_OK;
+  if (!x || !c) return ORACLE_ERR_ARG;
+  int rc = check_indices(idx, n_idx, count_blocks(n_elems, block_len));
+  if (rc) return rc;
+  size_t es = elem_size(dtype);
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+  for (int64_t i = 0; i < (int64_t)n_idx; ++i) {
+    uint64_t lo, hi;
+    block_range(idx[i], n_elems, block_len, &lo, &hi);
+    memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo) * es);
+    if (staging)
+      memcpy((char *)staging + (uint64_t)i * block_len * es, (const char *)x + lo * es,
+             (hi - lo) * es);
+  }
+  return ORACLE_OK;
+}
+
+/* Size of the perturbation a recovery of the blocks in idx causes (Appendix A.3):
+ * ||c_S - x_S||.  idx == NULL means every block (full recovery, ||c - x||).
+ * Float data: Euclidean.  Integer tables: sum of the per-block L1 distances (a
+ * positive combination of per-row norms, Appendix C). */
+int oracle_perturbation_norm(int dtype, const void *x, const void *c, uint64_t n_elems,
+                             uint32_t block_len, const uint32_t *idx, uint32_t n_idx,
+                             oracle_norm *out) {
+  if (!dtype_ok(dtype) || block_len == 0 || !out) return ORACLE_ERR_ARG;
+  uint64_t n_blocks = count_blocks(n_elems, block_len);
+  int64_t m = idx ? (int64_t)n_idx : (int64_t)n_blocks;
+  out->sum = 0.0;
+  out->norm = 0.0;
+  out->isum = 0;
+  if (m == 0) return ORACLE_OK;
+  if (!x || !c) return ORACLE_ERR_ARG;
+  if (idx) {
+    int rc = check_indices(idx, n_idx, n_blocks);
+    if (rc) return rc;
+  }
+  double *fpart = (double *)calloc((size_t)m, sizeof(double));
+  int64_t *ipart = (int64_t *)calloc((size_t)m, sizeof(int64_t));
+  if (!fpart || !ipart) {
+    free(fpart);
+    free(ipart);
+    return ORACLE_ERR_NOMEM;
+  }
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+  for (int64_t i = 0; i < m; ++i) {
+    uint64_t lo, hi;
+    block_range(idx ? idx[i] : (uint64_t)i, n_elems, block_len, &lo, &hi);
+    if (dtype == ORACLE_I32)
+      ipart[i] = block_l1((const int32_t *)c, (const int32_t *)x, lo, hi);
+    else
+      fpart[i] = block_sqdist(dtype, c, x, lo, hi);
+  }
+  double fs = 0.0;
+  int64_t is = 0;
+  for (int64_t i = 0; i < m; ++i) {
+    fs += fpart[i];
+    is += ipart[i];
+  }
+  free(fpart);
+  free(ipart);
+  if (dtype == ORACLE_I32) {
+    out->isum = is;
+    out->sum = (double)is;
+    out->norm = (double)is;
+  } else {
+    out->sum = fs;
+    out->norm = sqrt(fs);
+  }
+  return ORACLE_OK;
+}
+
+/* Partial recovery (Section 4.1): x_b <- c_b for the lost blocks b in S and nothing
+ * else.  If norm_out is not NULL it receives the perturbation ||c_S - x_S|| measured
+ * on x as it was before the overwrite. */
+int oracle_partial_recover(int dtype, void *x, const void *c, uint64_t n_elems,
+                           uint32_t block_len, const uint32_t *lost, uint32_t n_lost,
+                           oracle_norm *norm_out) {
+  if (!dtype_ok(dtype) || block_len == 0) return ORACLE_ERR_ARG;
+  if (norm_out) {
+    if (n_lost == 0) {
+      norm_out->sum = norm_out->norm = 0.0;
+      norm_out->isum = 0;
+    } else {
+      int rc = oracle_perturbation_norm(dtype, x, c, n_elems, block_len, lost, n_lost, norm_out);
+      if (rc) return rc;
+    }
+  }
+  if (n_lost == 0) return ORACLE_OK;
+  if (!x || !c) return ORACLE_ERR_ARG;
+  int rc = check_indices(lost, n_lost, count_blocks(n_elems, block_len));
+  if (rc) return rc;
+  size_t es = elem_size(dtype);
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+  for (int64_t i = 0; i < (int64_t)n_lost; ++i) {
+    uint64_t lo, hi;
+    block_range(lost[i], n_elems, block_len, &lo, &hi);
+    memcpy((char *)x + lo * es, (const char *)c + lo * es, (hi - lo) * es);
+  }
+  return ORACLE_OK;
+}
+
+/* The lost set as an index list: ascending indices b with mask[b] != 0. */
+int oracle_mask_to_indices(const uint8_t *mask, uint32_t n_blocks, uint32_t *out_idx,
+                           uint32_t *out_count) {
+  if (!out_count || (n_blocks && (!mask || !out_idx))) return ORACLE_ERR_ARG;
+  uint32_t m = 0;
+  for (uint32_t b = 0; b < n_blocks; ++b)
+    if (mask[b]) out_idx[m++] = b;
+  *out_count = m;
+  return ORACLE_OK;
+}

@@ -1,0 +1,448 @@
+"""Pins for the CPU oracle: it is checked against things other than itself - closed
+forms, the identities the paper proves (Theorems 4.1 and 4.2, Appendix A.3/A.4),
+brute force over all subsets on tiny inputs, special cases and a few values worked out
+by hand - chosen so that a dropped term, a wrong sign, a shifted block boundary or a
+swapped operand fails at least one of them.  CPU only.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import F32, BF16, I32
+
+
+def rng_of(seed):
+    return np.random.default_rng(seed)
+
+
+# --------------------------------------------------------------------------- scores
+
+@pytest.mark.parametrize("n_elems,L", [(40, 8), (45, 8), (7, 1), (5, 64), (1000, 100)])
+def test_scores_closed_form_constant_offset_per_block(n_elems, L):
+    # x = c + a_b with a_b a power of two: every difference is exact in fp32, so
+    # s_b = (elements in block b) * a_b^2 exactly, short tail block included.
+    nb = oracle.n_blocks_of(n_elems, L)
+    c = rng_of(1).integers(-8, 8, size=n_elems).astype(np.float32)
+    a = 2.0 ** rng_of(2).integers(-6, 6, size=nb)
+    x = (c + np.repeat(a, L)[:n_elems]).astype(np.float32)
+    s = oracle.block_scores(F32, x, c, L)
+    lens = np.minimum(L, n_elems - np.arange(nb) * L)
+    assert s.dtype == np.float64
+    np.testing.assert_array_equal(s, lens * a * a)
+
+
+def test_scores_zero_when_unchanged_and_symmetric():
+    x = rng_of(3).normal(size=300).astype(np.float32)
+    c = rng_of(4).normal(size=300).astype(np.float32)
+    np.testing.assert_array_equal(oracle.block_scores(F32, x, x.copy(), 7), np.zeros(43))
+    np.testing.assert_array_equal(oracle.block_scores(F32, x, c, 7), oracle.block_scores(F32, c, x, 7))
+
+
+def test_scores_single_changed_element_lands_in_its_block_only():
+    L, nb = 5, 9
+    for j in (0, 4, 5, 22, 44):
+        c = np.zeros(L * nb, dtype=np.float32)
+        x = c.copy()
+        x[j] = -3.0
+        s = oracle.block_scores(F32, x, c, L)
+        want = np.zeros(nb)
+        want[j // L] = 9.0
+        np.testing.assert_array_equal(s, want)
+
+
+def test_scores_hand_worked_values():
+    # blocks of 2: (3,4) -> 25 ; (1,-1) vs (0,1) -> 1+4 = 5 ; tail (0.5) vs (-0.5) -> 1
+    x = np.array([3, 4, 1, -1, 0.5], dtype=np.float32)
+    c = np.array([0, 0, 0, 1, -0.5], dtype=np.float32)
+    np.testing.assert_array_equal(oracle.block_scores(F32, x, c, 2), [25.0, 5.0, 1.0])
+
+
+def test_scores_accumulate_in_double():
+    # 1 + 2^-30 squared differences: a float32 accumulator would lose the small terms.
+    L = 1 << 12
+    c = np.zeros(L, dtype=np.float32)
+    x = np.full(L, 2.0 ** -15, dtype=np.float32)
+    x[0] = 1.0
+    s = oracle.block_scores(F32, x, c, L)
+    assert s[0] == 1.0 + (L - 1) * 2.0 ** -30
+
+
+def test_scores_sum_equals_flat_squared_distance():
+    x = rng_of(5).normal(size=12345).astype(np.float32)
+    c = rng_of(6).normal(size=12345).astype(np.float32)
+    d = x.astype(np.float64) - c.astype(np.float64)
+    s = oracle.block_scores(F32, x, c, 100)
+    assert math.isclose(s.sum(), float(d @ d), rel_tol=1e-13)
+    ref = np.add.reduceat(d * d, np.arange(0, 12345, 100))
+    np.testing.assert_allclose(s, ref, rtol=1e-13)
+
+
+def test_scores_bf16_bits_decode_exactly():
+    # 0x3F80 = 1.0, 0x3F00 = 0.5, 0xC000 = -2.0, 0x0000 = 0, 0x4049 = 3.140625
+    x = np.array([0x3F80, 0x3F80, 0xC000, 0x4049], dtype=np.uint16)
+    c = np.array([0x3F00, 0x3F00, 0x3F80, 0x0000], dtype=np.uint16)
+    s = oracle.block_scores(BF16, x, c, 2)
+    np.testing.assert_array_equal(s, [0.5, 9.0 + 3.140625 ** 2])
+
+
+def test_scores_int_l1_closed_form_and_extremes():
+    L, nb = 50, 6
+    c = rng_of(7).integers(0, 1000, size=L * nb).astype(np.int32)
+    x = c.copy()
+    want = np.zeros(nb, dtype=np.int64)
+    for b, (m, t) in enumerate([(0, 0), (1, 50), (3, 7), (2, 1), (5, 10), (7, 49)]):
+        cols = rng_of(10 + b).choice(L, size=t, replace=False)
+        sign = rng_of(20 + b).choice([-1, 1], size=t)
+        x[b * L + cols] += (sign * m).astype(np.int32)
+        want[b] = m * t
+    s = oracle.block_scores(I32, x, c, L)
+    assert s.dtype == np.int64
+    np.testing.assert_array_equal(s, want)
+    # no 32-bit wrap: max - min = 2^32 - 1 per element
+    hi = np.full(3, np.iinfo(np.int32).max, dtype=np.int32)
+    lo = np.full(3, np.iinfo(np.int32).min, dtype=np.int32)
+    np.testing.assert_array_equal(oracle.block_scores(I32, hi, lo, 3), [3 * (2 ** 32 - 1)])
+    np.testing.assert_array_equal(oracle.block_scores(I32, lo, hi, 2), [2 * (2 ** 32 - 1), 2 ** 32 - 1])
+
+
+def test_scores_int_row_moves_are_twice_scaled_total_variation():
+    # a row of topic counts with N tokens; moving m tokens between topics changes the
+    # length-scaled total variation N * (1/2) sum |x/N - c/N| by m, and L1 by 2m.
+    c = np.array([5, 0, 7, 8], dtype=np.int32)
+    x = np.array([3, 2, 7, 8], dtype=np.int32)     # 2 tokens moved topic 0 -> 1
+    n_tok = c.sum()
+    tv_scaled = n_tok * 0.5 * np.abs(x / n_tok - c / n_tok).sum()
+    s = oracle.block_scores(I32, x, c, 4)
+    assert s[0] == 4 and math.isclose(2 * tv_scaled, 4.0)
+
+
+# --------------------------------------------------------------------------- top-k
+
+def python_topk(scores, k):
+    order = sorted(range(len(scores)), key=lambda b: (-scores[b], b))
+    return sorted(order[:k])
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_topk_maximises_total_score_over_all_subsets(seed):
+    r = rng_of(100 + seed)
+    n = int(r.integers(1, 12))
+    scores = r.integers(0, 5, size=n).astype(np.float64) if seed % 2 else r.random(n)
+    for k in range(n + 1):
+        idx = oracle.select_topk(scores, k)
+        assert len(idx) == k and len(set(idx.tolist())) == k
+        best = max((sum(scores[list(sub)]) for sub in itertools.combinations(range(n), k)))
+        assert math.isclose(scores[idx].sum(), best, rel_tol=1e-12, abs_tol=0)
+        if k:
+            assert math.isclose(oracle.brute_force_topk(scores, k), best, rel_tol=1e-12)
+        np.testing.assert_array_equal(idx, python_topk(scores.tolist(), k))
+
+
+def test_topk_int_scores_brute_force_and_ties():
+    scores = np.array([4, 9, 4, 4, 0, 9, 1, 4], dtype=np.int64)
+    for k in range(9):
+        idx = oracle.select_topk(scores, k)
+        best = max(sum(int(scores[i]) for i in sub) for sub in itertools.combinations(range(8), k))
+        assert int(scores[idx].sum()) == best
+        if k:
+            assert oracle.brute_force_topk(scores, k) == best
+    # k = 4: both 9s, then the two lowest-index 4s
+    np.testing.assert_array_equal(oracle.select_topk(scores, 4), [0, 1, 2, 5])
+    np.testing.assert_array_equal(oracle.select_topk(scores, 3), [0, 1, 5])
+
+
+def test_topk_all_equal_takes_lowest_indices_and_edges():
+    s = np.full(10, 2.5)
+    np.testing.assert_array_equal(oracle.select_topk(s, 4), [0, 1, 2, 3])
+    np.testing.assert_array_equal(oracle.select_topk(np.zeros(6, dtype=np.int64), 2), [0, 1])
+    assert oracle.select_topk(s, 0).size == 0
+    np.testing.assert_array_equal(oracle.select_topk(s, 10), np.arange(10))
+    with pytest.raises(oracle.OracleError):
+        oracle.select_topk(s, 11)
+
+
+def test_topk_output_ascending_and_matches_stable_argsort():
+    s = rng_of(7).integers(0, 50, size=5000).astype(np.float64)
+    for k in (1, 17, 2500, 4999):
+        idx = oracle.select_topk(s, k)
+        assert np.all(np.diff(idx.astype(np.int64)) > 0)
+        ref = np.sort(np.argsort(-s, kind="stable")[:k])
+        np.testing.assert_array_equal(idx, ref)
+
+
+def test_topk_permutation_equivariance_distinct_scores():
+    r = rng_of(8)
+    s = r.permutation(200).astype(np.float64)
+    perm = r.permutation(200)
+    a = set(oracle.select_topk(s, 30).tolist())
+    b = oracle.select_topk(s[perm], 30)          # block j of the permuted store is block perm[j]
+    assert a == set(perm[b].tolist())
+
+
+def test_topk_nan_and_inf_order():
+    s = np.array([1.0, np.inf, np.nan, 5.0, -0.0, 0.0, np.nan])
+    np.testing.assert_array_equal(oracle.select_topk(s, 1), [2])
+    np.testing.assert_array_equal(oracle.select_topk(s, 2), [2, 6])
+    np.testing.assert_array_equal(oracle.select_topk(s, 3), [1, 2, 6])
+    np.testing.assert_array_equal(oracle.select_topk(s, 4), [1, 2, 3, 6])
+    # -0 and +0 tie: lower index first
+    np.testing.assert_array_equal(oracle.select_topk(s, 6), [0, 1, 2, 3, 4, 6])
+
+
+# --------------------------------------------------------------------------- commit
+
+def small_store(seed, n_elems=203, dtype=F32):
+    r = rng_of(seed)
+    if dtype == I32:
+        c = r.integers(0, 100, size=n_elems).astype(np.int32)
+        x = (c + r.integers(-3, 4, size=n_elems)).astype(np.int32)
+    elif dtype == BF16:
+        c = (r.integers(0, 1 << 15, size=n_elems) & 0x7F7F).astype(np.uint16)
+        x = (r.integers(0, 1 << 15, size=n_elems) & 0x7F7F).astype(np.uint16)
+    else:
+        c = r.normal(size=n_elems).astype(np.float32)
+        x = (c + r.normal(size=n_elems) * 0.1).astype(np.float32)
+    return x, c
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16, I32])
+def test_commit_all_blocks_makes_checkpoint_equal_x_and_norm_zero(dtype):
+    x, c = small_store(11, dtype=dtype)
+    L = 10
+    nb = oracle.n_blocks_of(x.size, L)
+    x0 = x.copy()
+    oracle.checkpoint_commit(dtype, x, c, L, np.arange(nb))
+    np.testing.assert_array_equal(c, x)
+    np.testing.assert_array_equal(x, x0)
+    s, nrm, isum = oracle.perturbation_norm(dtype, x, c, L)
+    assert s == 0.0 and nrm == 0.0 and isum == 0
+
+
+@pytest.mark.parametrize("dtype", [F32, I32])
+def test_commit_touches_only_chosen_blocks_and_fills_staging(dtype):
+    x, c = small_store(12, dtype=dtype)
+    L = 10
+    nb = oracle.n_blocks_of(x.size, L)           # 21 blocks, tail of 3
+    idx = np.array([20, 3, 7], dtype=np.uint32)  # unsorted on purpose, includes the tail
+    c0, x0 = c.copy(), x.copy()
+    staging = np.full(len(idx) * L, 77, dtype=x.dtype)
+    oracle.checkpoint_commit(dtype, x, c, L, idx, staging)
+    np.testing.assert_array_equal(x, x0)
+    for b in range(nb):
+        lo, hi = b * L, min(x.size, (b + 1) * L)
+        np.testing.assert_array_equal(c[lo:hi], x0[lo:hi] if b in idx else c0[lo:hi])
+    for i, b in enumerate(idx):
+        lo, hi = b * L, min(x.size, (b + 1) * L)
+        np.testing.assert_array_equal(staging[i * L:i * L + hi - lo], x0[lo:hi])
+    np.testing.assert_array_equal(staging[3:L], 77)   # row 0 holds the short tail: rest untouched
+
+
+def test_commit_subtracts_exactly_the_chosen_scores():
+    x, c = small_store(13, n_elems=400)
+    L = 16
+    s0 = oracle.block_scores(F32, x, c, L)
+    idx = oracle.select_topk(s0, 6)
+    oracle.checkpoint_commit(F32, x, c, L, idx)
+    s1 = oracle.block_scores(F32, x, c, L)
+    want = s0.copy()
+    want[idx] = 0.0
+    np.testing.assert_array_equal(s1, want)
+
+
+def test_priority_commit_minimises_distance_to_checkpoint_over_all_subsets():
+    # Saving the k most-changed blocks leaves the smallest ||x - c|| any k blocks can.
+    x, c = small_store(14, n_elems=9 * 4)
+    L, nb, k = 4, 9, 3
+    s0 = oracle.block_scores(F32, x, c, L)
+    idx = oracle.select_topk(s0, k)
+    c1 = c.copy()
+    oracle.checkpoint_commit(F32, x, c1, L, idx)
+    got = oracle.perturbation_norm(F32, x, c1, L)[0]
+    best = math.inf
+    for sub in itertools.combinations(range(nb), k):
+        c2 = c.copy()
+        oracle.checkpoint_commit(F32, x, c2, L, np.array(sub, dtype=np.uint32))
+        best = min(best, oracle.perturbation_norm(F32, x, c2, L)[0])
+    assert math.isclose(got, best, rel_tol=1e-12)
+
+
+def test_index_lists_are_validated():
+    x, c = small_store(15)
+    with pytest.raises(oracle.OracleError):
+        oracle.checkpoint_commit(F32, x, c, 10, np.array([1, 1], dtype=np.uint32))
+    with pytest.raises(oracle.OracleError):
+        oracle.checkpoint_commit(F32, x, c, 10, np.array([21], dtype=np.uint32))
+    with pytest.raises(oracle.OracleError):
+        oracle.partial_recover(F32, x, c, 10, np.array([0, 5, 0], dtype=np.uint32))
+    with pytest.raises(oracle.OracleError):
+        oracle.perturbation_norm(F32, x, c, 10, np.array([99], dtype=np.uint32))
+
+
+# --------------------------------------------------------------------------- recovery
+
+@pytest.mark.parametrize("dtype", [F32, BF16, I32])
+def test_recover_empty_lost_set_changes_nothing(dtype):
+    x, c = small_store(21, dtype=dtype)
+    x0, c0 = x.copy(), c.copy()
+    s, nrm, isum = oracle.partial_recover(dtype, x, c, 10, np.zeros(0, dtype=np.uint32))
+    np.testing.assert_array_equal(x, x0)
+    np.testing.assert_array_equal(c, c0)
+    assert (s, nrm, isum) == (0.0, 0.0, 0)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16, I32])
+def test_recover_all_is_full_recovery_and_idempotent(dtype):
+    x, c = small_store(22, dtype=dtype)
+    L = 10
+    nb = oracle.n_blocks_of(x.size, L)
+    full = oracle.perturbation_norm(dtype, x, c, L)
+    c0 = c.copy()
+    got = oracle.partial_recover(dtype, x, c, L, np.arange(nb))
+    assert got == full and full[0] > 0
+    np.testing.assert_array_equal(x, c)
+    np.testing.assert_array_equal(c, c0)
+    assert oracle.partial_recover(dtype, x, c, L, np.arange(nb)) == (0.0, 0.0, 0)
+
+
+def test_recover_touches_only_lost_blocks_and_reads_x_before_overwrite():
+    x, c = small_store(23)
+    L = 10
+    nb = oracle.n_blocks_of(x.size, L)
+    lost = np.array([0, 20, 9], dtype=np.uint32)
+    x0, c0 = x.copy(), c.copy()
+    d = c0.astype(np.float64) - x0.astype(np.float64)
+    want = sum(float(d[b * L:(b + 1) * L] @ d[b * L:(b + 1) * L]) for b in lost)
+    s, nrm, isum = oracle.partial_recover(F32, x, c, L, lost)
+    assert math.isclose(s, want, rel_tol=1e-13) and math.isclose(nrm, math.sqrt(want), rel_tol=1e-13)
+    assert isum == 0
+    for b in range(nb):
+        lo, hi = b * L, min(x.size, (b + 1) * L)
+        np.testing.assert_array_equal(x[lo:hi], c0[lo:hi] if b in lost else x0[lo:hi])
+    np.testing.assert_array_equal(c, c0)
+
+
+# --------------------------------------------------------------------------- norm
+
+def test_norm_hand_worked_values():
+    # one block (3,4): Euclidean 5.  Two blocks (3,4),(12,0) -> sqrt(169) = 13.
+    c = np.array([3, 4, 12, 0], dtype=np.float32)
+    x = np.zeros(4, dtype=np.float32)
+    assert oracle.perturbation_norm(F32, x, c, 2, [0]) == (25.0, 5.0, 0)
+    assert oracle.perturbation_norm(F32, x, c, 2) == (169.0, 13.0, 0)
+    assert oracle.perturbation_norm(F32, x, c, 2, []) == (0.0, 0.0, 0)
+    # integer table: plain sum of absolute differences, no square root
+    ci = np.array([3, -4, 12, 0, 1], dtype=np.int32)
+    xi = np.array([0, 0, 10, 5, 1], dtype=np.int32)
+    assert oracle.perturbation_norm(I32, xi, ci, 2) == (14.0, 14.0, 14)
+    assert oracle.perturbation_norm(I32, xi, ci, 2, [1, 2]) == (7.0, 7.0, 7)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16, I32])
+def test_partial_perturbation_never_exceeds_full(dtype):
+    # Theorem 4.1 (with the <= of its proof).
+    x, c = small_store(31, n_elems=997, dtype=dtype)
+    L = 13
+    nb = oracle.n_blocks_of(x.size, L)
+    full = oracle.perturbation_norm(dtype, x, c, L)[1]
+    for seed in range(20):
+        r = rng_of(seed)
+        lost = r.choice(nb, size=int(r.integers(0, nb + 1)), replace=False)
+        assert oracle.perturbation_norm(dtype, x, c, L, lost)[1] <= full
+    assert oracle.perturbation_norm(dtype, x, c, L, np.arange(nb))[1] == full
+
+
+@pytest.mark.parametrize("dtype", [F32, I32])
+def test_norm_is_additive_over_any_partition_of_blocks(dtype):
+    # Appendix A.4: ||d_S||^2 is a sum over the lost coordinates, so over a partition of
+    # the blocks the squared (float) or L1 (integer) norms add up to the full one.
+    x, c = small_store(32, n_elems=1203, dtype=dtype)
+    L = 10
+    nb = oracle.n_blocks_of(x.size, L)
+    full = oracle.perturbation_norm(dtype, x, c, L)
+    parts = np.array_split(rng_of(5).permutation(nb), 7)
+    tot = [oracle.perturbation_norm(dtype, x, c, L, p) for p in parts]
+    assert math.isclose(sum(t[0] for t in tot), full[0], rel_tol=1e-12)
+    assert sum(t[2] for t in tot) == full[2]
+
+
+def test_expected_partial_perturbation_is_p_times_full_exactly_over_all_subsets():
+    # Theorem 4.2: E||d'||^2 = p ||d||^2 when a uniformly random fraction p is lost.
+    # Averaging over *all* subsets of size m of n blocks makes the expectation exact.
+    x, c = small_store(33, n_elems=8 * 3)
+    L, nb = 3, 8
+    full = oracle.perturbation_norm(F32, x, c, L)[0]
+    for m in (1, 2, 4, 7):
+        vals = [oracle.perturbation_norm(F32, x, c, L, np.array(sub, dtype=np.uint32))[0]
+                for sub in itertools.combinations(range(nb), m)]
+        assert math.isclose(np.mean(vals), (m / nb) * full, rel_tol=1e-12)
+
+
+def test_expected_partial_perturbation_random_masks():
+    x, c = small_store(34, n_elems=4000)
+    L = 8
+    nb = 500
+    full = oracle.perturbation_norm(F32, x, c, L)[0]
+    p = 0.25
+    r = rng_of(9)
+    vals = []
+    for _ in range(400):
+        lost = oracle.mask_to_indices(r.random(nb) < p)
+        vals.append(oracle.perturbation_norm(F32, x, c, L, lost)[0])
+    assert abs(np.mean(vals) / (p * full) - 1.0) < 0.02
+
+
+def test_norm_consistent_with_scores_and_with_commit():
+    x, c = small_store(35, n_elems=640)
+    L = 16
+    s0 = oracle.block_scores(F32, x, c, L)
+    lost = np.array([1, 5, 6, 30, 39], dtype=np.uint32)
+    assert math.isclose(oracle.perturbation_norm(F32, x, c, L, lost)[0], s0[lost].sum(), rel_tol=1e-13)
+    K = oracle.select_topk(s0, 10)
+    oracle.checkpoint_commit(F32, x, c, L, K)
+    rest = [b for b in lost if b not in set(K.tolist())]
+    assert math.isclose(oracle.perturbation_norm(F32, x, c, L, lost)[0], s0[rest].sum(),
+                        rel_tol=1e-13, abs_tol=1e-300)
+
+
+def test_mask_to_indices():
+    m = np.array([0, 1, 1, 0, 0, 255, 0, 1], dtype=np.uint8)
+    np.testing.assert_array_equal(oracle.mask_to_indices(m), [1, 2, 5, 7])
+    assert oracle.mask_to_indices(np.zeros(5, dtype=np.uint8)).size == 0
+    assert oracle.mask_to_indices(np.zeros(0, dtype=np.uint8)).size == 0
+
+
+def test_threads_do_not_change_results():
+    x, c = small_store(36, n_elems=50000)
+    L = 7
+    oracle.set_num_threads(1)
+    a = oracle.block_scores(F32, x, c, L)
+    na = oracle.perturbation_norm(F32, x, c, L)
+    oracle.set_num_threads(4)
+    try:
+        b = oracle.block_scores(F32, x, c, L)
+        nb_ = oracle.perturbation_norm(F32, x, c, L)
+    finally:
+        oracle.set_num_threads(1)
+    np.testing.assert_array_equal(a, b)
+    assert na == nb_
+
+
+def test_three_cycles_keep_the_running_checkpoint_consistent():
+    # Running checkpoint starts at x(0) and holds a mix of ages afterwards (Section 4.2).
+    r = rng_of(40)
+    L, nb = 8, 64
+    x = r.normal(size=L * nb).astype(np.float32)
+    c = x.copy()
+    assert oracle.perturbation_norm(F32, x, c, L)[0] == 0.0
+    for cycle in range(3):
+        x += (r.normal(size=x.size) * 0.01).astype(np.float32)
+        s = oracle.block_scores(F32, x, c, L)
+        K = oracle.select_topk(s, 16)
+        oracle.checkpoint_commit(F32, x, c, L, K)
+        s_after = oracle.block_scores(F32, x, c, L)
+        assert np.all(s_after[K] == 0.0)
+        others = np.setdiff1d(np.arange(nb), K)
+        assert s_after[others].max() <= s[K].min()
