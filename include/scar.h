@@ -1,0 +1,161 @@
+/*
+ * scar.h - C ABI of the checkpoint hot path of SCAR (Self-Correcting Algorithm
+ * Recovery; "Fault Tolerance in Iterative-Convergent Machine Learning", Sections 4.1-4.3)
+ * for one AMD MI355X (gfx950).
+ *
+ * Vocabulary (the paper's):
+ *   x   live model parameters;
+ *   c   the running checkpoint (the paper's z): the in-memory cache of what was last
+ *       saved for every parameter, a mix of ages (Section 4.2, Section 4.3);
+ *   block   one "parameter" in the sense of the checkpoint protocol: the unit that is
+ *       scored, saved and lost as a whole - a matrix row, a factor row, a row of a count
+ *       table, a shard of a tensor (Section 5.1).  x and c are cut identically into
+ *       n_blocks = ceil(n_elems / block_len) blocks of block_len consecutive elements;
+ *       the last block may be short;
+ *   K   the blocks chosen for a partial checkpoint;  S  the blocks lost in a failure.
+ *
+ * One checkpoint-and-recovery cycle is
+ *   scar_block_scores -> scar_select_topk -> scar_checkpoint_commit      (Section 4.3,
+ *                                                     checkpoint steps 1, 3 and 4)
+ *   scar_partial_recover (with the norm)  /  scar_perturbation_norm      (Section 4.1,
+ *                                                     Appendix A.3)
+ *
+ * Conventions for every call
+ *   - Every data pointer (x, c, scores, idx, out_idx, staging, norm_out, mask, workspace)
+ *     is DEVICE memory owned by the caller.  The library allocates nothing and keeps no
+ *     state.  scar_layout and scalar arguments are host values.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call
+ *     validates its arguments on the host, enqueues its kernels on `stream` and returns;
+ *     it never synchronises.  Results are in device memory once the stream reaches them.
+ *   - Return value: SCAR_OK (0) or a negative scar_status.  On an error nothing has been
+ *     enqueued.  Nothing throws or aborts.
+ *   - x and c must not overlap.  x, c and staging must be aligned to the element size;
+ *     scores / out_idx / idx to their element type; workspace to 256 bytes.  When x and c
+ *     are 16-byte aligned and block_len * element size is a multiple of 16 the kernels
+ *     use 16-byte accesses; any other case is served by an element-wise path with the
+ *     same results.
+ *   - Index lists (idx, lost_idx) hold block numbers < n_blocks without repeats, in any
+ *     order (ascending is fastest).  This is not checked on the host (the lists live in
+ *     device memory); on the device an entry >= n_blocks is skipped, and a repeated
+ *     entry is counted twice by the norm.
+ *   - Calls that share a workspace must be ordered (same stream, or by events).
+ *   - n_elems == 0, k == 0, n_idx == 0 and n_lost == 0 are valid and do nothing
+ *     (norm_out, if given, is still written: all zero).
+ */
+#ifndef SCAR_H_
+#define SCAR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Element type of x and c. */
+typedef enum {
+  SCAR_F32 = 0,  /* IEEE binary32 */
+  SCAR_BF16 = 1, /* bfloat16 (upper 16 bits of a binary32), 2 bytes per element */
+  SCAR_I32 = 2   /* signed 32-bit counts (e.g. topic-count tables) */
+} scar_dtype;
+
+/* Element type of a score array. */
+typedef enum {
+  SCAR_SCORE_F32 = 0, /* float[n_blocks]: squared Euclidean distances (F32 / BF16 stores) */
+  SCAR_SCORE_I64 = 1  /* int64_t[n_blocks]: L1 distances (I32 stores) */
+} scar_score_type;
+
+typedef enum {
+  SCAR_OK = 0,
+  SCAR_ERR_INVALID_ARG = -1, /* NULL where data is required, block_len == 0, bad enum,
+                                k > n_blocks, n_blocks > SCAR_MAX_BLOCKS, misaligned pointer */
+  SCAR_ERR_WORKSPACE = -2,   /* workspace NULL, misaligned or smaller than scar_workspace_bytes */
+  SCAR_ERR_DEVICE = -3       /* HIP reported an error when a kernel was enqueued */
+} scar_status;
+
+#define SCAR_MAX_BLOCKS 0x7fffffffu
+
+/* How x and c are cut into blocks. */
+typedef struct {
+  int32_t dtype;      /* scar_dtype */
+  uint32_t block_len; /* elements per block, >= 1 */
+  uint64_t n_elems;   /* total elements in x (and in c); n_blocks <= SCAR_MAX_BLOCKS */
+} scar_layout;
+
+/* Size of a perturbation.  Float stores: sum = sum of (c_j - x_j)^2 over the blocks
+ * asked for, norm = sqrt(sum) (the Euclidean norm of Appendix A.3), isum = 0.
+ * I32 stores: isum = sum of |c_j - x_j| (exact), sum = norm = (double)isum. */
+typedef struct {
+  double sum;
+  double norm;
+  int64_t isum;
+} scar_norm;
+
+/* Number of blocks of a layout; 0 if the layout is invalid. */
+uint64_t scar_n_blocks(const scar_layout* layout);
+
+/* Bytes of device scratch that any call on a store of up to n_blocks blocks needs.
+ * Host-only arithmetic; never fails (returns 0 for n_blocks > SCAR_MAX_BLOCKS). */
+size_t scar_workspace_bytes(uint64_t n_blocks);
+
+/* Checkpoint step 1 (Section 4.3): the distance of every block of x from its value in
+ * the running checkpoint c.
+ *   F32 / BF16: scores = float[n_blocks], s_b = sum_j (x_j - c_j)^2 over block b
+ *               (the square of the Euclidean distance used in Appendix A; the order of
+ *               blocks is the same with or without the square root); bfloat16 values are
+ *               widened exactly and accumulated in float32/float64.
+ *   I32:        scores = int64_t[n_blocks], s_b = sum_j |x_j - c_j|, exact (for a row of
+ *               topic counts this is twice the document-length-scaled total variation of
+ *               Appendix C).
+ * Reads x and c once; writes scores. */
+int scar_block_scores(const scar_layout* layout, const void* x, const void* c, void* scores,
+                      void* stream);
+
+/* Checkpoint step 3 (Section 4.3): the k blocks with the largest scores - "the
+ * parameters which have changed the most since they were previously saved"
+ * (Section 4.2).  The order is total: larger score first, equal scores to the lower
+ * block index; NaN ranks above every number and -0 equals +0.  out_idx receives the k
+ * chosen block indices in ascending order.  scores is not modified.
+ *   score_type: SCAR_SCORE_F32 (float scores) or SCAR_SCORE_I64 (int64_t scores). */
+int scar_select_topk(int32_t score_type, const void* scores, uint32_t n_blocks, uint32_t k,
+                     uint32_t* out_idx, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Checkpoint step 4, the part on the critical path (Section 4.3): update the in-memory
+ * checkpoint, c_b <- x_b for the n_idx blocks in idx.  If staging is not NULL, row i of
+ * staging (block_len elements per row, packed) also receives block idx[i]: the bytes a
+ * background writer would send to persistent storage.  x is not modified; blocks of c
+ * outside idx are not touched. */
+int scar_checkpoint_commit(const scar_layout* layout, const void* x, void* c,
+                           const uint32_t* idx, uint32_t n_idx, void* staging, void* stream);
+
+/* Partial recovery (Section 4.1): x_b <- c_b for the n_lost lost blocks only; every
+ * other block of x keeps its value and c is not modified.  If norm_out is not NULL it
+ * receives, from the same pass, the size of the perturbation this recovery causes,
+ * ||c_S - x_S|| measured on x as it was before being overwritten (Appendix A.3).
+ * workspace may be NULL when norm_out is NULL. */
+int scar_partial_recover(const scar_layout* layout, void* x, const void* c,
+                         const uint32_t* lost_idx, uint32_t n_lost, scar_norm* norm_out,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Size of the perturbation a recovery of the blocks in idx would cause, ||c_S - x_S||
+ * (Appendix A.3; the quantity the iteration-cost bound of Theorem 3.1 grows with),
+ * without changing anything.  idx == NULL means every block: ||c - x||, the
+ * perturbation of a traditional full recovery (n_idx is then ignored). */
+int scar_perturbation_norm(const scar_layout* layout, const void* x, const void* c,
+                           const uint32_t* idx, uint32_t n_idx, scar_norm* norm_out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Convenience for callers that hold the lost set as a mask (one byte per block,
+ * non-zero = lost; Section 4.1's random partitions): out_idx receives the ascending
+ * indices of the non-zero bytes (room for n_blocks entries), *out_count how many. */
+int scar_mask_to_indices(const uint8_t* mask, uint32_t n_blocks, uint32_t* out_idx,
+                         uint32_t* out_count, void* workspace, size_t workspace_bytes,
+                         void* stream);
+
+/* Static, never NULL. */
+const char* scar_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCAR_H_ */

@@ -1,0 +1,205 @@
+// Device-side building blocks shared by the SCAR kernels (gfx950, wave64).
+//
+// A *group* is G consecutive lanes (G = 1..64 inside one wavefront, or G = 256 = the
+// whole workgroup) that together walk one block of x and c.  Group sizes are chosen on
+// the host so that every lane issues about four 16-byte loads per stream.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace scar {
+
+constexpr int kWG = 256;    // threads per workgroup, 4 wavefronts
+constexpr int kWave = 64;
+constexpr int kUnroll = 4;  // 16-byte loads per lane and stream kept in flight
+
+enum : int { DT_F32 = 0, DT_BF16 = 1, DT_I32 = 2 };
+
+__host__ __device__ constexpr int elem_bytes(int dt) { return dt == DT_BF16 ? 2 : 4; }
+
+// ---- per-element distance terms --------------------------------------------------
+
+__device__ __forceinline__ float sq(float d) { return d * d; }
+
+// Four float32 lanes of a 16-byte vector.
+__device__ __forceinline__ float sqdiff_f32(const uint4& a, const uint4& b) {
+  float s = sq(__uint_as_float(a.x) - __uint_as_float(b.x));
+  s += sq(__uint_as_float(a.y) - __uint_as_float(b.y));
+  s += sq(__uint_as_float(a.z) - __uint_as_float(b.z));
+  s += sq(__uint_as_float(a.w) - __uint_as_float(b.w));
+  return s;
+}
+
+// A 32-bit word holds two bfloat16; each widens exactly to float32 by a shift or a mask.
+__device__ __forceinline__ float sqdiff_bf16x2(uint32_t a, uint32_t b) {
+  float lo = __uint_as_float(a << 16) - __uint_as_float(b << 16);
+  float hi = __uint_as_float(a & 0xffff0000u) - __uint_as_float(b & 0xffff0000u);
+  return lo * lo + hi * hi;
+}
+
+__device__ __forceinline__ float sqdiff_bf16(const uint4& a, const uint4& b) {
+  return sqdiff_bf16x2(a.x, b.x) + sqdiff_bf16x2(a.y, b.y) + sqdiff_bf16x2(a.z, b.z) +
+         sqdiff_bf16x2(a.w, b.w);
+}
+
+// |a - b| of two int32 held in uint32: the true difference is below 2^32, so the
+// unsigned subtraction of the smaller from the larger is exact.
+__device__ __forceinline__ uint32_t absdiff_i32(uint32_t a, uint32_t b) {
+  int32_t sa = (int32_t)a, sb = (int32_t)b;
+  return sa > sb ? a - b : b - a;
+}
+
+__device__ __forceinline__ uint64_t absdiff_i32x4(const uint4& a, const uint4& b) {
+  return (uint64_t)absdiff_i32(a.x, b.x) + absdiff_i32(a.y, b.y) + absdiff_i32(a.z, b.z) +
+         absdiff_i32(a.w, b.w);
+}
+
+// ---- accumulators ------------------------------------------------------------------
+// Float stores: each 16-byte step is summed in float32 and folded into a float64
+// running sum, so long blocks and long index lists keep full accuracy.
+// Integer stores: exact in uint64.
+
+template <int DT>
+struct Acc {
+  using type = double;
+};
+template <>
+struct Acc<DT_I32> {
+  using type = unsigned long long;
+};
+
+template <int DT>
+__device__ __forceinline__ void accumulate_vec(typename Acc<DT>::type& acc, const uint4 (&a)[kUnroll],
+                                               const uint4 (&b)[kUnroll]) {
+  if constexpr (DT == DT_I32) {
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) acc += absdiff_i32x4(a[u], b[u]);
+  } else {
+    float part = 0.f;
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+      part += (DT == DT_F32) ? sqdiff_f32(a[u], b[u]) : sqdiff_bf16(a[u], b[u]);
+    acc += (double)part;
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ void accumulate_elem(typename Acc<DT>::type& acc, const char* a,
+                                                const char* b, uint64_t j) {
+  if constexpr (DT == DT_I32) {
+    acc += absdiff_i32(((const uint32_t*)a)[j], ((const uint32_t*)b)[j]);
+  } else if constexpr (DT == DT_F32) {
+    acc += (double)sq(((const float*)a)[j] - ((const float*)b)[j]);
+  } else {
+    uint32_t ua = ((const uint16_t*)a)[j], ub = ((const uint16_t*)b)[j];
+    acc += (double)sq(__uint_as_float(ua << 16) - __uint_as_float(ub << 16));
+  }
+}
+
+// ---- reductions --------------------------------------------------------------------
+
+// Sum over the G lanes of a group (G a power of two <= 64); every lane gets the total.
+template <int G, typename T>
+__device__ __forceinline__ T group_sum(T v) {
+#pragma unroll
+  for (int m = G / 2; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+  return v;
+}
+
+// Sum over the whole workgroup; the result is valid in thread 0.  `slots` is LDS for
+// kWG / kWave values.  Fixed order, so the result is reproducible.
+template <typename T>
+__device__ __forceinline__ T workgroup_sum(T v, T* slots) {
+  v = group_sum<kWave>(v);
+  const int wave = threadIdx.x / kWave;
+  __syncthreads();  // slots may still be read from a previous use
+  if ((threadIdx.x & (kWave - 1)) == 0) slots[wave] = v;
+  __syncthreads();
+  T total = slots[0];
+#pragma unroll
+  for (int w = 1; w < kWG / kWave; ++w) total += slots[w];
+  return total;
+}
+
+// ---- one block, one group ------------------------------------------------------------
+
+// Geometry of block b: byte offset of its first element and its element count.
+struct BlockSpan {
+  uint64_t byte_off;
+  uint32_t len;
+};
+
+__device__ __forceinline__ BlockSpan block_span(uint64_t b, uint64_t n_elems, uint32_t block_len,
+                                                int ebytes) {
+  uint64_t lo = b * (uint64_t)block_len;
+  uint64_t hi = lo + block_len;
+  if (hi > n_elems) hi = n_elems;
+  return {lo * (uint64_t)ebytes, (uint32_t)(hi - lo)};
+}
+
+// Distance term of one block, spread over the G lanes of a group; each lane returns its
+// share.  `vec` says that both block starts are 16-byte aligned.
+template <int DT, int G>
+__device__ __forceinline__ typename Acc<DT>::type block_distance(const char* xb, const char* cb,
+                                                                 uint32_t len, int lane, bool vec) {
+  constexpr int E = elem_bytes(DT);
+  constexpr int EPV = 16 / E;
+  typename Acc<DT>::type acc = 0;
+  const uint32_t nvec = vec ? len / EPV : 0;
+  const uint4* xv = (const uint4*)xb;
+  const uint4* cv = (const uint4*)cb;
+  for (uint32_t v0 = 0; v0 < nvec; v0 += G * kUnroll) {
+    uint4 a[kUnroll], b[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint32_t v = v0 + u * G + lane;
+      if (v < nvec) {
+        a[u] = xv[v];
+        b[u] = cv[v];
+      } else {
+        a[u] = make_uint4(0, 0, 0, 0);
+        b[u] = make_uint4(0, 0, 0, 0);
+      }
+    }
+    accumulate_vec<DT>(acc, a, b);
+  }
+  for (uint32_t j = nvec * EPV + lane; j < len; j += G) accumulate_elem<DT>(acc, xb, cb, j);
+  return acc;
+}
+
+// Copy one block src -> dst (and to dst2 if not NULL), spread over a group.  W is the
+// word type of the element-wise path (uint32_t for 4-byte elements, uint16_t for 2-byte).
+template <int G, typename W>
+__device__ __forceinline__ void block_copy(const char* src, char* dst, char* dst2, uint32_t nbytes,
+                                           int lane, bool vec, bool vec2) {
+  const uint32_t nvec = vec ? nbytes / 16 : 0;
+  const uint4* s = (const uint4*)src;
+  uint4* d = (uint4*)dst;
+  for (uint32_t v0 = 0; v0 < nvec; v0 += G * kUnroll) {
+    uint4 a[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint32_t v = v0 + u * G + lane;
+      if (v < nvec) a[u] = s[v];
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint32_t v = v0 + u * G + lane;
+      if (v < nvec) {
+        d[v] = a[u];
+        if (dst2 && vec2) ((uint4*)dst2)[v] = a[u];
+      }
+    }
+  }
+  // what the 16-byte steps did not cover (everything, on the element-wise path)
+  const uint32_t nword = nbytes / sizeof(W);
+  const uint32_t done = nvec * (16 / sizeof(W));
+  const W* sw = (const W*)src;
+  for (uint32_t h = done + lane; h < nword; h += G) ((W*)dst)[h] = sw[h];
+  if (dst2) {
+    for (uint32_t h = (vec2 ? done : 0) + lane; h < nword; h += G) ((W*)dst2)[h] = sw[h];
+  }
+}
+
+}  // namespace scar

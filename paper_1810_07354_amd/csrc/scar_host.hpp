@@ -1,0 +1,65 @@
+// Host-side helpers shared by the entry points: argument checks, block geometry,
+// choice of the group size, and the layout of the caller's workspace.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/scar.h"
+
+namespace scar {
+
+constexpr uint32_t kMaxBlockLen = 1u << 28;
+
+inline bool dtype_ok(int32_t dt) { return dt == SCAR_F32 || dt == SCAR_BF16 || dt == SCAR_I32; }
+inline int host_elem_bytes(int32_t dt) { return dt == SCAR_BF16 ? 2 : 4; }
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// n_blocks of a layout, or UINT64_MAX if the layout itself is not acceptable.
+inline uint64_t layout_blocks(const scar_layout* l) {
+  if (!l || !dtype_ok(l->dtype) || l->block_len == 0 || l->block_len > kMaxBlockLen) return UINT64_MAX;
+  const uint64_t nb = l->n_elems / l->block_len + (l->n_elems % l->block_len ? 1 : 0);
+  return nb > SCAR_MAX_BLOCKS ? UINT64_MAX : nb;
+}
+
+// Group size for blocks of `block_len` elements: the power of two in {1..64, 256} that
+// gives each lane about four loads per stream (16-byte loads on the vector path,
+// element loads otherwise).
+inline int pick_group(uint32_t block_len, int ebytes, bool vec) {
+  const uint64_t units = vec ? ((uint64_t)block_len * ebytes + 15) / 16 : block_len;
+  const uint64_t want = (units + 3) / 4;
+  int g = 1;
+  while (g < 256 && (uint64_t)g < want) g <<= 1;
+  return g == 128 ? 256 : g;
+}
+
+// ---- workspace layout ---------------------------------------------------------------
+// [0, 64 KiB)    selection: digit histograms, pass state, tickets   (select, mask)
+// [64 KiB, +64 KiB)  per-workgroup partial sums of the norm           (recover, norm)
+// [128 KiB, ...) per-tile counts of the compaction, 8 bytes per tile (select, mask)
+constexpr size_t kWsSelectBytes = 64 * 1024;
+constexpr size_t kWsNormOffset = kWsSelectBytes;
+constexpr size_t kWsNormBytes = 64 * 1024;
+constexpr size_t kWsTileOffset = kWsNormOffset + kWsNormBytes;
+constexpr uint32_t kTileKeys = 2048;   // keys per compaction tile
+constexpr uint32_t kMaxNormGrid = kWsNormBytes / 8;
+
+inline uint64_t n_tiles_of(uint64_t n) { return (n + kTileKeys - 1) / kTileKeys; }
+
+inline size_t workspace_bytes_for(uint64_t n_blocks) {
+  return kWsTileOffset + ((n_tiles_of(n_blocks) * 8 + 255) / 256) * 256 + 256;
+}
+
+inline int check_workspace(const void* ws, size_t bytes, uint64_t n_blocks) {
+  if (!ws || !aligned(ws, 256) || bytes < workspace_bytes_for(n_blocks)) return SCAR_ERR_WORKSPACE;
+  return SCAR_OK;
+}
+
+// Upper bounds on grid sizes; kernels stride over the rest.
+constexpr uint64_t kScoreGridCap = 1u << 20;
+constexpr uint64_t kCopyGridCap = 1u << 20;
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? SCAR_OK : SCAR_ERR_DEVICE; }
+
+}  // namespace scar

@@ -1,0 +1,271 @@
+// Index-driven row kernels: scar_checkpoint_commit (checkpoint step 4 of Section 4.3),
+// scar_partial_recover with the fused norm (Section 4.1, Appendix A.3) and
+// scar_perturbation_norm.
+//
+// Each group of G lanes takes one entry of the index list, finds its block and moves or
+// measures it with 16-byte accesses.  The norm is reduced in two deterministic stages:
+// one partial sum per workgroup (float64, or exact int64 for integer tables), then a
+// single workgroup adds the partials in a fixed order.
+#include "scar_device.hpp"
+#include "scar_host.hpp"
+
+namespace scar {
+
+// c_b <- x_b (and staging row i <- x_b) for b = idx[i].
+template <int G, typename W>
+__global__ __launch_bounds__(kWG) void k_commit(const char* __restrict__ x, char* __restrict__ c,
+                                                const uint32_t* __restrict__ idx, uint32_t n_idx,
+                                                char* __restrict__ staging, uint64_t n_elems,
+                                                uint32_t block_len, uint32_t n_blocks, bool vec,
+                                                bool vec_staging) {
+  constexpr int GPW = (G == 256) ? 1 : kWG / G;
+  const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
+  const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
+  for (uint64_t i = (uint64_t)blockIdx.x * GPW + grp; i < n_idx; i += (uint64_t)gridDim.x * GPW) {
+    const uint32_t b = idx[i];
+    if (b >= n_blocks) continue;
+    const BlockSpan sp = block_span(b, n_elems, block_len, sizeof(W));
+    char* st = staging ? staging + i * (uint64_t)block_len * sizeof(W) : nullptr;
+    block_copy<G, W>(x + sp.byte_off, c + sp.byte_off, st, sp.len * (uint32_t)sizeof(W), lane, vec,
+                     vec_staging);
+  }
+}
+
+// Recovery and/or norm over the blocks idx[0..n_idx) (idx == NULL: blocks 0..n_idx).
+//   STORE: x_b <- c_b after the block has been measured.
+//   NORM:  partial[blockIdx.x] <- this workgroup's share of sum (c - x)^2 or sum |c - x|.
+template <int DT, int G, bool STORE, bool NORM>
+__global__ __launch_bounds__(kWG) void k_recover(char* __restrict__ x, const char* __restrict__ c,
+                                                 const uint32_t* __restrict__ idx, uint32_t n_idx,
+                                                 uint64_t n_elems, uint32_t block_len,
+                                                 uint32_t n_blocks, bool vec,
+                                                 typename Acc<DT>::type* __restrict__ partial) {
+  constexpr int GPW = (G == 256) ? 1 : kWG / G;
+  constexpr int E = elem_bytes(DT);
+  constexpr int EPV = 16 / E;
+  using acc_t = typename Acc<DT>::type;
+  using word_t = typename std::conditional<E == 4, uint32_t, uint16_t>::type;
+  const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
+  const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
+  __shared__ acc_t slots[kWG / kWave];
+  acc_t acc = 0;
+
+  for (uint64_t i = (uint64_t)blockIdx.x * GPW + grp; i < n_idx; i += (uint64_t)gridDim.x * GPW) {
+    const uint32_t b = idx ? idx[i] : (uint32_t)i;
+    if (b >= n_blocks) continue;
+    const BlockSpan sp = block_span(b, n_elems, block_len, E);
+    char* xb = x + sp.byte_off;
+    const char* cb = c + sp.byte_off;
+    const uint32_t nvec = vec ? sp.len / EPV : 0;
+    for (uint32_t v0 = 0; v0 < nvec; v0 += G * kUnroll) {
+      uint4 xv[kUnroll], cv[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const uint32_t v = v0 + u * G + lane;
+        if (v < nvec) {
+          cv[u] = ((const uint4*)cb)[v];
+          if (NORM) xv[u] = ((const uint4*)xb)[v];
+        } else {
+          cv[u] = make_uint4(0, 0, 0, 0);
+          xv[u] = make_uint4(0, 0, 0, 0);
+        }
+      }
+      if (NORM) accumulate_vec<DT>(acc, cv, xv);
+      if (STORE) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+          const uint32_t v = v0 + u * G + lane;
+          if (v < nvec) ((uint4*)xb)[v] = cv[u];
+        }
+      }
+    }
+    for (uint32_t j = nvec * EPV + lane; j < sp.len; j += G) {
+      if (NORM) accumulate_elem<DT>(acc, cb, xb, j);
+      if (STORE) ((word_t*)xb)[j] = ((const word_t*)cb)[j];
+    }
+  }
+  if (NORM) {
+    acc = workgroup_sum(acc, slots);
+    if (threadIdx.x == 0) partial[blockIdx.x] = acc;
+  }
+}
+
+// Second stage of the norm: one workgroup adds n_partial partial sums in a fixed order
+// and writes the result.  n_partial == 0 writes zeros.
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_norm_finish(const typename Acc<DT>::type* __restrict__ partial,
+                                                     uint32_t n_partial, scar_norm* __restrict__ out) {
+  using acc_t = typename Acc<DT>::type;
+  __shared__ acc_t slots[kWG / kWave];
+  acc_t acc = 0;
+  for (uint32_t i = threadIdx.x; i < n_partial; i += kWG) acc += partial[i];
+  acc = workgroup_sum(acc, slots);
+  if (threadIdx.x == 0) {
+    if constexpr (DT == DT_I32) {
+      out->isum = (long long)acc;
+      out->sum = (double)acc;
+      out->norm = (double)acc;
+    } else {
+      out->isum = 0;
+      out->sum = acc;
+      out->norm = sqrt(acc);
+    }
+  }
+}
+
+template <int G, typename W>
+static void launch_commit(const scar_layout* l, const void* x, void* c, const uint32_t* idx,
+                          uint32_t n_idx, void* staging, uint32_t n_blocks, bool vec, bool vec_st,
+                          hipStream_t st) {
+  constexpr int GPW = (G == 256) ? 1 : kWG / G;
+  const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
+  const uint32_t grid = (uint32_t)(need < kCopyGridCap ? need : kCopyGridCap);
+  hipLaunchKernelGGL((k_commit<G, W>), dim3(grid), dim3(kWG), 0, st, (const char*)x, (char*)c, idx,
+                     n_idx, (char*)staging, l->n_elems, l->block_len, n_blocks, vec, vec_st);
+}
+
+template <typename W>
+static void dispatch_commit(int g, const scar_layout* l, const void* x, void* c, const uint32_t* idx,
+                            uint32_t n_idx, void* staging, uint32_t n_blocks, bool vec, bool vec_st,
+                            hipStream_t st) {
+  switch (g) {
+    case 1: launch_commit<1, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
+    case 2: launch_commit<2, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
+    case 4: launch_commit<4, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
+    case 8: launch_commit<8, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
+    case 16: launch_commit<16, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
+    case 32: launch_commit<32, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
+    case 64: launch_commit<64, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
+    default: launch_commit<256, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
+  }
+}
+
+// Launches the recovery / norm kernel; returns the number of partial sums it writes.
+template <int DT, int G, bool STORE, bool NORM>
+static uint32_t launch_recover(const scar_layout* l, void* x, const void* c, const uint32_t* idx,
+                               uint32_t n_idx, uint32_t n_blocks, bool vec, void* partial,
+                               hipStream_t st) {
+  constexpr int GPW = (G == 256) ? 1 : kWG / G;
+  const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
+  const uint32_t grid = (uint32_t)(need < kMaxNormGrid ? need : kMaxNormGrid);
+  hipLaunchKernelGGL((k_recover<DT, G, STORE, NORM>), dim3(grid), dim3(kWG), 0, st, (char*)x,
+                     (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, vec,
+                     (typename Acc<DT>::type*)partial);
+  return grid;
+}
+
+template <int DT, bool STORE, bool NORM>
+static uint32_t dispatch_recover_g(int g, const scar_layout* l, void* x, const void* c,
+                                   const uint32_t* idx, uint32_t n_idx, uint32_t n_blocks, bool vec,
+                                   void* partial, hipStream_t st) {
+  switch (g) {
+    case 1: return launch_recover<DT, 1, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
+    case 2: return launch_recover<DT, 2, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
+    case 4: return launch_recover<DT, 4, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
+    case 8: return launch_recover<DT, 8, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
+    case 16: return launch_recover<DT, 16, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
+    case 32: return launch_recover<DT, 32, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
+    case 64: return launch_recover<DT, 64, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
+    default: return launch_recover<DT, 256, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
+  }
+}
+
+template <bool STORE, bool NORM>
+static uint32_t dispatch_recover(int g, const scar_layout* l, void* x, const void* c,
+                                 const uint32_t* idx, uint32_t n_idx, uint32_t n_blocks, bool vec,
+                                 void* partial, hipStream_t st) {
+  switch (l->dtype) {
+    case SCAR_F32: return dispatch_recover_g<DT_F32, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, partial, st);
+    case SCAR_BF16: return dispatch_recover_g<DT_BF16, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, partial, st);
+    default: return dispatch_recover_g<DT_I32, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, partial, st);
+  }
+}
+
+static void launch_finish(int32_t dtype, const void* partial, uint32_t n_partial, scar_norm* out,
+                          hipStream_t st) {
+  if (dtype == SCAR_I32)
+    hipLaunchKernelGGL((k_norm_finish<DT_I32>), dim3(1), dim3(kWG), 0, st,
+                       (const unsigned long long*)partial, n_partial, out);
+  else
+    hipLaunchKernelGGL((k_norm_finish<DT_F32>), dim3(1), dim3(kWG), 0, st, (const double*)partial,
+                       n_partial, out);
+}
+
+// Shared body of scar_partial_recover (store = true) and scar_perturbation_norm.
+static int recover_or_norm(bool store, const scar_layout* layout, void* x, const void* c,
+                           const uint32_t* idx, uint32_t n_idx, bool all_blocks, scar_norm* norm_out,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  const uint64_t nb = layout_blocks(layout);
+  if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
+  const int eb = host_elem_bytes(layout->dtype);
+  if (all_blocks) n_idx = (uint32_t)nb;
+  if (norm_out) {
+    if (!aligned(norm_out, 8)) return SCAR_ERR_INVALID_ARG;
+    const int rc = check_workspace(workspace, workspace_bytes, nb);
+    if (rc) return rc;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  char* partial = norm_out ? (char*)workspace + kWsNormOffset : nullptr;
+  if (n_idx == 0 || nb == 0) {
+    if (norm_out) {
+      launch_finish(layout->dtype, partial, 0, norm_out, st);
+      return launch_status();
+    }
+    return SCAR_OK;
+  }
+  if (!x || !c || (!all_blocks && !idx) || !aligned(x, eb) || !aligned(c, eb) || !aligned(idx, 4))
+    return SCAR_ERR_INVALID_ARG;
+  const bool vec = aligned(x, 16) && aligned(c, 16) && ((uint64_t)layout->block_len * eb) % 16 == 0;
+  const int g = pick_group(layout->block_len, eb, vec);
+  const uint32_t n_blocks = (uint32_t)nb;
+  uint32_t n_partial = 0;
+  if (store && norm_out)
+    n_partial = dispatch_recover<true, true>(g, layout, x, c, idx, n_idx, n_blocks, vec, partial, st);
+  else if (store)
+    dispatch_recover<true, false>(g, layout, x, c, idx, n_idx, n_blocks, vec, nullptr, st);
+  else
+    n_partial = dispatch_recover<false, true>(g, layout, x, c, idx, n_idx, n_blocks, vec, partial, st);
+  if (norm_out) launch_finish(layout->dtype, partial, n_partial, norm_out, st);
+  return launch_status();
+}
+
+}  // namespace scar
+
+using namespace scar;
+
+extern "C" int scar_checkpoint_commit(const scar_layout* layout, const void* x, void* c,
+                                      const uint32_t* idx, uint32_t n_idx, void* staging,
+                                      void* stream) {
+  const uint64_t nb = layout_blocks(layout);
+  if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
+  if (n_idx == 0 || nb == 0) return SCAR_OK;
+  const int eb = host_elem_bytes(layout->dtype);
+  if (!x || !c || !idx || !aligned(x, eb) || !aligned(c, eb) || !aligned(idx, 4) ||
+      (staging && !aligned(staging, eb)))
+    return SCAR_ERR_INVALID_ARG;
+  const bool row16 = ((uint64_t)layout->block_len * eb) % 16 == 0;
+  const bool vec = aligned(x, 16) && aligned(c, 16) && row16;
+  const bool vec_st = vec && staging && aligned(staging, 16);
+  const int g = pick_group(layout->block_len, eb, vec);
+  hipStream_t st = (hipStream_t)stream;
+  if (eb == 4)
+    dispatch_commit<uint32_t>(g, layout, x, c, idx, n_idx, staging, (uint32_t)nb, vec, vec_st, st);
+  else
+    dispatch_commit<uint16_t>(g, layout, x, c, idx, n_idx, staging, (uint32_t)nb, vec, vec_st, st);
+  return launch_status();
+}
+
+extern "C" int scar_partial_recover(const scar_layout* layout, void* x, const void* c,
+                                    const uint32_t* lost_idx, uint32_t n_lost, scar_norm* norm_out,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+  return recover_or_norm(true, layout, x, c, lost_idx, n_lost, false, norm_out, workspace,
+                         workspace_bytes, stream);
+}
+
+extern "C" int scar_perturbation_norm(const scar_layout* layout, const void* x, const void* c,
+                                      const uint32_t* idx, uint32_t n_idx, scar_norm* norm_out,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+  if (!norm_out) return SCAR_ERR_INVALID_ARG;
+  return recover_or_norm(false, layout, const_cast<void*>(x), c, idx, n_idx, idx == nullptr, norm_out,
+                         workspace, workspace_bytes, stream);
+}

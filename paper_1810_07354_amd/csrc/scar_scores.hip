@@ -1,0 +1,87 @@
+// scar_block_scores: distance of every block of x from the running checkpoint c
+// (checkpoint step 1 of Section 4.3).
+//
+// The kernel is a pure two-stream read: 2 * n_elems * element-size bytes in, one score
+// per block out.  G lanes walk one block with 16-byte loads from x and from c issued
+// back to back (kUnroll of each before the first use), the per-lane sums are combined
+// with wavefront shuffles (G <= 64) or shuffles plus one LDS step (G = 256).
+#include "scar_device.hpp"
+#include "scar_host.hpp"
+
+namespace scar {
+
+template <int DT, int G>
+__global__ __launch_bounds__(kWG) void k_block_scores(const char* __restrict__ x,
+                                                      const char* __restrict__ c,
+                                                      void* __restrict__ scores, uint64_t n_elems,
+                                                      uint32_t block_len, uint32_t n_blocks, bool vec) {
+  constexpr int GPW = (G == 256) ? 1 : kWG / G;  // groups (= blocks in flight) per workgroup
+  using acc_t = typename Acc<DT>::type;
+  const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
+  const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
+  __shared__ acc_t slots[kWG / kWave];
+
+  for (uint64_t b = (uint64_t)blockIdx.x * GPW + grp; b < n_blocks; b += (uint64_t)gridDim.x * GPW) {
+    const BlockSpan sp = block_span(b, n_elems, block_len, elem_bytes(DT));
+    acc_t acc = block_distance<DT, G>(x + sp.byte_off, c + sp.byte_off, sp.len, lane, vec);
+    if constexpr (G == 256)
+      acc = workgroup_sum(acc, slots);
+    else
+      acc = group_sum<G>(acc);
+    if (lane == 0) {
+      if constexpr (DT == DT_I32)
+        ((long long*)scores)[b] = (long long)acc;
+      else
+        ((float*)scores)[b] = (float)acc;
+    }
+  }
+}
+
+template <int DT, int G>
+static void launch_scores(const scar_layout* l, const void* x, const void* c, void* scores,
+                          uint32_t n_blocks, bool vec, hipStream_t st) {
+  constexpr int GPW = (G == 256) ? 1 : kWG / G;
+  const uint64_t need = ((uint64_t)n_blocks + GPW - 1) / GPW;
+  const uint32_t grid = (uint32_t)(need < kScoreGridCap ? need : kScoreGridCap);
+  hipLaunchKernelGGL((k_block_scores<DT, G>), dim3(grid), dim3(kWG), 0, st, (const char*)x,
+                     (const char*)c, scores, l->n_elems, l->block_len, n_blocks, vec);
+}
+
+template <int DT>
+static void dispatch_scores(int g, const scar_layout* l, const void* x, const void* c, void* scores,
+                            uint32_t n_blocks, bool vec, hipStream_t st) {
+  switch (g) {
+    case 1: launch_scores<DT, 1>(l, x, c, scores, n_blocks, vec, st); break;
+    case 2: launch_scores<DT, 2>(l, x, c, scores, n_blocks, vec, st); break;
+    case 4: launch_scores<DT, 4>(l, x, c, scores, n_blocks, vec, st); break;
+    case 8: launch_scores<DT, 8>(l, x, c, scores, n_blocks, vec, st); break;
+    case 16: launch_scores<DT, 16>(l, x, c, scores, n_blocks, vec, st); break;
+    case 32: launch_scores<DT, 32>(l, x, c, scores, n_blocks, vec, st); break;
+    case 64: launch_scores<DT, 64>(l, x, c, scores, n_blocks, vec, st); break;
+    default: launch_scores<DT, 256>(l, x, c, scores, n_blocks, vec, st); break;
+  }
+}
+
+}  // namespace scar
+
+using namespace scar;
+
+extern "C" int scar_block_scores(const scar_layout* layout, const void* x, const void* c,
+                                 void* scores, void* stream) {
+  const uint64_t nb = layout_blocks(layout);
+  if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
+  if (nb == 0) return SCAR_OK;
+  const int eb = host_elem_bytes(layout->dtype);
+  if (!x || !c || !scores || !aligned(x, eb) || !aligned(c, eb) ||
+      !aligned(scores, layout->dtype == SCAR_I32 ? 8 : 4))
+    return SCAR_ERR_INVALID_ARG;
+  const bool vec = aligned(x, 16) && aligned(c, 16) && ((uint64_t)layout->block_len * eb) % 16 == 0;
+  const int g = pick_group(layout->block_len, eb, vec);
+  hipStream_t st = (hipStream_t)stream;
+  switch (layout->dtype) {
+    case SCAR_F32: dispatch_scores<DT_F32>(g, layout, x, c, scores, (uint32_t)nb, vec, st); break;
+    case SCAR_BF16: dispatch_scores<DT_BF16>(g, layout, x, c, scores, (uint32_t)nb, vec, st); break;
+    default: dispatch_scores<DT_I32>(g, layout, x, c, scores, (uint32_t)nb, vec, st); break;
+  }
+  return launch_status();
+}

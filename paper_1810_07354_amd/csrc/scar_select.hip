@@ -1,0 +1,328 @@
+// scar_select_topk: the k blocks with the largest scores (checkpoint step 3 of
+// Section 4.3), and scar_mask_to_indices.
+//
+// Scores become unsigned keys whose integer order is the score order (NaN on top, -0
+// equal to +0).  A most-significant-digit-first radix select finds the k-th largest key
+// T: each pass builds a histogram of one digit of the keys that still match the prefix
+// found so far (LDS histogram per workgroup, then one global atomic per non-empty bin);
+// the last workgroup to finish a pass walks the histogram from the top and fixes the
+// next digit.  No pass waits for another workgroup: the hand-over is a ticket counter.
+// After the last pass every key > T is selected together with the first `take` keys
+// equal to T in index order, where take = k - #(keys > T).
+//
+// The chosen indices are then written in ascending order by a two-level prefix sum
+// (per-tile counts, scan of the tile counts by the last workgroup, per-tile write), so
+// the result does not depend on the order in which workgroups run.
+#include "scar_device.hpp"
+#include "scar_host.hpp"
+
+namespace scar {
+
+constexpr int kMaxBins = 2048;
+constexpr int kMaxPasses = 6;
+constexpr uint32_t kHistKeysPerWG = 4096;
+constexpr uint32_t kHistGridCap = 2048;
+constexpr uint32_t kTileGridCap = 1u << 16;
+constexpr int kKeysPerThread = kTileKeys / kWG;  // 8 consecutive keys per thread
+
+enum : int { SRC_F32 = 0, SRC_I64 = 1, SRC_MASK = 2 };
+
+struct SelectState {
+  unsigned long long prefix;  // digits fixed so far, right-aligned
+  uint32_t k_rem;             // how many of the keys matching `prefix` are still to be taken
+  uint32_t pad;
+};
+
+// Layout of the selection part of the workspace.
+struct SelectWs {
+  uint32_t hist[kMaxPasses][kMaxBins];
+  SelectState state[kMaxPasses + 1];
+  uint32_t ticket[kMaxPasses + 2];
+};
+static_assert(sizeof(SelectWs) <= kWsSelectBytes, "selection scratch exceeds its share");
+
+template <int SRC>
+struct Key;
+
+template <>
+struct Key<SRC_F32> {
+  using type = uint32_t;
+  static constexpr int passes = 3;
+  __device__ static int shift(int p) { return p == 0 ? 21 : (p == 1 ? 10 : 0); }
+  __device__ static int bits(int p) { return p == 2 ? 10 : 11; }
+  __device__ static type load(const void* s, uint64_t i) {
+    uint32_t u = __float_as_uint(((const float*)s)[i]);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0xffffffffu;  // NaN: above everything
+    if (u == 0x80000000u) u = 0;                              // -0 == +0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  }
+};
+
+template <>
+struct Key<SRC_I64> {
+  using type = unsigned long long;
+  static constexpr int passes = 6;
+  __device__ static int shift(int p) { return p == 5 ? 0 : 53 - 11 * p; }
+  __device__ static int bits(int p) { return p == 5 ? 9 : 11; }
+  __device__ static type load(const void* s, uint64_t i) {
+    return (unsigned long long)((const long long*)s)[i] ^ 0x8000000000000000ull;
+  }
+};
+
+template <>
+struct Key<SRC_MASK> {  // only classified, never histogrammed
+  using type = uint32_t;
+  __device__ static type load(const void* s, uint64_t i) { return ((const uint8_t*)s)[i] ? 1u : 0u; }
+};
+
+// Exclusive prefix sum of v over the workgroup in thread order; *total gets the sum.
+// `slots` is LDS for kWG / kWave + 1 values.
+template <typename T>
+__device__ __forceinline__ T workgroup_exclusive_scan(T v, T* slots, T* total) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  T inc = v;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    T up = __shfl_up(inc, d, kWave);
+    if (lane >= d) inc += up;
+  }
+  __syncthreads();
+  if (lane == kWave - 1) slots[wave] = inc;
+  __syncthreads();
+  T base = 0, sum = 0;
+#pragma unroll
+  for (int w = 0; w < kWG / kWave; ++w) {
+    if (w < wave) base += slots[w];
+    sum += slots[w];
+  }
+  *total = sum;
+  return base + inc - v;
+}
+
+// True in every thread of exactly one workgroup: the last one to get here.  Everything
+// the other workgroups wrote before their call is visible to it afterwards.
+__device__ __forceinline__ bool last_workgroup(uint32_t* ticket) {
+  __shared__ uint32_t s_last;
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) s_last = (atomicAdd(ticket, 1u) == gridDim.x - 1);
+  __syncthreads();
+  const bool last = s_last != 0;
+  if (last) __threadfence();
+  return last;
+}
+
+// One workgroup zeroes the histograms, pass states and tickets and sets the first state.
+__global__ __launch_bounds__(kWG) void k_select_clear(SelectWs* ws, uint32_t k) {
+  uint32_t* words = (uint32_t*)ws;
+  for (uint32_t i = threadIdx.x; i < sizeof(SelectWs) / 4; i += kWG) words[i] = 0;
+  __syncthreads();
+  if (threadIdx.x == 0) ws->state[0].k_rem = k;
+}
+
+// One radix pass: histogram of digit `pass` over the keys matching state[pass].prefix;
+// the last workgroup derives state[pass + 1].
+template <int SRC>
+__global__ __launch_bounds__(kWG) void k_select_hist(const void* __restrict__ scores, uint32_t n,
+                                                     int pass, SelectWs* __restrict__ ws) {
+  using K = Key<SRC>;
+  using key_t = typename K::type;
+  __shared__ uint32_t lh[kMaxBins];
+  __shared__ uint32_t scan_slots[kWG / kWave + 1];
+  for (int b = threadIdx.x; b < kMaxBins; b += kWG) lh[b] = 0;
+  __syncthreads();
+  const SelectState cur = ws->state[pass];
+  const int shift = K::shift(pass), bits = K::bits(pass);
+  const uint32_t mask = (1u << bits) - 1;
+  for (uint64_t i = (uint64_t)blockIdx.x * kWG + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kWG) {
+    const key_t key = K::load(scores, i);
+    const bool match = pass == 0 || (key >> (shift + bits)) == (key_t)cur.prefix;
+    if (match) atomicAdd(&lh[(uint32_t)(key >> shift) & mask], 1u);
+  }
+  __syncthreads();
+  uint32_t* gh = ws->hist[pass];
+  for (int b = threadIdx.x; b < kMaxBins; b += kWG)
+    if (lh[b]) atomicAdd(&gh[b], lh[b]);
+
+  if (!last_workgroup(&ws->ticket[pass])) return;
+
+  // Walk the finished histogram from the top bin down; thread t owns 8 consecutive bins.
+  const int nbins = 1 << bits;
+  constexpr int kOwn = kMaxBins / kWG;
+  uint32_t own[kOwn];
+  uint32_t cnt = 0;
+#pragma unroll
+  for (int j = 0; j < kOwn; ++j) {
+    const int b = nbins - 1 - ((int)threadIdx.x * kOwn + j);
+    own[j] = b >= 0 ? __hip_atomic_load(&gh[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+    cnt += own[j];
+  }
+  uint32_t total;
+  uint32_t above = workgroup_exclusive_scan(cnt, scan_slots, &total);
+  const uint32_t k_rem = cur.k_rem;
+  if (above < k_rem && k_rem <= above + cnt) {
+#pragma unroll
+    for (int j = 0; j < kOwn; ++j) {
+      if (above + own[j] >= k_rem) {
+        const int b = nbins - 1 - ((int)threadIdx.x * kOwn + j);
+        ws->state[pass + 1].prefix = (cur.prefix << bits) | (unsigned long long)b;
+        ws->state[pass + 1].k_rem = k_rem - above;
+        break;
+      }
+      above += own[j];
+    }
+  }
+}
+
+// 0 = not selected on its own, 1 = above the threshold, 2 = equal to the threshold.
+template <int SRC>
+__device__ __forceinline__ int classify(const void* src, uint64_t i, typename Key<SRC>::type T) {
+  const typename Key<SRC>::type key = Key<SRC>::load(src, i);
+  if constexpr (SRC == SRC_MASK) return key ? 1 : 0;
+  return key > T ? 1 : (key == T ? 2 : 0);
+}
+
+// Per-tile counts (above, equal); the last workgroup turns them into exclusive prefix
+// sums over the tiles, in place, and reports the number of "above" entries if asked.
+template <int SRC>
+__global__ __launch_bounds__(kWG) void k_compact_count(const void* __restrict__ src, uint32_t n,
+                                                       uint32_t n_tiles, int final_pass,
+                                                       SelectWs* __restrict__ ws,
+                                                       unsigned long long* __restrict__ tile_cnt,
+                                                       uint32_t* __restrict__ out_count) {
+  using key_t = typename Key<SRC>::type;
+  __shared__ unsigned long long slots[kWG / kWave + 1];
+  const key_t T = SRC == SRC_MASK ? 0 : (key_t)ws->state[final_pass].prefix;
+  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const uint64_t base = (uint64_t)tile * kTileKeys + threadIdx.x * kKeysPerThread;
+    unsigned long long cnt = 0;  // low word: above, high word: equal
+#pragma unroll
+    for (int j = 0; j < kKeysPerThread; ++j) {
+      if (base + j < n) {
+        const int cls = classify<SRC>(src, base + j, T);
+        cnt += cls == 1 ? 1ull : (cls == 2 ? (1ull << 32) : 0ull);
+      }
+    }
+    cnt = workgroup_sum(cnt, slots);
+    if (threadIdx.x == 0) tile_cnt[tile] = cnt;
+  }
+
+  if (!last_workgroup(&ws->ticket[kMaxPasses])) return;
+
+  unsigned long long running = 0;
+  for (uint32_t t0 = 0; t0 < n_tiles; t0 += kWG) {
+    const uint32_t t = t0 + threadIdx.x;
+    const unsigned long long v =
+        t < n_tiles ? __hip_atomic_load(&tile_cnt[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+    unsigned long long total;
+    const unsigned long long ex = workgroup_exclusive_scan(v, slots, &total);
+    if (t < n_tiles) tile_cnt[t] = running + ex;
+    running += total;
+  }
+  if (out_count && threadIdx.x == 0) *out_count = (uint32_t)running;
+}
+
+// Writes the selected indices of each tile at their final, ascending positions.
+template <int SRC>
+__global__ __launch_bounds__(kWG) void k_compact_write(const void* __restrict__ src, uint32_t n,
+                                                       uint32_t n_tiles, int final_pass,
+                                                       const SelectWs* __restrict__ ws,
+                                                       const unsigned long long* __restrict__ tile_off,
+                                                       uint32_t* __restrict__ out_idx, uint32_t out_cap) {
+  using key_t = typename Key<SRC>::type;
+  __shared__ uint32_t slots[kWG / kWave + 1];
+  const key_t T = SRC == SRC_MASK ? 0 : (key_t)ws->state[final_pass].prefix;
+  const uint32_t take = SRC == SRC_MASK ? 0 : ws->state[final_pass].k_rem;
+  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const uint64_t base = (uint64_t)tile * kTileKeys + threadIdx.x * kKeysPerThread;
+    int cls[kKeysPerThread];
+    uint32_t cnt = 0;  // low half: above, high half: equal (a tile holds 2048 keys)
+#pragma unroll
+    for (int j = 0; j < kKeysPerThread; ++j) {
+      cls[j] = base + j < n ? classify<SRC>(src, base + j, T) : 0;
+      cnt += cls[j] == 1 ? 1u : (cls[j] == 2 ? (1u << 16) : 0u);
+    }
+    uint32_t total;
+    const uint32_t ex = workgroup_exclusive_scan(cnt, slots, &total);
+    const unsigned long long off = tile_off[tile];
+    uint32_t n_above = (uint32_t)off + (ex & 0xffffu);
+    uint32_t n_equal = (uint32_t)(off >> 32) + (ex >> 16);
+#pragma unroll
+    for (int j = 0; j < kKeysPerThread; ++j) {
+      if (cls[j] == 1) {
+        const uint32_t pos = n_above + (n_equal < take ? n_equal : take);
+        if (pos < out_cap) out_idx[pos] = (uint32_t)(base + j);
+        ++n_above;
+      } else if (cls[j] == 2) {
+        if (n_equal < take) {
+          const uint32_t pos = n_above + n_equal;
+          if (pos < out_cap) out_idx[pos] = (uint32_t)(base + j);
+        }
+        ++n_equal;
+      }
+    }
+  }
+}
+
+template <int SRC>
+static void run_select(const void* scores, uint32_t n, uint32_t k, uint32_t* out_idx, void* workspace,
+                       hipStream_t st) {
+  SelectWs* ws = (SelectWs*)workspace;
+  unsigned long long* tiles = (unsigned long long*)((char*)workspace + kWsTileOffset);
+  hipLaunchKernelGGL(k_select_clear, dim3(1), dim3(kWG), 0, st, ws, k);
+  uint32_t hgrid = (n + kHistKeysPerWG - 1) / kHistKeysPerWG;
+  if (hgrid > kHistGridCap) hgrid = kHistGridCap;
+  for (int p = 0; p < Key<SRC>::passes; ++p)
+    hipLaunchKernelGGL((k_select_hist<SRC>), dim3(hgrid), dim3(kWG), 0, st, scores, n, p, ws);
+  const uint32_t n_tiles = (uint32_t)n_tiles_of(n);
+  const uint32_t tgrid = n_tiles < kTileGridCap ? n_tiles : kTileGridCap;
+  hipLaunchKernelGGL((k_compact_count<SRC>), dim3(tgrid), dim3(kWG), 0, st, scores, n, n_tiles,
+                     Key<SRC>::passes, ws, tiles, (uint32_t*)nullptr);
+  hipLaunchKernelGGL((k_compact_write<SRC>), dim3(tgrid), dim3(kWG), 0, st, scores, n, n_tiles,
+                     Key<SRC>::passes, (const SelectWs*)ws, (const unsigned long long*)tiles, out_idx, k);
+}
+
+}  // namespace scar
+
+using namespace scar;
+
+extern "C" int scar_select_topk(int32_t score_type, const void* scores, uint32_t n_blocks, uint32_t k,
+                                uint32_t* out_idx, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+  if (score_type != SCAR_SCORE_F32 && score_type != SCAR_SCORE_I64) return SCAR_ERR_INVALID_ARG;
+  if (n_blocks > SCAR_MAX_BLOCKS || k > n_blocks) return SCAR_ERR_INVALID_ARG;
+  if (k == 0) return SCAR_OK;
+  if (!scores || !out_idx || !aligned(scores, score_type == SCAR_SCORE_I64 ? 8 : 4) ||
+      !aligned(out_idx, 4))
+    return SCAR_ERR_INVALID_ARG;
+  const int rc = check_workspace(workspace, workspace_bytes, n_blocks);
+  if (rc) return rc;
+  if (score_type == SCAR_SCORE_F32)
+    run_select<SRC_F32>(scores, n_blocks, k, out_idx, workspace, (hipStream_t)stream);
+  else
+    run_select<SRC_I64>(scores, n_blocks, k, out_idx, workspace, (hipStream_t)stream);
+  return launch_status();
+}
+
+extern "C" int scar_mask_to_indices(const uint8_t* mask, uint32_t n_blocks, uint32_t* out_idx,
+                                    uint32_t* out_count, void* workspace, size_t workspace_bytes,
+                                    void* stream) {
+  if (n_blocks > SCAR_MAX_BLOCKS || !out_count || !aligned(out_count, 4)) return SCAR_ERR_INVALID_ARG;
+  if (n_blocks && (!mask || !out_idx || !aligned(out_idx, 4))) return SCAR_ERR_INVALID_ARG;
+  const int rc = check_workspace(workspace, workspace_bytes, n_blocks);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  SelectWs* ws = (SelectWs*)workspace;
+  unsigned long long* tiles = (unsigned long long*)((char*)workspace + kWsTileOffset);
+  hipLaunchKernelGGL(k_select_clear, dim3(1), dim3(kWG), 0, st, ws, 0u);
+  const uint32_t n_tiles = (uint32_t)n_tiles_of(n_blocks);
+  // at least one workgroup, so that *out_count is written even for an empty mask
+  const uint32_t tgrid = n_tiles == 0 ? 1 : (n_tiles < kTileGridCap ? n_tiles : kTileGridCap);
+  hipLaunchKernelGGL((k_compact_count<SRC_MASK>), dim3(tgrid), dim3(kWG), 0, st, (const void*)mask,
+                     n_blocks, n_tiles, 0, ws, tiles, out_count);
+  if (n_tiles)
+    hipLaunchKernelGGL((k_compact_write<SRC_MASK>), dim3(tgrid), dim3(kWG), 0, st, (const void*)mask,
+                       n_blocks, n_tiles, 0, (const SelectWs*)ws, (const unsigned long long*)tiles,
+                       out_idx, n_blocks);
+  return launch_status();
+}

@@ -1,0 +1,223 @@
+"""Python face of the C-ABI library libscar.so: same names, argument marshalling only.
+
+Every function takes torch tensors that live on the GPU, hands their device pointers and
+torch's current HIP stream to the library and returns (asynchronously) torch tensors.
+Nothing is computed here, and there is no fallback: without the built library, or with
+tensors that are not on a GPU, these calls raise.
+"""
+import ctypes
+import os
+
+import torch
+
+F32, BF16, I32 = 0, 1, 2
+SCORE_F32, SCORE_I64 = 0, 1
+MAX_BLOCKS = 0x7FFFFFFF
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libscar.so")
+
+_TORCH_OF = {F32: torch.float32, BF16: torch.bfloat16, I32: torch.int32}
+_DTYPE_OF = {v: k for k, v in _TORCH_OF.items()}
+
+
+class ScarError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (what, strerror(status), status))
+
+
+class Layout(ctypes.Structure):
+    """scar_layout: how x and c are cut into blocks."""
+    _fields_ = [("dtype", ctypes.c_int32), ("block_len", ctypes.c_uint32), ("n_elems", ctypes.c_uint64)]
+
+
+class Norm(ctypes.Structure):
+    """scar_norm as laid out in device memory."""
+    _fields_ = [("sum", ctypes.c_double), ("norm", ctypes.c_double), ("isum", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libscar.so is not built: run `python -c 'import __graft_entry__ as g; "
+                               "g.build()'` (or paper_1810_07354_amd/build.py) first")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, u32, u64, i32, sz = (ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int32,
+                                 ctypes.c_size_t)
+        lp = ctypes.POINTER(Layout)
+        L.scar_n_blocks.argtypes = [lp]
+        L.scar_n_blocks.restype = u64
+        L.scar_workspace_bytes.argtypes = [u64]
+        L.scar_workspace_bytes.restype = sz
+        L.scar_strerror.argtypes = [ctypes.c_int]
+        L.scar_strerror.restype = ctypes.c_char_p
+        L.scar_block_scores.argtypes = [lp, vp, vp, vp, vp]
+        L.scar_select_topk.argtypes = [i32, vp, u32, u32, vp, vp, sz, vp]
+        L.scar_checkpoint_commit.argtypes = [lp, vp, vp, vp, u32, vp, vp]
+        L.scar_partial_recover.argtypes = [lp, vp, vp, vp, u32, vp, vp, sz, vp]
+        L.scar_perturbation_norm.argtypes = [lp, vp, vp, vp, u32, vp, vp, sz, vp]
+        L.scar_mask_to_indices.argtypes = [vp, u32, vp, vp, vp, sz, vp]
+        for name in ("scar_block_scores", "scar_select_topk", "scar_checkpoint_commit",
+                     "scar_partial_recover", "scar_perturbation_norm", "scar_mask_to_indices"):
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().scar_strerror(int(status)).decode()
+
+
+def _check(status, what):
+    if status != 0:
+        raise ScarError(status, what)
+
+
+def _dev(t, what):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a torch tensor on the GPU" % what)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % what)
+    return t
+
+
+def _p(t):
+    return ctypes.c_void_p(t.data_ptr() if t is not None else 0)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def layout_of(x, block_len: int) -> Layout:
+    if x.dtype not in _DTYPE_OF:
+        raise TypeError("unsupported element type %s" % x.dtype)
+    return Layout(_DTYPE_OF[x.dtype], int(block_len), x.numel())
+
+
+def n_blocks(layout: Layout) -> int:
+    return int(lib().scar_n_blocks(ctypes.byref(layout)))
+
+
+def workspace_bytes(n_blocks_: int) -> int:
+    return int(lib().scar_workspace_bytes(int(n_blocks_)))
+
+
+def new_workspace(n_blocks_: int, device) -> torch.Tensor:
+    """A device buffer big enough for any call on a store of n_blocks_ blocks."""
+    return torch.empty(workspace_bytes(n_blocks_), dtype=torch.uint8, device=device)
+
+
+def block_scores(x, c, block_len, out=None):
+    """scar_block_scores: float32 (F32/BF16 stores) or int64 (I32 stores) score per block."""
+    _dev(x, "x"), _dev(c, "c")
+    if x.dtype != c.dtype or x.numel() != c.numel():
+        raise ValueError("x and c must have the same element type and size")
+    lay = layout_of(x, block_len)
+    nb = n_blocks(lay)
+    if out is None:
+        out = torch.empty(nb, dtype=torch.int64 if x.dtype == torch.int32 else torch.float32,
+                          device=x.device)
+    _dev(out, "out")
+    _check(lib().scar_block_scores(ctypes.byref(lay), _p(x), _p(c), _p(out), _stream()),
+           "scar_block_scores")
+    return out
+
+
+def select_topk(scores, k, workspace, out=None):
+    """scar_select_topk: ascending int32-viewed uint32 indices of the k largest scores."""
+    _dev(scores, "scores"), _dev(workspace, "workspace")
+    if scores.dtype == torch.float32:
+        st = SCORE_F32
+    elif scores.dtype == torch.int64:
+        st = SCORE_I64
+    else:
+        raise TypeError("scores must be float32 or int64")
+    if out is None:
+        out = torch.empty(int(k), dtype=torch.int32, device=scores.device)
+    _check(lib().scar_select_topk(st, _p(scores), scores.numel(), int(k), _p(out), _p(workspace),
+                                  workspace.numel(), _stream()), "scar_select_topk")
+    return out
+
+
+def checkpoint_commit(x, c, block_len, idx, staging=None, n_idx=None):
+    """scar_checkpoint_commit: c[b] <- x[b] for b in idx (optionally also packed into staging)."""
+    _dev(x, "x"), _dev(c, "c"), _dev(idx, "idx")
+    if x.dtype != c.dtype or x.numel() != c.numel():
+        raise ValueError("x and c must have the same element type and size")
+    lay = layout_of(x, block_len)
+    n = idx.numel() if n_idx is None else int(n_idx)
+    if staging is not None:
+        _dev(staging, "staging")
+        if staging.dtype != x.dtype or staging.numel() < n * block_len:
+            raise ValueError("staging must hold n_idx * block_len elements of x's type")
+    _check(lib().scar_checkpoint_commit(ctypes.byref(lay), _p(x), _p(c), _p(idx), n, _p(staging),
+                                        _stream()), "scar_checkpoint_commit")
+
+
+def _norm_buffer(device):
+    return torch.empty(3, dtype=torch.float64, device=device)
+
+
+def read_norm(buf):
+    """(sum, norm, isum) from a device scar_norm buffer; synchronises."""
+    host = buf.cpu()
+    return float(host[0]), float(host[1]), int(host[2:3].view(torch.int64)[0])
+
+
+def partial_recover(x, c, block_len, lost_idx, workspace=None, want_norm=True, norm_out=None, n_lost=None):
+    """scar_partial_recover: x[b] <- c[b] for the lost blocks; returns the device scar_norm
+    buffer (read it with read_norm) or None."""
+    _dev(x, "x"), _dev(c, "c"), _dev(lost_idx, "lost_idx")
+    if x.dtype != c.dtype or x.numel() != c.numel():
+        raise ValueError("x and c must have the same element type and size")
+    lay = layout_of(x, block_len)
+    n = lost_idx.numel() if n_lost is None else int(n_lost)
+    if want_norm and norm_out is None:
+        norm_out = _norm_buffer(x.device)
+    if not want_norm:
+        norm_out = None
+    _check(lib().scar_partial_recover(ctypes.byref(lay), _p(x), _p(c), _p(lost_idx), n, _p(norm_out),
+                                      _p(workspace), workspace.numel() if workspace is not None else 0,
+                                      _stream()), "scar_partial_recover")
+    return norm_out
+
+
+def perturbation_norm(x, c, block_len, idx, workspace, norm_out=None, n_idx=None):
+    """scar_perturbation_norm over the blocks in idx (None = all blocks); returns the device
+    scar_norm buffer."""
+    _dev(x, "x"), _dev(c, "c"), _dev(workspace, "workspace")
+    if x.dtype != c.dtype or x.numel() != c.numel():
+        raise ValueError("x and c must have the same element type and size")
+    lay = layout_of(x, block_len)
+    if norm_out is None:
+        norm_out = _norm_buffer(x.device)
+    if idx is None:
+        ptr, n = ctypes.c_void_p(0), 0
+    else:
+        _dev(idx, "idx")
+        n = idx.numel() if n_idx is None else int(n_idx)
+        # an empty list means "no blocks", not "all blocks": keep the pointer non-NULL
+        ptr = _p(idx) if idx.numel() else _p(norm_out)
+    _check(lib().scar_perturbation_norm(ctypes.byref(lay), _p(x), _p(c), ptr, n, _p(norm_out),
+                                        _p(workspace), workspace.numel(), _stream()),
+           "scar_perturbation_norm")
+    return norm_out
+
+
+def mask_to_indices(mask, workspace):
+    """scar_mask_to_indices: (indices buffer of n_blocks int32, device count tensor)."""
+    _dev(mask, "mask"), _dev(workspace, "workspace")
+    if mask.dtype not in (torch.uint8, torch.bool):
+        raise TypeError("mask must be uint8 or bool")
+    out = torch.empty(mask.numel(), dtype=torch.int32, device=mask.device)
+    cnt = torch.empty(1, dtype=torch.int32, device=mask.device)
+    _check(lib().scar_mask_to_indices(_p(mask), mask.numel(), _p(out), _p(cnt), _p(workspace),
+                                      workspace.numel(), _stream()), "scar_mask_to_indices")
+    return out, cnt

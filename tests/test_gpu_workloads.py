@@ -1,0 +1,83 @@
+"""Whole checkpoint / failure / recovery cycles on the synthetic MLR-, MF-, LDA-, CNN-like
+stores and the flat store, GPU against the oracle after every call, three cycles with the
+store drifting in between (the running checkpoint holds a mix of ages, Section 4.2)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1810_07354_amd import scar
+from paper_1810_07354_amd import workloads as wl
+from gpu_util import (DEV, REL_TOL, DeviceStore, assert_norm_matches, assert_scores_match,
+                      assert_selection_matches, idx_dev, idx_host, to_dev, to_host)
+
+pytestmark = pytest.mark.gpu
+
+
+def drift(store: DeviceStore, seed: int):
+    """Untimed stand-in for training between checkpoints: move a random tenth of the store."""
+    r = np.random.default_rng(seed)
+    n = store.hx.size
+    lo = int(r.integers(0, n - n // 10))
+    hi = lo + n // 10
+    if store.dtype == wl.I32:
+        store.hx[lo:hi] += r.integers(-2, 3, size=hi - lo).astype(np.int32)
+    elif store.dtype == wl.BF16:
+        f = wl.bf16_bits_to_f32(store.hx[lo:hi]) + r.normal(0, 1e-3, size=hi - lo).astype(np.float32)
+        store.hx[lo:hi] = wl.f32_to_bf16_bits(f)
+    else:
+        store.hx[lo:hi] += r.normal(0, 1e-3, size=hi - lo).astype(np.float32)
+    store.x = to_dev(store.hx, store.dtype)
+
+
+def three_cycles(w: wl.Workload, staging=False):
+    s = DeviceStore(w)
+    for cyc in range(3):
+        print("%s cycle %d" % (w.name, cyc), flush=True)
+        lost = w.lost if cyc == 0 else wl.random_lost_blocks(w.n_blocks, w.lost.size, 50 + cyc)
+        s.cycle(w.k, lost, staging=staging and cyc == 0)
+        drift(s, 900 + cyc)
+
+
+def test_mlr_like_full_size():
+    three_cycles(wl.mlr_like(), staging=True)
+
+
+def test_mf_like_full_size():
+    three_cycles(wl.mf_like())
+
+
+def test_lda_like_quarter_size():
+    three_cycles(wl.lda_like(words=25_000, topics=1000))
+
+
+@pytest.mark.parametrize("fraction", [0.01, 0.10, 0.50])
+def test_cnn_like_full_size(fraction):
+    three_cycles(wl.cnn_like(fraction=fraction))
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+def test_flat_like_16m(dtype):
+    three_cycles(wl.flat_like(n_elems=1 << 24, dtype=dtype))
+
+
+def test_priority_beats_round_robin_and_random_on_the_norm():
+    # Saving the most-changed blocks leaves a smaller full-recovery perturbation than
+    # saving the same number of blocks chosen round-robin or at random (Section 5.4).
+    w = wl.cnn_like(n_elems=4_000_000)
+    nb, k, L = w.n_blocks, w.k, w.block_len
+    x = to_dev(w.x, w.dtype)
+    ws = scar.new_workspace(nb, DEV)
+    res = {}
+    picks = {"priority": None,
+             "round": np.arange(k, dtype=np.uint32),
+             "random": np.sort(np.random.default_rng(1).choice(nb, size=k, replace=False)).astype(np.uint32)}
+    for name, idx in picks.items():
+        c = to_dev(w.c, w.dtype)
+        if idx is None:
+            d_idx = scar.select_topk(scar.block_scores(x, c, L), k, ws)
+        else:
+            d_idx = idx_dev(idx)
+        scar.checkpoint_commit(x, c, L, d_idx)
+        res[name] = scar.read_norm(scar.perturbation_norm(x, c, L, None, ws))[1]
+    assert res["priority"] < res["round"] and res["priority"] < res["random"]
