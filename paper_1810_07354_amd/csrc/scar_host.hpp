@@ -36,11 +36,11 @@ inline int pick_group(uint32_t block_len, int ebytes, bool vec) {
 
 // ---- workspace layout ---------------------------------------------------------------
 // [0, 64 KiB)    selection: digit histograms, pass state, tickets   (select, mask)
-// [64 KiB, +64 KiB)  per-workgroup partial sums of the norm           (recover, norm)
-// [128 KiB, ...) per-tile counts of the compaction, 8 bytes per tile (select, mask)
+// [64 KiB, +512 KiB) per-workgroup partial sums of the norm          (recover, norm)
+// [576 KiB, ...) per-tile counts of the compaction, 8 bytes per tile (select, mask)
 constexpr size_t kWsSelectBytes = 64 * 1024;
 constexpr size_t kWsNormOffset = kWsSelectBytes;
-constexpr size_t kWsNormBytes = 64 * 1024;
+constexpr size_t kWsNormBytes = 512 * 1024;
 constexpr size_t kWsTileOffset = kWsNormOffset + kWsNormBytes;
 constexpr uint32_t kTileKeys = 2048;   // keys per compaction tile
 constexpr uint32_t kMaxNormGrid = kWsNormBytes / 8;
@@ -59,6 +59,13 @@ inline int check_workspace(const void* ws, size_t bytes, uint64_t n_blocks) {
 // Upper bounds on grid sizes; kernels stride over the rest.
 constexpr uint64_t kScoreGridCap = 1u << 20;
 constexpr uint64_t kCopyGridCap = 1u << 20;
+
+// Grid for `need` workgroups, at most `cap`, rounded up to a multiple of 8 (one share per
+// XCD; the kernels skip the overshoot).
+inline uint32_t xcd_grid(uint64_t need, uint64_t cap) {
+  const uint64_t g = need < cap ? need : cap;
+  return (uint32_t)((g + 7) / 8 * 8);
+}
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? SCAR_OK : SCAR_ERR_DEVICE; }
 

@@ -21,7 +21,8 @@ __global__ __launch_bounds__(kWG) void k_commit(const char* __restrict__ x, char
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
   const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
-  for (uint64_t i = (uint64_t)blockIdx.x * GPW + grp; i < n_idx; i += (uint64_t)gridDim.x * GPW) {
+  for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
+       i += (uint64_t)gridDim.x * GPW) {
     const uint32_t b = idx[i];
     if (b >= n_blocks) continue;
     const BlockSpan sp = block_span(b, n_elems, block_len, sizeof(W));
@@ -50,7 +51,8 @@ __global__ __launch_bounds__(kWG) void k_recover(char* __restrict__ x, const cha
   __shared__ acc_t slots[kWG / kWave];
   acc_t acc = 0;
 
-  for (uint64_t i = (uint64_t)blockIdx.x * GPW + grp; i < n_idx; i += (uint64_t)gridDim.x * GPW) {
+  for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
+       i += (uint64_t)gridDim.x * GPW) {
     const uint32_t b = idx ? idx[i] : (uint32_t)i;
     if (b >= n_blocks) continue;
     const BlockSpan sp = block_span(b, n_elems, block_len, E);
@@ -63,8 +65,8 @@ __global__ __launch_bounds__(kWG) void k_recover(char* __restrict__ x, const cha
       for (int u = 0; u < kUnroll; ++u) {
         const uint32_t v = v0 + u * G + lane;
         if (v < nvec) {
-          cv[u] = ((const uint4*)cb)[v];
-          if (NORM) xv[u] = ((const uint4*)xb)[v];
+          cv[u] = load_stream((const uint4*)cb + v);
+          xv[u] = NORM ? load_stream((const uint4*)xb + v) : make_uint4(0, 0, 0, 0);
         } else {
           cv[u] = make_uint4(0, 0, 0, 0);
           xv[u] = make_uint4(0, 0, 0, 0);
@@ -75,7 +77,7 @@ __global__ __launch_bounds__(kWG) void k_recover(char* __restrict__ x, const cha
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
           const uint32_t v = v0 + u * G + lane;
-          if (v < nvec) ((uint4*)xb)[v] = cv[u];
+          if (v < nvec) store_stream((uint4*)xb + v, cv[u]);
         }
       }
     }
@@ -90,25 +92,31 @@ __global__ __launch_bounds__(kWG) void k_recover(char* __restrict__ x, const cha
   }
 }
 
-// Second stage of the norm: one workgroup adds n_partial partial sums in a fixed order
-// and writes the result.  n_partial == 0 writes zeros.
+// Second stage of the norm: one workgroup of 1024 threads adds n_partial partial sums in
+// a fixed order and writes the result.  n_partial == 0 writes zeros.
+constexpr int kFinishThreads = 1024;
 template <int DT>
-__global__ __launch_bounds__(kWG) void k_norm_finish(const typename Acc<DT>::type* __restrict__ partial,
-                                                     uint32_t n_partial, scar_norm* __restrict__ out) {
+__global__ __launch_bounds__(kFinishThreads) void k_norm_finish(
+    const typename Acc<DT>::type* __restrict__ partial, uint32_t n_partial, scar_norm* __restrict__ out) {
   using acc_t = typename Acc<DT>::type;
-  __shared__ acc_t slots[kWG / kWave];
+  __shared__ acc_t slots[kFinishThreads / kWave];
   acc_t acc = 0;
-  for (uint32_t i = threadIdx.x; i < n_partial; i += kWG) acc += partial[i];
-  acc = workgroup_sum(acc, slots);
+#pragma unroll 8
+  for (uint32_t i = threadIdx.x; i < n_partial; i += kFinishThreads) acc += partial[i];
+  acc = group_sum<kWave>(acc);
+  if ((threadIdx.x & (kWave - 1)) == 0) slots[threadIdx.x / kWave] = acc;
+  __syncthreads();
   if (threadIdx.x == 0) {
+    acc_t total = 0;
+    for (int w = 0; w < kFinishThreads / kWave; ++w) total += slots[w];
     if constexpr (DT == DT_I32) {
-      out->isum = (long long)acc;
-      out->sum = (double)acc;
-      out->norm = (double)acc;
+      out->isum = (long long)total;
+      out->sum = (double)total;
+      out->norm = (double)total;
     } else {
       out->isum = 0;
-      out->sum = acc;
-      out->norm = sqrt(acc);
+      out->sum = total;
+      out->norm = sqrt(total);
     }
   }
 }
@@ -119,7 +127,7 @@ static void launch_commit(const scar_layout* l, const void* x, void* c, const ui
                           hipStream_t st) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
-  const uint32_t grid = (uint32_t)(need < kCopyGridCap ? need : kCopyGridCap);
+  const uint32_t grid = xcd_grid(need, kCopyGridCap);
   hipLaunchKernelGGL((k_commit<G, W>), dim3(grid), dim3(kWG), 0, st, (const char*)x, (char*)c, idx,
                      n_idx, (char*)staging, l->n_elems, l->block_len, n_blocks, vec, vec_st);
 }
@@ -147,7 +155,7 @@ static uint32_t launch_recover(const scar_layout* l, void* x, const void* c, con
                                hipStream_t st) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
-  const uint32_t grid = (uint32_t)(need < kMaxNormGrid ? need : kMaxNormGrid);
+  const uint32_t grid = xcd_grid(need, kMaxNormGrid);
   hipLaunchKernelGGL((k_recover<DT, G, STORE, NORM>), dim3(grid), dim3(kWG), 0, st, (char*)x,
                      (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, vec,
                      (typename Acc<DT>::type*)partial);
@@ -184,10 +192,10 @@ static uint32_t dispatch_recover(int g, const scar_layout* l, void* x, const voi
 static void launch_finish(int32_t dtype, const void* partial, uint32_t n_partial, scar_norm* out,
                           hipStream_t st) {
   if (dtype == SCAR_I32)
-    hipLaunchKernelGGL((k_norm_finish<DT_I32>), dim3(1), dim3(kWG), 0, st,
+    hipLaunchKernelGGL((k_norm_finish<DT_I32>), dim3(1), dim3(kFinishThreads), 0, st,
                        (const unsigned long long*)partial, n_partial, out);
   else
-    hipLaunchKernelGGL((k_norm_finish<DT_F32>), dim3(1), dim3(kWG), 0, st, (const double*)partial,
+    hipLaunchKernelGGL((k_norm_finish<DT_F32>), dim3(1), dim3(kFinishThreads), 0, st, (const double*)partial,
                        n_partial, out);
 }
 

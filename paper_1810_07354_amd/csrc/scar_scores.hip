@@ -4,7 +4,8 @@
 // The kernel is a pure two-stream read: 2 * n_elems * element-size bytes in, one score
 // per block out.  G lanes walk one block with 16-byte loads from x and from c issued
 // back to back (kUnroll of each before the first use), the per-lane sums are combined
-// with wavefront shuffles (G <= 64) or shuffles plus one LDS step (G = 256).
+// with wavefront shuffles (G <= 64) or shuffles plus one LDS step (G = 256).  Loads are
+// non-temporal and each XCD walks one contiguous eighth of the store.
 #include "scar_device.hpp"
 #include "scar_host.hpp"
 
@@ -21,7 +22,8 @@ __global__ __launch_bounds__(kWG) void k_block_scores(const char* __restrict__ x
   const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
   __shared__ acc_t slots[kWG / kWave];
 
-  for (uint64_t b = (uint64_t)blockIdx.x * GPW + grp; b < n_blocks; b += (uint64_t)gridDim.x * GPW) {
+  for (uint64_t b = (uint64_t)xcd_contiguous_block_id() * GPW + grp; b < n_blocks;
+       b += (uint64_t)gridDim.x * GPW) {
     const BlockSpan sp = block_span(b, n_elems, block_len, elem_bytes(DT));
     acc_t acc = block_distance<DT, G>(x + sp.byte_off, c + sp.byte_off, sp.len, lane, vec);
     if constexpr (G == 256)
@@ -42,7 +44,7 @@ static void launch_scores(const scar_layout* l, const void* x, const void* c, vo
                           uint32_t n_blocks, bool vec, hipStream_t st) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const uint64_t need = ((uint64_t)n_blocks + GPW - 1) / GPW;
-  const uint32_t grid = (uint32_t)(need < kScoreGridCap ? need : kScoreGridCap);
+  const uint32_t grid = xcd_grid(need, kScoreGridCap);
   hipLaunchKernelGGL((k_block_scores<DT, G>), dim3(grid), dim3(kWG), 0, st, (const char*)x,
                      (const char*)c, scores, l->n_elems, l->block_len, n_blocks, vec);
 }

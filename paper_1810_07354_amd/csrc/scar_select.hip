@@ -4,15 +4,16 @@
 // Scores become unsigned keys whose integer order is the score order (NaN on top, -0
 // equal to +0).  A most-significant-digit-first radix select finds the k-th largest key
 // T: each pass builds a histogram of one digit of the keys that still match the prefix
-// found so far (LDS histogram per workgroup, then one global atomic per non-empty bin);
-// the last workgroup to finish a pass walks the histogram from the top and fixes the
-// next digit.  No pass waits for another workgroup: the hand-over is a ticket counter.
+// found so far (LDS histogram per workgroup, then one global atomic per non-empty bin).
+// The next kernel in the stream walks the finished histogram from the top and fixes the
+// digit - every workgroup does this small walk for itself, so no workgroup ever waits
+// for another and no device-wide fence is needed inside a kernel.
 // After the last pass every key > T is selected together with the first `take` keys
 // equal to T in index order, where take = k - #(keys > T).
 //
 // The chosen indices are then written in ascending order by a two-level prefix sum
-// (per-tile counts, scan of the tile counts by the last workgroup, per-tile write), so
-// the result does not depend on the order in which workgroups run.
+// (per-tile counts, prefix over the tiles, per-tile write), so the result does not
+// depend on the order in which workgroups run.
 #include "scar_device.hpp"
 #include "scar_host.hpp"
 
@@ -20,8 +21,7 @@ namespace scar {
 
 constexpr int kMaxBins = 2048;
 constexpr int kMaxPasses = 6;
-constexpr uint32_t kHistKeysPerWG = 4096;
-constexpr uint32_t kHistGridCap = 2048;
+constexpr uint32_t kHistGridCap = 1u << 14;
 constexpr uint32_t kTileGridCap = 1u << 16;
 constexpr int kKeysPerThread = kTileKeys / kWG;  // 8 consecutive keys per thread
 
@@ -33,11 +33,10 @@ struct SelectState {
   uint32_t pad;
 };
 
-// Layout of the selection part of the workspace.
+// Layout of the selection part of the workspace.  state[p] is the state before pass p.
 struct SelectWs {
   uint32_t hist[kMaxPasses][kMaxBins];
   SelectState state[kMaxPasses + 1];
-  uint32_t ticket[kMaxPasses + 2];
 };
 static_assert(sizeof(SelectWs) <= kWsSelectBytes, "selection scratch exceeds its share");
 
@@ -99,20 +98,7 @@ __device__ __forceinline__ T workgroup_exclusive_scan(T v, T* slots, T* total) {
   return base + inc - v;
 }
 
-// True in every thread of exactly one workgroup: the last one to get here.  Everything
-// the other workgroups wrote before their call is visible to it afterwards.
-__device__ __forceinline__ bool last_workgroup(uint32_t* ticket) {
-  __shared__ uint32_t s_last;
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) s_last = (atomicAdd(ticket, 1u) == gridDim.x - 1);
-  __syncthreads();
-  const bool last = s_last != 0;
-  if (last) __threadfence();
-  return last;
-}
-
-// One workgroup zeroes the histograms, pass states and tickets and sets the first state.
+// One workgroup zeroes the histograms and sets the state before the first pass.
 __global__ __launch_bounds__(kWG) void k_select_clear(SelectWs* ws, uint32_t k) {
   uint32_t* words = (uint32_t*)ws;
   for (uint32_t i = threadIdx.x; i < sizeof(SelectWs) / 4; i += kWG) words[i] = 0;
@@ -120,58 +106,83 @@ __global__ __launch_bounds__(kWG) void k_select_clear(SelectWs* ws, uint32_t k) 
   if (threadIdx.x == 0) ws->state[0].k_rem = k;
 }
 
-// One radix pass: histogram of digit `pass` over the keys matching state[pass].prefix;
-// the last workgroup derives state[pass + 1].
-template <int SRC>
-__global__ __launch_bounds__(kWG) void k_select_hist(const void* __restrict__ scores, uint32_t n,
-                                                     int pass, SelectWs* __restrict__ ws) {
-  using K = Key<SRC>;
-  using key_t = typename K::type;
-  __shared__ uint32_t lh[kMaxBins];
-  __shared__ uint32_t scan_slots[kWG / kWave + 1];
-  for (int b = threadIdx.x; b < kMaxBins; b += kWG) lh[b] = 0;
-  __syncthreads();
-  const SelectState cur = ws->state[pass];
-  const int shift = K::shift(pass), bits = K::bits(pass);
-  const uint32_t mask = (1u << bits) - 1;
-  for (uint64_t i = (uint64_t)blockIdx.x * kWG + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kWG) {
-    const key_t key = K::load(scores, i);
-    const bool match = pass == 0 || (key >> (shift + bits)) == (key_t)cur.prefix;
-    if (match) atomicAdd(&lh[(uint32_t)(key >> shift) & mask], 1u);
-  }
-  __syncthreads();
-  uint32_t* gh = ws->hist[pass];
-  for (int b = threadIdx.x; b < kMaxBins; b += kWG)
-    if (lh[b]) atomicAdd(&gh[b], lh[b]);
-
-  if (!last_workgroup(&ws->ticket[pass])) return;
-
-  // Walk the finished histogram from the top bin down; thread t owns 8 consecutive bins.
+// Given the finished histogram of one digit and the state before that digit, walk the
+// bins from the top down to the one that holds the k_rem-th largest remaining key.
+// Every thread of the workgroup gets the state after the digit.  `scratch` is LDS for
+// kWG / kWave + 1 counters, `result` LDS for one state.
+__device__ __forceinline__ SelectState next_state(const uint32_t* __restrict__ gh, int bits,
+                                                  const SelectState cur, uint32_t* scratch,
+                                                  SelectState* result) {
   const int nbins = 1 << bits;
-  constexpr int kOwn = kMaxBins / kWG;
+  constexpr int kOwn = kMaxBins / kWG;  // thread t owns bins nbins-1-8t ... nbins-8-8t
   uint32_t own[kOwn];
   uint32_t cnt = 0;
 #pragma unroll
   for (int j = 0; j < kOwn; ++j) {
     const int b = nbins - 1 - ((int)threadIdx.x * kOwn + j);
-    own[j] = b >= 0 ? __hip_atomic_load(&gh[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+    own[j] = b >= 0 ? gh[b] : 0;
     cnt += own[j];
   }
   uint32_t total;
-  uint32_t above = workgroup_exclusive_scan(cnt, scan_slots, &total);
-  const uint32_t k_rem = cur.k_rem;
-  if (above < k_rem && k_rem <= above + cnt) {
+  uint32_t above = workgroup_exclusive_scan(cnt, scratch, &total);
+  if (above < cur.k_rem && cur.k_rem <= above + cnt) {  // true in exactly one thread
 #pragma unroll
     for (int j = 0; j < kOwn; ++j) {
-      if (above + own[j] >= k_rem) {
+      if (above + own[j] >= cur.k_rem) {
         const int b = nbins - 1 - ((int)threadIdx.x * kOwn + j);
-        ws->state[pass + 1].prefix = (cur.prefix << bits) | (unsigned long long)b;
-        ws->state[pass + 1].k_rem = k_rem - above;
+        result->prefix = (cur.prefix << bits) | (unsigned long long)b;
+        result->k_rem = cur.k_rem - above;
+        result->pad = 0;
         break;
       }
       above += own[j];
     }
   }
+  __syncthreads();
+  return *result;
+}
+
+// One radix pass over tiles of kTileKeys keys.  Each workgroup first derives the state
+// before this pass from the previous pass's finished histogram (all workgroups compute
+// the same values; workgroup 0 also stores them for later kernels), then adds the digit
+// histogram of the keys that match the prefix.
+template <int SRC>
+__global__ __launch_bounds__(kWG) void k_select_hist(const void* __restrict__ scores, uint32_t n,
+                                                     uint32_t n_tiles, int pass,
+                                                     SelectWs* __restrict__ ws) {
+  using K = Key<SRC>;
+  using key_t = typename K::type;
+  __shared__ uint32_t lh[kMaxBins];
+  __shared__ uint32_t scratch[kWG / kWave + 1];
+  __shared__ SelectState shared_state;
+  for (int b = threadIdx.x; b < kMaxBins; b += kWG) lh[b] = 0;
+  SelectState cur = ws->state[pass == 0 ? 0 : pass - 1];
+  if (pass > 0) {
+    cur = next_state(ws->hist[pass - 1], K::bits(pass - 1), cur, scratch, &shared_state);
+    if (blockIdx.x == 0 && threadIdx.x == 0) ws->state[pass] = cur;
+  }
+  __syncthreads();
+  const int shift = K::shift(pass), bits = K::bits(pass);
+  const uint32_t mask = (1u << bits) - 1;
+  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const uint64_t base = (uint64_t)tile * kTileKeys + threadIdx.x;
+    key_t key[kKeysPerThread];
+#pragma unroll
+    for (int j = 0; j < kKeysPerThread; ++j) {
+      const uint64_t i = base + (uint64_t)j * kWG;
+      key[j] = K::load(scores, i < n ? i : n - 1);
+    }
+#pragma unroll
+    for (int j = 0; j < kKeysPerThread; ++j) {
+      const uint64_t i = base + (uint64_t)j * kWG;
+      const bool match = pass == 0 || (key[j] >> (shift + bits)) == (key_t)cur.prefix;
+      if (i < n && match) atomicAdd(&lh[(uint32_t)(key[j] >> shift) & mask], 1u);
+    }
+  }
+  __syncthreads();
+  uint32_t* gh = ws->hist[pass];
+  for (int b = threadIdx.x; b < kMaxBins; b += kWG)
+    if (lh[b]) atomicAdd(&gh[b], lh[b]);
 }
 
 // 0 = not selected on its own, 1 = above the threshold, 2 = equal to the threshold.
@@ -182,20 +193,27 @@ __device__ __forceinline__ int classify(const void* src, uint64_t i, typename Ke
   return key > T ? 1 : (key == T ? 2 : 0);
 }
 
-// Per-tile counts (above, equal); the last workgroup turns them into exclusive prefix
-// sums over the tiles, in place, and reports the number of "above" entries if asked.
+// Per-tile counts of (above, equal), packed as low / high 32 bits.  For a selection the
+// threshold is first derived from the last pass's histogram, as in k_select_hist.
 template <int SRC>
 __global__ __launch_bounds__(kWG) void k_compact_count(const void* __restrict__ src, uint32_t n,
-                                                       uint32_t n_tiles, int final_pass,
+                                                       uint32_t n_tiles, int passes,
                                                        SelectWs* __restrict__ ws,
-                                                       unsigned long long* __restrict__ tile_cnt,
-                                                       uint32_t* __restrict__ out_count) {
+                                                       unsigned long long* __restrict__ tile_cnt) {
   using key_t = typename Key<SRC>::type;
-  __shared__ unsigned long long slots[kWG / kWave + 1];
-  const key_t T = SRC == SRC_MASK ? 0 : (key_t)ws->state[final_pass].prefix;
+  __shared__ unsigned long long slots[kWG / kWave];
+  __shared__ uint32_t scratch[kWG / kWave + 1];
+  __shared__ SelectState shared_state;
+  key_t T = 0;
+  if constexpr (SRC != SRC_MASK) {
+    const SelectState fin = next_state(ws->hist[passes - 1], Key<SRC>::bits(passes - 1),
+                                       ws->state[passes - 1], scratch, &shared_state);
+    if (blockIdx.x == 0 && threadIdx.x == 0) ws->state[passes] = fin;
+    T = (key_t)fin.prefix;
+  }
   for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
     const uint64_t base = (uint64_t)tile * kTileKeys + threadIdx.x * kKeysPerThread;
-    unsigned long long cnt = 0;  // low word: above, high word: equal
+    unsigned long long cnt = 0;
 #pragma unroll
     for (int j = 0; j < kKeysPerThread; ++j) {
       if (base + j < n) {
@@ -206,14 +224,17 @@ __global__ __launch_bounds__(kWG) void k_compact_count(const void* __restrict__ 
     cnt = workgroup_sum(cnt, slots);
     if (threadIdx.x == 0) tile_cnt[tile] = cnt;
   }
+}
 
-  if (!last_workgroup(&ws->ticket[kMaxPasses])) return;
-
+// Exclusive prefix sums of the per-tile counts, in place, by one workgroup; used when
+// there are too many tiles for every writer to add up its predecessors itself.
+__global__ __launch_bounds__(kWG) void k_compact_scan(unsigned long long* __restrict__ tile_cnt,
+                                                      uint32_t n_tiles, uint32_t* __restrict__ out_count) {
+  __shared__ unsigned long long slots[kWG / kWave + 1];
   unsigned long long running = 0;
   for (uint32_t t0 = 0; t0 < n_tiles; t0 += kWG) {
     const uint32_t t = t0 + threadIdx.x;
-    const unsigned long long v =
-        t < n_tiles ? __hip_atomic_load(&tile_cnt[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+    const unsigned long long v = t < n_tiles ? tile_cnt[t] : 0;
     unsigned long long total;
     const unsigned long long ex = workgroup_exclusive_scan(v, slots, &total);
     if (t < n_tiles) tile_cnt[t] = running + ex;
@@ -223,17 +244,37 @@ __global__ __launch_bounds__(kWG) void k_compact_count(const void* __restrict__ 
 }
 
 // Writes the selected indices of each tile at their final, ascending positions.
-template <int SRC>
+//   SCANNED: tile_cnt already holds exclusive prefix sums (k_compact_scan ran); otherwise
+//   it holds raw counts and each workgroup adds up the tiles before its own (few tiles).
+template <int SRC, bool SCANNED>
 __global__ __launch_bounds__(kWG) void k_compact_write(const void* __restrict__ src, uint32_t n,
-                                                       uint32_t n_tiles, int final_pass,
+                                                       uint32_t n_tiles, int passes,
                                                        const SelectWs* __restrict__ ws,
-                                                       const unsigned long long* __restrict__ tile_off,
-                                                       uint32_t* __restrict__ out_idx, uint32_t out_cap) {
+                                                       const unsigned long long* __restrict__ tile_cnt,
+                                                       uint32_t* __restrict__ out_idx, uint32_t out_cap,
+                                                       uint32_t* __restrict__ out_count) {
   using key_t = typename Key<SRC>::type;
   __shared__ uint32_t slots[kWG / kWave + 1];
-  const key_t T = SRC == SRC_MASK ? 0 : (key_t)ws->state[final_pass].prefix;
-  const uint32_t take = SRC == SRC_MASK ? 0 : ws->state[final_pass].k_rem;
+  __shared__ unsigned long long wide[kWG / kWave];
+  const key_t T = SRC == SRC_MASK ? 0 : (key_t)ws->state[passes].prefix;
+  const uint32_t take = SRC == SRC_MASK ? 0 : ws->state[passes].k_rem;
   for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    unsigned long long off;
+    if constexpr (SCANNED) {
+      off = tile_cnt[tile];
+    } else {
+      unsigned long long before = 0, all = 0;
+      for (uint32_t t = threadIdx.x; t < n_tiles; t += kWG) {
+        const unsigned long long v = tile_cnt[t];
+        all += v;
+        if (t < tile) before += v;
+      }
+      off = workgroup_sum(before, wide);
+      if (out_count && tile == 0) {
+        all = workgroup_sum(all, wide);
+        if (threadIdx.x == 0) *out_count = (uint32_t)all;
+      }
+    }
     const uint64_t base = (uint64_t)tile * kTileKeys + threadIdx.x * kKeysPerThread;
     int cls[kKeysPerThread];
     uint32_t cnt = 0;  // low half: above, high half: equal (a tile holds 2048 keys)
@@ -244,7 +285,6 @@ __global__ __launch_bounds__(kWG) void k_compact_write(const void* __restrict__ 
     }
     uint32_t total;
     const uint32_t ex = workgroup_exclusive_scan(cnt, slots, &total);
-    const unsigned long long off = tile_off[tile];
     uint32_t n_above = (uint32_t)off + (ex & 0xffffu);
     uint32_t n_equal = (uint32_t)(off >> 32) + (ex >> 16);
 #pragma unroll
@@ -264,22 +304,40 @@ __global__ __launch_bounds__(kWG) void k_compact_write(const void* __restrict__ 
   }
 }
 
+constexpr uint32_t kSelfScanTiles = 2048;  // up to here writers add up their predecessors
+
+// count -> (scan) -> write, shared by selection and mask compaction.
+template <int SRC>
+static void run_compaction(const void* src, uint32_t n, int passes, SelectWs* ws,
+                           unsigned long long* tiles, uint32_t* out_idx, uint32_t out_cap,
+                           uint32_t* out_count, hipStream_t st) {
+  const uint32_t n_tiles = (uint32_t)n_tiles_of(n);
+  const uint32_t tgrid = n_tiles < kTileGridCap ? n_tiles : kTileGridCap;
+  hipLaunchKernelGGL((k_compact_count<SRC>), dim3(tgrid), dim3(kWG), 0, st, src, n, n_tiles, passes,
+                     ws, tiles);
+  if (n_tiles <= kSelfScanTiles) {
+    hipLaunchKernelGGL((k_compact_write<SRC, false>), dim3(tgrid), dim3(kWG), 0, st, src, n, n_tiles,
+                       passes, (const SelectWs*)ws, (const unsigned long long*)tiles, out_idx, out_cap,
+                       out_count);
+  } else {
+    hipLaunchKernelGGL(k_compact_scan, dim3(1), dim3(kWG), 0, st, tiles, n_tiles, out_count);
+    hipLaunchKernelGGL((k_compact_write<SRC, true>), dim3(tgrid), dim3(kWG), 0, st, src, n, n_tiles,
+                       passes, (const SelectWs*)ws, (const unsigned long long*)tiles, out_idx, out_cap,
+                       (uint32_t*)nullptr);
+  }
+}
+
 template <int SRC>
 static void run_select(const void* scores, uint32_t n, uint32_t k, uint32_t* out_idx, void* workspace,
                        hipStream_t st) {
   SelectWs* ws = (SelectWs*)workspace;
   unsigned long long* tiles = (unsigned long long*)((char*)workspace + kWsTileOffset);
   hipLaunchKernelGGL(k_select_clear, dim3(1), dim3(kWG), 0, st, ws, k);
-  uint32_t hgrid = (n + kHistKeysPerWG - 1) / kHistKeysPerWG;
-  if (hgrid > kHistGridCap) hgrid = kHistGridCap;
-  for (int p = 0; p < Key<SRC>::passes; ++p)
-    hipLaunchKernelGGL((k_select_hist<SRC>), dim3(hgrid), dim3(kWG), 0, st, scores, n, p, ws);
   const uint32_t n_tiles = (uint32_t)n_tiles_of(n);
-  const uint32_t tgrid = n_tiles < kTileGridCap ? n_tiles : kTileGridCap;
-  hipLaunchKernelGGL((k_compact_count<SRC>), dim3(tgrid), dim3(kWG), 0, st, scores, n, n_tiles,
-                     Key<SRC>::passes, ws, tiles, (uint32_t*)nullptr);
-  hipLaunchKernelGGL((k_compact_write<SRC>), dim3(tgrid), dim3(kWG), 0, st, scores, n, n_tiles,
-                     Key<SRC>::passes, (const SelectWs*)ws, (const unsigned long long*)tiles, out_idx, k);
+  const uint32_t hgrid = n_tiles < kHistGridCap ? n_tiles : kHistGridCap;
+  for (int p = 0; p < Key<SRC>::passes; ++p)
+    hipLaunchKernelGGL((k_select_hist<SRC>), dim3(hgrid), dim3(kWG), 0, st, scores, n, n_tiles, p, ws);
+  run_compaction<SRC>(scores, n, Key<SRC>::passes, ws, tiles, out_idx, k, nullptr, st);
 }
 
 }  // namespace scar
@@ -312,17 +370,11 @@ extern "C" int scar_mask_to_indices(const uint8_t* mask, uint32_t n_blocks, uint
   const int rc = check_workspace(workspace, workspace_bytes, n_blocks);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;
-  SelectWs* ws = (SelectWs*)workspace;
   unsigned long long* tiles = (unsigned long long*)((char*)workspace + kWsTileOffset);
-  hipLaunchKernelGGL(k_select_clear, dim3(1), dim3(kWG), 0, st, ws, 0u);
-  const uint32_t n_tiles = (uint32_t)n_tiles_of(n_blocks);
-  // at least one workgroup, so that *out_count is written even for an empty mask
-  const uint32_t tgrid = n_tiles == 0 ? 1 : (n_tiles < kTileGridCap ? n_tiles : kTileGridCap);
-  hipLaunchKernelGGL((k_compact_count<SRC_MASK>), dim3(tgrid), dim3(kWG), 0, st, (const void*)mask,
-                     n_blocks, n_tiles, 0, ws, tiles, out_count);
-  if (n_tiles)
-    hipLaunchKernelGGL((k_compact_write<SRC_MASK>), dim3(tgrid), dim3(kWG), 0, st, (const void*)mask,
-                       n_blocks, n_tiles, 0, (const SelectWs*)ws, (const unsigned long long*)tiles,
-                       out_idx, n_blocks);
+  if (n_blocks == 0)  // nothing to scan: the one-workgroup scan of zero tiles writes *out_count = 0
+    hipLaunchKernelGGL(k_compact_scan, dim3(1), dim3(kWG), 0, st, tiles, 0u, out_count);
+  else
+    run_compaction<SRC_MASK>(mask, n_blocks, 0, (SelectWs*)workspace, tiles, out_idx, n_blocks,
+                             out_count, st);
   return launch_status();
 }
