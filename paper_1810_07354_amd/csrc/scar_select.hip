@@ -22,7 +22,7 @@ namespace scar {
 constexpr int kMaxBins = 2048;
 constexpr int kMaxPasses = 6;
 constexpr uint32_t kHistGridCap = 1u << 14;
-constexpr uint32_t kTileGridCap = 1u << 16;
+constexpr uint32_t kTileGridCap = 1u << 14;
 constexpr int kKeysPerThread = kTileKeys / kWG;  // 8 consecutive keys per thread
 
 enum : int { SRC_F32 = 0, SRC_I64 = 1, SRC_MASK = 2 };
@@ -304,6 +304,66 @@ __global__ __launch_bounds__(kWG) void k_compact_write(const void* __restrict__ 
   }
 }
 
+// Whole selection in one workgroup for small stores (n <= kSmallSelect): keys stay in
+// registers (kSmallKeys consecutive keys per thread), histograms in LDS, one launch
+// instead of six or nine.
+constexpr uint32_t kSmallSelect = 8192;
+template <int SRC>
+__global__ __launch_bounds__(kWG) void k_select_small(const void* __restrict__ scores, uint32_t n,
+                                                      uint32_t k, uint32_t* __restrict__ out_idx) {
+  using K = Key<SRC>;
+  using key_t = typename K::type;
+  constexpr int kSmallKeys = kSmallSelect / kWG;
+  __shared__ uint32_t lh[kMaxBins];
+  __shared__ uint32_t scratch[kWG / kWave + 1];
+  __shared__ SelectState shared_state;
+  const uint32_t base = threadIdx.x * kSmallKeys;
+  key_t key[kSmallKeys];
+#pragma unroll
+  for (int j = 0; j < kSmallKeys; ++j) key[j] = K::load(scores, base + j < n ? base + j : n - 1);
+
+  SelectState cur;
+  cur.prefix = 0, cur.k_rem = k, cur.pad = 0;
+  for (int pass = 0; pass < K::passes; ++pass) {
+    for (int b = threadIdx.x; b < kMaxBins; b += kWG) lh[b] = 0;
+    __syncthreads();
+    const int shift = K::shift(pass), bits = K::bits(pass);
+    const uint32_t mask = (1u << bits) - 1;
+#pragma unroll
+    for (int j = 0; j < kSmallKeys; ++j) {
+      const bool match = pass == 0 || (key[j] >> (shift + bits)) == (key_t)cur.prefix;
+      if (base + j < n && match) atomicAdd(&lh[(uint32_t)(key[j] >> shift) & mask], 1u);
+    }
+    __syncthreads();
+    cur = next_state(lh, bits, cur, scratch, &shared_state);
+    __syncthreads();
+  }
+  const key_t T = (key_t)cur.prefix;
+  const uint32_t take = cur.k_rem;
+  uint32_t cnt = 0;  // low half: above, high half: equal
+#pragma unroll
+  for (int j = 0; j < kSmallKeys; ++j)
+    if (base + j < n) cnt += key[j] > T ? 1u : (key[j] == T ? (1u << 16) : 0u);
+  uint32_t total;
+  const uint32_t ex = workgroup_exclusive_scan(cnt, scratch, &total);
+  uint32_t n_above = ex & 0xffffu, n_equal = ex >> 16;
+#pragma unroll
+  for (int j = 0; j < kSmallKeys; ++j) {
+    if (base + j >= n) break;
+    if (key[j] > T) {
+      const uint32_t pos = n_above + (n_equal < take ? n_equal : take);
+      if (pos < k) out_idx[pos] = base + j;
+      ++n_above;
+    } else if (key[j] == T) {
+      if (n_equal < take) {
+        const uint32_t pos = n_above + n_equal;
+        if (pos < k) out_idx[pos] = base + j;
+      }
+      ++n_equal;
+    }
+  }
+}
+
 constexpr uint32_t kSelfScanTiles = 2048;  // up to here writers add up their predecessors
 
 // count -> (scan) -> write, shared by selection and mask compaction.
@@ -330,6 +390,10 @@ static void run_compaction(const void* src, uint32_t n, int passes, SelectWs* ws
 template <int SRC>
 static void run_select(const void* scores, uint32_t n, uint32_t k, uint32_t* out_idx, void* workspace,
                        hipStream_t st) {
+  if (n <= kSmallSelect) {
+    hipLaunchKernelGGL((k_select_small<SRC>), dim3(1), dim3(kWG), 0, st, scores, n, k, out_idx);
+    return;
+  }
   SelectWs* ws = (SelectWs*)workspace;
   unsigned long long* tiles = (unsigned long long*)((char*)workspace + kWsTileOffset);
   hipLaunchKernelGGL(k_select_clear, dim3(1), dim3(kWG), 0, st, ws, k);

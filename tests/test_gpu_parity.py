@@ -63,6 +63,7 @@ def test_block_scores_int_extremes():
 
 
 @pytest.mark.parametrize("n,kind", [(1, "rand"), (7, "rand"), (2048, "rand"), (2049, "rand"),
+                                    (8192, "ties"), (8193, "ties"), (5000, "special"), (8000, "zeros"),
                                     (10_000, "rand"), (300_000, "rand"), (300_000, "ties"),
                                     (50_000, "zeros"), (70_000, "special")])
 def test_select_topk_float(n, kind):
@@ -90,7 +91,8 @@ def test_select_topk_float(n, kind):
         np.testing.assert_array_equal(got, oracle.select_topk(s.astype(np.float64), k))
 
 
-@pytest.mark.parametrize("n,hi", [(5, 3), (4097, 4), (100_000, 50), (100_000, 2 ** 40), (30_000, 1)])
+@pytest.mark.parametrize("n,hi", [(5, 3), (4097, 4), (8192, 2 ** 40), (100_000, 50), (100_000, 2 ** 40),
+                                  (30_000, 1)])
 def test_select_topk_int(n, hi):
     r = np.random.default_rng(n + 1)
     s = r.integers(0, hi, size=n).astype(np.int64)
@@ -104,6 +106,25 @@ def test_select_topk_int(n, hi):
         print("select int n=%d hi=%d k=%d" % (n, hi, k), flush=True)
         got = idx_host(scar.select_topk(d, k, ws))
         np.testing.assert_array_equal(got, oracle.select_topk(s, k))
+
+
+@pytest.mark.parametrize("n,k", [(5_000_000, 1234), (5_000_000, 2_500_000), (33_554_432 + 5000, 40_000)])
+def test_select_topk_many_tiles(n, k):
+    # more tiles than one workgroup sums on its own (separate scan kernel) and, for the
+    # largest case, more tiles than the grid (every workgroup strides over several)
+    r = np.random.default_rng(n + k)
+    s = r.integers(0, 1 << 20, size=n).astype(np.float32)       # many ties
+    d = torch.from_numpy(s).to(DEV)
+    ws = scar.new_workspace(n, DEV)
+    print("select many tiles n=%d k=%d" % (n, k), flush=True)
+    got = idx_host(scar.select_topk(d, k, ws))
+    oracle.set_num_threads(1)
+    np.testing.assert_array_equal(got, oracle.select_topk(s.astype(np.float64), k))
+    m = (s > (1 << 19)).astype(np.uint8)
+    out, cnt = scar.mask_to_indices(torch.from_numpy(m).to(DEV), ws)
+    want = oracle.mask_to_indices(m)
+    assert int(cnt.item()) == want.size
+    np.testing.assert_array_equal(idx_host(out)[: want.size], want)
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16, I32])
