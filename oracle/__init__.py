@@ -44,6 +44,10 @@ def lib():
         L.oracle_perturbation_norm.argtypes = [i32, vp, vp, u64, u32, vp, u32, ctypes.POINTER(Norm)]
         L.oracle_partial_recover.argtypes = [i32, vp, vp, u64, u32, vp, u32, ctypes.POINTER(Norm)]
         L.oracle_mask_to_indices.argtypes = [vp, u32, vp, ctypes.POINTER(u32)]
+        L.oracle_select_round.argtypes = [u32, u32, u64, vp]
+        L.oracle_select_random.argtypes = [u32, u32, u64, u64, vp]
+        L.oracle_philox4x32_10.argtypes = [vp, vp, vp]
+        L.oracle_philox4x32_10.restype = None
         _lib = L
     return _lib
 
@@ -173,3 +177,25 @@ def mask_to_indices(mask):
     _check(lib().oracle_mask_to_indices(_ptr(mask), mask.size, _ptr(out), ctypes.byref(cnt)),
            "oracle_mask_to_indices")
     return out[:cnt.value].copy()
+
+
+def select_round(n_blocks, k, cursor):
+    """Round-robin strategy: the k blocks from `cursor` on (mod n_blocks), ascending."""
+    out = np.zeros(k, dtype=np.uint32)
+    _check(lib().oracle_select_round(n_blocks, k, cursor, _ptr(out)), "oracle_select_round")
+    return out
+
+
+def select_random(n_blocks, k, seed, draw):
+    """Random strategy: a uniformly random k-subset fixed by (seed, draw), ascending."""
+    out = np.zeros(k, dtype=np.uint32)
+    _check(lib().oracle_select_random(n_blocks, k, seed, draw, _ptr(out)), "oracle_select_random")
+    return out
+
+
+def philox4x32_10(counter, key):
+    c = np.ascontiguousarray(counter, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().oracle_philox4x32_10(_ptr(c), _ptr(k), _ptr(out))
+    return out

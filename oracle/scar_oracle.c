@@ -339,3 +339,62 @@ int oracle_mask_to_indices(const uint8_t *mask, uint32_t n_blocks, uint32_t *out
   *out_count = m;
   return ORACLE_OK;
 }
+
+/* ---- the comparison strategies of Section 5.4: which blocks a checkpoint saves -------- */
+
+/* "round": blocks are saved in a round-robin manner.  A checkpoint that starts at
+ * `cursor` saves the k blocks cursor, cursor+1, ... (mod n_blocks); the caller advances
+ * the cursor by k per checkpoint.  out_idx ascending. */
+int oracle_select_round(uint32_t n_blocks, uint32_t k, uint64_t cursor, uint32_t *out_idx) {
+  if (k > n_blocks) return ORACLE_ERR_ARG;
+  if (k == 0) return ORACLE_OK;
+  if (!out_idx) return ORACLE_ERR_ARG;
+  for (uint32_t i = 0; i < k; ++i) out_idx[i] = (uint32_t)((cursor + i) % n_blocks);
+  qsort(out_idx, k, sizeof(uint32_t), cmp_u32_asc);
+  return ORACLE_OK;
+}
+
+/* Philox4x32-10, the counter-based generator of Salmon, Moraes, Dror and Shaw
+ * ("Parallel random numbers: as easy as 1, 2, 3", SC'11): ten rounds of
+ *   (c0,c1,c2,c3) <- (hi(M1*c2)^c1^k0, lo(M1*c2), hi(M0*c0)^c3^k1, lo(M0*c0))
+ * with the key advanced by the Weyl constants (W0, W1) before every round but the first. */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+  const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    if (round > 0) {
+      k0 += W0;
+      k1 += W1;
+    }
+    uint64_t p0 = M0 * c0, p1 = M1 * c2;
+    uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n1 = (uint32_t)p1;
+    uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1, n3 = (uint32_t)p0;
+    c0 = n0, c1 = n1, c2 = n2, c3 = n3;
+  }
+  out[0] = c0, out[1] = c1, out[2] = c2, out[3] = c3;
+}
+
+/* "random": blocks are saved uniformly at random.  Block b draws the 32-bit number
+ * Philox4x32-10(counter = (b, 0, draw_lo, draw_hi), key = (seed_lo, seed_hi))[0]; the k
+ * blocks with the largest numbers are saved (equal numbers: lower index first), which is
+ * a uniformly random k-subset up to ties between 32-bit draws.  `draw` numbers the
+ * checkpoint so that every checkpoint gets fresh numbers. */
+int oracle_select_random(uint32_t n_blocks, uint32_t k, uint64_t seed, uint64_t draw,
+                         uint32_t *out_idx) {
+  if (k > n_blocks) return ORACLE_ERR_ARG;
+  if (k == 0) return ORACLE_OK;
+  if (!out_idx) return ORACLE_ERR_ARG;
+  int64_t *num = (int64_t *)malloc((size_t)n_blocks * sizeof(int64_t));
+  if (!num) return ORACLE_ERR_NOMEM;
+  const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  for (uint32_t b = 0; b < n_blocks; ++b) {
+    const uint32_t ctr[4] = {b, 0u, (uint32_t)draw, (uint32_t)(draw >> 32)};
+    uint32_t r[4];
+    oracle_philox4x32_10(ctr, key, r);
+    num[b] = (int64_t)r[0];
+  }
+  int rc = oracle_select_topk(1, num, n_blocks, k, out_idx);
+  free(num);
+  return rc;
+}

@@ -446,3 +446,52 @@ def test_three_cycles_keep_the_running_checkpoint_consistent():
         assert np.all(s_after[K] == 0.0)
         others = np.setdiff1d(np.arange(nb), K)
         assert s_after[others].max() <= s[K].min()
+
+
+# --------------------------------------------------------------------------- comparison strategies
+
+def test_philox_known_answers():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        w = [int(v, 16) for v in r]
+        np.testing.assert_array_equal(oracle.philox4x32_10(w[0:4], w[4:6]), w[6:10])
+
+
+def test_round_robin_covers_every_block_once_per_sweep():
+    n, k = 40, 8
+    seen = []
+    for t in range(5):
+        idx = oracle.select_round(n, k, t * k)
+        np.testing.assert_array_equal(idx, np.arange(t * k, (t + 1) * k))
+        seen.extend(idx.tolist())
+    assert sorted(seen) == list(range(n))
+    # wrap-around stays ascending and the cursor is taken modulo n
+    np.testing.assert_array_equal(oracle.select_round(10, 4, 8), [0, 1, 8, 9])
+    np.testing.assert_array_equal(oracle.select_round(10, 4, 28), [0, 1, 8, 9])
+    np.testing.assert_array_equal(oracle.select_round(10, 10, 3), np.arange(10))
+    assert oracle.select_round(10, 0, 3).size == 0
+
+
+def test_random_strategy_is_a_seeded_uniform_subset():
+    n, k = 200, 50
+    a = oracle.select_random(n, k, seed=7, draw=0)
+    assert a.size == k and len(set(a.tolist())) == k and a.max() < n
+    assert np.all(np.diff(a.astype(np.int64)) > 0)
+    np.testing.assert_array_equal(a, oracle.select_random(n, k, seed=7, draw=0))
+    assert not np.array_equal(a, oracle.select_random(n, k, seed=7, draw=1))
+    assert not np.array_equal(a, oracle.select_random(n, k, seed=8, draw=0))
+    # the choice is the top-k of the blocks' Philox numbers
+    num = np.array([oracle.philox4x32_10([b, 0, 3, 0], [7, 0])[0] for b in range(n)], dtype=np.int64)
+    np.testing.assert_array_equal(oracle.select_random(n, k, seed=7, draw=3), oracle.select_topk(num, k))
+    # every block is chosen with probability k/n
+    hits = np.zeros(n)
+    draws = 2000
+    for d in range(draws):
+        hits[oracle.select_random(n, k, seed=1, draw=d)] += 1
+    p = k / n
+    z = (hits - draws * p) / np.sqrt(draws * p * (1 - p))
+    assert np.abs(z).max() < 4.5 and abs(z.mean()) < 0.3
+    np.testing.assert_array_equal(oracle.select_random(9, 9, 1, 1), np.arange(9))
