@@ -152,6 +152,24 @@ int scar_mask_to_indices(const uint8_t* mask, uint32_t n_blocks, uint32_t* out_i
                          uint32_t* out_count, void* workspace, size_t workspace_bytes,
                          void* stream);
 
+/* The comparison strategies of Section 5.4 for choosing K; their output feeds
+ * scar_checkpoint_commit exactly like scar_select_topk's.
+ *
+ * "round": blocks are saved in a round-robin manner.  out_idx receives the k blocks
+ * cursor, cursor+1, ... (taken modulo n_blocks) in ascending order; the caller advances
+ * cursor by k per checkpoint. */
+int scar_select_round(uint32_t n_blocks, uint32_t k, uint64_t cursor, uint32_t* out_idx,
+                      void* stream);
+
+/* "random": blocks are saved uniformly at random.  Block b draws the 32-bit number
+ * Philox4x32-10(counter = (b, 0, draw_lo, draw_hi), key = (seed_lo, seed_hi))[0]
+ * (Salmon et al., SC'11); the k blocks with the largest numbers are chosen, equal numbers
+ * to the lower index - a uniformly random k-subset up to ties between 32-bit draws.
+ * `draw` numbers the checkpoint, so each checkpoint of a run uses fresh numbers.
+ * out_idx ascending.  Same (seed, draw, n_blocks, k) => same result on every run. */
+int scar_select_random(uint32_t n_blocks, uint32_t k, uint64_t seed, uint64_t draw,
+                       uint32_t* out_idx, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Static, never NULL. */
 const char* scar_strerror(int status);
 

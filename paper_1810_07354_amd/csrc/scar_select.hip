@@ -25,7 +25,36 @@ constexpr uint32_t kHistGridCap = 1u << 14;
 constexpr uint32_t kTileGridCap = 1u << 14;
 constexpr int kKeysPerThread = kTileKeys / kWG;  // 8 consecutive keys per thread
 
-enum : int { SRC_F32 = 0, SRC_I64 = 1, SRC_MASK = 2 };
+enum : int { SRC_F32 = 0, SRC_I64 = 1, SRC_MASK = 2, SRC_RANDOM = 3 };
+
+// Where the keys come from: an array in device memory, or (SRC_RANDOM) the counter-based
+// generator, which needs no memory at all.
+struct KeyArgs {
+  const void* ptr;
+  uint64_t seed;
+  uint64_t draw;
+};
+
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy as 1, 2,
+// 3", SC'11), first output word: ten rounds of
+//   (c0,c1,c2,c3) <- (hi(M1*c2)^c1^k0, lo(M1*c2), hi(M0*c0)^c3^k1, lo(M0*c0)),
+// the key stepping by (W0, W1) between rounds.
+__device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2,
+                                                        uint32_t c3, uint32_t k0, uint32_t k1) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t h0 = __umulhi(M0, c0), l0 = M0 * c0;
+    const uint32_t h1 = __umulhi(M1, c2), l1 = M1 * c2;
+    c0 = h1 ^ c1 ^ k0;
+    c1 = l1;
+    c2 = h0 ^ c3 ^ k1;
+    c3 = l0;
+    k0 += W0;
+    k1 += W1;
+  }
+  return c0;
+}
 
 struct SelectState {
   unsigned long long prefix;  // digits fixed so far, right-aligned
@@ -49,8 +78,8 @@ struct Key<SRC_F32> {
   static constexpr int passes = 3;
   __device__ static int shift(int p) { return p == 0 ? 21 : (p == 1 ? 10 : 0); }
   __device__ static int bits(int p) { return p == 2 ? 10 : 11; }
-  __device__ static type load(const void* s, uint64_t i) {
-    uint32_t u = __float_as_uint(((const float*)s)[i]);
+  __device__ static type load(const KeyArgs& a, uint64_t i) {
+    uint32_t u = __float_as_uint(((const float*)a.ptr)[i]);
     if ((u & 0x7fffffffu) > 0x7f800000u) return 0xffffffffu;  // NaN: above everything
     if (u == 0x80000000u) u = 0;                              // -0 == +0
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
@@ -63,15 +92,29 @@ struct Key<SRC_I64> {
   static constexpr int passes = 6;
   __device__ static int shift(int p) { return p == 5 ? 0 : 53 - 11 * p; }
   __device__ static int bits(int p) { return p == 5 ? 9 : 11; }
-  __device__ static type load(const void* s, uint64_t i) {
-    return (unsigned long long)((const long long*)s)[i] ^ 0x8000000000000000ull;
+  __device__ static type load(const KeyArgs& a, uint64_t i) {
+    return (unsigned long long)((const long long*)a.ptr)[i] ^ 0x8000000000000000ull;
+  }
+};
+
+// The "random" strategy of Section 5.4: block i draws the 32-bit number
+// Philox4x32-10(counter = (i, 0, draw), key = seed)[0]; the k largest numbers win.
+template <>
+struct Key<SRC_RANDOM> {
+  using type = uint32_t;
+  static constexpr int passes = 3;
+  __device__ static int shift(int p) { return p == 0 ? 21 : (p == 1 ? 10 : 0); }
+  __device__ static int bits(int p) { return p == 2 ? 10 : 11; }
+  __device__ static type load(const KeyArgs& a, uint64_t i) {
+    return philox4x32_10_word0((uint32_t)i, 0u, (uint32_t)a.draw, (uint32_t)(a.draw >> 32),
+                               (uint32_t)a.seed, (uint32_t)(a.seed >> 32));
   }
 };
 
 template <>
 struct Key<SRC_MASK> {  // only classified, never histogrammed
   using type = uint32_t;
-  __device__ static type load(const void* s, uint64_t i) { return ((const uint8_t*)s)[i] ? 1u : 0u; }
+  __device__ static type load(const KeyArgs& a, uint64_t i) { return ((const uint8_t*)a.ptr)[i] ? 1u : 0u; }
 };
 
 // Exclusive prefix sum of v over the workgroup in thread order; *total gets the sum.
@@ -147,7 +190,7 @@ __device__ __forceinline__ SelectState next_state(const uint32_t* __restrict__ g
 // the same values; workgroup 0 also stores them for later kernels), then adds the digit
 // histogram of the keys that match the prefix.
 template <int SRC>
-__global__ __launch_bounds__(kWG) void k_select_hist(const void* __restrict__ scores, uint32_t n,
+__global__ __launch_bounds__(kWG) void k_select_hist(const KeyArgs scores, uint32_t n,
                                                      uint32_t n_tiles, int pass,
                                                      SelectWs* __restrict__ ws) {
   using K = Key<SRC>;
@@ -187,7 +230,7 @@ __global__ __launch_bounds__(kWG) void k_select_hist(const void* __restrict__ sc
 
 // 0 = not selected on its own, 1 = above the threshold, 2 = equal to the threshold.
 template <int SRC>
-__device__ __forceinline__ int classify(const void* src, uint64_t i, typename Key<SRC>::type T) {
+__device__ __forceinline__ int classify(const KeyArgs& src, uint64_t i, typename Key<SRC>::type T) {
   const typename Key<SRC>::type key = Key<SRC>::load(src, i);
   if constexpr (SRC == SRC_MASK) return key ? 1 : 0;
   return key > T ? 1 : (key == T ? 2 : 0);
@@ -196,7 +239,7 @@ __device__ __forceinline__ int classify(const void* src, uint64_t i, typename Ke
 // Per-tile counts of (above, equal), packed as low / high 32 bits.  For a selection the
 // threshold is first derived from the last pass's histogram, as in k_select_hist.
 template <int SRC>
-__global__ __launch_bounds__(kWG) void k_compact_count(const void* __restrict__ src, uint32_t n,
+__global__ __launch_bounds__(kWG) void k_compact_count(const KeyArgs src, uint32_t n,
                                                        uint32_t n_tiles, int passes,
                                                        SelectWs* __restrict__ ws,
                                                        unsigned long long* __restrict__ tile_cnt) {
@@ -247,7 +290,7 @@ __global__ __launch_bounds__(kWG) void k_compact_scan(unsigned long long* __rest
 //   SCANNED: tile_cnt already holds exclusive prefix sums (k_compact_scan ran); otherwise
 //   it holds raw counts and each workgroup adds up the tiles before its own (few tiles).
 template <int SRC, bool SCANNED>
-__global__ __launch_bounds__(kWG) void k_compact_write(const void* __restrict__ src, uint32_t n,
+__global__ __launch_bounds__(kWG) void k_compact_write(const KeyArgs src, uint32_t n,
                                                        uint32_t n_tiles, int passes,
                                                        const SelectWs* __restrict__ ws,
                                                        const unsigned long long* __restrict__ tile_cnt,
@@ -309,7 +352,7 @@ __global__ __launch_bounds__(kWG) void k_compact_write(const void* __restrict__ 
 // instead of six or nine.
 constexpr uint32_t kSmallSelect = 8192;
 template <int SRC>
-__global__ __launch_bounds__(kWG) void k_select_small(const void* __restrict__ scores, uint32_t n,
+__global__ __launch_bounds__(kWG) void k_select_small(const KeyArgs scores, uint32_t n,
                                                       uint32_t k, uint32_t* __restrict__ out_idx) {
   using K = Key<SRC>;
   using key_t = typename K::type;
@@ -368,7 +411,7 @@ constexpr uint32_t kSelfScanTiles = 2048;  // up to here writers add up their pr
 
 // count -> (scan) -> write, shared by selection and mask compaction.
 template <int SRC>
-static void run_compaction(const void* src, uint32_t n, int passes, SelectWs* ws,
+static void run_compaction(const KeyArgs src, uint32_t n, int passes, SelectWs* ws,
                            unsigned long long* tiles, uint32_t* out_idx, uint32_t out_cap,
                            uint32_t* out_count, hipStream_t st) {
   const uint32_t n_tiles = (uint32_t)n_tiles_of(n);
@@ -388,7 +431,7 @@ static void run_compaction(const void* src, uint32_t n, int passes, SelectWs* ws
 }
 
 template <int SRC>
-static void run_select(const void* scores, uint32_t n, uint32_t k, uint32_t* out_idx, void* workspace,
+static void run_select(const KeyArgs scores, uint32_t n, uint32_t k, uint32_t* out_idx, void* workspace,
                        hipStream_t st) {
   if (n <= kSmallSelect) {
     hipLaunchKernelGGL((k_select_small<SRC>), dim3(1), dim3(kWG), 0, st, scores, n, k, out_idx);
@@ -402,6 +445,15 @@ static void run_select(const void* scores, uint32_t n, uint32_t k, uint32_t* out
   for (int p = 0; p < Key<SRC>::passes; ++p)
     hipLaunchKernelGGL((k_select_hist<SRC>), dim3(hgrid), dim3(kWG), 0, st, scores, n, n_tiles, p, ws);
   run_compaction<SRC>(scores, n, Key<SRC>::passes, ws, tiles, out_idx, k, nullptr, st);
+}
+
+// Round-robin strategy: the k blocks start, start+1, ... (mod n), written ascending.  When
+// the run wraps, its wrapped head (blocks 0 .. wrap-1) comes first.
+__global__ __launch_bounds__(kWG) void k_select_round(uint32_t n, uint32_t k, uint32_t start,
+                                                      uint32_t* __restrict__ out_idx) {
+  const uint32_t wrap = (uint64_t)start + k > n ? (uint32_t)((uint64_t)start + k - n) : 0;
+  for (uint32_t i = blockIdx.x * kWG + threadIdx.x; i < k; i += gridDim.x * kWG)
+    out_idx[i] = i < wrap ? i : start + (i - wrap);
 }
 
 }  // namespace scar
@@ -420,9 +472,9 @@ extern "C" int scar_select_topk(int32_t score_type, const void* scores, uint32_t
   const int rc = check_workspace(workspace, workspace_bytes, n_blocks);
   if (rc) return rc;
   if (score_type == SCAR_SCORE_F32)
-    run_select<SRC_F32>(scores, n_blocks, k, out_idx, workspace, (hipStream_t)stream);
+    run_select<SRC_F32>(KeyArgs{scores, 0, 0}, n_blocks, k, out_idx, workspace, (hipStream_t)stream);
   else
-    run_select<SRC_I64>(scores, n_blocks, k, out_idx, workspace, (hipStream_t)stream);
+    run_select<SRC_I64>(KeyArgs{scores, 0, 0}, n_blocks, k, out_idx, workspace, (hipStream_t)stream);
   return launch_status();
 }
 
@@ -438,7 +490,31 @@ extern "C" int scar_mask_to_indices(const uint8_t* mask, uint32_t n_blocks, uint
   if (n_blocks == 0)  // nothing to scan: the one-workgroup scan of zero tiles writes *out_count = 0
     hipLaunchKernelGGL(k_compact_scan, dim3(1), dim3(kWG), 0, st, tiles, 0u, out_count);
   else
-    run_compaction<SRC_MASK>(mask, n_blocks, 0, (SelectWs*)workspace, tiles, out_idx, n_blocks,
+    run_compaction<SRC_MASK>(KeyArgs{mask, 0, 0}, n_blocks, 0, (SelectWs*)workspace, tiles, out_idx, n_blocks,
                              out_count, st);
+  return launch_status();
+}
+
+extern "C" int scar_select_round(uint32_t n_blocks, uint32_t k, uint64_t cursor, uint32_t* out_idx,
+                                 void* stream) {
+  if (n_blocks > SCAR_MAX_BLOCKS || k > n_blocks) return SCAR_ERR_INVALID_ARG;
+  if (k == 0) return SCAR_OK;
+  if (!out_idx || !aligned(out_idx, 4)) return SCAR_ERR_INVALID_ARG;
+  const uint32_t grid = (k + kWG - 1) / kWG < 4096 ? (k + kWG - 1) / kWG : 4096;
+  hipLaunchKernelGGL(k_select_round, dim3(grid), dim3(kWG), 0, (hipStream_t)stream, n_blocks, k,
+                     (uint32_t)(cursor % n_blocks), out_idx);
+  return launch_status();
+}
+
+extern "C" int scar_select_random(uint32_t n_blocks, uint32_t k, uint64_t seed, uint64_t draw,
+                                  uint32_t* out_idx, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+  if (n_blocks > SCAR_MAX_BLOCKS || k > n_blocks) return SCAR_ERR_INVALID_ARG;
+  if (k == 0) return SCAR_OK;
+  if (!out_idx || !aligned(out_idx, 4)) return SCAR_ERR_INVALID_ARG;
+  const int rc = check_workspace(workspace, workspace_bytes, n_blocks);
+  if (rc) return rc;
+  run_select<SRC_RANDOM>(KeyArgs{nullptr, seed, draw}, n_blocks, k, out_idx, workspace,
+                         (hipStream_t)stream);
   return launch_status();
 }

@@ -63,8 +63,11 @@ def lib():
         L.scar_partial_recover.argtypes = [lp, vp, vp, vp, u32, vp, vp, sz, vp]
         L.scar_perturbation_norm.argtypes = [lp, vp, vp, vp, u32, vp, vp, sz, vp]
         L.scar_mask_to_indices.argtypes = [vp, u32, vp, vp, vp, sz, vp]
+        L.scar_select_round.argtypes = [u32, u32, u64, vp, vp]
+        L.scar_select_random.argtypes = [u32, u32, u64, u64, vp, vp, sz, vp]
         for name in ("scar_block_scores", "scar_select_topk", "scar_checkpoint_commit",
-                     "scar_partial_recover", "scar_perturbation_norm", "scar_mask_to_indices"):
+                     "scar_partial_recover", "scar_perturbation_norm", "scar_mask_to_indices",
+                     "scar_select_round", "scar_select_random"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -221,3 +224,22 @@ def mask_to_indices(mask, workspace):
     _check(lib().scar_mask_to_indices(_p(mask), mask.numel(), _p(out), _p(cnt), _p(workspace),
                                       workspace.numel(), _stream()), "scar_mask_to_indices")
     return out, cnt
+
+
+def select_round(n_blocks_, k, cursor, device, out=None):
+    """scar_select_round: the round-robin strategy's k blocks from `cursor` on, ascending."""
+    if out is None:
+        out = torch.empty(int(k), dtype=torch.int32, device=device)
+    _check(lib().scar_select_round(int(n_blocks_), int(k), int(cursor), _p(out), _stream()),
+           "scar_select_round")
+    return out
+
+
+def select_random(n_blocks_, k, seed, draw, workspace, out=None):
+    """scar_select_random: a seeded uniformly random k-subset of the blocks, ascending."""
+    _dev(workspace, "workspace")
+    if out is None:
+        out = torch.empty(int(k), dtype=torch.int32, device=workspace.device)
+    _check(lib().scar_select_random(int(n_blocks_), int(k), int(seed), int(draw), _p(out),
+                                    _p(workspace), workspace.numel(), _stream()), "scar_select_random")
+    return out

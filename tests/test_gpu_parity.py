@@ -235,3 +235,18 @@ def test_argument_errors_are_reported_not_launched():
     with pytest.raises(scar.ScarError):
         scar.select_topk(s, 2, ws[1:])
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("n,k", [(1, 1), (10, 4), (8192, 1000), (8193, 8193), (100_000, 12_500),
+                                 (1 << 20, 104_858)])
+def test_comparison_strategies(n, k):
+    # Section 5.4's round-robin and random choices of K, index for index against the oracle
+    ws = scar.new_workspace(n, DEV)
+    for cursor in (0, n - 1, 3 * n + k // 2, n - k):
+        print("round n=%d k=%d cursor=%d" % (n, k, cursor), flush=True)
+        got = idx_host(scar.select_round(n, k, cursor, DEV))
+        np.testing.assert_array_equal(got, oracle.select_round(n, k, cursor))
+    for seed, draw in ((0, 0), (7, 3), (2 ** 40 + 5, 2 ** 33 + 1)):
+        print("random n=%d k=%d seed=%d draw=%d" % (n, k, seed, draw), flush=True)
+        got = idx_host(scar.select_random(n, k, seed, draw, ws))
+        np.testing.assert_array_equal(got, oracle.select_random(n, k, seed, draw))

@@ -81,3 +81,17 @@ def test_priority_beats_round_robin_and_random_on_the_norm():
         scar.checkpoint_commit(x, c, L, d_idx)
         res[name] = scar.read_norm(scar.perturbation_norm(x, c, L, None, ws))[1]
     assert res["priority"] < res["round"] and res["priority"] < res["random"]
+
+
+def test_strategy_study_orders_the_strategies_as_the_paper_does():
+    # Section 5.4 / Fig. 8: at the same write volume, prioritized partial checkpoints leave a
+    # smaller perturbation than round-robin or random ones, and partial recovery a smaller one
+    # than full recovery (Theorem 4.1; about sqrt(1/2) of it for half the blocks, Theorem 4.2).
+    from paper_1810_07354_amd import strategy_study
+    r = strategy_study.run(n_blocks=4096, block_len=256, iters=24, period=8, lost_fraction=0.5)
+    m = r["mean_perturbation_norm"]
+    print(r, flush=True)
+    assert m["priority"] < m["round"] and m["priority"] < m["random"]
+    assert m["partial"] < m["traditional"]
+    assert 0.6 < m["partial"] / m["traditional"] < 0.8
+    assert m["priority"] < m["partial"]
