@@ -23,15 +23,18 @@ inline uint64_t layout_blocks(const scar_layout* l) {
   return nb > SCAR_MAX_BLOCKS ? UINT64_MAX : nb;
 }
 
-// Group size for blocks of `block_len` elements: the power of two in {1..64, 256} that
-// gives each lane about four loads per stream (16-byte loads on the vector path,
-// element loads otherwise).
-inline int pick_group(uint32_t block_len, int ebytes, bool vec) {
+// Group size for blocks of `block_len` elements: the power of two that gives each lane
+// about `per_lane` loads per stream (16-byte loads on the vector path, element loads
+// otherwise).  The score kernel reduces inside a group, so it offers {1..64, 256} and
+// wants four loads per lane; the row kernels only move data and do best with one
+// (measured on 4 KiB rows: 5.66 TB/s with a whole workgroup per row against 5.33 TB/s with
+// one wavefront per row), and offer every power of two up to 256.
+inline int pick_group(uint32_t block_len, int ebytes, bool vec, int per_lane, bool allow_128) {
   const uint64_t units = vec ? ((uint64_t)block_len * ebytes + 15) / 16 : block_len;
-  const uint64_t want = (units + 3) / 4;
+  const uint64_t want = (units + per_lane - 1) / per_lane;
   int g = 1;
   while (g < 256 && (uint64_t)g < want) g <<= 1;
-  return g == 128 ? 256 : g;
+  return (g == 128 && !allow_128) ? 256 : g;
 }
 
 // ---- workspace layout ---------------------------------------------------------------

@@ -144,6 +144,7 @@ static void dispatch_commit(int g, const scar_layout* l, const void* x, void* c,
     case 16: launch_commit<16, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
     case 32: launch_commit<32, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
     case 64: launch_commit<64, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
+    case 128: launch_commit<128, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
     default: launch_commit<256, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
   }
 }
@@ -174,6 +175,7 @@ static uint32_t dispatch_recover_g(int g, const scar_layout* l, void* x, const v
     case 16: return launch_recover<DT, 16, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
     case 32: return launch_recover<DT, 32, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
     case 64: return launch_recover<DT, 64, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
+    case 128: return launch_recover<DT, 128, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
     default: return launch_recover<DT, 256, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
   }
 }
@@ -224,7 +226,7 @@ static int recover_or_norm(bool store, const scar_layout* layout, void* x, const
   if (!x || !c || (!all_blocks && !idx) || !aligned(x, eb) || !aligned(c, eb) || !aligned(idx, 4))
     return SCAR_ERR_INVALID_ARG;
   const bool vec = aligned(x, 16) && aligned(c, 16) && ((uint64_t)layout->block_len * eb) % 16 == 0;
-  const int g = pick_group(layout->block_len, eb, vec);
+  const int g = pick_group(layout->block_len, eb, vec, 1, true);
   const uint32_t n_blocks = (uint32_t)nb;
   uint32_t n_partial = 0;
   if (store && norm_out)
@@ -254,7 +256,7 @@ extern "C" int scar_checkpoint_commit(const scar_layout* layout, const void* x, 
   const bool row16 = ((uint64_t)layout->block_len * eb) % 16 == 0;
   const bool vec = aligned(x, 16) && aligned(c, 16) && row16;
   const bool vec_st = vec && staging && aligned(staging, 16);
-  const int g = pick_group(layout->block_len, eb, vec);
+  const int g = pick_group(layout->block_len, eb, vec, 1, true);
   hipStream_t st = (hipStream_t)stream;
   if (eb == 4)
     dispatch_commit<uint32_t>(g, layout, x, c, idx, n_idx, staging, (uint32_t)nb, vec, vec_st, st);
