@@ -44,6 +44,10 @@ def lib():
         L.oracle_perturbation_norm.argtypes = [i32, vp, vp, u64, u32, vp, u32, ctypes.POINTER(Norm)]
         L.oracle_partial_recover.argtypes = [i32, vp, vp, u64, u32, vp, u32, ctypes.POINTER(Norm)]
         L.oracle_mask_to_indices.argtypes = [vp, u32, vp, ctypes.POINTER(u32)]
+        L.oracle_var_block_scores.argtypes = [i32, vp, vp, vp, u32, vp]
+        L.oracle_var_checkpoint_commit.argtypes = [i32, vp, vp, vp, u32, vp, u32]
+        L.oracle_var_perturbation_norm.argtypes = [i32, vp, vp, vp, u32, vp, u32, ctypes.POINTER(Norm)]
+        L.oracle_var_partial_recover.argtypes = [i32, vp, vp, vp, u32, vp, u32, ctypes.POINTER(Norm)]
         L.oracle_select_round.argtypes = [u32, u32, u64, vp]
         L.oracle_select_random.argtypes = [u32, u32, u64, u64, vp]
         L.oracle_philox4x32_10.argtypes = [vp, vp, vp]
@@ -199,3 +203,47 @@ def philox4x32_10(counter, key):
     out = np.zeros(4, dtype=np.uint32)
     lib().oracle_philox4x32_10(_ptr(c), _ptr(k), _ptr(out))
     return out
+
+
+# ---- blocks of unequal length: offsets is a uint64 array of n_blocks + 1 element offsets
+
+def _offsets(offsets):
+    return np.ascontiguousarray(offsets, dtype=np.uint64)
+
+
+def var_block_scores(dtype, x, c, offsets):
+    x, c, off = _flat(x, dtype), _flat(c, dtype), _offsets(offsets)
+    nb = off.size - 1
+    out = np.zeros(nb, dtype=np.int64 if dtype == I32 else np.float64)
+    _check(lib().oracle_var_block_scores(dtype, _ptr(x), _ptr(c), _ptr(off), nb, _ptr(out)),
+           "oracle_var_block_scores")
+    return out
+
+
+def var_checkpoint_commit(dtype, x, c, offsets, idx):
+    x, c, off, idx = _flat(x, dtype), _flat(c, dtype), _offsets(offsets), _idx(idx)
+    _check(lib().oracle_var_checkpoint_commit(dtype, _ptr(x), _ptr(c), _ptr(off), off.size - 1,
+                                              _ptr(idx), idx.size), "oracle_var_checkpoint_commit")
+
+
+def var_perturbation_norm(dtype, x, c, offsets, idx=None):
+    x, c, off = _flat(x, dtype), _flat(c, dtype), _offsets(offsets)
+    out = Norm()
+    if idx is None:
+        ptr, n = ctypes.c_void_p(0), 0
+    else:
+        idx = _idx(idx)
+        keep = idx if idx.size else np.zeros(1, dtype=np.uint32)
+        ptr, n = ctypes.c_void_p(keep.ctypes.data), idx.size
+    _check(lib().oracle_var_perturbation_norm(dtype, _ptr(x), _ptr(c), _ptr(off), off.size - 1, ptr, n,
+                                              ctypes.byref(out)), "oracle_var_perturbation_norm")
+    return out.sum, out.norm, out.isum
+
+
+def var_partial_recover(dtype, x, c, offsets, lost):
+    x, c, off, lost = _flat(x, dtype), _flat(c, dtype), _offsets(offsets), _idx(lost)
+    out = Norm()
+    _check(lib().oracle_var_partial_recover(dtype, _ptr(x), _ptr(c), _ptr(off), off.size - 1,
+                                            _ptr(lost), lost.size, ctypes.byref(out)),
+           "oracle_var_partial_recover")
+    return out.sum, out.norm, out.isum

@@ -398,3 +398,100 @@ int oracle_select_random(uint32_t n_blocks, uint32_t k, uint64_t seed, uint64_t 
   free(num);
   return rc;
 }
+
+/* ---- blocks of unequal length (Section 5.1: "by-layer" partitioning, where every weight
+ * or bias tensor of the network is one parameter) --------------------------------------
+ * offsets has n_blocks + 1 non-decreasing entries, offsets[0] = 0; block b is the element
+ * range [offsets[b], offsets[b+1]) and may be empty.  Everything else is as above. */
+
+static int offsets_ok(const uint64_t *offsets, uint32_t n_blocks) {
+  if (!offsets || offsets[0] != 0) return 0;
+  for (uint32_t b = 0; b < n_blocks; ++b)
+    if (offsets[b + 1] < offsets[b]) return 0;
+  return 1;
+}
+
+int oracle_var_block_scores(int dtype, const void *x, const void *c, const uint64_t *offsets,
+                            uint32_t n_blocks, void *scores) {
+  if (!dtype_ok(dtype) || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
+  if (n_blocks == 0) return ORACLE_OK;
+  if (!scores || (offsets[n_blocks] && (!x || !c))) return ORACLE_ERR_ARG;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(g_threads)
+  for (int64_t b = 0; b < (int64_t)n_blocks; ++b) {
+    if (dtype == ORACLE_I32)
+      ((int64_t *)scores)[b] =
+          block_l1((const int32_t *)x, (const int32_t *)c, offsets[b], offsets[b + 1]);
+    else
+      ((double *)scores)[b] = block_sqdist(dtype, x, c, offsets[b], offsets[b + 1]);
+  }
+  return ORACLE_OK;
+}
+
+int oracle_var_checkpoint_commit(int dtype, const void *x, void *c, const uint64_t *offsets,
+                                 uint32_t n_blocks, const uint32_t *idx, uint32_t n_idx) {
+  if (!dtype_ok(dtype) || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
+  if (n_idx == 0) return ORACLE_OK;
+  int rc = check_indices(idx, n_idx, n_blocks);
+  if (rc) return rc;
+  size_t es = elem_size(dtype);
+  for (uint32_t i = 0; i < n_idx; ++i) {
+    uint64_t lo = offsets[idx[i]], hi = offsets[idx[i] + 1];
+    if (hi > lo) memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo) * es);
+  }
+  return ORACLE_OK;
+}
+
+/* idx == NULL: every block. */
+int oracle_var_perturbation_norm(int dtype, const void *x, const void *c, const uint64_t *offsets,
+                                 uint32_t n_blocks, const uint32_t *idx, uint32_t n_idx,
+                                 oracle_norm *out) {
+  if (!dtype_ok(dtype) || !offsets_ok(offsets, n_blocks) || !out) return ORACLE_ERR_ARG;
+  out->sum = out->norm = 0.0;
+  out->isum = 0;
+  uint32_t m = idx ? n_idx : n_blocks;
+  if (idx) {
+    int rc = check_indices(idx, n_idx, n_blocks);
+    if (rc) return rc;
+  }
+  double fs = 0.0;
+  int64_t is = 0;
+  for (uint32_t i = 0; i < m; ++i) {
+    uint32_t b = idx ? idx[i] : i;
+    if (dtype == ORACLE_I32)
+      is += block_l1((const int32_t *)c, (const int32_t *)x, offsets[b], offsets[b + 1]);
+    else
+      fs += block_sqdist(dtype, c, x, offsets[b], offsets[b + 1]);
+  }
+  if (dtype == ORACLE_I32) {
+    out->isum = is;
+    out->sum = out->norm = (double)is;
+  } else {
+    out->sum = fs;
+    out->norm = sqrt(fs);
+  }
+  return ORACLE_OK;
+}
+
+int oracle_var_partial_recover(int dtype, void *x, const void *c, const uint64_t *offsets,
+                               uint32_t n_blocks, const uint32_t *lost, uint32_t n_lost,
+                               oracle_norm *norm_out) {
+  if (!dtype_ok(dtype) || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
+  oracle_norm zero = {0.0, 0.0, 0};
+  if (n_lost == 0) {
+    if (norm_out) *norm_out = zero;
+    return ORACLE_OK;
+  }
+  if (norm_out) {
+    int rc = oracle_var_perturbation_norm(dtype, x, c, offsets, n_blocks, lost, n_lost, norm_out);
+    if (rc) return rc;
+  } else {
+    int rc = check_indices(lost, n_lost, n_blocks);
+    if (rc) return rc;
+  }
+  size_t es = elem_size(dtype);
+  for (uint32_t i = 0; i < n_lost; ++i) {
+    uint64_t lo = offsets[lost[i]], hi = offsets[lost[i] + 1];
+    if (hi > lo) memcpy((char *)x + lo * es, (const char *)c + lo * es, (hi - lo) * es);
+  }
+  return ORACLE_OK;
+}

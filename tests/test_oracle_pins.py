@@ -495,3 +495,75 @@ def test_random_strategy_is_a_seeded_uniform_subset():
     z = (hits - draws * p) / np.sqrt(draws * p * (1 - p))
     assert np.abs(z).max() < 4.5 and abs(z.mean()) < 0.3
     np.testing.assert_array_equal(oracle.select_random(9, 9, 1, 1), np.arange(9))
+
+
+# --------------------------------------------------------------------------- unequal blocks
+
+def ragged_offsets(seed, n_blocks, max_len, empties=True):
+    r = rng_of(seed)
+    lens = r.integers(1, max_len + 1, size=n_blocks)
+    if empties:
+        lens[r.choice(n_blocks, size=max(1, n_blocks // 10), replace=False)] = 0
+    return np.concatenate([[0], np.cumsum(lens)]).astype(np.uint64)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16, I32])
+def test_var_layout_with_equal_blocks_is_the_fixed_layout(dtype):
+    x, c = small_store(51, n_elems=230, dtype=dtype)
+    L = 10
+    off = np.arange(0, 231, L, dtype=np.uint64)
+    np.testing.assert_array_equal(oracle.var_block_scores(dtype, x, c, off), oracle.block_scores(dtype, x, c, L))
+    idx = np.array([3, 22, 0], dtype=np.uint32)
+    assert oracle.var_perturbation_norm(dtype, x, c, off, idx) == oracle.perturbation_norm(dtype, x, c, L, idx)
+    assert oracle.var_perturbation_norm(dtype, x, c, off) == oracle.perturbation_norm(dtype, x, c, L)
+    c1, c2 = c.copy(), c.copy()
+    oracle.var_checkpoint_commit(dtype, x, c1, off, idx)
+    oracle.checkpoint_commit(dtype, x, c2, L, idx)
+    np.testing.assert_array_equal(c1, c2)
+    x1, x2 = x.copy(), x.copy()
+    assert oracle.var_partial_recover(dtype, x1, c, off, idx) == oracle.partial_recover(dtype, x2, c, L, idx)
+    np.testing.assert_array_equal(x1, x2)
+
+
+def test_var_scores_closed_form_and_empty_blocks():
+    off = np.array([0, 3, 3, 10, 11, 11, 40], dtype=np.uint64)       # lengths 3 0 7 1 0 29
+    c = rng_of(52).integers(-4, 4, size=40).astype(np.float32)
+    a = np.array([0.5, 9.0, 2.0, -4.0, 7.0, 0.25])
+    x = (c + np.repeat(a, np.diff(off.astype(np.int64)))).astype(np.float32)
+    np.testing.assert_array_equal(oracle.var_block_scores(F32, x, c, off), np.diff(off.astype(np.int64)) * a * a)
+    s, nrm, _ = oracle.var_perturbation_norm(F32, x, c, off, [2, 3, 4])
+    assert s == 7 * 4.0 + 16.0 and nrm == math.sqrt(s)
+    ci = np.zeros(40, dtype=np.int32)
+    xi = np.repeat(np.array([1, 5, -2, 3, 9, 1]), np.diff(off.astype(np.int64))).astype(np.int32)
+    np.testing.assert_array_equal(oracle.var_block_scores(I32, xi, ci, off), [3, 0, 14, 3, 0, 29])
+
+
+def test_var_commit_and_recover_touch_only_their_blocks():
+    off = ragged_offsets(53, 30, 17)
+    n = int(off[-1])
+    x, c = small_store(54, n_elems=n)
+    x0, c0 = x.copy(), c.copy()
+    K = np.array([29, 4, 11], dtype=np.uint32)
+    oracle.var_checkpoint_commit(F32, x, c, off, K)
+    np.testing.assert_array_equal(x, x0)
+    for b in range(30):
+        lo, hi = int(off[b]), int(off[b + 1])
+        np.testing.assert_array_equal(c[lo:hi], x0[lo:hi] if b in K else c0[lo:hi])
+    S = np.array([0, 4, 17, 28], dtype=np.uint32)
+    c1 = c.copy()
+    full = oracle.var_perturbation_norm(F32, x, c, off)
+    got = oracle.var_partial_recover(F32, x, c, off, S)
+    assert got[1] <= full[1]
+    np.testing.assert_array_equal(c, c1)
+    for b in range(30):
+        lo, hi = int(off[b]), int(off[b + 1])
+        np.testing.assert_array_equal(x[lo:hi], c1[lo:hi] if b in S else x0[lo:hi])
+    assert oracle.var_partial_recover(F32, x, c, off, S) == (0.0, 0.0, 0)
+    parts = np.array_split(rng_of(1).permutation(30), 4)
+    x2, _ = small_store(55, n_elems=n)
+    tot = sum(oracle.var_perturbation_norm(F32, x2, c, off, p)[0] for p in parts)
+    assert math.isclose(tot, oracle.var_perturbation_norm(F32, x2, c, off)[0], rel_tol=1e-12)
+    with pytest.raises(oracle.OracleError):
+        oracle.var_checkpoint_commit(F32, x, c, off, [30])
+    with pytest.raises(oracle.OracleError):
+        oracle.var_block_scores(F32, x, c, np.array([0, 5, 4], dtype=np.uint64))
