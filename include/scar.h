@@ -170,6 +170,43 @@ int scar_select_round(uint32_t n_blocks, uint32_t k, uint64_t cursor, uint32_t* 
 int scar_select_random(uint32_t n_blocks, uint32_t k, uint64_t seed, uint64_t draw,
                        uint32_t* out_idx, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- Blocks of unequal length ---------------------------------------------------------
+ * Section 5.1's "by-layer" partitioning makes every weight or bias tensor of a network one
+ * parameter, so blocks differ in size by orders of magnitude.  Block b is the element
+ * range [offsets[b], offsets[b+1]); empty blocks are allowed (score 0).
+ * The calls below mirror the five above (scar_select_topk, _round and _random work on
+ * any score array and serve both layouts).  There is no staging output.
+ * All of them need a workspace of scar_var_workspace_bytes(n_blocks) bytes. */
+typedef struct {
+  int32_t dtype;           /* scar_dtype */
+  uint32_t n_blocks;       /* <= SCAR_MAX_BLOCKS */
+  uint64_t n_elems;        /* total elements of x (and c); must equal offsets[n_blocks] */
+  const uint64_t* offsets; /* DEVICE memory: n_blocks + 1 non-decreasing element offsets,
+                              offsets[0] = 0.  Not checked on the host; kernels never read or
+                              write outside [0, n_elems) whatever the offsets hold. */
+} scar_var_layout;
+
+size_t scar_var_workspace_bytes(uint64_t n_blocks);
+
+/* As scar_block_scores: scores = float[n_blocks] or int64_t[n_blocks]. */
+int scar_var_block_scores(const scar_var_layout* layout, const void* x, const void* c, void* scores,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* As scar_checkpoint_commit (without staging). */
+int scar_var_checkpoint_commit(const scar_var_layout* layout, const void* x, void* c,
+                               const uint32_t* idx, uint32_t n_idx, void* workspace,
+                               size_t workspace_bytes, void* stream);
+
+/* As scar_partial_recover; the workspace is always required. */
+int scar_var_partial_recover(const scar_var_layout* layout, void* x, const void* c,
+                             const uint32_t* lost_idx, uint32_t n_lost, scar_norm* norm_out,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* As scar_perturbation_norm (idx == NULL: every block). */
+int scar_var_perturbation_norm(const scar_var_layout* layout, const void* x, const void* c,
+                               const uint32_t* idx, uint32_t n_idx, scar_norm* norm_out,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
 /* Static, never NULL. */
 const char* scar_strerror(int status);
 

@@ -70,6 +70,39 @@ inline uint32_t xcd_grid(uint64_t need, uint64_t cap) {
   return (uint32_t)((g + 7) / 8 * 8);
 }
 
+// Second stage of the norm (defined with the row kernels): adds n_partial partial sums
+// (double, or uint64 for SCAR_I32) in a fixed order and writes *out.
+void launch_finish(int32_t dtype, const void* partial, uint32_t n_partial, scar_norm* out,
+                   hipStream_t st);
+
+// ---- blocks of unequal length ----------------------------------------------------------
+// The store is cut into ranges of `range_elems` consecutive elements, one workgroup each
+// (at most kVarMaxGrid of them); a range is a whole number of 4,096-element chunks.
+constexpr uint32_t kVarChunk = 4096;
+constexpr uint32_t kVarMaxGrid = 32768;
+
+struct VarGeometry {
+  uint64_t range_elems;
+  uint32_t n_wg;
+};
+
+inline VarGeometry var_geometry(uint64_t n_elems) {
+  const uint64_t n_chunks = (n_elems + kVarChunk - 1) / kVarChunk;
+  uint64_t per = (n_chunks + kVarMaxGrid - 1) / kVarMaxGrid;
+  if (per == 0) per = 1;
+  const uint64_t range = per * kVarChunk;
+  return {range, (uint32_t)((n_elems + range - 1) / range)};
+}
+
+// Workspace of the variable-length calls: [0, 8 * (kVarMaxGrid + n_blocks)) partial sums,
+// then one selection byte per block.
+inline size_t var_mask_offset(uint64_t n_blocks) {
+  return ((8 * ((size_t)kVarMaxGrid + n_blocks) + 255) / 256) * 256;
+}
+inline size_t var_workspace_bytes_for(uint64_t n_blocks) {
+  return var_mask_offset(n_blocks) + ((n_blocks + 255) / 256) * 256 + 256;
+}
+
 inline int launch_status() { return hipGetLastError() == hipSuccess ? SCAR_OK : SCAR_ERR_DEVICE; }
 
 }  // namespace scar

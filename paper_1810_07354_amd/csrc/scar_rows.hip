@@ -191,7 +191,7 @@ static uint32_t dispatch_recover(int g, const scar_layout* l, void* x, const voi
   }
 }
 
-static void launch_finish(int32_t dtype, const void* partial, uint32_t n_partial, scar_norm* out,
+void launch_finish(int32_t dtype, const void* partial, uint32_t n_partial, scar_norm* out,
                           hipStream_t st) {
   if (dtype == SCAR_I32)
     hipLaunchKernelGGL((k_norm_finish<DT_I32>), dim3(1), dim3(kFinishThreads), 0, st,

@@ -1,0 +1,339 @@
+// Blocks of unequal length (Section 5.1: "by-layer" partitioning, every weight or bias
+// tensor one parameter): scar_var_block_scores, scar_var_checkpoint_commit,
+// scar_var_partial_recover, scar_var_perturbation_norm.
+//
+// Block b is the element range [offsets[b], offsets[b+1]).  Sizes can differ by orders of
+// magnitude (a 3-million-element matrix next to a 10-element bias), so work is not dealt
+// out by block but by position: the store is cut into equal ranges of consecutive
+// elements, one workgroup per range.  A workgroup finds the block that holds its first
+// element (a 256-way search over the offsets), then walks forward through its range,
+// segment by segment, where a segment is the part of one block that lies inside the range.
+//
+//   scores:  the workgroup's sum for block b goes to partial[w + b] (w = range number).
+//            Along the store either w or b grows from one (range, block) pair to the next,
+//            so the slots are distinct and those of one block are consecutive; a second
+//            kernel adds each block's slots in a fixed order.  A giant block is thus summed
+//            by as many workgroups as it spans, a run of tiny blocks by one.
+//   commit / recover / norm:  a byte per block marks the chosen ones; every workgroup
+//            handles the chosen segments of its range and skips the rest.
+//
+// Segments start wherever a block starts, so each is split into a few leading elements up
+// to the next 16-byte boundary, a body of non-temporal 16-byte accesses, and a tail.
+#include "scar_device.hpp"
+#include "scar_host.hpp"
+
+namespace scar {
+
+// Sum of a 0/1 flag over the workgroup, in every thread.
+__device__ __forceinline__ uint32_t workgroup_count(bool flag, uint32_t* slots) {
+  return workgroup_sum<uint32_t>(flag ? 1u : 0u, slots);
+}
+
+// The block that holds element e: offsets[b] <= e < offsets[b+1].  All threads of the
+// workgroup take part and get the same answer.  Needs offsets[0] <= e < offsets[n_blocks];
+// whatever the offsets hold, the result is below n_blocks.
+__device__ __forceinline__ uint32_t find_block(const uint64_t* __restrict__ off, uint32_t n_blocks,
+                                               uint64_t e, uint32_t* slots) {
+  uint32_t lo = 0, hi = n_blocks;
+  while (hi - lo > 1) {
+    const uint32_t span = hi - lo;
+    if (span <= kWG) {  // one probe per candidate: the last one not above e wins
+      const bool le = threadIdx.x < span && off[lo + threadIdx.x] <= e;
+      const uint32_t cnt = workgroup_count(le, slots);
+      return lo + (cnt ? cnt - 1 : 0);
+    }
+    const uint32_t p = lo + (uint32_t)(((uint64_t)(threadIdx.x + 1) * span) / (kWG + 1));
+    const uint32_t cnt = workgroup_count(off[p] <= e, slots);
+    const uint32_t nlo = cnt ? lo + (uint32_t)(((uint64_t)cnt * span) / (kWG + 1)) : lo;
+    const uint32_t nhi = cnt < kWG ? lo + (uint32_t)(((uint64_t)(cnt + 1) * span) / (kWG + 1)) : hi;
+    lo = nlo;
+    hi = nhi;
+  }
+  return lo;
+}
+
+enum : int { COPY_NONE = 0, COPY_X_TO_C = 1, COPY_C_TO_X = 2 };
+
+// One segment of `len` elements starting at element `first`, spread over the workgroup.
+//   ACC:  acc += sum of (c - x)^2 or |c - x| over the segment (this lane's share)
+//   COPY: the segment is copied x -> c or c -> x afterwards
+template <int DT, bool ACC, int COPY>
+__device__ __forceinline__ void segment_apply(char* __restrict__ x, char* __restrict__ c,
+                                              uint64_t first, uint64_t len, bool base_aligned,
+                                              typename Acc<DT>::type& acc) {
+  constexpr int E = elem_bytes(DT);
+  constexpr int EPV = 16 / E;
+  using word_t = typename std::conditional<E == 4, uint32_t, uint16_t>::type;
+  char* xs = x + first * E;
+  char* cs = c + first * E;
+  auto element = [&](uint64_t j) {
+    if (ACC) accumulate_elem<DT>(acc, cs, xs, j);
+    if (COPY == COPY_X_TO_C) ((word_t*)cs)[j] = ((const word_t*)xs)[j];
+    if (COPY == COPY_C_TO_X) ((word_t*)xs)[j] = ((const word_t*)cs)[j];
+  };
+  uint64_t head = len;  // elements handled one by one before the 16-byte body
+  if (base_aligned) {
+    head = ((16 - ((first * E) & 15)) & 15) / E;
+    if (head > len) head = len;
+  }
+  for (uint64_t j = threadIdx.x; j < head; j += kWG) element(j);
+  const uint64_t nvec = (len - head) / EPV;
+  uint4* xv = (uint4*)(xs + head * E);
+  uint4* cv = (uint4*)(cs + head * E);
+  for (uint64_t v0 = 0; v0 < nvec; v0 += (uint64_t)kWG * kUnroll) {
+    uint4 a[kUnroll], b[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint64_t v = v0 + (uint64_t)u * kWG + threadIdx.x;
+      const bool ok = v < nvec;
+      a[u] = (ok && (ACC || COPY == COPY_X_TO_C)) ? load_stream(xv + v) : make_uint4(0, 0, 0, 0);
+      b[u] = (ok && (ACC || COPY == COPY_C_TO_X)) ? load_stream(cv + v) : make_uint4(0, 0, 0, 0);
+    }
+    if (ACC) accumulate_vec<DT>(acc, b, a);
+    if (COPY != COPY_NONE) {
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const uint64_t v = v0 + (uint64_t)u * kWG + threadIdx.x;
+        if (v < nvec) {
+          if (COPY == COPY_X_TO_C) store_stream(cv + v, a[u]);
+          if (COPY == COPY_C_TO_X) store_stream(xv + v, b[u]);
+        }
+      }
+    }
+  }
+  for (uint64_t j = head + nvec * EPV + threadIdx.x; j < len; j += kWG) element(j);
+}
+
+// The walk over one range.
+//   PER_BLOCK (scores): every block met gets its own sum in partial[w + b].
+//   otherwise: only blocks with mask[b] != 0 (all blocks if mask == NULL) are touched and
+//   the workgroup's total goes to partial[w] (if ACC).
+template <int DT, bool ACC, int COPY, bool PER_BLOCK>
+__global__ __launch_bounds__(kWG) void k_var_walk(char* __restrict__ x, char* __restrict__ c,
+                                                  const uint64_t* __restrict__ off, uint32_t n_blocks,
+                                                  uint64_t n_elems, uint64_t range_elems, uint32_t n_wg,
+                                                  const uint8_t* __restrict__ mask,
+                                                  typename Acc<DT>::type* __restrict__ partial,
+                                                  bool base_aligned) {
+  using acc_t = typename Acc<DT>::type;
+  __shared__ acc_t slots[kWG / kWave];
+  __shared__ uint32_t count_slots[kWG / kWave];
+  const uint32_t w = xcd_contiguous_block_id();
+  if (w >= n_wg) return;
+  const uint64_t e0 = (uint64_t)w * range_elems;
+  const uint64_t e1 = e0 + range_elems < n_elems ? e0 + range_elems : n_elems;
+  uint32_t cur = find_block(off, n_blocks, e0, count_slots);
+  acc_t acc = 0;
+  uint64_t pos = e0;
+  while (pos < e1) {
+    uint64_t bend = off[cur + 1];
+    while (bend <= pos && cur + 1 < n_blocks) {  // block `cur` ends here: hand in its sum
+      if (PER_BLOCK) {
+        const acc_t total = workgroup_sum(acc, slots);
+        if (threadIdx.x == 0) partial[(uint64_t)w + cur] = total;
+        acc = 0;
+      }
+      ++cur;
+      bend = off[cur + 1];
+    }
+    if (bend <= pos) break;  // offsets do not cover the store: leave the rest alone
+    const uint64_t seg_end = bend < e1 ? bend : e1;
+    if (PER_BLOCK || !mask || mask[cur])
+      segment_apply<DT, ACC, COPY>(x, c, pos, seg_end - pos, base_aligned, acc);
+    pos = seg_end;
+  }
+  if (ACC) {
+    const acc_t total = workgroup_sum(acc, slots);
+    if (threadIdx.x == 0) partial[PER_BLOCK ? (uint64_t)w + cur : (uint64_t)w] = total;
+  }
+}
+
+// Second stage of the scores: G lanes add the slots of one block in a fixed order.
+template <int DT, int G>
+__global__ __launch_bounds__(kWG) void k_var_scores_finish(const typename Acc<DT>::type* __restrict__ partial,
+                                                           const uint64_t* __restrict__ off,
+                                                           uint32_t n_blocks, uint64_t n_elems,
+                                                           uint64_t range_elems, void* __restrict__ scores) {
+  using acc_t = typename Acc<DT>::type;
+  constexpr int GPW = kWG / G;
+  __shared__ acc_t slots[kWG / kWave];
+  const int lane = threadIdx.x & (G - 1);
+  for (uint64_t b = (uint64_t)blockIdx.x * GPW + threadIdx.x / G; b < n_blocks;
+       b += (uint64_t)gridDim.x * GPW) {
+    const uint64_t lo = off[b];
+    uint64_t hi = off[b + 1];
+    if (hi > n_elems) hi = n_elems;
+    acc_t acc = 0;
+    if (hi > lo) {
+      const uint64_t w_first = lo / range_elems, w_last = (hi - 1) / range_elems;
+      for (uint64_t w = w_first + lane; w <= w_last; w += G) acc += partial[w + b];
+    }
+    if constexpr (G == kWG)
+      acc = workgroup_sum(acc, slots);
+    else
+      acc = group_sum<G>(acc);
+    if (lane == 0) {
+      if constexpr (DT == DT_I32)
+        ((long long*)scores)[b] = (long long)acc;
+      else
+        ((float*)scores)[b] = (float)acc;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kWG) void k_var_mask_clear(uint8_t* __restrict__ mask, uint32_t n_blocks) {
+  for (uint64_t i = (uint64_t)blockIdx.x * kWG + threadIdx.x; i < n_blocks; i += (uint64_t)gridDim.x * kWG)
+    mask[i] = 0;
+}
+
+__global__ __launch_bounds__(kWG) void k_var_mask_set(uint8_t* __restrict__ mask, uint32_t n_blocks,
+                                                      const uint32_t* __restrict__ idx, uint32_t n_idx) {
+  for (uint64_t i = (uint64_t)blockIdx.x * kWG + threadIdx.x; i < n_idx; i += (uint64_t)gridDim.x * kWG) {
+    const uint32_t b = idx[i];
+    if (b < n_blocks) mask[b] = 1;
+  }
+}
+
+static uint64_t var_blocks(const scar_var_layout* l) {
+  if (!l || !dtype_ok(l->dtype) || l->n_blocks > SCAR_MAX_BLOCKS) return UINT64_MAX;
+  if (l->n_blocks && (!l->offsets || !aligned(l->offsets, 8))) return UINT64_MAX;
+  return l->n_blocks;
+}
+
+static int check_var_workspace(const void* ws, size_t bytes, uint64_t n_blocks) {
+  if (!ws || !aligned(ws, 256) || bytes < var_workspace_bytes_for(n_blocks)) return SCAR_ERR_WORKSPACE;
+  return SCAR_OK;
+}
+
+template <int DT, bool ACC, int COPY, bool PER_BLOCK>
+static void launch_walk(const scar_var_layout* l, const void* x, const void* c, const uint8_t* mask,
+                        void* partial, const VarGeometry& g, hipStream_t st) {
+  const bool base_aligned = aligned(x, 16) && aligned(c, 16);
+  hipLaunchKernelGGL((k_var_walk<DT, ACC, COPY, PER_BLOCK>), dim3(xcd_grid(g.n_wg, kVarMaxGrid)), dim3(kWG),
+                     0, st, (char*)const_cast<void*>(x), (char*)const_cast<void*>(c), l->offsets,
+                     l->n_blocks, l->n_elems, g.range_elems, g.n_wg, mask,
+                     (typename Acc<DT>::type*)partial, base_aligned);
+}
+
+template <bool ACC, int COPY, bool PER_BLOCK>
+static void dispatch_walk(const scar_var_layout* l, const void* x, const void* c, const uint8_t* mask,
+                          void* partial, const VarGeometry& g, hipStream_t st) {
+  switch (l->dtype) {
+    case SCAR_F32: launch_walk<DT_F32, ACC, COPY, PER_BLOCK>(l, x, c, mask, partial, g, st); break;
+    case SCAR_BF16: launch_walk<DT_BF16, ACC, COPY, PER_BLOCK>(l, x, c, mask, partial, g, st); break;
+    default: launch_walk<DT_I32, ACC, COPY, PER_BLOCK>(l, x, c, mask, partial, g, st); break;
+  }
+}
+
+template <int DT>
+static void launch_scores_finish(const scar_var_layout* l, const void* partial, const VarGeometry& g,
+                                 void* scores, hipStream_t st) {
+  using acc_t = typename Acc<DT>::type;
+  if (l->n_blocks <= 16384) {  // few blocks, possibly huge: a whole workgroup adds each one's slots
+    hipLaunchKernelGGL((k_var_scores_finish<DT, kWG>), dim3(l->n_blocks), dim3(kWG), 0, st,
+                       (const acc_t*)partial, l->offsets, l->n_blocks, l->n_elems, g.range_elems, scores);
+  } else {
+    const uint64_t need = ((uint64_t)l->n_blocks + 3) / 4;
+    hipLaunchKernelGGL((k_var_scores_finish<DT, kWave>), dim3((uint32_t)(need < 65536 ? need : 65536)),
+                       dim3(kWG), 0, st, (const acc_t*)partial, l->offsets, l->n_blocks, l->n_elems,
+                       g.range_elems, scores);
+  }
+}
+
+// Marks the blocks of idx in the workspace's selection bytes; returns their address.
+static const uint8_t* mark_blocks(const scar_var_layout* l, const uint32_t* idx, uint32_t n_idx,
+                                  void* workspace, hipStream_t st) {
+  uint8_t* mask = (uint8_t*)workspace + var_mask_offset(l->n_blocks);
+  const uint32_t cg = (l->n_blocks + kWG * 16 - 1) / (kWG * 16);
+  hipLaunchKernelGGL(k_var_mask_clear, dim3(cg < 4096 ? cg : 4096), dim3(kWG), 0, st, mask, l->n_blocks);
+  const uint32_t sg = (n_idx + kWG - 1) / kWG;
+  hipLaunchKernelGGL(k_var_mask_set, dim3(sg < 4096 ? sg : 4096), dim3(kWG), 0, st, mask, l->n_blocks, idx,
+                     n_idx);
+  return mask;
+}
+
+// Shared body of commit (copy = COPY_X_TO_C), recovery (COPY_C_TO_X) and norm (COPY_NONE).
+static int var_rows(int copy, const scar_var_layout* layout, const void* x, const void* c,
+                    const uint32_t* idx, uint32_t n_idx, bool all_blocks, scar_norm* norm_out,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  const uint64_t nb = var_blocks(layout);
+  if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
+  if (norm_out && !aligned(norm_out, 8)) return SCAR_ERR_INVALID_ARG;
+  const int rc = check_var_workspace(workspace, workspace_bytes, nb);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const bool nothing = nb == 0 || layout->n_elems == 0 || (!all_blocks && n_idx == 0);
+  if (nothing) {
+    if (norm_out) {
+      launch_finish(layout->dtype, workspace, 0, norm_out, st);
+      return launch_status();
+    }
+    return SCAR_OK;
+  }
+  const int eb = host_elem_bytes(layout->dtype);
+  if (!x || !c || (!all_blocks && !idx) || !aligned(x, eb) || !aligned(c, eb) || !aligned(idx, 4))
+    return SCAR_ERR_INVALID_ARG;
+  const VarGeometry g = var_geometry(layout->n_elems);
+  const uint8_t* mask = all_blocks ? nullptr : mark_blocks(layout, idx, n_idx, workspace, st);
+  if (copy == COPY_X_TO_C)
+    dispatch_walk<false, COPY_X_TO_C, false>(layout, x, c, mask, nullptr, g, st);
+  else if (copy == COPY_C_TO_X && norm_out)
+    dispatch_walk<true, COPY_C_TO_X, false>(layout, x, c, mask, workspace, g, st);
+  else if (copy == COPY_C_TO_X)
+    dispatch_walk<false, COPY_C_TO_X, false>(layout, x, c, mask, nullptr, g, st);
+  else
+    dispatch_walk<true, COPY_NONE, false>(layout, x, c, mask, workspace, g, st);
+  if (norm_out) launch_finish(layout->dtype, workspace, g.n_wg, norm_out, st);
+  return launch_status();
+}
+
+}  // namespace scar
+
+using namespace scar;
+
+extern "C" size_t scar_var_workspace_bytes(uint64_t n_blocks) {
+  return n_blocks > SCAR_MAX_BLOCKS ? 0 : var_workspace_bytes_for(n_blocks);
+}
+
+extern "C" int scar_var_block_scores(const scar_var_layout* layout, const void* x, const void* c,
+                                     void* scores, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+  const uint64_t nb = var_blocks(layout);
+  if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
+  if (nb == 0) return SCAR_OK;
+  const int eb = host_elem_bytes(layout->dtype);
+  if (!scores || !aligned(scores, layout->dtype == SCAR_I32 ? 8 : 4)) return SCAR_ERR_INVALID_ARG;
+  if (layout->n_elems && (!x || !c || !aligned(x, eb) || !aligned(c, eb))) return SCAR_ERR_INVALID_ARG;
+  const int rc = check_var_workspace(workspace, workspace_bytes, nb);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const VarGeometry g = var_geometry(layout->n_elems);
+  if (layout->n_elems) dispatch_walk<true, COPY_NONE, true>(layout, x, c, nullptr, workspace, g, st);
+  switch (layout->dtype) {
+    case SCAR_I32: launch_scores_finish<DT_I32>(layout, workspace, g, scores, st); break;
+    default: launch_scores_finish<DT_F32>(layout, workspace, g, scores, st); break;
+  }
+  return launch_status();
+}
+
+extern "C" int scar_var_checkpoint_commit(const scar_var_layout* layout, const void* x, void* c,
+                                          const uint32_t* idx, uint32_t n_idx, void* workspace,
+                                          size_t workspace_bytes, void* stream) {
+  return var_rows(COPY_X_TO_C, layout, x, c, idx, n_idx, false, nullptr, workspace, workspace_bytes,
+                  stream);
+}
+
+extern "C" int scar_var_partial_recover(const scar_var_layout* layout, void* x, const void* c,
+                                        const uint32_t* lost_idx, uint32_t n_lost, scar_norm* norm_out,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+  return var_rows(COPY_C_TO_X, layout, x, c, lost_idx, n_lost, false, norm_out, workspace,
+                  workspace_bytes, stream);
+}
+
+extern "C" int scar_var_perturbation_norm(const scar_var_layout* layout, const void* x, const void* c,
+                                          const uint32_t* idx, uint32_t n_idx, scar_norm* norm_out,
+                                          void* workspace, size_t workspace_bytes, void* stream) {
+  if (!norm_out) return SCAR_ERR_INVALID_ARG;
+  return var_rows(COPY_NONE, layout, x, c, idx, n_idx, idx == nullptr, norm_out, workspace,
+                  workspace_bytes, stream);
+}

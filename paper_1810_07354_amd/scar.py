@@ -32,6 +32,12 @@ class Layout(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("block_len", ctypes.c_uint32), ("n_elems", ctypes.c_uint64)]
 
 
+class VarLayout(ctypes.Structure):
+    """scar_var_layout: blocks of unequal length given by device-resident offsets."""
+    _fields_ = [("dtype", ctypes.c_int32), ("n_blocks", ctypes.c_uint32), ("n_elems", ctypes.c_uint64),
+                ("offsets", ctypes.c_void_p)]
+
+
 class Norm(ctypes.Structure):
     """scar_norm as laid out in device memory."""
     _fields_ = [("sum", ctypes.c_double), ("norm", ctypes.c_double), ("isum", ctypes.c_int64)]
@@ -65,6 +71,16 @@ def lib():
         L.scar_mask_to_indices.argtypes = [vp, u32, vp, vp, vp, sz, vp]
         L.scar_select_round.argtypes = [u32, u32, u64, vp, vp]
         L.scar_select_random.argtypes = [u32, u32, u64, u64, vp, vp, sz, vp]
+        vlp = ctypes.POINTER(VarLayout)
+        L.scar_var_workspace_bytes.argtypes = [u64]
+        L.scar_var_workspace_bytes.restype = sz
+        L.scar_var_block_scores.argtypes = [vlp, vp, vp, vp, vp, sz, vp]
+        L.scar_var_checkpoint_commit.argtypes = [vlp, vp, vp, vp, u32, vp, sz, vp]
+        L.scar_var_partial_recover.argtypes = [vlp, vp, vp, vp, u32, vp, vp, sz, vp]
+        L.scar_var_perturbation_norm.argtypes = [vlp, vp, vp, vp, u32, vp, vp, sz, vp]
+        for name in ("scar_var_block_scores", "scar_var_checkpoint_commit", "scar_var_partial_recover",
+                     "scar_var_perturbation_norm"):
+            getattr(L, name).restype = ctypes.c_int
         for name in ("scar_block_scores", "scar_select_topk", "scar_checkpoint_commit",
                      "scar_partial_recover", "scar_perturbation_norm", "scar_mask_to_indices",
                      "scar_select_round", "scar_select_random"):
@@ -243,3 +259,74 @@ def select_random(n_blocks_, k, seed, draw, workspace, out=None):
     _check(lib().scar_select_random(int(n_blocks_), int(k), int(seed), int(draw), _p(out),
                                     _p(workspace), workspace.numel(), _stream()), "scar_select_random")
     return out
+
+
+# ---- blocks of unequal length -------------------------------------------------------------
+
+def var_layout_of(x, offsets) -> VarLayout:
+    """offsets: int64 device tensor of n_blocks + 1 element offsets (offsets[0] = 0)."""
+    _dev(offsets, "offsets")
+    if offsets.dtype != torch.int64:
+        raise TypeError("offsets must be an int64 tensor")
+    if x.dtype not in _DTYPE_OF:
+        raise TypeError("unsupported element type %s" % x.dtype)
+    return VarLayout(_DTYPE_OF[x.dtype], offsets.numel() - 1, x.numel(), offsets.data_ptr())
+
+
+def var_workspace_bytes(n_blocks_: int) -> int:
+    return int(lib().scar_var_workspace_bytes(int(n_blocks_)))
+
+
+def new_var_workspace(n_blocks_: int, device) -> torch.Tensor:
+    return torch.empty(var_workspace_bytes(n_blocks_), dtype=torch.uint8, device=device)
+
+
+def var_block_scores(x, c, offsets, workspace, out=None):
+    """scar_var_block_scores."""
+    _dev(x, "x"), _dev(c, "c"), _dev(workspace, "workspace")
+    if x.dtype != c.dtype or x.numel() != c.numel():
+        raise ValueError("x and c must have the same element type and size")
+    lay = var_layout_of(x, offsets)
+    if out is None:
+        out = torch.empty(lay.n_blocks, dtype=torch.int64 if x.dtype == torch.int32 else torch.float32,
+                          device=x.device)
+    _check(lib().scar_var_block_scores(ctypes.byref(lay), _p(x), _p(c), _p(out), _p(workspace),
+                                       workspace.numel(), _stream()), "scar_var_block_scores")
+    return out
+
+
+def var_checkpoint_commit(x, c, offsets, idx, workspace):
+    """scar_var_checkpoint_commit."""
+    _dev(x, "x"), _dev(c, "c"), _dev(idx, "idx"), _dev(workspace, "workspace")
+    lay = var_layout_of(x, offsets)
+    _check(lib().scar_var_checkpoint_commit(ctypes.byref(lay), _p(x), _p(c), _p(idx), idx.numel(),
+                                            _p(workspace), workspace.numel(), _stream()),
+           "scar_var_checkpoint_commit")
+
+
+def var_partial_recover(x, c, offsets, lost_idx, workspace, want_norm=True):
+    """scar_var_partial_recover; returns the device scar_norm buffer or None."""
+    _dev(x, "x"), _dev(c, "c"), _dev(lost_idx, "lost_idx"), _dev(workspace, "workspace")
+    lay = var_layout_of(x, offsets)
+    norm_out = _norm_buffer(x.device) if want_norm else None
+    _check(lib().scar_var_partial_recover(ctypes.byref(lay), _p(x), _p(c), _p(lost_idx), lost_idx.numel(),
+                                          _p(norm_out), _p(workspace), workspace.numel(), _stream()),
+           "scar_var_partial_recover")
+    return norm_out
+
+
+def var_perturbation_norm(x, c, offsets, idx, workspace):
+    """scar_var_perturbation_norm (idx None = every block)."""
+    _dev(x, "x"), _dev(c, "c"), _dev(workspace, "workspace")
+    lay = var_layout_of(x, offsets)
+    norm_out = _norm_buffer(x.device)
+    if idx is None:
+        ptr, n = ctypes.c_void_p(0), 0
+    else:
+        _dev(idx, "idx")
+        n = idx.numel()
+        ptr = _p(idx) if n else _p(norm_out)
+    _check(lib().scar_var_perturbation_norm(ctypes.byref(lay), _p(x), _p(c), ptr, n, _p(norm_out),
+                                            _p(workspace), workspace.numel(), _stream()),
+           "scar_var_perturbation_norm")
+    return norm_out

@@ -165,6 +165,62 @@ def cnn_like(seed: int = 3, n_elems: int = 25_000_000, block_len: int = 4096,
                     {"fraction": fraction})
 
 
+@dataclass
+class VarWorkload:
+    name: str
+    dtype: int
+    offsets: np.ndarray      # uint64, n_blocks + 1 element offsets
+    x: np.ndarray
+    c: np.ndarray
+    k: int
+    lost: np.ndarray
+    note: str = ""
+
+    @property
+    def n_blocks(self) -> int:
+        return int(self.offsets.size - 1)
+
+
+# The paper's CNN (Section 5.1): two 5x5 convolutions and three fully-connected layers,
+# weights and biases as separate parameters ("by-layer").  Sizes are those of a common
+# MNIST network of that shape.
+CNN_LAYER_SIZES = (5 * 5 * 1 * 32, 32, 5 * 5 * 32 * 64, 64, 7 * 7 * 64 * 1024, 1024,
+                   1024 * 512, 512, 512 * 10, 10)
+
+
+def layers_like(sizes=CNN_LAYER_SIZES, seed: int = 5, fraction: float = 0.25, n_lost: int = 3,
+                dtype: int = F32) -> VarWorkload:
+    """A store cut "by layer": one block per tensor, sizes as given (zero allowed)."""
+    rng = np.random.default_rng(seed)
+    sizes = np.asarray(sizes, dtype=np.int64)
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.uint64)
+    n, nb = int(off[-1]), sizes.size
+    if dtype == I32:
+        c = rng.integers(0, 1000, size=n).astype(np.int32)
+        x = c + (rng.integers(-3, 4, size=n) * (rng.random(n) < 0.05)).astype(np.int32)
+    else:
+        c = rng.normal(0.0, 0.02, size=n).astype(np.float32)
+        u = rng.uniform(0.1, 10.0, size=nb)
+        x = (c + rng.normal(0.0, 1e-3, size=n) * np.repeat(u, sizes)).astype(np.float32)
+        if dtype == BF16:
+            x, c = f32_to_bf16_bits(x), f32_to_bf16_bits(c)
+    k = k_of_fraction(fraction, nb)
+    lost = random_lost_blocks(nb, min(n_lost, nb), seed + 1000)
+    return VarWorkload("layers_like", dtype, off, x, c, k, lost,
+                       "%d tensors of %d..%d elements" % (nb, sizes.min(), sizes.max()))
+
+
+def mixed_layer_sizes(n_layers: int, total: int, seed: int = 6):
+    """n_layers tensor sizes spread over four orders of magnitude that add up to about
+    `total` elements, a few of them empty or tiny, none aligned to anything."""
+    rng = np.random.default_rng(seed)
+    w = rng.lognormal(0.0, 2.5, size=n_layers)
+    sizes = np.maximum(1, (w / w.sum() * total)).astype(np.int64)
+    sizes[rng.choice(n_layers, size=max(1, n_layers // 16), replace=False)] = 0
+    sizes[rng.choice(n_layers, size=max(1, n_layers // 16), replace=False)] = 3
+    return sizes
+
+
 def student_t3(rng: np.random.Generator, n: int) -> np.ndarray:
     """Student-t with 3 degrees of freedom: Z0 / sqrt((Z1^2 + Z2^2 + Z3^2) / 3)."""
     z = rng.standard_normal(size=(4, n))

@@ -1,0 +1,110 @@
+"""Blocks of unequal length ("by-layer" partitioning, Section 5.1) on the GPU against the
+oracle: scores, commit, recovery with the fused norm, the norm alone, and whole cycles."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1810_07354_amd import scar
+from paper_1810_07354_amd import workloads as wl
+from gpu_util import (DEV, REL_TOL, assert_norm_matches, assert_scores_match, assert_selection_matches,
+                      idx_dev, idx_host, to_dev, to_host)
+
+pytestmark = pytest.mark.gpu
+
+
+def off_dev(off):
+    return torch.from_numpy(off.astype(np.int64)).to(DEV)
+
+
+def cycle(w: wl.VarWorkload, k=None, lost=None, unaligned=False):
+    dt, off = w.dtype, w.offsets
+    k = w.k if k is None else k
+    lost = w.lost if lost is None else lost
+    hx, hc = w.x.copy(), w.c.copy()
+    if unaligned:                         # views that start one element into their allocation
+        pad = np.zeros(1, dtype=hx.dtype)
+        x, c = to_dev(np.concatenate([pad, hx]), dt)[1:], to_dev(np.concatenate([pad, hc]), dt)[1:]
+    else:
+        x, c = to_dev(hx, dt), to_dev(hc, dt)
+    d_off = off_dev(off)
+    nb = w.n_blocks
+    ws = scar.new_var_workspace(nb, DEV)
+    ws_sel = scar.new_workspace(nb, DEV)
+
+    s = scar.var_block_scores(x, c, d_off, ws)
+    s_ref = oracle.var_block_scores(dt, hx, hc, off)
+    assert_scores_match(s, s_ref, dt)
+
+    idx = scar.select_topk(s, k, ws_sel)
+    assert_selection_matches(idx_host(idx), s.cpu().numpy(), s_ref, k)
+
+    scar.var_checkpoint_commit(x, c, d_off, idx, ws)
+    oracle.var_checkpoint_commit(dt, hx, hc, off, idx_host(idx))
+    np.testing.assert_array_equal(to_host(c.contiguous()), hc)
+    np.testing.assert_array_equal(to_host(x.contiguous()), hx)
+
+    full = scar.read_norm(scar.var_perturbation_norm(x, c, d_off, None, ws))
+    assert_norm_matches(full, oracle.var_perturbation_norm(dt, hx, hc, off), dt)
+    part = scar.read_norm(scar.var_perturbation_norm(x, c, d_off, idx_dev(lost), ws))
+    got = scar.read_norm(scar.var_partial_recover(x, c, d_off, idx_dev(lost), ws))
+    want = oracle.var_partial_recover(dt, hx, hc, off, lost)
+    assert_norm_matches(got, want, dt)
+    assert part == got and got[1] <= full[1] * (1 + REL_TOL)
+    np.testing.assert_array_equal(to_host(x.contiguous()), hx)
+    np.testing.assert_array_equal(to_host(c.contiguous()), hc)
+    assert scar.read_norm(scar.var_partial_recover(x, c, d_off, idx_dev(lost), ws)) == (0.0, 0.0, 0)
+    scar.var_partial_recover(x, c, d_off, idx_dev(lost), ws, want_norm=False)
+    np.testing.assert_array_equal(to_host(x.contiguous()), hx)
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16, wl.I32])
+def test_cnn_by_layer(dtype):
+    print("by-layer CNN dtype=%d" % dtype, flush=True)
+    cycle(wl.layers_like(dtype=dtype))
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16, wl.I32])
+@pytest.mark.parametrize("unaligned", [False, True])
+def test_mixed_layers(dtype, unaligned):
+    sizes = wl.mixed_layer_sizes(200, 6_000_000)
+    w = wl.layers_like(sizes, seed=9, fraction=0.2, n_lost=50, dtype=dtype)
+    print("mixed layers dtype=%d unaligned=%s n=%d" % (dtype, unaligned, w.x.size), flush=True)
+    cycle(w, unaligned=unaligned)
+
+
+def test_many_small_unequal_blocks_and_long_ranges():
+    # 300,000 short ragged rows: long runs of small blocks inside one range; and a store big
+    # enough (> 32,768 chunks) for ranges of several chunks
+    r = np.random.default_rng(3)
+    sizes = r.integers(0, 40, size=300_000)
+    cycle(wl.layers_like(sizes, seed=10, fraction=0.1, n_lost=40_000))
+    sizes = wl.mixed_layer_sizes(64, 150_000_000, seed=8)
+    cycle(wl.layers_like(sizes, seed=11, fraction=0.25, n_lost=16))
+
+
+def test_equal_blocks_agree_with_the_fixed_layout_kernels():
+    w = wl.cnn_like(n_elems=3_000_000, block_len=4096)
+    x, c = to_dev(w.x, w.dtype), to_dev(w.c, w.dtype)
+    nb = w.n_blocks
+    off = np.minimum(np.arange(nb + 1, dtype=np.uint64) * 4096, np.uint64(w.x.size))
+    s_var = scar.var_block_scores(x, c, off_dev(off), scar.new_var_workspace(nb, DEV))
+    s_fix = scar.block_scores(x, c, 4096)
+    np.testing.assert_allclose(s_var.cpu().numpy(), s_fix.cpu().numpy(), rtol=1e-6)
+
+
+def test_edge_cases():
+    ws = scar.new_var_workspace(4, DEV)
+    x = torch.arange(10, dtype=torch.float32, device=DEV)
+    c = torch.zeros(10, dtype=torch.float32, device=DEV)
+    off = off_dev(np.array([0, 0, 10, 10, 10], dtype=np.uint64))       # one block holds everything
+    s = scar.var_block_scores(x, c, off, ws)
+    np.testing.assert_array_equal(s.cpu().numpy(), [0.0, 285.0, 0.0, 0.0])
+    empty = torch.zeros(0, dtype=torch.int32, device=DEV)
+    assert scar.read_norm(scar.var_perturbation_norm(x, c, off, empty, ws)) == (0.0, 0.0, 0)
+    assert scar.read_norm(scar.var_partial_recover(x, c, off, empty, ws)) == (0.0, 0.0, 0)
+    assert scar.read_norm(scar.var_perturbation_norm(x, c, off, idx_dev([0, 2, 3]), ws)) == (0.0, 0.0, 0)
+    scar.var_checkpoint_commit(x, c, off, idx_dev([1]), ws)
+    assert torch.equal(x, c)
+    with pytest.raises(scar.ScarError):
+        scar.var_block_scores(x, c, off, ws[:256])

@@ -84,3 +84,14 @@ def test_flat_like_torch_cpu_is_seeded():
     wl.drift_torch(x1, seed=7, fraction=0.25, block_len=1024)
     changed = (x1 != x0).reshape(16, 1024).any(dim=1)
     assert int(changed.sum()) == 4
+
+
+def test_by_layer_generators():
+    w = wl.layers_like()
+    assert w.n_blocks == 10 and int(w.offsets[-1]) == w.x.size == sum(wl.CNN_LAYER_SIZES)
+    assert w.k == 3 and w.lost.size == 3
+    sizes = wl.mixed_layer_sizes(200, 6_000_000)
+    assert sizes.size == 200 and (sizes == 0).sum() >= 1 and sizes.max() > 1000 * max(1, np.median(sizes)) / 50
+    assert 0.5 * 6_000_000 < sizes.sum() < 1.1 * 6_000_000
+    v = wl.layers_like(sizes, seed=9, dtype=wl.I32)
+    assert v.x.dtype == np.int32 and np.all(np.diff(v.offsets.astype(np.int64)) == sizes)
