@@ -171,13 +171,84 @@ def cpu_baseline(x, c, L, k_frac, lost_frac, sample_elems, threads):
             "single_thread_ms_per_cycle": times["one"] * 1e3}
 
 
+def main_layers(args):
+    """The by-layer variant: the 2^30-element f32 store cut into 96 tensors of very unequal
+    size (blocks of unequal length), through the scar_var_* entry points."""
+    import numpy as np
+    import torch
+    from paper_1810_07354_amd import scar, workloads as wl
+
+    dev = "cuda:0"
+    n_elems, seed = 1 << 30, 4
+    sizes = wl.mixed_layer_sizes(96, n_elems, seed=6)
+    sizes[np.argmax(sizes)] += n_elems - sizes.sum()          # make the sizes add up exactly
+    off_h = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    nb = sizes.size
+    x, c = wl.flat_like_torch(dev, seed=seed, n_elems=n_elems)
+    off = torch.from_numpy(off_h).to(dev)
+    k, n_lost = wl.k_of_fraction(0.10, nb), 12
+    ws, ws_sel = scar.new_var_workspace(nb, dev), scar.new_workspace(nb, dev)
+    scores = torch.empty(nb, dtype=torch.float32, device=dev)
+    idx = torch.empty(k, dtype=torch.int32, device=dev)
+    total = args.warmup + args.steps
+    lost_h = [wl.random_lost_blocks(nb, n_lost, seed + 1000 + i) for i in range(total)]
+    lost = [torch.from_numpy(l.view(np.int32).copy()).to(dev) for l in lost_h]
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(total)]
+    moved = []
+
+    def step(i):
+        ev[i][0].record()
+        scar.var_block_scores(x, c, off, ws, out=scores)
+        ev[i][1].record()
+        scar.select_topk(scores, k, ws_sel, out=idx)
+        scar.var_checkpoint_commit(x, c, off, idx, ws)
+        return scar.var_partial_recover(x, c, off, lost[i], ws)
+
+    wall = []
+    for i in range(total):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        nrm = step(i)
+        torch.cuda.synchronize()
+        if i >= args.warmup:
+            wall.append(time.perf_counter() - t0)
+            chosen = idx.cpu().numpy()
+            moved.append((2 * 4 * int(sizes[chosen].sum()), 3 * 4 * int(sizes[lost_h[i]].sum())))
+        for j in range(3):   # three separate windows, so that more tensors move than one checkpoint saves
+            wl.drift_torch(x, seed + 5000 + 3 * i + j, 0.10, 1024)
+    ms_step = 1e3 * sum(wall) / len(wall)
+    score_ms = sum(ev[i][0].elapsed_time(ev[i][1]) for i in range(args.warmup, total)) / args.steps
+    score_bytes = 2 * n_elems * 4 + 4 * nb
+    commit_bytes = sum(m[0] for m in moved) / len(moved)
+    recover_bytes = sum(m[1] for m in moved) / len(moved)
+    cycle_bytes = score_bytes + commit_bytes + recover_bytes
+    achieved = score_bytes / (score_ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "params scanned GB/s per checkpoint+recovery cycle",
+        "value": round(n_elems * 4 / (ms_step * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "2^30 x fp32 cut by layer into 96 tensors of %d..%d elements, k=10%% of "
+                               "tensors, 12 tensors lost" % (sizes.min(), sizes.max()),
+                   "n_elems": n_elems, "n_blocks": nb, "k": k, "n_lost": n_lost},
+        "pct_of_hbm_peak": round(100.0 * cycle_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+        "mean_bytes_per_cycle": cycle_bytes, "mean_commit_bytes": commit_bytes,
+        "mean_recover_bytes": recover_bytes, "last_norm": scar.read_norm(nrm)[1],
+        "roofline": {"bound": "hbm", "kernel": "k_var_walk (scores) + k_var_scores_finish",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "avg_ms": round(score_ms, 4), "algorithmic_bytes_per_launch": score_bytes},
+        "cpu_baseline": None}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="flat_f32",
-                    choices=["flat_f32", "flat_bf16", "mlr", "mf", "lda", "cnn"])
+                    choices=["flat_f32", "flat_bf16", "mlr", "mf", "lda", "cnn", "layers"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for HBM counters)")
@@ -202,6 +273,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     scar.lib()   # fail now if the HIP library is missing
+
+    if args.workload == "layers":
+        return main_layers(args)
 
     x, c, L, k, n_lost, lost_of, drift, label = make_workload(args.workload, dev)
     n_elems = x.numel()

@@ -95,16 +95,16 @@ struct Acc<DT_I32> {
   using type = unsigned long long;
 };
 
-template <int DT>
-__device__ __forceinline__ void accumulate_vec(typename Acc<DT>::type& acc, const uint4 (&a)[kUnroll],
-                                               const uint4 (&b)[kUnroll]) {
+template <int DT, int U>
+__device__ __forceinline__ void accumulate_vec(typename Acc<DT>::type& acc, const uint4 (&a)[U],
+                                               const uint4 (&b)[U]) {
   if constexpr (DT == DT_I32) {
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) acc += absdiff_i32x4(a[u], b[u]);
+    for (int u = 0; u < U; ++u) acc += absdiff_i32x4(a[u], b[u]);
   } else {
     float part = 0.f;
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u)
+    for (int u = 0; u < U; ++u)
       part += (DT == DT_F32) ? sqdiff_f32(a[u], b[u]) : sqdiff_bf16(a[u], b[u]);
     acc += (double)part;
   }
@@ -188,7 +188,7 @@ __device__ __forceinline__ typename Acc<DT>::type block_distance(const char* xb,
         b[u] = make_uint4(0, 0, 0, 0);
       }
     }
-    accumulate_vec<DT>(acc, a, b);
+    accumulate_vec<DT, kUnroll>(acc, a, b);
   }
   for (uint32_t j = nvec * EPV + lane; j < len; j += G) accumulate_elem<DT>(acc, xb, cb, j);
   return acc;

@@ -79,7 +79,7 @@ void launch_finish(int32_t dtype, const void* partial, uint32_t n_partial, scar_
 // The store is cut into ranges of `range_elems` consecutive elements, one workgroup each
 // (at most kVarMaxGrid of them); a range is a whole number of 4,096-element chunks.
 constexpr uint32_t kVarChunk = 4096;
-constexpr uint32_t kVarMaxGrid = 32768;
+constexpr uint32_t kVarMaxGrid = 65536;
 
 struct VarGeometry {
   uint64_t range_elems;
@@ -94,10 +94,14 @@ inline VarGeometry var_geometry(uint64_t n_elems) {
   return {range, (uint32_t)((n_elems + range - 1) / range)};
 }
 
-// Workspace of the variable-length calls: [0, 8 * (kVarMaxGrid + n_blocks)) partial sums,
+// Workspace of the variable-length calls: per range its first block (4 bytes) and whether
+// it holds a chosen block (1 byte); then 8 * (kVarMaxGrid + n_blocks) bytes of partial sums;
 // then one selection byte per block.
+constexpr size_t kVarPlanFirstBytes = 4 * (size_t)kVarMaxGrid;
+constexpr size_t kVarPlanAnyOffset = kVarPlanFirstBytes;
+constexpr size_t kVarPartialOffset = kVarPlanAnyOffset + kVarMaxGrid;
 inline size_t var_mask_offset(uint64_t n_blocks) {
-  return ((8 * ((size_t)kVarMaxGrid + n_blocks) + 255) / 256) * 256;
+  return kVarPartialOffset + ((8 * ((size_t)kVarMaxGrid + n_blocks) + 255) / 256) * 256;
 }
 inline size_t var_workspace_bytes_for(uint64_t n_blocks) {
   return var_mask_offset(n_blocks) + ((n_blocks + 255) / 256) * 256 + 256;

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kWG) void k_recover(char* __restrict__ x, const cha
           xv[u] = make_uint4(0, 0, 0, 0);
         }
       }
-      if (NORM) accumulate_vec<DT>(acc, cv, xv);
+      if (NORM) accumulate_vec<DT, kUnroll>(acc, cv, xv);
       if (STORE) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {

@@ -5,9 +5,10 @@
 // Block b is the element range [offsets[b], offsets[b+1]).  Sizes can differ by orders of
 // magnitude (a 3-million-element matrix next to a 10-element bias), so work is not dealt
 // out by block but by position: the store is cut into equal ranges of consecutive
-// elements, one workgroup per range.  A workgroup finds the block that holds its first
-// element (a 256-way search over the offsets), then walks forward through its range,
-// segment by segment, where a segment is the part of one block that lies inside the range.
+// elements, one workgroup per range.  A small planning kernel finds, for every range, the
+// block that holds its first element (binary search over the offsets) and whether the range
+// touches a chosen block at all; a workgroup then walks forward through its range, segment
+// by segment, where a segment is the part of one block that lies inside the range.
 //
 //   scores:  the workgroup's sum for block b goes to partial[w + b] (w = range number).
 //            Along the store either w or b grows from one (range, block) pair to the next,
@@ -15,7 +16,10 @@
 //            kernel adds each block's slots in a fixed order.  A giant block is thus summed
 //            by as many workgroups as it spans, a run of tiny blocks by one.
 //   commit / recover / norm:  a byte per block marks the chosen ones; every workgroup
-//            handles the chosen segments of its range and skips the rest.
+//            handles the chosen segments of its range and skips the rest (ranges without a
+//            chosen block leave at once).  Here ranges go to the XCDs round-robin, because a
+//            chosen tensor is one contiguous stretch and must not land on a single XCD; the
+//            dense score walk gives each XCD a contiguous eighth instead.
 //
 // Segments start wherever a block starts, so each is split into a few leading elements up
 // to the next 16-byte boundary, a body of non-temporal 16-byte accesses, and a tail.
@@ -24,32 +28,36 @@
 
 namespace scar {
 
-// Sum of a 0/1 flag over the workgroup, in every thread.
-__device__ __forceinline__ uint32_t workgroup_count(bool flag, uint32_t* slots) {
-  return workgroup_sum<uint32_t>(flag ? 1u : 0u, slots);
-}
-
-// The block that holds element e: offsets[b] <= e < offsets[b+1].  All threads of the
-// workgroup take part and get the same answer.  Needs offsets[0] <= e < offsets[n_blocks];
-// whatever the offsets hold, the result is below n_blocks.
-__device__ __forceinline__ uint32_t find_block(const uint64_t* __restrict__ off, uint32_t n_blocks,
-                                               uint64_t e, uint32_t* slots) {
+// One thread per range: first[w] = the block that holds the range's first element
+// (offsets[b] <= e < offsets[b+1]); any[w] = 1 if a block with mask != 0 reaches into the
+// range (always 1 without a mask).  Whatever the offsets hold, first[w] < n_blocks.
+__global__ __launch_bounds__(kWG) void k_var_plan(const uint64_t* __restrict__ off, uint32_t n_blocks,
+                                                  uint64_t n_elems, uint64_t range_elems, uint32_t n_wg,
+                                                  const uint8_t* __restrict__ mask,
+                                                  uint32_t* __restrict__ first, uint8_t* __restrict__ any) {
+  const uint32_t w = blockIdx.x * kWG + threadIdx.x;
+  if (w >= n_wg) return;
+  const uint64_t e0 = (uint64_t)w * range_elems;
+  const uint64_t e1 = e0 + range_elems < n_elems ? e0 + range_elems : n_elems;
   uint32_t lo = 0, hi = n_blocks;
   while (hi - lo > 1) {
-    const uint32_t span = hi - lo;
-    if (span <= kWG) {  // one probe per candidate: the last one not above e wins
-      const bool le = threadIdx.x < span && off[lo + threadIdx.x] <= e;
-      const uint32_t cnt = workgroup_count(le, slots);
-      return lo + (cnt ? cnt - 1 : 0);
-    }
-    const uint32_t p = lo + (uint32_t)(((uint64_t)(threadIdx.x + 1) * span) / (kWG + 1));
-    const uint32_t cnt = workgroup_count(off[p] <= e, slots);
-    const uint32_t nlo = cnt ? lo + (uint32_t)(((uint64_t)cnt * span) / (kWG + 1)) : lo;
-    const uint32_t nhi = cnt < kWG ? lo + (uint32_t)(((uint64_t)(cnt + 1) * span) / (kWG + 1)) : hi;
-    lo = nlo;
-    hi = nhi;
+    const uint32_t mid = lo + (hi - lo) / 2;
+    if (off[mid] <= e0)
+      lo = mid;
+    else
+      hi = mid;
   }
-  return lo;
+  first[w] = lo;
+  uint8_t hit = mask ? 0 : 1;
+  if (mask) {
+    for (uint32_t b = lo; b < n_blocks && off[b] < e1; ++b) {
+      if (mask[b] && off[b + 1] > off[b] && off[b + 1] > e0) {
+        hit = 1;
+        break;
+      }
+    }
+  }
+  any[w] = hit;
 }
 
 enum : int { COPY_NONE = 0, COPY_X_TO_C = 1, COPY_C_TO_X = 2 };
@@ -80,19 +88,21 @@ __device__ __forceinline__ void segment_apply(char* __restrict__ x, char* __rest
   const uint64_t nvec = (len - head) / EPV;
   uint4* xv = (uint4*)(xs + head * E);
   uint4* cv = (uint4*)(cs + head * E);
-  for (uint64_t v0 = 0; v0 < nvec; v0 += (uint64_t)kWG * kUnroll) {
-    uint4 a[kUnroll], b[kUnroll];
+  // a pure read keeps four loads per lane and stream in flight; copies do best with fewer
+  constexpr int U = COPY == COPY_NONE ? kUnroll : 2;
+  for (uint64_t v0 = 0; v0 < nvec; v0 += (uint64_t)kWG * U) {
+    uint4 a[U], b[U];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
+    for (int u = 0; u < U; ++u) {
       const uint64_t v = v0 + (uint64_t)u * kWG + threadIdx.x;
       const bool ok = v < nvec;
       a[u] = (ok && (ACC || COPY == COPY_X_TO_C)) ? load_stream(xv + v) : make_uint4(0, 0, 0, 0);
       b[u] = (ok && (ACC || COPY == COPY_C_TO_X)) ? load_stream(cv + v) : make_uint4(0, 0, 0, 0);
     }
-    if (ACC) accumulate_vec<DT>(acc, b, a);
+    if (ACC) accumulate_vec<DT, U>(acc, b, a);
     if (COPY != COPY_NONE) {
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u) {
+      for (int u = 0; u < U; ++u) {
         const uint64_t v = v0 + (uint64_t)u * kWG + threadIdx.x;
         if (v < nvec) {
           if (COPY == COPY_X_TO_C) store_stream(cv + v, a[u]);
@@ -113,16 +123,21 @@ __global__ __launch_bounds__(kWG) void k_var_walk(char* __restrict__ x, char* __
                                                   const uint64_t* __restrict__ off, uint32_t n_blocks,
                                                   uint64_t n_elems, uint64_t range_elems, uint32_t n_wg,
                                                   const uint8_t* __restrict__ mask,
+                                                  const uint32_t* __restrict__ first,
+                                                  const uint8_t* __restrict__ any,
                                                   typename Acc<DT>::type* __restrict__ partial,
                                                   bool base_aligned) {
   using acc_t = typename Acc<DT>::type;
   __shared__ acc_t slots[kWG / kWave];
-  __shared__ uint32_t count_slots[kWG / kWave];
-  const uint32_t w = xcd_contiguous_block_id();
+  const uint32_t w = PER_BLOCK ? xcd_contiguous_block_id() : blockIdx.x;
   if (w >= n_wg) return;
+  if (!PER_BLOCK && !any[w]) {  // nothing chosen in this range
+    if (ACC && threadIdx.x == 0) partial[w] = 0;
+    return;
+  }
   const uint64_t e0 = (uint64_t)w * range_elems;
   const uint64_t e1 = e0 + range_elems < n_elems ? e0 + range_elems : n_elems;
-  uint32_t cur = find_block(off, n_blocks, e0, count_slots);
+  uint32_t cur = first[w];
   acc_t acc = 0;
   uint64_t pos = e0;
   while (pos < e1) {
@@ -207,28 +222,34 @@ static int check_var_workspace(const void* ws, size_t bytes, uint64_t n_blocks) 
 
 template <int DT, bool ACC, int COPY, bool PER_BLOCK>
 static void launch_walk(const scar_var_layout* l, const void* x, const void* c, const uint8_t* mask,
-                        void* partial, const VarGeometry& g, hipStream_t st) {
+                        void* workspace, const VarGeometry& g, hipStream_t st) {
   const bool base_aligned = aligned(x, 16) && aligned(c, 16);
+  uint32_t* first = (uint32_t*)workspace;
+  uint8_t* any = (uint8_t*)workspace + kVarPlanAnyOffset;
+  void* partial = (char*)workspace + kVarPartialOffset;
+  hipLaunchKernelGGL(k_var_plan, dim3((g.n_wg + kWG - 1) / kWG), dim3(kWG), 0, st, l->offsets, l->n_blocks,
+                     l->n_elems, g.range_elems, g.n_wg, mask, first, any);
   hipLaunchKernelGGL((k_var_walk<DT, ACC, COPY, PER_BLOCK>), dim3(xcd_grid(g.n_wg, kVarMaxGrid)), dim3(kWG),
                      0, st, (char*)const_cast<void*>(x), (char*)const_cast<void*>(c), l->offsets,
-                     l->n_blocks, l->n_elems, g.range_elems, g.n_wg, mask,
-                     (typename Acc<DT>::type*)partial, base_aligned);
+                     l->n_blocks, l->n_elems, g.range_elems, g.n_wg, mask, (const uint32_t*)first,
+                     (const uint8_t*)any, (typename Acc<DT>::type*)partial, base_aligned);
 }
 
 template <bool ACC, int COPY, bool PER_BLOCK>
 static void dispatch_walk(const scar_var_layout* l, const void* x, const void* c, const uint8_t* mask,
-                          void* partial, const VarGeometry& g, hipStream_t st) {
+                          void* workspace, const VarGeometry& g, hipStream_t st) {
   switch (l->dtype) {
-    case SCAR_F32: launch_walk<DT_F32, ACC, COPY, PER_BLOCK>(l, x, c, mask, partial, g, st); break;
-    case SCAR_BF16: launch_walk<DT_BF16, ACC, COPY, PER_BLOCK>(l, x, c, mask, partial, g, st); break;
-    default: launch_walk<DT_I32, ACC, COPY, PER_BLOCK>(l, x, c, mask, partial, g, st); break;
+    case SCAR_F32: launch_walk<DT_F32, ACC, COPY, PER_BLOCK>(l, x, c, mask, workspace, g, st); break;
+    case SCAR_BF16: launch_walk<DT_BF16, ACC, COPY, PER_BLOCK>(l, x, c, mask, workspace, g, st); break;
+    default: launch_walk<DT_I32, ACC, COPY, PER_BLOCK>(l, x, c, mask, workspace, g, st); break;
   }
 }
 
 template <int DT>
-static void launch_scores_finish(const scar_var_layout* l, const void* partial, const VarGeometry& g,
+static void launch_scores_finish(const scar_var_layout* l, const void* workspace, const VarGeometry& g,
                                  void* scores, hipStream_t st) {
   using acc_t = typename Acc<DT>::type;
+  const void* partial = (const char*)workspace + kVarPartialOffset;
   if (l->n_blocks <= 16384) {  // few blocks, possibly huge: a whole workgroup adds each one's slots
     hipLaunchKernelGGL((k_var_scores_finish<DT, kWG>), dim3(l->n_blocks), dim3(kWG), 0, st,
                        (const acc_t*)partial, l->offsets, l->n_blocks, l->n_elems, g.range_elems, scores);
@@ -265,7 +286,7 @@ static int var_rows(int copy, const scar_var_layout* layout, const void* x, cons
   const bool nothing = nb == 0 || layout->n_elems == 0 || (!all_blocks && n_idx == 0);
   if (nothing) {
     if (norm_out) {
-      launch_finish(layout->dtype, workspace, 0, norm_out, st);
+      launch_finish(layout->dtype, (char*)workspace + kVarPartialOffset, 0, norm_out, st);
       return launch_status();
     }
     return SCAR_OK;
@@ -276,14 +297,15 @@ static int var_rows(int copy, const scar_var_layout* layout, const void* x, cons
   const VarGeometry g = var_geometry(layout->n_elems);
   const uint8_t* mask = all_blocks ? nullptr : mark_blocks(layout, idx, n_idx, workspace, st);
   if (copy == COPY_X_TO_C)
-    dispatch_walk<false, COPY_X_TO_C, false>(layout, x, c, mask, nullptr, g, st);
+    dispatch_walk<false, COPY_X_TO_C, false>(layout, x, c, mask, workspace, g, st);
   else if (copy == COPY_C_TO_X && norm_out)
     dispatch_walk<true, COPY_C_TO_X, false>(layout, x, c, mask, workspace, g, st);
   else if (copy == COPY_C_TO_X)
-    dispatch_walk<false, COPY_C_TO_X, false>(layout, x, c, mask, nullptr, g, st);
+    dispatch_walk<false, COPY_C_TO_X, false>(layout, x, c, mask, workspace, g, st);
   else
     dispatch_walk<true, COPY_NONE, false>(layout, x, c, mask, workspace, g, st);
-  if (norm_out) launch_finish(layout->dtype, workspace, g.n_wg, norm_out, st);
+  if (norm_out)
+    launch_finish(layout->dtype, (char*)workspace + kVarPartialOffset, g.n_wg, norm_out, st);
   return launch_status();
 }
 
