@@ -79,8 +79,18 @@ def main():
     ap.add_argument("--iters", type=int, default=48)
     ap.add_argument("--period", type=int, default=8)
     ap.add_argument("--lost-fraction", type=float, default=0.5)
+    ap.add_argument("--contraction", type=float, default=None,
+                    help="contraction factor c of the training update: also print Theorem 3.1's bound")
+    ap.add_argument("--dist0", type=float, default=100.0, help="||x(0) - x*|| for the bound")
+    ap.add_argument("--fail-at", type=int, default=50, help="iteration of the failure for the bound")
     args = ap.parse_args()
-    print(json.dumps(run(args.blocks, args.block_len, args.iters, args.period, args.lost_fraction)))
+    res = run(args.blocks, args.block_len, args.iters, args.period, args.lost_fraction)
+    if args.contraction is not None:
+        from . import bound
+        res["iteration_cost_bound"] = {
+            name: bound.iteration_cost_bound([norm], args.contraction, args.dist0, args.fail_at)
+            for name, norm in res["mean_perturbation_norm"].items()}
+    print(json.dumps(res))
 
 
 if __name__ == "__main__":
