@@ -11,8 +11,10 @@ import numpy as np
 
 from . import build as _build
 
-F32, BF16, I32 = 0, 1, 2
+F32, BF16, I32, F32_BF16C = 0, 1, 2, 3
 _NP_OF = {F32: np.float32, BF16: np.uint16, I32: np.int32}
+_X_OF = {F32: F32, BF16: BF16, I32: I32, F32_BF16C: F32}      # element type of x per store type
+_C_OF = {F32: F32, BF16: BF16, I32: I32, F32_BF16C: BF16}     # element type of c per store type
 
 
 class Norm(ctypes.Structure):
@@ -69,6 +71,14 @@ def _check(rc, what):
         raise OracleError("%s failed with status %d" % (what, rc))
 
 
+def _flat_x(a, dtype):
+    return _flat(a, _X_OF[dtype])
+
+
+def _flat_c(a, dtype):
+    return _flat(a, _C_OF[dtype])
+
+
 def _flat(a, dtype):
     a = np.asarray(a)
     if a.dtype != _NP_OF[dtype]:
@@ -95,7 +105,7 @@ def n_blocks_of(n_elems: int, block_len: int) -> int:
 
 def block_scores(dtype, x, c, block_len):
     """Distance of every block of x from c: float64 squared-L2 (float data) or int64 L1."""
-    x, c = _flat(x, dtype), _flat(c, dtype)
+    x, c = _flat_x(x, dtype), _flat_c(c, dtype)
     assert x.size == c.size
     nb = n_blocks_of(x.size, block_len)
     out = np.zeros(nb, dtype=np.int64 if dtype == I32 else np.float64)
@@ -136,9 +146,9 @@ def brute_force_topk(scores, k):
 
 def checkpoint_commit(dtype, x, c, block_len, idx, staging=None):
     """c[b] <- x[b] for b in idx, in place on c; optional packed staging rows."""
-    x, c = _flat(x, dtype), _flat(c, dtype)
+    x, c = _flat_x(x, dtype), _flat_c(c, dtype)
     idx = _idx(idx)
-    st = _flat(staging, dtype) if staging is not None else None
+    st = _flat_c(staging, dtype) if staging is not None else None
     if st is not None:
         assert st.size >= idx.size * block_len
     _check(lib().oracle_checkpoint_commit(dtype, _ptr(x), _ptr(c), x.size, block_len, _ptr(idx),
@@ -147,7 +157,7 @@ def checkpoint_commit(dtype, x, c, block_len, idx, staging=None):
 
 def perturbation_norm(dtype, x, c, block_len, idx=None):
     """(sum, norm, isum) of c - x over the blocks in idx (None = all blocks)."""
-    x, c = _flat(x, dtype), _flat(c, dtype)
+    x, c = _flat_x(x, dtype), _flat_c(c, dtype)
     idx = _idx(idx)
     out = Norm()
     if idx is None:
@@ -165,7 +175,7 @@ def perturbation_norm(dtype, x, c, block_len, idx=None):
 
 def partial_recover(dtype, x, c, block_len, lost, want_norm=True):
     """x[b] <- c[b] for b in lost, in place on x; returns (sum, norm, isum) or None."""
-    x, c = _flat(x, dtype), _flat(c, dtype)
+    x, c = _flat_x(x, dtype), _flat_c(c, dtype)
     lost = _idx(lost)
     out = Norm()
     _check(lib().oracle_partial_recover(dtype, _ptr(x), _ptr(c), x.size, block_len, _ptr(lost),
@@ -212,7 +222,7 @@ def _offsets(offsets):
 
 
 def var_block_scores(dtype, x, c, offsets):
-    x, c, off = _flat(x, dtype), _flat(c, dtype), _offsets(offsets)
+    x, c, off = _flat_x(x, dtype), _flat_c(c, dtype), _offsets(offsets)
     nb = off.size - 1
     out = np.zeros(nb, dtype=np.int64 if dtype == I32 else np.float64)
     _check(lib().oracle_var_block_scores(dtype, _ptr(x), _ptr(c), _ptr(off), nb, _ptr(out)),
@@ -221,13 +231,13 @@ def var_block_scores(dtype, x, c, offsets):
 
 
 def var_checkpoint_commit(dtype, x, c, offsets, idx):
-    x, c, off, idx = _flat(x, dtype), _flat(c, dtype), _offsets(offsets), _idx(idx)
+    x, c, off, idx = _flat_x(x, dtype), _flat_c(c, dtype), _offsets(offsets), _idx(idx)
     _check(lib().oracle_var_checkpoint_commit(dtype, _ptr(x), _ptr(c), _ptr(off), off.size - 1,
                                               _ptr(idx), idx.size), "oracle_var_checkpoint_commit")
 
 
 def var_perturbation_norm(dtype, x, c, offsets, idx=None):
-    x, c, off = _flat(x, dtype), _flat(c, dtype), _offsets(offsets)
+    x, c, off = _flat_x(x, dtype), _flat_c(c, dtype), _offsets(offsets)
     out = Norm()
     if idx is None:
         ptr, n = ctypes.c_void_p(0), 0
@@ -241,7 +251,7 @@ def var_perturbation_norm(dtype, x, c, offsets, idx=None):
 
 
 def var_partial_recover(dtype, x, c, offsets, lost):
-    x, c, off, lost = _flat(x, dtype), _flat(c, dtype), _offsets(offsets), _idx(lost)
+    x, c, off, lost = _flat_x(x, dtype), _flat_c(c, dtype), _offsets(offsets), _idx(lost)
     out = Norm()
     _check(lib().oracle_var_partial_recover(dtype, _ptr(x), _ptr(c), _ptr(off), off.size - 1,
                                             _ptr(lost), lost.size, ctypes.byref(out)),

@@ -26,7 +26,9 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_I32 = 2 };
+/* ORACLE_F32_BF16C: x is float32 and the checkpoint c is kept in bfloat16 (a reduced-
+ * precision checkpoint, Example 2.1): saving rounds to nearest even, restoring widens. */
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_I32 = 2, ORACLE_F32_BF16C = 3 };
 enum { ORACLE_OK = 0, ORACLE_ERR_ARG = -1, ORACLE_ERR_INDEX = -2, ORACLE_ERR_NOMEM = -3 };
 
 typedef struct {
@@ -47,10 +49,25 @@ int oracle_get_num_threads(void) {
 #endif
 }
 
-static size_t elem_size(int dtype) { return dtype == ORACLE_BF16 ? 2 : 4; }
+/* Element types of x and of c for a store type. */
+static int x_type(int dtype) { return dtype == ORACLE_F32_BF16C ? ORACLE_F32 : dtype; }
+static int c_type(int dtype) { return dtype == ORACLE_F32_BF16C ? ORACLE_BF16 : dtype; }
+static size_t elem_size(int type) { return type == ORACLE_BF16 ? 2 : 4; }
 
 static int dtype_ok(int dtype) {
-  return dtype == ORACLE_F32 || dtype == ORACLE_BF16 || dtype == ORACLE_I32;
+  return dtype == ORACLE_F32 || dtype == ORACLE_BF16 || dtype == ORACLE_I32 ||
+         dtype == ORACLE_F32_BF16C;
+}
+
+/* float32 -> bfloat16, round to nearest, ties to even (IEEE 754 roundTiesToEven on the
+ * 8-bit significand); NaN stays NaN (quiet), overflow rounds to infinity. */
+static uint16_t round_to_bf16(float f) {
+  uint32_t u;
+  memcpy(&u, &f, sizeof u);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+  uint32_t keep = u >> 16, rest = u & 0xffffu;
+  if (rest > 0x8000u || (rest == 0x8000u && (keep & 1u))) keep += 1;
+  return (uint16_t)keep;
 }
 
 static uint64_t count_blocks(uint64_t n_elems, uint32_t block_len) {
@@ -81,7 +98,7 @@ static void block_range(uint64_t b, uint64_t n_elems, uint32_t block_len, uint64
 static double block_sqdist(int dtype, const void *x, const void *c, uint64_t lo, uint64_t hi) {
   double s = 0.0;
   for (uint64_t j = lo; j < hi; ++j) {
-    double d = load_real(dtype, x, j) - load_real(dtype, c, j);
+    double d = load_real(x_type(dtype), x, j) - load_real(c_type(dtype), c, j);
     s += d * d;
   }
   return s;
@@ -232,14 +249,18 @@ int oracle_checkpoint_commit(int dtype, const void *x, void *c, uint64_t n_elems
   if (!x || !c) return ORACLE_ERR_ARG;
   int rc = check_indices(idx, n_idx, count_blocks(n_elems, block_len));
   if (rc) return rc;
-  size_t es = elem_size(dtype);
+  size_t es = elem_size(c_type(dtype));
 #pragma omp parallel for schedule(static) num_threads(g_threads)
   for (int64_t i = 0; i < (int64_t)n_idx; ++i) {
     uint64_t lo, hi;
     block_range(idx[i], n_elems, block_len, &lo, &hi);
-    memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo) * es);
-    if (staging)
-      memcpy((char *)staging + (uint64_t)i * block_len * es, (const char *)x + lo * es,
+    if (dtype == ORACLE_F32_BF16C) { /* what is saved is x rounded to the checkpoint's precision */
+      for (uint64_t j = lo; j < hi; ++j) ((uint16_t *)c)[j] = round_to_bf16(((const float *)x)[j]);
+    } else {
+      memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo) * es);
+    }
+    if (staging) /* the saved rows, in the checkpoint's element type */
+      memcpy((char *)staging + (uint64_t)i * block_len * es, (const char *)c + lo * es,
              (hi - lo) * es);
   }
   return ORACLE_OK;
@@ -278,7 +299,7 @@ int oracle_perturbation_norm(int dtype, const void *x, const void *c, uint64_t n
     if (dtype == ORACLE_I32)
       ipart[i] = block_l1((const int32_t *)c, (const int32_t *)x, lo, hi);
     else
-      fpart[i] = block_sqdist(dtype, c, x, lo, hi);
+      fpart[i] = block_sqdist(dtype, x, c, lo, hi);
   }
   double fs = 0.0;
   int64_t is = 0;
@@ -319,12 +340,16 @@ int oracle_partial_recover(int dtype, void *x, const void *c, uint64_t n_elems,
   if (!x || !c) return ORACLE_ERR_ARG;
   int rc = check_indices(lost, n_lost, count_blocks(n_elems, block_len));
   if (rc) return rc;
-  size_t es = elem_size(dtype);
+  size_t es = elem_size(x_type(dtype));
 #pragma omp parallel for schedule(static) num_threads(g_threads)
   for (int64_t i = 0; i < (int64_t)n_lost; ++i) {
     uint64_t lo, hi;
     block_range(lost[i], n_elems, block_len, &lo, &hi);
-    memcpy((char *)x + lo * es, (const char *)c + lo * es, (hi - lo) * es);
+    if (dtype == ORACLE_F32_BF16C) {
+      for (uint64_t j = lo; j < hi; ++j) ((float *)x)[j] = (float)load_real(ORACLE_BF16, c, j);
+    } else {
+      memcpy((char *)x + lo * es, (const char *)c + lo * es, (hi - lo) * es);
+    }
   }
   return ORACLE_OK;
 }
@@ -413,7 +438,7 @@ static int offsets_ok(const uint64_t *offsets, uint32_t n_blocks) {
 
 int oracle_var_block_scores(int dtype, const void *x, const void *c, const uint64_t *offsets,
                             uint32_t n_blocks, void *scores) {
-  if (!dtype_ok(dtype) || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
+  if (!dtype_ok(dtype) || dtype == ORACLE_F32_BF16C || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
   if (n_blocks == 0) return ORACLE_OK;
   if (!scores || (offsets[n_blocks] && (!x || !c))) return ORACLE_ERR_ARG;
 #pragma omp parallel for schedule(dynamic, 1) num_threads(g_threads)
@@ -429,7 +454,7 @@ int oracle_var_block_scores(int dtype, const void *x, const void *c, const uint6
 
 int oracle_var_checkpoint_commit(int dtype, const void *x, void *c, const uint64_t *offsets,
                                  uint32_t n_blocks, const uint32_t *idx, uint32_t n_idx) {
-  if (!dtype_ok(dtype) || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
+  if (!dtype_ok(dtype) || dtype == ORACLE_F32_BF16C || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
   if (n_idx == 0) return ORACLE_OK;
   int rc = check_indices(idx, n_idx, n_blocks);
   if (rc) return rc;
@@ -445,7 +470,7 @@ int oracle_var_checkpoint_commit(int dtype, const void *x, void *c, const uint64
 int oracle_var_perturbation_norm(int dtype, const void *x, const void *c, const uint64_t *offsets,
                                  uint32_t n_blocks, const uint32_t *idx, uint32_t n_idx,
                                  oracle_norm *out) {
-  if (!dtype_ok(dtype) || !offsets_ok(offsets, n_blocks) || !out) return ORACLE_ERR_ARG;
+  if (!dtype_ok(dtype) || dtype == ORACLE_F32_BF16C || !offsets_ok(offsets, n_blocks) || !out) return ORACLE_ERR_ARG;
   out->sum = out->norm = 0.0;
   out->isum = 0;
   uint32_t m = idx ? n_idx : n_blocks;
@@ -460,7 +485,7 @@ int oracle_var_perturbation_norm(int dtype, const void *x, const void *c, const 
     if (dtype == ORACLE_I32)
       is += block_l1((const int32_t *)c, (const int32_t *)x, offsets[b], offsets[b + 1]);
     else
-      fs += block_sqdist(dtype, c, x, offsets[b], offsets[b + 1]);
+      fs += block_sqdist(dtype, x, c, offsets[b], offsets[b + 1]);
   }
   if (dtype == ORACLE_I32) {
     out->isum = is;
@@ -475,7 +500,7 @@ int oracle_var_perturbation_norm(int dtype, const void *x, const void *c, const 
 int oracle_var_partial_recover(int dtype, void *x, const void *c, const uint64_t *offsets,
                                uint32_t n_blocks, const uint32_t *lost, uint32_t n_lost,
                                oracle_norm *norm_out) {
-  if (!dtype_ok(dtype) || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
+  if (!dtype_ok(dtype) || dtype == ORACLE_F32_BF16C || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
   oracle_norm zero = {0.0, 0.0, 0};
   if (n_lost == 0) {
     if (norm_out) *norm_out = zero;

@@ -567,3 +567,81 @@ def test_var_commit_and_recover_touch_only_their_blocks():
         oracle.var_checkpoint_commit(F32, x, c, off, [30])
     with pytest.raises(oracle.OracleError):
         oracle.var_block_scores(F32, x, c, np.array([0, 5, 4], dtype=np.uint64))
+
+
+# --------------------------------------------------------------------------- reduced-precision checkpoint
+
+MIX = oracle.F32_BF16C
+
+
+def bf16_of(values):
+    """bfloat16 bit patterns of values that are exactly representable (top 16 bits of the float32)."""
+    bits = np.asarray(values, dtype=np.float32).view(np.uint32)
+    assert np.all(bits & 0xFFFF == 0)
+    return (bits >> 16).astype(np.uint16)
+
+
+def test_mixed_scores_and_norm_hand_worked():
+    x = np.array([1.5, -2.0, 0.75, 3.0], dtype=np.float32)
+    c = bf16_of([1.0, -2.0, 0.25, -1.0])
+    np.testing.assert_array_equal(oracle.block_scores(MIX, x, c, 2), [0.25, 0.25 + 16.0])
+    assert oracle.perturbation_norm(MIX, x, c, 2) == (16.5, math.sqrt(16.5), 0)
+    assert oracle.perturbation_norm(MIX, x, c, 2, [0]) == (0.25, 0.5, 0)
+
+
+def test_mixed_commit_rounds_to_nearest_even_and_recover_widens():
+    # 1 + 2^-8 lies half-way between 1 and 1 + 2^-7: ties go to the even significand (1.0);
+    # 1 + 3*2^-8 is half-way between 1 + 2^-7 (odd) and 1 + 2^-6 (even) -> 1 + 2^-6;
+    # 1 + 2^-8 + 2^-20 is above the half-way point -> 1 + 2^-7; -0.3 -> nearest bfloat16
+    x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, -0.3,
+                  3.0e38, 1e-40, np.inf, 0.0], dtype=np.float32)
+    c = np.zeros(8, dtype=np.uint16)
+    st = np.zeros(8, dtype=np.uint16)
+    oracle.checkpoint_commit(MIX, x, c, 8, [0], st)
+    back = (c.astype(np.uint32) << 16).view(np.float32)
+    np.testing.assert_array_equal(back[:3], np.array([1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7], dtype=np.float32))
+    assert back[3] == np.float32(-0.30078125)
+    assert abs(back[4] - 3.0e38) <= 3.0e38 * 2.0 ** -8 and back[6] == np.inf and back[7] == 0.0
+    np.testing.assert_array_equal(st, c)
+    # second opinion on the rounding from a library conversion
+    import torch
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    np.testing.assert_array_equal(c, ref)
+    nan = np.array([np.nan], dtype=np.float32)
+    cn = np.zeros(1, dtype=np.uint16)
+    oracle.checkpoint_commit(MIX, nan, cn, 1, [0])
+    assert np.isnan((cn.astype(np.uint32) << 16).view(np.float32))[0]
+    # recovery widens exactly
+    x2 = np.zeros(8, dtype=np.float32)
+    oracle.partial_recover(MIX, x2, c, 8, [0])
+    np.testing.assert_array_equal(x2, back)
+
+
+def test_mixed_rounding_perturbation_obeys_the_reduced_precision_bound():
+    # Example 2.1: storing with a p-bit significand perturbs by less than 2^-(p-1) |y| per
+    # element (p = 8 for bfloat16; round-to-nearest achieves half of that), so right after
+    # saving everything the distance to the checkpoint is at most 2^-8 ||x||.
+    r = rng_of(70)
+    x = (r.normal(size=5000) * 10.0 ** r.uniform(-3, 3, size=5000)).astype(np.float32)
+    c = np.zeros(5000, dtype=np.uint16)
+    oracle.checkpoint_commit(MIX, x, c, 50, np.arange(100))
+    back = (c.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    assert np.all(np.abs(back - x) <= np.abs(x.astype(np.float64)) * 2.0 ** -8)
+    s, nrm, _ = oracle.perturbation_norm(MIX, x, c, 50)
+    assert 0 < nrm <= 2.0 ** -8 * float(np.linalg.norm(x.astype(np.float64)))
+    scores = oracle.block_scores(MIX, x, c, 50)
+    assert math.isclose(scores.sum(), s, rel_tol=1e-12)
+
+
+def test_mixed_equals_float_store_when_values_are_representable():
+    r = rng_of(71)
+    cf = (r.integers(-64, 64, size=300) / 8.0).astype(np.float32)      # exact in bfloat16
+    xf = (cf + r.integers(-8, 8, size=300) / 4.0).astype(np.float32)
+    cb = bf16_of(cf)
+    np.testing.assert_array_equal(oracle.block_scores(MIX, xf, cb, 7), oracle.block_scores(F32, xf, cf, 7))
+    assert oracle.perturbation_norm(MIX, xf, cb, 7, [1, 5]) == oracle.perturbation_norm(F32, xf, cf, 7, [1, 5])
+    x1, x2 = xf.copy(), xf.copy()
+    assert oracle.partial_recover(MIX, x1, cb, 7, [0, 42]) == oracle.partial_recover(F32, x2, cf, 7, [0, 42])
+    np.testing.assert_array_equal(x1, x2)
+    with pytest.raises(oracle.OracleError):
+        oracle.var_block_scores(MIX, xf, cb, np.array([0, 300], dtype=np.uint64))
