@@ -29,15 +29,14 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
 
-def algorithmic_bytes(n_elems, block_len, ebytes, score_bytes, k, n_lost, select_passes):
+def algorithmic_bytes(n_elems, block_len, xbytes, cbytes, score_bytes, k, n_lost, select_passes):
     """Bytes one cycle has to move, by step (what the method itself needs, not what a
-    particular kernel fetches)."""
+    particular kernel fetches).  xbytes / cbytes: element sizes of x and of the checkpoint."""
     nb = (n_elems + block_len - 1) // block_len
-    row = block_len * ebytes
-    scores = 2 * n_elems * ebytes + nb * score_bytes
+    scores = n_elems * (xbytes + cbytes) + nb * score_bytes
     select = select_passes * nb * score_bytes + 4 * k
-    commit = 2 * k * row + 4 * k
-    recover = 3 * n_lost * row + 4 * n_lost
+    commit = k * block_len * (xbytes + cbytes) + 4 * k
+    recover = n_lost * block_len * (cbytes + 2 * xbytes) + 4 * n_lost
     return {"scores": scores, "select": select, "commit": commit, "recover": recover,
             "total": scores + select + commit + recover}
 
@@ -84,12 +83,14 @@ def make_workload(name, dev):
             return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
         return torch.from_numpy(a).to(dev)
 
-    if name in ("flat_f32", "flat_bf16"):
+    if name in ("flat_f32", "flat_bf16", "flat_mixed"):
         n_elems, L, seed = 1 << 30, 1024, 4
         x, c = wl.flat_like_torch(dev, seed=seed, n_elems=n_elems)
         nb = n_elems // L
         if name == "flat_bf16":
             x, c = x.to(torch.bfloat16), c.to(torch.bfloat16)
+        elif name == "flat_mixed":
+            c = c.to(torch.bfloat16)
         k, n_lost = wl.k_of_fraction(0.10, nb), nb // 8
 
         def lost_of(cycle):
@@ -105,7 +106,7 @@ def make_workload(name, dev):
                 wl.drift_torch(f, seed + 5000 + cycle, 1.0, L)
                 x[lo:lo + m] = f.to(torch.bfloat16)
         label = "flat store 2^30 x %s, 1024-element blocks, k=10%%, lost=1/8" % (
-            "bf16" if name == "flat_bf16" else "fp32")
+            {"flat_bf16": "bf16", "flat_f32": "fp32", "flat_mixed": "fp32 with a bf16 checkpoint"}[name])
         return x, c, L, k, n_lost, lost_of, drift, label
 
     gens = {"mlr": wl.mlr_like, "mf": wl.mf_like, "lda": wl.lda_like, "cnn": wl.cnn_like}
@@ -143,6 +144,8 @@ def cpu_baseline(x, c, L, k_frac, lost_frac, sample_elems, threads):
         return t.cpu().numpy()
 
     dt = {torch.float32: wl.F32, torch.bfloat16: wl.BF16, torch.int32: wl.I32}[x.dtype]
+    if x.dtype == torch.float32 and c.dtype == torch.bfloat16:
+        dt = wl.F32_BF16C
     hx, hc = down(x), down(c)
     nb = (sample_elems + L - 1) // L
     k = wl.k_of_fraction(k_frac, nb)
@@ -153,12 +156,12 @@ def cpu_baseline(x, c, L, k_frac, lost_frac, sample_elems, threads):
         ts = []
         for rep in range(reps):
             lost = wl.random_lost_blocks(nb, n_lost, 77 + rep)
-            x1 = hx.copy()
+            x1, c1 = hx.copy(), hc.copy()
             t0 = time.perf_counter()
-            s = oracle.block_scores(dt, x1, hc, L)
+            s = oracle.block_scores(dt, x1, c1, L)
             idx = oracle.select_topk(s, k)
-            oracle.checkpoint_commit(dt, x1, hc, L, idx)
-            oracle.partial_recover(dt, x1, hc, L, lost)
+            oracle.checkpoint_commit(dt, x1, c1, L, idx)
+            oracle.partial_recover(dt, x1, c1, L, lost)
             ts.append(time.perf_counter() - t0)
         times[label] = statistics.median(ts)
     oracle.set_num_threads(1)
@@ -248,7 +251,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="flat_f32",
-                    choices=["flat_f32", "flat_bf16", "mlr", "mf", "lda", "cnn", "layers"])
+                    choices=["flat_f32", "flat_bf16", "flat_mixed", "mlr", "mf", "lda", "cnn", "layers"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for HBM counters)")
@@ -279,7 +282,7 @@ def main():
 
     x, c, L, k, n_lost, lost_of, drift, label = make_workload(args.workload, dev)
     n_elems = x.numel()
-    ebytes = x.element_size()
+    xbytes, cbytes = x.element_size(), c.element_size()
     nb = (n_elems + L - 1) // L
     is_int = x.dtype == torch.int32
     score_bytes = 8 if is_int else 4
@@ -297,8 +300,7 @@ def main():
     # enqueues (buffers, sizes and the stream do not change between steps).
     import ctypes
     L_ = scar.lib()
-    lay = scar.Layout({torch.float32: scar.F32, torch.bfloat16: scar.BF16, torch.int32: scar.I32}[x.dtype],
-                      L, n_elems)
+    lay = scar.Layout(scar.store_type(x, c), L, n_elems)
     lay_p = ctypes.byref(lay)
     vp = ctypes.c_void_p
     px, pc, ps, pi, pn, pw = (vp(t.data_ptr()) for t in (x, c, scores, idx, norm, ws))
@@ -352,8 +354,8 @@ def main():
     score_avg_ms = sum(score_ms) / len(score_ms)
 
     passes = 6 if is_int else 3
-    b = algorithmic_bytes(n_elems, L, ebytes, score_bytes, k, n_lost, passes + 2)
-    pbytes = n_elems * ebytes
+    b = algorithmic_bytes(n_elems, L, xbytes, cbytes, score_bytes, k, n_lost, passes + 2)
+    pbytes = n_elems * xbytes
     value = pbytes / (ms_step * 1e-3) / 1e9
     hbm_gbs = b["total"] / (ms_step * 1e-3) / 1e9
     achieved = b["scores"] / (score_avg_ms * 1e-3) / 1e9
@@ -369,7 +371,8 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": {torch.float32: "f32", torch.bfloat16: "bf16", torch.int32: "i32"}[x.dtype],
+        "dtype": {torch.float32: "f32", torch.bfloat16: "bf16", torch.int32: "i32"}[x.dtype]
+                 + ("+bf16c" if cbytes != xbytes else ""),
         "data": "synthetic",
         "config": {"workload": label, "n_elems": n_elems, "block_len": L, "n_blocks": nb, "k": k,
                    "n_lost": n_lost},
@@ -378,7 +381,8 @@ def main():
         "pct_of_hbm_peak": round(100.0 * hbm_gbs / HBM_PEAK_GBS, 2),
         "ms_per_step_events_median": round(statistics.median(cycle_ms), 4),
         "last_norm": scar.read_norm(norm)[1],
-        "roofline": {"bound": "hbm", "kernel": "k_block_scores", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": "k_mixed_scores" if cbytes != xbytes else "k_block_scores",
+                     "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": stored_traffic(args.workload), "avg_ms": round(score_avg_ms, 4),
                      "algorithmic_bytes_per_launch": b["scores"]},

@@ -56,7 +56,12 @@ extern "C" {
 typedef enum {
   SCAR_F32 = 0,  /* IEEE binary32 */
   SCAR_BF16 = 1, /* bfloat16 (upper 16 bits of a binary32), 2 bytes per element */
-  SCAR_I32 = 2   /* signed 32-bit counts (e.g. topic-count tables) */
+  SCAR_I32 = 2,  /* signed 32-bit counts (e.g. topic-count tables) */
+  SCAR_F32_BF16C = 3 /* reduced-precision checkpoint (Example 2.1): x is binary32, c is
+                        bfloat16.  Scores and norms use c widened exactly; a commit stores x
+                        rounded to nearest even (so a freshly saved block keeps a rounding
+                        distance of at most 2^-8 |x| per element); recovery widens c into x.
+                        staging rows are bfloat16.  Fixed-length blocks only. */
 } scar_dtype;
 
 /* Element type of a score array. */

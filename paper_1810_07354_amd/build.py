@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libscar.so")
-SOURCES = ["scar_api.hip", "scar_scores.hip", "scar_select.hip", "scar_rows.hip", "scar_var.hip"]
+SOURCES = ["scar_api.hip", "scar_scores.hip", "scar_select.hip", "scar_rows.hip", "scar_var.hip", "scar_mixed.hip"]
 HEADERS = ["scar_device.hpp", "scar_host.hpp", os.path.join("..", "..", "include", "scar.h")]
 
 # Packed-FP32 instruction selection is switched off for all device code.

@@ -11,7 +11,9 @@ namespace scar {
 
 constexpr uint32_t kMaxBlockLen = 1u << 28;
 
-inline bool dtype_ok(int32_t dt) { return dt == SCAR_F32 || dt == SCAR_BF16 || dt == SCAR_I32; }
+inline bool dtype_ok(int32_t dt) {
+  return dt == SCAR_F32 || dt == SCAR_BF16 || dt == SCAR_I32 || dt == SCAR_F32_BF16C;
+}
 inline int host_elem_bytes(int32_t dt) { return dt == SCAR_BF16 ? 2 : 4; }
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -29,12 +31,15 @@ inline uint64_t layout_blocks(const scar_layout* l) {
 // wants four loads per lane; the row kernels only move data and do best with one
 // (measured on 4 KiB rows: 5.66 TB/s with a whole workgroup per row against 5.33 TB/s with
 // one wavefront per row), and offer every power of two up to 256.
-inline int pick_group(uint32_t block_len, int ebytes, bool vec, int per_lane, bool allow_128) {
-  const uint64_t units = vec ? ((uint64_t)block_len * ebytes + 15) / 16 : block_len;
+inline int pick_group_units(uint64_t units, int per_lane, bool allow_128) {
   const uint64_t want = (units + per_lane - 1) / per_lane;
   int g = 1;
   while (g < 256 && (uint64_t)g < want) g <<= 1;
   return (g == 128 && !allow_128) ? 256 : g;
+}
+inline int pick_group(uint32_t block_len, int ebytes, bool vec, int per_lane, bool allow_128) {
+  const uint64_t units = vec ? ((uint64_t)block_len * ebytes + 15) / 16 : block_len;
+  return pick_group_units(units, per_lane, allow_128);
 }
 
 // ---- workspace layout ---------------------------------------------------------------
@@ -74,6 +79,17 @@ inline uint32_t xcd_grid(uint64_t need, uint64_t cap) {
 // (double, or uint64 for SCAR_I32) in a fixed order and writes *out.
 void launch_finish(int32_t dtype, const void* partial, uint32_t n_partial, scar_norm* out,
                    hipStream_t st);
+
+// ---- reduced-precision checkpoint (SCAR_F32_BF16C: x float32, c bfloat16) ---------------
+// Bodies of the entry points for that store type (defined with its kernels); arguments are
+// as in the entry points and the layout has already been checked.
+int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, const void* c,
+                       void* scores, hipStream_t st);
+int mixed_commit(const scar_layout* l, uint32_t n_blocks, const void* x, void* c, const uint32_t* idx,
+                 uint32_t n_idx, void* staging, hipStream_t st);
+int mixed_recover_or_norm(bool store, const scar_layout* l, uint32_t n_blocks, void* x, const void* c,
+                          const uint32_t* idx, uint32_t n_idx, scar_norm* norm_out, void* partial,
+                          hipStream_t st);
 
 // ---- blocks of unequal length ----------------------------------------------------------
 // The store is cut into ranges of `range_elems` consecutive elements, one workgroup each

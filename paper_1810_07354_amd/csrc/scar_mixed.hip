@@ -1,0 +1,287 @@
+// Reduced-precision checkpoint (store type SCAR_F32_BF16C): the live parameters x are
+// float32, the running checkpoint c is kept in bfloat16 (Example 2.1: a representation with
+// a p-bit significand perturbs every element by less than 2^-(p-1) |y|).  The score scan
+// then reads 6 bytes per parameter instead of 8.
+//
+//   scores / norm:  (x_j - widen(c_j))^2, c widened exactly (bfloat16 is the upper half of
+//                   a float32)
+//   commit:         c_j <- x_j rounded to nearest, ties to even
+//   recovery:       x_j <- widen(c_j)
+//
+// The unit of work is 4 elements: a 16-byte vector of x against 8 bytes of c, so that
+// consecutive lanes touch consecutive addresses in both streams.
+#include "scar_device.hpp"
+#include "scar_host.hpp"
+
+namespace scar {
+
+constexpr int kMixUnit = 4;  // elements per unit: one 16-byte vector of x, 8 bytes of c
+constexpr int kMixU = 4;     // units per lane kept in flight by the read-only kernels
+
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint2 load_stream2(const uint2* p) {
+  const u32x2 r = __builtin_nontemporal_load((const u32x2*)p);
+  return make_uint2(r.x, r.y);
+}
+__device__ __forceinline__ void store_stream2(uint2* p, const uint2& v) {
+  u32x2 r;
+  r.x = v.x, r.y = v.y;
+  __builtin_nontemporal_store(r, (u32x2*)p);
+}
+
+__device__ __forceinline__ float widen_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float widen_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// float32 bits -> bfloat16 bits, round to nearest even; NaN stays a (quiet) NaN.
+__device__ __forceinline__ uint32_t round_bf16(uint32_t u) {
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Sum of squared differences of one unit: xv holds 4 floats, cv the matching 4 bfloat16.
+__device__ __forceinline__ float sqdiff_unit(const uint4& xv, const uint2& cv) {
+  float s = sq(__uint_as_float(xv.x) - widen_lo(cv.x));
+  s += sq(__uint_as_float(xv.y) - widen_hi(cv.x));
+  s += sq(__uint_as_float(xv.z) - widen_lo(cv.y));
+  s += sq(__uint_as_float(xv.w) - widen_hi(cv.y));
+  return s;
+}
+
+__device__ __forceinline__ uint4 widen_unit(const uint2& cv) {
+  return make_uint4(cv.x << 16, cv.x & 0xffff0000u, cv.y << 16, cv.y & 0xffff0000u);
+}
+
+__device__ __forceinline__ uint2 round_unit(const uint4& xv) {
+  return make_uint2(round_bf16(xv.x) | (round_bf16(xv.y) << 16),
+                    round_bf16(xv.z) | (round_bf16(xv.w) << 16));
+}
+
+__device__ __forceinline__ float widen_elem(const uint16_t* c, uint64_t j) {
+  return __uint_as_float((uint32_t)c[j] << 16);
+}
+
+// Squared distance of one block (len elements at xb / cb), this lane's share.
+template <int G>
+__device__ __forceinline__ double mixed_distance(const float* xb, const uint16_t* cb, uint32_t len,
+                                                 int lane, bool vec) {
+  double acc = 0;
+  const uint32_t nunit = vec ? len / kMixUnit : 0;
+  const uint4* xv = (const uint4*)xb;
+  const uint2* cv = (const uint2*)cb;
+  for (uint32_t u0 = 0; u0 < nunit; u0 += G * kMixU) {
+    uint4 a[kMixU];
+    uint2 b[kMixU];
+#pragma unroll
+    for (int u = 0; u < kMixU; ++u) {
+      const uint32_t i = u0 + u * G + lane;
+      if (i < nunit) {
+        a[u] = load_stream(xv + i);
+        b[u] = load_stream2(cv + i);
+      } else {
+        a[u] = make_uint4(0, 0, 0, 0);
+        b[u] = make_uint2(0, 0);
+      }
+    }
+    float part = 0.f;
+#pragma unroll
+    for (int u = 0; u < kMixU; ++u) part += sqdiff_unit(a[u], b[u]);
+    acc += (double)part;
+  }
+  for (uint32_t j = nunit * kMixUnit + lane; j < len; j += G) acc += (double)sq(xb[j] - widen_elem(cb, j));
+  return acc;
+}
+
+template <int G>
+__global__ __launch_bounds__(kWG) void k_mixed_scores(const float* __restrict__ x,
+                                                      const uint16_t* __restrict__ c,
+                                                      float* __restrict__ scores, uint64_t n_elems,
+                                                      uint32_t block_len, uint32_t n_blocks, bool vec) {
+  constexpr int GPW = (G == 256) ? 1 : kWG / G;
+  const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
+  const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
+  __shared__ double slots[kWG / kWave];
+  for (uint64_t b = (uint64_t)xcd_contiguous_block_id() * GPW + grp; b < n_blocks;
+       b += (uint64_t)gridDim.x * GPW) {
+    const BlockSpan sp = block_span(b, n_elems, block_len, 1);  // byte_off = element offset
+    double acc = mixed_distance<G>(x + sp.byte_off, c + sp.byte_off, sp.len, lane, vec);
+    if constexpr (G == 256)
+      acc = workgroup_sum(acc, slots);
+    else
+      acc = group_sum<G>(acc);
+    if (lane == 0) scores[b] = (float)acc;
+  }
+}
+
+// c_b <- round(x_b) (and staging row i <- the same bfloat16 values) for b = idx[i].
+template <int G>
+__global__ __launch_bounds__(kWG) void k_mixed_commit(const float* __restrict__ x, uint16_t* __restrict__ c,
+                                                      const uint32_t* __restrict__ idx, uint32_t n_idx,
+                                                      uint16_t* __restrict__ staging, uint64_t n_elems,
+                                                      uint32_t block_len, uint32_t n_blocks, bool vec,
+                                                      bool vec_staging) {
+  constexpr int GPW = (G == 256) ? 1 : kWG / G;
+  const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
+  const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
+  for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
+       i += (uint64_t)gridDim.x * GPW) {
+    const uint32_t b = idx[i];
+    if (b >= n_blocks) continue;
+    const BlockSpan sp = block_span(b, n_elems, block_len, 1);
+    const float* xb = x + sp.byte_off;
+    uint16_t* cb = c + sp.byte_off;
+    uint16_t* sb = staging ? staging + i * (uint64_t)block_len : nullptr;
+    const uint32_t nunit = vec ? sp.len / kMixUnit : 0;
+    for (uint32_t u = lane; u < nunit; u += G) {
+      const uint2 r = round_unit(load_stream((const uint4*)xb + u));
+      store_stream2((uint2*)cb + u, r);
+      if (sb && vec_staging) store_stream2((uint2*)sb + u, r);
+    }
+    for (uint32_t j = nunit * kMixUnit + lane; j < sp.len; j += G) {
+      const uint16_t r = (uint16_t)round_bf16(__float_as_uint(xb[j]));
+      cb[j] = r;
+      if (sb) sb[j] = r;
+    }
+    if (sb && !vec_staging)
+      for (uint32_t j = lane; j < nunit * kMixUnit; j += G) sb[j] = (uint16_t)round_bf16(__float_as_uint(xb[j]));
+  }
+}
+
+// Recovery and/or norm over the blocks idx[0..n_idx) (idx == NULL: blocks 0..n_idx).
+template <int G, bool STORE, bool NORM>
+__global__ __launch_bounds__(kWG) void k_mixed_recover(float* __restrict__ x, const uint16_t* __restrict__ c,
+                                                       const uint32_t* __restrict__ idx, uint32_t n_idx,
+                                                       uint64_t n_elems, uint32_t block_len,
+                                                       uint32_t n_blocks, bool vec,
+                                                       double* __restrict__ partial) {
+  constexpr int GPW = (G == 256) ? 1 : kWG / G;
+  const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
+  const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
+  __shared__ double slots[kWG / kWave];
+  double acc = 0;
+  for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
+       i += (uint64_t)gridDim.x * GPW) {
+    const uint32_t b = idx ? idx[i] : (uint32_t)i;
+    if (b >= n_blocks) continue;
+    const BlockSpan sp = block_span(b, n_elems, block_len, 1);
+    float* xb = x + sp.byte_off;
+    const uint16_t* cb = c + sp.byte_off;
+    const uint32_t nunit = vec ? sp.len / kMixUnit : 0;
+    for (uint32_t u = lane; u < nunit; u += G) {
+      const uint2 cv = load_stream2((const uint2*)cb + u);
+      if (NORM) acc += (double)sqdiff_unit(load_stream((const uint4*)xb + u), cv);
+      if (STORE) store_stream((uint4*)xb + u, widen_unit(cv));
+    }
+    for (uint32_t j = nunit * kMixUnit + lane; j < sp.len; j += G) {
+      const float w = widen_elem(cb, j);
+      if (NORM) acc += (double)sq(xb[j] - w);
+      if (STORE) xb[j] = w;
+    }
+  }
+  if (NORM) {
+    acc = workgroup_sum(acc, slots);
+    if (threadIdx.x == 0) partial[blockIdx.x] = acc;
+  }
+}
+
+#define SCAR_FOR_GROUP(g, CALL)  \
+  switch (g) {                   \
+    case 1: CALL(1); break;      \
+    case 2: CALL(2); break;      \
+    case 4: CALL(4); break;      \
+    case 8: CALL(8); break;      \
+    case 16: CALL(16); break;    \
+    case 32: CALL(32); break;    \
+    case 64: CALL(64); break;    \
+    case 128: CALL(128); break;  \
+    default: CALL(256); break;   \
+  }
+
+static bool mixed_vec(const scar_layout* l, const void* x, const void* c) {
+  return aligned(x, 16) && aligned(c, 8) && l->block_len % kMixUnit == 0;
+}
+
+int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, const void* c,
+                       void* scores, hipStream_t st) {
+  if (!x || !c || !scores || !aligned(x, 4) || !aligned(c, 2) || !aligned(scores, 4))
+    return SCAR_ERR_INVALID_ARG;
+  const bool vec = mixed_vec(l, x, c);
+  const int g = pick_group_units(vec ? l->block_len / kMixUnit : l->block_len, vec ? kMixU : 4, false);
+#define CALL(G)                                                                                      \
+  {                                                                                                  \
+    constexpr int GPW = (G == 256) ? 1 : kWG / G;                                                    \
+    const uint32_t grid = xcd_grid(((uint64_t)n_blocks + GPW - 1) / GPW, kScoreGridCap);             \
+    hipLaunchKernelGGL((k_mixed_scores<G>), dim3(grid), dim3(kWG), 0, st, (const float*)x,           \
+                       (const uint16_t*)c, (float*)scores, l->n_elems, l->block_len, n_blocks, vec); \
+  }
+  switch (g) {  // the score kernel reduces inside a wavefront or a whole workgroup
+    case 1: CALL(1) break;
+    case 2: CALL(2) break;
+    case 4: CALL(4) break;
+    case 8: CALL(8) break;
+    case 16: CALL(16) break;
+    case 32: CALL(32) break;
+    case 64: CALL(64) break;
+    default: CALL(256) break;
+  }
+#undef CALL
+  return launch_status();
+}
+
+int mixed_commit(const scar_layout* l, uint32_t n_blocks, const void* x, void* c, const uint32_t* idx,
+                 uint32_t n_idx, void* staging, hipStream_t st) {
+  if (!x || !c || !idx || !aligned(x, 4) || !aligned(c, 2) || !aligned(idx, 4) ||
+      (staging && !aligned(staging, 2)))
+    return SCAR_ERR_INVALID_ARG;
+  const bool vec = mixed_vec(l, x, c);
+  const bool vec_st = vec && staging && aligned(staging, 8);
+  const int g = pick_group_units(vec ? l->block_len / kMixUnit : l->block_len, 1, true);
+#define CALL(G)                                                                                     \
+  {                                                                                                 \
+    constexpr int GPW = (G == 256) ? 1 : kWG / G;                                                   \
+    const uint32_t grid = xcd_grid(((uint64_t)n_idx + GPW - 1) / GPW, kCopyGridCap);                \
+    hipLaunchKernelGGL((k_mixed_commit<G>), dim3(grid), dim3(kWG), 0, st, (const float*)x,          \
+                       (uint16_t*)c, idx, n_idx, (uint16_t*)staging, l->n_elems, l->block_len,      \
+                       n_blocks, vec, vec_st);                                                      \
+  }
+  SCAR_FOR_GROUP(g, CALL)
+#undef CALL
+  return launch_status();
+}
+
+template <bool STORE, bool NORM>
+static uint32_t launch_mixed_recover(int g, const scar_layout* l, uint32_t n_blocks, void* x,
+                                     const void* c, const uint32_t* idx, uint32_t n_idx, bool vec,
+                                     void* partial, hipStream_t st) {
+  uint32_t grid = 0;
+#define CALL(G)                                                                                       \
+  {                                                                                                   \
+    constexpr int GPW = (G == 256) ? 1 : kWG / G;                                                     \
+    grid = xcd_grid(((uint64_t)n_idx + GPW - 1) / GPW, kMaxNormGrid);                                 \
+    hipLaunchKernelGGL((k_mixed_recover<G, STORE, NORM>), dim3(grid), dim3(kWG), 0, st, (float*)x,    \
+                       (const uint16_t*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, vec,       \
+                       (double*)partial);                                                             \
+  }
+  SCAR_FOR_GROUP(g, CALL)
+#undef CALL
+  return grid;
+}
+
+int mixed_recover_or_norm(bool store, const scar_layout* l, uint32_t n_blocks, void* x, const void* c,
+                          const uint32_t* idx, uint32_t n_idx, scar_norm* norm_out, void* partial,
+                          hipStream_t st) {
+  if (!aligned(x, 4) || !aligned(c, 2)) return SCAR_ERR_INVALID_ARG;
+  const bool vec = mixed_vec(l, x, c);
+  const int g = pick_group_units(vec ? l->block_len / kMixUnit : l->block_len, 1, true);
+  uint32_t n_partial = 0;
+  if (store && norm_out)
+    n_partial = launch_mixed_recover<true, true>(g, l, n_blocks, x, c, idx, n_idx, vec, partial, st);
+  else if (store)
+    launch_mixed_recover<true, false>(g, l, n_blocks, x, c, idx, n_idx, vec, nullptr, st);
+  else
+    n_partial = launch_mixed_recover<false, true>(g, l, n_blocks, x, c, idx, n_idx, vec, partial, st);
+  if (norm_out) launch_finish(l->dtype, partial, n_partial, norm_out, st);
+  return launch_status();
+}
+
+}  // namespace scar

@@ -223,8 +223,11 @@ static int recover_or_norm(bool store, const scar_layout* layout, void* x, const
     }
     return SCAR_OK;
   }
-  if (!x || !c || (!all_blocks && !idx) || !aligned(x, eb) || !aligned(c, eb) || !aligned(idx, 4))
-    return SCAR_ERR_INVALID_ARG;
+  if (!x || !c || (!all_blocks && !idx) || !aligned(idx, 4)) return SCAR_ERR_INVALID_ARG;
+  if (layout->dtype == SCAR_F32_BF16C)
+    return mixed_recover_or_norm(store, layout, (uint32_t)nb, x, c, all_blocks ? nullptr : idx, n_idx,
+                                 norm_out, partial, st);
+  if (!aligned(x, eb) || !aligned(c, eb)) return SCAR_ERR_INVALID_ARG;
   const bool vec = aligned(x, 16) && aligned(c, 16) && ((uint64_t)layout->block_len * eb) % 16 == 0;
   const int g = pick_group(layout->block_len, eb, vec, 1, true);
   const uint32_t n_blocks = (uint32_t)nb;
@@ -249,6 +252,8 @@ extern "C" int scar_checkpoint_commit(const scar_layout* layout, const void* x, 
   const uint64_t nb = layout_blocks(layout);
   if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
   if (n_idx == 0 || nb == 0) return SCAR_OK;
+  if (layout->dtype == SCAR_F32_BF16C)
+    return mixed_commit(layout, (uint32_t)nb, x, c, idx, n_idx, staging, (hipStream_t)stream);
   const int eb = host_elem_bytes(layout->dtype);
   if (!x || !c || !idx || !aligned(x, eb) || !aligned(c, eb) || !aligned(idx, 4) ||
       (staging && !aligned(staging, eb)))

@@ -73,6 +73,8 @@ extern "C" int scar_block_scores(const scar_layout* layout, const void* x, const
   const uint64_t nb = layout_blocks(layout);
   if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
   if (nb == 0) return SCAR_OK;
+  if (layout->dtype == SCAR_F32_BF16C)
+    return mixed_block_scores(layout, (uint32_t)nb, x, c, scores, (hipStream_t)stream);
   const int eb = host_elem_bytes(layout->dtype);
   if (!x || !c || !scores || !aligned(x, eb) || !aligned(c, eb) ||
       !aligned(scores, layout->dtype == SCAR_I32 ? 8 : 4))

@@ -210,7 +210,8 @@ __global__ __launch_bounds__(kWG) void k_var_mask_set(uint8_t* __restrict__ mask
 }
 
 static uint64_t var_blocks(const scar_var_layout* l) {
-  if (!l || !dtype_ok(l->dtype) || l->n_blocks > SCAR_MAX_BLOCKS) return UINT64_MAX;
+  if (!l || !dtype_ok(l->dtype) || l->dtype == SCAR_F32_BF16C || l->n_blocks > SCAR_MAX_BLOCKS)
+    return UINT64_MAX;
   if (l->n_blocks && (!l->offsets || !aligned(l->offsets, 8))) return UINT64_MAX;
   return l->n_blocks;
 }

@@ -10,7 +10,7 @@ import os
 
 import torch
 
-F32, BF16, I32 = 0, 1, 2
+F32, BF16, I32, F32_BF16C = 0, 1, 2, 3
 SCORE_F32, SCORE_I64 = 0, 1
 MAX_BLOCKS = 0x7FFFFFFF
 
@@ -114,10 +114,22 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def layout_of(x, block_len: int) -> Layout:
+def store_type(x, c=None) -> int:
+    """scar_dtype of a store: x's element type, or F32_BF16C for float32 x with a bfloat16
+    checkpoint (the reduced-precision checkpoint)."""
+    if c is not None and x.dtype == torch.float32 and c.dtype == torch.bfloat16:
+        return F32_BF16C
     if x.dtype not in _DTYPE_OF:
         raise TypeError("unsupported element type %s" % x.dtype)
-    return Layout(_DTYPE_OF[x.dtype], int(block_len), x.numel())
+    if c is not None and c.dtype != x.dtype:
+        raise ValueError("x and c must have the same element type (or float32 x with bfloat16 c)")
+    return _DTYPE_OF[x.dtype]
+
+
+def layout_of(x, block_len: int, c=None) -> Layout:
+    if c is not None and x.numel() != c.numel():
+        raise ValueError("x and c must have the same number of elements")
+    return Layout(store_type(x, c), int(block_len), x.numel())
 
 
 def n_blocks(layout: Layout) -> int:
@@ -136,9 +148,7 @@ def new_workspace(n_blocks_: int, device) -> torch.Tensor:
 def block_scores(x, c, block_len, out=None):
     """scar_block_scores: float32 (F32/BF16 stores) or int64 (I32 stores) score per block."""
     _dev(x, "x"), _dev(c, "c")
-    if x.dtype != c.dtype or x.numel() != c.numel():
-        raise ValueError("x and c must have the same element type and size")
-    lay = layout_of(x, block_len)
+    lay = layout_of(x, block_len, c)
     nb = n_blocks(lay)
     if out is None:
         out = torch.empty(nb, dtype=torch.int64 if x.dtype == torch.int32 else torch.float32,
@@ -168,14 +178,12 @@ def select_topk(scores, k, workspace, out=None):
 def checkpoint_commit(x, c, block_len, idx, staging=None, n_idx=None):
     """scar_checkpoint_commit: c[b] <- x[b] for b in idx (optionally also packed into staging)."""
     _dev(x, "x"), _dev(c, "c"), _dev(idx, "idx")
-    if x.dtype != c.dtype or x.numel() != c.numel():
-        raise ValueError("x and c must have the same element type and size")
-    lay = layout_of(x, block_len)
+    lay = layout_of(x, block_len, c)
     n = idx.numel() if n_idx is None else int(n_idx)
     if staging is not None:
         _dev(staging, "staging")
-        if staging.dtype != x.dtype or staging.numel() < n * block_len:
-            raise ValueError("staging must hold n_idx * block_len elements of x's type")
+        if staging.dtype != c.dtype or staging.numel() < n * block_len:
+            raise ValueError("staging must hold n_idx * block_len elements of c's type")
     _check(lib().scar_checkpoint_commit(ctypes.byref(lay), _p(x), _p(c), _p(idx), n, _p(staging),
                                         _stream()), "scar_checkpoint_commit")
 
@@ -194,9 +202,7 @@ def partial_recover(x, c, block_len, lost_idx, workspace=None, want_norm=True, n
     """scar_partial_recover: x[b] <- c[b] for the lost blocks; returns the device scar_norm
     buffer (read it with read_norm) or None."""
     _dev(x, "x"), _dev(c, "c"), _dev(lost_idx, "lost_idx")
-    if x.dtype != c.dtype or x.numel() != c.numel():
-        raise ValueError("x and c must have the same element type and size")
-    lay = layout_of(x, block_len)
+    lay = layout_of(x, block_len, c)
     n = lost_idx.numel() if n_lost is None else int(n_lost)
     if want_norm and norm_out is None:
         norm_out = _norm_buffer(x.device)
@@ -212,9 +218,7 @@ def perturbation_norm(x, c, block_len, idx, workspace, norm_out=None, n_idx=None
     """scar_perturbation_norm over the blocks in idx (None = all blocks); returns the device
     scar_norm buffer."""
     _dev(x, "x"), _dev(c, "c"), _dev(workspace, "workspace")
-    if x.dtype != c.dtype or x.numel() != c.numel():
-        raise ValueError("x and c must have the same element type and size")
-    lay = layout_of(x, block_len)
+    lay = layout_of(x, block_len, c)
     if norm_out is None:
         norm_out = _norm_buffer(x.device)
     if idx is None:

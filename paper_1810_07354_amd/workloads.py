@@ -15,7 +15,7 @@ import math
 
 import numpy as np
 
-F32, BF16, I32 = 0, 1, 2
+F32, BF16, I32, F32_BF16C = 0, 1, 2, 3      # F32_BF16C: float32 x, bfloat16 checkpoint c
 ELEM_BYTES = {F32: 4, BF16: 2, I32: 4}
 NUMPY_DTYPE = {F32: np.float32, BF16: np.uint16, I32: np.int32}
 
@@ -244,6 +244,8 @@ def flat_like(seed: int = 4, n_elems: int = 1 << 30, block_len: int = 1024,
     lost = random_lost_blocks(nb, nb // 8, seed + 1000)
     if dtype == BF16:
         x, c = f32_to_bf16_bits(x), f32_to_bf16_bits(c)
+    elif dtype == F32_BF16C:
+        c = f32_to_bf16_bits(c)
     return Workload("flat_like", dtype, block_len, x, c, k, lost,
                     "top 10% blocks, random 1/8 of blocks lost")
 

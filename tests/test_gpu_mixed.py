@@ -1,0 +1,95 @@
+"""Reduced-precision checkpoint (float32 x, bfloat16 c; Example 2.1) on the GPU against the
+oracle: scores, commit with rounding (bit-exact bfloat16 bits), recovery by widening, norms,
+whole cycles, and the precision bound right after a full save."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1810_07354_amd import scar
+from paper_1810_07354_amd import workloads as wl
+from gpu_util import (DEV, REL_TOL, assert_norm_matches, assert_selection_matches, idx_dev, idx_host,
+                      to_dev, to_host)
+
+pytestmark = pytest.mark.gpu
+MIX = wl.F32_BF16C
+
+
+def make(n_elems, seed):
+    r = np.random.default_rng(seed)
+    cf = r.normal(0, 0.1, size=n_elems).astype(np.float32)
+    x = (cf + r.normal(0, 0.01, size=n_elems) * (r.random(n_elems) < 0.7)).astype(np.float32)
+    return x, wl.f32_to_bf16_bits(cf)
+
+
+def scores_match(got, want):
+    np.testing.assert_allclose(got.cpu().numpy().astype(np.float64), want, rtol=REL_TOL, atol=0)
+
+
+@pytest.mark.parametrize("L", [1, 8, 24, 100, 784, 1024, 4096, 5000, 70000])
+@pytest.mark.parametrize("unaligned", [False, True])
+def test_mixed_calls(L, unaligned):
+    n = min(max(L * 37 + L // 3, 4099), 3_000_000)
+    hx, hc = make(n + 1, L)
+    if unaligned:
+        x, c = to_dev(hx, wl.F32)[1:], to_dev(hc, wl.BF16)[1:]
+        hx, hc = hx[1:].copy(), hc[1:].copy()
+    else:
+        x, c = to_dev(hx[:n], wl.F32), to_dev(hc[:n], wl.BF16)
+        hx, hc = hx[:n].copy(), hc[:n].copy()
+    n = hx.size
+    nb = oracle.n_blocks_of(n, L)
+    print("mixed L=%d unaligned=%s n=%d" % (L, unaligned, n), flush=True)
+    ws = scar.new_workspace(nb, DEV)
+    scores_match(scar.block_scores(x, c, L), oracle.block_scores(MIX, hx, hc, L))
+
+    r = np.random.default_rng(L)
+    K = np.unique(np.concatenate([r.permutation(nb)[: max(1, nb // 3)], [nb - 1]])).astype(np.uint32)
+    r.shuffle(K)
+    st = torch.zeros(K.size * L, dtype=torch.bfloat16, device=DEV)
+    scar.checkpoint_commit(x, c, L, idx_dev(K), st)
+    hst = np.zeros(K.size * L, dtype=np.uint16)
+    oracle.checkpoint_commit(MIX, hx, hc, L, K, hst)
+    np.testing.assert_array_equal(to_host(c.contiguous()), hc)          # rounded bits, exactly
+    np.testing.assert_array_equal(to_host(st), hst)
+
+    S = np.unique(np.concatenate([r.permutation(nb)[: nb // 2], [nb - 1]])).astype(np.uint32)
+    full = scar.read_norm(scar.perturbation_norm(x, c, L, None, ws))
+    assert_norm_matches(full, oracle.perturbation_norm(MIX, hx, hc, L), wl.F32)
+    got = scar.read_norm(scar.partial_recover(x, c, L, idx_dev(S), ws))
+    want = oracle.partial_recover(MIX, hx, hc, L, S)
+    assert_norm_matches(got, want, wl.F32)
+    assert got[1] <= full[1] * (1 + REL_TOL)
+    np.testing.assert_array_equal(to_host(x.contiguous()), hx)
+    assert scar.read_norm(scar.partial_recover(x, c, L, idx_dev(S), ws)) == (0.0, 0.0, 0)
+
+
+def test_mixed_three_cycles_and_precision_bound():
+    w = wl.flat_like(n_elems=1 << 22, dtype=MIX)
+    hx, hc, L, nb = w.x.copy(), w.c.copy(), w.block_len, w.n_blocks
+    x, c = to_dev(hx, wl.F32), to_dev(hc, wl.BF16)
+    ws = scar.new_workspace(nb, DEV)
+    r = np.random.default_rng(5)
+    for cyc in range(3):
+        print("mixed cycle %d" % cyc, flush=True)
+        s = scar.block_scores(x, c, L)
+        s_ref = oracle.block_scores(MIX, hx, hc, L)
+        scores_match(s, s_ref)
+        idx = scar.select_topk(s, w.k, ws)
+        assert_selection_matches(idx_host(idx), s.cpu().numpy(), s_ref, w.k)
+        scar.checkpoint_commit(x, c, L, idx)
+        oracle.checkpoint_commit(MIX, hx, hc, L, idx_host(idx))
+        np.testing.assert_array_equal(to_host(c), hc)
+        lost = wl.random_lost_blocks(nb, nb // 8, 60 + cyc)
+        got = scar.read_norm(scar.partial_recover(x, c, L, idx_dev(lost), ws))
+        assert_norm_matches(got, oracle.partial_recover(MIX, hx, hc, L, lost), wl.F32)
+        np.testing.assert_array_equal(to_host(x), hx)
+        lo = int(r.integers(0, hx.size - hx.size // 10))
+        hx[lo:lo + hx.size // 10] += r.normal(0, 1e-3, size=hx.size // 10).astype(np.float32)
+        x = to_dev(hx, wl.F32)
+    # save everything: what remains is rounding, below 2^-8 ||x|| (Example 2.1 with p = 8)
+    scar.checkpoint_commit(x, c, L, idx_dev(np.arange(nb)))
+    left = scar.read_norm(scar.perturbation_norm(x, c, L, None, ws))
+    assert 0 < left[1] <= 2.0 ** -8 * float(np.linalg.norm(hx.astype(np.float64)))
+    back = c.float()
+    assert torch.all((back - x).abs() <= x.abs() * 2.0 ** -8)
