@@ -250,3 +250,56 @@ def test_comparison_strategies(n, k):
         print("random n=%d k=%d seed=%d draw=%d" % (n, k, seed, draw), flush=True)
         got = idx_host(scar.select_random(n, k, seed, draw, ws))
         np.testing.assert_array_equal(got, oracle.select_random(n, k, seed, draw))
+
+
+def test_cycle_replays_correctly_from_a_hip_graph():
+    # The library enqueues only kernels (no allocation, no memset, no synchronisation), so a
+    # whole cycle can be captured once and replayed.  Every replay - with the program's own
+    # eager work and synchronisations in between - must give what the eager calls give.
+    w = wl.flat_like(n_elems=1 << 22)
+    L, nb, k = w.block_len, w.n_blocks, w.k
+    x, c = to_dev(w.x, w.dtype), to_dev(w.c, w.dtype)
+    ws = scar.new_workspace(nb, DEV)
+    scores = torch.empty(nb, dtype=torch.float32, device=DEV)
+    idx = torch.empty(k, dtype=torch.int32, device=DEV)
+    norm = torch.zeros(3, dtype=torch.float64, device=DEV)
+    lost = idx_dev(w.lost)
+
+    def cycle(x_, c_, scores_, idx_, norm_, ws_):
+        scar.block_scores(x_, c_, L, out=scores_)
+        scar.select_topk(scores_, k, ws_, out=idx_)
+        scar.checkpoint_commit(x_, c_, L, idx_)
+        scar.partial_recover(x_, c_, L, lost, ws_, norm_out=norm_)
+
+    x0, c0 = x.clone(), c.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside the capture
+        cycle(x, c, scores, idx, norm, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    x.copy_(x0), c.copy_(c0)
+    with torch.cuda.graph(graph):
+        cycle(x, c, scores, idx, norm, ws)
+    torch.cuda.synchronize()
+
+    ws2 = scar.new_workspace(nb, DEV)
+    s2, i2, n2 = torch.empty_like(scores), torch.empty_like(idx), torch.zeros_like(norm)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(1)
+    state_x, state_c = x0.clone(), c0.clone()
+    for rep in range(4):
+        print("graph replay %d" % rep, flush=True)
+        x.copy_(state_x), c.copy_(state_c)
+        graph.replay()
+        torch.cuda.synchronize()
+        x2, c2 = state_x.clone(), state_c.clone()
+        cycle(x2, c2, s2, i2, n2, ws2)                 # the same cycle, eagerly
+        torch.cuda.synchronize()
+        assert torch.equal(scores, s2) and torch.equal(idx, i2)
+        assert torch.equal(x, x2) and torch.equal(c, c2) and torch.equal(norm, n2)
+        # eager work between replays: the next state drifts from this one
+        state_x = x2 + 1e-3 * torch.empty_like(x2).normal_(generator=g) * (torch.rand(1, device=DEV) + 0.5)
+        state_c = c2
+        torch.cuda.synchronize()
