@@ -141,6 +141,26 @@ __device__ __forceinline__ T workgroup_exclusive_scan(T v, T* slots, T* total) {
   return base + inc - v;
 }
 
+// Adds one to lh[bin] for every lane with `active`.  Scores cluster (a few exponent values,
+// or thousands of equal integer scores), and 64 lanes hitting one LDS word serialise; so for
+// up to two rounds the lanes that share the first active lane's bin are counted with a
+// ballot and added once.  Whoever is left adds on its own.
+__device__ __forceinline__ void histogram_add(uint32_t* lh, uint32_t bin, bool active) {
+  const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+  for (int round = 0; round < 2; ++round) {
+    const unsigned long long act = __ballot(active);
+    if (act == 0) return;  // uniform over the wavefront
+    const int leader = __ffsll((long long)act) - 1;
+    const uint32_t leader_bin = __shfl(bin, leader, kWave);
+    const bool same = active && bin == leader_bin;
+    const unsigned long long mates = __ballot(same);
+    if (lane == leader) atomicAdd(&lh[leader_bin], (uint32_t)__popcll(mates));
+    active = active && !same;
+  }
+  if (active) atomicAdd(&lh[bin], 1u);
+}
+
 // One workgroup zeroes the histograms and sets the state before the first pass.
 __global__ __launch_bounds__(kWG) void k_select_clear(SelectWs* ws, uint32_t k) {
   uint32_t* words = (uint32_t*)ws;
@@ -199,6 +219,19 @@ __global__ __launch_bounds__(kWG) void k_select_hist(const KeyArgs scores, uint3
   __shared__ uint32_t scratch[kWG / kWave + 1];
   __shared__ SelectState shared_state;
   for (int b = threadIdx.x; b < kMaxBins; b += kWG) lh[b] = 0;
+  // The keys of the first tile are requested before the small histogram walk below, so
+  // that their latency (the scores usually sit in another XCD's L2) overlaps with it.
+  auto load_tile = [&](uint32_t tile, key_t (&key)[kKeysPerThread]) {
+    const uint64_t base = (uint64_t)tile * kTileKeys + threadIdx.x;
+#pragma unroll
+    for (int j = 0; j < kKeysPerThread; ++j) {
+      const uint64_t i = base + (uint64_t)j * kWG;
+      key[j] = K::load(scores, i < n ? i : n - 1);
+    }
+  };
+  key_t key[kKeysPerThread];
+  uint32_t tile = blockIdx.x;
+  if (tile < n_tiles) load_tile(tile, key);
   SelectState cur = ws->state[pass == 0 ? 0 : pass - 1];
   if (pass > 0) {
     cur = next_state(ws->hist[pass - 1], K::bits(pass - 1), cur, scratch, &shared_state);
@@ -207,20 +240,16 @@ __global__ __launch_bounds__(kWG) void k_select_hist(const KeyArgs scores, uint3
   __syncthreads();
   const int shift = K::shift(pass), bits = K::bits(pass);
   const uint32_t mask = (1u << bits) - 1;
-  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+  while (tile < n_tiles) {
     const uint64_t base = (uint64_t)tile * kTileKeys + threadIdx.x;
-    key_t key[kKeysPerThread];
-#pragma unroll
-    for (int j = 0; j < kKeysPerThread; ++j) {
-      const uint64_t i = base + (uint64_t)j * kWG;
-      key[j] = K::load(scores, i < n ? i : n - 1);
-    }
 #pragma unroll
     for (int j = 0; j < kKeysPerThread; ++j) {
       const uint64_t i = base + (uint64_t)j * kWG;
       const bool match = pass == 0 || (key[j] >> (shift + bits)) == (key_t)cur.prefix;
-      if (i < n && match) atomicAdd(&lh[(uint32_t)(key[j] >> shift) & mask], 1u);
+      histogram_add(lh, (uint32_t)(key[j] >> shift) & mask, i < n && match);
     }
+    tile += gridDim.x;
+    if (tile < n_tiles) load_tile(tile, key);
   }
   __syncthreads();
   uint32_t* gh = ws->hist[pass];
@@ -375,7 +404,7 @@ __global__ __launch_bounds__(kWG) void k_select_small(const KeyArgs scores, uint
 #pragma unroll
     for (int j = 0; j < kSmallKeys; ++j) {
       const bool match = pass == 0 || (key[j] >> (shift + bits)) == (key_t)cur.prefix;
-      if (base + j < n && match) atomicAdd(&lh[(uint32_t)(key[j] >> shift) & mask], 1u);
+      histogram_add(lh, (uint32_t)(key[j] >> shift) & mask, base + j < n && match);
     }
     __syncthreads();
     cur = next_state(lh, bits, cur, scratch, &shared_state);
