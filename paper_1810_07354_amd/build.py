@@ -6,13 +6,14 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libscar.so")
-SOURCES = ["scar_api.hip", "scar_scores.hip", "scar_select.hip", "scar_rows.hip", "scar_var.hip", "scar_mixed.hip"]
-HEADERS = ["scar_device.hpp", "scar_host.hpp", os.path.join("..", "..", "include", "scar.h")]
+SOURCES = ["scar_api.hip", "scar_scores.hip", "scar_select.hip", "scar_rows.hip", "scar_var.hip", "scar_mixed.hip", "scar_store.hip"]
+HEADERS = ["scar_device.hpp", "scar_host.hpp", os.path.join("..", "..", "include", "scar.h"),
+           os.path.join("..", "..", "include", "scar_store.h")]
 
 # Packed-FP32 instruction selection is switched off for all device code.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-               "-Wall", "-Wno-unused-function"]
+               "-Wall", "-Wno-unused-function", "-pthread"]
 
 
 def stale() -> bool:

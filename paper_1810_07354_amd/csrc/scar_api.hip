@@ -18,6 +18,7 @@ extern "C" const char* scar_strerror(int status) {
     case SCAR_ERR_INVALID_ARG: return "invalid argument";
     case SCAR_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case SCAR_ERR_DEVICE: return "HIP reported an error while enqueueing";
+    case -4: return "store file could not be created, opened, read or written";
     default: return "unknown status";
   }
 }

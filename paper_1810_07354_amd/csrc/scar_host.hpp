@@ -87,7 +87,7 @@ int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, c
                        void* scores, hipStream_t st);
 int mixed_commit(const scar_layout* l, uint32_t n_blocks, const void* x, void* c, const uint32_t* idx,
                  uint32_t n_idx, void* staging, hipStream_t st);
-int mixed_recover_or_norm(bool store, const scar_layout* l, uint32_t n_blocks, void* x, const void* c,
+int mixed_recover_or_norm(bool store, bool packed, const scar_layout* l, uint32_t n_blocks, void* x, const void* c,
                           const uint32_t* idx, uint32_t n_idx, scar_norm* norm_out, void* partial,
                           hipStream_t st);
 

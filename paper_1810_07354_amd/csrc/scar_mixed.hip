@@ -152,7 +152,7 @@ template <int G, bool STORE, bool NORM>
 __global__ __launch_bounds__(kWG) void k_mixed_recover(float* __restrict__ x, const uint16_t* __restrict__ c,
                                                        const uint32_t* __restrict__ idx, uint32_t n_idx,
                                                        uint64_t n_elems, uint32_t block_len,
-                                                       uint32_t n_blocks, bool vec,
+                                                       uint32_t n_blocks, bool vec, bool packed,
                                                        double* __restrict__ partial) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kWG) void k_mixed_recover(float* __restrict__ x, co
     if (b >= n_blocks) continue;
     const BlockSpan sp = block_span(b, n_elems, block_len, 1);
     float* xb = x + sp.byte_off;
-    const uint16_t* cb = c + sp.byte_off;
+    const uint16_t* cb = packed ? c + i * (uint64_t)block_len : c + sp.byte_off;
     const uint32_t nunit = vec ? sp.len / kMixUnit : 0;
     for (uint32_t u = lane; u < nunit; u += G) {
       const uint2 cv = load_stream2((const uint2*)cb + u);
@@ -252,7 +252,7 @@ int mixed_commit(const scar_layout* l, uint32_t n_blocks, const void* x, void* c
 template <bool STORE, bool NORM>
 static uint32_t launch_mixed_recover(int g, const scar_layout* l, uint32_t n_blocks, void* x,
                                      const void* c, const uint32_t* idx, uint32_t n_idx, bool vec,
-                                     void* partial, hipStream_t st) {
+                                     bool packed, void* partial, hipStream_t st) {
   uint32_t grid = 0;
 #define CALL(G)                                                                                       \
   {                                                                                                   \
@@ -260,14 +260,15 @@ static uint32_t launch_mixed_recover(int g, const scar_layout* l, uint32_t n_blo
     grid = xcd_grid(((uint64_t)n_idx + GPW - 1) / GPW, kMaxNormGrid);                                 \
     hipLaunchKernelGGL((k_mixed_recover<G, STORE, NORM>), dim3(grid), dim3(kWG), 0, st, (float*)x,    \
                        (const uint16_t*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, vec,       \
-                       (double*)partial);                                                             \
+                       packed, (double*)partial);                                                     \
   }
   SCAR_FOR_GROUP(g, CALL)
 #undef CALL
   return grid;
 }
 
-int mixed_recover_or_norm(bool store, const scar_layout* l, uint32_t n_blocks, void* x, const void* c,
+int mixed_recover_or_norm(bool store, bool packed, const scar_layout* l, uint32_t n_blocks, void* x,
+                          const void* c,
                           const uint32_t* idx, uint32_t n_idx, scar_norm* norm_out, void* partial,
                           hipStream_t st) {
   if (!aligned(x, 4) || !aligned(c, 2)) return SCAR_ERR_INVALID_ARG;
@@ -275,11 +276,11 @@ int mixed_recover_or_norm(bool store, const scar_layout* l, uint32_t n_blocks, v
   const int g = pick_group_units(vec ? l->block_len / kMixUnit : l->block_len, 1, true);
   uint32_t n_partial = 0;
   if (store && norm_out)
-    n_partial = launch_mixed_recover<true, true>(g, l, n_blocks, x, c, idx, n_idx, vec, partial, st);
+    n_partial = launch_mixed_recover<true, true>(g, l, n_blocks, x, c, idx, n_idx, vec, packed, partial, st);
   else if (store)
-    launch_mixed_recover<true, false>(g, l, n_blocks, x, c, idx, n_idx, vec, nullptr, st);
+    launch_mixed_recover<true, false>(g, l, n_blocks, x, c, idx, n_idx, vec, packed, nullptr, st);
   else
-    n_partial = launch_mixed_recover<false, true>(g, l, n_blocks, x, c, idx, n_idx, vec, partial, st);
+    n_partial = launch_mixed_recover<false, true>(g, l, n_blocks, x, c, idx, n_idx, vec, packed, partial, st);
   if (norm_out) launch_finish(l->dtype, partial, n_partial, norm_out, st);
   return launch_status();
 }

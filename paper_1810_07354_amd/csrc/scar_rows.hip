@@ -39,7 +39,7 @@ template <int DT, int G, bool STORE, bool NORM>
 __global__ __launch_bounds__(kWG) void k_recover(char* __restrict__ x, const char* __restrict__ c,
                                                  const uint32_t* __restrict__ idx, uint32_t n_idx,
                                                  uint64_t n_elems, uint32_t block_len,
-                                                 uint32_t n_blocks, bool vec,
+                                                 uint32_t n_blocks, bool vec, bool packed,
                                                  typename Acc<DT>::type* __restrict__ partial) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   constexpr int E = elem_bytes(DT);
@@ -57,7 +57,8 @@ __global__ __launch_bounds__(kWG) void k_recover(char* __restrict__ x, const cha
     if (b >= n_blocks) continue;
     const BlockSpan sp = block_span(b, n_elems, block_len, E);
     char* xb = x + sp.byte_off;
-    const char* cb = c + sp.byte_off;
+    // packed: c holds only the listed blocks, row i = block idx[i] (rows read back from storage)
+    const char* cb = packed ? c + i * (uint64_t)block_len * E : c + sp.byte_off;
     const uint32_t nvec = vec ? sp.len / EPV : 0;
     for (uint32_t v0 = 0; v0 < nvec; v0 += G * kUnroll) {
       uint4 xv[kUnroll], cv[kUnroll];
@@ -152,13 +153,13 @@ static void dispatch_commit(int g, const scar_layout* l, const void* x, void* c,
 // Launches the recovery / norm kernel; returns the number of partial sums it writes.
 template <int DT, int G, bool STORE, bool NORM>
 static uint32_t launch_recover(const scar_layout* l, void* x, const void* c, const uint32_t* idx,
-                               uint32_t n_idx, uint32_t n_blocks, bool vec, void* partial,
+                               uint32_t n_idx, uint32_t n_blocks, bool vec, bool packed, void* partial,
                                hipStream_t st) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
   const uint32_t grid = xcd_grid(need, kMaxNormGrid);
   hipLaunchKernelGGL((k_recover<DT, G, STORE, NORM>), dim3(grid), dim3(kWG), 0, st, (char*)x,
-                     (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, vec,
+                     (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, vec, packed,
                      (typename Acc<DT>::type*)partial);
   return grid;
 }
@@ -166,28 +167,28 @@ static uint32_t launch_recover(const scar_layout* l, void* x, const void* c, con
 template <int DT, bool STORE, bool NORM>
 static uint32_t dispatch_recover_g(int g, const scar_layout* l, void* x, const void* c,
                                    const uint32_t* idx, uint32_t n_idx, uint32_t n_blocks, bool vec,
-                                   void* partial, hipStream_t st) {
+                                   bool packed, void* partial, hipStream_t st) {
   switch (g) {
-    case 1: return launch_recover<DT, 1, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
-    case 2: return launch_recover<DT, 2, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
-    case 4: return launch_recover<DT, 4, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
-    case 8: return launch_recover<DT, 8, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
-    case 16: return launch_recover<DT, 16, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
-    case 32: return launch_recover<DT, 32, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
-    case 64: return launch_recover<DT, 64, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
-    case 128: return launch_recover<DT, 128, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
-    default: return launch_recover<DT, 256, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, partial, st);
+    case 1: return launch_recover<DT, 1, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
+    case 2: return launch_recover<DT, 2, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
+    case 4: return launch_recover<DT, 4, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
+    case 8: return launch_recover<DT, 8, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
+    case 16: return launch_recover<DT, 16, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
+    case 32: return launch_recover<DT, 32, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
+    case 64: return launch_recover<DT, 64, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
+    case 128: return launch_recover<DT, 128, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
+    default: return launch_recover<DT, 256, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
   }
 }
 
 template <bool STORE, bool NORM>
 static uint32_t dispatch_recover(int g, const scar_layout* l, void* x, const void* c,
                                  const uint32_t* idx, uint32_t n_idx, uint32_t n_blocks, bool vec,
-                                 void* partial, hipStream_t st) {
+                                 bool packed, void* partial, hipStream_t st) {
   switch (l->dtype) {
-    case SCAR_F32: return dispatch_recover_g<DT_F32, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, partial, st);
-    case SCAR_BF16: return dispatch_recover_g<DT_BF16, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, partial, st);
-    default: return dispatch_recover_g<DT_I32, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, partial, st);
+    case SCAR_F32: return dispatch_recover_g<DT_F32, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
+    case SCAR_BF16: return dispatch_recover_g<DT_BF16, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
+    default: return dispatch_recover_g<DT_I32, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
   }
 }
 
@@ -202,7 +203,7 @@ void launch_finish(int32_t dtype, const void* partial, uint32_t n_partial, scar_
 }
 
 // Shared body of scar_partial_recover (store = true) and scar_perturbation_norm.
-static int recover_or_norm(bool store, const scar_layout* layout, void* x, const void* c,
+static int recover_or_norm(bool store, bool packed, const scar_layout* layout, void* x, const void* c,
                            const uint32_t* idx, uint32_t n_idx, bool all_blocks, scar_norm* norm_out,
                            void* workspace, size_t workspace_bytes, void* stream) {
   const uint64_t nb = layout_blocks(layout);
@@ -225,19 +226,19 @@ static int recover_or_norm(bool store, const scar_layout* layout, void* x, const
   }
   if (!x || !c || (!all_blocks && !idx) || !aligned(idx, 4)) return SCAR_ERR_INVALID_ARG;
   if (layout->dtype == SCAR_F32_BF16C)
-    return mixed_recover_or_norm(store, layout, (uint32_t)nb, x, c, all_blocks ? nullptr : idx, n_idx,
-                                 norm_out, partial, st);
+    return mixed_recover_or_norm(store, packed, layout, (uint32_t)nb, x, c, all_blocks ? nullptr : idx,
+                                 n_idx, norm_out, partial, st);
   if (!aligned(x, eb) || !aligned(c, eb)) return SCAR_ERR_INVALID_ARG;
   const bool vec = aligned(x, 16) && aligned(c, 16) && ((uint64_t)layout->block_len * eb) % 16 == 0;
   const int g = pick_group(layout->block_len, eb, vec, 1, true);
   const uint32_t n_blocks = (uint32_t)nb;
   uint32_t n_partial = 0;
   if (store && norm_out)
-    n_partial = dispatch_recover<true, true>(g, layout, x, c, idx, n_idx, n_blocks, vec, partial, st);
+    n_partial = dispatch_recover<true, true>(g, layout, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
   else if (store)
-    dispatch_recover<true, false>(g, layout, x, c, idx, n_idx, n_blocks, vec, nullptr, st);
+    dispatch_recover<true, false>(g, layout, x, c, idx, n_idx, n_blocks, vec, packed, nullptr, st);
   else
-    n_partial = dispatch_recover<false, true>(g, layout, x, c, idx, n_idx, n_blocks, vec, partial, st);
+    n_partial = dispatch_recover<false, true>(g, layout, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
   if (norm_out) launch_finish(layout->dtype, partial, n_partial, norm_out, st);
   return launch_status();
 }
@@ -273,7 +274,14 @@ extern "C" int scar_checkpoint_commit(const scar_layout* layout, const void* x, 
 extern "C" int scar_partial_recover(const scar_layout* layout, void* x, const void* c,
                                     const uint32_t* lost_idx, uint32_t n_lost, scar_norm* norm_out,
                                     void* workspace, size_t workspace_bytes, void* stream) {
-  return recover_or_norm(true, layout, x, c, lost_idx, n_lost, false, norm_out, workspace,
+  return recover_or_norm(true, false, layout, x, c, lost_idx, n_lost, false, norm_out, workspace,
+                         workspace_bytes, stream);
+}
+
+extern "C" int scar_partial_recover_rows(const scar_layout* layout, void* x, const void* rows,
+                                         const uint32_t* lost_idx, uint32_t n_lost, scar_norm* norm_out,
+                                         void* workspace, size_t workspace_bytes, void* stream) {
+  return recover_or_norm(true, true, layout, x, rows, lost_idx, n_lost, false, norm_out, workspace,
                          workspace_bytes, stream);
 }
 
@@ -281,6 +289,6 @@ extern "C" int scar_perturbation_norm(const scar_layout* layout, const void* x, 
                                       const uint32_t* idx, uint32_t n_idx, scar_norm* norm_out,
                                       void* workspace, size_t workspace_bytes, void* stream) {
   if (!norm_out) return SCAR_ERR_INVALID_ARG;
-  return recover_or_norm(false, layout, const_cast<void*>(x), c, idx, n_idx, idx == nullptr, norm_out,
+  return recover_or_norm(false, false, layout, const_cast<void*>(x), c, idx, n_idx, idx == nullptr, norm_out,
                          workspace, workspace_bytes, stream);
 }

@@ -81,6 +81,17 @@ def lib():
         for name in ("scar_var_block_scores", "scar_var_checkpoint_commit", "scar_var_partial_recover",
                      "scar_var_perturbation_norm"):
             getattr(L, name).restype = ctypes.c_int
+        pp = ctypes.POINTER(ctypes.c_void_p)
+        L.scar_store_create.argtypes = [ctypes.c_char_p, lp, u32, pp]
+        L.scar_store_open.argtypes = [ctypes.c_char_p, u32, lp, pp]
+        L.scar_store_save_async.argtypes = [vp, vp, vp, u32, vp]
+        L.scar_store_wait.argtypes = [vp]
+        L.scar_store_load.argtypes = [vp, vp, u32, vp, vp]
+        L.scar_store_close.argtypes = [vp]
+        L.scar_partial_recover_rows.argtypes = [lp, vp, vp, vp, u32, vp, vp, sz, vp]
+        for name in ("scar_store_create", "scar_store_open", "scar_store_save_async", "scar_store_wait",
+                     "scar_store_load", "scar_store_close", "scar_partial_recover_rows"):
+            getattr(L, name).restype = ctypes.c_int
         for name in ("scar_block_scores", "scar_select_topk", "scar_checkpoint_commit",
                      "scar_partial_recover", "scar_perturbation_norm", "scar_mask_to_indices",
                      "scar_select_round", "scar_select_random"):
@@ -333,4 +344,60 @@ def var_perturbation_norm(x, c, offsets, idx, workspace):
     _check(lib().scar_var_perturbation_norm(ctypes.byref(lay), _p(x), _p(c), ptr, n, _p(norm_out),
                                             _p(workspace), workspace.numel(), _stream()),
            "scar_var_perturbation_norm")
+    return norm_out
+
+
+# ---- persistent-storage leg (include/scar_store.h) ----------------------------------------
+
+class Store:
+    """scar_store: the running checkpoint in a file, written by a background thread."""
+
+    def __init__(self, path, max_rows, layout=None):
+        """layout given: create (truncate) the file for that layout; else open an existing file."""
+        self._h = ctypes.c_void_p(0)
+        self.layout = Layout()
+        if layout is not None:
+            self.layout = layout
+            _check(lib().scar_store_create(os.fsencode(path), ctypes.byref(layout), int(max_rows),
+                                           ctypes.byref(self._h)), "scar_store_create")
+        else:
+            _check(lib().scar_store_open(os.fsencode(path), int(max_rows), ctypes.byref(self.layout),
+                                         ctypes.byref(self._h)), "scar_store_open")
+
+    def save_async(self, staging, idx, n_idx=None):
+        _dev(staging, "staging"), _dev(idx, "idx")
+        n = idx.numel() if n_idx is None else int(n_idx)
+        _check(lib().scar_store_save_async(self._h, _p(staging), _p(idx), n, _stream()),
+               "scar_store_save_async")
+
+    def wait(self):
+        _check(lib().scar_store_wait(self._h), "scar_store_wait")
+
+    def load(self, idx_host, rows):
+        """Reads the blocks idx_host (sequence of ints) into the packed device rows tensor."""
+        import numpy as np
+        idx_host = np.ascontiguousarray(idx_host, dtype=np.uint32)
+        _dev(rows, "rows")
+        _check(lib().scar_store_load(self._h, ctypes.c_void_p(idx_host.ctypes.data), idx_host.size,
+                                     _p(rows), _stream()), "scar_store_load")
+        return rows
+
+    def close(self):
+        if self._h:
+            h, self._h = self._h, ctypes.c_void_p(0)
+            _check(lib().scar_store_close(h), "scar_store_close")
+
+
+def partial_recover_rows(x, rows, block_len, lost_idx, workspace=None, want_norm=True):
+    """scar_partial_recover_rows: x[b] <- rows[i] for b = lost_idx[i]; returns the device
+    scar_norm buffer or None."""
+    _dev(x, "x"), _dev(rows, "rows"), _dev(lost_idx, "lost_idx")
+    lay = Layout(store_type(x, rows), int(block_len), x.numel())
+    if rows.numel() < lost_idx.numel() * block_len:
+        raise ValueError("rows must hold lost_idx.numel() * block_len elements")
+    norm_out = _norm_buffer(x.device) if want_norm else None
+    _check(lib().scar_partial_recover_rows(ctypes.byref(lay), _p(x), _p(rows), _p(lost_idx),
+                                           lost_idx.numel(), _p(norm_out), _p(workspace),
+                                           workspace.numel() if workspace is not None else 0, _stream()),
+           "scar_partial_recover_rows")
     return norm_out

@@ -1,0 +1,120 @@
+"""The persistent-storage leg (Section 4.3: rows saved asynchronously in the background,
+lost blocks re-loaded from the running checkpoint in storage).  The file is read back with
+numpy at the documented offsets and compared with the oracle's host mirror of the running
+checkpoint; recovery from the file is compared with the oracle's partial recovery."""
+import ctypes
+import struct
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1810_07354_amd import scar
+from paper_1810_07354_amd import workloads as wl
+from gpu_util import DEV, assert_norm_matches, idx_dev, idx_host, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+MIX = wl.F32_BF16C
+
+
+def make(dtype, n, seed):
+    r = np.random.default_rng(seed)
+    if dtype == wl.I32:
+        c = r.integers(0, 1000, size=n).astype(np.int32)
+        return (c + r.integers(-3, 4, size=n)).astype(np.int32), c
+    cf = r.normal(0, 0.1, size=n).astype(np.float32)
+    x = (cf + r.normal(0, 0.01, size=n)).astype(np.float32)
+    return (x, wl.f32_to_bf16_bits(cf)) if dtype == MIX else (x, cf)
+
+
+def file_checkpoint(path, like):
+    return np.fromfile(path, dtype=like.dtype, offset=4096, count=like.size)
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.I32, MIX])
+def test_store_follows_the_running_checkpoint_and_recovers_from_it(dtype, tmp_path):
+    L, nb = 100, 3000
+    n = L * nb - 37                                          # short last block
+    hx, hc = make(dtype, n, 5)
+    xt, ct = (wl.F32, wl.BF16) if dtype == MIX else (dtype, dtype)
+    x, c = to_dev(hx, xt), to_dev(hc, ct)
+    ws = scar.new_workspace(nb, DEV)
+    k = 400
+    path = str(tmp_path / "running.ckpt")
+    store = scar.Store(path, max_rows=1024, layout=scar.layout_of(x, L, c))
+    try:
+        head = open(path, "rb").read(28)
+        assert head[:8] == b"SCARSTO1"
+        assert struct.unpack("<iIQI", head[8:28]) == (dtype, L, n, L * c.element_size())
+
+        # the running checkpoint starts as a full save of the first state (Section 4.2)
+        staging = torch.empty(1024 * L, dtype=c.dtype, device=DEV)
+        everything = np.arange(nb, dtype=np.uint32)
+        for lo in range(0, nb, 1024):
+            part = idx_dev(everything[lo:lo + 1024])
+            scar.checkpoint_commit(x, c, L, part, staging)
+            store.save_async(staging, part)
+            torch.cuda.synchronize()                         # staging is reused by the next part
+        oracle.checkpoint_commit(dtype, hx, hc, L, everything)
+        store.wait()
+        np.testing.assert_array_equal(file_checkpoint(path, hc), hc)
+
+        # prioritized partial checkpoints, each saved in the background while x moves on
+        r = np.random.default_rng(1)
+        stagings = [torch.empty(k * L, dtype=c.dtype, device=DEV) for _ in range(3)]
+        for cyc in range(3):
+            print("store dtype=%d cycle %d" % (dtype, cyc), flush=True)
+            lo = int(r.integers(0, n - n // 5))
+            if dtype == wl.I32:
+                hx[lo:lo + n // 5] += r.integers(-2, 3, size=n // 5).astype(np.int32)
+            else:
+                hx[lo:lo + n // 5] += r.normal(0, 1e-2, size=n // 5).astype(np.float32)
+            x = to_dev(hx, xt)
+            s = scar.block_scores(x, c, L)
+            idx = scar.select_topk(s, k, ws)
+            scar.checkpoint_commit(x, c, L, idx, stagings[cyc])
+            store.save_async(stagings[cyc], idx)             # three saves in flight: two buffers
+            oracle.checkpoint_commit(dtype, hx, hc, L, idx_host(idx))
+        store.wait()
+        np.testing.assert_array_equal(to_host(c), hc)
+        np.testing.assert_array_equal(file_checkpoint(path, hc), hc)
+
+        # failure: the lost blocks come back from the file, not from the in-memory cache
+        hx[:] = hx + (1 if dtype == wl.I32 else np.float32(0.5))
+        x = to_dev(hx, xt)
+        lost = np.unique(np.concatenate([r.choice(nb, size=700, replace=False), [nb - 1]])).astype(np.uint32)
+        rows = torch.zeros(lost.size * L, dtype=c.dtype, device=DEV)
+        store.load(lost, rows)
+        got = scar.read_norm(scar.partial_recover_rows(x, rows, L, idx_dev(lost), ws))
+        want = oracle.partial_recover(dtype, hx, hc, L, lost)
+        assert_norm_matches(got, want, wl.I32 if dtype == wl.I32 else wl.F32)
+        np.testing.assert_array_equal(to_host(x), hx)
+        with pytest.raises(scar.ScarError):
+            store.save_async(staging, idx_dev(np.arange(1025)))
+    finally:
+        store.close()
+
+    again = scar.Store(path, max_rows=64)                    # a new process would open it like this
+    try:
+        assert (again.layout.dtype, again.layout.block_len, again.layout.n_elems) == (dtype, L, n)
+        rows = torch.zeros(3 * L, dtype=c.dtype, device=DEV)
+        again.load([5, nb - 1, 0], rows)
+        got = to_host(rows).reshape(3, L)
+        np.testing.assert_array_equal(got[0], hc[5 * L:6 * L])
+        np.testing.assert_array_equal(got[1][:L - 37], hc[(nb - 1) * L:])
+        np.testing.assert_array_equal(got[2], hc[:L])
+    finally:
+        again.close()
+
+
+def test_store_errors(tmp_path):
+    with pytest.raises(scar.ScarError) as e:
+        scar.Store(str(tmp_path / "missing.ckpt"), max_rows=4)
+    assert e.value.status == -4
+    bad = tmp_path / "bad.ckpt"
+    bad.write_bytes(b"not a store file" * 300)
+    with pytest.raises(scar.ScarError):
+        scar.Store(str(bad), max_rows=4)
+    with pytest.raises(scar.ScarError):
+        scar.Store(str(tmp_path / "no_such_dir" / "x.ckpt"), max_rows=4, layout=scar.Layout(scar.F32, 8, 64))
