@@ -80,7 +80,8 @@ extern "C" int scar_block_scores(const scar_layout* layout, const void* x, const
       !aligned(scores, layout->dtype == SCAR_I32 ? 8 : 4))
     return SCAR_ERR_INVALID_ARG;
   const bool vec = aligned(x, 16) && aligned(c, 16) && ((uint64_t)layout->block_len * eb) % 16 == 0;
-  const int g = pick_group(layout->block_len, eb, vec, 4, false);
+  int g = pick_group(layout->block_len, eb, vec, 4, false);
+  if (g == 32 && vec && (uint64_t)layout->block_len * eb >= 2048) g = 64;  // 2 KiB rows: a whole wavefront, two loads per lane
   hipStream_t st = (hipStream_t)stream;
   switch (layout->dtype) {
     case SCAR_F32: dispatch_scores<DT_F32>(g, layout, x, c, scores, (uint32_t)nb, vec, st); break;

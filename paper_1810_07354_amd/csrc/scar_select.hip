@@ -389,10 +389,14 @@ __global__ __launch_bounds__(kWG) void k_select_small(const KeyArgs scores, uint
   __shared__ uint32_t lh[kMaxBins];
   __shared__ uint32_t scratch[kWG / kWave + 1];
   __shared__ SelectState shared_state;
-  const uint32_t base = threadIdx.x * kSmallKeys;
+  // thread t holds the kpt consecutive keys from t * kpt on (kpt = ceil(n / 256) <= 32), so
+  // every thread has work whatever n is, and index order is thread order
+  const uint32_t kpt = (n + kWG - 1) / kWG;
+  const uint32_t base = threadIdx.x * kpt;
   key_t key[kSmallKeys];
 #pragma unroll
-  for (int j = 0; j < kSmallKeys; ++j) key[j] = K::load(scores, base + j < n ? base + j : n - 1);
+  for (int j = 0; j < kSmallKeys; ++j)
+    key[j] = (uint32_t)j < kpt ? K::load(scores, base + j < n ? base + j : n - 1) : (key_t)0;
 
   SelectState cur;
   cur.prefix = 0, cur.k_rem = k, cur.pad = 0;
@@ -404,7 +408,7 @@ __global__ __launch_bounds__(kWG) void k_select_small(const KeyArgs scores, uint
 #pragma unroll
     for (int j = 0; j < kSmallKeys; ++j) {
       const bool match = pass == 0 || (key[j] >> (shift + bits)) == (key_t)cur.prefix;
-      histogram_add(lh, (uint32_t)(key[j] >> shift) & mask, base + j < n && match);
+      if ((uint32_t)j < kpt && base + j < n && match) atomicAdd(&lh[(uint32_t)(key[j] >> shift) & mask], 1u);
     }
     __syncthreads();
     cur = next_state(lh, bits, cur, scratch, &shared_state);
@@ -415,13 +419,13 @@ __global__ __launch_bounds__(kWG) void k_select_small(const KeyArgs scores, uint
   uint32_t cnt = 0;  // low half: above, high half: equal
 #pragma unroll
   for (int j = 0; j < kSmallKeys; ++j)
-    if (base + j < n) cnt += key[j] > T ? 1u : (key[j] == T ? (1u << 16) : 0u);
+    if ((uint32_t)j < kpt && base + j < n) cnt += key[j] > T ? 1u : (key[j] == T ? (1u << 16) : 0u);
   uint32_t total;
   const uint32_t ex = workgroup_exclusive_scan(cnt, scratch, &total);
   uint32_t n_above = ex & 0xffffu, n_equal = ex >> 16;
 #pragma unroll
   for (int j = 0; j < kSmallKeys; ++j) {
-    if (base + j >= n) break;
+    if ((uint32_t)j >= kpt || base + j >= n) continue;
     if (key[j] > T) {
       const uint32_t pos = n_above + (n_equal < take ? n_equal : take);
       if (pos < k) out_idx[pos] = base + j;
