@@ -391,7 +391,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)
-        sample = min(n_elems, 1 << 28)
+        sample = min(n_elems, 1 << 29)
         sample -= sample % L
         out["cpu_baseline"] = cpu_baseline(x, c, L, k / nb, n_lost / nb, sample, threads)
     print(json.dumps(out), flush=True)
