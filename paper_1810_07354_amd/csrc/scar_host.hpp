@@ -43,7 +43,7 @@ inline int pick_group(uint32_t block_len, int ebytes, bool vec, int per_lane, bo
 }
 
 // ---- workspace layout ---------------------------------------------------------------
-// [0, 64 KiB)    selection: digit histograms, pass state, tickets   (select, mask)
+// [0, 64 KiB)    selection: digit histograms and pass states        (select)
 // [64 KiB, +512 KiB) per-workgroup partial sums of the norm          (recover, norm)
 // [576 KiB, ...) per-tile counts of the compaction, 8 bytes per tile (select, mask)
 constexpr size_t kWsSelectBytes = 64 * 1024;

@@ -27,12 +27,19 @@ def rows_to_host(t, rows):
     return to_host(sel).reshape(-1)
 
 
-@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+def bits(t):
+    """A view that torch.equal compares bit for bit (bfloat16 as int16)."""
+    return t.view(torch.int16) if t.dtype == torch.bfloat16 else t
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16, wl.F32_BF16C])
 def test_flat_store_full_size(dtype):
     print("full size dtype=%d: generate" % dtype, flush=True)
     x, c = wl.flat_like_torch(DEV, seed=4, n_elems=N_ELEMS)
     if dtype == wl.BF16:
         x, c = x.to(torch.bfloat16), c.to(torch.bfloat16)
+    elif dtype == wl.F32_BF16C:
+        c = c.to(torch.bfloat16)
     k, n_lost = wl.k_of_fraction(0.10, NB), NB // 8
     ws = scar.new_workspace(NB, DEV)
     oracle.set_num_threads(8)
@@ -66,9 +73,8 @@ def test_flat_store_full_size(dtype):
         np.testing.assert_array_equal(rows_to_host(c, sample), sub_c)
         expect = c_before
         idx_l = idx.long()
-        expect.view(NB, L)[idx_l] = x.view(NB, L)[idx_l]
-        assert torch.equal(c.view(torch.int16 if dtype == wl.BF16 else c.dtype),
-                           expect.view(torch.int16 if dtype == wl.BF16 else c.dtype))
+        expect.view(NB, L)[idx_l] = x.view(NB, L)[idx_l].to(c.dtype)     # torch rounds to nearest even too
+        assert torch.equal(bits(c), bits(expect))
         del expect, c_before
 
         # ---- partial recovery with the fused norm: the norm over all lost blocks by the oracle
@@ -83,9 +89,9 @@ def test_flat_store_full_size(dtype):
         assert abs(got[1] - want[1]) <= REL_TOL * want[1]
         assert got[1] <= full[1] * (1 + REL_TOL)                      # Theorem 4.1 (after the commit the
         lost_l = lost_d.long()                                         # full norm only shrank, so compare
-        x_before.view(NB, L)[lost_l] = c.view(NB, L)[lost_l]           # with the pre-commit one)
-        assert torch.equal(x.view(torch.int16 if dtype == wl.BF16 else x.dtype),
-                           x_before.view(torch.int16 if dtype == wl.BF16 else x.dtype))
-        np.testing.assert_array_equal(rows_to_host(x, lost[:256]), hc[:256 * L])
+        x_before.view(NB, L)[lost_l] = c.view(NB, L)[lost_l].to(x.dtype)   # with the pre-commit one)
+        assert torch.equal(bits(x), bits(x_before))
+        if dtype != wl.F32_BF16C:
+            np.testing.assert_array_equal(rows_to_host(x, lost[:256]), hc[:256 * L])
     finally:
         oracle.set_num_threads(1)

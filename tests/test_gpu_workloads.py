@@ -51,6 +51,16 @@ def test_lda_like_quarter_size():
     three_cycles(wl.lda_like(words=25_000, topics=1000))
 
 
+def test_lda_like_full_size_one_cycle():
+    w = wl.lda_like()
+    print("lda full size generated", flush=True)
+    oracle.set_num_threads(8)
+    try:
+        DeviceStore(w).cycle(w.k, w.lost)
+    finally:
+        oracle.set_num_threads(1)
+
+
 @pytest.mark.parametrize("fraction", [0.01, 0.10, 0.50])
 def test_cnn_like_full_size(fraction):
     three_cycles(wl.cnn_like(fraction=fraction))
