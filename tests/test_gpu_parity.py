@@ -303,3 +303,39 @@ def test_cycle_replays_correctly_from_a_hip_graph():
         state_x = x2 + 1e-3 * torch.empty_like(x2).normal_(generator=g) * (torch.rand(1, device=DEV) + 0.5)
         state_c = c2
         torch.cuda.synchronize()
+
+
+def test_random_layouts_whole_cycles():
+    # 60 seeded random stores: element type, block length, size (ragged or not), k and lost
+    # set all drawn at random; one full cycle each, compared with the oracle call by call
+    r = np.random.default_rng(2024)
+    for case in range(60):
+        dtype = int(r.choice([F32, BF16, I32, wl.F32_BF16C]))
+        L = int(r.choice([1, 2, 3, 4, 5, 7, 8, 12, 16, 31, 32, 33, 64, 100, 128, 255, 256, 500, 1000, 1024,
+                          2048, 3000, 4096, 9000]))
+        nb = int(r.integers(1, 400))
+        n = max(1, L * nb - int(r.integers(0, L)))
+        nb = oracle.n_blocks_of(n, L)
+        k = int(r.integers(0, nb + 1))
+        lost = np.sort(r.choice(nb, size=int(r.integers(0, nb + 1)), replace=False)).astype(np.uint32)
+        print("case %d dtype=%d L=%d n=%d k=%d lost=%d" % (case, dtype, L, n, k, lost.size), flush=True)
+        if dtype == wl.F32_BF16C:
+            hx, hc = make_store(F32, n, seed=case)
+            hc = wl.f32_to_bf16_bits(hc)
+            x, c = to_dev(hx, F32), to_dev(hc, BF16)
+        else:
+            hx, hc = make_store(dtype, n, seed=case)
+            x, c = to_dev(hx, dtype), to_dev(hc, dtype)
+        ws = scar.new_workspace(nb, DEV)
+        s = scar.block_scores(x, c, L)
+        s_ref = oracle.block_scores(dtype, hx, hc, L)
+        assert_scores_match(s, s_ref, I32 if dtype == I32 else F32)
+        idx = scar.select_topk(s, k, ws)
+        assert_selection_matches(idx_host(idx), s.cpu().numpy(), s_ref, k)
+        scar.checkpoint_commit(x, c, L, idx)
+        oracle.checkpoint_commit(dtype, hx, hc, L, idx_host(idx))
+        np.testing.assert_array_equal(to_host(c), hc)
+        got = scar.read_norm(scar.partial_recover(x, c, L, idx_dev(lost), ws))
+        want = oracle.partial_recover(dtype, hx, hc, L, lost)
+        assert_norm_matches(got, want, I32 if dtype == I32 else F32)
+        np.testing.assert_array_equal(to_host(x), hx)
