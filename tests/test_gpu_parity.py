@@ -339,3 +339,22 @@ def test_random_layouts_whole_cycles():
         want = oracle.partial_recover(dtype, hx, hc, L, lost)
         assert_norm_matches(got, want, I32 if dtype == I32 else F32)
         np.testing.assert_array_equal(to_host(x), hx)
+
+
+@pytest.mark.parametrize("dtype", [F32, I32])
+def test_out_of_range_list_entries_are_skipped(dtype):
+    # documented device-side behaviour: an index >= n_blocks in a list is ignored
+    L, nb = 64, 50
+    hx, hc = make_store(dtype, L * nb, seed=77)
+    x, c = to_dev(hx, dtype), to_dev(hc, dtype)
+    ws = scar.new_workspace(nb, DEV)
+    good = np.array([3, 49, 10], dtype=np.uint32)
+    mixed = np.array([3, 50, 49, 0xFFFFFFFF, 10, 1 << 20], dtype=np.uint32)
+    scar.checkpoint_commit(x, c, L, idx_dev(mixed))
+    oracle.checkpoint_commit(dtype, hx, hc, L, good)
+    np.testing.assert_array_equal(to_host(c), hc)
+    lost_good = np.array([0, 7, 48], dtype=np.uint32)
+    lost_mixed = np.array([0, 99, 7, 48, 50], dtype=np.uint32)
+    got = scar.read_norm(scar.partial_recover(x, c, L, idx_dev(lost_mixed), ws))
+    assert_norm_matches(got, oracle.partial_recover(dtype, hx, hc, L, lost_good), dtype)
+    np.testing.assert_array_equal(to_host(x), hx)
