@@ -264,8 +264,9 @@ def main():
         print(score_kernel_source_hash())
         return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this path runs on ONE GPU; --gpus %d is not supported "
-              "(see DESIGN.md for how it would shard)" % args.gpus, file=sys.stderr)
+        print("bench.py: this path runs on ONE GPU; --gpus %d is not supported (blocks would be "
+              "range-partitioned over GPUs and only the selection would exchange histograms)"
+              % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
