@@ -24,6 +24,11 @@ constexpr int kMaxPasses = 6;
 constexpr uint32_t kHistGridCap = 1u << 14;
 constexpr uint32_t kTileGridCap = 1u << 14;
 constexpr int kKeysPerThread = kTileKeys / kWG;  // 8 consecutive keys per thread
+// A histogram pass reads its keys from wherever the score kernel left them (usually another
+// XCD's L2 or HBM), so many small tiles - many loads in flight - beat few large ones, although
+// larger tiles would save global atomics at the end of the pass (measured both ways).
+constexpr int kHistKeysPerThread = kKeysPerThread;
+constexpr uint32_t kHistTileKeys = kHistKeysPerThread * kWG;
 
 enum : int { SRC_F32 = 0, SRC_I64 = 1, SRC_MASK = 2, SRC_RANDOM = 3 };
 
@@ -141,26 +146,6 @@ __device__ __forceinline__ T workgroup_exclusive_scan(T v, T* slots, T* total) {
   return base + inc - v;
 }
 
-// Adds one to lh[bin] for every lane with `active`.  Scores cluster (a few exponent values,
-// or thousands of equal integer scores), and 64 lanes hitting one LDS word serialise; so for
-// up to two rounds the lanes that share the first active lane's bin are counted with a
-// ballot and added once.  Whoever is left adds on its own.
-__device__ __forceinline__ void histogram_add(uint32_t* lh, uint32_t bin, bool active) {
-  const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-  for (int round = 0; round < 2; ++round) {
-    const unsigned long long act = __ballot(active);
-    if (act == 0) return;  // uniform over the wavefront
-    const int leader = __ffsll((long long)act) - 1;
-    const uint32_t leader_bin = __shfl(bin, leader, kWave);
-    const bool same = active && bin == leader_bin;
-    const unsigned long long mates = __ballot(same);
-    if (lane == leader) atomicAdd(&lh[leader_bin], (uint32_t)__popcll(mates));
-    active = active && !same;
-  }
-  if (active) atomicAdd(&lh[bin], 1u);
-}
-
 // One workgroup zeroes the histograms and sets the state before the first pass.
 __global__ __launch_bounds__(kWG) void k_select_clear(SelectWs* ws, uint32_t k) {
   uint32_t* words = (uint32_t*)ws;
@@ -221,15 +206,15 @@ __global__ __launch_bounds__(kWG) void k_select_hist(const KeyArgs scores, uint3
   for (int b = threadIdx.x; b < kMaxBins; b += kWG) lh[b] = 0;
   // The keys of the first tile are requested before the small histogram walk below, so
   // that their latency (the scores usually sit in another XCD's L2) overlaps with it.
-  auto load_tile = [&](uint32_t tile, key_t (&key)[kKeysPerThread]) {
-    const uint64_t base = (uint64_t)tile * kTileKeys + threadIdx.x;
+  auto load_tile = [&](uint32_t tile, key_t (&key)[kHistKeysPerThread]) {
+    const uint64_t base = (uint64_t)tile * kHistTileKeys + threadIdx.x;
 #pragma unroll
-    for (int j = 0; j < kKeysPerThread; ++j) {
+    for (int j = 0; j < kHistKeysPerThread; ++j) {
       const uint64_t i = base + (uint64_t)j * kWG;
       key[j] = K::load(scores, i < n ? i : n - 1);
     }
   };
-  key_t key[kKeysPerThread];
+  key_t key[kHistKeysPerThread];
   uint32_t tile = blockIdx.x;
   if (tile < n_tiles) load_tile(tile, key);
   SelectState cur = ws->state[pass == 0 ? 0 : pass - 1];
@@ -241,12 +226,12 @@ __global__ __launch_bounds__(kWG) void k_select_hist(const KeyArgs scores, uint3
   const int shift = K::shift(pass), bits = K::bits(pass);
   const uint32_t mask = (1u << bits) - 1;
   while (tile < n_tiles) {
-    const uint64_t base = (uint64_t)tile * kTileKeys + threadIdx.x;
+    const uint64_t base = (uint64_t)tile * kHistTileKeys + threadIdx.x;
 #pragma unroll
-    for (int j = 0; j < kKeysPerThread; ++j) {
+    for (int j = 0; j < kHistKeysPerThread; ++j) {
       const uint64_t i = base + (uint64_t)j * kWG;
       const bool match = pass == 0 || (key[j] >> (shift + bits)) == (key_t)cur.prefix;
-      histogram_add(lh, (uint32_t)(key[j] >> shift) & mask, i < n && match);
+      if (i < n && match) atomicAdd(&lh[(uint32_t)(key[j] >> shift) & mask], 1u);
     }
     tile += gridDim.x;
     if (tile < n_tiles) load_tile(tile, key);
@@ -473,10 +458,10 @@ static void run_select(const KeyArgs scores, uint32_t n, uint32_t k, uint32_t* o
   SelectWs* ws = (SelectWs*)workspace;
   unsigned long long* tiles = (unsigned long long*)((char*)workspace + kWsTileOffset);
   hipLaunchKernelGGL(k_select_clear, dim3(1), dim3(kWG), 0, st, ws, k);
-  const uint32_t n_tiles = (uint32_t)n_tiles_of(n);
-  const uint32_t hgrid = n_tiles < kHistGridCap ? n_tiles : kHistGridCap;
+  const uint32_t n_htiles = (uint32_t)(((uint64_t)n + kHistTileKeys - 1) / kHistTileKeys);
+  const uint32_t hgrid = n_htiles < kHistGridCap ? n_htiles : kHistGridCap;
   for (int p = 0; p < Key<SRC>::passes; ++p)
-    hipLaunchKernelGGL((k_select_hist<SRC>), dim3(hgrid), dim3(kWG), 0, st, scores, n, n_tiles, p, ws);
+    hipLaunchKernelGGL((k_select_hist<SRC>), dim3(hgrid), dim3(kWG), 0, st, scores, n, n_htiles, p, ws);
   run_compaction<SRC>(scores, n, Key<SRC>::passes, ws, tiles, out_idx, k, nullptr, st);
 }
 
