@@ -105,3 +105,20 @@ def test_strategy_study_orders_the_strategies_as_the_paper_does():
     assert m["partial"] < m["traditional"]
     assert 0.6 < m["partial"] / m["traditional"] < 0.8
     assert m["priority"] < m["partial"]
+
+
+def test_iteration_cost_demo_reproduces_the_papers_ordering():
+    # Figs. 7 and 8 on a synthetic contracting job: partial recovery costs fewer iterations
+    # than full recovery, prioritized partial checkpoints fewer still, and a full checkpoint
+    # every C iterations with full recovery costs about C/2 iterations per failure.
+    from paper_1810_07354_amd import iteration_cost_demo
+    r = iteration_cost_demo.run(n_blocks=1024, block_len=256, interval=32, fraction=0.125,
+                                lost_fraction=0.5, trials=8)
+    print(r, flush=True)
+    cost = r["mean_iteration_cost"]
+    assert all(v >= 0 for v in cost.values())
+    assert 4 <= cost["traditional"] <= 32
+    assert cost["partial"] <= cost["traditional"]
+    assert cost["priority"] < cost["partial"] and cost["priority"] < cost["round"]
+    for name, b in r["theorem_3_1_bound_at_mean"].items():
+        assert cost[name] <= b + 1, name
