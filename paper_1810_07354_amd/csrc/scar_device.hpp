@@ -133,18 +133,18 @@ __device__ __forceinline__ T group_sum(T v) {
   return v;
 }
 
-// Sum over the whole workgroup; the result is valid in thread 0.  `slots` is LDS for
-// kWG / kWave values.  Fixed order, so the result is reproducible.
-template <typename T>
-__device__ __forceinline__ T workgroup_sum(T v, T* slots) {
+// Sum over a workgroup of T threads; the result is valid in thread 0.  `slots` is LDS for
+// T / kWave values.  Fixed order, so the result is reproducible.
+template <int T = kWG, typename V>
+__device__ __forceinline__ V workgroup_sum(V v, V* slots) {
   v = group_sum<kWave>(v);
   const int wave = threadIdx.x / kWave;
   __syncthreads();  // slots may still be read from a previous use
   if ((threadIdx.x & (kWave - 1)) == 0) slots[wave] = v;
   __syncthreads();
-  T total = slots[0];
+  V total = slots[0];
 #pragma unroll
-  for (int w = 1; w < kWG / kWave; ++w) total += slots[w];
+  for (int w = 1; w < T / kWave; ++w) total += slots[w];
   return total;
 }
 

@@ -147,17 +147,18 @@ __global__ __launch_bounds__(kWG) void k_mixed_commit(const float* __restrict__ 
   }
 }
 
-// Recovery and/or norm over the blocks idx[0..n_idx) (idx == NULL: blocks 0..n_idx).
-template <int G, bool STORE, bool NORM>
-__global__ __launch_bounds__(kWG) void k_mixed_recover(float* __restrict__ x, const uint16_t* __restrict__ c,
-                                                       const uint32_t* __restrict__ idx, uint32_t n_idx,
-                                                       uint64_t n_elems, uint32_t block_len,
-                                                       uint32_t n_blocks, bool vec, bool packed,
-                                                       double* __restrict__ partial) {
-  constexpr int GPW = (G == 256) ? 1 : kWG / G;
-  const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
-  const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
-  __shared__ double slots[kWG / kWave];
+// Recovery and/or norm over the blocks idx[0..n_idx) (idx == NULL: blocks 0..n_idx), with T
+// threads per workgroup (1,024 for long index lists, so that no group takes a second entry).
+template <int G, int T, bool STORE, bool NORM>
+__global__ __launch_bounds__(T) void k_mixed_recover(float* __restrict__ x, const uint16_t* __restrict__ c,
+                                                     const uint32_t* __restrict__ idx, uint32_t n_idx,
+                                                     uint64_t n_elems, uint32_t block_len,
+                                                     uint32_t n_blocks, bool vec, bool packed,
+                                                     double* __restrict__ partial) {
+  constexpr int GPW = T / G;
+  const int lane = threadIdx.x & (G - 1);
+  const uint32_t grp = threadIdx.x / G;
+  __shared__ double slots[T / kWave];
   double acc = 0;
   for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
        i += (uint64_t)gridDim.x * GPW) {
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(kWG) void k_mixed_recover(float* __restrict__ x, co
     }
   }
   if (NORM) {
-    acc = workgroup_sum(acc, slots);
+    acc = workgroup_sum<T>(acc, slots);
     if (threadIdx.x == 0) partial[blockIdx.x] = acc;
   }
 }
@@ -254,16 +255,22 @@ static uint32_t launch_mixed_recover(int g, const scar_layout* l, uint32_t n_blo
                                      const void* c, const uint32_t* idx, uint32_t n_idx, bool vec,
                                      bool packed, void* partial, hipStream_t st) {
   uint32_t grid = 0;
-#define CALL(G)                                                                                       \
+  constexpr int kWide = 1024;
+#define LAUNCH(G, T)                                                                                  \
   {                                                                                                   \
-    constexpr int GPW = (G == 256) ? 1 : kWG / G;                                                     \
-    grid = xcd_grid(((uint64_t)n_idx + GPW - 1) / GPW, kMaxNormGrid);                                 \
-    hipLaunchKernelGGL((k_mixed_recover<G, STORE, NORM>), dim3(grid), dim3(kWG), 0, st, (float*)x,    \
+    grid = xcd_grid(((uint64_t)n_idx + (T / G) - 1) / (T / G), kMaxNormGrid);                         \
+    hipLaunchKernelGGL((k_mixed_recover<G, T, STORE, NORM>), dim3(grid), dim3(T), 0, st, (float*)x,   \
                        (const uint16_t*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, vec,       \
                        packed, (double*)partial);                                                     \
   }
+#define CALL(G)                                              \
+  if (((uint64_t)n_idx * G + kWG - 1) / kWG >= 8192)         \
+    LAUNCH(G, kWide)                                         \
+  else                                                       \
+    LAUNCH(G, kWG)
   SCAR_FOR_GROUP(g, CALL)
 #undef CALL
+#undef LAUNCH
   return grid;
 }
 

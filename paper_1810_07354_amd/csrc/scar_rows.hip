@@ -35,20 +35,24 @@ __global__ __launch_bounds__(kWG) void k_commit(const char* __restrict__ x, char
 // Recovery and/or norm over the blocks idx[0..n_idx) (idx == NULL: blocks 0..n_idx).
 //   STORE: x_b <- c_b after the block has been measured.
 //   NORM:  partial[blockIdx.x] <- this workgroup's share of sum (c - x)^2 or sum |c - x|.
-template <int DT, int G, bool STORE, bool NORM>
-__global__ __launch_bounds__(kWG) void k_recover(char* __restrict__ x, const char* __restrict__ c,
-                                                 const uint32_t* __restrict__ idx, uint32_t n_idx,
-                                                 uint64_t n_elems, uint32_t block_len,
-                                                 uint32_t n_blocks, bool vec, bool packed,
-                                                 typename Acc<DT>::type* __restrict__ partial) {
-  constexpr int GPW = (G == 256) ? 1 : kWG / G;
+//   T:     threads per workgroup, T / G groups.  Long index lists run with 1,024 threads: a
+//          workgroup that has to come back for a second entry waits a full memory round trip
+//          in between (131,072 rows of 4 KiB: 298 us with two entries per group, 283 us with
+//          one), and a quarter of the workgroups also means a quarter of the partial sums.
+template <int DT, int G, int T, bool STORE, bool NORM>
+__global__ __launch_bounds__(T) void k_recover(char* __restrict__ x, const char* __restrict__ c,
+                                               const uint32_t* __restrict__ idx, uint32_t n_idx,
+                                               uint64_t n_elems, uint32_t block_len,
+                                               uint32_t n_blocks, bool vec, bool packed,
+                                               typename Acc<DT>::type* __restrict__ partial) {
+  constexpr int GPW = T / G;
   constexpr int E = elem_bytes(DT);
   constexpr int EPV = 16 / E;
   using acc_t = typename Acc<DT>::type;
   using word_t = typename std::conditional<E == 4, uint32_t, uint16_t>::type;
-  const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
-  const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
-  __shared__ acc_t slots[kWG / kWave];
+  const int lane = threadIdx.x & (G - 1);
+  const uint32_t grp = threadIdx.x / G;
+  __shared__ acc_t slots[T / kWave];
   acc_t acc = 0;
 
   for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
@@ -60,6 +64,18 @@ __global__ __launch_bounds__(kWG) void k_recover(char* __restrict__ x, const cha
     // packed: c holds only the listed blocks, row i = block idx[i] (rows read back from storage)
     const char* cb = packed ? c + i * (uint64_t)block_len * E : c + sp.byte_off;
     const uint32_t nvec = vec ? sp.len / EPV : 0;
+    if (nvec <= (uint32_t)G) {
+      // the usual case (the host sizes G for one 16-byte step per lane): no inner loop
+      if ((uint32_t)lane < nvec) {
+        uint4 cv[1], xv[1];
+        cv[0] = load_stream((const uint4*)cb + lane);
+        if (NORM) {
+          xv[0] = load_stream((const uint4*)xb + lane);
+          accumulate_vec<DT, 1>(acc, cv, xv);
+        }
+        if (STORE) store_stream((uint4*)xb + lane, cv[0]);
+      }
+    } else
     for (uint32_t v0 = 0; v0 < nvec; v0 += G * kUnroll) {
       uint4 xv[kUnroll], cv[kUnroll];
 #pragma unroll
@@ -88,7 +104,7 @@ __global__ __launch_bounds__(kWG) void k_recover(char* __restrict__ x, const cha
     }
   }
   if (NORM) {
-    acc = workgroup_sum(acc, slots);
+    acc = workgroup_sum<T>(acc, slots);
     if (threadIdx.x == 0) partial[blockIdx.x] = acc;
   }
 }
@@ -151,17 +167,29 @@ static void dispatch_commit(int g, const scar_layout* l, const void* x, void* c,
 }
 
 // Launches the recovery / norm kernel; returns the number of partial sums it writes.
+constexpr int kWideWG = 1024;
+constexpr uint64_t kWideFrom = 8192;   // workgroups of kWG threads from which kWideWG is used
+
+template <int DT, int G, int T, bool STORE, bool NORM>
+static uint32_t launch_recover_t(const scar_layout* l, void* x, const void* c, const uint32_t* idx,
+                                 uint32_t n_idx, uint32_t n_blocks, bool vec, bool packed, void* partial,
+                                 hipStream_t st) {
+  constexpr int GPW = T / G;
+  const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
+  const uint32_t grid = xcd_grid(need, kMaxNormGrid);
+  hipLaunchKernelGGL((k_recover<DT, G, T, STORE, NORM>), dim3(grid), dim3(T), 0, st, (char*)x,
+                     (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, vec, packed,
+                     (typename Acc<DT>::type*)partial);
+  return grid;
+}
+
 template <int DT, int G, bool STORE, bool NORM>
 static uint32_t launch_recover(const scar_layout* l, void* x, const void* c, const uint32_t* idx,
                                uint32_t n_idx, uint32_t n_blocks, bool vec, bool packed, void* partial,
                                hipStream_t st) {
-  constexpr int GPW = (G == 256) ? 1 : kWG / G;
-  const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
-  const uint32_t grid = xcd_grid(need, kMaxNormGrid);
-  hipLaunchKernelGGL((k_recover<DT, G, STORE, NORM>), dim3(grid), dim3(kWG), 0, st, (char*)x,
-                     (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, vec, packed,
-                     (typename Acc<DT>::type*)partial);
-  return grid;
+  if (((uint64_t)n_idx * G + kWG - 1) / kWG >= kWideFrom)
+    return launch_recover_t<DT, G, kWideWG, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
+  return launch_recover_t<DT, G, kWG, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
 }
 
 template <int DT, bool STORE, bool NORM>
