@@ -5,7 +5,8 @@ The oracle cannot run 2 x 4 GiB in seconds, so it checks what it can compute one
 the scores of ~1,000 sampled blocks, the whole top-k on the GPU's scores (1M keys), the
 commit on the sampled blocks, the norm over all 131,072 lost blocks - and properties that
 hold at any size cover the rest (every byte outside K / S unchanged, every byte inside
-copied, sum of scores = squared full-recovery norm)."""
+copied, sum of scores = squared full-recovery norm).  The by-layer variant of the store has
+only 96 blocks, so there the oracle runs the whole cycle on the full host copy."""
 import numpy as np
 import pytest
 import torch
@@ -93,5 +94,55 @@ def test_flat_store_full_size(dtype):
         assert torch.equal(bits(x), bits(x_before))
         if dtype != wl.F32_BF16C:
             np.testing.assert_array_equal(rows_to_host(x, lost[:256]), hc[:256 * L])
+    finally:
+        oracle.set_num_threads(1)
+
+
+def test_by_layer_store_full_size():
+    """The by-layer benchmark workload (2^30 f32 in 96 tensors of very unequal length) through
+    the variable-length entry points; here the oracle runs the whole cycle on the full store."""
+    print("by-layer full size: generate", flush=True)
+    sizes = wl.mixed_layer_sizes(96, N_ELEMS, seed=6)
+    sizes[np.argmax(sizes)] += N_ELEMS - sizes.sum()
+    off_h = np.concatenate([[0], np.cumsum(sizes)]).astype(np.uint64)
+    nb = sizes.size
+    x, c = wl.flat_like_torch(DEV, seed=4, n_elems=N_ELEMS)
+    for j in range(3):
+        wl.drift_torch(x, 7000 + j, 0.10, 1024)
+    off = torch.from_numpy(off_h.astype(np.int64)).to(DEV)
+    k = wl.k_of_fraction(0.10, nb)
+    lost = wl.random_lost_blocks(nb, 12, 4 + 1000)
+    ws, ws_sel = scar.new_var_workspace(nb, DEV), scar.new_workspace(nb, DEV)
+    hx, hc = x.cpu().numpy(), c.cpu().numpy()
+    oracle.set_num_threads(8)
+    try:
+        print("scores", flush=True)
+        s = scar.var_block_scores(x, c, off, ws)
+        s_ref = oracle.var_block_scores(wl.F32, hx, hc, off_h)
+        s_h = s.cpu().numpy()
+        np.testing.assert_allclose(s_h.astype(np.float64), s_ref, rtol=REL_TOL, atol=0)
+
+        print("select", flush=True)
+        idx = scar.select_topk(s, k, ws_sel)
+        idx_h = idx_host(idx)
+        np.testing.assert_array_equal(idx_h, oracle.select_topk(s_h.astype(np.float64), k))
+
+        print("commit", flush=True)
+        scar.var_checkpoint_commit(x, c, off, idx, ws)
+        oracle.var_checkpoint_commit(wl.F32, hx, hc, off_h, idx_h)
+        assert torch.equal(c.cpu(), torch.from_numpy(hc))
+        assert torch.equal(x.cpu(), torch.from_numpy(hx))
+
+        print("recover", flush=True)
+        full = scar.read_norm(scar.var_perturbation_norm(x, c, off, None, ws))
+        want_full = oracle.var_perturbation_norm(wl.F32, hx, hc, off_h)
+        assert abs(full[1] - want_full[1]) <= REL_TOL * want_full[1]
+        got = scar.read_norm(scar.var_partial_recover(x, c, off, idx_dev(lost), ws))
+        want = oracle.var_partial_recover(wl.F32, hx, hc, off_h, lost)
+        assert abs(got[0] - want[0]) <= REL_TOL * want[0]
+        assert abs(got[1] - want[1]) <= REL_TOL * want[1]
+        assert got[1] <= full[1] * (1 + REL_TOL)                      # Theorem 4.1
+        assert torch.equal(x.cpu(), torch.from_numpy(hx))
+        assert torch.equal(c.cpu(), torch.from_numpy(hc))
     finally:
         oracle.set_num_threads(1)
