@@ -122,9 +122,9 @@ struct Key<SRC_MASK> {  // only classified, never histogrammed
   __device__ static type load(const KeyArgs& a, uint64_t i) { return ((const uint8_t*)a.ptr)[i] ? 1u : 0u; }
 };
 
-// Exclusive prefix sum of v over the workgroup in thread order; *total gets the sum.
-// `slots` is LDS for kWG / kWave + 1 values.
-template <typename T>
+// Exclusive prefix sum of v over a workgroup of NT threads in thread order; *total gets the
+// sum.  `slots` is LDS for NT / kWave + 1 values.
+template <int NT = kWG, typename T>
 __device__ __forceinline__ T workgroup_exclusive_scan(T v, T* slots, T* total) {
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   T inc = v;
@@ -138,7 +138,7 @@ __device__ __forceinline__ T workgroup_exclusive_scan(T v, T* slots, T* total) {
   __syncthreads();
   T base = 0, sum = 0;
 #pragma unroll
-  for (int w = 0; w < kWG / kWave; ++w) {
+  for (int w = 0; w < NT / kWave; ++w) {
     if (w < wave) base += slots[w];
     sum += slots[w];
   }
@@ -156,13 +156,14 @@ __global__ __launch_bounds__(kWG) void k_select_clear(SelectWs* ws, uint32_t k) 
 
 // Given the finished histogram of one digit and the state before that digit, walk the
 // bins from the top down to the one that holds the k_rem-th largest remaining key.
-// Every thread of the workgroup gets the state after the digit.  `scratch` is LDS for
-// kWG / kWave + 1 counters, `result` LDS for one state.
+// Every thread of the workgroup (NT threads) gets the state after the digit.  `scratch` is
+// LDS for NT / kWave + 1 counters, `result` LDS for one state.
+template <int NT = kWG>
 __device__ __forceinline__ SelectState next_state(const uint32_t* __restrict__ gh, int bits,
                                                   const SelectState cur, uint32_t* scratch,
                                                   SelectState* result) {
   const int nbins = 1 << bits;
-  constexpr int kOwn = kMaxBins / kWG;  // thread t owns bins nbins-1-8t ... nbins-8-8t
+  constexpr int kOwn = kMaxBins / NT;  // thread t owns bins nbins-1-kOwn*t ... nbins-kOwn-kOwn*t
   uint32_t own[kOwn];
   uint32_t cnt = 0;
 #pragma unroll
@@ -172,7 +173,7 @@ __device__ __forceinline__ SelectState next_state(const uint32_t* __restrict__ g
     cnt += own[j];
   }
   uint32_t total;
-  uint32_t above = workgroup_exclusive_scan(cnt, scratch, &total);
+  uint32_t above = workgroup_exclusive_scan<NT>(cnt, scratch, &total);
   if (above < cur.k_rem && cur.k_rem <= above + cnt) {  // true in exactly one thread
 #pragma unroll
     for (int j = 0; j < kOwn; ++j) {
@@ -361,22 +362,23 @@ __global__ __launch_bounds__(kWG) void k_compact_write(const KeyArgs src, uint32
   }
 }
 
-// Whole selection in one workgroup for small stores (n <= kSmallSelect): keys stay in
-// registers (kSmallKeys consecutive keys per thread), histograms in LDS, one launch
-// instead of six or nine.
+// Whole selection in one workgroup of 1,024 threads for small stores (n <= kSmallSelect):
+// keys stay in registers (up to kSmallKeys consecutive keys per thread), histograms in LDS,
+// one launch instead of six or nine.
 constexpr uint32_t kSmallSelect = 8192;
+constexpr int kSmallWG = 1024;
 template <int SRC>
-__global__ __launch_bounds__(kWG) void k_select_small(const KeyArgs scores, uint32_t n,
-                                                      uint32_t k, uint32_t* __restrict__ out_idx) {
+__global__ __launch_bounds__(kSmallWG) void k_select_small(const KeyArgs scores, uint32_t n,
+                                                           uint32_t k, uint32_t* __restrict__ out_idx) {
   using K = Key<SRC>;
   using key_t = typename K::type;
-  constexpr int kSmallKeys = kSmallSelect / kWG;
+  constexpr int kSmallKeys = kSmallSelect / kSmallWG;
   __shared__ uint32_t lh[kMaxBins];
-  __shared__ uint32_t scratch[kWG / kWave + 1];
+  __shared__ uint32_t scratch[kSmallWG / kWave + 1];
   __shared__ SelectState shared_state;
-  // thread t holds the kpt consecutive keys from t * kpt on (kpt = ceil(n / 256) <= 32), so
+  // thread t holds the kpt consecutive keys from t * kpt on (kpt = ceil(n / 1024) <= 8), so
   // every thread has work whatever n is, and index order is thread order
-  const uint32_t kpt = (n + kWG - 1) / kWG;
+  const uint32_t kpt = (n + kSmallWG - 1) / kSmallWG;
   const uint32_t base = threadIdx.x * kpt;
   key_t key[kSmallKeys];
 #pragma unroll
@@ -386,7 +388,7 @@ __global__ __launch_bounds__(kWG) void k_select_small(const KeyArgs scores, uint
   SelectState cur;
   cur.prefix = 0, cur.k_rem = k, cur.pad = 0;
   for (int pass = 0; pass < K::passes; ++pass) {
-    for (int b = threadIdx.x; b < kMaxBins; b += kWG) lh[b] = 0;
+    for (int b = threadIdx.x; b < kMaxBins; b += kSmallWG) lh[b] = 0;
     __syncthreads();
     const int shift = K::shift(pass), bits = K::bits(pass);
     const uint32_t mask = (1u << bits) - 1;
@@ -396,7 +398,7 @@ __global__ __launch_bounds__(kWG) void k_select_small(const KeyArgs scores, uint
       if ((uint32_t)j < kpt && base + j < n && match) atomicAdd(&lh[(uint32_t)(key[j] >> shift) & mask], 1u);
     }
     __syncthreads();
-    cur = next_state(lh, bits, cur, scratch, &shared_state);
+    cur = next_state<kSmallWG>(lh, bits, cur, scratch, &shared_state);
     __syncthreads();
   }
   const key_t T = (key_t)cur.prefix;
@@ -406,7 +408,7 @@ __global__ __launch_bounds__(kWG) void k_select_small(const KeyArgs scores, uint
   for (int j = 0; j < kSmallKeys; ++j)
     if ((uint32_t)j < kpt && base + j < n) cnt += key[j] > T ? 1u : (key[j] == T ? (1u << 16) : 0u);
   uint32_t total;
-  const uint32_t ex = workgroup_exclusive_scan(cnt, scratch, &total);
+  const uint32_t ex = workgroup_exclusive_scan<kSmallWG>(cnt, scratch, &total);
   uint32_t n_above = ex & 0xffffu, n_equal = ex >> 16;
 #pragma unroll
   for (int j = 0; j < kSmallKeys; ++j) {
@@ -452,7 +454,7 @@ template <int SRC>
 static void run_select(const KeyArgs scores, uint32_t n, uint32_t k, uint32_t* out_idx, void* workspace,
                        hipStream_t st) {
   if (n <= kSmallSelect) {
-    hipLaunchKernelGGL((k_select_small<SRC>), dim3(1), dim3(kWG), 0, st, scores, n, k, out_idx);
+    hipLaunchKernelGGL((k_select_small<SRC>), dim3(1), dim3(kSmallWG), 0, st, scores, n, k, out_idx);
     return;
   }
   SelectWs* ws = (SelectWs*)workspace;
