@@ -93,3 +93,27 @@ def test_mixed_three_cycles_and_precision_bound():
     assert 0 < left[1] <= 2.0 ** -8 * float(np.linalg.norm(hx.astype(np.float64)))
     back = c.float()
     assert torch.all((back - x).abs() <= x.abs() * 2.0 ** -8)
+
+
+@pytest.mark.parametrize("L,nb", [(24, 600_000), (1024, 40_000)])
+def test_mixed_recover_over_long_index_lists(L, nb):
+    # long index lists run the recovery kernel with larger workgroups
+    n = L * nb - L // 2
+    hx, hc = make(n, 5 * L)
+    x, c = to_dev(hx, wl.F32), to_dev(hc, wl.BF16)
+    r = np.random.default_rng(L + nb)
+    S = np.unique(np.append(r.permutation(nb)[: (3 * nb) // 4], nb - 1)).astype(np.uint32)
+    r.shuffle(S)
+    print("mixed long list L=%d n_idx=%d" % (L, S.size), flush=True)
+    ws = scar.new_workspace(nb, DEV)
+    oracle.set_num_threads(8)
+    try:
+        full = scar.read_norm(scar.perturbation_norm(x, c, L, None, ws))
+        assert_norm_matches(full, oracle.perturbation_norm(MIX, hx, hc, L), wl.F32)
+        got = scar.read_norm(scar.partial_recover(x, c, L, idx_dev(S), ws))
+        want = oracle.partial_recover(MIX, hx, hc, L, S)
+    finally:
+        oracle.set_num_threads(1)
+    assert_norm_matches(got, want, wl.F32)
+    np.testing.assert_array_equal(to_host(x), hx)
+    np.testing.assert_array_equal(to_host(c), hc)

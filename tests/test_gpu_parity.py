@@ -169,6 +169,34 @@ def test_commit_and_recover(dtype, L):
     np.testing.assert_array_equal(to_host(dx), x)
 
 
+@pytest.mark.parametrize("dtype,L,nb", [(F32, 24, 600_000), (BF16, 40, 600_000), (I32, 8, 1_500_000),
+                                        (F32, 1024, 40_000), (I32, 7, 300_000)])
+def test_recover_and_norm_over_long_index_lists(dtype, L, nb):
+    # Long index lists run the recovery kernel with larger workgroups (several groups per
+    # workgroup, every group width); results must not depend on that.
+    n_elems = L * nb - (L // 2)
+    x, c = make_store(dtype, n_elems, seed=3 * L + dtype)
+    r = np.random.default_rng(L + nb)
+    S = np.unique(np.append(r.permutation(nb)[: (3 * nb) // 4], nb - 1)).astype(np.uint32)
+    r.shuffle(S)                                                      # unsorted, holds the tail block
+    print("long list dtype=%d L=%d n_idx=%d" % (dtype, L, S.size), flush=True)
+    dx, dc = to_dev(x, dtype), to_dev(c, dtype)
+    ws = scar.new_workspace(nb, DEV)
+    oracle.set_num_threads(8)
+    try:
+        pre = scar.read_norm(scar.perturbation_norm(dx, dc, L, idx_dev(S), ws))
+        full = scar.read_norm(scar.perturbation_norm(dx, dc, L, None, ws))
+        assert_norm_matches(full, oracle.perturbation_norm(dtype, x, c, L), dtype)
+        nrm = scar.read_norm(scar.partial_recover(dx, dc, L, idx_dev(S), ws))
+        want = oracle.partial_recover(dtype, x, c, L, S)
+    finally:
+        oracle.set_num_threads(1)
+    assert_norm_matches(nrm, want, dtype)
+    assert pre == nrm
+    np.testing.assert_array_equal(to_host(dx), x)
+    np.testing.assert_array_equal(to_host(dc), c)
+
+
 @pytest.mark.parametrize("dtype", [F32, I32])
 def test_invariants_on_the_gpu(dtype):
     L = 96
