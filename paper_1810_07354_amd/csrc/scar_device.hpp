@@ -48,25 +48,29 @@ __device__ __forceinline__ uint32_t xcd_contiguous_block_id() {
 
 __device__ __forceinline__ float sq(float d) { return d * d; }
 
+// Sums of squares are written with explicit fused multiply-adds, so that every kernel that
+// measures a block rounds in the same places whatever else it does with the data (the norm
+// alone and the norm fused into the recovery agree bit for bit).
+
 // Four float32 lanes of a 16-byte vector.
 __device__ __forceinline__ float sqdiff_f32(const uint4& a, const uint4& b) {
-  float s = sq(__uint_as_float(a.x) - __uint_as_float(b.x));
-  s += sq(__uint_as_float(a.y) - __uint_as_float(b.y));
-  s += sq(__uint_as_float(a.z) - __uint_as_float(b.z));
-  s += sq(__uint_as_float(a.w) - __uint_as_float(b.w));
-  return s;
+  const float d0 = __uint_as_float(a.x) - __uint_as_float(b.x);
+  const float d1 = __uint_as_float(a.y) - __uint_as_float(b.y);
+  const float d2 = __uint_as_float(a.z) - __uint_as_float(b.z);
+  const float d3 = __uint_as_float(a.w) - __uint_as_float(b.w);
+  return __builtin_fmaf(d3, d3, __builtin_fmaf(d2, d2, __builtin_fmaf(d1, d1, d0 * d0)));
 }
 
 // A 32-bit word holds two bfloat16; each widens exactly to float32 by a shift or a mask.
 __device__ __forceinline__ float sqdiff_bf16x2(uint32_t a, uint32_t b) {
-  float lo = __uint_as_float(a << 16) - __uint_as_float(b << 16);
-  float hi = __uint_as_float(a & 0xffff0000u) - __uint_as_float(b & 0xffff0000u);
-  return lo * lo + hi * hi;
+  const float lo = __uint_as_float(a << 16) - __uint_as_float(b << 16);
+  const float hi = __uint_as_float(a & 0xffff0000u) - __uint_as_float(b & 0xffff0000u);
+  return __builtin_fmaf(hi, hi, lo * lo);
 }
 
 __device__ __forceinline__ float sqdiff_bf16(const uint4& a, const uint4& b) {
-  return sqdiff_bf16x2(a.x, b.x) + sqdiff_bf16x2(a.y, b.y) + sqdiff_bf16x2(a.z, b.z) +
-         sqdiff_bf16x2(a.w, b.w);
+  return (sqdiff_bf16x2(a.x, b.x) + sqdiff_bf16x2(a.y, b.y)) +
+         (sqdiff_bf16x2(a.z, b.z) + sqdiff_bf16x2(a.w, b.w));
 }
 
 // |a - b| of two int32 held in uint32: the true difference is below 2^32, so the
@@ -164,17 +168,42 @@ __device__ __forceinline__ BlockSpan block_span(uint64_t b, uint64_t n_elems, ui
   return {lo * (uint64_t)ebytes, (uint32_t)(hi - lo)};
 }
 
+// How a row that need not start on a 16-byte boundary is walked: `head` single elements up
+// to the next boundary, then `nvec` 16-byte steps, then the remaining elements.  The two
+// streams must sit at the same offset within their 16-byte lines; if they do not, the whole
+// row is walked element by element.  E = element size in bytes (pointers are E-aligned).
+struct RowSplit {
+  uint32_t head, nvec;
+};
+
+template <int E>
+__device__ __forceinline__ RowSplit row_split(const void* a, const void* b, uint32_t len) {
+  const uint32_t ma = (uint32_t)((uintptr_t)a & 15), mb = (uint32_t)((uintptr_t)b & 15);
+  if (ma != mb) return {len, 0};
+  uint32_t head = ((16 - ma) & 15) / E;
+  if (head > len) head = len;
+  return {head, (len - head) / (16 / E)};
+}
+
 // Distance term of one block, spread over the G lanes of a group; each lane returns its
-// share.  `vec` says that both block starts are 16-byte aligned.
-template <int DT, int G>
+// share.  VEC: every block of both streams starts 16-byte aligned and is a whole number of
+// 16-byte steps; otherwise each row is split as row_split says.
+template <int DT, int G, bool VEC>
 __device__ __forceinline__ typename Acc<DT>::type block_distance(const char* xb, const char* cb,
-                                                                 uint32_t len, int lane, bool vec) {
+                                                                 uint32_t len, int lane) {
   constexpr int E = elem_bytes(DT);
   constexpr int EPV = 16 / E;
   typename Acc<DT>::type acc = 0;
-  const uint32_t nvec = vec ? len / EPV : 0;
-  const uint4* xv = (const uint4*)xb;
-  const uint4* cv = (const uint4*)cb;
+  uint32_t head = 0, nvec;
+  if constexpr (VEC) {
+    nvec = len / EPV;
+  } else {
+    const RowSplit rs = row_split<E>(xb, cb, len);
+    head = rs.head, nvec = rs.nvec;
+    for (uint32_t j = lane; j < head; j += G) accumulate_elem<DT>(acc, xb, cb, j);
+  }
+  const uint4* xv = (const uint4*)(xb + (size_t)head * E);
+  const uint4* cv = (const uint4*)(cb + (size_t)head * E);
   for (uint32_t v0 = 0; v0 < nvec; v0 += G * kUnroll) {
     uint4 a[kUnroll], b[kUnroll];
 #pragma unroll
@@ -190,18 +219,28 @@ __device__ __forceinline__ typename Acc<DT>::type block_distance(const char* xb,
     }
     accumulate_vec<DT, kUnroll>(acc, a, b);
   }
-  for (uint32_t j = nvec * EPV + lane; j < len; j += G) accumulate_elem<DT>(acc, xb, cb, j);
+  for (uint32_t j = head + nvec * EPV + lane; j < len; j += G) accumulate_elem<DT>(acc, xb, cb, j);
   return acc;
 }
 
 // Copy one block src -> dst (and to dst2 if not NULL), spread over a group.  W is the
 // word type of the element-wise path (uint32_t for 4-byte elements, uint16_t for 2-byte).
+// vec: src and dst start 16-byte aligned; otherwise the row is split as row_split says.
+// vec2 (only with vec): dst2 can take the same 16-byte steps.
 template <int G, typename W>
 __device__ __forceinline__ void block_copy(const char* src, char* dst, char* dst2, uint32_t nbytes,
                                            int lane, bool vec, bool vec2) {
-  const uint32_t nvec = vec ? nbytes / 16 : 0;
-  const uint4* s = (const uint4*)src;
-  uint4* d = (uint4*)dst;
+  const uint32_t nword = nbytes / sizeof(W);
+  uint32_t head = 0, nvec;
+  if (vec) {
+    nvec = nbytes / 16;
+  } else {
+    const RowSplit rs = row_split<sizeof(W)>(src, dst, nword);
+    head = rs.head, nvec = rs.nvec;
+    for (uint32_t h = lane; h < head; h += G) ((W*)dst)[h] = ((const W*)src)[h];
+  }
+  const uint4* s = (const uint4*)(src + (size_t)head * sizeof(W));
+  uint4* d = (uint4*)(dst + (size_t)head * sizeof(W));
   for (uint32_t v0 = 0; v0 < nvec; v0 += G * kUnroll) {
     uint4 a[kUnroll];
 #pragma unroll
@@ -218,13 +257,12 @@ __device__ __forceinline__ void block_copy(const char* src, char* dst, char* dst
       }
     }
   }
-  // what the 16-byte steps did not cover (everything, on the element-wise path)
-  const uint32_t nword = nbytes / sizeof(W);
-  const uint32_t done = nvec * (16 / sizeof(W));
+  // what the 16-byte steps did not cover
   const W* sw = (const W*)src;
-  for (uint32_t h = done + lane; h < nword; h += G) ((W*)dst)[h] = sw[h];
+  for (uint32_t h = head + nvec * (16 / sizeof(W)) + lane; h < nword; h += G) ((W*)dst)[h] = sw[h];
   if (dst2) {
-    for (uint32_t h = (vec2 ? done : 0) + lane; h < nword; h += G) ((W*)dst2)[h] = sw[h];
+    const uint32_t done2 = vec2 ? nvec * (16 / sizeof(W)) : 0;   // vec2 implies head == 0
+    for (uint32_t h = done2 + lane; h < nword; h += G) ((W*)dst2)[h] = sw[h];
   }
 }
 

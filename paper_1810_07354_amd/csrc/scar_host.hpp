@@ -26,8 +26,8 @@ inline uint64_t layout_blocks(const scar_layout* l) {
 }
 
 // Group size for blocks of `block_len` elements: the power of two that gives each lane
-// about `per_lane` loads per stream (16-byte loads on the vector path, element loads
-// otherwise).  The score kernel reduces inside a group, so it offers {1..64, 256} and
+// about `per_lane` loads per stream (16-byte loads when the streams allow them - by16 -,
+// element loads otherwise).  The score kernel reduces inside a group, so it offers {1..64, 256} and
 // wants four loads per lane; the row kernels only move data and do best with one
 // (measured on 4 KiB rows: 5.66 TB/s with a whole workgroup per row against 5.33 TB/s with
 // one wavefront per row), and offer every power of two up to 256.
@@ -37,9 +37,16 @@ inline int pick_group_units(uint64_t units, int per_lane, bool allow_128) {
   while (g < 256 && (uint64_t)g < want) g <<= 1;
   return (g == 128 && !allow_128) ? 256 : g;
 }
-inline int pick_group(uint32_t block_len, int ebytes, bool vec, int per_lane, bool allow_128) {
-  const uint64_t units = vec ? ((uint64_t)block_len * ebytes + 15) / 16 : block_len;
+inline int pick_group(uint32_t block_len, int ebytes, bool by16, int per_lane, bool allow_128) {
+  const uint64_t units = by16 ? ((uint64_t)block_len * ebytes + 15) / 16 : block_len;
   return pick_group_units(units, per_lane, allow_128);
+}
+
+// True if a and b sit at the same offset within their 16-byte lines: then rows of the two
+// streams can be walked with 16-byte steps between a few leading and trailing elements,
+// whatever the row length.
+inline bool co_aligned(const void* a, const void* b) {
+  return ((reinterpret_cast<uintptr_t>(a) ^ reinterpret_cast<uintptr_t>(b)) & 15) == 0;
 }
 
 // ---- workspace layout ---------------------------------------------------------------

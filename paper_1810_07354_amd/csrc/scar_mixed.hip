@@ -41,10 +41,11 @@ __device__ __forceinline__ uint32_t round_bf16(uint32_t u) {
 
 // Sum of squared differences of one unit: xv holds 4 floats, cv the matching 4 bfloat16.
 __device__ __forceinline__ float sqdiff_unit(const uint4& xv, const uint2& cv) {
-  float s = sq(__uint_as_float(xv.x) - widen_lo(cv.x));
-  s += sq(__uint_as_float(xv.y) - widen_hi(cv.x));
-  s += sq(__uint_as_float(xv.z) - widen_lo(cv.y));
-  s += sq(__uint_as_float(xv.w) - widen_hi(cv.y));
+  const float d0 = __uint_as_float(xv.x) - widen_lo(cv.x);
+  const float d1 = __uint_as_float(xv.y) - widen_hi(cv.x);
+  const float d2 = __uint_as_float(xv.z) - widen_lo(cv.y);
+  const float d3 = __uint_as_float(xv.w) - widen_hi(cv.y);
+  const float s = __builtin_fmaf(d3, d3, __builtin_fmaf(d2, d2, __builtin_fmaf(d1, d1, d0 * d0)));
   return s;
 }
 

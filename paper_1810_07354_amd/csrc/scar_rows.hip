@@ -32,38 +32,22 @@ __global__ __launch_bounds__(kWG) void k_commit(const char* __restrict__ x, char
   }
 }
 
-// Recovery and/or norm over the blocks idx[0..n_idx) (idx == NULL: blocks 0..n_idx).
-//   STORE: x_b <- c_b after the block has been measured.
-//   NORM:  partial[blockIdx.x] <- this workgroup's share of sum (c - x)^2 or sum |c - x|.
-//   T:     threads per workgroup, T / G groups.  Long index lists run with 1,024 threads: a
-//          workgroup that has to come back for a second entry waits a full memory round trip
-//          in between (131,072 rows of 4 KiB: 298 us with two entries per group, 283 us with
-//          one), and a quarter of the workgroups also means a quarter of the partial sums.
-template <int DT, int G, int T, bool STORE, bool NORM>
-__global__ __launch_bounds__(T) void k_recover(char* __restrict__ x, const char* __restrict__ c,
-                                               const uint32_t* __restrict__ idx, uint32_t n_idx,
-                                               uint64_t n_elems, uint32_t block_len,
-                                               uint32_t n_blocks, bool vec, bool packed,
-                                               typename Acc<DT>::type* __restrict__ partial) {
-  constexpr int GPW = T / G;
+// One row of the recovery / norm pass, spread over a group of G lanes: acc gets this lane's
+// share of sum (c - x)^2 or sum |c - x| (NORM), then x <- c (STORE).
+//   VEC: both rows start 16-byte aligned and are whole 16-byte steps (up to a tail that only
+//   the store's last, short block has); otherwise the row is split as row_split says.
+template <int DT, int G, bool STORE, bool NORM, bool VEC>
+__device__ __forceinline__ void recover_row(char* xb, const char* cb, uint32_t len, int lane,
+                                            typename Acc<DT>::type& acc) {
   constexpr int E = elem_bytes(DT);
   constexpr int EPV = 16 / E;
-  using acc_t = typename Acc<DT>::type;
   using word_t = typename std::conditional<E == 4, uint32_t, uint16_t>::type;
-  const int lane = threadIdx.x & (G - 1);
-  const uint32_t grp = threadIdx.x / G;
-  __shared__ acc_t slots[T / kWave];
-  acc_t acc = 0;
-
-  for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
-       i += (uint64_t)gridDim.x * GPW) {
-    const uint32_t b = idx ? idx[i] : (uint32_t)i;
-    if (b >= n_blocks) continue;
-    const BlockSpan sp = block_span(b, n_elems, block_len, E);
-    char* xb = x + sp.byte_off;
-    // packed: c holds only the listed blocks, row i = block idx[i] (rows read back from storage)
-    const char* cb = packed ? c + i * (uint64_t)block_len * E : c + sp.byte_off;
-    const uint32_t nvec = vec ? sp.len / EPV : 0;
+  auto element = [&](uint32_t j) {
+    if (NORM) accumulate_elem<DT>(acc, cb, xb, j);
+    if (STORE) ((word_t*)xb)[j] = ((const word_t*)cb)[j];
+  };
+  uint32_t head = 0, nvec = len / EPV;
+  if constexpr (VEC) {
     if (nvec <= (uint32_t)G) {
       // the usual case (the host sizes G for one 16-byte step per lane): no inner loop
       if ((uint32_t)lane < nvec) {
@@ -75,33 +59,70 @@ __global__ __launch_bounds__(T) void k_recover(char* __restrict__ x, const char*
         }
         if (STORE) store_stream((uint4*)xb + lane, cv[0]);
       }
-    } else
-    for (uint32_t v0 = 0; v0 < nvec; v0 += G * kUnroll) {
-      uint4 xv[kUnroll], cv[kUnroll];
+      for (uint32_t j = nvec * EPV + lane; j < len; j += G) element(j);
+      return;
+    }
+  } else {
+    const RowSplit rs = row_split<E>(xb, cb, len);
+    head = rs.head, nvec = rs.nvec;
+    for (uint32_t j = lane; j < head; j += G) element(j);
+  }
+  uint4* xvp = (uint4*)(xb + (size_t)head * E);
+  const uint4* cvp = (const uint4*)(cb + (size_t)head * E);
+  for (uint32_t v0 = 0; v0 < nvec; v0 += G * kUnroll) {
+    uint4 xv[kUnroll], cv[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint32_t v = v0 + u * G + lane;
+      if (v < nvec) {
+        cv[u] = load_stream(cvp + v);
+        xv[u] = NORM ? load_stream((const uint4*)xvp + v) : make_uint4(0, 0, 0, 0);
+      } else {
+        cv[u] = make_uint4(0, 0, 0, 0);
+        xv[u] = make_uint4(0, 0, 0, 0);
+      }
+    }
+    if (NORM) accumulate_vec<DT, kUnroll>(acc, cv, xv);
+    if (STORE) {
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {
         const uint32_t v = v0 + u * G + lane;
-        if (v < nvec) {
-          cv[u] = load_stream((const uint4*)cb + v);
-          xv[u] = NORM ? load_stream((const uint4*)xb + v) : make_uint4(0, 0, 0, 0);
-        } else {
-          cv[u] = make_uint4(0, 0, 0, 0);
-          xv[u] = make_uint4(0, 0, 0, 0);
-        }
-      }
-      if (NORM) accumulate_vec<DT, kUnroll>(acc, cv, xv);
-      if (STORE) {
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-          const uint32_t v = v0 + u * G + lane;
-          if (v < nvec) store_stream((uint4*)xb + v, cv[u]);
-        }
+        if (v < nvec) store_stream(xvp + v, cv[u]);
       }
     }
-    for (uint32_t j = nvec * EPV + lane; j < sp.len; j += G) {
-      if (NORM) accumulate_elem<DT>(acc, cb, xb, j);
-      if (STORE) ((word_t*)xb)[j] = ((const word_t*)cb)[j];
-    }
+  }
+  for (uint32_t j = head + nvec * EPV + lane; j < len; j += G) element(j);
+}
+
+// Recovery and/or norm over the blocks idx[0..n_idx) (idx == NULL: blocks 0..n_idx).
+//   STORE: x_b <- c_b after the block has been measured.
+//   NORM:  partial[blockIdx.x] <- this workgroup's share of sum (c - x)^2 or sum |c - x|.
+//   T:     threads per workgroup, T / G groups.  Long index lists run with 1,024 threads: a
+//          workgroup that has to come back for a second entry waits a full memory round trip
+//          in between (131,072 rows of 4 KiB: 298 us with two entries per group, 283 us with
+//          one), and a quarter of the workgroups also means a quarter of the partial sums.
+template <int DT, int G, int T, bool STORE, bool NORM, bool VEC>
+__global__ __launch_bounds__(T) void k_recover(char* __restrict__ x, const char* __restrict__ c,
+                                               const uint32_t* __restrict__ idx, uint32_t n_idx,
+                                               uint64_t n_elems, uint32_t block_len,
+                                               uint32_t n_blocks, bool packed,
+                                               typename Acc<DT>::type* __restrict__ partial) {
+  constexpr int GPW = T / G;
+  constexpr int E = elem_bytes(DT);
+  using acc_t = typename Acc<DT>::type;
+  const int lane = threadIdx.x & (G - 1);
+  const uint32_t grp = threadIdx.x / G;
+  __shared__ acc_t slots[T / kWave];
+  acc_t acc = 0;
+
+  for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
+       i += (uint64_t)gridDim.x * GPW) {
+    const uint32_t b = idx ? idx[i] : (uint32_t)i;
+    if (b >= n_blocks) continue;
+    const BlockSpan sp = block_span(b, n_elems, block_len, E);
+    // packed: c holds only the listed blocks, row i = block idx[i] (rows read back from storage)
+    const char* cb = packed ? c + i * (uint64_t)block_len * E : c + sp.byte_off;
+    recover_row<DT, G, STORE, NORM, VEC>(x + sp.byte_off, cb, sp.len, lane, acc);
   }
   if (NORM) {
     acc = workgroup_sum<T>(acc, slots);
@@ -170,15 +191,15 @@ static void dispatch_commit(int g, const scar_layout* l, const void* x, void* c,
 constexpr int kWideWG = 1024;
 constexpr uint64_t kWideFrom = 8192;   // workgroups of kWG threads from which kWideWG is used
 
-template <int DT, int G, int T, bool STORE, bool NORM>
+template <int DT, int G, int T, bool STORE, bool NORM, bool VEC>
 static uint32_t launch_recover_t(const scar_layout* l, void* x, const void* c, const uint32_t* idx,
-                                 uint32_t n_idx, uint32_t n_blocks, bool vec, bool packed, void* partial,
+                                 uint32_t n_idx, uint32_t n_blocks, bool packed, void* partial,
                                  hipStream_t st) {
   constexpr int GPW = T / G;
   const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
   const uint32_t grid = xcd_grid(need, kMaxNormGrid);
-  hipLaunchKernelGGL((k_recover<DT, G, T, STORE, NORM>), dim3(grid), dim3(T), 0, st, (char*)x,
-                     (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, vec, packed,
+  hipLaunchKernelGGL((k_recover<DT, G, T, STORE, NORM, VEC>), dim3(grid), dim3(T), 0, st, (char*)x,
+                     (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, packed,
                      (typename Acc<DT>::type*)partial);
   return grid;
 }
@@ -187,9 +208,11 @@ template <int DT, int G, bool STORE, bool NORM>
 static uint32_t launch_recover(const scar_layout* l, void* x, const void* c, const uint32_t* idx,
                                uint32_t n_idx, uint32_t n_blocks, bool vec, bool packed, void* partial,
                                hipStream_t st) {
+  if (!vec)
+    return launch_recover_t<DT, G, kWG, STORE, NORM, false>(l, x, c, idx, n_idx, n_blocks, packed, partial, st);
   if (((uint64_t)n_idx * G + kWG - 1) / kWG >= kWideFrom)
-    return launch_recover_t<DT, G, kWideWG, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
-  return launch_recover_t<DT, G, kWG, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
+    return launch_recover_t<DT, G, kWideWG, STORE, NORM, true>(l, x, c, idx, n_idx, n_blocks, packed, partial, st);
+  return launch_recover_t<DT, G, kWG, STORE, NORM, true>(l, x, c, idx, n_idx, n_blocks, packed, partial, st);
 }
 
 template <int DT, bool STORE, bool NORM>
@@ -258,7 +281,7 @@ static int recover_or_norm(bool store, bool packed, const scar_layout* layout, v
                                  n_idx, norm_out, partial, st);
   if (!aligned(x, eb) || !aligned(c, eb)) return SCAR_ERR_INVALID_ARG;
   const bool vec = aligned(x, 16) && aligned(c, 16) && ((uint64_t)layout->block_len * eb) % 16 == 0;
-  const int g = pick_group(layout->block_len, eb, vec, 1, true);
+  const int g = pick_group(layout->block_len, eb, co_aligned(x, c), 1, true);
   const uint32_t n_blocks = (uint32_t)nb;
   uint32_t n_partial = 0;
   if (store && norm_out)
@@ -290,7 +313,7 @@ extern "C" int scar_checkpoint_commit(const scar_layout* layout, const void* x, 
   const bool row16 = ((uint64_t)layout->block_len * eb) % 16 == 0;
   const bool vec = aligned(x, 16) && aligned(c, 16) && row16;
   const bool vec_st = vec && staging && aligned(staging, 16);
-  const int g = pick_group(layout->block_len, eb, vec, 1, true);
+  const int g = pick_group(layout->block_len, eb, co_aligned(x, c), 1, true);
   hipStream_t st = (hipStream_t)stream;
   if (eb == 4)
     dispatch_commit<uint32_t>(g, layout, x, c, idx, n_idx, staging, (uint32_t)nb, vec, vec_st, st);
