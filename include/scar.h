@@ -32,8 +32,10 @@
  *   - x and c must not overlap.  x, c and staging must be aligned to the element size;
  *     scores / out_idx / idx to their element type; workspace to 256 bytes.  When x and c
  *     are 16-byte aligned and block_len * element size is a multiple of 16 the kernels
- *     use 16-byte accesses; any other case is served by an element-wise path with the
- *     same results.
+ *     use 16-byte accesses throughout (fastest).  Otherwise every row is walked as a few
+ *     leading elements, a 16-byte body and a tail, which needs x and c at the same offset
+ *     within their 16-byte lines; if they are not, rows are walked element by element.
+ *     Results are the same in every case.
  *   - Index lists (idx, lost_idx) hold block numbers < n_blocks without repeats, in any
  *     order (ascending is fastest).  This is not checked on the host (the lists live in
  *     device memory); on the device an entry >= n_blocks is skipped, and a repeated
