@@ -35,7 +35,8 @@
  *     use 16-byte accesses throughout (fastest).  Otherwise every row is walked as a few
  *     leading elements, a 16-byte body and a tail, which needs x and c at the same offset
  *     within their 16-byte lines; if they are not, rows are walked element by element.
- *     Results are the same in every case.
+ *     Copies and integer results are identical in every case, float sums up to the order
+ *     of the additions.
  *   - Index lists (idx, lost_idx) hold block numbers < n_blocks without repeats, in any
  *     order (ascending is fastest).  This is not checked on the host (the lists live in
  *     device memory); on the device an entry >= n_blocks is skipped, and a repeated
