@@ -369,6 +369,43 @@ def test_random_layouts_whole_cycles():
         np.testing.assert_array_equal(to_host(x), hx)
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16, I32])
+@pytest.mark.parametrize("off_x,off_c", [(1, 1), (3, 3), (1, 2), (0, 5), (4, 0)])
+def test_misaligned_bases_whole_cycles(dtype, off_x, off_c):
+    # x and c start off_x / off_c elements into their allocations: with equal offsets rows
+    # are walked as head + 16-byte body + tail, with different ones element by element; both
+    # must give the oracle's results for every row length, with and without staging rows
+    r = np.random.default_rng(100 * off_x + off_c)
+    for L in (1, 3, 4, 6, 9, 37, 100, 250, 1000, 1024, 4100):
+        nb = 260 if L < 2000 else 40
+        n = L * nb - L // 3
+        nbk = oracle.n_blocks_of(n, L)
+        hx, hc = make_store(dtype, n, seed=L + dtype)
+        pad_x, pad_c = np.zeros(off_x, dtype=hx.dtype), np.zeros(off_c, dtype=hc.dtype)
+        x = to_dev(np.concatenate([pad_x, hx]), dtype)[off_x:]
+        c = to_dev(np.concatenate([pad_c, hc]), dtype)[off_c:]
+        print("misaligned dtype=%d L=%d offsets=(%d,%d)" % (dtype, L, off_x, off_c), flush=True)
+        ws = scar.new_workspace(nbk, DEV)
+        s = scar.block_scores(x, c, L)
+        assert_scores_match(s, oracle.block_scores(dtype, hx, hc, L), dtype)
+        K = np.unique(np.append(r.permutation(nbk)[: nbk // 3], nbk - 1)).astype(np.uint32)
+        r.shuffle(K)
+        st = torch.zeros(K.size * L + 1, dtype=x.dtype, device=DEV)[1:]      # staging off the grid too
+        scar.checkpoint_commit(x, c, L, idx_dev(K), st)
+        hst = np.zeros(K.size * L, dtype=hx.dtype)
+        oracle.checkpoint_commit(dtype, hx, hc, L, K, hst)
+        np.testing.assert_array_equal(to_host(c.contiguous()), hc)
+        np.testing.assert_array_equal(to_host(st.contiguous()), hst)
+        S = np.unique(np.append(r.permutation(nbk)[: nbk // 2], nbk - 1)).astype(np.uint32)
+        pre = scar.read_norm(scar.perturbation_norm(x, c, L, idx_dev(S), ws))
+        got = scar.read_norm(scar.partial_recover(x, c, L, idx_dev(S), ws))
+        want = oracle.partial_recover(dtype, hx, hc, L, S)
+        assert_norm_matches(got, want, dtype)
+        assert pre == got
+        np.testing.assert_array_equal(to_host(x.contiguous()), hx)
+        np.testing.assert_array_equal(to_host(c.contiguous()), hc)
+
+
 @pytest.mark.parametrize("dtype", [F32, I32])
 def test_out_of_range_list_entries_are_skipped(dtype):
     # documented device-side behaviour: an index >= n_blocks in a list is ignored
