@@ -52,6 +52,9 @@ def lib():
         L.oracle_var_checkpoint_commit.argtypes = [i32, vp, vp, vp, u32, vp, u32]
         L.oracle_var_perturbation_norm.argtypes = [i32, vp, vp, vp, u32, vp, u32, ctypes.POINTER(Norm)]
         L.oracle_var_partial_recover.argtypes = [i32, vp, vp, vp, u32, vp, u32, ctypes.POINTER(Norm)]
+        L.oracle_tv_block_scores.argtypes = [i32, vp, vp, u64, u32, vp, vp]
+        L.oracle_tv_perturbation_norm.argtypes = [i32, vp, vp, u64, u32, vp, vp, u32, ctypes.POINTER(Norm)]
+        L.oracle_tv_partial_recover.argtypes = [i32, vp, vp, u64, u32, vp, vp, u32, ctypes.POINTER(Norm)]
         L.oracle_select_round.argtypes = [u32, u32, u64, vp]
         L.oracle_select_random.argtypes = [u32, u32, u64, u64, vp]
         L.oracle_philox4x32_10.argtypes = [vp, vp, vp]
@@ -259,3 +262,41 @@ def var_partial_recover(dtype, x, c, offsets, lost):
                                             _ptr(lost), lost.size, ctypes.byref(out)),
            "oracle_var_partial_recover")
     return out.sum, out.norm, out.isum
+
+
+# ---- document-length-scaled total variation (rows of a float store are distributions) -------
+
+def _weights(w):
+    return None if w is None else np.ascontiguousarray(w, dtype=np.float32)
+
+
+def tv_block_scores(dtype, x, c, block_len, weights=None):
+    """w_b * TV(x_b, c_b) per block, TV = half the L1 distance; float64."""
+    x, c, w = _flat_x(x, dtype), _flat_c(c, dtype), _weights(weights)
+    out = np.zeros(n_blocks_of(x.size, block_len), dtype=np.float64)
+    _check(lib().oracle_tv_block_scores(dtype, _ptr(x), _ptr(c), x.size, block_len, _ptr(w), _ptr(out)),
+           "oracle_tv_block_scores")
+    return out
+
+
+def tv_perturbation_norm(dtype, x, c, block_len, weights=None, idx=None):
+    x, c, w = _flat_x(x, dtype), _flat_c(c, dtype), _weights(weights)
+    out = Norm()
+    if idx is None:
+        ptr, n = ctypes.c_void_p(0), 0
+    else:
+        idx = _idx(idx)
+        keep = idx if idx.size else np.zeros(1, dtype=np.uint32)
+        ptr, n = ctypes.c_void_p(keep.ctypes.data), idx.size
+    _check(lib().oracle_tv_perturbation_norm(dtype, _ptr(x), _ptr(c), x.size, block_len, _ptr(w), ptr, n,
+                                             ctypes.byref(out)), "oracle_tv_perturbation_norm")
+    return out.sum, out.norm, out.isum
+
+
+def tv_partial_recover(dtype, x, c, block_len, lost, weights=None):
+    x, c, w, lost = _flat_x(x, dtype), _flat_c(c, dtype), _weights(weights), _idx(lost)
+    out = Norm()
+    _check(lib().oracle_tv_partial_recover(dtype, _ptr(x), _ptr(c), x.size, block_len, _ptr(w), _ptr(lost),
+                                           lost.size, ctypes.byref(out)), "oracle_tv_partial_recover")
+    return out.sum, out.norm, out.isum
+

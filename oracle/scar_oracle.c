@@ -520,3 +520,77 @@ int oracle_var_partial_recover(int dtype, void *x, const void *c, const uint64_t
   }
   return ORACLE_OK;
 }
+
+/* ---- document-length-scaled total variation (Section 5.1 "LDA", Appendix C) ----------
+ * When the rows of a float store are distributions (a document's topic proportions), the
+ * distance of row b is w_b * TV(x_b, c_b) with TV(p, q) = 1/2 * sum_j |p_j - q_j| and w_b
+ * the length of document b; the size of a whole perturbation is the sum of the rows'
+ * distances (a positive linear combination of total-variation norms).  weights == NULL
+ * means w_b = 1 (plain total variation).  Only float stores (ORACLE_F32, ORACLE_BF16). */
+
+static int tv_dtype_ok(int dtype) { return dtype == ORACLE_F32 || dtype == ORACLE_BF16; }
+
+static double block_tv(int dtype, const void *x, const void *c, uint64_t lo, uint64_t hi) {
+  double s = 0.0;
+  for (uint64_t j = lo; j < hi; ++j) s += fabs(load_real(dtype, x, j) - load_real(dtype, c, j));
+  return 0.5 * s;
+}
+
+int oracle_tv_block_scores(int dtype, const void *x, const void *c, uint64_t n_elems,
+                           uint32_t block_len, const float *weights, double *scores) {
+  if (!tv_dtype_ok(dtype) || block_len == 0) return ORACLE_ERR_ARG;
+  if (n_elems == 0) return ORACLE_OK;
+  if (!x || !c || !scores) return ORACLE_ERR_ARG;
+  int64_t n_blocks = (int64_t)count_blocks(n_elems, block_len);
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+  for (int64_t b = 0; b < n_blocks; ++b) {
+    uint64_t lo, hi;
+    block_range((uint64_t)b, n_elems, block_len, &lo, &hi);
+    scores[b] = (weights ? (double)weights[b] : 1.0) * block_tv(dtype, x, c, lo, hi);
+  }
+  return ORACLE_OK;
+}
+
+/* sum = norm = sum over the listed blocks (all blocks if idx == NULL) of w_b * TV_b. */
+int oracle_tv_perturbation_norm(int dtype, const void *x, const void *c, uint64_t n_elems,
+                                uint32_t block_len, const float *weights, const uint32_t *idx,
+                                uint32_t n_idx, oracle_norm *out) {
+  if (!tv_dtype_ok(dtype) || block_len == 0 || !out) return ORACLE_ERR_ARG;
+  uint64_t n_blocks = count_blocks(n_elems, block_len);
+  int64_t m = idx ? (int64_t)n_idx : (int64_t)n_blocks;
+  out->sum = out->norm = 0.0;
+  out->isum = 0;
+  if (m == 0) return ORACLE_OK;
+  if (!x || !c) return ORACLE_ERR_ARG;
+  if (idx) {
+    int rc = check_indices(idx, n_idx, n_blocks);
+    if (rc) return rc;
+  }
+  double total = 0.0;
+  for (int64_t i = 0; i < m; ++i) {
+    uint64_t b = idx ? idx[i] : (uint64_t)i, lo, hi;
+    block_range(b, n_elems, block_len, &lo, &hi);
+    total += (weights ? (double)weights[b] : 1.0) * block_tv(dtype, x, c, lo, hi);
+  }
+  out->sum = out->norm = total;
+  return ORACLE_OK;
+}
+
+/* Partial recovery whose perturbation is measured in the scaled total variation. */
+int oracle_tv_partial_recover(int dtype, void *x, const void *c, uint64_t n_elems,
+                              uint32_t block_len, const float *weights, const uint32_t *lost,
+                              uint32_t n_lost, oracle_norm *norm_out) {
+  if (!tv_dtype_ok(dtype)) return ORACLE_ERR_ARG;
+  if (norm_out) {
+    if (n_lost == 0) {
+      norm_out->sum = norm_out->norm = 0.0;
+      norm_out->isum = 0;
+    } else {
+      int rc = oracle_tv_perturbation_norm(dtype, x, c, n_elems, block_len, weights, lost, n_lost,
+                                           norm_out);
+      if (rc) return rc;
+    }
+  }
+  return oracle_partial_recover(dtype, x, c, n_elems, block_len, lost, n_lost, NULL);
+}
+

@@ -53,6 +53,16 @@ MUTANTS = [
     ("random draw ignores the checkpoint number", "const uint32_t ctr[4] = {b, 0u, (uint32_t)draw, (uint32_t)(draw >> 32)};", "const uint32_t ctr[4] = {b, 0u, 0u, 0u};"),
     ("unequal blocks: score of the next block", "block_sqdist(dtype, x, c, offsets[b], offsets[b + 1]);\n  }\n  return ORACLE_OK;",
      "block_sqdist(dtype, x, c, offsets[b + 1], b + 2 <= n_blocks ? offsets[b + 2 <= n_blocks ? b + 2 : b + 1] : offsets[b + 1]);\n  }\n  return ORACLE_OK;"),
+    ("total variation without the half", "  return 0.5 * s;", "  return s;"),
+    ("total variation of squares", "s += fabs(load_real(dtype, x, j) - load_real(dtype, c, j));",
+     "s += (load_real(dtype, x, j) - load_real(dtype, c, j)) * (load_real(dtype, x, j) - load_real(dtype, c, j));"),
+    ("total variation signed", "s += fabs(load_real(dtype, x, j) - load_real(dtype, c, j));",
+     "s += load_real(dtype, x, j) - load_real(dtype, c, j);"),
+    ("document length ignored in the score", "    scores[b] = (weights ? (double)weights[b] : 1.0) * block_tv(dtype, x, c, lo, hi);",
+     "    scores[b] = block_tv(dtype, x, c, lo, hi);"),
+    ("document length of the list position", "    total += (weights ? (double)weights[b] : 1.0) * block_tv(dtype, x, c, lo, hi);",
+     "    total += (weights ? (double)weights[i] : 1.0) * block_tv(dtype, x, c, lo, hi);"),
+    ("scaled norm as a root", "  out->sum = out->norm = total;", "  out->sum = total; out->norm = sqrt(total);"),
     ("unequal blocks: commit one element short", "    if (hi > lo) memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo) * es);",
      "    if (hi > lo) memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo - 1) * es);"),
 ]

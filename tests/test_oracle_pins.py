@@ -645,3 +645,103 @@ def test_mixed_equals_float_store_when_values_are_representable():
     np.testing.assert_array_equal(x1, x2)
     with pytest.raises(oracle.OracleError):
         oracle.var_block_scores(MIX, xf, cb, np.array([0, 300], dtype=np.uint64))
+
+
+# ------------------------------------------- scaled total variation (Section 5.1, Appendix C)
+
+def one_hot(n, i):
+    v = np.zeros(n, dtype=np.float32)
+    v[i] = 1.0
+    return v
+
+
+def test_tv_of_disjoint_and_equal_distributions():
+    # TV of two distributions with disjoint support is 1, of equal ones 0; the score is the
+    # document length times that
+    x = np.concatenate([one_hot(5, 0), one_hot(5, 2), one_hot(5, 4)])
+    c = np.concatenate([one_hot(5, 1), one_hot(5, 2), one_hot(5, 0)])
+    np.testing.assert_array_equal(oracle.tv_block_scores(F32, x, c, 5), [1.0, 0.0, 1.0])
+    np.testing.assert_array_equal(oracle.tv_block_scores(F32, x, c, 5, [120, 7, 33]), [120.0, 0.0, 33.0])
+    np.testing.assert_array_equal(oracle.tv_block_scores(F32, c, x, 5, [120, 7, 33]), [120.0, 0.0, 33.0])
+
+
+def test_tv_closed_form_and_ragged_tail():
+    # x = c + a on t entries of a block  =>  TV = t * a / 2, the short tail block included
+    L, n = 8, 8 * 5 + 3
+    c = np.full(n, 0.125, dtype=np.float32)
+    x = c.copy()
+    x[0:3] += 0.25           # block 0: t = 3
+    x[17] -= 0.5             # block 2: t = 1
+    x[40:43] += 2.0 ** -10   # tail block (3 elements): t = 3
+    w = np.array([2, 3, 5, 7, 11, 13], dtype=np.float32)
+    want = np.array([3 * 0.25 / 2, 0, 0.5 / 2, 0, 0, 3 * 2.0 ** -10 / 2])
+    np.testing.assert_array_equal(oracle.tv_block_scores(F32, x, c, L), want)
+    np.testing.assert_array_equal(oracle.tv_block_scores(F32, x, c, L, w), want * w)
+
+
+def test_tv_on_normalised_counts_is_half_the_l1_of_the_counts():
+    # rows of topic counts with N = 1024 tokens each (n / N is exact in float32): the
+    # length-scaled TV of the normalised rows is exactly half the L1 distance of the counts,
+    # which is what the integer path scores (its reading of the same norm)
+    r = np.random.default_rng(5)
+    rows, topics, n_tok = 40, 16, 1024
+    c = r.multinomial(n_tok, np.full(topics, 1.0 / topics), size=rows).astype(np.int32)
+    x = c.copy()
+    for d in range(rows):
+        for _ in range(int(r.integers(0, 6))):
+            src, dst = r.choice(topics, size=2, replace=False)
+            m = min(int(x[d, src]), int(r.integers(1, 4)))
+            x[d, src] -= m
+            x[d, dst] += m
+    l1 = oracle.block_scores(I32, x.ravel(), c.ravel(), topics)
+    tv = oracle.tv_block_scores(F32, (x / n_tok).astype(np.float32).ravel(), (c / n_tok).astype(np.float32).ravel(),
+                                topics, np.full(rows, n_tok, dtype=np.float32))
+    np.testing.assert_array_equal(2 * tv, l1.astype(np.float64))
+
+
+def test_tv_is_a_metric_bounded_by_one_on_distributions():
+    r = np.random.default_rng(6)
+    L, nb = 20, 50
+    p, q, s = (r.dirichlet(np.full(L, 0.3), size=nb).astype(np.float32).ravel() for _ in range(3))
+    pq, qs, ps = (oracle.tv_block_scores(F32, a, b, L) for a, b in ((p, q), (q, s), (p, s)))
+    assert np.all(pq >= 0) and np.all(pq <= 1 + 1e-6)
+    assert np.all(ps <= pq + qs + 1e-12)                                   # triangle inequality
+    np.testing.assert_array_equal(pq, oracle.tv_block_scores(F32, q, p, L))
+    ref = 0.5 * np.abs(p.astype(np.float64) - q.astype(np.float64)).reshape(nb, L).sum(1)
+    np.testing.assert_allclose(pq, ref, rtol=1e-14)
+    # bfloat16 rows decode exactly
+    pb, qb = (np.frombuffer(a.tobytes(), dtype=np.uint16)[1::2].copy() for a in (p, q))
+    pf, qf = ((b.astype(np.uint32) << 16).view(np.float32) for b in (pb, qb))
+    np.testing.assert_array_equal(oracle.tv_block_scores(BF16, pb, qb, L), oracle.tv_block_scores(F32, pf, qf, L))
+
+
+def test_tv_norm_is_the_weighted_sum_of_the_block_distances():
+    r = np.random.default_rng(7)
+    L, nb = 12, 30
+    x = r.dirichlet(np.full(L, 0.5), size=nb).astype(np.float32).ravel()[: L * nb - 5]
+    c = r.dirichlet(np.full(L, 0.5), size=nb).astype(np.float32).ravel()[: L * nb - 5]
+    w = r.integers(1, 500, size=nb).astype(np.float32)
+    s = oracle.tv_block_scores(F32, x, c, L, w)
+    full = oracle.tv_perturbation_norm(F32, x, c, L, w)
+    assert math.isclose(full[0], s.sum(), rel_tol=1e-13) and full[0] == full[1] and full[2] == 0
+    S = np.array([29, 3, 11, 4], dtype=np.uint32)
+    part = oracle.tv_perturbation_norm(F32, x, c, L, w, S)
+    assert math.isclose(part[0], s[S].sum(), rel_tol=1e-13)
+    assert part[1] <= full[1]                                               # Theorem 4.1's analogue
+    rest = np.setdiff1d(np.arange(nb), S).astype(np.uint32)
+    assert math.isclose(part[0] + oracle.tv_perturbation_norm(F32, x, c, L, w, rest)[0], full[0], rel_tol=1e-13)
+    assert oracle.tv_perturbation_norm(F32, x, c, L, w, np.zeros(0, dtype=np.uint32)) == (0.0, 0.0, 0)
+    unweighted = oracle.tv_perturbation_norm(F32, x, c, L)
+    assert math.isclose(unweighted[0], oracle.tv_block_scores(F32, x, c, L).sum(), rel_tol=1e-13)
+    # recovery: the norm is measured before the overwrite, only the lost rows change
+    x0 = x.copy()
+    got = oracle.tv_partial_recover(F32, x, c, L, S, w)
+    assert got == part
+    keep = np.ones(x.size, dtype=bool)
+    for b in S:
+        keep[b * L:(b + 1) * L] = False
+        np.testing.assert_array_equal(x[b * L:(b + 1) * L], c[b * L:(b + 1) * L])
+    np.testing.assert_array_equal(x[keep], x0[keep])
+    assert oracle.tv_partial_recover(F32, x, c, L, S, w) == (0.0, 0.0, 0)
+    with pytest.raises(oracle.OracleError):
+        oracle.tv_block_scores(I32, x.view(np.int32), c.view(np.int32), L)
