@@ -215,6 +215,33 @@ int scar_var_perturbation_norm(const scar_var_layout* layout, const void* x, con
                                const uint32_t* idx, uint32_t n_idx, scar_norm* norm_out,
                                void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- document-length-scaled total variation (Section 5.1 "LDA", Appendix C) -----------
+ * When the rows of a float store are distributions (a document's topic proportions), the
+ * paper measures distances in total variation, each row scaled by the length of its
+ * document: distance of block b = w_b * 1/2 * sum_j |x_j - c_j|, and the size of a
+ * perturbation is the sum of its rows' distances (a positive combination of total-variation
+ * norms), not a root of squares.  The three calls below are scar_block_scores,
+ * scar_partial_recover and scar_perturbation_norm in that norm; selection and commit do not
+ * depend on the norm and are shared.
+ *   layout->dtype: SCAR_F32 or SCAR_BF16 (anything else: SCAR_ERR_INVALID_ARG).
+ *   weights: float[n_blocks] in DEVICE memory (document lengths, > 0 by the caller's care),
+ *            or NULL for w_b = 1 (plain total variation).
+ *   scores:  float[n_blocks].
+ *   norm_out: sum = norm = the scaled total variation over the listed blocks, isum = 0.
+ * A table of integer topic counts needs none of this: with SCAR_I32 the plain calls score the
+ * L1 distance of the counts, which is exactly twice this norm when row totals are unchanged. */
+int scar_tv_block_scores(const scar_layout* layout, const void* x, const void* c,
+                         const float* weights, float* scores, void* stream);
+
+int scar_tv_partial_recover(const scar_layout* layout, void* x, const void* c, const float* weights,
+                            const uint32_t* lost_idx, uint32_t n_lost, scar_norm* norm_out,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+int scar_tv_perturbation_norm(const scar_layout* layout, const void* x, const void* c,
+                              const float* weights, const uint32_t* idx, uint32_t n_idx,
+                              scar_norm* norm_out, void* workspace, size_t workspace_bytes,
+                              void* stream);
+
 /* Static, never NULL. */
 const char* scar_strerror(int status);
 

@@ -14,9 +14,12 @@ constexpr int kWG = 256;    // threads per workgroup, 4 wavefronts
 constexpr int kWave = 64;
 constexpr int kUnroll = 4;  // 16-byte loads per lane and stream kept in flight
 
-enum : int { DT_F32 = 0, DT_BF16 = 1, DT_I32 = 2 };
+// What a kernel measures: squared L2 on float32 / bfloat16, exact L1 on int32 counts, or
+// (the *_TV kinds) the total variation 1/2 * sum |x - c| of float rows that are distributions.
+enum : int { DT_F32 = 0, DT_BF16 = 1, DT_I32 = 2, DT_F32_TV = 3, DT_BF16_TV = 4 };
 
-__host__ __device__ constexpr int elem_bytes(int dt) { return dt == DT_BF16 ? 2 : 4; }
+__host__ __device__ constexpr int elem_bytes(int dt) { return (dt == DT_BF16 || dt == DT_BF16_TV) ? 2 : 4; }
+__host__ __device__ constexpr bool is_tv(int dt) { return dt == DT_F32_TV || dt == DT_BF16_TV; }
 
 // ---- streaming memory access ---------------------------------------------------------
 // Every byte of x and c is touched once per kernel, so all 16-byte accesses carry the
@@ -73,6 +76,26 @@ __device__ __forceinline__ float sqdiff_bf16(const uint4& a, const uint4& b) {
          (sqdiff_bf16x2(a.z, b.z) + sqdiff_bf16x2(a.w, b.w));
 }
 
+// Sums of absolute differences (total variation), added in a fixed order.
+__device__ __forceinline__ float absdiff_f32(const uint4& a, const uint4& b) {
+  const float d0 = __builtin_fabsf(__uint_as_float(a.x) - __uint_as_float(b.x));
+  const float d1 = __builtin_fabsf(__uint_as_float(a.y) - __uint_as_float(b.y));
+  const float d2 = __builtin_fabsf(__uint_as_float(a.z) - __uint_as_float(b.z));
+  const float d3 = __builtin_fabsf(__uint_as_float(a.w) - __uint_as_float(b.w));
+  return (d0 + d1) + (d2 + d3);
+}
+
+__device__ __forceinline__ float absdiff_bf16x2(uint32_t a, uint32_t b) {
+  const float lo = __uint_as_float(a << 16) - __uint_as_float(b << 16);
+  const float hi = __uint_as_float(a & 0xffff0000u) - __uint_as_float(b & 0xffff0000u);
+  return __builtin_fabsf(lo) + __builtin_fabsf(hi);
+}
+
+__device__ __forceinline__ float absdiff_bf16(const uint4& a, const uint4& b) {
+  return (absdiff_bf16x2(a.x, b.x) + absdiff_bf16x2(a.y, b.y)) +
+         (absdiff_bf16x2(a.z, b.z) + absdiff_bf16x2(a.w, b.w));
+}
+
 // |a - b| of two int32 held in uint32: the true difference is below 2^32, so the
 // unsigned subtraction of the smaller from the larger is exact.
 __device__ __forceinline__ uint32_t absdiff_i32(uint32_t a, uint32_t b) {
@@ -108,8 +131,12 @@ __device__ __forceinline__ void accumulate_vec(typename Acc<DT>::type& acc, cons
   } else {
     float part = 0.f;
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-      part += (DT == DT_F32) ? sqdiff_f32(a[u], b[u]) : sqdiff_bf16(a[u], b[u]);
+    for (int u = 0; u < U; ++u) {
+      if constexpr (DT == DT_F32) part += sqdiff_f32(a[u], b[u]);
+      if constexpr (DT == DT_BF16) part += sqdiff_bf16(a[u], b[u]);
+      if constexpr (DT == DT_F32_TV) part += absdiff_f32(a[u], b[u]);
+      if constexpr (DT == DT_BF16_TV) part += absdiff_bf16(a[u], b[u]);
+    }
     acc += (double)part;
   }
 }
@@ -121,9 +148,12 @@ __device__ __forceinline__ void accumulate_elem(typename Acc<DT>::type& acc, con
     acc += absdiff_i32(((const uint32_t*)a)[j], ((const uint32_t*)b)[j]);
   } else if constexpr (DT == DT_F32) {
     acc += (double)sq(((const float*)a)[j] - ((const float*)b)[j]);
+  } else if constexpr (DT == DT_F32_TV) {
+    acc += (double)__builtin_fabsf(((const float*)a)[j] - ((const float*)b)[j]);
   } else {
     uint32_t ua = ((const uint16_t*)a)[j], ub = ((const uint16_t*)b)[j];
-    acc += (double)sq(__uint_as_float(ua << 16) - __uint_as_float(ub << 16));
+    const float d = __uint_as_float(ua << 16) - __uint_as_float(ub << 16);
+    acc += (double)(DT == DT_BF16 ? sq(d) : __builtin_fabsf(d));
   }
 }
 

@@ -97,6 +97,7 @@ __device__ __forceinline__ void recover_row(char* xb, const char* cb, uint32_t l
 // Recovery and/or norm over the blocks idx[0..n_idx) (idx == NULL: blocks 0..n_idx).
 //   STORE: x_b <- c_b after the block has been measured.
 //   NORM:  partial[blockIdx.x] <- this workgroup's share of sum (c - x)^2 or sum |c - x|.
+//   weights (total-variation kinds only): per-block factors of the sum, NULL = 1.
 //   T:     threads per workgroup, T / G groups.  Long index lists run with 1,024 threads: a
 //          workgroup that has to come back for a second entry waits a full memory round trip
 //          in between (131,072 rows of 4 KiB: 298 us with two entries per group, 283 us with
@@ -106,7 +107,8 @@ __global__ __launch_bounds__(T) void k_recover(char* __restrict__ x, const char*
                                                const uint32_t* __restrict__ idx, uint32_t n_idx,
                                                uint64_t n_elems, uint32_t block_len,
                                                uint32_t n_blocks, bool packed,
-                                               typename Acc<DT>::type* __restrict__ partial) {
+                                               typename Acc<DT>::type* __restrict__ partial,
+                                               const float* __restrict__ weights) {
   constexpr int GPW = T / G;
   constexpr int E = elem_bytes(DT);
   using acc_t = typename Acc<DT>::type;
@@ -122,7 +124,13 @@ __global__ __launch_bounds__(T) void k_recover(char* __restrict__ x, const char*
     const BlockSpan sp = block_span(b, n_elems, block_len, E);
     // packed: c holds only the listed blocks, row i = block idx[i] (rows read back from storage)
     const char* cb = packed ? c + i * (uint64_t)block_len * E : c + sp.byte_off;
-    recover_row<DT, G, STORE, NORM, VEC>(x + sp.byte_off, cb, sp.len, lane, acc);
+    if constexpr (is_tv(DT)) {  // each row's share counts with the row's weight
+      acc_t row = 0;
+      recover_row<DT, G, STORE, NORM, VEC>(x + sp.byte_off, cb, sp.len, lane, row);
+      acc += (weights ? (double)weights[b] : 1.0) * row;
+    } else {
+      recover_row<DT, G, STORE, NORM, VEC>(x + sp.byte_off, cb, sp.len, lane, acc);
+    }
   }
   if (NORM) {
     acc = workgroup_sum<T>(acc, slots);
@@ -151,6 +159,10 @@ __global__ __launch_bounds__(kFinishThreads) void k_norm_finish(
       out->isum = (long long)total;
       out->sum = (double)total;
       out->norm = (double)total;
+    } else if constexpr (is_tv(DT)) {  // sum of w_b * 1/2 * sum |c - x|; the norm is that sum
+      out->isum = 0;
+      out->sum = 0.5 * total;
+      out->norm = 0.5 * total;
     } else {
       out->isum = 0;
       out->sum = total;
@@ -194,53 +206,68 @@ constexpr uint64_t kWideFrom = 8192;   // workgroups of kWG threads from which k
 template <int DT, int G, int T, bool STORE, bool NORM, bool VEC>
 static uint32_t launch_recover_t(const scar_layout* l, void* x, const void* c, const uint32_t* idx,
                                  uint32_t n_idx, uint32_t n_blocks, bool packed, void* partial,
-                                 hipStream_t st) {
+                                 const float* weights, hipStream_t st) {
   constexpr int GPW = T / G;
   const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
   const uint32_t grid = xcd_grid(need, kMaxNormGrid);
   hipLaunchKernelGGL((k_recover<DT, G, T, STORE, NORM, VEC>), dim3(grid), dim3(T), 0, st, (char*)x,
                      (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, packed,
-                     (typename Acc<DT>::type*)partial);
+                     (typename Acc<DT>::type*)partial, weights);
   return grid;
 }
 
 template <int DT, int G, bool STORE, bool NORM>
 static uint32_t launch_recover(const scar_layout* l, void* x, const void* c, const uint32_t* idx,
                                uint32_t n_idx, uint32_t n_blocks, bool vec, bool packed, void* partial,
-                               hipStream_t st) {
+                               const float* weights, hipStream_t st) {
   if (!vec)
-    return launch_recover_t<DT, G, kWG, STORE, NORM, false>(l, x, c, idx, n_idx, n_blocks, packed, partial, st);
+    return launch_recover_t<DT, G, kWG, STORE, NORM, false>(l, x, c, idx, n_idx, n_blocks, packed, partial, weights, st);
   if (((uint64_t)n_idx * G + kWG - 1) / kWG >= kWideFrom)
-    return launch_recover_t<DT, G, kWideWG, STORE, NORM, true>(l, x, c, idx, n_idx, n_blocks, packed, partial, st);
-  return launch_recover_t<DT, G, kWG, STORE, NORM, true>(l, x, c, idx, n_idx, n_blocks, packed, partial, st);
+    return launch_recover_t<DT, G, kWideWG, STORE, NORM, true>(l, x, c, idx, n_idx, n_blocks, packed, partial, weights, st);
+  return launch_recover_t<DT, G, kWG, STORE, NORM, true>(l, x, c, idx, n_idx, n_blocks, packed, partial, weights, st);
 }
 
 template <int DT, bool STORE, bool NORM>
 static uint32_t dispatch_recover_g(int g, const scar_layout* l, void* x, const void* c,
                                    const uint32_t* idx, uint32_t n_idx, uint32_t n_blocks, bool vec,
-                                   bool packed, void* partial, hipStream_t st) {
+                                   bool packed, void* partial, const float* weights, hipStream_t st) {
+#define SCAR_CALL(G) \
+  return launch_recover<DT, G, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, weights, st)
   switch (g) {
-    case 1: return launch_recover<DT, 1, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
-    case 2: return launch_recover<DT, 2, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
-    case 4: return launch_recover<DT, 4, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
-    case 8: return launch_recover<DT, 8, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
-    case 16: return launch_recover<DT, 16, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
-    case 32: return launch_recover<DT, 32, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
-    case 64: return launch_recover<DT, 64, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
-    case 128: return launch_recover<DT, 128, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
-    default: return launch_recover<DT, 256, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
+    case 1: SCAR_CALL(1);
+    case 2: SCAR_CALL(2);
+    case 4: SCAR_CALL(4);
+    case 8: SCAR_CALL(8);
+    case 16: SCAR_CALL(16);
+    case 32: SCAR_CALL(32);
+    case 64: SCAR_CALL(64);
+    case 128: SCAR_CALL(128);
+    default: SCAR_CALL(256);
+  }
+#undef SCAR_CALL
+}
+
+// dt: what is measured (a DT_* kind).  The total-variation kinds always measure (NORM).
+template <bool STORE, bool NORM>
+static uint32_t dispatch_recover(int dt, int g, const scar_layout* l, void* x, const void* c,
+                                 const uint32_t* idx, uint32_t n_idx, uint32_t n_blocks, bool vec,
+                                 bool packed, void* partial, const float* weights, hipStream_t st) {
+  switch (dt) {
+    case DT_F32: return dispatch_recover_g<DT_F32, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, nullptr, st);
+    case DT_BF16: return dispatch_recover_g<DT_BF16, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, nullptr, st);
+    case DT_I32: return dispatch_recover_g<DT_I32, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, nullptr, st);
+    case DT_F32_TV:
+      if constexpr (NORM) return dispatch_recover_g<DT_F32_TV, STORE, true>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, weights, st);
+      return 0;
+    default:
+      if constexpr (NORM) return dispatch_recover_g<DT_BF16_TV, STORE, true>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, weights, st);
+      return 0;
   }
 }
 
-template <bool STORE, bool NORM>
-static uint32_t dispatch_recover(int g, const scar_layout* l, void* x, const void* c,
-                                 const uint32_t* idx, uint32_t n_idx, uint32_t n_blocks, bool vec,
-                                 bool packed, void* partial, hipStream_t st) {
-  switch (l->dtype) {
-    case SCAR_F32: return dispatch_recover_g<DT_F32, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
-    case SCAR_BF16: return dispatch_recover_g<DT_BF16, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
-    default: return dispatch_recover_g<DT_I32, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
-  }
+static void launch_finish_tv(const void* partial, uint32_t n_partial, scar_norm* out, hipStream_t st) {
+  hipLaunchKernelGGL((k_norm_finish<DT_F32_TV>), dim3(1), dim3(kFinishThreads), 0, st, (const double*)partial,
+                     n_partial, out);
 }
 
 void launch_finish(int32_t dtype, const void* partial, uint32_t n_partial, scar_norm* out,
@@ -253,12 +280,15 @@ void launch_finish(int32_t dtype, const void* partial, uint32_t n_partial, scar_
                        n_partial, out);
 }
 
-// Shared body of scar_partial_recover (store = true) and scar_perturbation_norm.
-static int recover_or_norm(bool store, bool packed, const scar_layout* layout, void* x, const void* c,
-                           const uint32_t* idx, uint32_t n_idx, bool all_blocks, scar_norm* norm_out,
-                           void* workspace, size_t workspace_bytes, void* stream) {
+// Shared body of scar_partial_recover (store = true) and scar_perturbation_norm, and of their
+// total-variation twins (tv = true: float stores only, weights may be NULL).
+static int recover_or_norm(bool store, bool packed, bool tv, const scar_layout* layout, void* x,
+                           const void* c, const float* weights, const uint32_t* idx, uint32_t n_idx,
+                           bool all_blocks, scar_norm* norm_out, void* workspace, size_t workspace_bytes,
+                           void* stream) {
   const uint64_t nb = layout_blocks(layout);
   if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
+  if (tv && layout->dtype != SCAR_F32 && layout->dtype != SCAR_BF16) return SCAR_ERR_INVALID_ARG;
   const int eb = host_elem_bytes(layout->dtype);
   if (all_blocks) n_idx = (uint32_t)nb;
   if (norm_out) {
@@ -268,14 +298,20 @@ static int recover_or_norm(bool store, bool packed, const scar_layout* layout, v
   }
   hipStream_t st = (hipStream_t)stream;
   char* partial = norm_out ? (char*)workspace + kWsNormOffset : nullptr;
+  auto finish = [&](uint32_t n_partial) {
+    if (tv)
+      launch_finish_tv(partial, n_partial, norm_out, st);
+    else
+      launch_finish(layout->dtype, partial, n_partial, norm_out, st);
+  };
   if (n_idx == 0 || nb == 0) {
     if (norm_out) {
-      launch_finish(layout->dtype, partial, 0, norm_out, st);
+      finish(0);
       return launch_status();
     }
     return SCAR_OK;
   }
-  if (!x || !c || (!all_blocks && !idx) || !aligned(idx, 4)) return SCAR_ERR_INVALID_ARG;
+  if (!x || !c || (!all_blocks && !idx) || !aligned(idx, 4) || !aligned(weights, 4)) return SCAR_ERR_INVALID_ARG;
   if (layout->dtype == SCAR_F32_BF16C)
     return mixed_recover_or_norm(store, packed, layout, (uint32_t)nb, x, c, all_blocks ? nullptr : idx,
                                  n_idx, norm_out, partial, st);
@@ -283,14 +319,17 @@ static int recover_or_norm(bool store, bool packed, const scar_layout* layout, v
   const bool vec = aligned(x, 16) && aligned(c, 16) && ((uint64_t)layout->block_len * eb) % 16 == 0;
   const int g = pick_group(layout->block_len, eb, co_aligned(x, c), 1, true);
   const uint32_t n_blocks = (uint32_t)nb;
+  // what the pass measures; a recovery without a norm only copies, whatever the metric
+  int dt = layout->dtype == SCAR_F32 ? DT_F32 : (layout->dtype == SCAR_BF16 ? DT_BF16 : DT_I32);
+  if (tv && norm_out) dt = layout->dtype == SCAR_F32 ? DT_F32_TV : DT_BF16_TV;
   uint32_t n_partial = 0;
   if (store && norm_out)
-    n_partial = dispatch_recover<true, true>(g, layout, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
+    n_partial = dispatch_recover<true, true>(dt, g, layout, x, c, idx, n_idx, n_blocks, vec, packed, partial, weights, st);
   else if (store)
-    dispatch_recover<true, false>(g, layout, x, c, idx, n_idx, n_blocks, vec, packed, nullptr, st);
+    dispatch_recover<true, false>(dt, g, layout, x, c, idx, n_idx, n_blocks, vec, packed, nullptr, nullptr, st);
   else
-    n_partial = dispatch_recover<false, true>(g, layout, x, c, idx, n_idx, n_blocks, vec, packed, partial, st);
-  if (norm_out) launch_finish(layout->dtype, partial, n_partial, norm_out, st);
+    n_partial = dispatch_recover<false, true>(dt, g, layout, x, c, idx, n_idx, n_blocks, vec, packed, partial, weights, st);
+  if (norm_out) finish(n_partial);
   return launch_status();
 }
 
@@ -325,21 +364,39 @@ extern "C" int scar_checkpoint_commit(const scar_layout* layout, const void* x, 
 extern "C" int scar_partial_recover(const scar_layout* layout, void* x, const void* c,
                                     const uint32_t* lost_idx, uint32_t n_lost, scar_norm* norm_out,
                                     void* workspace, size_t workspace_bytes, void* stream) {
-  return recover_or_norm(true, false, layout, x, c, lost_idx, n_lost, false, norm_out, workspace,
-                         workspace_bytes, stream);
+  return recover_or_norm(true, false, false, layout, x, c, nullptr, lost_idx, n_lost, false, norm_out,
+                         workspace, workspace_bytes, stream);
 }
 
 extern "C" int scar_partial_recover_rows(const scar_layout* layout, void* x, const void* rows,
                                          const uint32_t* lost_idx, uint32_t n_lost, scar_norm* norm_out,
                                          void* workspace, size_t workspace_bytes, void* stream) {
-  return recover_or_norm(true, true, layout, x, rows, lost_idx, n_lost, false, norm_out, workspace,
-                         workspace_bytes, stream);
+  return recover_or_norm(true, true, false, layout, x, rows, nullptr, lost_idx, n_lost, false, norm_out,
+                         workspace, workspace_bytes, stream);
 }
 
 extern "C" int scar_perturbation_norm(const scar_layout* layout, const void* x, const void* c,
                                       const uint32_t* idx, uint32_t n_idx, scar_norm* norm_out,
                                       void* workspace, size_t workspace_bytes, void* stream) {
   if (!norm_out) return SCAR_ERR_INVALID_ARG;
-  return recover_or_norm(false, false, layout, const_cast<void*>(x), c, idx, n_idx, idx == nullptr, norm_out,
+  return recover_or_norm(false, false, false, layout, const_cast<void*>(x), c, nullptr, idx, n_idx,
+                         idx == nullptr, norm_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" int scar_tv_partial_recover(const scar_layout* layout, void* x, const void* c,
+                                       const float* weights, const uint32_t* lost_idx, uint32_t n_lost,
+                                       scar_norm* norm_out, void* workspace, size_t workspace_bytes,
+                                       void* stream) {
+  return recover_or_norm(true, false, true, layout, x, c, weights, lost_idx, n_lost, false, norm_out,
                          workspace, workspace_bytes, stream);
 }
+
+extern "C" int scar_tv_perturbation_norm(const scar_layout* layout, const void* x, const void* c,
+                                         const float* weights, const uint32_t* idx, uint32_t n_idx,
+                                         scar_norm* norm_out, void* workspace, size_t workspace_bytes,
+                                         void* stream) {
+  if (!norm_out) return SCAR_ERR_INVALID_ARG;
+  return recover_or_norm(false, false, true, layout, const_cast<void*>(x), c, weights, idx, n_idx,
+                         idx == nullptr, norm_out, workspace, workspace_bytes, stream);
+}
+

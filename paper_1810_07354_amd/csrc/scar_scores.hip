@@ -15,7 +15,8 @@ template <int DT, int G, bool VEC>
 __global__ __launch_bounds__(kWG) void k_block_scores(const char* __restrict__ x,
                                                       const char* __restrict__ c,
                                                       void* __restrict__ scores, uint64_t n_elems,
-                                                      uint32_t block_len, uint32_t n_blocks) {
+                                                      uint32_t block_len, uint32_t n_blocks,
+                                                      const float* __restrict__ weights) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;  // groups (= blocks in flight) per workgroup
   using acc_t = typename Acc<DT>::type;
   const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
@@ -33,6 +34,8 @@ __global__ __launch_bounds__(kWG) void k_block_scores(const char* __restrict__ x
     if (lane == 0) {
       if constexpr (DT == DT_I32)
         ((long long*)scores)[b] = (long long)acc;
+      else if constexpr (is_tv(DT))  // w_b * 1/2 * sum |x - c|
+        ((float*)scores)[b] = (float)(0.5 * acc * (weights ? (double)weights[b] : 1.0));
       else
         ((float*)scores)[b] = (float)acc;
     }
@@ -41,30 +44,30 @@ __global__ __launch_bounds__(kWG) void k_block_scores(const char* __restrict__ x
 
 template <int DT, int G>
 static void launch_scores(const scar_layout* l, const void* x, const void* c, void* scores,
-                          uint32_t n_blocks, bool vec, hipStream_t st) {
+                          uint32_t n_blocks, bool vec, const float* weights, hipStream_t st) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const uint64_t need = ((uint64_t)n_blocks + GPW - 1) / GPW;
   const uint32_t grid = xcd_grid(need, kScoreGridCap);
   if (vec)
     hipLaunchKernelGGL((k_block_scores<DT, G, true>), dim3(grid), dim3(kWG), 0, st, (const char*)x,
-                       (const char*)c, scores, l->n_elems, l->block_len, n_blocks);
+                       (const char*)c, scores, l->n_elems, l->block_len, n_blocks, weights);
   else
     hipLaunchKernelGGL((k_block_scores<DT, G, false>), dim3(grid), dim3(kWG), 0, st, (const char*)x,
-                       (const char*)c, scores, l->n_elems, l->block_len, n_blocks);
+                       (const char*)c, scores, l->n_elems, l->block_len, n_blocks, weights);
 }
 
 template <int DT>
 static void dispatch_scores(int g, const scar_layout* l, const void* x, const void* c, void* scores,
-                            uint32_t n_blocks, bool vec, hipStream_t st) {
+                            uint32_t n_blocks, bool vec, const float* weights, hipStream_t st) {
   switch (g) {
-    case 1: launch_scores<DT, 1>(l, x, c, scores, n_blocks, vec, st); break;
-    case 2: launch_scores<DT, 2>(l, x, c, scores, n_blocks, vec, st); break;
-    case 4: launch_scores<DT, 4>(l, x, c, scores, n_blocks, vec, st); break;
-    case 8: launch_scores<DT, 8>(l, x, c, scores, n_blocks, vec, st); break;
-    case 16: launch_scores<DT, 16>(l, x, c, scores, n_blocks, vec, st); break;
-    case 32: launch_scores<DT, 32>(l, x, c, scores, n_blocks, vec, st); break;
-    case 64: launch_scores<DT, 64>(l, x, c, scores, n_blocks, vec, st); break;
-    default: launch_scores<DT, 256>(l, x, c, scores, n_blocks, vec, st); break;
+    case 1: launch_scores<DT, 1>(l, x, c, scores, n_blocks, vec, weights, st); break;
+    case 2: launch_scores<DT, 2>(l, x, c, scores, n_blocks, vec, weights, st); break;
+    case 4: launch_scores<DT, 4>(l, x, c, scores, n_blocks, vec, weights, st); break;
+    case 8: launch_scores<DT, 8>(l, x, c, scores, n_blocks, vec, weights, st); break;
+    case 16: launch_scores<DT, 16>(l, x, c, scores, n_blocks, vec, weights, st); break;
+    case 32: launch_scores<DT, 32>(l, x, c, scores, n_blocks, vec, weights, st); break;
+    case 64: launch_scores<DT, 64>(l, x, c, scores, n_blocks, vec, weights, st); break;
+    default: launch_scores<DT, 256>(l, x, c, scores, n_blocks, vec, weights, st); break;
   }
 }
 
@@ -72,15 +75,17 @@ static void dispatch_scores(int g, const scar_layout* l, const void* x, const vo
 
 using namespace scar;
 
-extern "C" int scar_block_scores(const scar_layout* layout, const void* x, const void* c,
-                                 void* scores, void* stream) {
+// Shared body of scar_block_scores (tv = false) and scar_tv_block_scores.
+static int block_scores(bool tv, const scar_layout* layout, const void* x, const void* c,
+                        const float* weights, void* scores, void* stream) {
   const uint64_t nb = layout_blocks(layout);
   if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
+  if (tv && layout->dtype != SCAR_F32 && layout->dtype != SCAR_BF16) return SCAR_ERR_INVALID_ARG;
   if (nb == 0) return SCAR_OK;
   if (layout->dtype == SCAR_F32_BF16C)
     return mixed_block_scores(layout, (uint32_t)nb, x, c, scores, (hipStream_t)stream);
   const int eb = host_elem_bytes(layout->dtype);
-  if (!x || !c || !scores || !aligned(x, eb) || !aligned(c, eb) ||
+  if (!x || !c || !scores || !aligned(x, eb) || !aligned(c, eb) || !aligned(weights, 4) ||
       !aligned(scores, layout->dtype == SCAR_I32 ? 8 : 4))
     return SCAR_ERR_INVALID_ARG;
   const bool vec = aligned(x, 16) && aligned(c, 16) && ((uint64_t)layout->block_len * eb) % 16 == 0;
@@ -92,10 +97,28 @@ extern "C" int scar_block_scores(const scar_layout* layout, const void* x, const
   int g = pick_group(layout->block_len, eb, co_aligned(x, c), per_lane, false);
   if (g == 32 && vec && row_bytes >= 2048) g = 64;  // 2 KiB rows: a whole wavefront, two loads per lane
   hipStream_t st = (hipStream_t)stream;
+  const uint32_t n = (uint32_t)nb;
+  if (tv) {
+    if (layout->dtype == SCAR_F32)
+      dispatch_scores<DT_F32_TV>(g, layout, x, c, scores, n, vec, weights, st);
+    else
+      dispatch_scores<DT_BF16_TV>(g, layout, x, c, scores, n, vec, weights, st);
+    return launch_status();
+  }
   switch (layout->dtype) {
-    case SCAR_F32: dispatch_scores<DT_F32>(g, layout, x, c, scores, (uint32_t)nb, vec, st); break;
-    case SCAR_BF16: dispatch_scores<DT_BF16>(g, layout, x, c, scores, (uint32_t)nb, vec, st); break;
-    default: dispatch_scores<DT_I32>(g, layout, x, c, scores, (uint32_t)nb, vec, st); break;
+    case SCAR_F32: dispatch_scores<DT_F32>(g, layout, x, c, scores, n, vec, nullptr, st); break;
+    case SCAR_BF16: dispatch_scores<DT_BF16>(g, layout, x, c, scores, n, vec, nullptr, st); break;
+    default: dispatch_scores<DT_I32>(g, layout, x, c, scores, n, vec, nullptr, st); break;
   }
   return launch_status();
+}
+
+extern "C" int scar_block_scores(const scar_layout* layout, const void* x, const void* c,
+                                 void* scores, void* stream) {
+  return block_scores(false, layout, x, c, nullptr, scores, stream);
+}
+
+extern "C" int scar_tv_block_scores(const scar_layout* layout, const void* x, const void* c,
+                                    const float* weights, float* scores, void* stream) {
+  return block_scores(true, layout, x, c, weights, scores, stream);
 }

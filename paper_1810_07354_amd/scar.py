@@ -81,6 +81,11 @@ def lib():
         for name in ("scar_var_block_scores", "scar_var_checkpoint_commit", "scar_var_partial_recover",
                      "scar_var_perturbation_norm"):
             getattr(L, name).restype = ctypes.c_int
+        L.scar_tv_block_scores.argtypes = [lp, vp, vp, vp, vp, vp]
+        L.scar_tv_partial_recover.argtypes = [lp, vp, vp, vp, vp, u32, vp, vp, sz, vp]
+        L.scar_tv_perturbation_norm.argtypes = [lp, vp, vp, vp, vp, u32, vp, vp, sz, vp]
+        for name in ("scar_tv_block_scores", "scar_tv_partial_recover", "scar_tv_perturbation_norm"):
+            getattr(L, name).restype = ctypes.c_int
         pp = ctypes.POINTER(ctypes.c_void_p)
         L.scar_store_create.argtypes = [ctypes.c_char_p, lp, u32, pp]
         L.scar_store_open.argtypes = [ctypes.c_char_p, u32, lp, pp]
@@ -344,6 +349,62 @@ def var_perturbation_norm(x, c, offsets, idx, workspace):
     _check(lib().scar_var_perturbation_norm(ctypes.byref(lay), _p(x), _p(c), ptr, n, _p(norm_out),
                                             _p(workspace), workspace.numel(), _stream()),
            "scar_var_perturbation_norm")
+    return norm_out
+
+
+# ---- document-length-scaled total variation (float rows that are distributions) ----------
+
+def _weights(weights, n_blocks_, device):
+    if weights is None:
+        return None
+    _dev(weights, "weights")
+    if weights.dtype != torch.float32 or weights.numel() != n_blocks_ or not weights.is_contiguous():
+        raise ValueError("weights must be a contiguous float32 tensor with one entry per block")
+    return weights
+
+
+def tv_block_scores(x, c, block_len, weights=None, out=None):
+    """scar_tv_block_scores: w_b * TV(x_b, c_b) per block (float32)."""
+    _dev(x, "x"), _dev(c, "c")
+    lay = layout_of(x, block_len, c)
+    nb = n_blocks(lay)
+    w = _weights(weights, nb, x.device)
+    if out is None:
+        out = torch.empty(nb, dtype=torch.float32, device=x.device)
+    _check(lib().scar_tv_block_scores(ctypes.byref(lay), _p(x), _p(c), _p(w), _p(out), _stream()),
+           "scar_tv_block_scores")
+    return out
+
+
+def tv_partial_recover(x, c, block_len, lost_idx, workspace, weights=None, want_norm=True):
+    """scar_tv_partial_recover; returns the device scar_norm buffer or None."""
+    _dev(x, "x"), _dev(c, "c"), _dev(lost_idx, "lost_idx")
+    lay = layout_of(x, block_len, c)
+    w = _weights(weights, n_blocks(lay), x.device)
+    norm_out = _norm_buffer(x.device) if want_norm else None
+    if want_norm:
+        _dev(workspace, "workspace")
+    _check(lib().scar_tv_partial_recover(ctypes.byref(lay), _p(x), _p(c), _p(w), _p(lost_idx), lost_idx.numel(),
+                                         _p(norm_out), _p(workspace), workspace.numel() if workspace is not None else 0,
+                                         _stream()), "scar_tv_partial_recover")
+    return norm_out
+
+
+def tv_perturbation_norm(x, c, block_len, idx, workspace, weights=None):
+    """scar_tv_perturbation_norm (idx None = every block)."""
+    _dev(x, "x"), _dev(c, "c"), _dev(workspace, "workspace")
+    lay = layout_of(x, block_len, c)
+    w = _weights(weights, n_blocks(lay), x.device)
+    norm_out = _norm_buffer(x.device)
+    if idx is None:
+        ptr, n = ctypes.c_void_p(0), 0
+    else:
+        _dev(idx, "idx")
+        n = idx.numel()
+        ptr = _p(idx) if n else _p(norm_out)
+    _check(lib().scar_tv_perturbation_norm(ctypes.byref(lay), _p(x), _p(c), _p(w), ptr, n, _p(norm_out),
+                                           _p(workspace), workspace.numel(), _stream()),
+           "scar_tv_perturbation_norm")
     return norm_out
 
 

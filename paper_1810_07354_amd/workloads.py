@@ -142,6 +142,36 @@ def lda_like(seed: int = 2, words: int = 100_000, topics: int = 1000, tokens: fl
                     "top 5% rows, one of 8 random partitions lost")
 
 
+def doc_topic_like(seed: int = 7, docs: int = 20_000, topics: int = 100, resampled: float = 0.05,
+                   dtype: int = F32):
+    """Document-topic distributions as an LDA trainer holds them (Section 5.1): row d is the
+    topic proportions of a document of N_d tokens (N_d log-normal, median about 150),
+    checkpoint c = the proportions at the last checkpoint, x = after a fraction `resampled`
+    of every document's tokens has been re-assigned to another topic.  Returns the workload
+    with extra["lengths"] = float32 N_d, the weights of the scaled total variation."""
+    rng = np.random.default_rng(seed)
+    lengths = np.maximum(5, rng.lognormal(5.0, 1.0, size=docs)).astype(np.int64)
+    theta = rng.dirichlet(np.full(topics, 0.1), size=docs)
+    counts_c = np.stack([rng.multinomial(int(n), p) for n, p in zip(lengths, theta)]).astype(np.int64)
+    counts_x = counts_c.copy()
+    moves = rng.binomial(lengths, resampled)
+    for d in np.nonzero(moves)[0]:
+        for _ in range(int(moves[d])):
+            src = rng.choice(topics, p=counts_x[d] / counts_x[d].sum())
+            dst = int(rng.integers(0, topics))
+            counts_x[d, src] -= 1
+            counts_x[d, dst] += 1
+    c = (counts_c / lengths[:, None]).astype(np.float32)
+    x = (counts_x / lengths[:, None]).astype(np.float32)
+    if dtype == BF16:
+        x, c = f32_to_bf16_bits(x), f32_to_bf16_bits(c)
+    k = k_of_fraction(0.125, docs)
+    lost = random_partitions(docs, 4, seed + 1000)[0]
+    return Workload("doc_topic_like", dtype, topics, x.reshape(-1), c.reshape(-1), k, lost,
+                    "top 1/8 of the documents, one of 4 random partitions lost",
+                    {"lengths": lengths.astype(np.float32)})
+
+
 def cnn_like(seed: int = 3, n_elems: int = 25_000_000, block_len: int = 4096,
              fraction: float = 0.10) -> Workload:
     """CNN-like flat fp32 vector in fixed-size shards (ragged tail), per-shard change scale."""
