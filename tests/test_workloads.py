@@ -95,3 +95,18 @@ def test_by_layer_generators():
     assert 0.5 * 6_000_000 < sizes.sum() < 1.1 * 6_000_000
     v = wl.layers_like(sizes, seed=9, dtype=wl.I32)
     assert v.x.dtype == np.int32 and np.all(np.diff(v.offsets.astype(np.int64)) == sizes)
+
+
+def test_doc_topic_rows_are_distributions_with_lengths():
+    w = wl.doc_topic_like(docs=300, topics=20)
+    x, c = w.x.reshape(-1, 20), w.c.reshape(-1, 20)
+    np.testing.assert_allclose(x.sum(1), 1.0, atol=1e-5)
+    np.testing.assert_allclose(c.sum(1), 1.0, atol=1e-5)
+    assert np.all(x >= 0) and np.all(c >= 0)
+    n = w.extra["lengths"]
+    assert n.dtype == np.float32 and n.shape == (300,) and np.all(n >= 5)
+    # rows are whole token counts over the document's length
+    np.testing.assert_allclose(c * n[:, None], np.round(c * n[:, None]), atol=1e-3)
+    assert np.any(x != c) and w.k == 38 and w.lost.size == 75
+    w2 = wl.doc_topic_like(docs=300, topics=20)
+    np.testing.assert_array_equal(w.x, w2.x)
