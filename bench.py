@@ -76,7 +76,8 @@ def stored_traffic(workload):
 
 
 def make_workload(name, dev):
-    """Returns (x, c, block_len, k, n_lost, lost_of(cycle), drift(cycle), label)."""
+    """Returns (x, c, block_len, k, n_lost, lost_of(cycle), drift(cycle), label, weights);
+    weights is None except for the total-variation workload (document lengths, on the device)."""
     import numpy as np
     import torch
     from paper_1810_07354_amd import workloads as wl
@@ -110,7 +111,10 @@ def make_workload(name, dev):
                 x[lo:lo + m] = f.to(torch.bfloat16)
         label = "flat store 2^30 x %s, 1024-element blocks, k=10%%, lost=1/8" % (
             {"flat_bf16": "bf16", "flat_f32": "fp32", "flat_mixed": "fp32 with a bf16 checkpoint"}[name])
-        return x, c, L, k, n_lost, lost_of, drift, label
+        return x, c, L, k, n_lost, lost_of, drift, label, None
+
+    if name == "doctopic":
+        return make_doctopic(dev)
 
     gens = {"mlr": wl.mlr_like, "mf": wl.mf_like, "lda": wl.lda_like, "cnn": wl.cnn_like}
     w = gens[name]()
@@ -130,10 +134,54 @@ def make_workload(name, dev):
         else:
             x[lo:lo + m] += 1e-3 * torch.empty(m, device=dev).normal_(generator=g)
 
-    return x, c, L, w.k, w.lost.size, lost_of, drift, "%s (%s)" % (w.name, w.note)
+    return x, c, L, w.k, w.lost.size, lost_of, drift, "%s (%s)" % (w.name, w.note), None
 
 
-def cpu_baseline(x, c, L, k_frac, lost_frac, sample_elems, threads):
+def make_doctopic(dev, docs=2_000_000, topics=100, seed=7):
+    """Document-topic rows for the scaled total variation: 2,000,000 documents x 100 topics
+    f32 made on the device (rows ~ Dirichlet(0.1) via normalised gamma draws, document lengths
+    log-normal); x = c with 30 % of the rows mixed 5 % towards another Dirichlet draw."""
+    import torch
+    from paper_1810_07354_amd import workloads as wl
+    g = torch.Generator(device=dev)
+    g.manual_seed(seed)
+
+    def dirichlet_rows(n):
+        out = torch.empty(n, topics, device=dev)
+        for lo in range(0, n, 1 << 18):
+            hi = min(n, lo + (1 << 18))
+            u = torch.rand(hi - lo, topics, device=dev, generator=g).clamp_(min=1e-12)
+            e = torch.empty(hi - lo, topics, device=dev).exponential_(generator=g)
+            out[lo:hi] = u.pow_(10.0).mul_(e)            # Gamma(0.1)-like: heavy mass near 0
+            out[lo:hi] /= out[lo:hi].sum(1, keepdim=True)
+        return out
+
+    def mix(rows_view, frac_rows):
+        n = rows_view.shape[0]
+        pick = torch.rand(n, device=dev, generator=g) < frac_rows
+        other = dirichlet_rows(n)
+        rows_view[pick] = (rows_view[pick] + 0.05 * other[pick]) / 1.05
+
+    c = dirichlet_rows(docs)
+    x = c.clone()
+    mix(x, 0.3)
+    lengths = torch.empty(docs, device=dev).normal_(5.0, 1.0, generator=g).exp_().clamp_(min=5.0).floor_()
+    k, n_lost = wl.k_of_fraction(0.125, docs), docs // 4
+
+    def lost_of(cycle):
+        return wl.random_lost_blocks(docs, n_lost, seed + 1000 + cycle)
+
+    def drift(cycle):
+        m = (2 * docs) // 5                     # a fifth of the documents move per cycle, more than k
+        lo = (cycle * 7919) % (docs - m)
+        mix(x[lo:lo + m], 0.5)
+
+    label = ("document-topic rows %d x %d fp32, scaled total variation (weights = document lengths), "
+             "k=1/8, lost=1/4" % (docs, topics))
+    return x.view(-1), c.view(-1), topics, k, n_lost, lost_of, drift, label, lengths
+
+
+def cpu_baseline(x, c, L, k_frac, lost_frac, sample_elems, threads, weights=None):
     """The oracle's cycle on the first `sample_elems` elements of the same store."""
     import numpy as np
     import torch
@@ -151,6 +199,7 @@ def cpu_baseline(x, c, L, k_frac, lost_frac, sample_elems, threads):
         dt = wl.F32_BF16C
     hx, hc = down(x), down(c)
     nb = (sample_elems + L - 1) // L
+    hw = weights[:nb].cpu().numpy() if weights is not None else None
     k = wl.k_of_fraction(k_frac, nb)
     n_lost = max(1, int(nb * lost_frac))
     times = {}
@@ -161,10 +210,13 @@ def cpu_baseline(x, c, L, k_frac, lost_frac, sample_elems, threads):
             lost = wl.random_lost_blocks(nb, n_lost, 77 + rep)
             x1, c1 = hx.copy(), hc.copy()
             t0 = time.perf_counter()
-            s = oracle.block_scores(dt, x1, c1, L)
+            s = oracle.block_scores(dt, x1, c1, L) if hw is None else oracle.tv_block_scores(dt, x1, c1, L, hw)
             idx = oracle.select_topk(s, k)
             oracle.checkpoint_commit(dt, x1, c1, L, idx)
-            oracle.partial_recover(dt, x1, c1, L, lost)
+            if hw is None:
+                oracle.partial_recover(dt, x1, c1, L, lost)
+            else:
+                oracle.tv_partial_recover(dt, x1, c1, L, lost, hw)
             ts.append(time.perf_counter() - t0)
         times[label] = statistics.median(ts)
     oracle.set_num_threads(1)
@@ -254,7 +306,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="flat_f32",
-                    choices=["flat_f32", "flat_bf16", "flat_mixed", "mlr", "mf", "lda", "cnn", "layers"])
+                    choices=["flat_f32", "flat_bf16", "flat_mixed", "mlr", "mf", "lda", "cnn", "layers", "doctopic"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for HBM counters)")
@@ -286,7 +338,7 @@ def main():
     if args.workload == "layers":
         return main_layers(args)
 
-    x, c, L, k, n_lost, lost_of, drift, label = make_workload(args.workload, dev)
+    x, c, L, k, n_lost, lost_of, drift, label, weights = make_workload(args.workload, dev)
     n_elems = x.numel()
     xbytes, cbytes = x.element_size(), c.element_size()
     nb = (n_elems + L - 1) // L
@@ -319,14 +371,29 @@ def main():
         if rc != 0:
             raise scar.ScarError(rc, "bench step")
 
+    if weights is None:
+        def call_scores(st):
+            return L_.scar_block_scores(lay_p, px, pc, ps, st)
+
+        def call_recover(lost, st):
+            return L_.scar_partial_recover(lay_p, px, pc, lost, n_lost, pn, pw, wbytes, st)
+    else:   # the same cycle in the document-length-scaled total variation
+        pwt = vp(weights.data_ptr())
+
+        def call_scores(st):
+            return L_.scar_tv_block_scores(lay_p, px, pc, pwt, ps, st)
+
+        def call_recover(lost, st):
+            return L_.scar_tv_partial_recover(lay_p, px, pc, pwt, lost, n_lost, pn, pw, wbytes, st)
+
     def step(i):
         e0, e1, e2 = ev[i]
         e0.record()
-        check(L_.scar_block_scores(lay_p, px, pc, ps, stream))
+        check(call_scores(stream))
         e1.record()
         check(L_.scar_select_topk(score_type, ps, nb, k, pi, pw, wbytes, stream))
         check(L_.scar_checkpoint_commit(lay_p, px, pc, pi, k, None, stream))
-        check(L_.scar_partial_recover(lay_p, px, pc, lost_p[i], n_lost, pn, pw, wbytes, stream))
+        check(call_recover(lost_p[i], stream))
         e2.record()
 
     if args.calibrate_copy:
@@ -358,10 +425,10 @@ def main():
         torch.cuda.synchronize()
         with torch.cuda.graph(graph, stream=side):
             cap = vp(torch.cuda.current_stream().cuda_stream)
-            check(L_.scar_block_scores(lay_p, px, pc, ps, cap))
+            check(call_scores(cap))
             check(L_.scar_select_topk(score_type, ps, nb, k, pi, pw, wbytes, cap))
             check(L_.scar_checkpoint_commit(lay_p, px, pc, pi, k, None, cap))
-            check(L_.scar_partial_recover(lay_p, px, pc, p_lost, n_lost, pn, pw, wbytes, cap))
+            check(call_recover(p_lost, cap))
         torch.cuda.synchronize()
 
     wall = []
@@ -415,7 +482,8 @@ def main():
         "pct_of_measured_read_ceiling": round(100.0 * hbm_gbs / READ_CEILING_GBS, 2),
         "ms_per_step_events_median": round(statistics.median(cycle_ms), 4),
         "last_norm": scar.read_norm(norm)[1],
-        "roofline": {"bound": "hbm", "kernel": "k_mixed_scores" if cbytes != xbytes else "k_block_scores",
+        "roofline": {"bound": "hbm", "kernel": "k_mixed_scores" if cbytes != xbytes else
+                     ("k_block_scores (total variation)" if weights is not None else "k_block_scores"),
                      "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": stored_traffic(args.workload), "avg_ms": round(score_avg_ms, 4),
@@ -427,7 +495,7 @@ def main():
         threads = min(16, os.cpu_count() or 1)
         sample = min(n_elems, 1 << 29)
         sample -= sample % L
-        out["cpu_baseline"] = cpu_baseline(x, c, L, k / nb, n_lost / nb, sample, threads)
+        out["cpu_baseline"] = cpu_baseline(x, c, L, k / nb, n_lost / nb, sample, threads, weights)
     print(json.dumps(out), flush=True)
 
 
