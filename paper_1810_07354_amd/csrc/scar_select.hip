@@ -363,20 +363,22 @@ __global__ __launch_bounds__(kWG) void k_compact_write(const KeyArgs src, uint32
 }
 
 // Whole selection in one workgroup of 1,024 threads for small stores (n <= kSmallSelect):
-// keys stay in registers (up to kSmallKeys consecutive keys per thread), histograms in LDS,
-// one launch instead of six or nine.
-constexpr uint32_t kSmallSelect = 8192;
+// keys stay in registers (up to KPT consecutive keys per thread, KPT = 8 or 16 by n),
+// histograms in LDS, one launch instead of six or nine.  Its time grows with n (12 us at
+// 8,192 float keys, 19 us at 16,384, 35 us at 32,768) while the tiled passes below stay near
+// 25 us (40 us for 64-bit keys) up to a few hundred thousand keys, hence the limit.
 constexpr int kSmallWG = 1024;
-template <int SRC>
+constexpr uint32_t kSmallSelect = 16 * kSmallWG;
+template <int SRC, int KPT>
 __global__ __launch_bounds__(kSmallWG) void k_select_small(const KeyArgs scores, uint32_t n,
                                                            uint32_t k, uint32_t* __restrict__ out_idx) {
   using K = Key<SRC>;
   using key_t = typename K::type;
-  constexpr int kSmallKeys = kSmallSelect / kSmallWG;
+  constexpr int kSmallKeys = KPT;
   __shared__ uint32_t lh[kMaxBins];
   __shared__ uint32_t scratch[kSmallWG / kWave + 1];
   __shared__ SelectState shared_state;
-  // thread t holds the kpt consecutive keys from t * kpt on (kpt = ceil(n / 1024) <= 8), so
+  // thread t holds the kpt consecutive keys from t * kpt on (kpt = ceil(n / 1024) <= KPT), so
   // every thread has work whatever n is, and index order is thread order
   const uint32_t kpt = (n + kSmallWG - 1) / kSmallWG;
   const uint32_t base = threadIdx.x * kpt;
@@ -395,7 +397,25 @@ __global__ __launch_bounds__(kSmallWG) void k_select_small(const KeyArgs scores,
 #pragma unroll
     for (int j = 0; j < kSmallKeys; ++j) {
       const bool match = pass == 0 || (key[j] >> (shift + bits)) == (key_t)cur.prefix;
-      if ((uint32_t)j < kpt && base + j < n && match) atomicAdd(&lh[(uint32_t)(key[j] >> shift) & mask], 1u);
+      const bool on = (uint32_t)j < kpt && base + j < n && match;
+      const uint32_t bin = (uint32_t)(key[j] >> shift) & mask;
+      // When a whole wavefront hits one bin (the top digits of small integer scores are all
+      // alike) its 64 adds to one LDS word would run one after the other: add the count once.
+      // (64-bit integer keys only: float scores rarely agree, and the test costs them 1-2 us.)
+      if constexpr (SRC == SRC_I64) {
+        const unsigned long long act = __ballot(on);
+        if (act) {
+          const int leader = __ffsll((long long)act) - 1;
+          const uint32_t bin0 = __shfl(bin, leader, kWave);
+          if (__ballot(on && bin == bin0) == act) {
+            if ((int)(threadIdx.x & (kWave - 1)) == leader) atomicAdd(&lh[bin0], (uint32_t)__popcll(act));
+          } else if (on) {
+            atomicAdd(&lh[bin], 1u);
+          }
+        }
+      } else {
+        if (on) atomicAdd(&lh[bin], 1u);
+      }
     }
     __syncthreads();
     cur = next_state<kSmallWG>(lh, bits, cur, scratch, &shared_state);
@@ -454,7 +474,10 @@ template <int SRC>
 static void run_select(const KeyArgs scores, uint32_t n, uint32_t k, uint32_t* out_idx, void* workspace,
                        hipStream_t st) {
   if (n <= kSmallSelect) {
-    hipLaunchKernelGGL((k_select_small<SRC>), dim3(1), dim3(kSmallWG), 0, st, scores, n, k, out_idx);
+    if (n <= 8 * kSmallWG)
+      hipLaunchKernelGGL((k_select_small<SRC, 8>), dim3(1), dim3(kSmallWG), 0, st, scores, n, k, out_idx);
+    else
+      hipLaunchKernelGGL((k_select_small<SRC, 16>), dim3(1), dim3(kSmallWG), 0, st, scores, n, k, out_idx);
     return;
   }
   SelectWs* ws = (SelectWs*)workspace;

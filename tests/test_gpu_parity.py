@@ -64,7 +64,9 @@ def test_block_scores_int_extremes():
 
 @pytest.mark.parametrize("n,kind", [(1, "rand"), (7, "rand"), (2048, "rand"), (2049, "rand"),
                                     (8192, "ties"), (8193, "ties"), (5000, "special"), (8000, "zeros"),
-                                    (10_000, "rand"), (300_000, "rand"), (300_000, "ties"),
+                                    (10_000, "rand"), (16_384, "rand"), (16_384, "ties"), (16_385, "ties"),
+                                    (12_000, "special"), (16_384, "zeros"), (32_769, "rand"),
+                                    (300_000, "rand"), (300_000, "ties"),
                                     (50_000, "zeros"), (70_000, "special")])
 def test_select_topk_float(n, kind):
     r = np.random.default_rng(n)
@@ -92,7 +94,7 @@ def test_select_topk_float(n, kind):
 
 
 @pytest.mark.parametrize("n,hi", [(5, 3), (4097, 4), (8192, 2 ** 40), (100_000, 50), (100_000, 2 ** 40),
-                                  (30_000, 1)])
+                                  (30_000, 1), (16_000, 2 ** 40), (16_384, 2 ** 40), (16_384, 7), (16_385, 2 ** 40)])
 def test_select_topk_int(n, hi):
     r = np.random.default_rng(n + 1)
     s = r.integers(0, hi, size=n).astype(np.int64)
