@@ -28,15 +28,12 @@
 
 namespace scar {
 
-// One thread per range: first[w] = the block that holds the range's first element
+// Planning of range w: first[w] = the block that holds the range's first element
 // (offsets[b] <= e < offsets[b+1]); any[w] = 1 if a block with mask != 0 reaches into the
 // range (always 1 without a mask).  Whatever the offsets hold, first[w] < n_blocks.
-__global__ __launch_bounds__(kWG) void k_var_plan(const uint64_t* __restrict__ off, uint32_t n_blocks,
-                                                  uint64_t n_elems, uint64_t range_elems, uint32_t n_wg,
-                                                  const uint8_t* __restrict__ mask,
-                                                  uint32_t* __restrict__ first, uint8_t* __restrict__ any) {
-  const uint32_t w = blockIdx.x * kWG + threadIdx.x;
-  if (w >= n_wg) return;
+__device__ __forceinline__ void plan_range(uint32_t w, const uint64_t* __restrict__ off, uint32_t n_blocks,
+                                           uint64_t n_elems, uint64_t range_elems, const uint8_t* mask,
+                                           uint32_t* __restrict__ first, uint8_t* __restrict__ any) {
   const uint64_t e0 = (uint64_t)w * range_elems;
   const uint64_t e1 = e0 + range_elems < n_elems ? e0 + range_elems : n_elems;
   uint32_t lo = 0, hi = n_blocks;
@@ -58,6 +55,35 @@ __global__ __launch_bounds__(kWG) void k_var_plan(const uint64_t* __restrict__ o
     }
   }
   any[w] = hit;
+}
+
+// One thread per range.
+__global__ __launch_bounds__(kWG) void k_var_plan(const uint64_t* __restrict__ off, uint32_t n_blocks,
+                                                  uint64_t n_elems, uint64_t range_elems, uint32_t n_wg,
+                                                  const uint8_t* __restrict__ mask,
+                                                  uint32_t* __restrict__ first, uint8_t* __restrict__ any) {
+  const uint32_t w = blockIdx.x * kWG + threadIdx.x;
+  if (w < n_wg) plan_range(w, off, n_blocks, n_elems, range_elems, mask, first, any);
+}
+
+// Small stores (few ranges, few blocks - a network cut by layer): marking the chosen blocks
+// and planning the ranges in one launch by one workgroup instead of three launches.
+constexpr int kPrepareThreads = 1024;
+constexpr uint32_t kPrepareMaxRanges = 1024;
+constexpr uint32_t kPrepareMaxBlocks = 65536;
+__global__ __launch_bounds__(kPrepareThreads) void k_var_prepare(
+    const uint64_t* __restrict__ off, uint32_t n_blocks, uint64_t n_elems, uint64_t range_elems,
+    uint32_t n_wg, uint8_t* mask, const uint32_t* __restrict__ idx, uint32_t n_idx,
+    uint32_t* __restrict__ first, uint8_t* __restrict__ any) {
+  for (uint32_t b = threadIdx.x; b < n_blocks; b += kPrepareThreads) mask[b] = 0;
+  __syncthreads();
+  for (uint32_t i = threadIdx.x; i < n_idx; i += kPrepareThreads) {
+    const uint32_t b = idx[i];
+    if (b < n_blocks) mask[b] = 1;
+  }
+  __syncthreads();
+  for (uint32_t w = threadIdx.x; w < n_wg; w += kPrepareThreads)
+    plan_range(w, off, n_blocks, n_elems, range_elems, mask, first, any);
 }
 
 enum : int { COPY_NONE = 0, COPY_X_TO_C = 1, COPY_C_TO_X = 2 };
@@ -223,13 +249,14 @@ static int check_var_workspace(const void* ws, size_t bytes, uint64_t n_blocks) 
 
 template <int DT, bool ACC, int COPY, bool PER_BLOCK>
 static void launch_walk(const scar_var_layout* l, const void* x, const void* c, const uint8_t* mask,
-                        void* workspace, const VarGeometry& g, hipStream_t st) {
+                        bool planned, void* workspace, const VarGeometry& g, hipStream_t st) {
   const bool base_aligned = aligned(x, 16) && aligned(c, 16);
   uint32_t* first = (uint32_t*)workspace;
   uint8_t* any = (uint8_t*)workspace + kVarPlanAnyOffset;
   void* partial = (char*)workspace + kVarPartialOffset;
-  hipLaunchKernelGGL(k_var_plan, dim3((g.n_wg + kWG - 1) / kWG), dim3(kWG), 0, st, l->offsets, l->n_blocks,
-                     l->n_elems, g.range_elems, g.n_wg, mask, first, any);
+  if (!planned)
+    hipLaunchKernelGGL(k_var_plan, dim3((g.n_wg + kWG - 1) / kWG), dim3(kWG), 0, st, l->offsets, l->n_blocks,
+                       l->n_elems, g.range_elems, g.n_wg, mask, first, any);
   hipLaunchKernelGGL((k_var_walk<DT, ACC, COPY, PER_BLOCK>), dim3(xcd_grid(g.n_wg, kVarMaxGrid)), dim3(kWG),
                      0, st, (char*)const_cast<void*>(x), (char*)const_cast<void*>(c), l->offsets,
                      l->n_blocks, l->n_elems, g.range_elems, g.n_wg, mask, (const uint32_t*)first,
@@ -238,11 +265,11 @@ static void launch_walk(const scar_var_layout* l, const void* x, const void* c, 
 
 template <bool ACC, int COPY, bool PER_BLOCK>
 static void dispatch_walk(const scar_var_layout* l, const void* x, const void* c, const uint8_t* mask,
-                          void* workspace, const VarGeometry& g, hipStream_t st) {
+                          bool planned, void* workspace, const VarGeometry& g, hipStream_t st) {
   switch (l->dtype) {
-    case SCAR_F32: launch_walk<DT_F32, ACC, COPY, PER_BLOCK>(l, x, c, mask, workspace, g, st); break;
-    case SCAR_BF16: launch_walk<DT_BF16, ACC, COPY, PER_BLOCK>(l, x, c, mask, workspace, g, st); break;
-    default: launch_walk<DT_I32, ACC, COPY, PER_BLOCK>(l, x, c, mask, workspace, g, st); break;
+    case SCAR_F32: launch_walk<DT_F32, ACC, COPY, PER_BLOCK>(l, x, c, mask, planned, workspace, g, st); break;
+    case SCAR_BF16: launch_walk<DT_BF16, ACC, COPY, PER_BLOCK>(l, x, c, mask, planned, workspace, g, st); break;
+    default: launch_walk<DT_I32, ACC, COPY, PER_BLOCK>(l, x, c, mask, planned, workspace, g, st); break;
   }
 }
 
@@ -262,15 +289,24 @@ static void launch_scores_finish(const scar_var_layout* l, const void* workspace
   }
 }
 
-// Marks the blocks of idx in the workspace's selection bytes; returns their address.
+// Marks the blocks of idx in the workspace's selection bytes; returns their address.  Small
+// stores also get their ranges planned in the same launch (*planned = true).
 static const uint8_t* mark_blocks(const scar_var_layout* l, const uint32_t* idx, uint32_t n_idx,
-                                  void* workspace, hipStream_t st) {
+                                  void* workspace, const VarGeometry& g, bool* planned, hipStream_t st) {
   uint8_t* mask = (uint8_t*)workspace + var_mask_offset(l->n_blocks);
+  if (g.n_wg <= kPrepareMaxRanges && l->n_blocks <= kPrepareMaxBlocks) {
+    hipLaunchKernelGGL(k_var_prepare, dim3(1), dim3(kPrepareThreads), 0, st, l->offsets, l->n_blocks,
+                       l->n_elems, g.range_elems, g.n_wg, mask, idx, n_idx, (uint32_t*)workspace,
+                       (uint8_t*)workspace + kVarPlanAnyOffset);
+    *planned = true;
+    return mask;
+  }
   const uint32_t cg = (l->n_blocks + kWG * 16 - 1) / (kWG * 16);
   hipLaunchKernelGGL(k_var_mask_clear, dim3(cg < 4096 ? cg : 4096), dim3(kWG), 0, st, mask, l->n_blocks);
   const uint32_t sg = (n_idx + kWG - 1) / kWG;
   hipLaunchKernelGGL(k_var_mask_set, dim3(sg < 4096 ? sg : 4096), dim3(kWG), 0, st, mask, l->n_blocks, idx,
                      n_idx);
+  *planned = false;
   return mask;
 }
 
@@ -296,15 +332,16 @@ static int var_rows(int copy, const scar_var_layout* layout, const void* x, cons
   if (!x || !c || (!all_blocks && !idx) || !aligned(x, eb) || !aligned(c, eb) || !aligned(idx, 4))
     return SCAR_ERR_INVALID_ARG;
   const VarGeometry g = var_geometry(layout->n_elems);
-  const uint8_t* mask = all_blocks ? nullptr : mark_blocks(layout, idx, n_idx, workspace, st);
+  bool planned = false;
+  const uint8_t* mask = all_blocks ? nullptr : mark_blocks(layout, idx, n_idx, workspace, g, &planned, st);
   if (copy == COPY_X_TO_C)
-    dispatch_walk<false, COPY_X_TO_C, false>(layout, x, c, mask, workspace, g, st);
+    dispatch_walk<false, COPY_X_TO_C, false>(layout, x, c, mask, planned, workspace, g, st);
   else if (copy == COPY_C_TO_X && norm_out)
-    dispatch_walk<true, COPY_C_TO_X, false>(layout, x, c, mask, workspace, g, st);
+    dispatch_walk<true, COPY_C_TO_X, false>(layout, x, c, mask, planned, workspace, g, st);
   else if (copy == COPY_C_TO_X)
-    dispatch_walk<false, COPY_C_TO_X, false>(layout, x, c, mask, workspace, g, st);
+    dispatch_walk<false, COPY_C_TO_X, false>(layout, x, c, mask, planned, workspace, g, st);
   else
-    dispatch_walk<true, COPY_NONE, false>(layout, x, c, mask, workspace, g, st);
+    dispatch_walk<true, COPY_NONE, false>(layout, x, c, mask, planned, workspace, g, st);
   if (norm_out)
     launch_finish(layout->dtype, (char*)workspace + kVarPartialOffset, g.n_wg, norm_out, st);
   return launch_status();
@@ -331,7 +368,7 @@ extern "C" int scar_var_block_scores(const scar_var_layout* layout, const void* 
   if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;
   const VarGeometry g = var_geometry(layout->n_elems);
-  if (layout->n_elems) dispatch_walk<true, COPY_NONE, true>(layout, x, c, nullptr, workspace, g, st);
+  if (layout->n_elems) dispatch_walk<true, COPY_NONE, true>(layout, x, c, nullptr, false, workspace, g, st);
   switch (layout->dtype) {
     case SCAR_I32: launch_scores_finish<DT_I32>(layout, workspace, g, scores, st); break;
     default: launch_scores_finish<DT_F32>(layout, workspace, g, scores, st); break;
