@@ -99,32 +99,37 @@ int mixed_recover_or_norm(bool store, bool packed, const scar_layout* l, uint32_
                           hipStream_t st);
 
 // ---- blocks of unequal length ----------------------------------------------------------
-// The store is cut into ranges of `range_elems` consecutive elements, one workgroup each
-// (at most kVarMaxGrid of them); a range is a whole number of 4,096-element chunks.
+// The store is cut into ranges of `range_elems` consecutive elements, one workgroup each; a
+// range is a whole number of 4,096-element chunks.  Walks that add something up (scores,
+// norms) use at most kVarMaxGrid ranges, because every range hands in a partial sum that a
+// single workgroup has to add afterwards; walks that only copy use up to four times as many,
+// shorter ones (a 2^30-element store: 16 KiB instead of 64 KiB per workgroup and stream, 800
+// -> 744 us on a 4 GB commit).
 constexpr uint32_t kVarChunk = 4096;
 constexpr uint32_t kVarMaxGrid = 65536;
+constexpr uint32_t kVarMaxGridCopy = 4 * kVarMaxGrid;
 
 struct VarGeometry {
   uint64_t range_elems;
   uint32_t n_wg;
 };
 
-inline VarGeometry var_geometry(uint64_t n_elems) {
+inline VarGeometry var_geometry(uint64_t n_elems, uint32_t max_grid = kVarMaxGrid) {
   const uint64_t n_chunks = (n_elems + kVarChunk - 1) / kVarChunk;
-  uint64_t per = (n_chunks + kVarMaxGrid - 1) / kVarMaxGrid;
+  uint64_t per = (n_chunks + max_grid - 1) / max_grid;
   if (per == 0) per = 1;
   const uint64_t range = per * kVarChunk;
   return {range, (uint32_t)((n_elems + range - 1) / range)};
 }
 
 // Workspace of the variable-length calls: per range its first block (4 bytes) and whether
-// it holds a chosen block (1 byte); then 8 * (kVarMaxGrid + n_blocks) bytes of partial sums;
-// then one selection byte per block.
-constexpr size_t kVarPlanFirstBytes = 4 * (size_t)kVarMaxGrid;
+// it holds a chosen block (1 byte), both sized for the copy walks; then
+// 8 * (kVarMaxGrid + n_blocks) bytes of partial sums; then one selection byte per block.
+constexpr size_t kVarPlanFirstBytes = 4 * (size_t)kVarMaxGridCopy;
 constexpr size_t kVarPlanAnyOffset = kVarPlanFirstBytes;
-constexpr size_t kVarPartialOffset = kVarPlanAnyOffset + kVarMaxGrid;
+constexpr size_t kVarPartialOffset = kVarPlanAnyOffset + kVarMaxGridCopy;
 inline size_t var_mask_offset(uint64_t n_blocks) {
-  return kVarPartialOffset + ((8 * ((size_t)kVarMaxGrid + n_blocks) + 255) / 256) * 256;
+  return kVarPartialOffset + ((8 * ((size_t)kVarMaxGridCopy + n_blocks) + 255) / 256) * 256;
 }
 inline size_t var_workspace_bytes_for(uint64_t n_blocks) {
   return var_mask_offset(n_blocks) + ((n_blocks + 255) / 256) * 256 + 256;

@@ -147,8 +147,15 @@ __global__ __launch_bounds__(kFinishThreads) void k_norm_finish(
   using acc_t = typename Acc<DT>::type;
   __shared__ acc_t slots[kFinishThreads / kWave];
   acc_t acc = 0;
-#pragma unroll 8
-  for (uint32_t i = threadIdx.x; i < n_partial; i += kFinishThreads) acc += partial[i];
+  uint32_t i = threadIdx.x;
+  for (; i + 15 * kFinishThreads < n_partial; i += 16 * kFinishThreads) {  // 16 loads in flight
+    acc_t t[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) t[u] = partial[i + u * kFinishThreads];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) acc += t[u];
+  }
+  for (; i < n_partial; i += kFinishThreads) acc += partial[i];
   acc = group_sum<kWave>(acc);
   if ((threadIdx.x & (kWave - 1)) == 0) slots[threadIdx.x / kWave] = acc;
   __syncthreads();

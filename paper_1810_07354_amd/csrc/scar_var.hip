@@ -189,15 +189,16 @@ __global__ __launch_bounds__(kWG) void k_var_walk(char* __restrict__ x, char* __
   }
 }
 
-// Second stage of the scores: G lanes add the slots of one block in a fixed order.
-template <int DT, int G>
-__global__ __launch_bounds__(kWG) void k_var_scores_finish(const typename Acc<DT>::type* __restrict__ partial,
-                                                           const uint64_t* __restrict__ off,
-                                                           uint32_t n_blocks, uint64_t n_elems,
-                                                           uint64_t range_elems, void* __restrict__ scores) {
+// Second stage of the scores: G lanes (of a workgroup of T threads; G = T or G <= 64) add the
+// slots of one block in a fixed order.
+template <int DT, int G, int T>
+__global__ __launch_bounds__(T) void k_var_scores_finish(const typename Acc<DT>::type* __restrict__ partial,
+                                                         const uint64_t* __restrict__ off,
+                                                         uint32_t n_blocks, uint64_t n_elems,
+                                                         uint64_t range_elems, void* __restrict__ scores) {
   using acc_t = typename Acc<DT>::type;
-  constexpr int GPW = kWG / G;
-  __shared__ acc_t slots[kWG / kWave];
+  constexpr int GPW = T / G;
+  __shared__ acc_t slots[T / kWave];
   const int lane = threadIdx.x & (G - 1);
   for (uint64_t b = (uint64_t)blockIdx.x * GPW + threadIdx.x / G; b < n_blocks;
        b += (uint64_t)gridDim.x * GPW) {
@@ -207,10 +208,20 @@ __global__ __launch_bounds__(kWG) void k_var_scores_finish(const typename Acc<DT
     acc_t acc = 0;
     if (hi > lo) {
       const uint64_t w_first = lo / range_elems, w_last = (hi - 1) / range_elems;
-      for (uint64_t w = w_first + lane; w <= w_last; w += G) acc += partial[w + b];
+      const acc_t* slot = partial + w_first + b;
+      const uint64_t n_slots = w_last - w_first + 1;
+      uint64_t i = lane;
+      for (; i + 7 * G < n_slots; i += 8 * G) {  // eight loads in flight, added in index order
+        acc_t t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = slot[i + u * G];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += t[u];
+      }
+      for (; i < n_slots; i += G) acc += slot[i];
     }
-    if constexpr (G == kWG)
-      acc = workgroup_sum(acc, slots);
+    if constexpr (G == T)
+      acc = workgroup_sum<T>(acc, slots);
     else
       acc = group_sum<G>(acc);
     if (lane == 0) {
@@ -257,7 +268,7 @@ static void launch_walk(const scar_var_layout* l, const void* x, const void* c, 
   if (!planned)
     hipLaunchKernelGGL(k_var_plan, dim3((g.n_wg + kWG - 1) / kWG), dim3(kWG), 0, st, l->offsets, l->n_blocks,
                        l->n_elems, g.range_elems, g.n_wg, mask, first, any);
-  hipLaunchKernelGGL((k_var_walk<DT, ACC, COPY, PER_BLOCK>), dim3(xcd_grid(g.n_wg, kVarMaxGrid)), dim3(kWG),
+  hipLaunchKernelGGL((k_var_walk<DT, ACC, COPY, PER_BLOCK>), dim3(xcd_grid(g.n_wg, kVarMaxGridCopy)), dim3(kWG),
                      0, st, (char*)const_cast<void*>(x), (char*)const_cast<void*>(c), l->offsets,
                      l->n_blocks, l->n_elems, g.range_elems, g.n_wg, mask, (const uint32_t*)first,
                      (const uint8_t*)any, (typename Acc<DT>::type*)partial, base_aligned);
@@ -279,11 +290,11 @@ static void launch_scores_finish(const scar_var_layout* l, const void* workspace
   using acc_t = typename Acc<DT>::type;
   const void* partial = (const char*)workspace + kVarPartialOffset;
   if (l->n_blocks <= 16384) {  // few blocks, possibly huge: a whole workgroup adds each one's slots
-    hipLaunchKernelGGL((k_var_scores_finish<DT, kWG>), dim3(l->n_blocks), dim3(kWG), 0, st,
+    hipLaunchKernelGGL((k_var_scores_finish<DT, 1024, 1024>), dim3(l->n_blocks), dim3(1024), 0, st,
                        (const acc_t*)partial, l->offsets, l->n_blocks, l->n_elems, g.range_elems, scores);
   } else {
     const uint64_t need = ((uint64_t)l->n_blocks + 3) / 4;
-    hipLaunchKernelGGL((k_var_scores_finish<DT, kWave>), dim3((uint32_t)(need < 65536 ? need : 65536)),
+    hipLaunchKernelGGL((k_var_scores_finish<DT, kWave, kWG>), dim3((uint32_t)(need < 65536 ? need : 65536)),
                        dim3(kWG), 0, st, (const acc_t*)partial, l->offsets, l->n_blocks, l->n_elems,
                        g.range_elems, scores);
   }
@@ -331,7 +342,8 @@ static int var_rows(int copy, const scar_var_layout* layout, const void* x, cons
   const int eb = host_elem_bytes(layout->dtype);
   if (!x || !c || (!all_blocks && !idx) || !aligned(x, eb) || !aligned(c, eb) || !aligned(idx, 4))
     return SCAR_ERR_INVALID_ARG;
-  const VarGeometry g = var_geometry(layout->n_elems);
+  // walks that add nothing up take the finer cut
+  const VarGeometry g = var_geometry(layout->n_elems, norm_out ? kVarMaxGrid : kVarMaxGridCopy);
   bool planned = false;
   const uint8_t* mask = all_blocks ? nullptr : mark_blocks(layout, idx, n_idx, workspace, g, &planned, st);
   if (copy == COPY_X_TO_C)
@@ -367,7 +379,7 @@ extern "C" int scar_var_block_scores(const scar_var_layout* layout, const void* 
   const int rc = check_var_workspace(workspace, workspace_bytes, nb);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;
-  const VarGeometry g = var_geometry(layout->n_elems);
+  const VarGeometry g = var_geometry(layout->n_elems, kVarMaxGridCopy);
   if (layout->n_elems) dispatch_walk<true, COPY_NONE, true>(layout, x, c, nullptr, false, workspace, g, st);
   switch (layout->dtype) {
     case SCAR_I32: launch_scores_finish<DT_I32>(layout, workspace, g, scores, st); break;
