@@ -109,3 +109,22 @@ def test_edge_cases():
     assert torch.equal(x, c)
     with pytest.raises(scar.ScarError):
         scar.var_block_scores(x, c, off, ws[:256])
+
+
+def test_random_by_layer_stores():
+    # 30 seeded stores: block count, block sizes (zeros, tiny, huge), element type, alignment,
+    # checkpoint size and lost set all drawn at random; sizes on both sides of the limit up to
+    # which marking and planning share one launch (1,024 ranges = 4 M elements)
+    r = np.random.default_rng(77)
+    for case in range(30):
+        nb = int(r.integers(1, 400))
+        total = int(r.choice([50, 3000, 200_000, 3_000_000, 4_300_000, 9_000_000]))
+        sizes = wl.mixed_layer_sizes(nb, total, seed=100 + case)
+        dtype = int(r.choice([wl.F32, wl.BF16, wl.I32]))
+        w = wl.layers_like(sizes, seed=200 + case, fraction=float(r.uniform(0.0, 1.0)),
+                           n_lost=int(r.integers(0, nb + 1)), dtype=dtype)
+        print("random by-layer case %d dtype=%d blocks=%d elems=%d k=%d lost=%d"
+              % (case, dtype, nb, w.x.size, w.k, w.lost.size), flush=True)
+        if w.x.size == 0:
+            continue
+        cycle(w, unaligned=bool(r.integers(0, 2)))
