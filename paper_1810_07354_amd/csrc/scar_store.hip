@@ -140,7 +140,18 @@ int finish_open(scar_store* s, uint32_t max_rows, scar_store** out) {
     delete s;
     return SCAR_ERR_DEVICE;
   }
-  s->writer = std::thread([s] { s->run(); });
+  try {
+    s->writer = std::thread([s] { s->run(); });
+  } catch (...) {  // no thread to be had: undo everything, nothing leaves this call but a status
+    for (Slot& sl : s->slot) {
+      (void)hipHostFree(sl.rows);
+      (void)hipHostFree(sl.idx);
+      (void)hipEventDestroy(sl.copied);
+    }
+    close(s->fd);
+    delete s;
+    return SCAR_ERR_DEVICE;
+  }
   *out = s;
   return SCAR_OK;
 }
