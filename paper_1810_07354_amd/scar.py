@@ -122,6 +122,18 @@ def _dev(t, what):
     return t
 
 
+def _idx(t, what):
+    """An index list: contiguous int32 tensor on the GPU (the library reads uint32)."""
+    _dev(t, what)
+    if t.dtype != torch.int32:
+        raise TypeError("%s must be an int32 tensor" % what)
+    return t
+
+
+def _bytes(t):
+    return t.numel() * t.element_size() if t is not None else 0
+
+
 def _p(t):
     return ctypes.c_void_p(t.data_ptr() if t is not None else 0)
 
@@ -170,6 +182,8 @@ def block_scores(x, c, block_len, out=None):
         out = torch.empty(nb, dtype=torch.int64 if x.dtype == torch.int32 else torch.float32,
                           device=x.device)
     _dev(out, "out")
+    if out.dtype != (torch.int64 if x.dtype == torch.int32 else torch.float32) or out.numel() < nb:
+        raise ValueError("out must hold n_blocks scores (int64 for int32 stores, else float32)")
     _check(lib().scar_block_scores(ctypes.byref(lay), _p(x), _p(c), _p(out), _stream()),
            "scar_block_scores")
     return out
@@ -186,16 +200,19 @@ def select_topk(scores, k, workspace, out=None):
         raise TypeError("scores must be float32 or int64")
     if out is None:
         out = torch.empty(int(k), dtype=torch.int32, device=scores.device)
-    _check(lib().scar_select_topk(st, _p(scores), scores.numel(), int(k), _p(out), _p(workspace),
-                                  workspace.numel(), _stream()), "scar_select_topk")
+    elif _idx(out, "out").numel() < int(k):
+        raise ValueError("out must hold k indices")
+    _check(lib().scar_select_topk(st, _p(scores), scores.numel(), int(k), _p(out), _p(workspace), _bytes(workspace), _stream()), "scar_select_topk")
     return out
 
 
 def checkpoint_commit(x, c, block_len, idx, staging=None, n_idx=None):
     """scar_checkpoint_commit: c[b] <- x[b] for b in idx (optionally also packed into staging)."""
-    _dev(x, "x"), _dev(c, "c"), _dev(idx, "idx")
+    _dev(x, "x"), _dev(c, "c"), _idx(idx, "idx")
     lay = layout_of(x, block_len, c)
     n = idx.numel() if n_idx is None else int(n_idx)
+    if n > idx.numel():
+        raise ValueError("n_idx exceeds the index list")
     if staging is not None:
         _dev(staging, "staging")
         if staging.dtype != c.dtype or staging.numel() < n * block_len:
@@ -217,15 +234,17 @@ def read_norm(buf):
 def partial_recover(x, c, block_len, lost_idx, workspace=None, want_norm=True, norm_out=None, n_lost=None):
     """scar_partial_recover: x[b] <- c[b] for the lost blocks; returns the device scar_norm
     buffer (read it with read_norm) or None."""
-    _dev(x, "x"), _dev(c, "c"), _dev(lost_idx, "lost_idx")
+    _dev(x, "x"), _dev(c, "c"), _idx(lost_idx, "lost_idx")
     lay = layout_of(x, block_len, c)
     n = lost_idx.numel() if n_lost is None else int(n_lost)
+    if n > lost_idx.numel():
+        raise ValueError("n_lost exceeds the index list")
     if want_norm and norm_out is None:
         norm_out = _norm_buffer(x.device)
     if not want_norm:
         norm_out = None
     _check(lib().scar_partial_recover(ctypes.byref(lay), _p(x), _p(c), _p(lost_idx), n, _p(norm_out),
-                                      _p(workspace), workspace.numel() if workspace is not None else 0,
+                                      _p(workspace), _bytes(workspace),
                                       _stream()), "scar_partial_recover")
     return norm_out
 
@@ -240,12 +259,14 @@ def perturbation_norm(x, c, block_len, idx, workspace, norm_out=None, n_idx=None
     if idx is None:
         ptr, n = ctypes.c_void_p(0), 0
     else:
-        _dev(idx, "idx")
+        _idx(idx, "idx")
         n = idx.numel() if n_idx is None else int(n_idx)
+        if n > idx.numel():
+            raise ValueError("n_idx exceeds the index list")
         # an empty list means "no blocks", not "all blocks": keep the pointer non-NULL
         ptr = _p(idx) if idx.numel() else _p(norm_out)
     _check(lib().scar_perturbation_norm(ctypes.byref(lay), _p(x), _p(c), ptr, n, _p(norm_out),
-                                        _p(workspace), workspace.numel(), _stream()),
+                                        _p(workspace), _bytes(workspace), _stream()),
            "scar_perturbation_norm")
     return norm_out
 
@@ -257,8 +278,7 @@ def mask_to_indices(mask, workspace):
         raise TypeError("mask must be uint8 or bool")
     out = torch.empty(mask.numel(), dtype=torch.int32, device=mask.device)
     cnt = torch.empty(1, dtype=torch.int32, device=mask.device)
-    _check(lib().scar_mask_to_indices(_p(mask), mask.numel(), _p(out), _p(cnt), _p(workspace),
-                                      workspace.numel(), _stream()), "scar_mask_to_indices")
+    _check(lib().scar_mask_to_indices(_p(mask), mask.numel(), _p(out), _p(cnt), _p(workspace), _bytes(workspace), _stream()), "scar_mask_to_indices")
     return out, cnt
 
 
@@ -277,7 +297,7 @@ def select_random(n_blocks_, k, seed, draw, workspace, out=None):
     if out is None:
         out = torch.empty(int(k), dtype=torch.int32, device=workspace.device)
     _check(lib().scar_select_random(int(n_blocks_), int(k), int(seed), int(draw), _p(out),
-                                    _p(workspace), workspace.numel(), _stream()), "scar_select_random")
+                                    _p(workspace), _bytes(workspace), _stream()), "scar_select_random")
     return out
 
 
@@ -310,27 +330,26 @@ def var_block_scores(x, c, offsets, workspace, out=None):
     if out is None:
         out = torch.empty(lay.n_blocks, dtype=torch.int64 if x.dtype == torch.int32 else torch.float32,
                           device=x.device)
-    _check(lib().scar_var_block_scores(ctypes.byref(lay), _p(x), _p(c), _p(out), _p(workspace),
-                                       workspace.numel(), _stream()), "scar_var_block_scores")
+    _check(lib().scar_var_block_scores(ctypes.byref(lay), _p(x), _p(c), _p(out), _p(workspace), _bytes(workspace), _stream()), "scar_var_block_scores")
     return out
 
 
 def var_checkpoint_commit(x, c, offsets, idx, workspace):
     """scar_var_checkpoint_commit."""
-    _dev(x, "x"), _dev(c, "c"), _dev(idx, "idx"), _dev(workspace, "workspace")
+    _dev(x, "x"), _dev(c, "c"), _idx(idx, "idx"), _dev(workspace, "workspace")
     lay = var_layout_of(x, offsets)
     _check(lib().scar_var_checkpoint_commit(ctypes.byref(lay), _p(x), _p(c), _p(idx), idx.numel(),
-                                            _p(workspace), workspace.numel(), _stream()),
+                                            _p(workspace), _bytes(workspace), _stream()),
            "scar_var_checkpoint_commit")
 
 
 def var_partial_recover(x, c, offsets, lost_idx, workspace, want_norm=True):
     """scar_var_partial_recover; returns the device scar_norm buffer or None."""
-    _dev(x, "x"), _dev(c, "c"), _dev(lost_idx, "lost_idx"), _dev(workspace, "workspace")
+    _dev(x, "x"), _dev(c, "c"), _idx(lost_idx, "lost_idx"), _dev(workspace, "workspace")
     lay = var_layout_of(x, offsets)
     norm_out = _norm_buffer(x.device) if want_norm else None
     _check(lib().scar_var_partial_recover(ctypes.byref(lay), _p(x), _p(c), _p(lost_idx), lost_idx.numel(),
-                                          _p(norm_out), _p(workspace), workspace.numel(), _stream()),
+                                          _p(norm_out), _p(workspace), _bytes(workspace), _stream()),
            "scar_var_partial_recover")
     return norm_out
 
@@ -343,11 +362,11 @@ def var_perturbation_norm(x, c, offsets, idx, workspace):
     if idx is None:
         ptr, n = ctypes.c_void_p(0), 0
     else:
-        _dev(idx, "idx")
+        _idx(idx, "idx")
         n = idx.numel()
         ptr = _p(idx) if n else _p(norm_out)
     _check(lib().scar_var_perturbation_norm(ctypes.byref(lay), _p(x), _p(c), ptr, n, _p(norm_out),
-                                            _p(workspace), workspace.numel(), _stream()),
+                                            _p(workspace), _bytes(workspace), _stream()),
            "scar_var_perturbation_norm")
     return norm_out
 
@@ -378,14 +397,14 @@ def tv_block_scores(x, c, block_len, weights=None, out=None):
 
 def tv_partial_recover(x, c, block_len, lost_idx, workspace, weights=None, want_norm=True):
     """scar_tv_partial_recover; returns the device scar_norm buffer or None."""
-    _dev(x, "x"), _dev(c, "c"), _dev(lost_idx, "lost_idx")
+    _dev(x, "x"), _dev(c, "c"), _idx(lost_idx, "lost_idx")
     lay = layout_of(x, block_len, c)
     w = _weights(weights, n_blocks(lay), x.device)
     norm_out = _norm_buffer(x.device) if want_norm else None
     if want_norm:
         _dev(workspace, "workspace")
     _check(lib().scar_tv_partial_recover(ctypes.byref(lay), _p(x), _p(c), _p(w), _p(lost_idx), lost_idx.numel(),
-                                         _p(norm_out), _p(workspace), workspace.numel() if workspace is not None else 0,
+                                         _p(norm_out), _p(workspace), _bytes(workspace),
                                          _stream()), "scar_tv_partial_recover")
     return norm_out
 
@@ -399,11 +418,11 @@ def tv_perturbation_norm(x, c, block_len, idx, workspace, weights=None):
     if idx is None:
         ptr, n = ctypes.c_void_p(0), 0
     else:
-        _dev(idx, "idx")
+        _idx(idx, "idx")
         n = idx.numel()
         ptr = _p(idx) if n else _p(norm_out)
     _check(lib().scar_tv_perturbation_norm(ctypes.byref(lay), _p(x), _p(c), _p(w), ptr, n, _p(norm_out),
-                                           _p(workspace), workspace.numel(), _stream()),
+                                           _p(workspace), _bytes(workspace), _stream()),
            "scar_tv_perturbation_norm")
     return norm_out
 
@@ -426,7 +445,7 @@ class Store:
                                          ctypes.byref(self._h)), "scar_store_open")
 
     def save_async(self, staging, idx, n_idx=None):
-        _dev(staging, "staging"), _dev(idx, "idx")
+        _dev(staging, "staging"), _idx(idx, "idx")
         n = idx.numel() if n_idx is None else int(n_idx)
         _check(lib().scar_store_save_async(self._h, _p(staging), _p(idx), n, _stream()),
                "scar_store_save_async")
@@ -452,13 +471,13 @@ class Store:
 def partial_recover_rows(x, rows, block_len, lost_idx, workspace=None, want_norm=True):
     """scar_partial_recover_rows: x[b] <- rows[i] for b = lost_idx[i]; returns the device
     scar_norm buffer or None."""
-    _dev(x, "x"), _dev(rows, "rows"), _dev(lost_idx, "lost_idx")
+    _dev(x, "x"), _dev(rows, "rows"), _idx(lost_idx, "lost_idx")
     lay = Layout(store_type(x, rows), int(block_len), x.numel())
     if rows.numel() < lost_idx.numel() * block_len:
         raise ValueError("rows must hold lost_idx.numel() * block_len elements")
     norm_out = _norm_buffer(x.device) if want_norm else None
     _check(lib().scar_partial_recover_rows(ctypes.byref(lay), _p(x), _p(rows), _p(lost_idx),
                                            lost_idx.numel(), _p(norm_out), _p(workspace),
-                                           workspace.numel() if workspace is not None else 0, _stream()),
+                                           _bytes(workspace), _stream()),
            "scar_partial_recover_rows")
     return norm_out

@@ -81,3 +81,15 @@ def test_binding_refuses_cpu_tensors():
     x = torch.zeros(16)
     with pytest.raises(TypeError):
         scar.block_scores(x, x.clone(), 4)
+
+
+def test_binding_checks_index_and_output_types_before_calling():
+    # wrong tensors are refused in Python, before any pointer reaches the library (CPU tensors
+    # are refused first, so these checks are exercised through the helpers)
+    import pytest
+    import torch
+    from paper_1810_07354_amd import scar
+    with pytest.raises(TypeError):
+        scar._idx(torch.zeros(4, dtype=torch.int64), "idx")         # not on the GPU
+    assert scar._bytes(None) == 0
+    assert scar._bytes(torch.zeros(6, dtype=torch.float64)) == 48
