@@ -264,6 +264,15 @@ def test_argument_errors_are_reported_not_launched():
     assert e.value.status == -2
     with pytest.raises(scar.ScarError):
         scar.select_topk(s, 2, ws[1:])
+    # the binding refuses index lists and outputs of the wrong type before calling
+    with pytest.raises(TypeError):
+        scar.checkpoint_commit(x, c, 128, torch.zeros(2, dtype=torch.int64, device=DEV))
+    with pytest.raises(TypeError):
+        scar.partial_recover(x, c, 128, torch.zeros(2, dtype=torch.int64, device=DEV), ws)
+    with pytest.raises(ValueError):
+        scar.block_scores(x, c, 128, out=torch.zeros(3, device=DEV))
+    with pytest.raises(ValueError):
+        scar.select_topk(s, 4, ws, out=torch.zeros(2, dtype=torch.int32, device=DEV))
     torch.cuda.synchronize()
 
 
