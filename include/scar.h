@@ -115,7 +115,10 @@ size_t scar_workspace_bytes(uint64_t n_blocks);
  *   I32:        scores = int64_t[n_blocks], s_b = sum_j |x_j - c_j|, exact (for a row of
  *               topic counts this is twice the document-length-scaled total variation of
  *               Appendix C).
- * Reads x and c once; writes scores. */
+ * Reads x and c once; writes scores.  A block is summed by one workgroup at most, which suits
+ * thousands of blocks and more; a store cut into a few hundred very long blocks is scanned at
+ * full rate by scar_var_block_scores instead (its workspace lets many workgroups share a
+ * block).  The copy calls below have no such limit: long rows are handed out in 4 KiB pieces. */
 int scar_block_scores(const scar_layout* layout, const void* x, const void* c, void* scores,
                       void* stream);
 

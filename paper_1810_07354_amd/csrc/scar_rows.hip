@@ -11,31 +11,60 @@
 
 namespace scar {
 
+// Long rows are handed out in pieces of kPieceBytes, so that a few long rows fill the chip as
+// well as many short ones (and every piece takes the loop-free path): the grid's y dimension
+// runs over the pieces of a row, its x dimension over the index list.  pieces == 1: whole rows
+// of any length.
+constexpr uint32_t kPieceBytes = 4096;
+
+struct RowPiece {
+  uint64_t byte_off;   // of the piece within x and c
+  uint32_t row_off;    // of the piece within its row, in bytes
+  uint32_t len;        // elements
+};
+
+// False if there is nothing there (index out of range, piece beyond a short last block).
+template <int E>
+__device__ __forceinline__ bool row_piece(uint32_t b, uint32_t piece, uint32_t pieces, uint32_t n_blocks,
+                                          uint64_t n_elems, uint32_t block_len, RowPiece* out) {
+  if (b >= n_blocks) return false;
+  const BlockSpan sp = block_span(b, n_elems, block_len, E);
+  constexpr uint32_t kPieceElems = kPieceBytes / E;
+  const uint32_t first = piece * kPieceElems;
+  if (first >= sp.len) return false;
+  uint32_t len = sp.len - first;
+  if (pieces > 1 && len > kPieceElems) len = kPieceElems;
+  *out = {sp.byte_off + (uint64_t)first * E, first * (uint32_t)E, len};
+  return true;
+}
+
 // c_b <- x_b (and staging row i <- x_b) for b = idx[i].
 template <int G, typename W>
 __global__ __launch_bounds__(kWG) void k_commit(const char* __restrict__ x, char* __restrict__ c,
                                                 const uint32_t* __restrict__ idx, uint32_t n_idx,
                                                 char* __restrict__ staging, uint64_t n_elems,
-                                                uint32_t block_len, uint32_t n_blocks, bool vec,
-                                                bool vec_staging) {
+                                                uint32_t block_len, uint32_t n_blocks, uint32_t pieces,
+                                                bool vec, bool vec_staging) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
   const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
-  for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
-       i += (uint64_t)gridDim.x * GPW) {
-    const uint32_t b = idx[i];
-    if (b >= n_blocks) continue;
-    const BlockSpan sp = block_span(b, n_elems, block_len, sizeof(W));
-    char* st = staging ? staging + i * (uint64_t)block_len * sizeof(W) : nullptr;
-    block_copy<G, W>(x + sp.byte_off, c + sp.byte_off, st, sp.len * (uint32_t)sizeof(W), lane, vec,
-                     vec_staging);
+  for (uint32_t piece = blockIdx.y; piece < pieces; piece += gridDim.y) {
+    for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
+         i += (uint64_t)gridDim.x * GPW) {
+      RowPiece rp;
+      if (!row_piece<sizeof(W)>(idx[i], piece, pieces, n_blocks, n_elems, block_len, &rp)) continue;
+      char* st = staging ? staging + i * (uint64_t)block_len * sizeof(W) + rp.row_off : nullptr;
+      block_copy<G, W>(x + rp.byte_off, c + rp.byte_off, st, rp.len * (uint32_t)sizeof(W), lane, vec,
+                       vec_staging);
+    }
   }
 }
 
-// One row of the recovery / norm pass, spread over a group of G lanes: acc gets this lane's
-// share of sum (c - x)^2 or sum |c - x| (NORM), then x <- c (STORE).
-//   VEC: both rows start 16-byte aligned and are whole 16-byte steps (up to a tail that only
-//   the store's last, short block has); otherwise the row is split as row_split says.
+// One row (or one piece of a long row) of the recovery / norm pass, spread over a group of G
+// lanes: acc gets this lane's share of sum (c - x)^2 or sum |c - x| (NORM), then x <- c (STORE).
+//   VEC: both rows start 16-byte aligned and hold at most G 16-byte steps - the host sizes G
+//   and the pieces for that - plus a tail that only the store's last, short block can have:
+//   one load per stream and lane, no loop.  Otherwise the row is split as row_split says.
 template <int DT, int G, bool STORE, bool NORM, bool VEC>
 __device__ __forceinline__ void recover_row(char* xb, const char* cb, uint32_t len, int lane,
                                             typename Acc<DT>::type& acc) {
@@ -46,27 +75,23 @@ __device__ __forceinline__ void recover_row(char* xb, const char* cb, uint32_t l
     if (NORM) accumulate_elem<DT>(acc, cb, xb, j);
     if (STORE) ((word_t*)xb)[j] = ((const word_t*)cb)[j];
   };
-  uint32_t head = 0, nvec = len / EPV;
   if constexpr (VEC) {
-    if (nvec <= (uint32_t)G) {
-      // the usual case (the host sizes G for one 16-byte step per lane): no inner loop
-      if ((uint32_t)lane < nvec) {
-        uint4 cv[1], xv[1];
-        cv[0] = load_stream((const uint4*)cb + lane);
-        if (NORM) {
-          xv[0] = load_stream((const uint4*)xb + lane);
-          accumulate_vec<DT, 1>(acc, cv, xv);
-        }
-        if (STORE) store_stream((uint4*)xb + lane, cv[0]);
+    const uint32_t nvec = len / EPV;
+    if ((uint32_t)lane < nvec) {
+      uint4 cv[1], xv[1];
+      cv[0] = load_stream((const uint4*)cb + lane);
+      if (NORM) {
+        xv[0] = load_stream((const uint4*)xb + lane);
+        accumulate_vec<DT, 1>(acc, cv, xv);
       }
-      for (uint32_t j = nvec * EPV + lane; j < len; j += G) element(j);
-      return;
+      if (STORE) store_stream((uint4*)xb + lane, cv[0]);
     }
-  } else {
-    const RowSplit rs = row_split<E>(xb, cb, len);
-    head = rs.head, nvec = rs.nvec;
-    for (uint32_t j = lane; j < head; j += G) element(j);
+    for (uint32_t j = nvec * EPV + lane; j < len; j += G) element(j);
+    return;
   }
+  const RowSplit rs = row_split<E>(xb, cb, len);
+  const uint32_t head = rs.head, nvec = rs.nvec;
+  for (uint32_t j = lane; j < head; j += G) element(j);
   uint4* xvp = (uint4*)(xb + (size_t)head * E);
   const uint4* cvp = (const uint4*)(cb + (size_t)head * E);
   for (uint32_t v0 = 0; v0 < nvec; v0 += G * kUnroll) {
@@ -98,15 +123,17 @@ __device__ __forceinline__ void recover_row(char* xb, const char* cb, uint32_t l
 //   STORE: x_b <- c_b after the block has been measured.
 //   NORM:  partial[blockIdx.x] <- this workgroup's share of sum (c - x)^2 or sum |c - x|.
 //   weights (total-variation kinds only): per-block factors of the sum, NULL = 1.
-//   T:     threads per workgroup, T / G groups.  Long index lists run with 1,024 threads: a
+//   T:     threads per workgroup, T / G groups.  The second launch bound asks for 8 wavefronts
+//          per SIMD when T = 1,024 (at most 64 registers), so that two such workgroups fit a
+//          compute unit; with one more register the kernel runs a quarter slower.  Long index lists run with 1,024 threads: a
 //          workgroup that has to come back for a second entry waits a full memory round trip
 //          in between (131,072 rows of 4 KiB: 298 us with two entries per group, 283 us with
 //          one), and a quarter of the workgroups also means a quarter of the partial sums.
 template <int DT, int G, int T, bool STORE, bool NORM, bool VEC>
-__global__ __launch_bounds__(T) void k_recover(char* __restrict__ x, const char* __restrict__ c,
+__global__ __launch_bounds__(T, T / 128) void k_recover(char* __restrict__ x, const char* __restrict__ c,
                                                const uint32_t* __restrict__ idx, uint32_t n_idx,
                                                uint64_t n_elems, uint32_t block_len,
-                                               uint32_t n_blocks, bool packed,
+                                               uint32_t n_blocks, uint32_t pieces, bool packed,
                                                typename Acc<DT>::type* __restrict__ partial,
                                                const float* __restrict__ weights) {
   constexpr int GPW = T / G;
@@ -117,24 +144,26 @@ __global__ __launch_bounds__(T) void k_recover(char* __restrict__ x, const char*
   __shared__ acc_t slots[T / kWave];
   acc_t acc = 0;
 
-  for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
-       i += (uint64_t)gridDim.x * GPW) {
-    const uint32_t b = idx ? idx[i] : (uint32_t)i;
-    if (b >= n_blocks) continue;
-    const BlockSpan sp = block_span(b, n_elems, block_len, E);
-    // packed: c holds only the listed blocks, row i = block idx[i] (rows read back from storage)
-    const char* cb = packed ? c + i * (uint64_t)block_len * E : c + sp.byte_off;
-    if constexpr (is_tv(DT)) {  // each row's share counts with the row's weight
-      acc_t row = 0;
-      recover_row<DT, G, STORE, NORM, VEC>(x + sp.byte_off, cb, sp.len, lane, row);
-      acc += (weights ? (double)weights[b] : 1.0) * row;
-    } else {
-      recover_row<DT, G, STORE, NORM, VEC>(x + sp.byte_off, cb, sp.len, lane, acc);
+  for (uint32_t piece = blockIdx.y; piece < pieces; piece += gridDim.y) {
+    for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
+         i += (uint64_t)gridDim.x * GPW) {
+      const uint32_t b = idx ? idx[i] : (uint32_t)i;
+      RowPiece rp;
+      if (!row_piece<E>(b, piece, pieces, n_blocks, n_elems, block_len, &rp)) continue;
+      // packed: c holds only the listed blocks, row i = block idx[i] (rows read back from storage)
+      const char* cb = packed ? c + i * (uint64_t)block_len * E + rp.row_off : c + rp.byte_off;
+      if constexpr (is_tv(DT)) {  // each row's share counts with the row's weight
+        acc_t row = 0;
+        recover_row<DT, G, STORE, NORM, VEC>(x + rp.byte_off, cb, rp.len, lane, row);
+        acc += (weights ? (double)weights[b] : 1.0) * row;
+      } else {
+        recover_row<DT, G, STORE, NORM, VEC>(x + rp.byte_off, cb, rp.len, lane, acc);
+      }
     }
   }
   if (NORM) {
     acc = workgroup_sum<T>(acc, slots);
-    if (threadIdx.x == 0) partial[blockIdx.x] = acc;
+    if (threadIdx.x == 0) partial[blockIdx.y * gridDim.x + blockIdx.x] = acc;
   }
 }
 
@@ -178,32 +207,50 @@ __global__ __launch_bounds__(kFinishThreads) void k_norm_finish(
   }
 }
 
+// Grid size in y for rows cut into `pieces`: one slice per piece while grid_x * grid_y stays
+// within `cap` workgroups (and the 65,535 of the y dimension); slices stride over the rest.
+static uint32_t piece_grid(uint32_t pieces, uint32_t grid_x, uint64_t cap) {
+  uint64_t y = cap / (grid_x ? grid_x : 1);
+  if (y > pieces) y = pieces;
+  if (y > 65535) y = 65535;
+  return y ? (uint32_t)y : 1;
+}
+
 template <int G, typename W>
 static void launch_commit(const scar_layout* l, const void* x, void* c, const uint32_t* idx,
-                          uint32_t n_idx, void* staging, uint32_t n_blocks, bool vec, bool vec_st,
-                          hipStream_t st) {
+                          uint32_t n_idx, void* staging, uint32_t n_blocks, uint32_t pieces, bool vec,
+                          bool vec_st, hipStream_t st) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
   const uint32_t grid = xcd_grid(need, kCopyGridCap);
-  hipLaunchKernelGGL((k_commit<G, W>), dim3(grid), dim3(kWG), 0, st, (const char*)x, (char*)c, idx,
-                     n_idx, (char*)staging, l->n_elems, l->block_len, n_blocks, vec, vec_st);
+  hipLaunchKernelGGL((k_commit<G, W>), dim3(grid, piece_grid(pieces, grid, kCopyGridCap)), dim3(kWG), 0, st, (const char*)x, (char*)c, idx,
+                     n_idx, (char*)staging, l->n_elems, l->block_len, n_blocks, pieces, vec, vec_st);
 }
 
 template <typename W>
 static void dispatch_commit(int g, const scar_layout* l, const void* x, void* c, const uint32_t* idx,
-                            uint32_t n_idx, void* staging, uint32_t n_blocks, bool vec, bool vec_st,
-                            hipStream_t st) {
+                            uint32_t n_idx, void* staging, uint32_t n_blocks, uint32_t pieces, bool vec,
+                            bool vec_st, hipStream_t st) {
+#define SCAR_CALL(G) launch_commit<G, W>(l, x, c, idx, n_idx, staging, n_blocks, pieces, vec, vec_st, st); break
   switch (g) {
-    case 1: launch_commit<1, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
-    case 2: launch_commit<2, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
-    case 4: launch_commit<4, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
-    case 8: launch_commit<8, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
-    case 16: launch_commit<16, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
-    case 32: launch_commit<32, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
-    case 64: launch_commit<64, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
-    case 128: launch_commit<128, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
-    default: launch_commit<256, W>(l, x, c, idx, n_idx, staging, n_blocks, vec, vec_st, st); break;
+    case 1: SCAR_CALL(1);
+    case 2: SCAR_CALL(2);
+    case 4: SCAR_CALL(4);
+    case 8: SCAR_CALL(8);
+    case 16: SCAR_CALL(16);
+    case 32: SCAR_CALL(32);
+    case 64: SCAR_CALL(64);
+    case 128: SCAR_CALL(128);
+    default: SCAR_CALL(256);
   }
+#undef SCAR_CALL
+}
+
+// Pieces per row for the copy kernels: long rows of a 16-byte-aligned store are cut at every
+// kPieceBytes; anything else goes row by row.
+static uint32_t row_pieces(const scar_layout* l, int eb, bool vec) {
+  const uint64_t row_bytes = (uint64_t)l->block_len * eb;
+  return (vec && row_bytes > kPieceBytes) ? (uint32_t)((row_bytes + kPieceBytes - 1) / kPieceBytes) : 1;
 }
 
 // Launches the recovery / norm kernel; returns the number of partial sums it writes.
@@ -212,34 +259,36 @@ constexpr uint64_t kWideFrom = 8192;   // workgroups of kWG threads from which k
 
 template <int DT, int G, int T, bool STORE, bool NORM, bool VEC>
 static uint32_t launch_recover_t(const scar_layout* l, void* x, const void* c, const uint32_t* idx,
-                                 uint32_t n_idx, uint32_t n_blocks, bool packed, void* partial,
-                                 const float* weights, hipStream_t st) {
+                                 uint32_t n_idx, uint32_t n_blocks, uint32_t pieces, bool packed,
+                                 void* partial, const float* weights, hipStream_t st) {
   constexpr int GPW = T / G;
   const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
   const uint32_t grid = xcd_grid(need, kMaxNormGrid);
-  hipLaunchKernelGGL((k_recover<DT, G, T, STORE, NORM, VEC>), dim3(grid), dim3(T), 0, st, (char*)x,
-                     (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, packed,
+  const uint32_t grid_y = piece_grid(pieces, grid, kMaxNormGrid);
+  hipLaunchKernelGGL((k_recover<DT, G, T, STORE, NORM, VEC>), dim3(grid, grid_y), dim3(T), 0, st, (char*)x,
+                     (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, pieces, packed,
                      (typename Acc<DT>::type*)partial, weights);
-  return grid;
+  return grid * grid_y;
 }
 
 template <int DT, int G, bool STORE, bool NORM>
 static uint32_t launch_recover(const scar_layout* l, void* x, const void* c, const uint32_t* idx,
-                               uint32_t n_idx, uint32_t n_blocks, bool vec, bool packed, void* partial,
-                               const float* weights, hipStream_t st) {
+                               uint32_t n_idx, uint32_t n_blocks, uint32_t pieces, bool vec, bool packed,
+                               void* partial, const float* weights, hipStream_t st) {
   if (!vec)
-    return launch_recover_t<DT, G, kWG, STORE, NORM, false>(l, x, c, idx, n_idx, n_blocks, packed, partial, weights, st);
-  if (((uint64_t)n_idx * G + kWG - 1) / kWG >= kWideFrom)
-    return launch_recover_t<DT, G, kWideWG, STORE, NORM, true>(l, x, c, idx, n_idx, n_blocks, packed, partial, weights, st);
-  return launch_recover_t<DT, G, kWG, STORE, NORM, true>(l, x, c, idx, n_idx, n_blocks, packed, partial, weights, st);
+    return launch_recover_t<DT, G, kWG, STORE, NORM, false>(l, x, c, idx, n_idx, n_blocks, pieces, packed, partial, weights, st);
+  if (((uint64_t)n_idx * pieces * G + kWG - 1) / kWG >= kWideFrom)
+    return launch_recover_t<DT, G, kWideWG, STORE, NORM, true>(l, x, c, idx, n_idx, n_blocks, pieces, packed, partial, weights, st);
+  return launch_recover_t<DT, G, kWG, STORE, NORM, true>(l, x, c, idx, n_idx, n_blocks, pieces, packed, partial, weights, st);
 }
 
 template <int DT, bool STORE, bool NORM>
 static uint32_t dispatch_recover_g(int g, const scar_layout* l, void* x, const void* c,
-                                   const uint32_t* idx, uint32_t n_idx, uint32_t n_blocks, bool vec,
-                                   bool packed, void* partial, const float* weights, hipStream_t st) {
+                                   const uint32_t* idx, uint32_t n_idx, uint32_t n_blocks,
+                                   uint32_t pieces, bool vec, bool packed, void* partial,
+                                   const float* weights, hipStream_t st) {
 #define SCAR_CALL(G) \
-  return launch_recover<DT, G, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, vec, packed, partial, weights, st)
+  return launch_recover<DT, G, STORE, NORM>(l, x, c, idx, n_idx, n_blocks, pieces, vec, packed, partial, weights, st)
   switch (g) {
     case 1: SCAR_CALL(1);
     case 2: SCAR_CALL(2);
@@ -257,17 +306,17 @@ static uint32_t dispatch_recover_g(int g, const scar_layout* l, void* x, const v
 // dt: what is measured (a DT_* kind).  The total-variation kinds always measure (NORM).
 template <bool STORE, bool NORM>
 static uint32_t dispatch_recover(int dt, int g, const scar_layout* l, void* x, const void* c,
-                                 const uint32_t* idx, uint32_t n_idx, uint32_t n_blocks, bool vec,
-                                 bool packed, void* partial, const float* weights, hipStream_t st) {
+                                 const uint32_t* idx, uint32_t n_idx, uint32_t n_blocks, uint32_t pieces,
+                                 bool vec, bool packed, void* partial, const float* weights, hipStream_t st) {
   switch (dt) {
-    case DT_F32: return dispatch_recover_g<DT_F32, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, nullptr, st);
-    case DT_BF16: return dispatch_recover_g<DT_BF16, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, nullptr, st);
-    case DT_I32: return dispatch_recover_g<DT_I32, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, nullptr, st);
+    case DT_F32: return dispatch_recover_g<DT_F32, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, pieces, vec, packed, partial, nullptr, st);
+    case DT_BF16: return dispatch_recover_g<DT_BF16, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, pieces, vec, packed, partial, nullptr, st);
+    case DT_I32: return dispatch_recover_g<DT_I32, STORE, NORM>(g, l, x, c, idx, n_idx, n_blocks, pieces, vec, packed, partial, nullptr, st);
     case DT_F32_TV:
-      if constexpr (NORM) return dispatch_recover_g<DT_F32_TV, STORE, true>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, weights, st);
+      if constexpr (NORM) return dispatch_recover_g<DT_F32_TV, STORE, true>(g, l, x, c, idx, n_idx, n_blocks, pieces, vec, packed, partial, weights, st);
       return 0;
     default:
-      if constexpr (NORM) return dispatch_recover_g<DT_BF16_TV, STORE, true>(g, l, x, c, idx, n_idx, n_blocks, vec, packed, partial, weights, st);
+      if constexpr (NORM) return dispatch_recover_g<DT_BF16_TV, STORE, true>(g, l, x, c, idx, n_idx, n_blocks, pieces, vec, packed, partial, weights, st);
       return 0;
   }
 }
@@ -324,18 +373,19 @@ static int recover_or_norm(bool store, bool packed, bool tv, const scar_layout* 
                                  n_idx, norm_out, partial, st);
   if (!aligned(x, eb) || !aligned(c, eb)) return SCAR_ERR_INVALID_ARG;
   const bool vec = aligned(x, 16) && aligned(c, 16) && ((uint64_t)layout->block_len * eb) % 16 == 0;
-  const int g = pick_group(layout->block_len, eb, co_aligned(x, c), 1, true);
+  const uint32_t pieces = row_pieces(layout, eb, vec);
+  const int g = pieces > 1 ? 256 : pick_group(layout->block_len, eb, co_aligned(x, c), 1, true);
   const uint32_t n_blocks = (uint32_t)nb;
   // what the pass measures; a recovery without a norm only copies, whatever the metric
   int dt = layout->dtype == SCAR_F32 ? DT_F32 : (layout->dtype == SCAR_BF16 ? DT_BF16 : DT_I32);
   if (tv && norm_out) dt = layout->dtype == SCAR_F32 ? DT_F32_TV : DT_BF16_TV;
   uint32_t n_partial = 0;
   if (store && norm_out)
-    n_partial = dispatch_recover<true, true>(dt, g, layout, x, c, idx, n_idx, n_blocks, vec, packed, partial, weights, st);
+    n_partial = dispatch_recover<true, true>(dt, g, layout, x, c, idx, n_idx, n_blocks, pieces, vec, packed, partial, weights, st);
   else if (store)
-    dispatch_recover<true, false>(dt, g, layout, x, c, idx, n_idx, n_blocks, vec, packed, nullptr, nullptr, st);
+    dispatch_recover<true, false>(dt, g, layout, x, c, idx, n_idx, n_blocks, pieces, vec, packed, nullptr, nullptr, st);
   else
-    n_partial = dispatch_recover<false, true>(dt, g, layout, x, c, idx, n_idx, n_blocks, vec, packed, partial, weights, st);
+    n_partial = dispatch_recover<false, true>(dt, g, layout, x, c, idx, n_idx, n_blocks, pieces, vec, packed, partial, weights, st);
   if (norm_out) finish(n_partial);
   return launch_status();
 }
@@ -359,12 +409,13 @@ extern "C" int scar_checkpoint_commit(const scar_layout* layout, const void* x, 
   const bool row16 = ((uint64_t)layout->block_len * eb) % 16 == 0;
   const bool vec = aligned(x, 16) && aligned(c, 16) && row16;
   const bool vec_st = vec && staging && aligned(staging, 16);
-  const int g = pick_group(layout->block_len, eb, co_aligned(x, c), 1, true);
+  const uint32_t pieces = row_pieces(layout, eb, vec);
+  const int g = pieces > 1 ? 256 : pick_group(layout->block_len, eb, co_aligned(x, c), 1, true);
   hipStream_t st = (hipStream_t)stream;
   if (eb == 4)
-    dispatch_commit<uint32_t>(g, layout, x, c, idx, n_idx, staging, (uint32_t)nb, vec, vec_st, st);
+    dispatch_commit<uint32_t>(g, layout, x, c, idx, n_idx, staging, (uint32_t)nb, pieces, vec, vec_st, st);
   else
-    dispatch_commit<uint16_t>(g, layout, x, c, idx, n_idx, staging, (uint32_t)nb, vec, vec_st, st);
+    dispatch_commit<uint16_t>(g, layout, x, c, idx, n_idx, staging, (uint32_t)nb, pieces, vec, vec_st, st);
   return launch_status();
 }
 
