@@ -514,6 +514,11 @@ extern "C" int scar_select_topk(int32_t score_type, const void* scores, uint32_t
     return SCAR_ERR_INVALID_ARG;
   const int rc = check_workspace(workspace, workspace_bytes, n_blocks);
   if (rc) return rc;
+  if (k == n_blocks) {  // a full checkpoint: every block, whatever the scores
+    const uint32_t grid = (k + kWG - 1) / kWG < 4096 ? (k + kWG - 1) / kWG : 4096;
+    hipLaunchKernelGGL(k_select_round, dim3(grid), dim3(kWG), 0, (hipStream_t)stream, n_blocks, k, 0u, out_idx);
+    return launch_status();
+  }
   if (score_type == SCAR_SCORE_F32)
     run_select<SRC_F32>(KeyArgs{scores, 0, 0}, n_blocks, k, out_idx, workspace, (hipStream_t)stream);
   else
