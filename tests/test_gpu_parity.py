@@ -434,3 +434,77 @@ def test_out_of_range_list_entries_are_skipped(dtype):
     got = scar.read_norm(scar.partial_recover(x, c, L, idx_dev(lost_mixed), ws))
     assert_norm_matches(got, oracle.partial_recover(dtype, hx, hc, L, lost_good), dtype)
     np.testing.assert_array_equal(to_host(x), hx)
+
+
+@pytest.mark.parametrize("kind", ["by_layer", "total_variation", "bf16_checkpoint"])
+def test_other_cycles_replay_correctly_from_a_hip_graph(kind):
+    # the by-layer, total-variation and reduced-precision paths are kernels only as well
+    r = np.random.default_rng(5)
+    if kind == "by_layer":
+        w = wl.layers_like(wl.mixed_layer_sizes(120, 5_000_000, seed=3), seed=4, fraction=0.2, n_lost=30)
+        x, c = to_dev(w.x, w.dtype), to_dev(w.c, w.dtype)
+        off = torch.from_numpy(w.offsets.astype(np.int64)).to(DEV)
+        nb, k, lost = w.n_blocks, w.k, idx_dev(w.lost)
+        ws, ws_sel = scar.new_var_workspace(nb, DEV), scar.new_workspace(nb, DEV)
+
+        def cycle(x_, c_):
+            s = scar.var_block_scores(x_, c_, off, ws)
+            idx = scar.select_topk(s, k, ws_sel)
+            scar.var_checkpoint_commit(x_, c_, off, idx, ws)
+            return s, idx, scar.var_partial_recover(x_, c_, off, lost, ws)
+    elif kind == "total_variation":
+        L, nb = 100, 30_000
+        hx = r.dirichlet(np.full(L, 0.3), size=nb).astype(np.float32).ravel()
+        hc = r.dirichlet(np.full(L, 0.3), size=nb).astype(np.float32).ravel()
+        x, c = to_dev(hx, F32), to_dev(hc, F32)
+        wts = torch.from_numpy(r.integers(5, 2000, size=nb).astype(np.float32)).to(DEV)
+        k, lost = nb // 8, idx_dev(wl.random_lost_blocks(nb, nb // 4, 9))
+        ws = scar.new_workspace(nb, DEV)
+
+        def cycle(x_, c_):
+            s = scar.tv_block_scores(x_, c_, L, wts)
+            idx = scar.select_topk(s, k, ws)
+            scar.checkpoint_commit(x_, c_, L, idx)
+            return s, idx, scar.tv_partial_recover(x_, c_, L, lost, ws, wts)
+    else:
+        L, nb = 1024, 4096
+        hx, hc = make_store(F32, L * nb, seed=8)
+        x, c = to_dev(hx, F32), to_dev(wl.f32_to_bf16_bits(hc), BF16)
+        k, lost = nb // 10, idx_dev(wl.random_lost_blocks(nb, nb // 8, 9))
+        ws = scar.new_workspace(nb, DEV)
+
+        def cycle(x_, c_):
+            s = scar.block_scores(x_, c_, L)
+            idx = scar.select_topk(s, k, ws)
+            scar.checkpoint_commit(x_, c_, L, idx)
+            return s, idx, scar.partial_recover(x_, c_, L, lost, ws)
+
+    x0, c0 = x.clone(), c.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside the capture
+        cycle(x, c)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    x.copy_(x0), c.copy_(c0)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        s_g, idx_g, norm_g = cycle(x, c)
+    torch.cuda.synchronize()
+    state_x, state_c = x0.clone(), c0.clone()
+    g = torch.Generator(device=DEV)
+    g.manual_seed(2)
+    for rep in range(3):
+        print("%s graph replay %d" % (kind, rep), flush=True)
+        x.copy_(state_x), c.copy_(state_c)
+        graph.replay()
+        torch.cuda.synchronize()
+        x2, c2 = state_x.clone(), state_c.clone()
+        s2, idx2, norm2 = cycle(x2, c2)
+        torch.cuda.synchronize()
+        assert torch.equal(s_g, s2) and torch.equal(idx_g, idx2) and torch.equal(norm_g, norm2)
+        assert torch.equal(x.view(torch.int32), x2.view(torch.int32))
+        assert torch.equal(c.view(torch.int16), c2.view(torch.int16))
+        noise = 1e-3 * torch.empty(x2.numel(), device=DEV).normal_(generator=g)
+        state_x, state_c = (x2 + noise.to(x2.dtype)).contiguous(), c2
+        torch.cuda.synchronize()
