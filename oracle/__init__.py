@@ -42,6 +42,7 @@ def lib():
         L.oracle_set_num_threads.restype = None
         L.oracle_get_num_threads.restype = i32
         L.oracle_block_scores.argtypes = [i32, vp, vp, u64, u32, vp]
+        L.oracle_block_scores_rows.argtypes = [i32, vp, vp, u64, u32, vp, u32, vp]
         L.oracle_select_topk.argtypes = [i32, vp, u32, u32, vp]
         L.oracle_brute_force_topk.argtypes = [i32, vp, u32, u32, vp]
         L.oracle_checkpoint_commit.argtypes = [i32, vp, vp, u64, u32, vp, u32, vp]
@@ -117,6 +118,16 @@ def block_scores(dtype, x, c, block_len):
     _check(lib().oracle_block_scores(dtype, _ptr(x), _ptr(c), x.size, block_len, _ptr(out)),
            "oracle_block_scores")
     return out
+
+
+def block_scores_rows(dtype, x, c, block_len, idx, scores):
+    """Recomputes scores[b] for b in idx, in place; other entries stay."""
+    x, c, idx = _flat_x(x, dtype), _flat_c(c, dtype), _idx(idx)
+    want = np.int64 if dtype == I32 else np.float64
+    assert scores.dtype == want and scores.flags.c_contiguous and scores.size == n_blocks_of(x.size, block_len)
+    _check(lib().oracle_block_scores_rows(dtype, _ptr(x), _ptr(c), x.size, block_len, _ptr(idx), idx.size,
+                                          _ptr(scores)), "oracle_block_scores_rows")
+    return scores
 
 
 def select_topk(scores, k):

@@ -156,6 +156,27 @@ int oracle_block_scores(int dtype, const void *x, const void *c, uint64_t n_elem
   return ORACLE_OK;
 }
 
+/* The same distances for the listed blocks only: scores[b] is recomputed for b in idx and
+ * every other entry is left alone (a trainer that knows which rows an iteration touched
+ * need not look at the rest; the values are those of oracle_block_scores). */
+int oracle_block_scores_rows(int dtype, const void *x, const void *c, uint64_t n_elems,
+                             uint32_t block_len, const uint32_t *idx, uint32_t n_idx, void *scores) {
+  if (!dtype_ok(dtype) || dtype == ORACLE_F32_BF16C || block_len == 0) return ORACLE_ERR_ARG;
+  if (n_idx == 0) return ORACLE_OK;
+  if (!x || !c || !scores) return ORACLE_ERR_ARG;
+  int rc = check_indices(idx, n_idx, count_blocks(n_elems, block_len));
+  if (rc) return rc;
+  for (uint32_t i = 0; i < n_idx; ++i) {
+    uint64_t lo, hi;
+    block_range(idx[i], n_elems, block_len, &lo, &hi);
+    if (dtype == ORACLE_I32)
+      ((int64_t *)scores)[idx[i]] = block_l1((const int32_t *)x, (const int32_t *)c, lo, hi);
+    else
+      ((double *)scores)[idx[i]] = block_sqdist(dtype, x, c, lo, hi);
+  }
+  return ORACLE_OK;
+}
+
 /* ---- checkpoint step 3: the k blocks with the largest distances -------------- */
 
 typedef struct {

@@ -53,6 +53,10 @@ MUTANTS = [
     ("random draw ignores the checkpoint number", "const uint32_t ctr[4] = {b, 0u, (uint32_t)draw, (uint32_t)(draw >> 32)};", "const uint32_t ctr[4] = {b, 0u, 0u, 0u};"),
     ("unequal blocks: score of the next block", "block_sqdist(dtype, x, c, offsets[b], offsets[b + 1]);\n  }\n  return ORACLE_OK;",
      "block_sqdist(dtype, x, c, offsets[b + 1], b + 2 <= n_blocks ? offsets[b + 2 <= n_blocks ? b + 2 : b + 1] : offsets[b + 1]);\n  }\n  return ORACLE_OK;"),
+    ("listed scores stored by list position", "      ((double *)scores)[idx[i]] = block_sqdist(dtype, x, c, lo, hi);",
+     "      ((double *)scores)[i] = block_sqdist(dtype, x, c, lo, hi);"),
+    ("listed integer scores of the block before", "      ((int64_t *)scores)[idx[i]] = block_l1((const int32_t *)x, (const int32_t *)c, lo, hi);",
+     "      ((int64_t *)scores)[idx[i]] = block_l1((const int32_t *)x, (const int32_t *)c, lo - (lo ? 1 : 0), hi);"),
     ("total variation without the half", "  return 0.5 * s;", "  return s;"),
     ("total variation of squares", "s += fabs(load_real(dtype, x, j) - load_real(dtype, c, j));",
      "s += (load_real(dtype, x, j) - load_real(dtype, c, j)) * (load_real(dtype, x, j) - load_real(dtype, c, j));"),

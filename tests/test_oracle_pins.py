@@ -745,3 +745,44 @@ def test_tv_norm_is_the_weighted_sum_of_the_block_distances():
     assert oracle.tv_partial_recover(F32, x, c, L, S, w) == (0.0, 0.0, 0)
     with pytest.raises(oracle.OracleError):
         oracle.tv_block_scores(I32, x.view(np.int32), c.view(np.int32), L)
+
+
+# ------------------------------------------------------------- scores of listed blocks only
+
+@pytest.mark.parametrize("dtype", [F32, BF16, I32])
+def test_rescoring_listed_blocks_equals_rescoring_everything(dtype):
+    r = np.random.default_rng(21 + dtype)
+    L, nb = 7, 40
+    n = L * nb - 3
+    if dtype == I32:
+        c = r.integers(-50, 50, size=n).astype(np.int32)
+        x = c.copy()
+    else:
+        c = r.normal(size=n).astype(np.float32)
+        x = c.copy()
+        if dtype == BF16:
+            x, c = (np.frombuffer(a.tobytes(), dtype=np.uint16)[1::2].copy() for a in (x, c))
+    s = oracle.block_scores(dtype, x, c, L)
+    assert not s.any()
+    touched = np.array([39, 0, 17, 5], dtype=np.uint32)          # unsorted, holds the short tail
+    for b in touched:
+        lo, hi = b * L, min((b + 1) * L, n)
+        if dtype == I32:
+            x[lo:hi] += 3
+        elif dtype == F32:
+            x[lo:hi] += np.float32(0.5)
+        else:
+            x[lo:hi] ^= np.uint16(0x0080)                         # flip a mantissa bit
+    full = oracle.block_scores(dtype, x, c, L)
+    assert full[touched].all() and np.count_nonzero(full) == touched.size
+    stale = s.copy()
+    stale[1] = 123                                                # an entry that must survive
+    got = oracle.block_scores_rows(dtype, x, c, L, touched, stale)
+    want = full.copy()
+    want[1] = 123
+    np.testing.assert_array_equal(got, want)
+    np.testing.assert_array_equal(oracle.block_scores_rows(dtype, x, c, L, np.zeros(0, dtype=np.uint32), stale), want)
+    with pytest.raises(oracle.OracleError):
+        oracle.block_scores_rows(dtype, x, c, L, np.array([40], dtype=np.uint32), stale)
+    with pytest.raises(oracle.OracleError):
+        oracle.block_scores_rows(dtype, x, c, L, np.array([3, 3], dtype=np.uint32), stale)
