@@ -764,7 +764,7 @@ def test_rescoring_listed_blocks_equals_rescoring_everything(dtype):
             x, c = (np.frombuffer(a.tobytes(), dtype=np.uint16)[1::2].copy() for a in (x, c))
     s = oracle.block_scores(dtype, x, c, L)
     assert not s.any()
-    touched = np.array([39, 0, 17, 5], dtype=np.uint32)          # unsorted, holds the short tail
+    touched = np.array([39, 0, 17, 5, 16], dtype=np.uint32)      # unsorted, two neighbours, the short tail
     for b in touched:
         lo, hi = b * L, min((b + 1) * L, n)
         if dtype == I32:
