@@ -122,6 +122,17 @@ size_t scar_workspace_bytes(uint64_t n_blocks);
 int scar_block_scores(const scar_layout* layout, const void* x, const void* c, void* scores,
                       void* stream);
 
+/* The same scores for the listed blocks only: scores[b] is recomputed for every b in idx
+ * (device memory, entries >= n_blocks are skipped) and all other entries of scores are left
+ * as they are.  For trainers that know which rows an iteration touched (sparse updates, as in
+ * matrix factorisation or LDA): between two checkpoints only those rows can have moved, so
+ * rescoring them - and setting the score of a block to 0 when it is saved, which scoring it
+ * after the commit does - keeps `scores` equal to what the full scan would give, at a
+ * fraction of the traffic.  (An economy on top of the paper's protocol, which looks at every
+ * parameter at every checkpoint.)  Not for SCAR_F32_BF16C. */
+int scar_block_scores_rows(const scar_layout* layout, const void* x, const void* c,
+                           const uint32_t* idx, uint32_t n_idx, void* scores, void* stream);
+
 /* Checkpoint step 3 (Section 4.3): the k blocks with the largest scores - "the
  * parameters which have changed the most since they were previously saved"
  * (Section 4.2).  The order is total: larger score first, equal scores to the lower

@@ -11,20 +11,29 @@
 
 namespace scar {
 
-template <int DT, int G, bool VEC>
+// LISTED: only the blocks idx[0..n_idx) are scored (entries >= n_blocks are skipped) and the
+// other entries of scores stay as they are; otherwise every block is.
+template <int DT, int G, bool VEC, bool LISTED>
 __global__ __launch_bounds__(kWG) void k_block_scores(const char* __restrict__ x,
                                                       const char* __restrict__ c,
                                                       void* __restrict__ scores, uint64_t n_elems,
                                                       uint32_t block_len, uint32_t n_blocks,
-                                                      const float* __restrict__ weights) {
+                                                      const float* __restrict__ weights,
+                                                      const uint32_t* __restrict__ idx, uint32_t n_idx) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;  // groups (= blocks in flight) per workgroup
   using acc_t = typename Acc<DT>::type;
   const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
   const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
   __shared__ acc_t slots[kWG / kWave];
 
-  for (uint64_t b = (uint64_t)xcd_contiguous_block_id() * GPW + grp; b < n_blocks;
-       b += (uint64_t)gridDim.x * GPW) {
+  const uint64_t n_items = LISTED ? n_idx : n_blocks;
+  for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_items;
+       i += (uint64_t)gridDim.x * GPW) {
+    uint64_t b = i;
+    if constexpr (LISTED) {
+      b = idx[i];
+      if (b >= n_blocks) continue;
+    }
     const BlockSpan sp = block_span(b, n_elems, block_len, elem_bytes(DT));
     acc_t acc = block_distance<DT, G, VEC>(x + sp.byte_off, c + sp.byte_off, sp.len, lane);
     if constexpr (G == 256)
@@ -44,30 +53,41 @@ __global__ __launch_bounds__(kWG) void k_block_scores(const char* __restrict__ x
 
 template <int DT, int G>
 static void launch_scores(const scar_layout* l, const void* x, const void* c, void* scores,
-                          uint32_t n_blocks, bool vec, const float* weights, hipStream_t st) {
+                          uint32_t n_blocks, bool vec, const float* weights, const uint32_t* idx,
+                          uint32_t n_idx, hipStream_t st) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
-  const uint64_t need = ((uint64_t)n_blocks + GPW - 1) / GPW;
+  const uint64_t need = ((uint64_t)(idx ? n_idx : n_blocks) + GPW - 1) / GPW;
   const uint32_t grid = xcd_grid(need, kScoreGridCap);
-  if (vec)
-    hipLaunchKernelGGL((k_block_scores<DT, G, true>), dim3(grid), dim3(kWG), 0, st, (const char*)x,
-                       (const char*)c, scores, l->n_elems, l->block_len, n_blocks, weights);
-  else
-    hipLaunchKernelGGL((k_block_scores<DT, G, false>), dim3(grid), dim3(kWG), 0, st, (const char*)x,
-                       (const char*)c, scores, l->n_elems, l->block_len, n_blocks, weights);
+#define SCAR_LAUNCH(VEC, LISTED)                                                                          \
+  hipLaunchKernelGGL((k_block_scores<DT, G, VEC, LISTED>), dim3(grid), dim3(kWG), 0, st, (const char*)x, \
+                     (const char*)c, scores, l->n_elems, l->block_len, n_blocks, weights, idx, n_idx)
+  if (idx) {
+    if (vec)
+      SCAR_LAUNCH(true, true);
+    else
+      SCAR_LAUNCH(false, true);
+  } else {
+    if (vec)
+      SCAR_LAUNCH(true, false);
+    else
+      SCAR_LAUNCH(false, false);
+  }
+#undef SCAR_LAUNCH
 }
 
 template <int DT>
 static void dispatch_scores(int g, const scar_layout* l, const void* x, const void* c, void* scores,
-                            uint32_t n_blocks, bool vec, const float* weights, hipStream_t st) {
+                            uint32_t n_blocks, bool vec, const float* weights, const uint32_t* idx,
+                            uint32_t n_idx, hipStream_t st) {
   switch (g) {
-    case 1: launch_scores<DT, 1>(l, x, c, scores, n_blocks, vec, weights, st); break;
-    case 2: launch_scores<DT, 2>(l, x, c, scores, n_blocks, vec, weights, st); break;
-    case 4: launch_scores<DT, 4>(l, x, c, scores, n_blocks, vec, weights, st); break;
-    case 8: launch_scores<DT, 8>(l, x, c, scores, n_blocks, vec, weights, st); break;
-    case 16: launch_scores<DT, 16>(l, x, c, scores, n_blocks, vec, weights, st); break;
-    case 32: launch_scores<DT, 32>(l, x, c, scores, n_blocks, vec, weights, st); break;
-    case 64: launch_scores<DT, 64>(l, x, c, scores, n_blocks, vec, weights, st); break;
-    default: launch_scores<DT, 256>(l, x, c, scores, n_blocks, vec, weights, st); break;
+    case 1: launch_scores<DT, 1>(l, x, c, scores, n_blocks, vec, weights, idx, n_idx, st); break;
+    case 2: launch_scores<DT, 2>(l, x, c, scores, n_blocks, vec, weights, idx, n_idx, st); break;
+    case 4: launch_scores<DT, 4>(l, x, c, scores, n_blocks, vec, weights, idx, n_idx, st); break;
+    case 8: launch_scores<DT, 8>(l, x, c, scores, n_blocks, vec, weights, idx, n_idx, st); break;
+    case 16: launch_scores<DT, 16>(l, x, c, scores, n_blocks, vec, weights, idx, n_idx, st); break;
+    case 32: launch_scores<DT, 32>(l, x, c, scores, n_blocks, vec, weights, idx, n_idx, st); break;
+    case 64: launch_scores<DT, 64>(l, x, c, scores, n_blocks, vec, weights, idx, n_idx, st); break;
+    default: launch_scores<DT, 256>(l, x, c, scores, n_blocks, vec, weights, idx, n_idx, st); break;
   }
 }
 
@@ -75,13 +95,18 @@ static void dispatch_scores(int g, const scar_layout* l, const void* x, const vo
 
 using namespace scar;
 
-// Shared body of scar_block_scores (tv = false) and scar_tv_block_scores.
-static int block_scores(bool tv, const scar_layout* layout, const void* x, const void* c,
-                        const float* weights, void* scores, void* stream) {
+// Shared body of scar_block_scores (tv = false), scar_tv_block_scores and, with a list of
+// blocks (listed = true), scar_block_scores_rows.
+static int block_scores(bool tv, bool listed, const scar_layout* layout, const void* x, const void* c,
+                        const float* weights, const uint32_t* idx, uint32_t n_idx, void* scores,
+                        void* stream) {
   const uint64_t nb = layout_blocks(layout);
   if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
   if (tv && layout->dtype != SCAR_F32 && layout->dtype != SCAR_BF16) return SCAR_ERR_INVALID_ARG;
-  if (nb == 0) return SCAR_OK;
+  if (listed && layout->dtype == SCAR_F32_BF16C) return SCAR_ERR_INVALID_ARG;
+  if (nb == 0 || (listed && n_idx == 0)) return SCAR_OK;
+  if (listed && (!idx || !aligned(idx, 4))) return SCAR_ERR_INVALID_ARG;
+  if (!listed) idx = nullptr;
   if (layout->dtype == SCAR_F32_BF16C)
     return mixed_block_scores(layout, (uint32_t)nb, x, c, scores, (hipStream_t)stream);
   const int eb = host_elem_bytes(layout->dtype);
@@ -100,25 +125,31 @@ static int block_scores(bool tv, const scar_layout* layout, const void* x, const
   const uint32_t n = (uint32_t)nb;
   if (tv) {
     if (layout->dtype == SCAR_F32)
-      dispatch_scores<DT_F32_TV>(g, layout, x, c, scores, n, vec, weights, st);
+      dispatch_scores<DT_F32_TV>(g, layout, x, c, scores, n, vec, weights, idx, n_idx, st);
     else
-      dispatch_scores<DT_BF16_TV>(g, layout, x, c, scores, n, vec, weights, st);
+      dispatch_scores<DT_BF16_TV>(g, layout, x, c, scores, n, vec, weights, idx, n_idx, st);
     return launch_status();
   }
   switch (layout->dtype) {
-    case SCAR_F32: dispatch_scores<DT_F32>(g, layout, x, c, scores, n, vec, nullptr, st); break;
-    case SCAR_BF16: dispatch_scores<DT_BF16>(g, layout, x, c, scores, n, vec, nullptr, st); break;
-    default: dispatch_scores<DT_I32>(g, layout, x, c, scores, n, vec, nullptr, st); break;
+    case SCAR_F32: dispatch_scores<DT_F32>(g, layout, x, c, scores, n, vec, nullptr, idx, n_idx, st); break;
+    case SCAR_BF16: dispatch_scores<DT_BF16>(g, layout, x, c, scores, n, vec, nullptr, idx, n_idx, st); break;
+    default: dispatch_scores<DT_I32>(g, layout, x, c, scores, n, vec, nullptr, idx, n_idx, st); break;
   }
   return launch_status();
 }
 
 extern "C" int scar_block_scores(const scar_layout* layout, const void* x, const void* c,
                                  void* scores, void* stream) {
-  return block_scores(false, layout, x, c, nullptr, scores, stream);
+  return block_scores(false, false, layout, x, c, nullptr, nullptr, 0, scores, stream);
 }
 
 extern "C" int scar_tv_block_scores(const scar_layout* layout, const void* x, const void* c,
                                     const float* weights, float* scores, void* stream) {
-  return block_scores(true, layout, x, c, weights, scores, stream);
+  return block_scores(true, false, layout, x, c, weights, nullptr, 0, scores, stream);
 }
+
+extern "C" int scar_block_scores_rows(const scar_layout* layout, const void* x, const void* c,
+                                      const uint32_t* idx, uint32_t n_idx, void* scores, void* stream) {
+  return block_scores(false, true, layout, x, c, nullptr, idx, n_idx, scores, stream);
+}
+

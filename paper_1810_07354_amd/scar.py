@@ -64,6 +64,8 @@ def lib():
         L.scar_strerror.argtypes = [ctypes.c_int]
         L.scar_strerror.restype = ctypes.c_char_p
         L.scar_block_scores.argtypes = [lp, vp, vp, vp, vp]
+        L.scar_block_scores_rows.argtypes = [lp, vp, vp, vp, u32, vp, vp]
+        L.scar_block_scores_rows.restype = ctypes.c_int
         L.scar_select_topk.argtypes = [i32, vp, u32, u32, vp, vp, sz, vp]
         L.scar_checkpoint_commit.argtypes = [lp, vp, vp, vp, u32, vp, vp]
         L.scar_partial_recover.argtypes = [lp, vp, vp, vp, u32, vp, vp, sz, vp]
@@ -187,6 +189,17 @@ def block_scores(x, c, block_len, out=None):
     _check(lib().scar_block_scores(ctypes.byref(lay), _p(x), _p(c), _p(out), _stream()),
            "scar_block_scores")
     return out
+
+
+def block_scores_rows(x, c, block_len, idx, scores):
+    """scar_block_scores_rows: recomputes scores[b] for b in idx, in place."""
+    _dev(x, "x"), _dev(c, "c"), _idx(idx, "idx"), _dev(scores, "scores")
+    lay = layout_of(x, block_len, c)
+    if scores.dtype != (torch.int64 if x.dtype == torch.int32 else torch.float32) or scores.numel() < n_blocks(lay):
+        raise ValueError("scores must hold n_blocks scores (int64 for int32 stores, else float32)")
+    _check(lib().scar_block_scores_rows(ctypes.byref(lay), _p(x), _p(c), _p(idx), idx.numel(), _p(scores),
+                                        _stream()), "scar_block_scores_rows")
+    return scores
 
 
 def select_topk(scores, k, workspace, out=None):

@@ -55,6 +55,65 @@ def test_block_scores_unaligned_base(dtype, L):
     assert_scores_match(got, oracle.block_scores(dtype, x[1:].copy(), c[1:].copy(), L), dtype)
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16, I32])
+@pytest.mark.parametrize("L", [1, 6, 100, 1000, 1024, 5000])
+def test_block_scores_of_listed_blocks(dtype, L):
+    # scores[b] for b in idx equals the full scan's, every other entry stays as it was; the
+    # list is unsorted, holds the short tail block and two entries out of range (skipped)
+    nb = 3000 if L <= 1024 else 300
+    n = L * nb - L // 2
+    x, c = make_store(dtype, n, seed=11 * L + dtype)
+    nbk = oracle.n_blocks_of(n, L)
+    r = np.random.default_rng(L)
+    listed = np.unique(np.append(r.permutation(nbk)[: nbk // 5], nbk - 1)).astype(np.uint32)
+    r.shuffle(listed)
+    print("listed scores dtype=%d L=%d n_idx=%d" % (dtype, L, listed.size), flush=True)
+    dx, dc = to_dev(x, dtype), to_dev(c, dtype)
+    stale_h = (np.arange(nbk) * 7).astype(np.int64 if dtype == I32 else np.float32)
+    stale = torch.from_numpy(stale_h.copy()).to(DEV)
+    with_bad = np.concatenate([listed[:5], [nbk, 0xFFFFFFFF], listed[5:]]).astype(np.uint32)
+    scar.block_scores_rows(dx, dc, L, idx_dev(with_bad), stale)
+    want = stale_h.astype(np.int64 if dtype == I32 else np.float64)
+    oracle.block_scores_rows(dtype, x, c, L, listed, want)
+    got = stale.cpu().numpy()
+    keep = np.ones(nbk, dtype=bool)
+    keep[listed] = False
+    np.testing.assert_array_equal(got[keep], stale_h[keep])
+    if dtype == I32:
+        np.testing.assert_array_equal(got, want)
+    else:
+        np.testing.assert_allclose(got[listed].astype(np.float64), want[listed], rtol=1e-5, atol=0)
+    # the listed scores are bit for bit those of the full scan
+    full = scar.block_scores(dx, dc, L)
+    assert torch.equal(full[idx_dev(listed).long()], stale[idx_dev(listed).long()])
+    # an empty list changes nothing
+    before = stale.clone()
+    scar.block_scores_rows(dx, dc, L, torch.zeros(0, dtype=torch.int32, device=DEV), stale)
+    assert torch.equal(before, stale)
+
+
+def test_incremental_scores_track_the_full_scan_over_cycles():
+    # a trainer that touches a few rows per iteration keeps `scores` current by rescoring the
+    # touched rows and the saved ones: after every cycle they equal the full scan's, bit for bit
+    L, nb, k = 100, 20_000, 500
+    hx, hc = make_store(F32, L * nb, seed=5)
+    x, c = to_dev(hx, F32), to_dev(hc, F32)
+    ws = scar.new_workspace(nb, DEV)
+    scores = scar.block_scores(x, c, L)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(3)
+    for it in range(4):
+        touched = torch.randperm(nb, device=DEV, generator=g)[:1500].to(torch.int32)
+        rows = x.view(nb, L)
+        rows[touched.long()] += 1e-2 * torch.empty(1500, L, device=DEV).normal_(generator=g)
+        scar.block_scores_rows(x, c, L, touched, scores)
+        idx = scar.select_topk(scores, k, ws)
+        scar.checkpoint_commit(x, c, L, idx)
+        scar.block_scores_rows(x, c, L, idx, scores)            # saved blocks: distance 0 again
+        assert torch.equal(scores, scar.block_scores(x, c, L))
+        assert float(scores[idx.long()].abs().max()) == 0.0
+
+
 def test_block_scores_int_extremes():
     hi = np.full(2048, np.iinfo(np.int32).max, dtype=np.int32)
     lo = np.full(2048, np.iinfo(np.int32).min, dtype=np.int32)
