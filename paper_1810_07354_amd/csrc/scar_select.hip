@@ -231,7 +231,24 @@ __global__ __launch_bounds__(kWG) void k_select_hist(const KeyArgs scores, uint3
     for (int j = 0; j < kHistKeysPerThread; ++j) {
       const uint64_t i = base + (uint64_t)j * kWG;
       const bool match = pass == 0 || (key[j] >> (shift + bits)) == (key_t)cur.prefix;
-      if (i < n && match) atomicAdd(&lh[(uint32_t)(key[j] >> shift) & mask], 1u);
+      const bool on = i < n && match;
+      const uint32_t bin = (uint32_t)(key[j] >> shift) & mask;
+      if constexpr (SRC == SRC_I64) {
+        // the top digits of small integer scores are all alike: a wavefront whose keys fall
+        // into one bin adds its count once instead of 64 adds to the same LDS word in a row
+        const unsigned long long act = __ballot(on);
+        if (act) {
+          const int leader = __ffsll((long long)act) - 1;
+          const uint32_t bin0 = __shfl(bin, leader, kWave);
+          if (__ballot(on && bin == bin0) == act) {
+            if ((int)(threadIdx.x & (kWave - 1)) == leader) atomicAdd(&lh[bin0], (uint32_t)__popcll(act));
+          } else if (on) {
+            atomicAdd(&lh[bin], 1u);
+          }
+        }
+      } else {
+        if (on) atomicAdd(&lh[bin], 1u);
+      }
     }
     tile += gridDim.x;
     if (tile < n_tiles) load_tile(tile, key);
