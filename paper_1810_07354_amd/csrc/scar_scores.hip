@@ -51,6 +51,85 @@ __global__ __launch_bounds__(kWG) void k_block_scores(const char* __restrict__ x
   }
 }
 
+// Rows shorter than 16 bytes (selection per scalar or per pair, block_len = 1, 2 or 4): a group
+// per row would leave a lane with 4 or 8 bytes to fetch.  Here a lane takes a whole 16-byte
+// step of x and of c - RPV = 16 / row bytes rows - and writes their RPV scores; the terms are
+// added as the element-wise walk adds them, so the values are the same bit for bit.
+// Needs 16-byte aligned bases; the elements after the last whole step (fewer than one step)
+// are scored by the first lanes of the first workgroup.
+template <int DT, int EPR>
+__global__ __launch_bounds__(kWG) void k_block_scores_tiny(const char* __restrict__ x,
+                                                           const char* __restrict__ c,
+                                                           void* __restrict__ scores, uint64_t n_elems) {
+  constexpr int E = elem_bytes(DT);
+  constexpr int EPV = 16 / E;
+  constexpr int RPV = EPV / EPR;
+  using acc_t = typename Acc<DT>::type;
+  const uint64_t nvec = n_elems / EPV;
+  auto put = [&](uint64_t row, acc_t acc) {
+    if constexpr (DT == DT_I32)
+      ((long long*)scores)[row] = (long long)acc;
+    else
+      ((float*)scores)[row] = (float)acc;
+  };
+  for (uint64_t v0 = (uint64_t)xcd_contiguous_block_id() * kWG * kUnroll; v0 < nvec;
+       v0 += (uint64_t)gridDim.x * kWG * kUnroll) {
+    uint4 a[kUnroll], b[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint64_t v = v0 + (uint64_t)u * kWG + threadIdx.x;
+      if (v < nvec) {
+        a[u] = load_stream((const uint4*)x + v);
+        b[u] = load_stream((const uint4*)c + v);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint64_t v = v0 + (uint64_t)u * kWG + threadIdx.x;
+      if (v >= nvec) continue;
+#pragma unroll
+      for (int r = 0; r < RPV; ++r) {
+        acc_t acc = 0;
+#pragma unroll
+        for (int e = 0; e < EPR; ++e)  // element r * EPR + e of the 16 bytes held in registers
+          accumulate_elem<DT>(acc, (const char*)&a[u], (const char*)&b[u], (uint64_t)(r * EPR + e));
+        put(v * RPV + r, acc);
+      }
+    }
+  }
+  // what is left after the last whole step: fewer than EPV elements, i.e. fewer than RPV + 1 rows
+  if (blockIdx.x == 0) {
+    const uint64_t first_row = nvec * RPV;
+    const uint64_t row = first_row + threadIdx.x;
+    const uint64_t lo = row * EPR;
+    if (threadIdx.x <= RPV && lo < n_elems) {
+      const uint64_t hi = lo + EPR < n_elems ? lo + EPR : n_elems;
+      acc_t acc = 0;
+      for (uint64_t j = lo; j < hi; ++j) accumulate_elem<DT>(acc, x, c, j);
+      put(row, acc);
+    }
+  }
+}
+
+template <int DT>
+static bool launch_scores_tiny(const scar_layout* l, const void* x, const void* c, void* scores,
+                               hipStream_t st) {
+  constexpr int E = elem_bytes(DT);
+  const uint64_t nvec = l->n_elems / (16 / E);
+  const uint64_t need = (nvec + (uint64_t)kWG * kUnroll - 1) / ((uint64_t)kWG * kUnroll);
+  const uint32_t grid = xcd_grid(need ? need : 1, kScoreGridCap);
+#define SCAR_TINY(EPR)                                                                                  \
+  hipLaunchKernelGGL((k_block_scores_tiny<DT, EPR>), dim3(grid), dim3(kWG), 0, st, (const char*)x,     \
+                     (const char*)c, scores, l->n_elems)
+  switch (l->block_len * E) {
+    case 2: if constexpr (E == 2) { SCAR_TINY(1); return true; } return false;
+    case 4: SCAR_TINY(4 / E); return true;
+    case 8: SCAR_TINY(8 / E); return true;
+    default: return false;
+  }
+#undef SCAR_TINY
+}
+
 template <int DT, int G>
 static void launch_scores(const scar_layout* l, const void* x, const void* c, void* scores,
                           uint32_t n_blocks, bool vec, const float* weights, const uint32_t* idx,
@@ -123,6 +202,15 @@ static int block_scores(bool tv, bool listed, const scar_layout* layout, const v
   if (g == 32 && vec && row_bytes >= 2048) g = 64;  // 2 KiB rows: a whole wavefront, two loads per lane
   hipStream_t st = (hipStream_t)stream;
   const uint32_t n = (uint32_t)nb;
+  if (!tv && !listed && row_bytes < 16 && aligned(x, 16) && aligned(c, 16)) {  // rows of 2, 4 or 8 bytes
+    bool done = false;
+    switch (layout->dtype) {
+      case SCAR_F32: done = launch_scores_tiny<DT_F32>(layout, x, c, scores, st); break;
+      case SCAR_BF16: done = launch_scores_tiny<DT_BF16>(layout, x, c, scores, st); break;
+      default: done = launch_scores_tiny<DT_I32>(layout, x, c, scores, st); break;
+    }
+    if (done) return launch_status();
+  }
   if (tv) {
     if (layout->dtype == SCAR_F32)
       dispatch_scores<DT_F32_TV>(g, layout, x, c, scores, n, vec, weights, idx, n_idx, st);

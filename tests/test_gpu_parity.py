@@ -114,6 +114,18 @@ def test_incremental_scores_track_the_full_scan_over_cycles():
         assert float(scores[idx.long()].abs().max()) == 0.0
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16, I32])
+@pytest.mark.parametrize("L", [1, 2, 4])
+def test_block_scores_of_rows_shorter_than_16_bytes(dtype, L):
+    # per-scalar and per-pair selection: a lane scores several rows from one 16-byte step; every
+    # remainder of the store after the last whole step (0 ... 7 elements, ragged last row) is tried
+    for n in [1, 2, 3, 5, 8, 4096, 100_000, 100_001, 100_002, 100_003, 100_005, 100_007, 1_000_003]:
+        x, c = make_store(dtype, n, seed=n + L)
+        s = scar.block_scores(to_dev(x, dtype), to_dev(c, dtype), L)
+        assert s.numel() == oracle.n_blocks_of(n, L)
+        assert_scores_match(s, oracle.block_scores(dtype, x, c, L), dtype)
+
+
 def test_block_scores_int_extremes():
     hi = np.full(2048, np.iinfo(np.int32).max, dtype=np.int32)
     lo = np.full(2048, np.iinfo(np.int32).min, dtype=np.int32)
