@@ -502,9 +502,10 @@ static void run_select(const KeyArgs scores, uint32_t n, uint32_t k, uint32_t* o
   const uint32_t n_htiles = (uint32_t)(((uint64_t)n + kHistTileKeys - 1) / kHistTileKeys);
   // Every workgroup ends a pass with one global add per non-empty bin, so beyond a few
   // hundred workgroups more of them only add flush traffic: an eighth of the tiles, between
-  // 512 and 2,048 (16.7 M float keys: 434 us with 16,384 workgroups, 192 us with 1,024).
+  // 256 and 2,048 (16.7 M float keys: 434 us with 16,384 workgroups, 192 us with 1,024; on the
+  // benchmark's 2^20 keys a pass averages 9.4 us with 512 workgroups, 7.9 with 256, 9.0 with 128).
   uint32_t hgrid = n_htiles / 8;
-  hgrid = hgrid < 512 ? 512 : (hgrid > 2048 ? 2048 : hgrid);
+  hgrid = hgrid < 256 ? 256 : (hgrid > 2048 ? 2048 : hgrid);
   if (hgrid > n_htiles) hgrid = n_htiles;
   for (int p = 0; p < Key<SRC>::passes; ++p)
     hipLaunchKernelGGL((k_select_hist<SRC>), dim3(hgrid), dim3(kWG), 0, st, scores, n, n_htiles, p, ws);
