@@ -82,6 +82,18 @@ inline uint32_t xcd_grid(uint64_t need, uint64_t cap) {
   return (uint32_t)((g + 7) / 8 * 8);
 }
 
+// The copy kernels hand rows longer than kPieceBytes out in pieces of that size (grid y =
+// piece).  Grid size in y for rows cut into `pieces`: one slice per piece while
+// grid_x * grid_y stays within `cap` workgroups (and the 65,535 of the y dimension); slices
+// stride over the rest.
+constexpr uint32_t kPieceBytes = 4096;
+inline uint32_t piece_grid(uint32_t pieces, uint32_t grid_x, uint64_t cap) {
+  uint64_t y = cap / (grid_x ? grid_x : 1);
+  if (y > pieces) y = pieces;
+  if (y > 65535) y = 65535;
+  return y ? (uint32_t)y : 1;
+}
+
 // Second stage of the norm (defined with the row kernels): adds n_partial partial sums
 // (double, or uint64 for SCAR_I32) in a fixed order and writes *out.
 void launch_finish(int32_t dtype, const void* partial, uint32_t n_partial, scar_norm* out,

@@ -114,37 +114,57 @@ __global__ __launch_bounds__(kWG) void k_mixed_scores(const float* __restrict__ 
   }
 }
 
+// Rows longer than kMixPieceElems elements (4 KiB of x) are handed out in pieces of that
+// length, one per grid-y slice, like the rows of the other store types.
+constexpr uint32_t kMixPieceElems = kPieceBytes / 4;
+
+// Element range [first, first + len) of block b that piece `piece` covers; false if none.
+__device__ __forceinline__ bool mixed_piece(uint32_t b, uint32_t piece, uint32_t pieces, uint32_t n_blocks,
+                                            uint64_t n_elems, uint32_t block_len, uint64_t* elem_off,
+                                            uint32_t* first, uint32_t* len) {
+  if (b >= n_blocks) return false;
+  const BlockSpan sp = block_span(b, n_elems, block_len, 1);  // byte_off = element offset
+  *first = piece * kMixPieceElems;
+  if (*first >= sp.len) return false;
+  *len = sp.len - *first;
+  if (pieces > 1 && *len > kMixPieceElems) *len = kMixPieceElems;
+  *elem_off = sp.byte_off + *first;
+  return true;
+}
+
 // c_b <- round(x_b) (and staging row i <- the same bfloat16 values) for b = idx[i].
 template <int G>
 __global__ __launch_bounds__(kWG) void k_mixed_commit(const float* __restrict__ x, uint16_t* __restrict__ c,
                                                       const uint32_t* __restrict__ idx, uint32_t n_idx,
                                                       uint16_t* __restrict__ staging, uint64_t n_elems,
-                                                      uint32_t block_len, uint32_t n_blocks, bool vec,
-                                                      bool vec_staging) {
+                                                      uint32_t block_len, uint32_t n_blocks, uint32_t pieces,
+                                                      bool vec, bool vec_staging) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
   const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
-  for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
-       i += (uint64_t)gridDim.x * GPW) {
-    const uint32_t b = idx[i];
-    if (b >= n_blocks) continue;
-    const BlockSpan sp = block_span(b, n_elems, block_len, 1);
-    const float* xb = x + sp.byte_off;
-    uint16_t* cb = c + sp.byte_off;
-    uint16_t* sb = staging ? staging + i * (uint64_t)block_len : nullptr;
-    const uint32_t nunit = vec ? sp.len / kMixUnit : 0;
-    for (uint32_t u = lane; u < nunit; u += G) {
-      const uint2 r = round_unit(load_stream((const uint4*)xb + u));
-      store_stream2((uint2*)cb + u, r);
-      if (sb && vec_staging) store_stream2((uint2*)sb + u, r);
+  for (uint32_t piece = blockIdx.y; piece < pieces; piece += gridDim.y) {
+    for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
+         i += (uint64_t)gridDim.x * GPW) {
+      uint64_t off;
+      uint32_t first, len;
+      if (!mixed_piece(idx[i], piece, pieces, n_blocks, n_elems, block_len, &off, &first, &len)) continue;
+      const float* xb = x + off;
+      uint16_t* cb = c + off;
+      uint16_t* sb = staging ? staging + i * (uint64_t)block_len + first : nullptr;
+      const uint32_t nunit = vec ? len / kMixUnit : 0;
+      for (uint32_t u = lane; u < nunit; u += G) {
+        const uint2 r = round_unit(load_stream((const uint4*)xb + u));
+        store_stream2((uint2*)cb + u, r);
+        if (sb && vec_staging) store_stream2((uint2*)sb + u, r);
+      }
+      for (uint32_t j = nunit * kMixUnit + lane; j < len; j += G) {
+        const uint16_t r = (uint16_t)round_bf16(__float_as_uint(xb[j]));
+        cb[j] = r;
+        if (sb) sb[j] = r;
+      }
+      if (sb && !vec_staging)
+        for (uint32_t j = lane; j < nunit * kMixUnit; j += G) sb[j] = (uint16_t)round_bf16(__float_as_uint(xb[j]));
     }
-    for (uint32_t j = nunit * kMixUnit + lane; j < sp.len; j += G) {
-      const uint16_t r = (uint16_t)round_bf16(__float_as_uint(xb[j]));
-      cb[j] = r;
-      if (sb) sb[j] = r;
-    }
-    if (sb && !vec_staging)
-      for (uint32_t j = lane; j < nunit * kMixUnit; j += G) sb[j] = (uint16_t)round_bf16(__float_as_uint(xb[j]));
   }
 }
 
@@ -154,35 +174,39 @@ template <int G, int T, bool STORE, bool NORM>
 __global__ __launch_bounds__(T) void k_mixed_recover(float* __restrict__ x, const uint16_t* __restrict__ c,
                                                      const uint32_t* __restrict__ idx, uint32_t n_idx,
                                                      uint64_t n_elems, uint32_t block_len,
-                                                     uint32_t n_blocks, bool vec, bool packed,
+                                                     uint32_t n_blocks, uint32_t pieces, bool vec, bool packed,
                                                      double* __restrict__ partial) {
   constexpr int GPW = T / G;
   const int lane = threadIdx.x & (G - 1);
   const uint32_t grp = threadIdx.x / G;
   __shared__ double slots[T / kWave];
   double acc = 0;
-  for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
-       i += (uint64_t)gridDim.x * GPW) {
-    const uint32_t b = idx ? idx[i] : (uint32_t)i;
-    if (b >= n_blocks) continue;
-    const BlockSpan sp = block_span(b, n_elems, block_len, 1);
-    float* xb = x + sp.byte_off;
-    const uint16_t* cb = packed ? c + i * (uint64_t)block_len : c + sp.byte_off;
-    const uint32_t nunit = vec ? sp.len / kMixUnit : 0;
-    for (uint32_t u = lane; u < nunit; u += G) {
-      const uint2 cv = load_stream2((const uint2*)cb + u);
-      if (NORM) acc += (double)sqdiff_unit(load_stream((const uint4*)xb + u), cv);
-      if (STORE) store_stream((uint4*)xb + u, widen_unit(cv));
-    }
-    for (uint32_t j = nunit * kMixUnit + lane; j < sp.len; j += G) {
-      const float w = widen_elem(cb, j);
-      if (NORM) acc += (double)sq(xb[j] - w);
-      if (STORE) xb[j] = w;
+  for (uint32_t piece = blockIdx.y; piece < pieces; piece += gridDim.y) {
+    for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
+         i += (uint64_t)gridDim.x * GPW) {
+      uint64_t off;
+      uint32_t first, len;
+      if (!mixed_piece(idx ? idx[i] : (uint32_t)i, piece, pieces, n_blocks, n_elems, block_len, &off, &first,
+                       &len))
+        continue;
+      float* xb = x + off;
+      const uint16_t* cb = packed ? c + i * (uint64_t)block_len + first : c + off;
+      const uint32_t nunit = vec ? len / kMixUnit : 0;
+      for (uint32_t u = lane; u < nunit; u += G) {
+        const uint2 cv = load_stream2((const uint2*)cb + u);
+        if (NORM) acc += (double)sqdiff_unit(load_stream((const uint4*)xb + u), cv);
+        if (STORE) store_stream((uint4*)xb + u, widen_unit(cv));
+      }
+      for (uint32_t j = nunit * kMixUnit + lane; j < len; j += G) {
+        const float w = widen_elem(cb, j);
+        if (NORM) acc += (double)sq(xb[j] - w);
+        if (STORE) xb[j] = w;
+      }
     }
   }
   if (NORM) {
     acc = workgroup_sum<T>(acc, slots);
-    if (threadIdx.x == 0) partial[blockIdx.x] = acc;
+    if (threadIdx.x == 0) partial[blockIdx.y * gridDim.x + blockIdx.x] = acc;
   }
 }
 
@@ -201,6 +225,11 @@ __global__ __launch_bounds__(T) void k_mixed_recover(float* __restrict__ x, cons
 
 static bool mixed_vec(const scar_layout* l, const void* x, const void* c) {
   return aligned(x, 16) && aligned(c, 8) && l->block_len % kMixUnit == 0;
+}
+
+// Pieces per row for the copy kernels (1 unless the store is aligned and rows exceed a piece).
+static uint32_t mixed_pieces(const scar_layout* l, bool vec) {
+  return (vec && l->block_len > kMixPieceElems) ? (l->block_len + kMixPieceElems - 1) / kMixPieceElems : 1;
 }
 
 int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, const void* c,
@@ -237,14 +266,15 @@ int mixed_commit(const scar_layout* l, uint32_t n_blocks, const void* x, void* c
     return SCAR_ERR_INVALID_ARG;
   const bool vec = mixed_vec(l, x, c);
   const bool vec_st = vec && staging && aligned(staging, 8);
-  const int g = pick_group_units(vec ? l->block_len / kMixUnit : l->block_len, 1, true);
+  const uint32_t pieces = mixed_pieces(l, vec);
+  const int g = pieces > 1 ? 256 : pick_group_units(vec ? l->block_len / kMixUnit : l->block_len, 1, true);
 #define CALL(G)                                                                                     \
   {                                                                                                 \
     constexpr int GPW = (G == 256) ? 1 : kWG / G;                                                   \
     const uint32_t grid = xcd_grid(((uint64_t)n_idx + GPW - 1) / GPW, kCopyGridCap);                \
-    hipLaunchKernelGGL((k_mixed_commit<G>), dim3(grid), dim3(kWG), 0, st, (const float*)x,          \
-                       (uint16_t*)c, idx, n_idx, (uint16_t*)staging, l->n_elems, l->block_len,      \
-                       n_blocks, vec, vec_st);                                                      \
+    hipLaunchKernelGGL((k_mixed_commit<G>), dim3(grid, piece_grid(pieces, grid, kCopyGridCap)),     \
+                       dim3(kWG), 0, st, (const float*)x, (uint16_t*)c, idx, n_idx,                 \
+                       (uint16_t*)staging, l->n_elems, l->block_len, n_blocks, pieces, vec, vec_st); \
   }
   SCAR_FOR_GROUP(g, CALL)
 #undef CALL
@@ -253,26 +283,27 @@ int mixed_commit(const scar_layout* l, uint32_t n_blocks, const void* x, void* c
 
 template <bool STORE, bool NORM>
 static uint32_t launch_mixed_recover(int g, const scar_layout* l, uint32_t n_blocks, void* x,
-                                     const void* c, const uint32_t* idx, uint32_t n_idx, bool vec,
-                                     bool packed, void* partial, hipStream_t st) {
-  uint32_t grid = 0;
+                                     const void* c, const uint32_t* idx, uint32_t n_idx, uint32_t pieces,
+                                     bool vec, bool packed, void* partial, hipStream_t st) {
+  uint32_t grid = 0, grid_y = 1;
   constexpr int kWide = 1024;
 #define LAUNCH(G, T)                                                                                  \
   {                                                                                                   \
     grid = xcd_grid(((uint64_t)n_idx + (T / G) - 1) / (T / G), kMaxNormGrid);                         \
-    hipLaunchKernelGGL((k_mixed_recover<G, T, STORE, NORM>), dim3(grid), dim3(T), 0, st, (float*)x,   \
-                       (const uint16_t*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, vec,       \
-                       packed, (double*)partial);                                                     \
+    grid_y = piece_grid(pieces, grid, kMaxNormGrid);                                                  \
+    hipLaunchKernelGGL((k_mixed_recover<G, T, STORE, NORM>), dim3(grid, grid_y), dim3(T), 0, st,      \
+                       (float*)x, (const uint16_t*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, \
+                       pieces, vec, packed, (double*)partial);                                        \
   }
-#define CALL(G)                                              \
-  if (((uint64_t)n_idx * G + kWG - 1) / kWG >= 8192)         \
-    LAUNCH(G, kWide)                                         \
-  else                                                       \
+#define CALL(G)                                                       \
+  if (((uint64_t)n_idx * pieces * G + kWG - 1) / kWG >= 8192)         \
+    LAUNCH(G, kWide)                                                  \
+  else                                                                \
     LAUNCH(G, kWG)
   SCAR_FOR_GROUP(g, CALL)
 #undef CALL
 #undef LAUNCH
-  return grid;
+  return grid * grid_y;
 }
 
 int mixed_recover_or_norm(bool store, bool packed, const scar_layout* l, uint32_t n_blocks, void* x,
@@ -281,14 +312,15 @@ int mixed_recover_or_norm(bool store, bool packed, const scar_layout* l, uint32_
                           hipStream_t st) {
   if (!aligned(x, 4) || !aligned(c, 2)) return SCAR_ERR_INVALID_ARG;
   const bool vec = mixed_vec(l, x, c);
-  const int g = pick_group_units(vec ? l->block_len / kMixUnit : l->block_len, 1, true);
+  const uint32_t pieces = mixed_pieces(l, vec);
+  const int g = pieces > 1 ? 256 : pick_group_units(vec ? l->block_len / kMixUnit : l->block_len, 1, true);
   uint32_t n_partial = 0;
   if (store && norm_out)
-    n_partial = launch_mixed_recover<true, true>(g, l, n_blocks, x, c, idx, n_idx, vec, packed, partial, st);
+    n_partial = launch_mixed_recover<true, true>(g, l, n_blocks, x, c, idx, n_idx, pieces, vec, packed, partial, st);
   else if (store)
-    launch_mixed_recover<true, false>(g, l, n_blocks, x, c, idx, n_idx, vec, packed, nullptr, st);
+    launch_mixed_recover<true, false>(g, l, n_blocks, x, c, idx, n_idx, pieces, vec, packed, nullptr, st);
   else
-    n_partial = launch_mixed_recover<false, true>(g, l, n_blocks, x, c, idx, n_idx, vec, packed, partial, st);
+    n_partial = launch_mixed_recover<false, true>(g, l, n_blocks, x, c, idx, n_idx, pieces, vec, packed, partial, st);
   if (norm_out) launch_finish(l->dtype, partial, n_partial, norm_out, st);
   return launch_status();
 }

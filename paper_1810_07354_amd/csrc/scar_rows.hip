@@ -15,8 +15,6 @@ namespace scar {
 // well as many short ones (and every piece takes the loop-free path): the grid's y dimension
 // runs over the pieces of a row, its x dimension over the index list.  pieces == 1: whole rows
 // of any length.
-constexpr uint32_t kPieceBytes = 4096;
-
 struct RowPiece {
   uint64_t byte_off;   // of the piece within x and c
   uint32_t row_off;    // of the piece within its row, in bytes
@@ -205,15 +203,6 @@ __global__ __launch_bounds__(kFinishThreads) void k_norm_finish(
       out->norm = sqrt(total);
     }
   }
-}
-
-// Grid size in y for rows cut into `pieces`: one slice per piece while grid_x * grid_y stays
-// within `cap` workgroups (and the 65,535 of the y dimension); slices stride over the rest.
-static uint32_t piece_grid(uint32_t pieces, uint32_t grid_x, uint64_t cap) {
-  uint64_t y = cap / (grid_x ? grid_x : 1);
-  if (y > pieces) y = pieces;
-  if (y > 65535) y = 65535;
-  return y ? (uint32_t)y : 1;
 }
 
 template <int G, typename W>

@@ -95,7 +95,7 @@ def test_mixed_three_cycles_and_precision_bound():
     assert torch.all((back - x).abs() <= x.abs() * 2.0 ** -8)
 
 
-@pytest.mark.parametrize("L,nb", [(24, 600_000), (1024, 40_000)])
+@pytest.mark.parametrize("L,nb", [(24, 600_000), (1024, 40_000), (4096, 5_000)])
 def test_mixed_recover_over_long_index_lists(L, nb):
     # long index lists run the recovery kernel with larger workgroups
     n = L * nb - L // 2
@@ -117,3 +117,39 @@ def test_mixed_recover_over_long_index_lists(L, nb):
     assert_norm_matches(got, want, wl.F32)
     np.testing.assert_array_equal(to_host(x), hx)
     np.testing.assert_array_equal(to_host(c), hc)
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16, wl.I32, MIX])
+@pytest.mark.parametrize("L", [24, 5000, 70000])
+def test_recover_from_packed_rows_of_any_length(dtype, L):
+    # rows read back from storage (Section 4.3, recovery step 2): row i of `rows` is block
+    # lost[i]; long rows are walked in pieces, the last block of the store is short
+    nb = 41
+    n = L * nb - L // 3
+    r = np.random.default_rng(L + dtype)
+    if dtype == MIX:
+        hx, hc = make(n, L)
+        xt, ct = wl.F32, wl.BF16
+    elif dtype == wl.I32:
+        hc = r.integers(0, 50, size=n).astype(np.int32)
+        hx = (hc + r.integers(-3, 4, size=n)).astype(np.int32)
+        xt = ct = wl.I32
+    else:
+        hc = r.normal(0, 0.1, size=n).astype(np.float32)
+        hx = (hc + r.normal(0, 0.01, size=n)).astype(np.float32)
+        if dtype == wl.BF16:
+            hx, hc = wl.f32_to_bf16_bits(hx), wl.f32_to_bf16_bits(hc)
+        xt = ct = dtype
+    lost = np.unique(np.append(r.permutation(nb)[: nb // 2], nb - 1)).astype(np.uint32)
+    r.shuffle(lost)
+    hrows = np.zeros(lost.size * L, dtype=hc.dtype)
+    for i, b in enumerate(lost):
+        blk = hc[int(b) * L:(int(b) + 1) * L]
+        hrows[i * L:i * L + blk.size] = blk
+    print("packed rows dtype=%d L=%d n_lost=%d" % (dtype, L, lost.size), flush=True)
+    x, rows = to_dev(hx, xt), to_dev(hrows, ct)
+    ws = scar.new_workspace(nb, DEV)
+    got = scar.read_norm(scar.partial_recover_rows(x, rows, L, idx_dev(lost), ws))
+    want = oracle.partial_recover(dtype, hx, hc, L, lost)
+    assert_norm_matches(got, want, wl.I32 if dtype == wl.I32 else wl.F32)
+    np.testing.assert_array_equal(to_host(x), hx)
