@@ -27,9 +27,6 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
-# What a plain non-temporal read of 8 GiB reaches on this chip (measured once with a bare
-# read kernel, outside this file): context for the fractions of the published peak.
-READ_CEILING_GBS = 7040.0
 
 
 def algorithmic_bytes(n_elems, block_len, xbytes, cbytes, score_bytes, k, n_lost, select_passes):
@@ -479,7 +476,6 @@ def main():
         "algorithmic_bytes_per_cycle": b,
         "hbm_GBps_algorithmic": round(hbm_gbs, 1),
         "pct_of_hbm_peak": round(100.0 * hbm_gbs / HBM_PEAK_GBS, 2),
-        "pct_of_measured_read_ceiling": round(100.0 * hbm_gbs / READ_CEILING_GBS, 2),
         "ms_per_step_events_median": round(statistics.median(cycle_ms), 4),
         "last_norm": scar.read_norm(norm)[1],
         "roofline": {"bound": "hbm", "kernel": "k_mixed_scores" if cbytes != xbytes else

@@ -82,6 +82,26 @@ inline uint32_t xcd_grid(uint64_t need, uint64_t cap) {
   return (uint32_t)((g + 7) / 8 * 8);
 }
 
+// A long streaming read runs fastest with 80-96 KiB of loads in flight per compute unit,
+// not with as many workgroups as registers allow: fewer, longer address streams reach the
+// memory at a time (2^30 float32 in 1,024-element blocks, 32 KiB in flight per workgroup:
+// 1,200 us with eight workgroups per compute unit, 1,160 us with three; 512-element blocks,
+// 16 KiB per workgroup: best with four or five).  The streaming kernels use next to no LDS, so
+// a launch limits its workgroups per compute unit by asking for LDS it does not use: this
+// returns the dynamic LDS bytes for a launch of `grid` workgroups that each keep
+// `wg_bytes_in_flight` bytes of loads outstanding (0 = no limit: short launches, and
+// workgroups with so little in flight that eight of them are needed anyway).
+constexpr uint64_t kStreamFromGrid = 4096;
+constexpr uint64_t kStreamBytesPerCu = 86 * 1024;  // 32 KiB a workgroup -> 3, 24 -> 4, 16 -> 5
+constexpr size_t kLdsPerCu = 160 * 1024;
+inline size_t stream_lds_bytes(uint64_t grid, uint64_t wg_bytes_in_flight) {
+  if (grid < kStreamFromGrid || wg_bytes_in_flight == 0) return 0;
+  uint64_t wgs = (kStreamBytesPerCu + wg_bytes_in_flight / 2) / wg_bytes_in_flight;
+  if (wgs < 3) wgs = 3;
+  if (wgs >= 8) return 0;
+  return kLdsPerCu / wgs - 1024;
+}
+
 // The copy kernels hand rows longer than kPieceBytes out in pieces of that size (grid y =
 // piece).  Grid size in y for rows cut into `pieces`: one slice per piece while
 // grid_x * grid_y stays within `cap` workgroups (and the 65,535 of the y dimension); slices

@@ -237,12 +237,17 @@ int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, c
   if (!x || !c || !scores || !aligned(x, 4) || !aligned(c, 2) || !aligned(scores, 4))
     return SCAR_ERR_INVALID_ARG;
   const bool vec = mixed_vec(l, x, c);
-  const int g = pick_group_units(vec ? l->block_len / kMixUnit : l->block_len, vec ? kMixU : 4, false);
+  // loads in flight: one 16-byte step of x and 8 bytes of c per unit (element-wise: 4 + 2)
+  const uint64_t units = vec ? l->block_len / kMixUnit : l->block_len;
+  const int g = pick_group_units(units, vec ? kMixU : 4, false);
 #define CALL(G)                                                                                      \
   {                                                                                                  \
     constexpr int GPW = (G == 256) ? 1 : kWG / G;                                                    \
-    const uint32_t grid = xcd_grid(((uint64_t)n_blocks + GPW - 1) / GPW, kScoreGridCap);             \
-    hipLaunchKernelGGL((k_mixed_scores<G>), dim3(grid), dim3(kWG), 0, st, (const float*)x,           \
+    const uint64_t need = ((uint64_t)n_blocks + GPW - 1) / GPW;                                      \
+    const uint32_t grid = xcd_grid(need, kScoreGridCap);                                             \
+    const uint64_t group_units = units < (uint64_t)G * kMixU ? units : (uint64_t)G * kMixU;          \
+    const size_t lds = stream_lds_bytes(need, (vec ? 24 : 6) * group_units * GPW);                   \
+    hipLaunchKernelGGL((k_mixed_scores<G>), dim3(grid), dim3(kWG), lds, st, (const float*)x,         \
                        (const uint16_t*)c, (float*)scores, l->n_elems, l->block_len, n_blocks, vec); \
   }
   switch (g) {  // the score kernel reduces inside a wavefront or a whole workgroup

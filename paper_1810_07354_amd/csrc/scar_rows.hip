@@ -151,9 +151,10 @@ __global__ __launch_bounds__(T, T / 128) void k_recover(char* __restrict__ x, co
       // packed: c holds only the listed blocks, row i = block idx[i] (rows read back from storage)
       const char* cb = packed ? c + i * (uint64_t)block_len * E + rp.row_off : c + rp.byte_off;
       if constexpr (is_tv(DT)) {  // each row's share counts with the row's weight
+        const float w = weights ? weights[b] : 1.f;  // asked for before the row, used after it
         acc_t row = 0;
         recover_row<DT, G, STORE, NORM, VEC>(x + rp.byte_off, cb, rp.len, lane, row);
-        acc += (weights ? (double)weights[b] : 1.0) * row;
+        acc += (double)w * row;
       } else {
         recover_row<DT, G, STORE, NORM, VEC>(x + rp.byte_off, cb, rp.len, lane, acc);
       }

@@ -35,6 +35,9 @@ __global__ __launch_bounds__(kWG) void k_block_scores(const char* __restrict__ x
       if (b >= n_blocks) continue;
     }
     const BlockSpan sp = block_span(b, n_elems, block_len, elem_bytes(DT));
+    float w = 1.f;  // asked for before the walk, so that it has arrived when the walk is done
+    if constexpr (is_tv(DT))
+      if (weights && lane == 0) w = weights[b];
     acc_t acc = block_distance<DT, G, VEC>(x + sp.byte_off, c + sp.byte_off, sp.len, lane);
     if constexpr (G == 256)
       acc = workgroup_sum(acc, slots);
@@ -44,7 +47,7 @@ __global__ __launch_bounds__(kWG) void k_block_scores(const char* __restrict__ x
       if constexpr (DT == DT_I32)
         ((long long*)scores)[b] = (long long)acc;
       else if constexpr (is_tv(DT))  // w_b * 1/2 * sum |x - c|
-        ((float*)scores)[b] = (float)(0.5 * acc * (weights ? (double)weights[b] : 1.0));
+        ((float*)scores)[b] = (float)(0.5 * acc * (double)w);
       else
         ((float*)scores)[b] = (float)acc;
     }
@@ -137,8 +140,12 @@ static void launch_scores(const scar_layout* l, const void* x, const void* c, vo
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const uint64_t need = ((uint64_t)(idx ? n_idx : n_blocks) + GPW - 1) / GPW;
   const uint32_t grid = xcd_grid(need, kScoreGridCap);
-#define SCAR_LAUNCH(VEC, LISTED)                                                                          \
-  hipLaunchKernelGGL((k_block_scores<DT, G, VEC, LISTED>), dim3(grid), dim3(kWG), 0, st, (const char*)x, \
+  // loads a workgroup keeps in flight: up to kUnroll 16-byte steps per lane and stream
+  const uint64_t row_vecs = ((uint64_t)l->block_len * elem_bytes(DT) + 15) / 16;
+  const uint64_t group_vecs = row_vecs < (uint64_t)G * kUnroll ? row_vecs : (uint64_t)G * kUnroll;
+  const size_t lds = stream_lds_bytes(need, 2 * 16 * group_vecs * GPW);
+#define SCAR_LAUNCH(VEC, LISTED)                                                                            \
+  hipLaunchKernelGGL((k_block_scores<DT, G, VEC, LISTED>), dim3(grid), dim3(kWG), lds, st, (const char*)x, \
                      (const char*)c, scores, l->n_elems, l->block_len, n_blocks, weights, idx, n_idx)
   if (idx) {
     if (vec)
@@ -152,6 +159,158 @@ static void launch_scores(const scar_layout* l, const void* x, const void* c, vo
       SCAR_LAUNCH(false, false);
   }
 #undef SCAR_LAUNCH
+}
+
+// Short rows that are whole 16-byte steps (32 ... kFlatRowBytes bytes) of a 16-byte aligned
+// store.  A group per row reads such rows in pieces that start and end inside cache lines and
+// leaves lanes idle (25 steps over 16 lanes); here a workgroup reads a *chunk* of `chunk_rows`
+// whole rows as one contiguous run of at most kFlatVecs 16-byte steps per stream, every lane
+// loading kUnroll of them fully coalesced, and leaves one partial sum per step in LDS.  The
+// groups then add each row's partial sums in exactly the order in which block_distance adds
+// them from memory (same lane -> step mapping, same float and float64 stages, same shuffles),
+// so the scores are bit for bit those of k_block_scores - which still serves listed blocks.
+// Only whole rows are handled (n_rows of them); a short last block of the store is left to
+// k_block_scores.
+constexpr uint32_t kFlatVecs = kWG * kUnroll;
+constexpr uint32_t kFlatRowBytes = 512;
+constexpr uint32_t kFlatMinRows = 4096;  // below this a launch is all the time there is
+
+template <int DT>
+struct StepSum {
+  using type = float;
+};
+template <>
+struct StepSum<DT_I32> {
+  using type = unsigned long long;
+};
+
+template <int DT, int G>
+__global__ __launch_bounds__(kWG) void k_block_scores_flat(const char* __restrict__ x,
+                                                           const char* __restrict__ c,
+                                                           void* __restrict__ scores, uint32_t block_len,
+                                                           uint32_t n_rows, uint32_t chunk_rows,
+                                                           uint32_t n_chunks,
+                                                           const float* __restrict__ weights) {
+  constexpr int E = elem_bytes(DT);
+  constexpr int EPV = 16 / E;
+  constexpr int GPW = kWG / G;
+  using acc_t = typename Acc<DT>::type;
+  using step_t = typename StepSum<DT>::type;
+  __shared__ step_t steps[kFlatVecs];
+  __shared__ float row_weight[is_tv(DT) ? kFlatVecs / 2 : 1];  // rows are two steps or more
+  const int lane = threadIdx.x & (G - 1);
+  const uint32_t grp = threadIdx.x / G;
+  const uint32_t row_vecs = block_len / EPV;
+
+  for (uint32_t chunk = xcd_contiguous_block_id(); chunk < n_chunks; chunk += gridDim.x) {
+    const uint64_t row0 = (uint64_t)chunk * chunk_rows;
+    const uint32_t rows = (uint32_t)(n_rows - row0 < chunk_rows ? n_rows - row0 : chunk_rows);
+    const uint32_t nvec = rows * row_vecs;
+    const uint4* xv = (const uint4*)(x + row0 * block_len * E);
+    const uint4* cv = (const uint4*)(c + row0 * block_len * E);
+    float w[2] = {1.f, 1.f};  // the rows' weights travel with the rows
+    if constexpr (is_tv(DT)) {
+      if (weights) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+          if (u * kWG + threadIdx.x < rows) w[u] = weights[row0 + u * kWG + threadIdx.x];
+      }
+    }
+    uint4 a[kUnroll], b[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint32_t v = u * kWG + threadIdx.x;
+      if (v < nvec) {
+        a[u] = load_stream(xv + v);
+        b[u] = load_stream(cv + v);
+      }
+    }
+    if constexpr (is_tv(DT)) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+        if (u * kWG + threadIdx.x < rows) row_weight[u * kWG + threadIdx.x] = w[u];
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint32_t v = u * kWG + threadIdx.x;
+      if (v >= nvec) continue;
+      if constexpr (DT == DT_I32) steps[v] = absdiff_i32x4(a[u], b[u]);
+      if constexpr (DT == DT_F32) steps[v] = sqdiff_f32(a[u], b[u]);
+      if constexpr (DT == DT_BF16) steps[v] = sqdiff_bf16(a[u], b[u]);
+      if constexpr (DT == DT_F32_TV) steps[v] = absdiff_f32(a[u], b[u]);
+      if constexpr (DT == DT_BF16_TV) steps[v] = absdiff_bf16(a[u], b[u]);
+    }
+    __syncthreads();
+    for (uint32_t r = grp; r < rows; r += GPW) {
+      const step_t* p = steps + r * row_vecs;
+      acc_t acc = 0;
+      for (uint32_t v0 = 0; v0 < row_vecs; v0 += G * kUnroll) {  // the order of block_distance
+        step_t part = 0;
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+          const uint32_t v = v0 + u * G + lane;
+          part += v < row_vecs ? p[v] : (step_t)0;
+        }
+        acc += (acc_t)part;
+      }
+      acc = group_sum<G>(acc);
+      if (lane == 0) {
+        const uint64_t row = row0 + r;
+        if constexpr (DT == DT_I32)
+          ((long long*)scores)[row] = (long long)acc;
+        else if constexpr (is_tv(DT))
+          ((float*)scores)[row] = (float)(0.5 * acc * (double)row_weight[r]);
+        else
+          ((float*)scores)[row] = (float)acc;
+      }
+    }
+    __syncthreads();  // the next chunk overwrites steps
+  }
+}
+
+// Rows per chunk: as many as fit kFlatVecs steps, rounded down so that chunks start on
+// 128-byte lines.
+static uint32_t flat_chunk_rows(uint32_t row_vecs) {
+  uint32_t rows = kFlatVecs / row_vecs;
+  uint32_t m = 8;  // rows * row_vecs must be a multiple of 8 steps
+  for (uint32_t v = row_vecs; m > 1 && v % 2 == 0; v /= 2) m /= 2;
+  return rows / m * m;
+}
+
+template <int DT, int G>
+static void launch_scores_flat(const scar_layout* l, const void* x, const void* c, void* scores,
+                               const float* weights, hipStream_t st) {
+  constexpr int E = elem_bytes(DT);
+  const uint32_t n_rows = (uint32_t)(l->n_elems / l->block_len);
+  const uint32_t chunk_rows = flat_chunk_rows(l->block_len / (16 / E));
+  const uint32_t n_chunks = (n_rows + chunk_rows - 1) / chunk_rows;
+  // five workgroups per compute unit (32 KiB of LDS each, most of it unused) are the best
+  // measured: 2.7 M rows of 400 bytes 334 us with eight, 314 us with five or four
+  const size_t lds = 32 * 1024 - kFlatVecs * sizeof(typename StepSum<DT>::type) - (is_tv(DT) ? kFlatVecs * 2 : 0) - 256;
+  hipLaunchKernelGGL((k_block_scores_flat<DT, G>), dim3(xcd_grid(n_chunks, kScoreGridCap)), dim3(kWG), lds,
+                     st, (const char*)x, (const char*)c, scores, l->block_len, n_rows, chunk_rows, n_chunks,
+                     weights);
+  const uint64_t done = (uint64_t)n_rows * l->block_len;
+  if (done < l->n_elems) {  // a short last block: a store of one block for the group walk
+    const scar_layout last = {l->dtype, l->block_len, l->n_elems - done};
+    char* out = (char*)scores + (size_t)n_rows * (DT == DT_I32 ? 8 : 4);
+    launch_scores<DT, G>(&last, (const char*)x + done * E, (const char*)c + done * E, out, 1, true,
+                         weights ? weights + n_rows : nullptr, nullptr, 0, st);
+  }
+}
+
+template <int DT>
+static bool dispatch_scores_flat(int g, const scar_layout* l, const void* x, const void* c, void* scores,
+                                 const float* weights, hipStream_t st) {
+  switch (g) {
+    case 1: launch_scores_flat<DT, 1>(l, x, c, scores, weights, st); return true;
+    case 2: launch_scores_flat<DT, 2>(l, x, c, scores, weights, st); return true;
+    case 4: launch_scores_flat<DT, 4>(l, x, c, scores, weights, st); return true;
+    case 8: launch_scores_flat<DT, 8>(l, x, c, scores, weights, st); return true;
+    case 16: launch_scores_flat<DT, 16>(l, x, c, scores, weights, st); return true;
+    case 32: launch_scores_flat<DT, 32>(l, x, c, scores, weights, st); return true;
+    default: return false;
+  }
 }
 
 template <int DT>
@@ -209,6 +368,15 @@ static int block_scores(bool tv, bool listed, const scar_layout* layout, const v
       case SCAR_BF16: done = launch_scores_tiny<DT_BF16>(layout, x, c, scores, st); break;
       default: done = launch_scores_tiny<DT_I32>(layout, x, c, scores, st); break;
     }
+    if (done) return launch_status();
+  }
+  if (!listed && vec && row_bytes >= 32 && row_bytes <= kFlatRowBytes && n >= kFlatMinRows) {
+    bool done = false;
+    if (tv && layout->dtype == SCAR_F32) done = dispatch_scores_flat<DT_F32_TV>(g, layout, x, c, scores, weights, st);
+    else if (tv) done = dispatch_scores_flat<DT_BF16_TV>(g, layout, x, c, scores, weights, st);
+    else if (layout->dtype == SCAR_F32) done = dispatch_scores_flat<DT_F32>(g, layout, x, c, scores, nullptr, st);
+    else if (layout->dtype == SCAR_BF16) done = dispatch_scores_flat<DT_BF16>(g, layout, x, c, scores, nullptr, st);
+    else done = dispatch_scores_flat<DT_I32>(g, layout, x, c, scores, nullptr, st);
     if (done) return launch_status();
   }
   if (tv) {

@@ -268,8 +268,12 @@ static void launch_walk(const scar_var_layout* l, const void* x, const void* c, 
   if (!planned)
     hipLaunchKernelGGL(k_var_plan, dim3((g.n_wg + kWG - 1) / kWG), dim3(kWG), 0, st, l->offsets, l->n_blocks,
                        l->n_elems, g.range_elems, g.n_wg, mask, first, any);
+  // the score walk reads everything and keeps kUnroll 16-byte steps per lane and stream in flight
+  uint64_t in_flight = 2 * g.range_elems * elem_bytes(DT);
+  if (in_flight > 2 * 16 * kWG * kUnroll) in_flight = 2 * 16 * kWG * kUnroll;
+  const size_t lds = (COPY == COPY_NONE && PER_BLOCK) ? stream_lds_bytes(g.n_wg, in_flight) : 0;
   hipLaunchKernelGGL((k_var_walk<DT, ACC, COPY, PER_BLOCK>), dim3(xcd_grid(g.n_wg, kVarMaxGridCopy)), dim3(kWG),
-                     0, st, (char*)const_cast<void*>(x), (char*)const_cast<void*>(c), l->offsets,
+                     lds, st, (char*)const_cast<void*>(x), (char*)const_cast<void*>(c), l->offsets,
                      l->n_blocks, l->n_elems, g.range_elems, g.n_wg, mask, (const uint32_t*)first,
                      (const uint8_t*)any, (typename Acc<DT>::type*)partial, base_aligned);
 }

@@ -115,6 +115,26 @@ def test_incremental_scores_track_the_full_scan_over_cycles():
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16, I32])
+@pytest.mark.parametrize("row_bytes", [16, 32, 48, 80, 112, 128, 208, 400, 496, 512, 528])
+def test_block_scores_of_many_short_rows(dtype, row_bytes):
+    # many rows of 16 ... 512 bytes are read as contiguous runs of whole rows; the scores are
+    # the oracle's and, bit for bit, those of the listed walk; last block whole, short by less
+    # than a 16-byte step, and short by more
+    L = row_bytes // (2 if dtype == BF16 else 4)
+    for nb, cut in [(4096, 0), (9001, 1), (20_011, L // 2 + 1), (70_000, L - 1)]:
+        n = L * nb - cut
+        x, c = make_store(dtype, n, seed=row_bytes + nb)
+        dx, dc = to_dev(x, dtype), to_dev(c, dtype)
+        print("short rows dtype=%d L=%d nb=%d cut=%d" % (dtype, L, nb, cut), flush=True)
+        s = scar.block_scores(dx, dc, L)
+        assert s.numel() == nb
+        assert_scores_match(s, oracle.block_scores(dtype, x, c, L), dtype)
+        listed = torch.full_like(s, -1)
+        scar.block_scores_rows(dx, dc, L, torch.randperm(nb, device=DEV).to(torch.int32), listed)
+        assert torch.equal(s, listed)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16, I32])
 @pytest.mark.parametrize("L", [1, 2, 4])
 def test_block_scores_of_rows_shorter_than_16_bytes(dtype, L):
     # per-scalar and per-pair selection: a lane scores several rows from one 16-byte step; every

@@ -67,6 +67,22 @@ def test_tv_calls(dtype, L, weighted):
     assert scar.read_norm(scar.tv_perturbation_norm(x, c, L, empty, ws, w)) == (0.0, 0.0, 0)
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("row_bytes", [16, 80, 400, 512])
+@pytest.mark.parametrize("weighted", [False, True])
+def test_tv_scores_of_many_short_rows(dtype, row_bytes, weighted):
+    # enough rows of 16 ... 512 bytes for the scan that reads whole runs of rows; last row short
+    L = row_bytes // (2 if dtype == BF16 else 4)
+    nb = 9001
+    hx, hc = rows(dtype, nb, L, seed=row_bytes + dtype)
+    assert oracle.n_blocks_of(hx.size, L) == nb
+    hw = np.random.default_rng(L).integers(5, 3000, size=nb).astype(np.float32) if weighted else None
+    w = torch.from_numpy(hw).to(DEV) if weighted else None
+    print("tv short rows dtype=%d L=%d weighted=%s" % (dtype, L, weighted), flush=True)
+    s = scar.tv_block_scores(to_dev(hx, dtype), to_dev(hc, dtype), L, w)
+    close(s.cpu().numpy(), oracle.tv_block_scores(dtype, hx, hc, L, hw))
+
+
 def test_tv_unaligned_bases():
     L, nb = 37, 400
     hx, hc = rows(F32, nb, L, seed=3)
