@@ -161,30 +161,60 @@ static void launch_scores(const scar_layout* l, const void* x, const void* c, vo
 #undef SCAR_LAUNCH
 }
 
-// Short rows that are whole 16-byte steps (32 ... kFlatRowBytes bytes) of a 16-byte aligned
-// store.  A group per row reads such rows in pieces that start and end inside cache lines and
-// leaves lanes idle (25 steps over 16 lanes); here a workgroup reads a *chunk* of `chunk_rows`
-// whole rows as one contiguous run of at most kFlatVecs 16-byte steps per stream, every lane
-// loading kUnroll of them fully coalesced, and leaves one partial sum per step in LDS.  The
-// groups then add each row's partial sums in exactly the order in which block_distance adds
-// them from memory (same lane -> step mapping, same float and float64 stages, same shuffles),
-// so the scores are bit for bit those of k_block_scores - which still serves listed blocks.
-// Only whole rows are handled (n_rows of them); a short last block of the store is left to
-// k_block_scores.
+// Many short rows of a 16-byte aligned store, read as runs of whole rows.  A group per row
+// reads such rows in pieces that start and end inside cache lines, leaves lanes idle (25 steps
+// over 16 lanes) and, when a row is not a whole number of 16-byte steps, walks its ends element
+// by element from memory.  Here a workgroup reads a *chunk* of `chunk_rows` whole rows as one
+// contiguous run of at most kFlatVecs 16-byte steps per stream, every lane loading kUnroll of
+// them fully coalesced, and leaves in LDS one partial sum per step and - SPLIT, for rows that
+// are not whole steps - one term per element.  The groups then add each row's partial sums and
+// terms in exactly the order in which block_distance adds them from memory (leading elements,
+// steps, trailing elements; same lane -> step mapping, same float and float64 stages, same
+// shuffles), so the scores are bit for bit those of k_block_scores - which still serves listed
+// blocks.  Only whole rows are handled (n_rows of them); a short last block of the store is
+// left to k_block_scores.  Chunks start on 16-byte boundaries (the host sizes chunk_rows for
+// that), on 128-byte lines when the rows allow it.
 constexpr uint32_t kFlatVecs = kWG * kUnroll;
-constexpr uint32_t kFlatRowBytes = 512;
-constexpr uint32_t kFlatMinRows = 4096;  // below this a launch is all the time there is
+constexpr uint32_t kFlatRowBytes = 512;        // longest row that is a whole number of steps
+constexpr uint32_t kFlatSplitRowBytes = 4096 + 15;  // longest row that is not
+constexpr uint32_t kFlatMinRows = 4096;        // below this a launch is all the time there is
 
 template <int DT>
 struct StepSum {
-  using type = float;
+  using type = float;  // per step; the terms of single elements have the same type
 };
 template <>
 struct StepSum<DT_I32> {
   using type = unsigned long long;
 };
+template <int DT>
+struct ElemTerm {
+  using type = float;
+};
+template <>
+struct ElemTerm<DT_I32> {
+  using type = uint32_t;
+};
 
-template <int DT, int G>
+// Distance term of element e (a compile-time constant) of a 16-byte step, as accumulate_elem
+// computes it from memory.
+template <int DT>
+__device__ __forceinline__ typename ElemTerm<DT>::type elem_term(const uint4& a, const uint4& b, int e) {
+  const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+  if constexpr (DT == DT_I32) {
+    return absdiff_i32(aw[e], bw[e]);
+  } else if constexpr (DT == DT_F32 || DT == DT_F32_TV) {
+    const float d = __uint_as_float(aw[e]) - __uint_as_float(bw[e]);
+    return DT == DT_F32 ? sq(d) : __builtin_fabsf(d);
+  } else {
+    const uint32_t ua = (e & 1) ? (aw[e / 2] & 0xffff0000u) : (aw[e / 2] << 16);
+    const uint32_t ub = (e & 1) ? (bw[e / 2] & 0xffff0000u) : (bw[e / 2] << 16);
+    const float d = __uint_as_float(ua) - __uint_as_float(ub);
+    return DT == DT_BF16 ? sq(d) : __builtin_fabsf(d);
+  }
+}
+
+template <int DT, int G, bool SPLIT>
 __global__ __launch_bounds__(kWG) void k_block_scores_flat(const char* __restrict__ x,
                                                            const char* __restrict__ c,
                                                            void* __restrict__ scores, uint32_t block_len,
@@ -196,18 +226,22 @@ __global__ __launch_bounds__(kWG) void k_block_scores_flat(const char* __restric
   constexpr int GPW = kWG / G;
   using acc_t = typename Acc<DT>::type;
   using step_t = typename StepSum<DT>::type;
+  using term_t = typename ElemTerm<DT>::type;
   __shared__ step_t steps[kFlatVecs];
-  __shared__ float row_weight[is_tv(DT) ? kFlatVecs / 2 : 1];  // rows are two steps or more
+  __shared__ __align__(16) term_t terms[SPLIT ? kFlatVecs * EPV : 1];
+  __shared__ float row_weight[is_tv(DT) ? kFlatVecs / 2 : 1];  // rows are 32 bytes or more
   const int lane = threadIdx.x & (G - 1);
   const uint32_t grp = threadIdx.x / G;
-  const uint32_t row_vecs = block_len / EPV;
 
   for (uint32_t chunk = xcd_contiguous_block_id(); chunk < n_chunks; chunk += gridDim.x) {
     const uint64_t row0 = (uint64_t)chunk * chunk_rows;
     const uint32_t rows = (uint32_t)(n_rows - row0 < chunk_rows ? n_rows - row0 : chunk_rows);
-    const uint32_t nvec = rows * row_vecs;
-    const uint4* xv = (const uint4*)(x + row0 * block_len * E);
-    const uint4* cv = (const uint4*)(c + row0 * block_len * E);
+    const uint32_t n_el = rows * block_len;
+    const uint32_t nvec = n_el / EPV;  // whole steps; only the last chunk can end inside one
+    const char* xc = x + row0 * block_len * E;
+    const char* cc = c + row0 * block_len * E;
+    const uint4* xv = (const uint4*)xc;
+    const uint4* cv = (const uint4*)cc;
     float w[2] = {1.f, 1.f};  // the rows' weights travel with the rows
     if constexpr (is_tv(DT)) {
       if (weights) {
@@ -239,11 +273,31 @@ __global__ __launch_bounds__(kWG) void k_block_scores_flat(const char* __restric
       if constexpr (DT == DT_BF16) steps[v] = sqdiff_bf16(a[u], b[u]);
       if constexpr (DT == DT_F32_TV) steps[v] = absdiff_f32(a[u], b[u]);
       if constexpr (DT == DT_BF16_TV) steps[v] = absdiff_bf16(a[u], b[u]);
+      if constexpr (SPLIT) {
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) terms[v * EPV + e] = elem_term<DT>(a[u], b[u], e);
+      }
+    }
+    if constexpr (SPLIT) {  // the elements after the last whole step (last chunk only)
+      for (uint32_t j = nvec * EPV + threadIdx.x; j < n_el; j += kWG) {
+        acc_t t = 0;
+        accumulate_elem<DT>(t, xc, cc, j);
+        terms[j] = (term_t)t;
+      }
     }
     __syncthreads();
     for (uint32_t r = grp; r < rows; r += GPW) {
-      const step_t* p = steps + r * row_vecs;
       acc_t acc = 0;
+      uint32_t head = 0, row_vecs = block_len / EPV, first_vec = r * row_vecs;
+      const uint32_t e_lo = r * block_len;
+      if constexpr (SPLIT) {  // the row's own split, as row_split makes it
+        head = (EPV - (e_lo & (EPV - 1))) & (EPV - 1);
+        if (head > block_len) head = block_len;
+        row_vecs = (block_len - head) / EPV;
+        first_vec = (e_lo + head) / EPV;
+        for (uint32_t j = lane; j < head; j += G) acc += (acc_t)terms[e_lo + j];
+      }
+      const step_t* p = steps + first_vec;
       for (uint32_t v0 = 0; v0 < row_vecs; v0 += G * kUnroll) {  // the order of block_distance
         step_t part = 0;
 #pragma unroll
@@ -252,6 +306,9 @@ __global__ __launch_bounds__(kWG) void k_block_scores_flat(const char* __restric
           part += v < row_vecs ? p[v] : (step_t)0;
         }
         acc += (acc_t)part;
+      }
+      if constexpr (SPLIT) {
+        for (uint32_t j = head + row_vecs * EPV + lane; j < block_len; j += G) acc += (acc_t)terms[e_lo + j];
       }
       acc = group_sum<G>(acc);
       if (lane == 0) {
@@ -264,53 +321,67 @@ __global__ __launch_bounds__(kWG) void k_block_scores_flat(const char* __restric
           ((float*)scores)[row] = (float)acc;
       }
     }
-    __syncthreads();  // the next chunk overwrites steps
+    __syncthreads();  // the next chunk overwrites steps and terms
   }
 }
 
 // Rows per chunk: as many as fit kFlatVecs steps, rounded down so that chunks start on
-// 128-byte lines.
-static uint32_t flat_chunk_rows(uint32_t row_vecs) {
-  uint32_t rows = kFlatVecs / row_vecs;
-  uint32_t m = 8;  // rows * row_vecs must be a multiple of 8 steps
-  for (uint32_t v = row_vecs; m > 1 && v % 2 == 0; v /= 2) m /= 2;
-  return rows / m * m;
+// 128-byte lines, or at least on 16-byte boundaries; 0 if not even that fits.
+static uint32_t flat_chunk_rows(uint64_t row_bytes) {
+  const uint32_t fit = (uint32_t)((uint64_t)kFlatVecs * 16 / row_bytes);
+  for (uint32_t align = 128; align >= 16; align /= 2) {
+    uint32_t m = align;  // rows * row_bytes must be a multiple of align
+    for (uint64_t v = row_bytes; m > 1 && v % 2 == 0; v /= 2) m /= 2;
+    if (fit >= m) return fit / m * m;
+  }
+  return 0;
 }
 
-template <int DT, int G>
+template <int DT, int G, bool SPLIT>
 static void launch_scores_flat(const scar_layout* l, const void* x, const void* c, void* scores,
                                const float* weights, hipStream_t st) {
   constexpr int E = elem_bytes(DT);
   const uint32_t n_rows = (uint32_t)(l->n_elems / l->block_len);
-  const uint32_t chunk_rows = flat_chunk_rows(l->block_len / (16 / E));
+  const uint32_t chunk_rows = flat_chunk_rows((uint64_t)l->block_len * E);
   const uint32_t n_chunks = (n_rows + chunk_rows - 1) / chunk_rows;
-  // five workgroups per compute unit (32 KiB of LDS each, most of it unused) are the best
+  // five workgroups per compute unit (32 KiB of LDS each, part of it unused) are the best
   // measured: 2.7 M rows of 400 bytes 334 us with eight, 314 us with five or four
-  const size_t lds = 32 * 1024 - kFlatVecs * sizeof(typename StepSum<DT>::type) - (is_tv(DT) ? kFlatVecs * 2 : 0) - 256;
-  hipLaunchKernelGGL((k_block_scores_flat<DT, G>), dim3(xcd_grid(n_chunks, kScoreGridCap)), dim3(kWG), lds,
-                     st, (const char*)x, (const char*)c, scores, l->block_len, n_rows, chunk_rows, n_chunks,
-                     weights);
+  const size_t used = kFlatVecs * sizeof(typename StepSum<DT>::type) + (is_tv(DT) ? kFlatVecs * 2 : 0) +
+                      (SPLIT ? kFlatVecs * 16 / E * sizeof(typename ElemTerm<DT>::type) : 0) + 256;
+  const size_t lds = used < 32 * 1024 ? 32 * 1024 - used : 0;
+  hipLaunchKernelGGL((k_block_scores_flat<DT, G, SPLIT>), dim3(xcd_grid(n_chunks, kScoreGridCap)), dim3(kWG),
+                     lds, st, (const char*)x, (const char*)c, scores, l->block_len, n_rows, chunk_rows,
+                     n_chunks, weights);
   const uint64_t done = (uint64_t)n_rows * l->block_len;
   if (done < l->n_elems) {  // a short last block: a store of one block for the group walk
     const scar_layout last = {l->dtype, l->block_len, l->n_elems - done};
     char* out = (char*)scores + (size_t)n_rows * (DT == DT_I32 ? 8 : 4);
-    launch_scores<DT, G>(&last, (const char*)x + done * E, (const char*)c + done * E, out, 1, true,
+    launch_scores<DT, G>(&last, (const char*)x + done * E, (const char*)c + done * E, out, 1, !SPLIT,
                          weights ? weights + n_rows : nullptr, nullptr, 0, st);
   }
 }
 
 template <int DT>
-static bool dispatch_scores_flat(int g, const scar_layout* l, const void* x, const void* c, void* scores,
-                                 const float* weights, hipStream_t st) {
+static bool dispatch_scores_flat(int g, bool split, const scar_layout* l, const void* x, const void* c,
+                                 void* scores, const float* weights, hipStream_t st) {
+#define SCAR_FLAT(G)                                                         \
+  case G:                                                                    \
+    if (split)                                                               \
+      launch_scores_flat<DT, G, true>(l, x, c, scores, weights, st);         \
+    else                                                                     \
+      launch_scores_flat<DT, G, false>(l, x, c, scores, weights, st);        \
+    return true;
   switch (g) {
-    case 1: launch_scores_flat<DT, 1>(l, x, c, scores, weights, st); return true;
-    case 2: launch_scores_flat<DT, 2>(l, x, c, scores, weights, st); return true;
-    case 4: launch_scores_flat<DT, 4>(l, x, c, scores, weights, st); return true;
-    case 8: launch_scores_flat<DT, 8>(l, x, c, scores, weights, st); return true;
-    case 16: launch_scores_flat<DT, 16>(l, x, c, scores, weights, st); return true;
-    case 32: launch_scores_flat<DT, 32>(l, x, c, scores, weights, st); return true;
+    SCAR_FLAT(1)
+    SCAR_FLAT(2)
+    SCAR_FLAT(4)
+    SCAR_FLAT(8)
+    SCAR_FLAT(16)
+    SCAR_FLAT(32)
+    SCAR_FLAT(64)
     default: return false;
   }
+#undef SCAR_FLAT
 }
 
 template <int DT>
@@ -370,13 +441,17 @@ static int block_scores(bool tv, bool listed, const scar_layout* layout, const v
     }
     if (done) return launch_status();
   }
-  if (!listed && vec && row_bytes >= 32 && row_bytes <= kFlatRowBytes && n >= kFlatMinRows) {
+  // many short rows of an aligned store: read as runs of whole rows
+  const bool split = row_bytes % 16 != 0;
+  if (!listed && aligned(x, 16) && aligned(c, 16) && n >= kFlatMinRows && (uint64_t)g * kUnroll * 16 >= row_bytes &&
+      (split ? row_bytes <= kFlatSplitRowBytes && (!tv || row_bytes >= 32) && flat_chunk_rows(row_bytes) > 0
+             : row_bytes >= 32 && row_bytes <= kFlatRowBytes)) {
     bool done = false;
-    if (tv && layout->dtype == SCAR_F32) done = dispatch_scores_flat<DT_F32_TV>(g, layout, x, c, scores, weights, st);
-    else if (tv) done = dispatch_scores_flat<DT_BF16_TV>(g, layout, x, c, scores, weights, st);
-    else if (layout->dtype == SCAR_F32) done = dispatch_scores_flat<DT_F32>(g, layout, x, c, scores, nullptr, st);
-    else if (layout->dtype == SCAR_BF16) done = dispatch_scores_flat<DT_BF16>(g, layout, x, c, scores, nullptr, st);
-    else done = dispatch_scores_flat<DT_I32>(g, layout, x, c, scores, nullptr, st);
+    if (tv && layout->dtype == SCAR_F32) done = dispatch_scores_flat<DT_F32_TV>(g, split, layout, x, c, scores, weights, st);
+    else if (tv) done = dispatch_scores_flat<DT_BF16_TV>(g, split, layout, x, c, scores, weights, st);
+    else if (layout->dtype == SCAR_F32) done = dispatch_scores_flat<DT_F32>(g, split, layout, x, c, scores, nullptr, st);
+    else if (layout->dtype == SCAR_BF16) done = dispatch_scores_flat<DT_BF16>(g, split, layout, x, c, scores, nullptr, st);
+    else done = dispatch_scores_flat<DT_I32>(g, split, layout, x, c, scores, nullptr, st);
     if (done) return launch_status();
   }
   if (tv) {

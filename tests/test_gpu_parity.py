@@ -114,14 +114,20 @@ def test_incremental_scores_track_the_full_scan_over_cycles():
         assert float(scores[idx.long()].abs().max()) == 0.0
 
 
-@pytest.mark.parametrize("dtype", [F32, BF16, I32])
-@pytest.mark.parametrize("row_bytes", [16, 32, 48, 80, 112, 128, 208, 400, 496, 512, 528])
+SHORT_ROW_BYTES = [16, 32, 48, 80, 112, 128, 208, 400, 496, 512, 528,        # whole 16-byte steps
+                   12, 20, 36, 100, 200, 404, 1000, 2004, 4004, 4100,        # whole 4-byte words
+                   6, 18, 50, 202, 1002, 2002, 4090]                         # bfloat16 only
+
+
+@pytest.mark.parametrize("dtype,row_bytes", [(d, rb) for d in (F32, BF16, I32) for rb in SHORT_ROW_BYTES
+                                             if d == BF16 or rb % 4 == 0])
 def test_block_scores_of_many_short_rows(dtype, row_bytes):
-    # many rows of 16 ... 512 bytes are read as contiguous runs of whole rows; the scores are
-    # the oracle's and, bit for bit, those of the listed walk; last block whole, short by less
-    # than a 16-byte step, and short by more
+    # many rows of up to 512 bytes (up to 4 KiB when they are not whole 16-byte steps) are read
+    # as contiguous runs of whole rows; the scores are the oracle's and, bit for bit, those of
+    # the listed walk; last block whole, short by less than a 16-byte step, and short by more
     L = row_bytes // (2 if dtype == BF16 else 4)
-    for nb, cut in [(4096, 0), (9001, 1), (20_011, L // 2 + 1), (70_000, L - 1)]:
+    sizes = [(4096, 0), (9001, 1), (20_011, L // 2 + 1), (70_000, L - 1)]
+    for nb, cut in sizes if row_bytes <= 1024 else [(4096, 0), (6001, 1), (9011, L // 2 + 1)]:
         n = L * nb - cut
         x, c = make_store(dtype, n, seed=row_bytes + nb)
         dx, dc = to_dev(x, dtype), to_dev(c, dtype)

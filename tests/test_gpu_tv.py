@@ -68,7 +68,7 @@ def test_tv_calls(dtype, L, weighted):
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
-@pytest.mark.parametrize("row_bytes", [16, 80, 400, 512])
+@pytest.mark.parametrize("row_bytes", [16, 80, 400, 512, 20, 36, 100, 404, 2004])
 @pytest.mark.parametrize("weighted", [False, True])
 def test_tv_scores_of_many_short_rows(dtype, row_bytes, weighted):
     # enough rows of 16 ... 512 bytes for the scan that reads whole runs of rows; last row short
