@@ -8,6 +8,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace scar {
 
 constexpr int kWG = 256;    // threads per workgroup, 4 wavefronts
@@ -223,14 +225,28 @@ __device__ __forceinline__ typename Acc<DT>::type block_distance(const char* xb,
                                                                  uint32_t len, int lane) {
   constexpr int E = elem_bytes(DT);
   constexpr int EPV = 16 / E;
+  using word_t = typename std::conditional<E == 4, uint32_t, uint16_t>::type;
   typename Acc<DT>::type acc = 0;
   uint32_t head = 0, nvec;
+  // The few elements before and after the 16-byte steps of a split row are asked for together
+  // with the first steps (one round trip to memory less at each end of the row) when the group
+  // has a lane for each of them; they are still added in the order head, steps, tail.
+  bool has_head = false, has_tail = false;
+  word_t hx = 0, hc = 0, tx = 0, tc = 0;
   if constexpr (VEC) {
     nvec = len / EPV;
   } else {
     const RowSplit rs = row_split<E>(xb, cb, len);
     head = rs.head, nvec = rs.nvec;
-    for (uint32_t j = lane; j < head; j += G) accumulate_elem<DT>(acc, xb, cb, j);
+    if (G >= EPV && head < (uint32_t)EPV) {
+      const uint32_t tail0 = head + nvec * EPV;
+      has_head = (uint32_t)lane < head, has_tail = tail0 + lane < len;
+      if (has_head) hx = ((const word_t*)xb)[lane], hc = ((const word_t*)cb)[lane];
+      if (has_tail) tx = ((const word_t*)xb)[tail0 + lane], tc = ((const word_t*)cb)[tail0 + lane];
+      if (nvec == 0 && has_head) accumulate_elem<DT>(acc, (const char*)&hx, (const char*)&hc, 0);
+    } else {
+      for (uint32_t j = lane; j < head; j += G) accumulate_elem<DT>(acc, xb, cb, j);
+    }
   }
   const uint4* xv = (const uint4*)(xb + (size_t)head * E);
   const uint4* cv = (const uint4*)(cb + (size_t)head * E);
@@ -247,7 +263,15 @@ __device__ __forceinline__ typename Acc<DT>::type block_distance(const char* xb,
         b[u] = make_uint4(0, 0, 0, 0);
       }
     }
+    if constexpr (!VEC)
+      if (v0 == 0 && has_head) accumulate_elem<DT>(acc, (const char*)&hx, (const char*)&hc, 0);
     accumulate_vec<DT, kUnroll>(acc, a, b);
+  }
+  if constexpr (!VEC) {
+    if (G >= EPV && head < (uint32_t)EPV) {
+      if (has_tail) accumulate_elem<DT>(acc, (const char*)&tx, (const char*)&tc, 0);
+      return acc;
+    }
   }
   for (uint32_t j = head + nvec * EPV + lane; j < len; j += G) accumulate_elem<DT>(acc, xb, cb, j);
   return acc;
