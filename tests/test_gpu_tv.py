@@ -147,3 +147,34 @@ def test_tv_large_store_and_long_lists():
     finally:
         oracle.set_num_threads(1)
     np.testing.assert_array_equal(to_host(x), hx)
+
+
+def test_tv_cycle_at_the_benchmark_size():
+    # the total-variation workload of bench.py (2,000,000 documents x 100 topics, weighted) in
+    # the benchmark's launch configuration: every score, the whole selection, the commit and
+    # the recovery with its norm against the oracle on the full host copy
+    import os
+    import sys
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import bench
+    x, c, L, k, n_lost, lost_of, _drift, label, lengths = bench.make_doctopic(DEV)
+    print(label, flush=True)
+    nb = x.numel() // L
+    hx, hc, hw = to_host(x), to_host(c), lengths.cpu().numpy()
+    ws = scar.new_workspace(nb, DEV)
+    oracle.set_num_threads(8)
+    try:
+        s = scar.tv_block_scores(x, c, L, lengths)
+        s_ref = oracle.tv_block_scores(F32, hx, hc, L, hw)
+        close(s.cpu().numpy(), s_ref)
+        idx = scar.select_topk(s, k, ws)
+        assert_selection_matches(idx_host(idx), s.cpu().numpy(), s_ref, k)
+        scar.checkpoint_commit(x, c, L, idx)
+        oracle.checkpoint_commit(F32, hx, hc, L, idx_host(idx))
+        assert torch.equal(c, torch.from_numpy(hc).to(DEV))
+        lost = lost_of(0)
+        got = scar.read_norm(scar.tv_partial_recover(x, c, L, idx_dev(lost), ws, lengths))
+        norm_close(got, oracle.tv_partial_recover(F32, hx, hc, L, lost, hw))
+        assert torch.equal(x, torch.from_numpy(hx).to(DEV))
+    finally:
+        oracle.set_num_threads(1)
