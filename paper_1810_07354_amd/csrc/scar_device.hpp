@@ -51,7 +51,14 @@ __device__ __forceinline__ uint32_t xcd_contiguous_block_id() {
 
 // ---- per-element distance terms --------------------------------------------------
 
-__device__ __forceinline__ float sq(float d) { return d * d; }
+// The square is rounded to float32 on its own, never fused into a following addition: where
+// the compiler can see two of these added up (a lane holding a whole short row) it would
+// otherwise make one a fused multiply-add, and the same row scored by a kernel that walks it
+// in a loop would round differently (seen on 8-byte float32 rows: one ulp in 8 % of them).
+__device__ __forceinline__ float sq(float d) {
+#pragma clang fp contract(off)
+  return d * d;
+}
 
 // Sums of squares are written with explicit fused multiply-adds, so that every kernel that
 // measures a block rounds in the same places whatever else it does with the data (the norm

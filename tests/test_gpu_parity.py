@@ -147,9 +147,13 @@ def test_block_scores_of_rows_shorter_than_16_bytes(dtype, L):
     # remainder of the store after the last whole step (0 ... 7 elements, ragged last row) is tried
     for n in [1, 2, 3, 5, 8, 4096, 100_000, 100_001, 100_002, 100_003, 100_005, 100_007, 1_000_003]:
         x, c = make_store(dtype, n, seed=n + L)
-        s = scar.block_scores(to_dev(x, dtype), to_dev(c, dtype), L)
+        dx, dc = to_dev(x, dtype), to_dev(c, dtype)
+        s = scar.block_scores(dx, dc, L)
         assert s.numel() == oracle.n_blocks_of(n, L)
         assert_scores_match(s, oracle.block_scores(dtype, x, c, L), dtype)
+        listed = torch.full_like(s, -1)                      # the listed walk agrees bit for bit
+        scar.block_scores_rows(dx, dc, L, torch.arange(s.numel(), dtype=torch.int32, device=DEV), listed)
+        assert torch.equal(s, listed)
 
 
 def test_block_scores_int_extremes():
@@ -605,3 +609,48 @@ def test_other_cycles_replay_correctly_from_a_hip_graph(kind):
         noise = 1e-3 * torch.empty(x2.numel(), device=DEV).normal_(generator=g)
         state_x, state_c = (x2 + noise.to(x2.dtype)).contiguous(), c2
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_layouts_whole_cycles(seed):
+    # seeded random stores - element type, block length (log-uniform 1 ... 6,000), block count
+    # (a few ... tens of thousands, so both the group-per-row and the run-of-rows scans are
+    # met), offsets of x and c into their allocations, short last block - each taken through
+    # scores (full and listed), selection, commit with staging, norm and recovery
+    r = np.random.default_rng(1000 + seed)
+    for case in range(10):
+        dtype = int(r.choice([F32, BF16, I32]))
+        L = int(np.exp(r.uniform(0, np.log(6000))))
+        nb = int(np.exp(r.uniform(np.log(3), np.log(60_000))))
+        nb = max(2, min(nb, 6_000_000 // L))
+        n = L * nb - int(r.integers(0, L))
+        nbk = oracle.n_blocks_of(n, L)
+        off_x = int(r.choice([0, 0, 0, 1, 4, 5]))
+        off_c = off_x if r.random() < 0.8 else int(r.integers(0, 8))
+        hx, hc = make_store(dtype, n, seed=seed * 100 + case)
+        x = to_dev(np.concatenate([np.zeros(off_x, dtype=hx.dtype), hx]), dtype)[off_x:]
+        c = to_dev(np.concatenate([np.zeros(off_c, dtype=hc.dtype), hc]), dtype)[off_c:]
+        print("random layout seed=%d case=%d dtype=%d L=%d nb=%d n=%d offsets=(%d,%d)"
+              % (seed, case, dtype, L, nbk, n, off_x, off_c), flush=True)
+        ws = scar.new_workspace(nbk, DEV)
+        s = scar.block_scores(x, c, L)
+        s_ref = oracle.block_scores(dtype, hx, hc, L)
+        assert_scores_match(s, s_ref, dtype)
+        listed = torch.full_like(s, -1)
+        scar.block_scores_rows(x, c, L, torch.randperm(nbk, device=DEV).to(torch.int32), listed)
+        assert torch.equal(s, listed)
+        k = int(r.integers(1, nbk + 1))
+        idx = scar.select_topk(s, k, ws)
+        assert_selection_matches(idx_host(idx), s.cpu().numpy(), s_ref, k)
+        st = torch.zeros(k * L, dtype=x.dtype, device=DEV)
+        scar.checkpoint_commit(x, c, L, idx, st)
+        hst = np.zeros(k * L, dtype=hx.dtype)
+        oracle.checkpoint_commit(dtype, hx, hc, L, idx_host(idx), hst)
+        np.testing.assert_array_equal(to_host(c.contiguous()), hc)
+        np.testing.assert_array_equal(to_host(st), hst)
+        S = r.permutation(nbk)[: max(1, nbk // 3)].astype(np.uint32)
+        pre = scar.read_norm(scar.perturbation_norm(x, c, L, idx_dev(S), ws))
+        got = scar.read_norm(scar.partial_recover(x, c, L, idx_dev(S), ws))
+        assert_norm_matches(got, oracle.partial_recover(dtype, hx, hc, L, S), dtype)
+        assert pre == got
+        np.testing.assert_array_equal(to_host(x.contiguous()), hx)
