@@ -153,3 +153,41 @@ def test_recover_from_packed_rows_of_any_length(dtype, L):
     want = oracle.partial_recover(dtype, hx, hc, L, lost)
     assert_norm_matches(got, want, wl.I32 if dtype == wl.I32 else wl.F32)
     np.testing.assert_array_equal(to_host(x), hx)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_mixed_random_layouts(seed):
+    # seeded random stores (block length, block count, short last block, x and c one element
+    # into their allocations or not) through scores, commit with staging, norm and recovery
+    r = np.random.default_rng(3000 + seed)
+    for case in range(8):
+        L = int(np.exp(r.uniform(0, np.log(6000))))
+        nb = int(np.exp(r.uniform(np.log(3), np.log(40_000))))
+        nb = max(2, min(nb, 4_000_000 // L))
+        n = L * nb - int(r.integers(0, L))
+        nbk = oracle.n_blocks_of(n, L)
+        off_x, off_c = int(r.choice([0, 0, 1])), int(r.choice([0, 0, 1, 3]))
+        hx, hc = make(n, seed * 100 + case)
+        x = to_dev(np.concatenate([np.zeros(off_x, dtype=hx.dtype), hx]), wl.F32)[off_x:]
+        c = to_dev(np.concatenate([np.zeros(off_c, dtype=hc.dtype), hc]), wl.BF16)[off_c:]
+        print("mixed random seed=%d case=%d L=%d nb=%d n=%d offsets=(%d,%d)" % (seed, case, L, nbk, n, off_x, off_c),
+              flush=True)
+        ws = scar.new_workspace(nbk, DEV)
+        s = scar.block_scores(x, c, L)
+        s_ref = oracle.block_scores(MIX, hx, hc, L)
+        scores_match(s, s_ref)
+        k = int(r.integers(1, nbk + 1))
+        idx = scar.select_topk(s, k, ws)
+        assert_selection_matches(idx_host(idx), s.cpu().numpy(), s_ref, k)
+        st = torch.zeros(k * L, dtype=torch.bfloat16, device=DEV)
+        scar.checkpoint_commit(x, c, L, idx, st)
+        hst = np.zeros(k * L, dtype=np.uint16)
+        oracle.checkpoint_commit(MIX, hx, hc, L, idx_host(idx), hst)
+        np.testing.assert_array_equal(to_host(c.contiguous()), hc)
+        np.testing.assert_array_equal(to_host(st), hst)
+        S = r.permutation(nbk)[: max(1, nbk // 3)].astype(np.uint32)
+        pre = scar.read_norm(scar.perturbation_norm(x, c, L, idx_dev(S), ws))
+        got = scar.read_norm(scar.partial_recover(x, c, L, idx_dev(S), ws))
+        assert_norm_matches(got, oracle.partial_recover(MIX, hx, hc, L, S), wl.F32)
+        assert pre == got
+        np.testing.assert_array_equal(to_host(x.contiguous()), hx)

@@ -178,3 +178,34 @@ def test_tv_cycle_at_the_benchmark_size():
         assert torch.equal(x, torch.from_numpy(hx).to(DEV))
     finally:
         oracle.set_num_threads(1)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_tv_random_layouts(seed):
+    # seeded random stores (element type, row length, row count, weights or none, short last
+    # row, x and c one element into their allocations or not) through the three calls
+    r = np.random.default_rng(2000 + seed)
+    for case in range(8):
+        dtype = int(r.choice([F32, BF16]))
+        L = int(np.exp(r.uniform(0, np.log(3000))))
+        nb = int(np.exp(r.uniform(np.log(3), np.log(40_000))))
+        nb = max(2, min(nb, 3_000_000 // L))
+        hx, hc = rows(dtype, nb, L, seed=seed * 100 + case, ragged=bool(r.integers(0, 2)))
+        nbk = oracle.n_blocks_of(hx.size, L)
+        off = int(r.choice([0, 0, 1]))
+        x = to_dev(np.concatenate([np.zeros(off, dtype=hx.dtype), hx]), dtype)[off:]
+        c = to_dev(np.concatenate([np.zeros(off, dtype=hc.dtype), hc]), dtype)[off:]
+        hw = r.integers(5, 3000, size=nbk).astype(np.float32) if r.random() < 0.7 else None
+        w = torch.from_numpy(hw).to(DEV) if hw is not None else None
+        print("tv random seed=%d case=%d dtype=%d L=%d nb=%d off=%d weighted=%s"
+              % (seed, case, dtype, L, nbk, off, hw is not None), flush=True)
+        ws = scar.new_workspace(nbk, DEV)
+        close(scar.tv_block_scores(x, c, L, w).cpu().numpy(), oracle.tv_block_scores(dtype, hx, hc, L, hw))
+        norm_close(scar.read_norm(scar.tv_perturbation_norm(x, c, L, None, ws, w)),
+                   oracle.tv_perturbation_norm(dtype, hx, hc, L, hw))
+        S = r.permutation(nbk)[: max(1, nbk // 3)].astype(np.uint32)
+        pre = scar.read_norm(scar.tv_perturbation_norm(x, c, L, idx_dev(S), ws, w))
+        got = scar.read_norm(scar.tv_partial_recover(x, c, L, idx_dev(S), ws, w))
+        norm_close(got, oracle.tv_partial_recover(dtype, hx, hc, L, S, hw))
+        assert pre == got
+        np.testing.assert_array_equal(to_host(x.contiguous()), hx)
