@@ -337,6 +337,17 @@ static uint32_t flat_chunk_rows(uint64_t row_bytes) {
   return 0;
 }
 
+// Row lengths the run-of-rows kernel takes: whole 16-byte steps from 32 to kFlatRowBytes
+// bytes (longer ones do as well with a group per row); any other length up to
+// kFlatSplitRowBytes whose chunks can start on 16-byte boundaries.  g is the group size the
+// listed walk would use - the kernel adds in its order and has G up to 64.  Weighted rows
+// (total variation) keep their weights in LDS, which holds them for rows of 32 bytes or more.
+static bool flat_rows_fit(bool tv, uint64_t row_bytes, int g) {
+  if (g > 64 || (uint64_t)g * kUnroll * 16 < row_bytes) return false;
+  if (row_bytes % 16 == 0) return row_bytes >= 32 && row_bytes <= kFlatRowBytes;
+  return row_bytes <= kFlatSplitRowBytes && (!tv || row_bytes >= 32) && flat_chunk_rows(row_bytes) > 0;
+}
+
 template <int DT, int G, bool SPLIT>
 static void launch_scores_flat(const scar_layout* l, const void* x, const void* c, void* scores,
                                const float* weights, hipStream_t st) {
@@ -443,9 +454,7 @@ static int block_scores(bool tv, bool listed, const scar_layout* layout, const v
   }
   // many short rows of an aligned store: read as runs of whole rows
   const bool split = row_bytes % 16 != 0;
-  if (!listed && aligned(x, 16) && aligned(c, 16) && n >= kFlatMinRows && (uint64_t)g * kUnroll * 16 >= row_bytes &&
-      (split ? row_bytes <= kFlatSplitRowBytes && (!tv || row_bytes >= 32) && flat_chunk_rows(row_bytes) > 0
-             : row_bytes >= 32 && row_bytes <= kFlatRowBytes)) {
+  if (!listed && aligned(x, 16) && aligned(c, 16) && n >= kFlatMinRows && flat_rows_fit(tv, row_bytes, g)) {
     bool done = false;
     if (tv && layout->dtype == SCAR_F32) done = dispatch_scores_flat<DT_F32_TV>(g, split, layout, x, c, scores, weights, st);
     else if (tv) done = dispatch_scores_flat<DT_BF16_TV>(g, split, layout, x, c, scores, weights, st);
