@@ -654,3 +654,28 @@ def test_random_layouts_whole_cycles(seed):
         assert_norm_matches(got, oracle.partial_recover(dtype, hx, hc, L, S), dtype)
         assert pre == got
         np.testing.assert_array_equal(to_host(x.contiguous()), hx)
+
+
+@pytest.mark.parametrize("dtype,L,nb", [(F32, 3, 20_000_003), (BF16, 50, 5_000_001), (I32, 25, 6_000_000),
+                                        (F32, 100, 2_684_354)])
+def test_block_scores_of_very_many_short_rows(dtype, L, nb):
+    # tens of thousands of chunks of the run-of-rows scan
+    n = L * nb - (L // 2)
+    r = np.random.default_rng(L + nb)
+    if dtype == I32:
+        c = r.integers(-50, 50, size=n, dtype=np.int32)
+        x = c + (r.integers(0, 16, size=n, dtype=np.int32) == 0)
+        x = x.astype(np.int32)
+    else:
+        c = r.random(n, dtype=np.float32)
+        x = c + np.float32(0.01) * r.random(n, dtype=np.float32)
+        if dtype == BF16:
+            x, c = wl.f32_to_bf16_bits(x), wl.f32_to_bf16_bits(c)
+    print("very many short rows dtype=%d L=%d nb=%d" % (dtype, L, nb), flush=True)
+    oracle.set_num_threads(8)
+    try:
+        want = oracle.block_scores(dtype, x, c, L)
+    finally:
+        oracle.set_num_threads(1)
+    s = scar.block_scores(to_dev(x, dtype), to_dev(c, dtype), L)
+    assert_scores_match(s, want, dtype)
