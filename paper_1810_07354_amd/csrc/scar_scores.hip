@@ -181,7 +181,7 @@ constexpr uint32_t kFlatMinRows = 4096;        // below this a launch is all the
 
 template <int DT>
 struct StepSum {
-  using type = float;  // per step; the terms of single elements have the same type
+  using type = float;  // sum of the terms of one 16-byte step
 };
 template <>
 struct StepSum<DT_I32> {
@@ -189,7 +189,7 @@ struct StepSum<DT_I32> {
 };
 template <int DT>
 struct ElemTerm {
-  using type = float;
+  using type = float;  // term of a single element
 };
 template <>
 struct ElemTerm<DT_I32> {
