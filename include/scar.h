@@ -129,7 +129,7 @@ int scar_block_scores(const scar_layout* layout, const void* x, const void* c, v
  * rescoring them - and setting the score of a block to 0 when it is saved, which scoring it
  * after the commit does - keeps `scores` equal to what the full scan would give, at a
  * fraction of the traffic.  (An economy on top of the paper's protocol, which looks at every
- * parameter at every checkpoint.)  Not for SCAR_F32_BF16C. */
+ * parameter at every checkpoint.) */
 int scar_block_scores_rows(const scar_layout* layout, const void* x, const void* c,
                            const uint32_t* idx, uint32_t n_idx, void* scores, void* stream);
 

@@ -161,7 +161,7 @@ int oracle_block_scores(int dtype, const void *x, const void *c, uint64_t n_elem
  * need not look at the rest; the values are those of oracle_block_scores). */
 int oracle_block_scores_rows(int dtype, const void *x, const void *c, uint64_t n_elems,
                              uint32_t block_len, const uint32_t *idx, uint32_t n_idx, void *scores) {
-  if (!dtype_ok(dtype) || dtype == ORACLE_F32_BF16C || block_len == 0) return ORACLE_ERR_ARG;
+  if (!dtype_ok(dtype) || block_len == 0) return ORACLE_ERR_ARG;
   if (n_idx == 0) return ORACLE_OK;
   if (!x || !c || !scores) return ORACLE_ERR_ARG;
   int rc = check_indices(idx, n_idx, count_blocks(n_elems, block_len));

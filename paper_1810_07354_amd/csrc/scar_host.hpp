@@ -123,7 +123,7 @@ void launch_finish(int32_t dtype, const void* partial, uint32_t n_partial, scar_
 // Bodies of the entry points for that store type (defined with its kernels); arguments are
 // as in the entry points and the layout has already been checked.
 int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, const void* c,
-                       void* scores, hipStream_t st);
+                       const uint32_t* idx, uint32_t n_idx, void* scores, hipStream_t st);
 int mixed_commit(const scar_layout* l, uint32_t n_blocks, const void* x, void* c, const uint32_t* idx,
                  uint32_t n_idx, void* staging, hipStream_t st);
 int mixed_recover_or_norm(bool store, bool packed, const scar_layout* l, uint32_t n_blocks, void* x, const void* c,

@@ -93,17 +93,26 @@ __device__ __forceinline__ double mixed_distance(const float* xb, const uint16_t
   return acc;
 }
 
-template <int G>
+// LISTED: only the blocks idx[0..n_idx) are scored (entries >= n_blocks are skipped); the other
+// entries of scores stay as they are.
+template <int G, bool LISTED>
 __global__ __launch_bounds__(kWG) void k_mixed_scores(const float* __restrict__ x,
                                                       const uint16_t* __restrict__ c,
                                                       float* __restrict__ scores, uint64_t n_elems,
-                                                      uint32_t block_len, uint32_t n_blocks, bool vec) {
+                                                      uint32_t block_len, uint32_t n_blocks, bool vec,
+                                                      const uint32_t* __restrict__ idx, uint32_t n_idx) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
   const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
   __shared__ double slots[kWG / kWave];
-  for (uint64_t b = (uint64_t)xcd_contiguous_block_id() * GPW + grp; b < n_blocks;
-       b += (uint64_t)gridDim.x * GPW) {
+  const uint64_t n_items = LISTED ? n_idx : n_blocks;
+  for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_items;
+       i += (uint64_t)gridDim.x * GPW) {
+    uint64_t b = i;
+    if constexpr (LISTED) {
+      b = idx[i];
+      if (b >= n_blocks) continue;
+    }
     const BlockSpan sp = block_span(b, n_elems, block_len, 1);  // byte_off = element offset
     double acc = mixed_distance<G>(x + sp.byte_off, c + sp.byte_off, sp.len, lane, vec);
     if constexpr (G == 256)
@@ -233,7 +242,7 @@ static uint32_t mixed_pieces(const scar_layout* l, bool vec) {
 }
 
 int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, const void* c,
-                       void* scores, hipStream_t st) {
+                       const uint32_t* idx, uint32_t n_idx, void* scores, hipStream_t st) {
   if (!x || !c || !scores || !aligned(x, 4) || !aligned(c, 2) || !aligned(scores, 4))
     return SCAR_ERR_INVALID_ARG;
   const bool vec = mixed_vec(l, x, c);
@@ -243,12 +252,18 @@ int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, c
 #define CALL(G)                                                                                      \
   {                                                                                                  \
     constexpr int GPW = (G == 256) ? 1 : kWG / G;                                                    \
-    const uint64_t need = ((uint64_t)n_blocks + GPW - 1) / GPW;                                      \
+    const uint64_t need = ((uint64_t)(idx ? n_idx : n_blocks) + GPW - 1) / GPW;                      \
     const uint32_t grid = xcd_grid(need, kScoreGridCap);                                             \
     const uint64_t group_units = units < (uint64_t)G * kMixU ? units : (uint64_t)G * kMixU;          \
     const size_t lds = stream_lds_bytes(need, (vec ? 24 : 6) * group_units * GPW);                   \
-    hipLaunchKernelGGL((k_mixed_scores<G>), dim3(grid), dim3(kWG), lds, st, (const float*)x,         \
-                       (const uint16_t*)c, (float*)scores, l->n_elems, l->block_len, n_blocks, vec); \
+    if (idx)                                                                                         \
+      hipLaunchKernelGGL((k_mixed_scores<G, true>), dim3(grid), dim3(kWG), lds, st, (const float*)x, \
+                         (const uint16_t*)c, (float*)scores, l->n_elems, l->block_len, n_blocks,     \
+                         vec, idx, n_idx);                                                           \
+    else                                                                                             \
+      hipLaunchKernelGGL((k_mixed_scores<G, false>), dim3(grid), dim3(kWG), lds, st,                 \
+                         (const float*)x, (const uint16_t*)c, (float*)scores, l->n_elems,            \
+                         l->block_len, n_blocks, vec, idx, n_idx);                                   \
   }
   switch (g) {  // the score kernel reduces inside a wavefront or a whole workgroup
     case 1: CALL(1) break;

@@ -423,12 +423,11 @@ static int block_scores(bool tv, bool listed, const scar_layout* layout, const v
   const uint64_t nb = layout_blocks(layout);
   if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
   if (tv && layout->dtype != SCAR_F32 && layout->dtype != SCAR_BF16) return SCAR_ERR_INVALID_ARG;
-  if (listed && layout->dtype == SCAR_F32_BF16C) return SCAR_ERR_INVALID_ARG;
   if (nb == 0 || (listed && n_idx == 0)) return SCAR_OK;
   if (listed && (!idx || !aligned(idx, 4))) return SCAR_ERR_INVALID_ARG;
   if (!listed) idx = nullptr;
   if (layout->dtype == SCAR_F32_BF16C)
-    return mixed_block_scores(layout, (uint32_t)nb, x, c, scores, (hipStream_t)stream);
+    return mixed_block_scores(layout, (uint32_t)nb, x, c, idx, n_idx, scores, (hipStream_t)stream);
   const int eb = host_elem_bytes(layout->dtype);
   if (!x || !c || !scores || !aligned(x, eb) || !aligned(c, eb) || !aligned(weights, 4) ||
       !aligned(scores, layout->dtype == SCAR_I32 ? 8 : 4))

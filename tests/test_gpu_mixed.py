@@ -191,3 +191,29 @@ def test_mixed_random_layouts(seed):
         assert_norm_matches(got, oracle.partial_recover(MIX, hx, hc, L, S), wl.F32)
         assert pre == got
         np.testing.assert_array_equal(to_host(x.contiguous()), hx)
+
+
+@pytest.mark.parametrize("L,nb", [(1, 5000), (24, 3000), (100, 9000), (1024, 700), (5000, 60)])
+def test_mixed_scores_of_listed_blocks(L, nb):
+    # scores[b] for b in idx equal the full scan's bit for bit, the other entries stay; the
+    # list is unsorted, holds the short last block and two entries out of range (skipped)
+    n = L * nb - L // 2
+    hx, hc = make(n, 7 * L)
+    x, c = to_dev(hx, wl.F32), to_dev(hc, wl.BF16)
+    nbk = oracle.n_blocks_of(n, L)
+    r = np.random.default_rng(L)
+    listed = np.unique(np.append(r.permutation(nbk)[: nbk // 5], nbk - 1)).astype(np.uint32)
+    r.shuffle(listed)
+    stale_h = (np.arange(nbk) * 3).astype(np.float32)
+    stale = torch.from_numpy(stale_h.copy()).to(DEV)
+    with_bad = np.concatenate([listed[:3], [nbk, 0xFFFFFFFF], listed[3:]]).astype(np.uint32)
+    scar.block_scores_rows(x, c, L, idx_dev(with_bad), stale)
+    want = stale_h.astype(np.float64)
+    oracle.block_scores_rows(MIX, hx, hc, L, listed, want)
+    got = stale.cpu().numpy()
+    keep = np.ones(nbk, dtype=bool)
+    keep[listed] = False
+    np.testing.assert_array_equal(got[keep], stale_h[keep])
+    np.testing.assert_allclose(got[listed].astype(np.float64), want[listed], rtol=REL_TOL, atol=0)
+    full = scar.block_scores(x, c, L)
+    assert torch.equal(full[idx_dev(listed).long()], stale[idx_dev(listed).long()])

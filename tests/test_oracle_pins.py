@@ -749,7 +749,7 @@ def test_tv_norm_is_the_weighted_sum_of_the_block_distances():
 
 # ------------------------------------------------------------- scores of listed blocks only
 
-@pytest.mark.parametrize("dtype", [F32, BF16, I32])
+@pytest.mark.parametrize("dtype", [F32, BF16, I32, oracle.F32_BF16C])
 def test_rescoring_listed_blocks_equals_rescoring_everything(dtype):
     r = np.random.default_rng(21 + dtype)
     L, nb = 7, 40
@@ -762,6 +762,9 @@ def test_rescoring_listed_blocks_equals_rescoring_everything(dtype):
         x = c.copy()
         if dtype == BF16:
             x, c = (np.frombuffer(a.tobytes(), dtype=np.uint16)[1::2].copy() for a in (x, c))
+        elif dtype == oracle.F32_BF16C:                           # c in bfloat16, x its exact widening
+            c = np.frombuffer(c.tobytes(), dtype=np.uint16)[1::2].copy()
+            x = (c.astype(np.uint32) << 16).view(np.float32)
     s = oracle.block_scores(dtype, x, c, L)
     assert not s.any()
     touched = np.array([39, 0, 17, 5, 16], dtype=np.uint32)      # unsorted, two neighbours, the short tail
@@ -769,7 +772,7 @@ def test_rescoring_listed_blocks_equals_rescoring_everything(dtype):
         lo, hi = b * L, min((b + 1) * L, n)
         if dtype == I32:
             x[lo:hi] += 3
-        elif dtype == F32:
+        elif x.dtype == np.float32:
             x[lo:hi] += np.float32(0.5)
         else:
             x[lo:hi] ^= np.uint16(0x0080)                         # flip a mantissa bit
