@@ -123,6 +123,102 @@ __global__ __launch_bounds__(kWG) void k_mixed_scores(const float* __restrict__ 
   }
 }
 
+// Many short rows of an aligned store, read as runs of whole rows (the reduced-precision twin
+// of k_block_scores_flat): a workgroup loads a chunk of `chunk_rows` whole rows - at most
+// kMixFlatUnits units per stream, every lane kMixU of them, fully coalesced - and leaves in LDS
+// one partial sum per unit or, SPLIT (rows that are not whole units, which k_mixed_scores walks
+// element by element), one term per element.  The groups then add each row's values in the
+// order in which mixed_distance adds them from memory, so the scores are bit for bit those of
+// k_mixed_scores, which still serves listed blocks and a short last block of the store.
+// Chunks start on 16-byte boundaries of x (8-byte boundaries of c); the host sizes chunk_rows
+// for that.
+constexpr uint32_t kMixFlatUnits = kWG * kMixU;
+constexpr uint32_t kMixFlatRowElems = 128;       // longest row of whole units taken (512 bytes of x)
+constexpr uint32_t kMixFlatSplitRowElems = 256;  // longest row that is not (G <= 64 element-wise)
+constexpr uint32_t kMixFlatMinRows = 4096;
+
+template <int G, bool SPLIT>
+__global__ __launch_bounds__(kWG) void k_mixed_scores_flat(const float* __restrict__ x,
+                                                           const uint16_t* __restrict__ c,
+                                                           float* __restrict__ scores, uint32_t block_len,
+                                                           uint32_t n_rows, uint32_t chunk_rows,
+                                                           uint32_t n_chunks) {
+  constexpr int GPW = kWG / G;
+  __shared__ __align__(16) float vals[SPLIT ? kMixFlatUnits * kMixUnit : kMixFlatUnits];
+  const int lane = threadIdx.x & (G - 1);
+  const uint32_t grp = threadIdx.x / G;
+  for (uint32_t chunk = xcd_contiguous_block_id(); chunk < n_chunks; chunk += gridDim.x) {
+    const uint64_t row0 = (uint64_t)chunk * chunk_rows;
+    const uint32_t rows = (uint32_t)(n_rows - row0 < chunk_rows ? n_rows - row0 : chunk_rows);
+    const uint32_t n_el = rows * block_len;
+    const uint32_t nunit = n_el / kMixUnit;  // whole units; only the last chunk can end inside one
+    const float* xc = x + row0 * block_len;
+    const uint16_t* cc = c + row0 * block_len;
+    uint4 a[kMixU];
+    uint2 b[kMixU];
+#pragma unroll
+    for (int u = 0; u < kMixU; ++u) {
+      const uint32_t i = u * kWG + threadIdx.x;
+      if (i < nunit) {
+        a[u] = load_stream((const uint4*)xc + i);
+        b[u] = load_stream2((const uint2*)cc + i);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kMixU; ++u) {
+      const uint32_t i = u * kWG + threadIdx.x;
+      if (i >= nunit) continue;
+      if constexpr (SPLIT) {
+        float4 t;  // the terms of the element-wise walk
+        t.x = sq(__uint_as_float(a[u].x) - widen_lo(b[u].x));
+        t.y = sq(__uint_as_float(a[u].y) - widen_hi(b[u].x));
+        t.z = sq(__uint_as_float(a[u].z) - widen_lo(b[u].y));
+        t.w = sq(__uint_as_float(a[u].w) - widen_hi(b[u].y));
+        ((float4*)vals)[i] = t;
+      } else {
+        vals[i] = sqdiff_unit(a[u], b[u]);
+      }
+    }
+    if constexpr (SPLIT)  // the elements after the last whole unit (last chunk only)
+      for (uint32_t j = nunit * kMixUnit + threadIdx.x; j < n_el; j += kWG) vals[j] = sq(xc[j] - widen_elem(cc, j));
+    __syncthreads();
+    for (uint32_t r = grp; r < rows; r += GPW) {
+      double acc = 0;
+      if constexpr (SPLIT) {
+        const float* p = vals + r * block_len;
+        for (uint32_t j = lane; j < block_len; j += G) acc += (double)p[j];
+      } else {
+        const uint32_t row_units = block_len / kMixUnit;
+        const float* p = vals + r * row_units;
+        for (uint32_t u0 = 0; u0 < row_units; u0 += G * kMixU) {  // the order of mixed_distance
+          float part = 0.f;
+#pragma unroll
+          for (int u = 0; u < kMixU; ++u) {
+            const uint32_t i = u0 + u * G + lane;
+            part += i < row_units ? p[i] : 0.f;
+          }
+          acc += (double)part;
+        }
+      }
+      acc = group_sum<G>(acc);
+      if (lane == 0) scores[row0 + r] = (float)acc;
+    }
+    __syncthreads();  // the next chunk overwrites vals
+  }
+}
+
+// Rows per chunk of the run-of-rows kernel: as many as fit, rounded down so that chunks start
+// on 128-byte lines of x, or at least on 16-byte boundaries; 0 if not even that fits.
+static uint32_t mixed_flat_chunk_rows(uint32_t block_len) {
+  const uint32_t fit = kMixFlatUnits * kMixUnit / block_len;
+  for (uint32_t align = 32; align >= 4; align /= 2) {  // in elements of x
+    uint32_t m = align;
+    for (uint32_t v = block_len; m > 1 && v % 2 == 0; v /= 2) m /= 2;
+    if (fit >= m) return fit / m * m;
+  }
+  return 0;
+}
+
 // Rows longer than kMixPieceElems elements (4 KiB of x) are handed out in pieces of that
 // length, one per grid-y slice, like the rows of the other store types.
 constexpr uint32_t kMixPieceElems = kPieceBytes / 4;
@@ -249,6 +345,41 @@ int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, c
   // loads in flight: one 16-byte step of x and 8 bytes of c per unit (element-wise: 4 + 2)
   const uint64_t units = vec ? l->block_len / kMixUnit : l->block_len;
   const int g = pick_group_units(units, vec ? kMixU : 4, false);
+  // many short rows of an aligned store: read as runs of whole rows, added up in the order of
+  // the group walk with the same g
+  const bool split = l->block_len % kMixUnit != 0;
+  if (!idx && aligned(x, 16) && aligned(c, 8) && n_blocks >= kMixFlatMinRows && g <= 64 &&
+      l->block_len <= (split ? kMixFlatSplitRowElems : kMixFlatRowElems) &&
+      mixed_flat_chunk_rows(l->block_len) > 0) {
+    const uint32_t n_rows = (uint32_t)(l->n_elems / l->block_len);
+    const uint32_t chunk_rows = mixed_flat_chunk_rows(l->block_len);
+    const uint32_t n_chunks = (n_rows + chunk_rows - 1) / chunk_rows;
+    const uint32_t grid = xcd_grid(n_chunks, kScoreGridCap);
+    // four workgroups per compute unit: 40 KiB of LDS each, part of it unused
+    const size_t used = (split ? kMixFlatUnits * kMixUnit : kMixFlatUnits) * sizeof(float) + 256;
+    const size_t lds = 40 * 1024 - used;
+#define FLAT(G)                                                                                        \
+  case G:                                                                                              \
+    if (split)                                                                                         \
+      hipLaunchKernelGGL((k_mixed_scores_flat<G, true>), dim3(grid), dim3(kWG), lds, st,               \
+                         (const float*)x, (const uint16_t*)c, (float*)scores, l->block_len, n_rows,    \
+                         chunk_rows, n_chunks);                                                        \
+    else                                                                                               \
+      hipLaunchKernelGGL((k_mixed_scores_flat<G, false>), dim3(grid), dim3(kWG), lds, st,              \
+                         (const float*)x, (const uint16_t*)c, (float*)scores, l->block_len, n_rows,    \
+                         chunk_rows, n_chunks);                                                        \
+    break;
+    switch (g) {
+      FLAT(1) FLAT(2) FLAT(4) FLAT(8) FLAT(16) FLAT(32) FLAT(64)
+    }
+#undef FLAT
+    const uint64_t done = (uint64_t)n_rows * l->block_len;
+    if (done == l->n_elems) return launch_status();
+    // a short last block: a store of one block for the group walk below
+    const scar_layout last = {l->dtype, l->block_len, l->n_elems - done};
+    return mixed_block_scores(&last, 1, (const float*)x + done, (const uint16_t*)c + done, nullptr, 0,
+                              (float*)scores + n_rows, st);
+  }
 #define CALL(G)                                                                                      \
   {                                                                                                  \
     constexpr int GPW = (G == 256) ? 1 : kWG / G;                                                    \

@@ -217,3 +217,20 @@ def test_mixed_scores_of_listed_blocks(L, nb):
     np.testing.assert_allclose(got[listed].astype(np.float64), want[listed], rtol=REL_TOL, atol=0)
     full = scar.block_scores(x, c, L)
     assert torch.equal(full[idx_dev(listed).long()], stale[idx_dev(listed).long()])
+
+
+@pytest.mark.parametrize("L", [1, 3, 4, 6, 12, 25, 52, 100, 101, 128, 200, 255, 256])
+def test_mixed_scores_of_many_short_rows(L):
+    # enough short rows for the scan that reads runs of whole rows; the scores are the
+    # oracle's and, bit for bit, those of the listed walk; last block whole and short
+    for nb, cut in [(4096, 0), (9001, 1), (30_011, L // 2)]:
+        n = L * nb - min(cut, L - 1)
+        hx, hc = make(n, L + nb)
+        x, c = to_dev(hx, wl.F32), to_dev(hc, wl.BF16)
+        print("mixed short rows L=%d nb=%d n=%d" % (L, nb, n), flush=True)
+        s = scar.block_scores(x, c, L)
+        assert s.numel() == oracle.n_blocks_of(n, L)
+        scores_match(s, oracle.block_scores(MIX, hx, hc, L))
+        listed = torch.full_like(s, -1)
+        scar.block_scores_rows(x, c, L, torch.randperm(s.numel(), device=DEV).to(torch.int32), listed)
+        assert torch.equal(s, listed)
