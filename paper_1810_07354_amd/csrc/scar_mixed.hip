@@ -457,6 +457,41 @@ static uint32_t launch_mixed_recover(int g, const scar_layout* l, uint32_t n_blo
   return grid * grid_y;
 }
 
+// The norm over the whole store with nothing stored: one flat reduction over units of 4
+// elements, kMixU of them per lane in flight, each unit's float32 sum folded into float64 on
+// its own as the row walk does it.  Needs x 16-byte and c 8-byte aligned; the elements after
+// the last whole unit go to the first workgroup.
+__global__ __launch_bounds__(kWG) void k_mixed_norm_all(const float* __restrict__ x,
+                                                        const uint16_t* __restrict__ c, uint64_t n_elems,
+                                                        double* __restrict__ partial) {
+  __shared__ double slots[kWG / kWave];
+  const uint64_t nunit = n_elems / kMixUnit;
+  double acc = 0;
+  for (uint64_t u0 = (uint64_t)xcd_contiguous_block_id() * (kWG * kMixU); u0 < nunit;
+       u0 += (uint64_t)gridDim.x * (kWG * kMixU)) {
+    uint4 a[kMixU];
+    uint2 b[kMixU];
+#pragma unroll
+    for (int u = 0; u < kMixU; ++u) {
+      const uint64_t i = u0 + (uint64_t)u * kWG + threadIdx.x;
+      if (i < nunit) {
+        a[u] = load_stream((const uint4*)x + i);
+        b[u] = load_stream2((const uint2*)c + i);
+      } else {
+        a[u] = make_uint4(0, 0, 0, 0);
+        b[u] = make_uint2(0, 0);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kMixU; ++u) acc += (double)sqdiff_unit(a[u], b[u]);
+  }
+  if (blockIdx.x == 0)
+    for (uint64_t j = nunit * kMixUnit + threadIdx.x; j < n_elems; j += kWG)
+      acc += (double)sq(x[j] - widen_elem(c, j));
+  acc = workgroup_sum(acc, slots);
+  if (threadIdx.x == 0) partial[blockIdx.x] = acc;
+}
+
 int mixed_recover_or_norm(bool store, bool packed, const scar_layout* l, uint32_t n_blocks, void* x,
                           const void* c,
                           const uint32_t* idx, uint32_t n_idx, scar_norm* norm_out, void* partial,
@@ -466,6 +501,14 @@ int mixed_recover_or_norm(bool store, bool packed, const scar_layout* l, uint32_
   const uint32_t pieces = mixed_pieces(l, vec);
   const int g = pieces > 1 ? 256 : pick_group_units(vec ? l->block_len / kMixUnit : l->block_len, 1, true);
   uint32_t n_partial = 0;
+  if (!store && norm_out && !idx && !packed && aligned(x, 16) && aligned(c, 8)) {  // the whole store
+    const uint64_t chunks = (l->n_elems / kMixUnit + kWG * kMixU - 1) / (kWG * kMixU);
+    const uint32_t grid = xcd_grid(chunks ? chunks : 1, kMaxNormGrid);
+    hipLaunchKernelGGL(k_mixed_norm_all, dim3(grid), dim3(kWG), stream_lds_bytes(grid, 24 * kWG * kMixU), st,
+                       (const float*)x, (const uint16_t*)c, l->n_elems, (double*)partial);
+    launch_finish(l->dtype, partial, grid, norm_out, st);
+    return launch_status();
+  }
   if (store && norm_out)
     n_partial = launch_mixed_recover<true, true>(g, l, n_blocks, x, c, idx, n_idx, pieces, vec, packed, partial, st);
   else if (store)

@@ -189,6 +189,55 @@ __global__ __launch_bounds__(T, T / 128) void k_recover(char* __restrict__ x, co
   }
 }
 
+// The norm over the whole store with nothing stored (the perturbation a traditional full
+// recovery would cause, Appendix A.3): the sum does not depend on where the blocks begin, so
+// this is one flat two-stream reduction - kUnroll 16-byte loads per lane and stream in flight,
+// as in the score scan, instead of one row per group.  Each 16-byte step is summed in float32
+// and folded into float64 on its own, as the row walk does it.  Needs 16-byte aligned bases;
+// the elements after the last whole step go to the first workgroup.
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_norm_all(const char* __restrict__ x, const char* __restrict__ c,
+                                                  uint64_t n_elems,
+                                                  typename Acc<DT>::type* __restrict__ partial) {
+  constexpr int EPV = 16 / elem_bytes(DT);
+  using acc_t = typename Acc<DT>::type;
+  __shared__ acc_t slots[kWG / kWave];
+  const uint64_t nvec = n_elems / EPV;
+  acc_t acc = 0;
+  for (uint64_t v0 = (uint64_t)xcd_contiguous_block_id() * (kWG * kUnroll); v0 < nvec;
+       v0 += (uint64_t)gridDim.x * (kWG * kUnroll)) {
+    uint4 cv[kUnroll][1], xv[kUnroll][1];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint64_t v = v0 + (uint64_t)u * kWG + threadIdx.x;
+      if (v < nvec) {
+        cv[u][0] = load_stream((const uint4*)c + v);
+        xv[u][0] = load_stream((const uint4*)x + v);
+      } else {
+        cv[u][0] = make_uint4(0, 0, 0, 0);
+        xv[u][0] = make_uint4(0, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) accumulate_vec<DT, 1>(acc, cv[u], xv[u]);
+  }
+  if (blockIdx.x == 0)
+    for (uint64_t j = nvec * EPV + threadIdx.x; j < n_elems; j += kWG) accumulate_elem<DT>(acc, c, x, j);
+  acc = workgroup_sum(acc, slots);
+  if (threadIdx.x == 0) partial[blockIdx.x] = acc;
+}
+
+template <int DT>
+static uint32_t launch_norm_all(const scar_layout* l, const void* x, const void* c, void* partial,
+                                hipStream_t st) {
+  const uint64_t nvec = l->n_elems / (16 / elem_bytes(DT));
+  const uint64_t chunks = (nvec + kWG * kUnroll - 1) / (kWG * kUnroll);
+  const uint32_t grid = xcd_grid(chunks ? chunks : 1, kMaxNormGrid);
+  hipLaunchKernelGGL((k_norm_all<DT>), dim3(grid), dim3(kWG), stream_lds_bytes(grid, 2 * 16 * kWG * kUnroll), st,
+                     (const char*)x, (const char*)c, l->n_elems, (typename Acc<DT>::type*)partial);
+  return grid;
+}
+
 // Second stage of the norm: one workgroup of 1024 threads adds n_partial partial sums in
 // a fixed order and writes the result.  n_partial == 0 writes zeros.
 constexpr int kFinishThreads = 1024;
@@ -393,6 +442,17 @@ static int recover_or_norm(bool store, bool packed, bool tv, const scar_layout* 
   int dt = layout->dtype == SCAR_F32 ? DT_F32 : (layout->dtype == SCAR_BF16 ? DT_BF16 : DT_I32);
   if (tv && norm_out) dt = layout->dtype == SCAR_F32 ? DT_F32_TV : DT_BF16_TV;
   uint32_t n_partial = 0;
+  if (!store && norm_out && all_blocks && !packed && !(tv && weights) && aligned(x, 16) && aligned(c, 16)) {
+    switch (dt) {  // the whole store, nothing to weigh: no need to look at the blocks
+      case DT_F32: n_partial = launch_norm_all<DT_F32>(layout, x, c, partial, st); break;
+      case DT_BF16: n_partial = launch_norm_all<DT_BF16>(layout, x, c, partial, st); break;
+      case DT_I32: n_partial = launch_norm_all<DT_I32>(layout, x, c, partial, st); break;
+      case DT_F32_TV: n_partial = launch_norm_all<DT_F32_TV>(layout, x, c, partial, st); break;
+      default: n_partial = launch_norm_all<DT_BF16_TV>(layout, x, c, partial, st); break;
+    }
+    finish(n_partial);
+    return launch_status();
+  }
   if (store && norm_out)
     n_partial = dispatch_recover<true, true>(dt, g, layout, x, c, idx, n_idx, n_blocks, pieces, vec, packed, partial, weights, st);
   else if (store)
