@@ -128,8 +128,9 @@ int scar_block_scores(const scar_layout* layout, const void* x, const void* c, v
  * matrix factorisation or LDA): between two checkpoints only those rows can have moved, so
  * rescoring them - and setting the score of a block to 0 when it is saved, which scoring it
  * after the commit does - keeps `scores` equal to what the full scan would give, at a
- * fraction of the traffic.  (An economy on top of the paper's protocol, which looks at every
- * parameter at every checkpoint.) */
+ * fraction of the traffic: the values are bit for bit those of scar_block_scores on the same
+ * data, for every store type.  (An economy on top of the paper's protocol, which looks at
+ * every parameter at every checkpoint.) */
 int scar_block_scores_rows(const scar_layout* layout, const void* x, const void* c,
                            const uint32_t* idx, uint32_t n_idx, void* scores, void* stream);
 
