@@ -189,6 +189,92 @@ __global__ __launch_bounds__(T, T / 128) void k_recover(char* __restrict__ x, co
   }
 }
 
+// The norm alone over a long list (nothing stored), with the result of k_recover<DT, G, 1024,
+// false, true, true> bit for bit - the norm fused into the recovery must equal the norm taken
+// beforehand - but with the loads of the score scan: a workgroup of 256 threads stands in for
+// one of 1,024, each wavefront for kVirtual of the wide kernel's wavefronts.  A lane asks for
+// the 16-byte steps of its kVirtual virtual lanes before it uses the first (4 loads per stream
+// in flight instead of 1), keeps one sum per virtual lane, reduces each virtual wavefront on
+// its own and leaves the 16 sums in the slots in the wide kernel's order.  Launched with that
+// kernel's grid, so the partial sums are the same ones.  (131,072 rows of 4 KiB: 240 -> 191 us
+// with the final sum; limiting the workgroups per compute unit, good for the scans, costs 40 %
+// here: every workgroup first waits for its index entries.)
+constexpr int kVirtual = 4;
+template <int DT, int G>
+__global__ __launch_bounds__(kWG) void k_norm_wide(const char* __restrict__ x, const char* __restrict__ c,
+                                                   const uint32_t* __restrict__ idx, uint32_t n_idx,
+                                                   uint64_t n_elems, uint32_t block_len,
+                                                   uint32_t n_blocks, uint32_t pieces, bool packed,
+                                                   typename Acc<DT>::type* __restrict__ partial,
+                                                   const float* __restrict__ weights) {
+  constexpr int T = kWG * kVirtual;  // threads of the kernel this one stands in for
+  constexpr int GPW = T / G;
+  constexpr int E = elem_bytes(DT);
+  constexpr int EPV = 16 / E;
+  using acc_t = typename Acc<DT>::type;
+  __shared__ acc_t slots[T / kWave];
+  const uint32_t wave = threadIdx.x / kWave, in_wave = threadIdx.x & (kWave - 1);
+  acc_t acc[kVirtual];
+#pragma unroll
+  for (int q = 0; q < kVirtual; ++q) acc[q] = 0;
+
+  for (uint32_t piece = blockIdx.y; piece < pieces; piece += gridDim.y) {
+    for (uint64_t i0 = (uint64_t)xcd_contiguous_block_id() * GPW; i0 < n_idx; i0 += (uint64_t)gridDim.x * GPW) {
+      const char* xb[kVirtual];
+      const char* cb[kVirtual];
+      uint32_t len[kVirtual], lane[kVirtual];
+      float w[kVirtual];
+      uint4 cv[kVirtual][1], xv[kVirtual][1];
+      bool on[kVirtual], has_step[kVirtual];
+#pragma unroll
+      for (int q = 0; q < kVirtual; ++q) {
+        const uint32_t vt = (wave * kVirtual + q) * kWave + in_wave;  // thread of the wide workgroup
+        lane[q] = vt & (G - 1);
+        const uint64_t i = i0 + vt / G;
+        on[q] = false, has_step[q] = false, w[q] = 1.f;
+        if (i >= n_idx) continue;
+        const uint32_t b = idx ? idx[i] : (uint32_t)i;
+        RowPiece rp;
+        if (!row_piece<E>(b, piece, pieces, n_blocks, n_elems, block_len, &rp)) continue;
+        on[q] = true;
+        xb[q] = x + rp.byte_off;
+        cb[q] = packed ? c + i * (uint64_t)block_len * E + rp.row_off : c + rp.byte_off;
+        len[q] = rp.len;
+        if constexpr (is_tv(DT))
+          if (weights) w[q] = weights[b];
+        has_step[q] = lane[q] < rp.len / EPV;
+        if (has_step[q]) {
+          cv[q][0] = load_stream((const uint4*)cb[q] + lane[q]);
+          xv[q][0] = load_stream((const uint4*)xb[q] + lane[q]);
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < kVirtual; ++q) {
+        if (!on[q]) continue;
+        // as k_recover adds: the step, then what a short last block has left - into the running
+        // sum, or (total variation) into the row's own sum, which counts with the row's weight
+        acc_t row = 0;
+        acc_t& into = is_tv(DT) ? row : acc[q];
+        if (has_step[q]) accumulate_vec<DT, 1>(into, cv[q], xv[q]);
+        for (uint32_t j = len[q] / EPV * EPV + lane[q]; j < len[q]; j += G) accumulate_elem<DT>(into, cb[q], xb[q], j);
+        if constexpr (is_tv(DT)) acc[q] += (double)w[q] * row;
+      }
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < kVirtual; ++q) {
+    const acc_t v = group_sum<kWave>(acc[q]);
+    if (in_wave == 0) slots[wave * kVirtual + q] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    acc_t total = slots[0];
+#pragma unroll
+    for (int v = 1; v < T / kWave; ++v) total += slots[v];
+    partial[blockIdx.y * gridDim.x + blockIdx.x] = total;
+  }
+}
+
 // The norm over the whole store with nothing stored (the perturbation a traditional full
 // recovery would cause, Appendix A.3): the sum does not depend on where the blocks begin, so
 // this is one flat two-stream reduction - kUnroll 16-byte loads per lane and stream in flight,
@@ -339,8 +425,21 @@ static uint32_t launch_recover(const scar_layout* l, void* x, const void* c, con
                                void* partial, const float* weights, hipStream_t st) {
   if (!vec)
     return launch_recover_t<DT, G, kWG, STORE, NORM, false>(l, x, c, idx, n_idx, n_blocks, pieces, packed, partial, weights, st);
-  if (((uint64_t)n_idx * pieces * G + kWG - 1) / kWG >= kWideFrom)
+  if (((uint64_t)n_idx * pieces * G + kWG - 1) / kWG >= kWideFrom) {
+    if constexpr (!STORE && NORM) {  // read-only: the same sums from a kernel with more loads in flight
+      static_assert(kWideWG == kWG * kVirtual, "k_norm_wide stands in for the wide kernel");
+      constexpr int GPW = kWideWG / G;
+      const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
+      const uint32_t grid = xcd_grid(need, kMaxNormGrid);
+      const uint32_t grid_y = piece_grid(pieces, grid, kMaxNormGrid);
+      hipLaunchKernelGGL((k_norm_wide<DT, G>), dim3(grid, grid_y), dim3(kWG),
+                         0, st, (const char*)x,
+                         (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, pieces, packed,
+                         (typename Acc<DT>::type*)partial, weights);
+      return grid * grid_y;
+    }
     return launch_recover_t<DT, G, kWideWG, STORE, NORM, true>(l, x, c, idx, n_idx, n_blocks, pieces, packed, partial, weights, st);
+  }
   return launch_recover_t<DT, G, kWG, STORE, NORM, true>(l, x, c, idx, n_idx, n_blocks, pieces, packed, partial, weights, st);
 }
 

@@ -173,8 +173,10 @@ def test_tv_cycle_at_the_benchmark_size():
         oracle.checkpoint_commit(F32, hx, hc, L, idx_host(idx))
         assert torch.equal(c, torch.from_numpy(hc).to(DEV))
         lost = lost_of(0)
+        pre = scar.read_norm(scar.tv_perturbation_norm(x, c, L, idx_dev(lost), ws, lengths))
         got = scar.read_norm(scar.tv_partial_recover(x, c, L, idx_dev(lost), ws, lengths))
         norm_close(got, oracle.tv_partial_recover(F32, hx, hc, L, lost, hw))
+        assert pre == got                                   # the norm alone, bit for bit
         assert torch.equal(x, torch.from_numpy(hx).to(DEV))
     finally:
         oracle.set_num_threads(1)
