@@ -91,7 +91,7 @@ inline uint32_t xcd_grid(uint64_t need, uint64_t cap) {
 // returns the dynamic LDS bytes for a launch of `grid` workgroups that each keep
 // `wg_bytes_in_flight` bytes of loads outstanding (0 = no limit: short launches, and
 // workgroups with so little in flight that eight of them are needed anyway).
-constexpr uint64_t kStreamFromGrid = 4096;
+constexpr uint64_t kStreamFromGrid = 16384;  // half a GiB of loads; below, no gain (6,104 workgroups: 4 % slower)
 constexpr uint64_t kStreamBytesPerCu = 86 * 1024;  // 32 KiB a workgroup -> 3, 24 -> 4, 16 -> 5
 constexpr size_t kLdsPerCu = 160 * 1024;
 inline size_t stream_lds_bytes(uint64_t grid, uint64_t wg_bytes_in_flight) {

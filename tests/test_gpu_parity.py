@@ -396,9 +396,9 @@ def test_cycle_replays_correctly_from_a_hip_graph():
     # The library enqueues only kernels (no allocation, no memset, no synchronisation), so a
     # whole cycle can be captured once and replayed.  Every replay - with the program's own
     # eager work and synchronisations in between - must give what the eager calls give.
-    # (2^24 elements: large enough for the launches that ask for unused LDS to limit the
+    # (2^26 elements: large enough for the launches that ask for unused LDS to limit the
     # workgroups per compute unit.)
-    w = wl.flat_like(n_elems=1 << 24)
+    w = wl.flat_like(n_elems=1 << 26)
     L, nb, k = w.block_len, w.n_blocks, w.k
     x, c = to_dev(w.x, w.dtype), to_dev(w.c, w.dtype)
     ws = scar.new_workspace(nb, DEV)
