@@ -102,6 +102,21 @@ inline size_t stream_lds_bytes(uint64_t grid, uint64_t wg_bytes_in_flight) {
   return kLdsPerCu / wgs - 1024;
 }
 
+// Rows per chunk of the run-of-rows score kernels: as many rows of `row_bytes` bytes as fit
+// `max_steps` 16-byte steps, rounded down so that every chunk starts on a 128-byte line, or
+// else on the largest power of two down to 16 bytes that the row length allows; 0 if not even
+// one such group of rows fits.
+inline uint32_t run_chunk_rows(uint64_t row_bytes, uint32_t max_steps) {
+  if (row_bytes == 0) return 0;
+  const uint64_t fit = (uint64_t)max_steps * 16 / row_bytes;
+  for (uint32_t align = 128; align >= 16; align /= 2) {
+    uint32_t m = align;  // rows * row_bytes must be a multiple of align
+    for (uint64_t v = row_bytes; m > 1 && v % 2 == 0; v /= 2) m /= 2;
+    if (fit >= m) return (uint32_t)(fit / m * m);
+  }
+  return 0;
+}
+
 // The copy kernels hand rows longer than kPieceBytes out in pieces of that size (grid y =
 // piece).  Grid size in y for rows cut into `pieces`: one slice per piece while
 // grid_x * grid_y stays within `cap` workgroups (and the 65,535 of the y dimension); slices

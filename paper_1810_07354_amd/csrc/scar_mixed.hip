@@ -207,18 +207,6 @@ __global__ __launch_bounds__(kWG) void k_mixed_scores_flat(const float* __restri
   }
 }
 
-// Rows per chunk of the run-of-rows kernel: as many as fit, rounded down so that chunks start
-// on 128-byte lines of x, or at least on 16-byte boundaries; 0 if not even that fits.
-static uint32_t mixed_flat_chunk_rows(uint32_t block_len) {
-  const uint32_t fit = kMixFlatUnits * kMixUnit / block_len;
-  for (uint32_t align = 32; align >= 4; align /= 2) {  // in elements of x
-    uint32_t m = align;
-    for (uint32_t v = block_len; m > 1 && v % 2 == 0; v /= 2) m /= 2;
-    if (fit >= m) return fit / m * m;
-  }
-  return 0;
-}
-
 // Rows longer than kMixPieceElems elements (4 KiB of x) are handed out in pieces of that
 // length, one per grid-y slice, like the rows of the other store types.
 constexpr uint32_t kMixPieceElems = kPieceBytes / 4;
@@ -350,9 +338,9 @@ int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, c
   const bool split = l->block_len % kMixUnit != 0;
   if (!idx && aligned(x, 16) && aligned(c, 8) && n_blocks >= kMixFlatMinRows && g <= 64 &&
       l->block_len <= (split ? kMixFlatSplitRowElems : kMixFlatRowElems) &&
-      mixed_flat_chunk_rows(l->block_len) > 0) {
+      run_chunk_rows((uint64_t)l->block_len * 4, kMixFlatUnits) > 0) {
     const uint32_t n_rows = (uint32_t)(l->n_elems / l->block_len);
-    const uint32_t chunk_rows = mixed_flat_chunk_rows(l->block_len);
+    const uint32_t chunk_rows = run_chunk_rows((uint64_t)l->block_len * 4, kMixFlatUnits);  // sized by the rows of x
     const uint32_t n_chunks = (n_rows + chunk_rows - 1) / chunk_rows;
     const uint32_t grid = xcd_grid(n_chunks, kScoreGridCap);
     // four workgroups per compute unit: 40 KiB of LDS each, part of it unused

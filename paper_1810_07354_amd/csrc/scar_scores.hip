@@ -325,18 +325,6 @@ __global__ __launch_bounds__(kWG) void k_block_scores_flat(const char* __restric
   }
 }
 
-// Rows per chunk: as many as fit kFlatVecs steps, rounded down so that chunks start on
-// 128-byte lines, or at least on 16-byte boundaries; 0 if not even that fits.
-static uint32_t flat_chunk_rows(uint64_t row_bytes) {
-  const uint32_t fit = (uint32_t)((uint64_t)kFlatVecs * 16 / row_bytes);
-  for (uint32_t align = 128; align >= 16; align /= 2) {
-    uint32_t m = align;  // rows * row_bytes must be a multiple of align
-    for (uint64_t v = row_bytes; m > 1 && v % 2 == 0; v /= 2) m /= 2;
-    if (fit >= m) return fit / m * m;
-  }
-  return 0;
-}
-
 // Row lengths the run-of-rows kernel takes: whole 16-byte steps from 32 to kFlatRowBytes
 // bytes (longer ones do as well with a group per row); any other length up to
 // kFlatSplitRowBytes whose chunks can start on 16-byte boundaries.  g is the group size the
@@ -345,7 +333,7 @@ static uint32_t flat_chunk_rows(uint64_t row_bytes) {
 static bool flat_rows_fit(bool tv, uint64_t row_bytes, int g) {
   if (g > 64 || (uint64_t)g * kUnroll * 16 < row_bytes) return false;
   if (row_bytes % 16 == 0) return row_bytes >= 32 && row_bytes <= kFlatRowBytes;
-  return row_bytes <= kFlatSplitRowBytes && (!tv || row_bytes >= 32) && flat_chunk_rows(row_bytes) > 0;
+  return row_bytes <= kFlatSplitRowBytes && (!tv || row_bytes >= 32) && run_chunk_rows(row_bytes, kFlatVecs) > 0;
 }
 
 template <int DT, int G, bool SPLIT>
@@ -353,7 +341,7 @@ static void launch_scores_flat(const scar_layout* l, const void* x, const void* 
                                const float* weights, hipStream_t st) {
   constexpr int E = elem_bytes(DT);
   const uint32_t n_rows = (uint32_t)(l->n_elems / l->block_len);
-  const uint32_t chunk_rows = flat_chunk_rows((uint64_t)l->block_len * E);
+  const uint32_t chunk_rows = run_chunk_rows((uint64_t)l->block_len * E, kFlatVecs);
   const uint32_t n_chunks = (n_rows + chunk_rows - 1) / chunk_rows;
   // five workgroups per compute unit (32 KiB of LDS each, part of it unused) are the best
   // measured: 2.7 M rows of 400 bytes 334 us with eight, 314 us with five or four
