@@ -27,8 +27,12 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call
  *     validates its arguments on the host, enqueues its kernels on `stream` and returns;
  *     it never synchronises.  Results are in device memory once the stream reaches them.
- *   - Return value: SCAR_OK (0) or a negative scar_status.  On an error nothing has been
- *     enqueued.  Nothing throws or aborts.
+ *   - Return value: SCAR_OK (0) or a negative scar_status.  SCAR_ERR_INVALID_ARG,
+ *     SCAR_ERR_WORKSPACE and SCAR_ERR_UNSUPPORTED are found on the host before anything is
+ *     enqueued.  SCAR_ERR_DEVICE is the status HIP returned for one of this call's own
+ *     launches (the thread's HIP error state is neither read nor cleared, so an error left by
+ *     the caller's earlier work is not reported here); launches of the call that came before
+ *     the failed one have been enqueued, none after it.  Nothing throws or aborts.
  *   - x and c must not overlap.  x, c and staging must be aligned to the element size;
  *     scores / out_idx / idx to their element type; workspace to 256 bytes.  When x and c
  *     are 16-byte aligned and block_len * element size is a multiple of 16 the kernels
@@ -78,7 +82,11 @@ typedef enum {
   SCAR_ERR_INVALID_ARG = -1, /* NULL where data is required, block_len == 0, bad enum,
                                 k > n_blocks, n_blocks > SCAR_MAX_BLOCKS, misaligned pointer */
   SCAR_ERR_WORKSPACE = -2,   /* workspace NULL, misaligned or smaller than scar_workspace_bytes */
-  SCAR_ERR_DEVICE = -3       /* HIP reported an error when a kernel was enqueued */
+  SCAR_ERR_DEVICE = -3,      /* HIP reported an error when a kernel was enqueued */
+  /* -4 is SCAR_ERR_IO of scar_store.h */
+  SCAR_ERR_UNSUPPORTED = -5  /* every argument is valid, but this combination of store type
+                                and call is not built (e.g. the total-variation calls on
+                                SCAR_I32 or SCAR_F32_BF16C stores) */
 } scar_status;
 
 #define SCAR_MAX_BLOCKS 0x7fffffffu
@@ -134,9 +142,9 @@ int scar_block_scores(const scar_layout* layout, const void* x, const void* c, v
 int scar_block_scores_rows(const scar_layout* layout, const void* x, const void* c,
                            const uint32_t* idx, uint32_t n_idx, void* scores, void* stream);
 
-/* Checkpoint step 3 (Section 4.3): the k blocks with the largest scores - "the
- * parameters which have changed the most since they were previously saved"
- * (Section 4.2).  The order is total: larger score first, equal scores to the lower
+/* Checkpoint step 3 (Section 4.3): the k blocks with the largest scores, i.e. those that
+ * moved farthest from their last saved value - the priority rule of Section 4.2.  The order
+ * is total: larger score first, equal scores to the lower
  * block index; NaN ranks above every number and -0 equals +0.  out_idx receives the k
  * chosen block indices in ascending order.  scores is not modified.
  *   score_type: SCAR_SCORE_F32 (float scores) or SCAR_SCORE_I64 (int64_t scores). */
@@ -198,7 +206,8 @@ int scar_select_random(uint32_t n_blocks, uint32_t k, uint64_t seed, uint64_t dr
  * parameter, so blocks differ in size by orders of magnitude.  Block b is the element
  * range [offsets[b], offsets[b+1]); empty blocks are allowed (score 0).
  * The calls below mirror the five above (scar_select_topk, _round and _random work on
- * any score array and serve both layouts).  There is no staging output.
+ * any score array and serve both layouts).  There is no staging output.  SCAR_F32_BF16C
+ * stores have fixed-length blocks only: SCAR_ERR_UNSUPPORTED here.
  * All of them need a workspace of scar_var_workspace_bytes(n_blocks) bytes. */
 typedef struct {
   int32_t dtype;           /* scar_dtype */
@@ -238,7 +247,7 @@ int scar_var_perturbation_norm(const scar_var_layout* layout, const void* x, con
  * norms), not a root of squares.  The three calls below are scar_block_scores,
  * scar_partial_recover and scar_perturbation_norm in that norm; selection and commit do not
  * depend on the norm and are shared.
- *   layout->dtype: SCAR_F32 or SCAR_BF16 (anything else: SCAR_ERR_INVALID_ARG).
+ *   layout->dtype: SCAR_F32 or SCAR_BF16 (other store types: SCAR_ERR_UNSUPPORTED).
  *   weights: float[n_blocks] in DEVICE memory (document lengths, > 0 by the caller's care),
  *            or NULL for w_b = 1 (plain total variation).
  *   scores:  float[n_blocks].

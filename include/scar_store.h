@@ -1,9 +1,9 @@
 /*
- * scar_store.h - the persistent-storage leg of SCAR's checkpoint protocol (Section 4.3):
- * "each PS node updates its in-memory cache, and saves those parameters to the shared
- * persistent storage ... output to the shared persistent storage happens asynchronously in
- * the background", and, after a failure, the lost parameters are re-loaded "from the current
- * running checkpoint in shared persistent storage".
+ * scar_store.h - the persistent-storage leg of SCAR's checkpoint protocol (Section 4.3,
+ * checkpoint step 4 and recovery step 2): the blocks chosen for a partial checkpoint go to
+ * the in-memory checkpoint first and from there, in the background and off the critical
+ * path, to persistent storage; after a failure the lost blocks are read back from the
+ * running checkpoint that storage holds.
  *
  * A store file holds the running checkpoint of one parameter store with fixed-length
  * blocks: a 4,096-byte header, then block b at byte 4096 + b * row_bytes, where row_bytes =

@@ -19,6 +19,7 @@ extern "C" const char* scar_strerror(int status) {
     case SCAR_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case SCAR_ERR_DEVICE: return "HIP reported an error while enqueueing";
     case -4: return "store file could not be created, opened, read or written";
+    case SCAR_ERR_UNSUPPORTED: return "valid arguments, but this store type is not built for this call";
     default: return "unknown status";
   }
 }

@@ -5,6 +5,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <utility>
+
 #include "../../include/scar.h"
 
 namespace scar {
@@ -60,9 +63,9 @@ constexpr size_t kWsTileOffset = kWsNormOffset + kWsNormBytes;
 constexpr uint32_t kTileKeys = 2048;   // keys per compaction tile
 constexpr uint32_t kMaxNormGrid = kWsNormBytes / 8;
 
-inline uint64_t n_tiles_of(uint64_t n) { return (n + kTileKeys - 1) / kTileKeys; }
+constexpr uint64_t n_tiles_of(uint64_t n) { return (n + kTileKeys - 1) / kTileKeys; }
 
-inline size_t workspace_bytes_for(uint64_t n_blocks) {
+constexpr size_t workspace_bytes_for(uint64_t n_blocks) {
   return kWsTileOffset + ((n_tiles_of(n_blocks) * 8 + 255) / 256) * 256 + 256;
 }
 
@@ -182,6 +185,37 @@ inline size_t var_workspace_bytes_for(uint64_t n_blocks) {
   return var_mask_offset(n_blocks) + ((n_blocks + 255) / 256) * 256 + 256;
 }
 
-inline int launch_status() { return hipGetLastError() == hipSuccess ? SCAR_OK : SCAR_ERR_DEVICE; }
+// ---- enqueueing kernels ---------------------------------------------------------------
+// Every kernel goes out through launch(), which keeps the status that HIP returns for that
+// very launch: the thread's "last error" state is neither read nor cleared, so a failure
+// left behind by the caller's own earlier HIP work is not mistaken for this call's, and
+// stays where the caller can still find it.  After a launch has failed, the rest of the
+// entry point's launches are skipped; launch_status() ends the entry point: it returns what
+// happened and clears the note for the thread's next call.
+inline hipError_t& launch_error() {
+  static thread_local hipError_t err = hipSuccess;
+  return err;
+}
+
+template <typename... KArgs, size_t... I>
+inline hipError_t launch_packed(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t st,
+                                std::tuple<KArgs...>& vals, std::index_sequence<I...>) {
+  void* ptrs[sizeof...(KArgs) ? sizeof...(KArgs) : 1] = {(void*)&std::get<I>(vals)...};
+  return hipLaunchKernel((const void*)kernel, grid, block, ptrs, lds, st);
+}
+
+template <typename... KArgs, typename... Args>
+inline void launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args) {
+  static_assert(sizeof...(KArgs) == sizeof...(Args), "one argument per kernel parameter");
+  if (launch_error() != hipSuccess) return;
+  std::tuple<KArgs...> vals{static_cast<KArgs>(args)...};
+  launch_error() = launch_packed(kernel, grid, block, lds, st, vals, std::index_sequence_for<KArgs...>{});
+}
+
+inline int launch_status() {
+  const hipError_t err = launch_error();
+  launch_error() = hipSuccess;
+  return err == hipSuccess ? SCAR_OK : SCAR_ERR_DEVICE;
+}
 
 }  // namespace scar

@@ -349,11 +349,11 @@ int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, c
 #define FLAT(G)                                                                                        \
   case G:                                                                                              \
     if (split)                                                                                         \
-      hipLaunchKernelGGL((k_mixed_scores_flat<G, true>), dim3(grid), dim3(kWG), lds, st,               \
+      launch((k_mixed_scores_flat<G, true>), dim3(grid), dim3(kWG), lds, st,               \
                          (const float*)x, (const uint16_t*)c, (float*)scores, l->block_len, n_rows,    \
                          chunk_rows, n_chunks);                                                        \
     else                                                                                               \
-      hipLaunchKernelGGL((k_mixed_scores_flat<G, false>), dim3(grid), dim3(kWG), lds, st,              \
+      launch((k_mixed_scores_flat<G, false>), dim3(grid), dim3(kWG), lds, st,              \
                          (const float*)x, (const uint16_t*)c, (float*)scores, l->block_len, n_rows,    \
                          chunk_rows, n_chunks);                                                        \
     break;
@@ -376,11 +376,11 @@ int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, c
     const uint64_t group_units = units < (uint64_t)G * kMixU ? units : (uint64_t)G * kMixU;          \
     const size_t lds = stream_lds_bytes(need, (vec ? 24 : 6) * group_units * GPW);                   \
     if (idx)                                                                                         \
-      hipLaunchKernelGGL((k_mixed_scores<G, true>), dim3(grid), dim3(kWG), lds, st, (const float*)x, \
+      launch((k_mixed_scores<G, true>), dim3(grid), dim3(kWG), lds, st, (const float*)x, \
                          (const uint16_t*)c, (float*)scores, l->n_elems, l->block_len, n_blocks,     \
                          vec, idx, n_idx);                                                           \
     else                                                                                             \
-      hipLaunchKernelGGL((k_mixed_scores<G, false>), dim3(grid), dim3(kWG), lds, st,                 \
+      launch((k_mixed_scores<G, false>), dim3(grid), dim3(kWG), lds, st,                 \
                          (const float*)x, (const uint16_t*)c, (float*)scores, l->n_elems,            \
                          l->block_len, n_blocks, vec, idx, n_idx);                                   \
   }
@@ -411,7 +411,7 @@ int mixed_commit(const scar_layout* l, uint32_t n_blocks, const void* x, void* c
   {                                                                                                 \
     constexpr int GPW = (G == 256) ? 1 : kWG / G;                                                   \
     const uint32_t grid = xcd_grid(((uint64_t)n_idx + GPW - 1) / GPW, kCopyGridCap);                \
-    hipLaunchKernelGGL((k_mixed_commit<G>), dim3(grid, piece_grid(pieces, grid, kCopyGridCap)),     \
+    launch((k_mixed_commit<G>), dim3(grid, piece_grid(pieces, grid, kCopyGridCap)),     \
                        dim3(kWG), 0, st, (const float*)x, (uint16_t*)c, idx, n_idx,                 \
                        (uint16_t*)staging, l->n_elems, l->block_len, n_blocks, pieces, vec, vec_st); \
   }
@@ -430,7 +430,7 @@ static uint32_t launch_mixed_recover(int g, const scar_layout* l, uint32_t n_blo
   {                                                                                                   \
     grid = xcd_grid(((uint64_t)n_idx + (T / G) - 1) / (T / G), kMaxNormGrid);                         \
     grid_y = piece_grid(pieces, grid, kMaxNormGrid);                                                  \
-    hipLaunchKernelGGL((k_mixed_recover<G, T, STORE, NORM>), dim3(grid, grid_y), dim3(T), 0, st,      \
+    launch((k_mixed_recover<G, T, STORE, NORM>), dim3(grid, grid_y), dim3(T), 0, st,      \
                        (float*)x, (const uint16_t*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, \
                        pieces, vec, packed, (double*)partial);                                        \
   }
@@ -492,7 +492,7 @@ int mixed_recover_or_norm(bool store, bool packed, const scar_layout* l, uint32_
   if (!store && norm_out && !idx && !packed && aligned(x, 16) && aligned(c, 8)) {  // the whole store
     const uint64_t chunks = (l->n_elems / kMixUnit + kWG * kMixU - 1) / (kWG * kMixU);
     const uint32_t grid = xcd_grid(chunks ? chunks : 1, kMaxNormGrid);
-    hipLaunchKernelGGL(k_mixed_norm_all, dim3(grid), dim3(kWG), stream_lds_bytes(grid, 24 * kWG * kMixU), st,
+    launch(k_mixed_norm_all, dim3(grid), dim3(kWG), stream_lds_bytes(grid, 24 * kWG * kMixU), st,
                        (const float*)x, (const uint16_t*)c, l->n_elems, (double*)partial);
     launch_finish(l->dtype, partial, grid, norm_out, st);
     return launch_status();

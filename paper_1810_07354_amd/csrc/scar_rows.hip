@@ -319,7 +319,7 @@ static uint32_t launch_norm_all(const scar_layout* l, const void* x, const void*
   const uint64_t nvec = l->n_elems / (16 / elem_bytes(DT));
   const uint64_t chunks = (nvec + kWG * kUnroll - 1) / (kWG * kUnroll);
   const uint32_t grid = xcd_grid(chunks ? chunks : 1, kMaxNormGrid);
-  hipLaunchKernelGGL((k_norm_all<DT>), dim3(grid), dim3(kWG), stream_lds_bytes(grid, 2 * 16 * kWG * kUnroll), st,
+  launch((k_norm_all<DT>), dim3(grid), dim3(kWG), stream_lds_bytes(grid, 2 * 16 * kWG * kUnroll), st,
                      (const char*)x, (const char*)c, l->n_elems, (typename Acc<DT>::type*)partial);
   return grid;
 }
@@ -371,7 +371,7 @@ static void launch_commit(const scar_layout* l, const void* x, void* c, const ui
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
   const uint32_t grid = xcd_grid(need, kCopyGridCap);
-  hipLaunchKernelGGL((k_commit<G, W>), dim3(grid, piece_grid(pieces, grid, kCopyGridCap)), dim3(kWG), 0, st, (const char*)x, (char*)c, idx,
+  launch((k_commit<G, W>), dim3(grid, piece_grid(pieces, grid, kCopyGridCap)), dim3(kWG), 0, st, (const char*)x, (char*)c, idx,
                      n_idx, (char*)staging, l->n_elems, l->block_len, n_blocks, pieces, vec, vec_st);
 }
 
@@ -413,7 +413,7 @@ static uint32_t launch_recover_t(const scar_layout* l, void* x, const void* c, c
   const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
   const uint32_t grid = xcd_grid(need, kMaxNormGrid);
   const uint32_t grid_y = piece_grid(pieces, grid, kMaxNormGrid);
-  hipLaunchKernelGGL((k_recover<DT, G, T, STORE, NORM, VEC>), dim3(grid, grid_y), dim3(T), 0, st, (char*)x,
+  launch((k_recover<DT, G, T, STORE, NORM, VEC>), dim3(grid, grid_y), dim3(T), 0, st, (char*)x,
                      (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, pieces, packed,
                      (typename Acc<DT>::type*)partial, weights);
   return grid * grid_y;
@@ -432,7 +432,7 @@ static uint32_t launch_recover(const scar_layout* l, void* x, const void* c, con
       const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
       const uint32_t grid = xcd_grid(need, kMaxNormGrid);
       const uint32_t grid_y = piece_grid(pieces, grid, kMaxNormGrid);
-      hipLaunchKernelGGL((k_norm_wide<DT, G>), dim3(grid, grid_y), dim3(kWG),
+      launch((k_norm_wide<DT, G>), dim3(grid, grid_y), dim3(kWG),
                          0, st, (const char*)x,
                          (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, pieces, packed,
                          (typename Acc<DT>::type*)partial, weights);
@@ -483,17 +483,17 @@ static uint32_t dispatch_recover(int dt, int g, const scar_layout* l, void* x, c
 }
 
 static void launch_finish_tv(const void* partial, uint32_t n_partial, scar_norm* out, hipStream_t st) {
-  hipLaunchKernelGGL((k_norm_finish<DT_F32_TV>), dim3(1), dim3(kFinishThreads), 0, st, (const double*)partial,
+  launch((k_norm_finish<DT_F32_TV>), dim3(1), dim3(kFinishThreads), 0, st, (const double*)partial,
                      n_partial, out);
 }
 
 void launch_finish(int32_t dtype, const void* partial, uint32_t n_partial, scar_norm* out,
                           hipStream_t st) {
   if (dtype == SCAR_I32)
-    hipLaunchKernelGGL((k_norm_finish<DT_I32>), dim3(1), dim3(kFinishThreads), 0, st,
+    launch((k_norm_finish<DT_I32>), dim3(1), dim3(kFinishThreads), 0, st,
                        (const unsigned long long*)partial, n_partial, out);
   else
-    hipLaunchKernelGGL((k_norm_finish<DT_F32>), dim3(1), dim3(kFinishThreads), 0, st, (const double*)partial,
+    launch((k_norm_finish<DT_F32>), dim3(1), dim3(kFinishThreads), 0, st, (const double*)partial,
                        n_partial, out);
 }
 
@@ -505,7 +505,7 @@ static int recover_or_norm(bool store, bool packed, bool tv, const scar_layout* 
                            void* stream) {
   const uint64_t nb = layout_blocks(layout);
   if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
-  if (tv && layout->dtype != SCAR_F32 && layout->dtype != SCAR_BF16) return SCAR_ERR_INVALID_ARG;
+  if (tv && layout->dtype != SCAR_F32 && layout->dtype != SCAR_BF16) return SCAR_ERR_UNSUPPORTED;
   const int eb = host_elem_bytes(layout->dtype);
   if (all_blocks) n_idx = (uint32_t)nb;
   if (norm_out) {

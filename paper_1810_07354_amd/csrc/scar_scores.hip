@@ -122,7 +122,7 @@ static bool launch_scores_tiny(const scar_layout* l, const void* x, const void* 
   const uint64_t need = (nvec + (uint64_t)kWG * kUnroll - 1) / ((uint64_t)kWG * kUnroll);
   const uint32_t grid = xcd_grid(need ? need : 1, kScoreGridCap);
 #define SCAR_TINY(EPR)                                                                                  \
-  hipLaunchKernelGGL((k_block_scores_tiny<DT, EPR>), dim3(grid), dim3(kWG), 0, st, (const char*)x,     \
+  launch((k_block_scores_tiny<DT, EPR>), dim3(grid), dim3(kWG), 0, st, (const char*)x,     \
                      (const char*)c, scores, l->n_elems)
   switch (l->block_len * E) {
     case 2: if constexpr (E == 2) { SCAR_TINY(1); return true; } return false;
@@ -145,7 +145,7 @@ static void launch_scores(const scar_layout* l, const void* x, const void* c, vo
   const uint64_t group_vecs = row_vecs < (uint64_t)G * kUnroll ? row_vecs : (uint64_t)G * kUnroll;
   const size_t lds = stream_lds_bytes(need, 2 * 16 * group_vecs * GPW);
 #define SCAR_LAUNCH(VEC, LISTED)                                                                            \
-  hipLaunchKernelGGL((k_block_scores<DT, G, VEC, LISTED>), dim3(grid), dim3(kWG), lds, st, (const char*)x, \
+  launch((k_block_scores<DT, G, VEC, LISTED>), dim3(grid), dim3(kWG), lds, st, (const char*)x, \
                      (const char*)c, scores, l->n_elems, l->block_len, n_blocks, weights, idx, n_idx)
   if (idx) {
     if (vec)
@@ -348,7 +348,7 @@ static void launch_scores_flat(const scar_layout* l, const void* x, const void* 
   const size_t used = kFlatVecs * sizeof(typename StepSum<DT>::type) + (is_tv(DT) ? kFlatVecs * 2 : 0) +
                       (SPLIT ? kFlatVecs * 16 / E * sizeof(typename ElemTerm<DT>::type) : 0) + 256;
   const size_t lds = used < 32 * 1024 ? 32 * 1024 - used : 0;
-  hipLaunchKernelGGL((k_block_scores_flat<DT, G, SPLIT>), dim3(xcd_grid(n_chunks, kScoreGridCap)), dim3(kWG),
+  launch((k_block_scores_flat<DT, G, SPLIT>), dim3(xcd_grid(n_chunks, kScoreGridCap)), dim3(kWG),
                      lds, st, (const char*)x, (const char*)c, scores, l->block_len, n_rows, chunk_rows,
                      n_chunks, weights);
   const uint64_t done = (uint64_t)n_rows * l->block_len;
@@ -410,7 +410,7 @@ static int block_scores(bool tv, bool listed, const scar_layout* layout, const v
                         void* stream) {
   const uint64_t nb = layout_blocks(layout);
   if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
-  if (tv && layout->dtype != SCAR_F32 && layout->dtype != SCAR_BF16) return SCAR_ERR_INVALID_ARG;
+  if (tv && layout->dtype != SCAR_F32 && layout->dtype != SCAR_BF16) return SCAR_ERR_UNSUPPORTED;
   if (nb == 0 || (listed && n_idx == 0)) return SCAR_OK;
   if (listed && (!idx || !aligned(idx, 4))) return SCAR_ERR_INVALID_ARG;
   if (!listed) idx = nullptr;

@@ -472,15 +472,15 @@ static void run_compaction(const KeyArgs src, uint32_t n, int passes, SelectWs* 
                            uint32_t* out_count, hipStream_t st) {
   const uint32_t n_tiles = (uint32_t)n_tiles_of(n);
   const uint32_t tgrid = n_tiles < kTileGridCap ? n_tiles : kTileGridCap;
-  hipLaunchKernelGGL((k_compact_count<SRC>), dim3(tgrid), dim3(kWG), 0, st, src, n, n_tiles, passes,
+  launch((k_compact_count<SRC>), dim3(tgrid), dim3(kWG), 0, st, src, n, n_tiles, passes,
                      ws, tiles);
   if (n_tiles <= kSelfScanTiles) {
-    hipLaunchKernelGGL((k_compact_write<SRC, false>), dim3(tgrid), dim3(kWG), 0, st, src, n, n_tiles,
+    launch((k_compact_write<SRC, false>), dim3(tgrid), dim3(kWG), 0, st, src, n, n_tiles,
                        passes, (const SelectWs*)ws, (const unsigned long long*)tiles, out_idx, out_cap,
                        out_count);
   } else {
-    hipLaunchKernelGGL(k_compact_scan, dim3(1), dim3(kWG), 0, st, tiles, n_tiles, out_count);
-    hipLaunchKernelGGL((k_compact_write<SRC, true>), dim3(tgrid), dim3(kWG), 0, st, src, n, n_tiles,
+    launch(k_compact_scan, dim3(1), dim3(kWG), 0, st, tiles, n_tiles, out_count);
+    launch((k_compact_write<SRC, true>), dim3(tgrid), dim3(kWG), 0, st, src, n, n_tiles,
                        passes, (const SelectWs*)ws, (const unsigned long long*)tiles, out_idx, out_cap,
                        (uint32_t*)nullptr);
   }
@@ -491,14 +491,14 @@ static void run_select(const KeyArgs scores, uint32_t n, uint32_t k, uint32_t* o
                        hipStream_t st) {
   if (n <= kSmallSelect) {
     if (n <= 8 * kSmallWG)
-      hipLaunchKernelGGL((k_select_small<SRC, 8>), dim3(1), dim3(kSmallWG), 0, st, scores, n, k, out_idx);
+      launch((k_select_small<SRC, 8>), dim3(1), dim3(kSmallWG), 0, st, scores, n, k, out_idx);
     else
-      hipLaunchKernelGGL((k_select_small<SRC, 16>), dim3(1), dim3(kSmallWG), 0, st, scores, n, k, out_idx);
+      launch((k_select_small<SRC, 16>), dim3(1), dim3(kSmallWG), 0, st, scores, n, k, out_idx);
     return;
   }
   SelectWs* ws = (SelectWs*)workspace;
   unsigned long long* tiles = (unsigned long long*)((char*)workspace + kWsTileOffset);
-  hipLaunchKernelGGL(k_select_clear, dim3(1), dim3(kWG), 0, st, ws, k);
+  launch(k_select_clear, dim3(1), dim3(kWG), 0, st, ws, k);
   const uint32_t n_htiles = (uint32_t)(((uint64_t)n + kHistTileKeys - 1) / kHistTileKeys);
   // Every workgroup ends a pass with one global add per non-empty bin, so beyond a few
   // hundred workgroups more of them only add flush traffic: an eighth of the tiles, between
@@ -508,7 +508,7 @@ static void run_select(const KeyArgs scores, uint32_t n, uint32_t k, uint32_t* o
   hgrid = hgrid < 256 ? 256 : (hgrid > 2048 ? 2048 : hgrid);
   if (hgrid > n_htiles) hgrid = n_htiles;
   for (int p = 0; p < Key<SRC>::passes; ++p)
-    hipLaunchKernelGGL((k_select_hist<SRC>), dim3(hgrid), dim3(kWG), 0, st, scores, n, n_htiles, p, ws);
+    launch((k_select_hist<SRC>), dim3(hgrid), dim3(kWG), 0, st, scores, n, n_htiles, p, ws);
   run_compaction<SRC>(scores, n, Key<SRC>::passes, ws, tiles, out_idx, k, nullptr, st);
 }
 
@@ -538,7 +538,7 @@ extern "C" int scar_select_topk(int32_t score_type, const void* scores, uint32_t
   if (rc) return rc;
   if (k == n_blocks) {  // a full checkpoint: every block, whatever the scores
     const uint32_t grid = (k + kWG - 1) / kWG < 4096 ? (k + kWG - 1) / kWG : 4096;
-    hipLaunchKernelGGL(k_select_round, dim3(grid), dim3(kWG), 0, (hipStream_t)stream, n_blocks, k, 0u, out_idx);
+    launch(k_select_round, dim3(grid), dim3(kWG), 0, (hipStream_t)stream, n_blocks, k, 0u, out_idx);
     return launch_status();
   }
   if (score_type == SCAR_SCORE_F32)
@@ -558,7 +558,7 @@ extern "C" int scar_mask_to_indices(const uint8_t* mask, uint32_t n_blocks, uint
   hipStream_t st = (hipStream_t)stream;
   unsigned long long* tiles = (unsigned long long*)((char*)workspace + kWsTileOffset);
   if (n_blocks == 0)  // nothing to scan: the one-workgroup scan of zero tiles writes *out_count = 0
-    hipLaunchKernelGGL(k_compact_scan, dim3(1), dim3(kWG), 0, st, tiles, 0u, out_count);
+    launch(k_compact_scan, dim3(1), dim3(kWG), 0, st, tiles, 0u, out_count);
   else
     run_compaction<SRC_MASK>(KeyArgs{mask, 0, 0}, n_blocks, 0, (SelectWs*)workspace, tiles, out_idx, n_blocks,
                              out_count, st);
@@ -571,7 +571,7 @@ extern "C" int scar_select_round(uint32_t n_blocks, uint32_t k, uint64_t cursor,
   if (k == 0) return SCAR_OK;
   if (!out_idx || !aligned(out_idx, 4)) return SCAR_ERR_INVALID_ARG;
   const uint32_t grid = (k + kWG - 1) / kWG < 4096 ? (k + kWG - 1) / kWG : 4096;
-  hipLaunchKernelGGL(k_select_round, dim3(grid), dim3(kWG), 0, (hipStream_t)stream, n_blocks, k,
+  launch(k_select_round, dim3(grid), dim3(kWG), 0, (hipStream_t)stream, n_blocks, k,
                      (uint32_t)(cursor % n_blocks), out_idx);
   return launch_status();
 }

@@ -228,6 +228,9 @@ extern "C" int scar_store_save_async(scar_store* s, const void* staging, const u
   bool ok = hipMemcpyAsync(sl.idx, idx, (size_t)n_idx * 4, hipMemcpyDeviceToHost, st) == hipSuccess;
   ok = ok && hipMemcpyAsync(sl.rows, staging, (size_t)n_idx * s->row_bytes, hipMemcpyDeviceToHost, st) == hipSuccess;
   ok = ok && hipEventRecord(sl.copied, st) == hipSuccess;
+  // A copy that was enqueued before a later step failed may still be writing into the pinned
+  // buffer: the slot is handed back only once the stream has passed it.
+  if (!ok) (void)hipStreamSynchronize(st);
   std::lock_guard<std::mutex> lock(s->mu);
   if (!ok) {
     sl.busy = false;

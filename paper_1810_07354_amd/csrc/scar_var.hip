@@ -266,13 +266,13 @@ static void launch_walk(const scar_var_layout* l, const void* x, const void* c, 
   uint8_t* any = (uint8_t*)workspace + kVarPlanAnyOffset;
   void* partial = (char*)workspace + kVarPartialOffset;
   if (!planned)
-    hipLaunchKernelGGL(k_var_plan, dim3((g.n_wg + kWG - 1) / kWG), dim3(kWG), 0, st, l->offsets, l->n_blocks,
+    launch(k_var_plan, dim3((g.n_wg + kWG - 1) / kWG), dim3(kWG), 0, st, l->offsets, l->n_blocks,
                        l->n_elems, g.range_elems, g.n_wg, mask, first, any);
   // the score walk reads everything and keeps kUnroll 16-byte steps per lane and stream in flight
   uint64_t in_flight = 2 * g.range_elems * elem_bytes(DT);
   if (in_flight > 2 * 16 * kWG * kUnroll) in_flight = 2 * 16 * kWG * kUnroll;
   const size_t lds = (COPY == COPY_NONE && PER_BLOCK) ? stream_lds_bytes(g.n_wg, in_flight) : 0;
-  hipLaunchKernelGGL((k_var_walk<DT, ACC, COPY, PER_BLOCK>), dim3(xcd_grid(g.n_wg, kVarMaxGridCopy)), dim3(kWG),
+  launch((k_var_walk<DT, ACC, COPY, PER_BLOCK>), dim3(xcd_grid(g.n_wg, kVarMaxGridCopy)), dim3(kWG),
                      lds, st, (char*)const_cast<void*>(x), (char*)const_cast<void*>(c), l->offsets,
                      l->n_blocks, l->n_elems, g.range_elems, g.n_wg, mask, (const uint32_t*)first,
                      (const uint8_t*)any, (typename Acc<DT>::type*)partial, base_aligned);
@@ -294,11 +294,11 @@ static void launch_scores_finish(const scar_var_layout* l, const void* workspace
   using acc_t = typename Acc<DT>::type;
   const void* partial = (const char*)workspace + kVarPartialOffset;
   if (l->n_blocks <= 16384) {  // few blocks, possibly huge: a whole workgroup adds each one's slots
-    hipLaunchKernelGGL((k_var_scores_finish<DT, 1024, 1024>), dim3(l->n_blocks), dim3(1024), 0, st,
+    launch((k_var_scores_finish<DT, 1024, 1024>), dim3(l->n_blocks), dim3(1024), 0, st,
                        (const acc_t*)partial, l->offsets, l->n_blocks, l->n_elems, g.range_elems, scores);
   } else {
     const uint64_t need = ((uint64_t)l->n_blocks + 3) / 4;
-    hipLaunchKernelGGL((k_var_scores_finish<DT, kWave, kWG>), dim3((uint32_t)(need < 65536 ? need : 65536)),
+    launch((k_var_scores_finish<DT, kWave, kWG>), dim3((uint32_t)(need < 65536 ? need : 65536)),
                        dim3(kWG), 0, st, (const acc_t*)partial, l->offsets, l->n_blocks, l->n_elems,
                        g.range_elems, scores);
   }
@@ -310,16 +310,16 @@ static const uint8_t* mark_blocks(const scar_var_layout* l, const uint32_t* idx,
                                   void* workspace, const VarGeometry& g, bool* planned, hipStream_t st) {
   uint8_t* mask = (uint8_t*)workspace + var_mask_offset(l->n_blocks);
   if (g.n_wg <= kPrepareMaxRanges && l->n_blocks <= kPrepareMaxBlocks) {
-    hipLaunchKernelGGL(k_var_prepare, dim3(1), dim3(kPrepareThreads), 0, st, l->offsets, l->n_blocks,
+    launch(k_var_prepare, dim3(1), dim3(kPrepareThreads), 0, st, l->offsets, l->n_blocks,
                        l->n_elems, g.range_elems, g.n_wg, mask, idx, n_idx, (uint32_t*)workspace,
                        (uint8_t*)workspace + kVarPlanAnyOffset);
     *planned = true;
     return mask;
   }
   const uint32_t cg = (l->n_blocks + kWG * 16 - 1) / (kWG * 16);
-  hipLaunchKernelGGL(k_var_mask_clear, dim3(cg < 4096 ? cg : 4096), dim3(kWG), 0, st, mask, l->n_blocks);
+  launch(k_var_mask_clear, dim3(cg < 4096 ? cg : 4096), dim3(kWG), 0, st, mask, l->n_blocks);
   const uint32_t sg = (n_idx + kWG - 1) / kWG;
-  hipLaunchKernelGGL(k_var_mask_set, dim3(sg < 4096 ? sg : 4096), dim3(kWG), 0, st, mask, l->n_blocks, idx,
+  launch(k_var_mask_set, dim3(sg < 4096 ? sg : 4096), dim3(kWG), 0, st, mask, l->n_blocks, idx,
                      n_idx);
   *planned = false;
   return mask;
@@ -329,6 +329,7 @@ static const uint8_t* mark_blocks(const scar_var_layout* l, const uint32_t* idx,
 static int var_rows(int copy, const scar_var_layout* layout, const void* x, const void* c,
                     const uint32_t* idx, uint32_t n_idx, bool all_blocks, scar_norm* norm_out,
                     void* workspace, size_t workspace_bytes, void* stream) {
+  if (layout && layout->dtype == SCAR_F32_BF16C) return SCAR_ERR_UNSUPPORTED;
   const uint64_t nb = var_blocks(layout);
   if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
   if (norm_out && !aligned(norm_out, 8)) return SCAR_ERR_INVALID_ARG;
@@ -374,6 +375,7 @@ extern "C" size_t scar_var_workspace_bytes(uint64_t n_blocks) {
 extern "C" int scar_var_block_scores(const scar_var_layout* layout, const void* x, const void* c,
                                      void* scores, void* workspace, size_t workspace_bytes,
                                      void* stream) {
+  if (layout && layout->dtype == SCAR_F32_BF16C) return SCAR_ERR_UNSUPPORTED;
   const uint64_t nb = var_blocks(layout);
   if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
   if (nb == 0) return SCAR_OK;

@@ -103,6 +103,11 @@ def lib():
                      "scar_partial_recover", "scar_perturbation_norm", "scar_mask_to_indices",
                      "scar_select_round", "scar_select_random"):
             getattr(L, name).restype = ctypes.c_int
+        L.scar_ceiling_read2.argtypes = [vp, vp, u64, vp, vp]
+        L.scar_ceiling_copy.argtypes = [vp, vp, u64, vp]
+        L.scar_ceiling_read2_write1.argtypes = [vp, vp, u64, vp, vp]
+        for name in ("scar_ceiling_read2", "scar_ceiling_copy", "scar_ceiling_read2_write1"):
+            getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
 

@@ -1,12 +1,13 @@
-"""The benchmark's own workload at full size (2^30 elements, 1,024-element blocks, f32 and
-its bf16 copy), through the same entry points and launch configuration as bench.py.
+"""The benchmark's own workload at full size (2^30 elements, 1,024-element blocks; f32, its
+bf16 copy, and f32 with a bf16 checkpoint), through the same entry points and launch
+configuration as bench.py.
 
-The oracle cannot run 2 x 4 GiB in seconds, so it checks what it can compute one by one -
-the scores of ~1,000 sampled blocks, the whole top-k on the GPU's scores (1M keys), the
-commit on the sampled blocks, the norm over all 131,072 lost blocks - and properties that
-hold at any size cover the rest (every byte outside K / S unchanged, every byte inside
-copied, sum of scores = squared full-recovery norm).  The by-layer variant of the store has
-only 96 blocks, so there the oracle runs the whole cycle on the full host copy."""
+The whole store is brought to the host and the oracle (OpenMP over blocks) runs the whole
+cycle on it: every one of the 1,048,576 scores is compared, the selection is checked by both
+rules (exactly the oracle's choice on the GPU's own scores; against the oracle's float64
+scores within the band around its k-th score), and after the commit and after the recovery
+every byte of c and of x is compared with the oracle's host mirrors.  The by-layer variant of
+the store (96 tensors) is treated the same way."""
 import numpy as np
 import pytest
 import torch
@@ -14,23 +15,23 @@ import torch
 import oracle
 from paper_1810_07354_amd import scar
 from paper_1810_07354_amd import workloads as wl
-from gpu_util import DEV, REL_TOL, idx_dev, idx_host, to_host
+from gpu_util import (DEV, REL_TOL, assert_norm_matches, assert_scores_match, assert_selection_matches,
+                      idx_dev, idx_host, to_host)
 
 pytestmark = pytest.mark.gpu
 
 N_ELEMS, L = 1 << 30, 1024
 NB = N_ELEMS // L
+ORACLE_THREADS = 16
 
 
-def rows_to_host(t, rows):
-    """Blocks `rows` of device store t as one contiguous host store (bf16 as uint16 bits)."""
-    sel = t.view(NB, L)[torch.from_numpy(rows.astype(np.int64)).to(DEV)].contiguous()
-    return to_host(sel).reshape(-1)
-
-
-def bits(t):
-    """A view that torch.equal compares bit for bit (bfloat16 as int16)."""
-    return t.view(torch.int16) if t.dtype == torch.bfloat16 else t
+def same_bits(t: torch.Tensor, host: np.ndarray) -> bool:
+    """Device tensor against a host mirror, bit for bit, a slab at a time (bfloat16 as uint16)."""
+    step = 1 << 28
+    for lo in range(0, t.numel(), step):
+        if not np.array_equal(to_host(t[lo:lo + step]), host[lo:lo + step]):
+            return False
+    return True
 
 
 @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16, wl.F32_BF16C])
@@ -43,57 +44,71 @@ def test_flat_store_full_size(dtype):
         c = c.to(torch.bfloat16)
     k, n_lost = wl.k_of_fraction(0.10, NB), NB // 8
     ws = scar.new_workspace(NB, DEV)
-    oracle.set_num_threads(8)
+    hx, hc = to_host(x), to_host(c)
+    score_kind = wl.F32          # float scores whatever the store holds
+    oracle.set_num_threads(ORACLE_THREADS)
     try:
-        # ---- scores: sampled blocks through the oracle
+        # ---- scores: every block against the oracle
         print("scores", flush=True)
         s = scar.block_scores(x, c, L)
-        r = np.random.default_rng(11)
-        sample = np.unique(np.concatenate([r.choice(NB, size=1024, replace=False), [0, 1, NB - 2, NB - 1]]))
-        ref = oracle.block_scores(dtype, rows_to_host(x, sample), rows_to_host(c, sample), L)
+        s_ref = oracle.block_scores(dtype, hx, hc, L)
+        assert_scores_match(s, s_ref, score_kind)
         s_h = s.cpu().numpy()
-        np.testing.assert_allclose(s_h[sample].astype(np.float64), ref, rtol=REL_TOL, atol=0)
-        # sum of all scores = squared norm of a full recovery (Appendix A.3)
+        # sum of all scores = squared norm of a full recovery (Appendix A.3), both from the oracle
+        full_ref = oracle.perturbation_norm(dtype, hx, hc, L)
+        assert abs(s_ref.sum() - full_ref[0]) <= 1e-9 * full_ref[0]
         full = scar.read_norm(scar.perturbation_norm(x, c, L, None, ws))
-        assert abs(s_h.astype(np.float64).sum() - full[0]) <= REL_TOL * full[0]
+        assert_norm_matches(full, full_ref, score_kind)
 
-        # ---- selection: the whole top-k on the GPU's own scores
+        # ---- selection: both rules on all 2^20 keys
         print("select", flush=True)
         idx = scar.select_topk(s, k, ws)
         idx_h = idx_host(idx)
-        np.testing.assert_array_equal(idx_h, oracle.select_topk(s_h.astype(np.float64), k))
+        assert_selection_matches(idx_h, s_h, s_ref, k)
 
-        # ---- commit: sampled blocks through the oracle, everything else by property
+        # ---- commit: the oracle advances its mirror, every byte of c and x compared
         print("commit", flush=True)
-        c_before = c.clone()
         scar.checkpoint_commit(x, c, L, idx)
-        chosen = np.zeros(NB, dtype=bool)
-        chosen[idx_h] = True
-        sub_x, sub_c = rows_to_host(x, sample), rows_to_host(c_before, sample)
-        oracle.checkpoint_commit(dtype, sub_x, sub_c, L, np.nonzero(chosen[sample])[0].astype(np.uint32))
-        np.testing.assert_array_equal(rows_to_host(c, sample), sub_c)
-        expect = c_before
-        idx_l = idx.long()
-        expect.view(NB, L)[idx_l] = x.view(NB, L)[idx_l].to(c.dtype)     # torch rounds to nearest even too
-        assert torch.equal(bits(c), bits(expect))
-        del expect, c_before
+        oracle.checkpoint_commit(dtype, hx, hc, L, idx_h)
+        assert same_bits(c, hc), "c differs from the oracle's mirror after the commit"
+        assert same_bits(x, hx), "the commit changed x"
 
-        # ---- partial recovery with the fused norm: the norm over all lost blocks by the oracle
+        # ---- partial recovery with the fused norm
         print("recover", flush=True)
         lost = wl.random_lost_blocks(NB, n_lost, 4 + 1000)
-        lost_d = idx_dev(lost)
-        hx, hc = rows_to_host(x, lost), rows_to_host(c, lost)
-        want = oracle.perturbation_norm(dtype, hx, hc, L)
-        x_before = x.clone()
-        got = scar.read_norm(scar.partial_recover(x, c, L, lost_d, ws))
-        assert abs(got[0] - want[0]) <= REL_TOL * want[0]
-        assert abs(got[1] - want[1]) <= REL_TOL * want[1]
-        assert got[1] <= full[1] * (1 + REL_TOL)                      # Theorem 4.1 (after the commit the
-        lost_l = lost_d.long()                                         # full norm only shrank, so compare
-        x_before.view(NB, L)[lost_l] = c.view(NB, L)[lost_l].to(x.dtype)   # with the pre-commit one)
-        assert torch.equal(bits(x), bits(x_before))
-        if dtype != wl.F32_BF16C:
-            np.testing.assert_array_equal(rows_to_host(x, lost[:256]), hc[:256 * L])
+        got = scar.read_norm(scar.partial_recover(x, c, L, idx_dev(lost), ws))
+        want = oracle.partial_recover(dtype, hx, hc, L, lost)
+        assert_norm_matches(got, want, score_kind)
+        assert got[1] <= full[1] * (1 + REL_TOL)                      # Theorem 4.1
+        assert same_bits(x, hx), "x differs from the oracle's mirror after the recovery"
+        assert same_bits(c, hc), "the recovery changed c"
+    finally:
+        oracle.set_num_threads(1)
+
+
+@pytest.mark.parametrize("log2_elems", [26, 27])
+def test_scores_in_the_occupancy_limited_launch(log2_elems):
+    """2^26 and 2^27 float32 elements in 1,024-element blocks: 65,536 / 131,072 workgroup-sized
+    launches, the size from which the score scan limits its workgroups per compute unit - the
+    launch the benchmark's store uses - with every score compared with the oracle."""
+    n = 1 << log2_elems
+    print("occupancy-limited scores n=2^%d" % log2_elems, flush=True)
+    x, c = wl.flat_like_torch(DEV, seed=40 + log2_elems, n_elems=n)
+    hx, hc = to_host(x), to_host(c)
+    oracle.set_num_threads(ORACLE_THREADS)
+    try:
+        for dtype in (wl.F32, wl.BF16, wl.F32_BF16C):
+            if dtype == wl.BF16:
+                xd, cd = x.to(torch.bfloat16), c.to(torch.bfloat16)
+            elif dtype == wl.F32_BF16C:
+                xd, cd = x, c.to(torch.bfloat16)
+            else:
+                xd, cd = x, c
+            for bl in (512, 1024, 2048):
+                s = scar.block_scores(xd, cd, bl)
+                s_ref = oracle.block_scores(dtype, to_host(xd) if dtype == wl.BF16 else hx,
+                                            to_host(cd) if dtype != wl.F32 else hc, bl)
+                assert_scores_match(s, s_ref, wl.F32)
     finally:
         oracle.set_num_threads(1)
 

@@ -447,7 +447,7 @@ def test_cycle_replays_correctly_from_a_hip_graph():
         torch.cuda.synchronize()
 
 
-def test_random_layouts_whole_cycles():
+def test_sixty_random_stores_incl_bf16_checkpoint():
     # 60 seeded random stores: element type, block length, size (ragged or not), k and lost
     # set all drawn at random; one full cycle each, compared with the oracle call by call
     r = np.random.default_rng(2024)
