@@ -151,6 +151,23 @@ int scar_block_scores_rows(const scar_layout* layout, const void* x, const void*
 int scar_select_topk(int32_t score_type, const void* scores, uint32_t n_blocks, uint32_t k,
                      uint32_t* out_idx, void* workspace, size_t workspace_bytes, void* stream);
 
+/* scar_select_topk for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same result (index for index) as scar_select_topk, but the scratch is a fixed
+ * array inside the library's code object - about 641 KiB on every GPU the library runs on,
+ * held until the process ends - so the call allocates nothing, directly or indirectly.
+ *   n_blocks > SCAR_STATIC_MAX_BLOCKS: SCAR_ERR_WORKSPACE, nothing enqueued.
+ *   The first call on a device looks up the array's address on that device (one runtime
+ *   query, no allocation; make it before a capture starts); it returns SCAR_ERR_DEVICE if
+ *   that fails.
+ *   All calls on one GPU share the one array, and it keeps the last call's contents; every
+ *   call clears what it needs with a kernel of its own.  Calls that overlap on one GPU (two
+ *   streams, two threads) race on it: order them, or use scar_select_topk with a workspace
+ *   each. */
+#define SCAR_STATIC_MAX_BLOCKS (1u << 24)
+int scar_select_topk_static(int32_t score_type, const void* scores, uint32_t n_blocks, uint32_t k,
+                            uint32_t* out_idx, void* stream);
+
 /* Checkpoint step 4, the part on the critical path (Section 4.3): update the in-memory
  * checkpoint, c_b <- x_b for the n_idx blocks in idx.  If staging is not NULL, row i of
  * staging (block_len elements per row, packed) also receives block idx[i]: the bytes a

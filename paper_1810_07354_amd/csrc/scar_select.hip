@@ -14,6 +14,8 @@
 // The chosen indices are then written in ascending order by a two-level prefix sum
 // (per-tile counts, prefix over the tiles, per-tile write), so the result does not
 // depend on the order in which workgroups run.
+#include <mutex>
+
 #include "scar_device.hpp"
 #include "scar_host.hpp"
 
@@ -525,27 +527,74 @@ __global__ __launch_bounds__(kWG) void k_select_round(uint32_t n, uint32_t k, ui
 
 using namespace scar;
 
-extern "C" int scar_select_topk(int32_t score_type, const void* scores, uint32_t n_blocks, uint32_t k,
-                                uint32_t* out_idx, void* workspace, size_t workspace_bytes,
-                                void* stream) {
+// Body of scar_select_topk and scar_select_topk_static once the workspace is known.
+static int select_topk_checked(int32_t score_type, const void* scores, uint32_t n_blocks, uint32_t k,
+                               uint32_t* out_idx, void* workspace, hipStream_t st) {
+  if (k == n_blocks) {  // a full checkpoint: every block, whatever the scores
+    const uint32_t grid = (k + kWG - 1) / kWG < 4096 ? (k + kWG - 1) / kWG : 4096;
+    launch(k_select_round, dim3(grid), dim3(kWG), 0, st, n_blocks, k, 0u, out_idx);
+    return launch_status();
+  }
+  if (score_type == SCAR_SCORE_F32)
+    run_select<SRC_F32>(KeyArgs{scores, 0, 0}, n_blocks, k, out_idx, workspace, st);
+  else
+    run_select<SRC_I64>(KeyArgs{scores, 0, 0}, n_blocks, k, out_idx, workspace, st);
+  return launch_status();
+}
+
+static int select_topk_args(int32_t score_type, const void* scores, uint32_t n_blocks, uint32_t k,
+                            uint32_t* out_idx) {
   if (score_type != SCAR_SCORE_F32 && score_type != SCAR_SCORE_I64) return SCAR_ERR_INVALID_ARG;
   if (n_blocks > SCAR_MAX_BLOCKS || k > n_blocks) return SCAR_ERR_INVALID_ARG;
   if (k == 0) return SCAR_OK;
   if (!scores || !out_idx || !aligned(scores, score_type == SCAR_SCORE_I64 ? 8 : 4) ||
       !aligned(out_idx, 4))
     return SCAR_ERR_INVALID_ARG;
-  const int rc = check_workspace(workspace, workspace_bytes, n_blocks);
+  return SCAR_OK;
+}
+
+extern "C" int scar_select_topk(int32_t score_type, const void* scores, uint32_t n_blocks, uint32_t k,
+                                uint32_t* out_idx, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+  int rc = select_topk_args(score_type, scores, n_blocks, k, out_idx);
+  if (rc || k == 0) return rc;
+  rc = check_workspace(workspace, workspace_bytes, n_blocks);
   if (rc) return rc;
-  if (k == n_blocks) {  // a full checkpoint: every block, whatever the scores
-    const uint32_t grid = (k + kWG - 1) / kWG < 4096 ? (k + kWG - 1) / kWG : 4096;
-    launch(k_select_round, dim3(grid), dim3(kWG), 0, (hipStream_t)stream, n_blocks, k, 0u, out_idx);
-    return launch_status();
+  return select_topk_checked(score_type, scores, n_blocks, k, out_idx, workspace, (hipStream_t)stream);
+}
+
+// ---- the selection for callers that cannot allocate -------------------------------------
+// The scratch of scar_select_topk_static: one array per GPU, part of the loaded code object,
+// sized for SCAR_STATIC_MAX_BLOCKS blocks.  In host code the array's name is only a handle;
+// its device address is asked for once per device and kept.
+static __device__ __align__(256) unsigned char scratch[workspace_bytes_for(SCAR_STATIC_MAX_BLOCKS)];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device, or NULL.
+static void* scratch_of_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = p;
   }
-  if (score_type == SCAR_SCORE_F32)
-    run_select<SRC_F32>(KeyArgs{scores, 0, 0}, n_blocks, k, out_idx, workspace, (hipStream_t)stream);
-  else
-    run_select<SRC_I64>(KeyArgs{scores, 0, 0}, n_blocks, k, out_idx, workspace, (hipStream_t)stream);
-  return launch_status();
+  return g_scratch_ptr[dev];
+}
+
+extern "C" int scar_select_topk_static(int32_t score_type, const void* scores, uint32_t n_blocks,
+                                       uint32_t k, uint32_t* out_idx, void* stream) {
+  int rc = select_topk_args(score_type, scores, n_blocks, k, out_idx);
+  if (rc) return rc;
+  if (n_blocks > SCAR_STATIC_MAX_BLOCKS) return SCAR_ERR_WORKSPACE;
+  if (k == 0) return SCAR_OK;
+  void* ws = scratch_of_current_device();
+  if (!ws) return SCAR_ERR_DEVICE;
+  return select_topk_checked(score_type, scores, n_blocks, k, out_idx, ws, (hipStream_t)stream);
 }
 
 extern "C" int scar_mask_to_indices(const uint8_t* mask, uint32_t n_blocks, uint32_t* out_idx,

@@ -68,6 +68,8 @@ def lib():
         L.scar_block_scores_rows.restype = ctypes.c_int
         L.scar_select_topk.argtypes = [i32, vp, u32, u32, vp, vp, sz, vp]
         L.scar_checkpoint_commit.argtypes = [lp, vp, vp, vp, u32, vp, vp]
+        L.scar_select_topk_static.argtypes = [i32, vp, u32, u32, vp, vp]
+        L.scar_select_topk_static.restype = ctypes.c_int
         L.scar_partial_recover.argtypes = [lp, vp, vp, vp, u32, vp, vp, sz, vp]
         L.scar_perturbation_norm.argtypes = [lp, vp, vp, vp, u32, vp, vp, sz, vp]
         L.scar_mask_to_indices.argtypes = [vp, u32, vp, vp, vp, sz, vp]
@@ -221,6 +223,28 @@ def select_topk(scores, k, workspace, out=None):
     elif _idx(out, "out").numel() < int(k):
         raise ValueError("out must hold k indices")
     _check(lib().scar_select_topk(st, _p(scores), scores.numel(), int(k), _p(out), _p(workspace), _bytes(workspace), _stream()), "scar_select_topk")
+    return out
+
+
+STATIC_MAX_BLOCKS = 1 << 24
+
+
+def select_topk_static(scores, k, out=None):
+    """scar_select_topk_static: scar_select_topk on the library's own fixed scratch (no
+    workspace, nothing allocated by the call when `out` is given)."""
+    _dev(scores, "scores")
+    if scores.dtype == torch.float32:
+        st = SCORE_F32
+    elif scores.dtype == torch.int64:
+        st = SCORE_I64
+    else:
+        raise TypeError("scores must be float32 or int64")
+    if out is None:
+        out = torch.empty(int(k), dtype=torch.int32, device=scores.device)
+    elif _idx(out, "out").numel() < int(k):
+        raise ValueError("out must hold k indices")
+    _check(lib().scar_select_topk_static(st, _p(scores), scores.numel(), int(k), _p(out), _stream()),
+           "scar_select_topk_static")
     return out
 
 
