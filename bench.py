@@ -84,8 +84,8 @@ def make_workload(name, dev):
             return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
         return torch.from_numpy(a).to(dev)
 
-    if name in ("flat_f32", "flat_bf16", "flat_mixed"):
-        n_elems, L, seed = 1 << 30, 1024, 4
+    if name in ("flat_f32", "flat_bf16", "flat_mixed", "giant"):
+        n_elems, L, seed = 1 << 30, (1 << 26) if name == "giant" else 1024, 4
         x, c = wl.flat_like_torch(dev, seed=seed, n_elems=n_elems)
         nb = n_elems // L
         if name == "flat_bf16":
@@ -93,28 +93,32 @@ def make_workload(name, dev):
         elif name == "flat_mixed":
             c = c.to(torch.bfloat16)
         k, n_lost = wl.k_of_fraction(0.10, nb), nb // 8
+        drift_len = min(L, 1024)
 
         def lost_of(cycle):
             return wl.random_lost_blocks(nb, n_lost, seed + 1000 + cycle)
 
         def drift(cycle):
             if x.dtype == torch.float32:
-                wl.drift_torch(x, seed + 5000 + cycle, 0.10, L)
+                wl.drift_torch(x, seed + 5000 + cycle, 0.10, drift_len)
             else:
                 m = (nb // 10) * L
                 lo = ((cycle * 7919) % (nb - nb // 10)) * L
                 f = x[lo:lo + m].float()
                 wl.drift_torch(f, seed + 5000 + cycle, 1.0, L)
                 x[lo:lo + m] = f.to(torch.bfloat16)
-        label = "flat store 2^30 x %s, 1024-element blocks, k=10%%, lost=1/8" % (
-            {"flat_bf16": "bf16", "flat_f32": "fp32", "flat_mixed": "fp32 with a bf16 checkpoint"}[name])
+        label = "flat store 2^30 x %s, %d-element blocks, k=10%%, lost=1/8" % (
+            {"flat_bf16": "bf16", "flat_f32": "fp32", "flat_mixed": "fp32 with a bf16 checkpoint",
+             "giant": "fp32 in 16 shards"}[name], L)
         return x, c, L, k, n_lost, lost_of, drift, label, None
 
     if name == "doctopic":
         return make_doctopic(dev)
 
-    gens = {"mlr": wl.mlr_like, "mf": wl.mf_like, "lda": wl.lda_like, "cnn": wl.cnn_like}
-    w = gens[name]()
+    if name.startswith("cnn@"):      # the CNN-sized store at 1, 10 or 50 % of the shards per checkpoint
+        w = wl.cnn_like(fraction=int(name[4:]) / 100.0)
+    else:
+        w = {"mlr": wl.mlr_like, "mf": wl.mf_like, "lda": wl.lda_like, "cnn": wl.cnn_like}[name]()
     x, c = up(w.x, w.dtype), up(w.c, w.dtype)
     nb, L = w.n_blocks, w.block_len
 
@@ -179,7 +183,8 @@ def make_doctopic(dev, docs=2_000_000, topics=100, seed=7):
 
 
 def cpu_baseline(x, c, L, k_frac, lost_frac, sample_elems, threads, weights=None):
-    """The oracle's cycle on the first `sample_elems` elements of the same store."""
+    """The oracle's cycle on the first `sample_elems` elements of the same store (the whole
+    store unless the caller had to bound it), with `threads` OpenMP threads and with one."""
     import numpy as np
     import torch
     import oracle
@@ -200,12 +205,13 @@ def cpu_baseline(x, c, L, k_frac, lost_frac, sample_elems, threads, weights=None
     k = wl.k_of_fraction(k_frac, nb)
     n_lost = max(1, int(nb * lost_frac))
     times = {}
+    x1, c1 = np.empty_like(hx), np.empty_like(hc)
     for label, nt, reps in (("all", threads, 3), ("one", 1, 1)):
         oracle.set_num_threads(nt)
         ts = []
         for rep in range(reps):
             lost = wl.random_lost_blocks(nb, n_lost, 77 + rep)
-            x1, c1 = hx.copy(), hc.copy()
+            np.copyto(x1, hx), np.copyto(c1, hc)
             t0 = time.perf_counter()
             s = oracle.block_scores(dt, x1, c1, L) if hw is None else oracle.tv_block_scores(dt, x1, c1, L, hw)
             idx = oracle.select_topk(s, k)
@@ -218,12 +224,59 @@ def cpu_baseline(x, c, L, k_frac, lost_frac, sample_elems, threads, weights=None
         times[label] = statistics.median(ts)
     oracle.set_num_threads(1)
     pbytes = hx.nbytes
-    return {"value": pbytes / times["all"] / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "sample": "first %d elements (%d blocks) of the same store, k=%d, lost=%d; median of 3 "
-                      "cycles; store bytes / cycle time" % (sample_elems, nb, k, n_lost),
+    whole = sample_elems == x.numel()
+    return {"value": pbytes / times["all"] / 1e9, "unit": "GB/s", "cores": threads, "threads": threads,
+            "host_cores": os.cpu_count(), "kind": "oracle",
+            "sample": "%s (%d elements, %d blocks), k=%d, lost=%d; median of 3 cycles with %d OpenMP "
+                      "threads (the GPU box's CPU share is 16 whatever the host's core count), 1 cycle "
+                      "with one thread; store bytes / cycle time"
+                      % ("the whole store" if whole else "the first part of the same store", sample_elems,
+                         nb, k, n_lost, threads),
             "ms_per_cycle": times["all"] * 1e3,
             "single_thread_value": pbytes / times["one"] / 1e9,
             "single_thread_ms_per_cycle": times["one"] * 1e3}
+
+
+def measure_ceilings(dev, bytes_per_stream, reps=10):
+    """The three plain bandwidth kernels of scar_ceilings.h on two fresh buffers of
+    `bytes_per_stream` bytes each: GB/s of a two-stream read, a copy and a read-two-write-one
+    pass, each launch timed with events on the launch stream (median)."""
+    import ctypes
+    import torch
+    from paper_1810_07354_amd import scar
+    L_ = scar.lib()
+    vp = ctypes.c_void_p
+    n = bytes_per_stream // 4
+    a = torch.empty(n, dtype=torch.float32, device=dev).normal_()
+    b = torch.empty(n, dtype=torch.float32, device=dev).normal_()
+    sink = torch.zeros(1, dtype=torch.int64, device=dev)
+    st = vp(torch.cuda.current_stream().cuda_stream)
+    pa, pb, ps = vp(a.data_ptr()), vp(b.data_ptr()), vp(sink.data_ptr())
+    calls = {
+        "read2": (lambda: L_.scar_ceiling_read2(pa, pb, bytes_per_stream, ps, st), 2),
+        "copy": (lambda: L_.scar_ceiling_copy(pa, pb, bytes_per_stream, st), 2),
+        "read2_write1": (lambda: L_.scar_ceiling_read2_write1(pa, pb, bytes_per_stream, ps, st), 3),
+    }
+    out = {"bytes_per_stream": bytes_per_stream}
+    for name, (call, streams) in calls.items():
+        ms = []
+        for i in range(3 + reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            rc = call()
+            e1.record()
+            if rc != 0:
+                raise scar.ScarError(rc, "scar_ceiling_" + name)
+            torch.cuda.synchronize()
+            if i >= 3:
+                ms.append(e0.elapsed_time(e1))
+        t = statistics.median(ms)
+        out[name + "_GBps"] = round(streams * bytes_per_stream / (t * 1e-3) / 1e9, 1)
+        out[name + "_ms"] = round(t, 4)
+    del a, b
+    torch.cuda.empty_cache()
+    return out
 
 
 def main_layers(args):
@@ -297,63 +350,44 @@ def main_layers(args):
         "cpu_baseline": None}), flush=True)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="flat_f32",
-                    choices=["flat_f32", "flat_bf16", "flat_mixed", "mlr", "mf", "lda", "cnn", "layers", "doctopic"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run a plain 1 GiB device copy three times (reference for HBM counters)")
-    ap.add_argument("--hip-graph", action="store_true",
-                    help="capture the cycle in a HIP graph and time its replays (needs --warmup >= 1)")
-    ap.add_argument("--print-source-hash", action="store_true",
-                    help="print the SHA-256 of the score kernel's sources and exit")
-    args = ap.parse_args()
-    if args.print_source_hash:
-        print(score_kernel_source_hash())
-        return
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this path runs on ONE GPU; --gpus %d is not supported (blocks would be "
-              "range-partitioned over GPUs and only the selection would exchange histograms)"
-              % args.gpus, file=sys.stderr)
-        sys.exit(2)
+STRATEGIES = ("priority", "round", "random", "full")
+OTHER_WORKLOADS = ("flat_bf16", "mlr", "mf", "lda", "cnn@1", "cnn@10", "cnn@50")
 
+
+def run_workload(name, dev, steps, warmup, strategy="priority", hip_graph=False):
+    """Times `steps` cycles of one workload after `warmup` untimed ones.  Returns (JSON fields,
+    store) where store = (x, c, L, k, n_lost, nb, weights) for the CPU baseline.
+
+    strategy: how the blocks to save are chosen (Section 5.4): "priority" = scores + top-k (the
+    method); "round" / "random" = the comparison strategies' generators in place of scores and
+    selection; "full" = the traditional set-up, every block saved and every block recovered."""
+    import ctypes
     import numpy as np
     import torch
     from paper_1810_07354_amd import scar
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
-    dev = "cuda:0"
-    torch.cuda.set_device(0)
-    scar.lib()   # fail now if the HIP library is missing
-
-    if args.workload == "layers":
-        return main_layers(args)
-
-    x, c, L, k, n_lost, lost_of, drift, label, weights = make_workload(args.workload, dev)
+    x, c, L, k, n_lost, lost_of, drift, label, weights = make_workload(name, dev)
     n_elems = x.numel()
     xbytes, cbytes = x.element_size(), c.element_size()
     nb = (n_elems + L - 1) // L
     is_int = x.dtype == torch.int32
     score_bytes = 8 if is_int else 4
+    total = warmup + steps
+    if strategy == "full":
+        k, n_lost = nb, nb
+        all_blocks = torch.arange(nb, dtype=torch.int32, device=dev)
+        lost_sets = [all_blocks] * total
+    else:
+        lost_sets = [torch.from_numpy(lost_of(i).view(np.int32).copy()).to(dev) for i in range(total)]
     ws = scar.new_workspace(nb, dev)
     scores = torch.empty(nb, dtype=torch.int64 if is_int else torch.float32, device=dev)
     idx = torch.empty(k, dtype=torch.int32, device=dev)
     norm = torch.zeros(3, dtype=torch.float64, device=dev)
-    total = args.warmup + args.steps
-    lost_sets = [torch.from_numpy(lost_of(i).view(np.int32).copy()).to(dev) for i in range(total)]
 
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
-           torch.cuda.Event(enable_timing=True)) for _ in range(total)]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(total)]
 
-    # The five C-ABI calls with their arguments marshalled once: the timed loop then only
+    # The C-ABI calls with their arguments marshalled once: the timed loop then only
     # enqueues (buffers, sizes and the stream do not change between steps).
-    import ctypes
     L_ = scar.lib()
     lay = scar.Layout(scar.store_type(x, c), L, n_elems)
     lay_p = ctypes.byref(lay)
@@ -383,33 +417,41 @@ def main():
         def call_recover(lost, st):
             return L_.scar_tv_partial_recover(lay_p, px, pc, pwt, lost, n_lost, pn, pw, wbytes, st)
 
-    def step(i):
-        e0, e1, e2 = ev[i]
-        e0.record()
-        check(call_scores(stream))
-        e1.record()
-        check(L_.scar_select_topk(score_type, ps, nb, k, pi, pw, wbytes, stream))
-        check(L_.scar_checkpoint_commit(lay_p, px, pc, pi, k, None, stream))
-        check(call_recover(lost_p[i], stream))
-        e2.record()
+    def call_choose(i, st):
+        if strategy == "priority":
+            if is_int:   # an L1 distance over L int32 elements is at most L * (2^32 - 1): fewer digit passes
+                return L_.scar_select_topk_bounded(score_type, ps, nb, k, L * (2 ** 32 - 1), pi, pw, wbytes, st)
+            return L_.scar_select_topk(score_type, ps, nb, k, pi, pw, wbytes, st)
+        if strategy == "round":
+            return L_.scar_select_round(nb, k, (i * k) % nb, pi, st)
+        if strategy == "random":
+            return L_.scar_select_random(nb, k, 2024, i, pi, pw, wbytes, st)
+        return L_.scar_select_round(nb, nb, 0, pi, st)     # full: every block
 
-    if args.calibrate_copy:
-        # A plain copy of known size (1 GiB read, 1 GiB written per launch) so that a
-        # counter run of this command also shows what the HBM counters read for it.
-        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+    def enqueue(i, st, lost, events=None):
+        if events:
+            events[0].record()
+        if strategy == "priority":
+            check(call_scores(st))
+        if events:
+            events[1].record()
+        check(call_choose(i, st))
+        if events:
+            events[2].record()
+        check(L_.scar_checkpoint_commit(lay_p, px, pc, pi, k, None, st))
+        if events:
+            events[3].record()
+        check(call_recover(lost, st))
+        if events:
+            events[4].record()
 
-    for i in range(args.warmup):
-        step(i)
+    for i in range(warmup):
+        enqueue(i, stream, lost_p[i], ev[i])
         drift(i)
     torch.cuda.synchronize()
 
     graph = None
-    if args.hip_graph:
+    if hip_graph:
         # The library only enqueues kernels, so the whole cycle can be captured once and
         # replayed with one launch: what a caller with a launch-bound (small) store would do.
         # The lost set of each step is copied into a fixed buffer before the step is timed.
@@ -421,15 +463,11 @@ def main():
         lost_static.copy_(lost_sets[0])
         torch.cuda.synchronize()
         with torch.cuda.graph(graph, stream=side):
-            cap = vp(torch.cuda.current_stream().cuda_stream)
-            check(call_scores(cap))
-            check(L_.scar_select_topk(score_type, ps, nb, k, pi, pw, wbytes, cap))
-            check(L_.scar_checkpoint_commit(lay_p, px, pc, pi, k, None, cap))
-            check(call_recover(p_lost, cap))
+            enqueue(0, vp(torch.cuda.current_stream().cuda_stream), p_lost)
         torch.cuda.synchronize()
 
     wall = []
-    for i in range(args.warmup, total):
+    for i in range(warmup, total):
         if graph is not None:
             lost_static.copy_(lost_sets[i])
         torch.cuda.synchronize()
@@ -437,7 +475,7 @@ def main():
         if graph is not None:
             graph.replay()
         else:
-            step(i)
+            enqueue(i, stream, lost_p[i], ev[i])
         torch.cuda.synchronize()
         wall.append(time.perf_counter() - t0)
         drift(i)
@@ -445,25 +483,37 @@ def main():
 
     ms_step = 1e3 * sum(wall) / len(wall)
     # with a graph the per-kernel events come from the eager warm-up steps
-    timed = range(args.warmup) if graph is not None else range(args.warmup, total)
-    score_ms = [ev[i][0].elapsed_time(ev[i][1]) for i in timed]
-    cycle_ms = [ev[i][0].elapsed_time(ev[i][2]) for i in timed]
-    score_avg_ms = sum(score_ms) / len(score_ms)
+    timed = range(warmup) if graph is not None else range(warmup, total)
 
-    passes = 6 if is_int else 3
+    def avg_ms(a, b):
+        return sum(ev[i][a].elapsed_time(ev[i][b]) for i in timed) / len(timed)
+
+    step_ms = {"scores": avg_ms(0, 1), "select": avg_ms(1, 2), "commit": avg_ms(2, 3), "recover": avg_ms(3, 4)}
+    cycle_ms = [ev[i][0].elapsed_time(ev[i][4]) for i in timed]
+
+    passes = ((L * (2 ** 32 - 1)).bit_length() + 10) // 11 if is_int else 3
     b = algorithmic_bytes(n_elems, L, xbytes, cbytes, score_bytes, k, n_lost, passes + 2)
+    if strategy != "priority":     # nothing is scored; the generator writes k indices
+        b["scores"], b["select"] = 0, 4 * k
+        b["total"] = b["select"] + b["commit"] + b["recover"]
     pbytes = n_elems * xbytes
     value = pbytes / (ms_step * 1e-3) / 1e9
     hbm_gbs = b["total"] / (ms_step * 1e-3) / 1e9
-    achieved = b["scores"] / (score_avg_ms * 1e-3) / 1e9
+    if strategy == "priority":
+        roof_kernel = ("k_mixed_scores" if cbytes != xbytes else
+                       ("k_block_scores (total variation)" if weights is not None else "k_block_scores"))
+        roof_bytes, roof_ms = b["scores"], step_ms["scores"]
+    else:                          # the copy kernels dominate: the recovery with the fused norm
+        roof_kernel, roof_bytes, roof_ms = "k_recover + k_norm_finish", b["recover"], step_ms["recover"]
+    achieved = roof_bytes / (roof_ms * 1e-3) / 1e9
 
     out = {
         "metric": "params scanned GB/s per checkpoint+recovery cycle",
         "value": round(value, 2),
         "unit": "GB/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": round(ms_step, 4),
         "higher_is_better": True,
         "scaling": "weak",
@@ -471,27 +521,134 @@ def main():
         "dtype": {torch.float32: "f32", torch.bfloat16: "bf16", torch.int32: "i32"}[x.dtype]
                  + ("+bf16c" if cbytes != xbytes else ""),
         "data": "synthetic",
-        "config": {"workload": label, "n_elems": n_elems, "block_len": L, "n_blocks": nb, "k": k,
-                   "n_lost": n_lost, "launch": "hip graph replay" if graph is not None else "stream"},
+        "config": {"workload": label, "name": name, "strategy": strategy, "n_elems": n_elems, "block_len": L,
+                   "n_blocks": nb, "k": k, "n_lost": n_lost,
+                   "launch": "hip graph replay" if graph is not None else "stream"},
         "algorithmic_bytes_per_cycle": b,
         "hbm_GBps_algorithmic": round(hbm_gbs, 1),
         "pct_of_hbm_peak": round(100.0 * hbm_gbs / HBM_PEAK_GBS, 2),
         "ms_per_step_events_median": round(statistics.median(cycle_ms), 4),
+        "step_ms_events": {key: round(v, 4) for key, v in step_ms.items()},
         "last_norm": scar.read_norm(norm)[1],
-        "roofline": {"bound": "hbm", "kernel": "k_mixed_scores" if cbytes != xbytes else
-                     ("k_block_scores (total variation)" if weights is not None else "k_block_scores"),
+        "roofline": {"bound": "hbm", "kernel": roof_kernel,
                      "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": stored_traffic(args.workload), "avg_ms": round(score_avg_ms, 4),
-                     "algorithmic_bytes_per_launch": b["scores"]},
+                     "traffic": stored_traffic(name) if strategy == "priority" else None,
+                     "traffic_source": ("profiles/" + TRAFFIC_FILES[name]) if name in TRAFFIC_FILES else None,
+                     "avg_ms": round(roof_ms, 4),
+                     "algorithmic_bytes_per_launch": roof_bytes},
         "paper_context": "paper reports 78-95% lower iteration cost (hardware not stated; overhead "
                          "run on 4x AWS i3.2xlarge); no throughput figure exists for this path",
     }
-    if not args.no_cpu_baseline:
+    return out, (x, c, L, k, n_lost, nb, weights)
+
+
+def brief(out):
+    """The fields of a workload's result that the headline line carries for the other workloads."""
+    r = out["roofline"]
+    return {"workload": out["config"]["name"], "label": out["config"]["workload"], "dtype": out["dtype"],
+            "strategy": out["config"]["strategy"], "steps": out["steps"],
+            "ms_per_step": out["ms_per_step"], "value": out["value"], "unit": out["unit"],
+            "pct_of_hbm_peak": out["pct_of_hbm_peak"], "step_ms_events": out["step_ms_events"],
+            "roofline": {"kernel": r["kernel"], "achieved": r["achieved"], "frac": r["frac"],
+                         "avg_ms": r["avg_ms"]}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="flat_f32",
+                    choices=["flat_f32", "flat_bf16", "flat_mixed", "mlr", "mf", "lda", "cnn", "cnn@1", "cnn@10",
+                             "cnn@50", "layers", "doctopic", "giant"])
+    ap.add_argument("--strategy", default="priority", choices=STRATEGIES,
+                    help="how K is chosen: the method (priority) or a comparison set-up of Section 5.4; "
+                         "full = every block saved and every block recovered (traditional checkpointing)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the bf16 copy and the MLR / MF / LDA / CNN-sized stores that the default "
+                         "run times after the headline workload")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the plain read / copy / read-two-write-one kernels (measured ceilings)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy three times (reference for HBM counters)")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="capture the cycle in a HIP graph and time its replays (needs --warmup >= 1)")
+    ap.add_argument("--print-source-hash", action="store_true",
+                    help="print the SHA-256 of the score kernel's sources and exit")
+    args = ap.parse_args()
+    if args.print_source_hash:
+        print(score_kernel_source_hash())
+        return
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on ONE GPU; --gpus %d is not supported (blocks would be "
+              "range-partitioned over GPUs and only the selection would exchange histograms)"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1810_07354_amd import scar
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    scar.lib()   # fail now if the HIP library is missing
+
+    if args.workload == "layers":
+        return main_layers(args)
+
+    if args.calibrate_copy:
+        # A plain copy of known size (1 GiB read, 1 GiB written per launch) so that a
+        # counter run of this command also shows what the HBM counters read for it.
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    headline = args.workload == "flat_f32" and args.strategy == "priority" and not args.hip_graph
+    out, store = run_workload(args.workload, dev, args.steps, args.warmup, args.strategy, args.hip_graph)
+    x, c, L, k, n_lost, nb, weights = store
+    if not args.no_cpu_baseline and args.strategy == "priority":
         threads = min(16, os.cpu_count() or 1)
-        sample = min(n_elems, 1 << 29)
-        sample -= sample % L
-        out["cpu_baseline"] = cpu_baseline(x, c, L, k / nb, n_lost / nb, sample, threads, weights)
+        out["cpu_baseline"] = cpu_baseline(x, c, L, k / nb, n_lost / nb, x.numel(), threads, weights)
+    store_bytes = x.numel() * x.element_size()
+    del x, c, weights, store
+    torch.cuda.empty_cache()
+
+    if not args.no_ceilings:
+        # the plain kernels on buffers of the store's size (at most 4 GiB per stream)
+        ce = measure_ceilings(dev, min(store_bytes, 1 << 32) // 16 * 16)
+        out["ceilings"] = ce
+        roof = out["roofline"]
+        shape = "read2" if args.strategy == "priority" else "read2_write1"
+        roof["ceiling_kernel"] = "scar_ceiling_" + shape
+        roof["read_ceiling_GBps" if shape == "read2" else "ceiling_GBps"] = ce[shape + "_GBps"]
+        roof["frac_of_ceiling"] = round(roof["achieved"] / ce[shape + "_GBps"], 4)
+        # every step of the cycle against the plain kernel of its access shape (event-to-event
+        # times, so each includes the launch gap before its first kernel)
+        per_step = {}
+        for step, shape in (("scores", "read2"), ("commit", "copy"), ("recover", "read2_write1")):
+            nbytes, ms = out["algorithmic_bytes_per_cycle"][step], out["step_ms_events"][step]
+            if nbytes and ms > 0:
+                gbs = nbytes / (ms * 1e-3) / 1e9
+                per_step[step] = {"GBps": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
+                                  "ceiling": "scar_ceiling_" + shape, "ceiling_GBps": ce[shape + "_GBps"],
+                                  "frac_of_ceiling": round(gbs / ce[shape + "_GBps"], 4)}
+        out["step_rooflines"] = per_step
+
+    if headline and not args.no_other_workloads:
+        others = []
+        for name in OTHER_WORKLOADS:
+            o, st = run_workload(name, dev, 20, 3)
+            others.append(brief(o))
+            del st
+            torch.cuda.empty_cache()
+        out["other_workloads"] = others
     print(json.dumps(out), flush=True)
 
 

@@ -123,10 +123,11 @@ size_t scar_workspace_bytes(uint64_t n_blocks);
  *   I32:        scores = int64_t[n_blocks], s_b = sum_j |x_j - c_j|, exact (for a row of
  *               topic counts this is twice the document-length-scaled total variation of
  *               Appendix C).
- * Reads x and c once; writes scores.  A block is summed by one workgroup at most, which suits
- * thousands of blocks and more; a store cut into a few hundred very long blocks is scanned at
- * full rate by scar_var_block_scores instead (its workspace lets many workgroups share a
- * block).  The copy calls below have no such limit: long rows are handed out in 4 KiB pieces. */
+ * Reads x and c once; writes scores.  Stores of at most 2,048 blocks of 256 KiB or more (a
+ * tensor cut into a few large shards) are scored in pieces by many workgroups per block; the
+ * pieces' sums wait in a fixed 512 KiB array inside the library (this call takes no workspace),
+ * so two calls of that kind must not overlap on one GPU.  SCAR_F32_BF16C stores keep one
+ * workgroup per block.  The copy calls below hand long rows out in 4 KiB pieces. */
 int scar_block_scores(const scar_layout* layout, const void* x, const void* c, void* scores,
                       void* stream);
 
@@ -150,6 +151,27 @@ int scar_block_scores_rows(const scar_layout* layout, const void* x, const void*
  *   score_type: SCAR_SCORE_F32 (float scores) or SCAR_SCORE_I64 (int64_t scores). */
 int scar_select_topk(int32_t score_type, const void* scores, uint32_t n_blocks, uint32_t k,
                      uint32_t* out_idx, void* workspace, size_t workspace_bytes, void* stream);
+
+/* scar_select_topk for 64-bit integer scores with a known upper bound.  A caller that scores
+ * an int32 store knows one without looking at the data: an L1 distance over block_len
+ * elements is at most block_len * (2^32 - 1).  The selection looks at the keys one 11-bit
+ * digit at a time, most significant first; the digits above the bound are the same in every
+ * key, and each pass not needed to find that out is a kernel launch saved (bound < 2^44:
+ * four passes instead of six; < 2^33: three; < 2^22: two).
+ *   score_max: every score is taken into [0, score_max]: a negative score counts as 0, a
+ *              larger one as score_max (so a wrong bound costs order among the offenders, no
+ *              more).  score_max >= 2^55 needs all six passes.  SCAR_SCORE_F32 scores
+ *              ignore the bound: exactly scar_select_topk. */
+int scar_select_topk_bounded(int32_t score_type, const void* scores, uint32_t n_blocks, uint32_t k,
+                             uint64_t score_max, uint32_t* out_idx, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+/* Testing aid.  The ordered write of scar_select_topk, scar_select_random and
+ * scar_mask_to_indices is a chained scan: a workgroup waits for the counts of the tiles before
+ * its own for at most `polls` polls (about a microsecond each; default 65,536) and then counts
+ * those tiles itself, which always ends.  0 forces that path.  Process-wide, host-side; not
+ * to be changed while calls are being made on other threads. */
+void scar_set_lookback_spin_limit(uint32_t polls);
 
 /* scar_select_topk for callers that cannot allocate device memory or hand over a workspace:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same

@@ -3,8 +3,8 @@
  * the checkpoint path (scar.h) are compared with.  They compute nothing of the method: each
  * has the memory access shape of one step of Section 4.3's cycle with the index lists,
  * block boundaries and arithmetic taken away, written with the same access style (16-byte
- * non-temporal accesses, four per lane and stream in flight, each XCD walking a contiguous
- * eighth of the range).
+ * non-temporal accesses, each XCD walking a contiguous eighth of the range) and launched in
+ * the shape that was measured fastest for it.
  *
  *   scar_ceiling_read2         reads a and b                  - the shape of scar_block_scores
  *   scar_ceiling_copy          reads a, writes b              - the shape of scar_checkpoint_commit

@@ -49,6 +49,25 @@ __device__ __forceinline__ uint32_t xcd_contiguous_block_id() {
   return (blockIdx.x % kXcds) * (gridDim.x / kXcds) + blockIdx.x / kXcds;
 }
 
+// The two-dimensional grids of the row kernels: x runs over the index list (`need_x` slots
+// hold entries, the rest is padding up to a multiple of 8), y over the pieces of a long row.
+// The hardware hands workgroups to the XCDs in the order x fastest, so with x renumbered as
+// above an XCD owns an eighth of the list with all its pieces - right for long lists.  A
+// short list of very long rows (two lost shards of 256 MiB) would leave the work to the XCDs
+// that own x = 0 and x = 1; there the host does not pad x, makes gridDim.y a multiple of 8, and
+// the whole grid is renumbered so that each XCD walks a contiguous eighth of the pieces of
+// every row.
+struct GridSlot {
+  uint32_t x, y;
+};
+__device__ __forceinline__ GridSlot row_grid_slot(uint64_t need_x) {
+  if (gridDim.y == 1 || need_x >= 256) return {xcd_contiguous_block_id(), blockIdx.y};  // host: row_grid
+  const uint32_t total = gridDim.x * gridDim.y;
+  const uint32_t lin = blockIdx.y * gridDim.x + blockIdx.x;
+  const uint32_t id = (lin % kXcds) * (total / kXcds) + lin / kXcds;
+  return {id % gridDim.x, id / gridDim.x};
+}
+
 // ---- per-element distance terms --------------------------------------------------
 
 // The square is rounded to float32 on its own, never fused into a following addition: where

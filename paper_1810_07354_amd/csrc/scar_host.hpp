@@ -132,6 +132,28 @@ inline uint32_t piece_grid(uint32_t pieces, uint32_t grid_x, uint64_t cap) {
   return y ? (uint32_t)y : 1;
 }
 
+// Grid of a row kernel: x over the `need_x` workgroup-sized slots of the index list, y over
+// the pieces.  Long lists: x padded to a multiple of 8 (each XCD an eighth of the list, see
+// xcd_contiguous_block_id), y as piece_grid says.  A list of fewer than kRowSpreadBelow slots
+// whose rows are cut into pieces is spread over the XCDs by its pieces instead (row_grid_slot
+// on the device applies the same rule): x is not padded - padding would be idle workgroups,
+// seven in eight for a list of one slot - and y is a multiple of 8.
+constexpr uint64_t kRowSpreadBelow = 256;
+struct RowGrid {
+  uint32_t x, y;
+};
+inline RowGrid row_grid(uint64_t need_x, uint32_t pieces, uint64_t cap) {
+  if (pieces > 1 && need_x > 0 && need_x < kRowSpreadBelow) {
+    uint64_t y = cap / need_x;
+    if (y > pieces) y = pieces;
+    if (y > 65528) y = 65528;
+    y = y < 8 ? 8 : y / 8 * 8;
+    return {(uint32_t)need_x, (uint32_t)y};
+  }
+  const uint32_t x = xcd_grid(need_x, cap);
+  return {x, piece_grid(pieces, x, cap)};
+}
+
 // Second stage of the norm (defined with the row kernels): adds n_partial partial sums
 // (double, or uint64 for SCAR_I32) in a fixed order and writes *out.
 void launch_finish(int32_t dtype, const void* partial, uint32_t n_partial, scar_norm* out,

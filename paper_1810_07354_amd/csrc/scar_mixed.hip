@@ -235,8 +235,9 @@ __global__ __launch_bounds__(kWG) void k_mixed_commit(const float* __restrict__ 
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
   const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
-  for (uint32_t piece = blockIdx.y; piece < pieces; piece += gridDim.y) {
-    for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
+  const GridSlot slot = row_grid_slot(((uint64_t)n_idx + GPW - 1) / GPW);
+  for (uint32_t piece = slot.y; piece < pieces; piece += gridDim.y) {
+    for (uint64_t i = (uint64_t)slot.x * GPW + grp; i < n_idx;
          i += (uint64_t)gridDim.x * GPW) {
       uint64_t off;
       uint32_t first, len;
@@ -274,8 +275,9 @@ __global__ __launch_bounds__(T) void k_mixed_recover(float* __restrict__ x, cons
   const uint32_t grp = threadIdx.x / G;
   __shared__ double slots[T / kWave];
   double acc = 0;
-  for (uint32_t piece = blockIdx.y; piece < pieces; piece += gridDim.y) {
-    for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
+  const GridSlot slot = row_grid_slot(((uint64_t)n_idx + GPW - 1) / GPW);
+  for (uint32_t piece = slot.y; piece < pieces; piece += gridDim.y) {
+    for (uint64_t i = (uint64_t)slot.x * GPW + grp; i < n_idx;
          i += (uint64_t)gridDim.x * GPW) {
       uint64_t off;
       uint32_t first, len;
@@ -410,8 +412,8 @@ int mixed_commit(const scar_layout* l, uint32_t n_blocks, const void* x, void* c
 #define CALL(G)                                                                                     \
   {                                                                                                 \
     constexpr int GPW = (G == 256) ? 1 : kWG / G;                                                   \
-    const uint32_t grid = xcd_grid(((uint64_t)n_idx + GPW - 1) / GPW, kCopyGridCap);                \
-    launch((k_mixed_commit<G>), dim3(grid, piece_grid(pieces, grid, kCopyGridCap)),     \
+    const RowGrid rg = row_grid(((uint64_t)n_idx + GPW - 1) / GPW, pieces, kCopyGridCap);           \
+    launch((k_mixed_commit<G>), dim3(rg.x, rg.y),                                                   \
                        dim3(kWG), 0, st, (const float*)x, (uint16_t*)c, idx, n_idx,                 \
                        (uint16_t*)staging, l->n_elems, l->block_len, n_blocks, pieces, vec, vec_st); \
   }
@@ -428,14 +430,14 @@ static uint32_t launch_mixed_recover(int g, const scar_layout* l, uint32_t n_blo
   constexpr int kWide = 1024;
 #define LAUNCH(G, T)                                                                                  \
   {                                                                                                   \
-    grid = xcd_grid(((uint64_t)n_idx + (T / G) - 1) / (T / G), kMaxNormGrid);                         \
-    grid_y = piece_grid(pieces, grid, kMaxNormGrid);                                                  \
+    const RowGrid rg = row_grid(((uint64_t)n_idx + (T / G) - 1) / (T / G), pieces, kMaxNormGrid);     \
+    grid = rg.x, grid_y = rg.y;                                                                       \
     launch((k_mixed_recover<G, T, STORE, NORM>), dim3(grid, grid_y), dim3(T), 0, st,      \
                        (float*)x, (const uint16_t*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, \
                        pieces, vec, packed, (double*)partial);                                        \
   }
 #define CALL(G)                                                       \
-  if (((uint64_t)n_idx * pieces * G + kWG - 1) / kWG >= 8192)         \
+  if (n_idx >= 64 && ((uint64_t)n_idx * pieces * G + kWG - 1) / kWG >= 8192) \
     LAUNCH(G, kWide)                                                  \
   else                                                                \
     LAUNCH(G, kWG)

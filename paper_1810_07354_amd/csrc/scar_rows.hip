@@ -46,8 +46,9 @@ __global__ __launch_bounds__(kWG) void k_commit(const char* __restrict__ x, char
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
   const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
-  for (uint32_t piece = blockIdx.y; piece < pieces; piece += gridDim.y) {
-    for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
+  const GridSlot slot = row_grid_slot(((uint64_t)n_idx + GPW - 1) / GPW);
+  for (uint32_t piece = slot.y; piece < pieces; piece += gridDim.y) {
+    for (uint64_t i = (uint64_t)slot.x * GPW + grp; i < n_idx;
          i += (uint64_t)gridDim.x * GPW) {
       RowPiece rp;
       if (!row_piece<sizeof(W)>(idx[i], piece, pieces, n_blocks, n_elems, block_len, &rp)) continue;
@@ -165,8 +166,9 @@ __global__ __launch_bounds__(T, T / 128) void k_recover(char* __restrict__ x, co
   __shared__ acc_t slots[T / kWave];
   acc_t acc = 0;
 
-  for (uint32_t piece = blockIdx.y; piece < pieces; piece += gridDim.y) {
-    for (uint64_t i = (uint64_t)xcd_contiguous_block_id() * GPW + grp; i < n_idx;
+  const GridSlot slot = row_grid_slot(((uint64_t)n_idx + GPW - 1) / GPW);
+  for (uint32_t piece = slot.y; piece < pieces; piece += gridDim.y) {
+    for (uint64_t i = (uint64_t)slot.x * GPW + grp; i < n_idx;
          i += (uint64_t)gridDim.x * GPW) {
       const uint32_t b = idx ? idx[i] : (uint32_t)i;
       RowPiece rp;
@@ -218,8 +220,9 @@ __global__ __launch_bounds__(kWG) void k_norm_wide(const char* __restrict__ x, c
 #pragma unroll
   for (int q = 0; q < kVirtual; ++q) acc[q] = 0;
 
-  for (uint32_t piece = blockIdx.y; piece < pieces; piece += gridDim.y) {
-    for (uint64_t i0 = (uint64_t)xcd_contiguous_block_id() * GPW; i0 < n_idx; i0 += (uint64_t)gridDim.x * GPW) {
+  const GridSlot slot = row_grid_slot(((uint64_t)n_idx + GPW - 1) / GPW);
+  for (uint32_t piece = slot.y; piece < pieces; piece += gridDim.y) {
+    for (uint64_t i0 = (uint64_t)slot.x * GPW; i0 < n_idx; i0 += (uint64_t)gridDim.x * GPW) {
       const char* xb[kVirtual];
       const char* cb[kVirtual];
       uint32_t len[kVirtual], lane[kVirtual];
@@ -369,9 +372,8 @@ static void launch_commit(const scar_layout* l, const void* x, void* c, const ui
                           uint32_t n_idx, void* staging, uint32_t n_blocks, uint32_t pieces, bool vec,
                           bool vec_st, hipStream_t st) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
-  const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
-  const uint32_t grid = xcd_grid(need, kCopyGridCap);
-  launch((k_commit<G, W>), dim3(grid, piece_grid(pieces, grid, kCopyGridCap)), dim3(kWG), 0, st, (const char*)x, (char*)c, idx,
+  const RowGrid rg = row_grid(((uint64_t)n_idx + GPW - 1) / GPW, pieces, kCopyGridCap);
+  launch((k_commit<G, W>), dim3(rg.x, rg.y), dim3(kWG), 0, st, (const char*)x, (char*)c, idx,
                      n_idx, (char*)staging, l->n_elems, l->block_len, n_blocks, pieces, vec, vec_st);
 }
 
@@ -404,15 +406,15 @@ static uint32_t row_pieces(const scar_layout* l, int eb, bool vec) {
 // Launches the recovery / norm kernel; returns the number of partial sums it writes.
 constexpr int kWideWG = 1024;
 constexpr uint64_t kWideFrom = 8192;   // workgroups of kWG threads from which kWideWG is used
+constexpr uint32_t kWideMinEntries = 64;
 
 template <int DT, int G, int T, bool STORE, bool NORM, bool VEC>
 static uint32_t launch_recover_t(const scar_layout* l, void* x, const void* c, const uint32_t* idx,
                                  uint32_t n_idx, uint32_t n_blocks, uint32_t pieces, bool packed,
                                  void* partial, const float* weights, hipStream_t st) {
   constexpr int GPW = T / G;
-  const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
-  const uint32_t grid = xcd_grid(need, kMaxNormGrid);
-  const uint32_t grid_y = piece_grid(pieces, grid, kMaxNormGrid);
+  const RowGrid rg = row_grid(((uint64_t)n_idx + GPW - 1) / GPW, pieces, kMaxNormGrid);
+  const uint32_t grid = rg.x, grid_y = rg.y;
   launch((k_recover<DT, G, T, STORE, NORM, VEC>), dim3(grid, grid_y), dim3(T), 0, st, (char*)x,
                      (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, pieces, packed,
                      (typename Acc<DT>::type*)partial, weights);
@@ -425,13 +427,13 @@ static uint32_t launch_recover(const scar_layout* l, void* x, const void* c, con
                                void* partial, const float* weights, hipStream_t st) {
   if (!vec)
     return launch_recover_t<DT, G, kWG, STORE, NORM, false>(l, x, c, idx, n_idx, n_blocks, pieces, packed, partial, weights, st);
-  if (((uint64_t)n_idx * pieces * G + kWG - 1) / kWG >= kWideFrom) {
+  // (a list shorter than the groups of a few wide workgroups would leave most of them idle)
+  if (n_idx >= kWideMinEntries && ((uint64_t)n_idx * pieces * G + kWG - 1) / kWG >= kWideFrom) {
     if constexpr (!STORE && NORM) {  // read-only: the same sums from a kernel with more loads in flight
       static_assert(kWideWG == kWG * kVirtual, "k_norm_wide stands in for the wide kernel");
       constexpr int GPW = kWideWG / G;
-      const uint64_t need = ((uint64_t)n_idx + GPW - 1) / GPW;
-      const uint32_t grid = xcd_grid(need, kMaxNormGrid);
-      const uint32_t grid_y = piece_grid(pieces, grid, kMaxNormGrid);
+      const RowGrid rg = row_grid(((uint64_t)n_idx + GPW - 1) / GPW, pieces, kMaxNormGrid);
+      const uint32_t grid = rg.x, grid_y = rg.y;
       launch((k_norm_wide<DT, G>), dim3(grid, grid_y), dim3(kWG),
                          0, st, (const char*)x,
                          (const char*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, pieces, packed,

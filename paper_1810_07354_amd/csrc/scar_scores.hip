@@ -6,6 +6,8 @@
 // back to back (kUnroll of each before the first use), the per-lane sums are combined
 // with wavefront shuffles (G <= 64) or shuffles plus one LDS step (G = 256).  Loads are
 // non-temporal and each XCD walks one contiguous eighth of the store.
+#include <mutex>
+
 #include "scar_device.hpp"
 #include "scar_host.hpp"
 
@@ -383,6 +385,133 @@ static bool dispatch_scores_flat(int g, bool split, const scar_layout* l, const 
 #undef SCAR_FLAT
 }
 
+// ---- a few very long blocks --------------------------------------------------------------
+// One workgroup per block leaves most of the chip idle when a store has fewer blocks than the
+// chip has room for workgroups (16 shards of 2^26 elements: 16 of 256 compute units).  Such
+// blocks are cut into `ppb` pieces of `piece_elems` elements (whole 16-byte steps), one
+// workgroup each; a piece's sum goes to partial[entry * ppb + piece] and a second kernel adds a
+// block's pieces in a fixed order (reproducible, no atomics).  The pieces depend only on the
+// layout, so listed blocks (scar_block_scores_rows) get bit for bit the scores of the full scan.
+//
+// The partial sums live in a fixed array inside the library's code object (512 KiB per GPU;
+// scar_block_scores takes no workspace): calls of this kind on one GPU share it and must not
+// overlap.  In host code the array's name is only a handle; its device address is asked for
+// once per device and kept.
+constexpr uint32_t kGiantMaxPartials = 65536;
+constexpr uint32_t kGiantMaxBlocks = 2048;            // more blocks than this fill the chip by themselves
+constexpr uint64_t kGiantMinRowBytes = 256 * 1024;    // shorter rows: a workgroup per row is fine
+constexpr uint32_t kGiantPieceBytes = 64 * 1024;      // per stream and workgroup, at least
+static __device__ __align__(256) unsigned long long giant_partials[kGiantMaxPartials];
+
+constexpr int kGiantMaxDevices = 64;
+static void* g_giant_ptr[kGiantMaxDevices];
+static std::mutex g_giant_mutex;
+
+static void* giant_partials_of_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kGiantMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_giant_mutex);
+  if (!g_giant_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(giant_partials)) != hipSuccess) return nullptr;
+    g_giant_ptr[dev] = p;
+  }
+  return g_giant_ptr[dev];
+}
+
+template <int DT, bool VEC>
+__global__ __launch_bounds__(kWG) void k_giant_pieces(const char* __restrict__ x, const char* __restrict__ c,
+                                                      uint64_t n_elems, uint32_t block_len, uint32_t n_blocks,
+                                                      uint32_t ppb, uint32_t piece_elems,
+                                                      const uint32_t* __restrict__ idx, uint32_t first_entry,
+                                                      uint32_t n_entries,
+                                                      typename Acc<DT>::type* __restrict__ partial) {
+  using acc_t = typename Acc<DT>::type;
+  __shared__ acc_t slots[kWG / kWave];
+  const uint64_t total = (uint64_t)n_entries * ppb;
+  for (uint64_t w = xcd_contiguous_block_id(); w < total; w += gridDim.x) {
+    const uint32_t e = (uint32_t)(w / ppb), piece = (uint32_t)(w % ppb);
+    const uint64_t b = idx ? idx[first_entry + e] : first_entry + e;
+    acc_t acc = 0;
+    if (b < n_blocks) {
+      const BlockSpan sp = block_span(b, n_elems, block_len, elem_bytes(DT));
+      const uint64_t lo = (uint64_t)piece * piece_elems;
+      if (lo < sp.len) {
+        const uint32_t len = (uint32_t)(sp.len - lo < piece_elems ? sp.len - lo : piece_elems);
+        const uint64_t off = sp.byte_off + lo * elem_bytes(DT);
+        acc = block_distance<DT, 256, VEC>(x + off, c + off, len, threadIdx.x);
+      }
+    }
+    acc = workgroup_sum(acc, slots);
+    if (threadIdx.x == 0) partial[w] = acc;
+  }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_giant_finish(const typename Acc<DT>::type* __restrict__ partial,
+                                                      uint32_t ppb, uint32_t n_blocks,
+                                                      const uint32_t* __restrict__ idx, uint32_t first_entry,
+                                                      const float* __restrict__ weights, void* __restrict__ scores) {
+  using acc_t = typename Acc<DT>::type;
+  __shared__ acc_t slots[kWG / kWave];
+  const uint32_t e = blockIdx.x;
+  const uint64_t b = idx ? idx[first_entry + e] : first_entry + e;
+  if (b >= n_blocks) return;
+  acc_t acc = 0;
+  for (uint32_t p = threadIdx.x; p < ppb; p += kWG) acc += partial[(uint64_t)e * ppb + p];
+  acc = workgroup_sum(acc, slots);
+  if (threadIdx.x == 0) {
+    if constexpr (DT == DT_I32)
+      ((long long*)scores)[b] = (long long)acc;
+    else if constexpr (is_tv(DT))
+      ((float*)scores)[b] = (float)(0.5 * acc * (double)(weights ? weights[b] : 1.f));
+    else
+      ((float*)scores)[b] = (float)acc;
+  }
+}
+
+// True if the layout is scored by pieces; ppb / piece_elems receive the cut.
+static bool giant_geometry(const scar_layout* l, int eb, uint32_t n_blocks, uint32_t* ppb, uint32_t* piece_elems) {
+  const uint64_t row_bytes = (uint64_t)l->block_len * eb;
+  if (n_blocks == 0 || n_blocks > kGiantMaxBlocks || row_bytes < kGiantMinRowBytes) return false;
+  uint64_t pieces = (row_bytes + kGiantPieceBytes - 1) / kGiantPieceBytes;
+  const uint64_t room = kGiantMaxPartials / n_blocks;
+  if (pieces > room) pieces = room;
+  // whole 16-byte steps per piece, so that every piece starts as aligned as its block does
+  const uint64_t per = 16 / eb;
+  uint64_t pe = ((uint64_t)l->block_len + pieces - 1) / pieces;
+  pe = (pe + per - 1) / per * per;
+  *piece_elems = (uint32_t)pe;
+  *ppb = (uint32_t)(((uint64_t)l->block_len + pe - 1) / pe);
+  return true;
+}
+
+template <int DT>
+static int launch_giant(const scar_layout* l, const void* x, const void* c, void* scores, uint32_t n_blocks,
+                        bool vec, const float* weights, const uint32_t* idx, uint32_t n_idx, uint32_t ppb,
+                        uint32_t piece_elems, hipStream_t st) {
+  using acc_t = typename Acc<DT>::type;
+  acc_t* partial = (acc_t*)giant_partials_of_current_device();
+  if (!partial) return SCAR_ERR_DEVICE;
+  const uint32_t n_items = idx ? n_idx : n_blocks;
+  const uint32_t per_launch = kGiantMaxPartials / ppb;  // >= n_blocks by construction
+  for (uint32_t first = 0; first < n_items; first += per_launch) {
+    const uint32_t n_entries = n_items - first < per_launch ? n_items - first : per_launch;
+    const uint64_t total = (uint64_t)n_entries * ppb;
+    const uint32_t grid = xcd_grid(total, kScoreGridCap);
+    const size_t lds = stream_lds_bytes(total, 2 * 16 * kWG * kUnroll);
+    if (vec)
+      launch((k_giant_pieces<DT, true>), dim3(grid), dim3(kWG), lds, st, (const char*)x, (const char*)c,
+             l->n_elems, l->block_len, n_blocks, ppb, piece_elems, idx, first, n_entries, partial);
+    else
+      launch((k_giant_pieces<DT, false>), dim3(grid), dim3(kWG), lds, st, (const char*)x, (const char*)c,
+             l->n_elems, l->block_len, n_blocks, ppb, piece_elems, idx, first, n_entries, partial);
+    launch((k_giant_finish<DT>), dim3(n_entries), dim3(kWG), 0, st, (const acc_t*)partial, ppb, n_blocks, idx,
+           first, weights, scores);
+  }
+  return launch_status();
+}
+
 template <int DT>
 static void dispatch_scores(int g, const scar_layout* l, const void* x, const void* c, void* scores,
                             uint32_t n_blocks, bool vec, const float* weights, const uint32_t* idx,
@@ -438,6 +567,19 @@ static int block_scores(bool tv, bool listed, const scar_layout* layout, const v
       default: done = launch_scores_tiny<DT_I32>(layout, x, c, scores, st); break;
     }
     if (done) return launch_status();
+  }
+  // a few very long blocks: cut into pieces, many workgroups per block
+  uint32_t ppb = 0, piece_elems = 0;
+  if (giant_geometry(layout, eb, n, &ppb, &piece_elems)) {
+    const bool vec_pieces = aligned(x, 16) && aligned(c, 16) && row_bytes % 16 == 0;
+    if (tv && layout->dtype == SCAR_F32)
+      return launch_giant<DT_F32_TV>(layout, x, c, scores, n, vec_pieces, weights, idx, n_idx, ppb, piece_elems, st);
+    if (tv) return launch_giant<DT_BF16_TV>(layout, x, c, scores, n, vec_pieces, weights, idx, n_idx, ppb, piece_elems, st);
+    switch (layout->dtype) {
+      case SCAR_F32: return launch_giant<DT_F32>(layout, x, c, scores, n, vec_pieces, nullptr, idx, n_idx, ppb, piece_elems, st);
+      case SCAR_BF16: return launch_giant<DT_BF16>(layout, x, c, scores, n, vec_pieces, nullptr, idx, n_idx, ppb, piece_elems, st);
+      default: return launch_giant<DT_I32>(layout, x, c, scores, n, vec_pieces, nullptr, idx, n_idx, ppb, piece_elems, st);
+    }
   }
   // many short rows of an aligned store: read as runs of whole rows
   const bool split = row_bytes % 16 != 0;

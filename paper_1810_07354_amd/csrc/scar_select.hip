@@ -11,9 +11,10 @@
 // After the last pass every key > T is selected together with the first `take` keys
 // equal to T in index order, where take = k - #(keys > T).
 //
-// The chosen indices are then written in ascending order by a two-level prefix sum
-// (per-tile counts, prefix over the tiles, per-tile write), so the result does not
-// depend on the order in which workgroups run.
+// The chosen indices are then written in ascending order by one kernel: every workgroup
+// classifies one tile of 2,048 keys, publishes its counts and looks back over the tiles
+// before it for the sum of theirs (a chained scan), so the result does not depend on the
+// order in which workgroups run.
 #include <mutex>
 
 #include "scar_device.hpp"
@@ -23,7 +24,6 @@ namespace scar {
 
 constexpr int kMaxBins = 2048;
 constexpr int kMaxPasses = 6;
-constexpr uint32_t kTileGridCap = 1u << 14;
 constexpr int kKeysPerThread = kTileKeys / kWG;  // 8 consecutive keys per thread
 // A histogram pass reads its keys from wherever the score kernel left them (usually another
 // XCD's L2 or HBM), so many small tiles - many loads in flight - beat few large ones, although
@@ -39,7 +39,17 @@ struct KeyArgs {
   const void* ptr;
   uint64_t seed;
   uint64_t draw;
+  // 64-bit integer scores: number of 11-bit digits (6 covers all 64 bits) and, when `bounded`,
+  // the largest score the caller vouches for - scores are then clamped into [0, cap], whose
+  // keys fit `passes` digits
+  int passes;
+  int bounded;
+  unsigned long long cap;
 };
+
+inline KeyArgs key_args(const void* ptr, uint64_t seed = 0, uint64_t draw = 0) {
+  return KeyArgs{ptr, seed, draw, 6, 0, ~0ull};
+}
 
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy as 1, 2,
 // 3", SC'11), first output word: ten rounds of
@@ -81,9 +91,9 @@ struct Key;
 template <>
 struct Key<SRC_F32> {
   using type = uint32_t;
-  static constexpr int passes = 3;
-  __device__ static int shift(int p) { return p == 0 ? 21 : (p == 1 ? 10 : 0); }
-  __device__ static int bits(int p) { return p == 2 ? 10 : 11; }
+  __host__ __device__ static int passes(const KeyArgs&) { return 3; }
+  __device__ static int shift(const KeyArgs&, int p) { return p == 0 ? 21 : (p == 1 ? 10 : 0); }
+  __device__ static int bits(const KeyArgs&, int p) { return p == 2 ? 10 : 11; }
   __device__ static type load(const KeyArgs& a, uint64_t i) {
     uint32_t u = __float_as_uint(((const float*)a.ptr)[i]);
     if ((u & 0x7fffffffu) > 0x7f800000u) return 0xffffffffu;  // NaN: above everything
@@ -92,14 +102,23 @@ struct Key<SRC_F32> {
   }
 };
 
+// 64-bit integer scores: `passes` digits of 11 bits, the last one at bit 0.  Six digits cover
+// every int64 (the first then holds the top 9 bits); a caller who knows an upper bound of
+// the scores gets fewer (scar_select_topk_bounded): the digits above the bound are the same
+// in every key, and a pass that can only find that out is a launch saved.
 template <>
 struct Key<SRC_I64> {
   using type = unsigned long long;
-  static constexpr int passes = 6;
-  __device__ static int shift(int p) { return p == 5 ? 0 : 53 - 11 * p; }
-  __device__ static int bits(int p) { return p == 5 ? 9 : 11; }
+  __host__ __device__ static int passes(const KeyArgs& a) { return a.passes; }
+  __device__ static int shift(const KeyArgs& a, int p) { return 11 * (a.passes - 1 - p); }
+  __device__ static int bits(const KeyArgs&, int) { return 11; }
   __device__ static type load(const KeyArgs& a, uint64_t i) {
-    return (unsigned long long)((const long long*)a.ptr)[i] ^ 0x8000000000000000ull;
+    const long long v = ((const long long*)a.ptr)[i];
+    if (a.bounded) {
+      const unsigned long long u = v < 0 ? 0ull : (unsigned long long)v;
+      return u > a.cap ? a.cap : u;
+    }
+    return (unsigned long long)v ^ 0x8000000000000000ull;
   }
 };
 
@@ -108,9 +127,9 @@ struct Key<SRC_I64> {
 template <>
 struct Key<SRC_RANDOM> {
   using type = uint32_t;
-  static constexpr int passes = 3;
-  __device__ static int shift(int p) { return p == 0 ? 21 : (p == 1 ? 10 : 0); }
-  __device__ static int bits(int p) { return p == 2 ? 10 : 11; }
+  __host__ __device__ static int passes(const KeyArgs&) { return 3; }
+  __device__ static int shift(const KeyArgs&, int p) { return p == 0 ? 21 : (p == 1 ? 10 : 0); }
+  __device__ static int bits(const KeyArgs&, int p) { return p == 2 ? 10 : 11; }
   __device__ static type load(const KeyArgs& a, uint64_t i) {
     return philox4x32_10_word0((uint32_t)i, 0u, (uint32_t)a.draw, (uint32_t)(a.draw >> 32),
                                (uint32_t)a.seed, (uint32_t)(a.seed >> 32));
@@ -120,6 +139,7 @@ struct Key<SRC_RANDOM> {
 template <>
 struct Key<SRC_MASK> {  // only classified, never histogrammed
   using type = uint32_t;
+  __host__ __device__ static int passes(const KeyArgs&) { return 0; }
   __device__ static type load(const KeyArgs& a, uint64_t i) { return ((const uint8_t*)a.ptr)[i] ? 1u : 0u; }
 };
 
@@ -147,12 +167,16 @@ __device__ __forceinline__ T workgroup_exclusive_scan(T v, T* slots, T* total) {
   return base + inc - v;
 }
 
-// One workgroup zeroes the histograms and sets the state before the first pass.
-__global__ __launch_bounds__(kWG) void k_select_clear(SelectWs* ws, uint32_t k) {
+// Zeroes the histograms and the per-tile words of the compaction, and sets the state before
+// the first pass.  `ws_words`: 32-bit words of the selection scratch to clear.
+__global__ __launch_bounds__(kWG) void k_select_clear(SelectWs* ws, uint32_t ws_words, uint32_t k,
+                                                      unsigned long long* __restrict__ tile_state,
+                                                      uint32_t n_tiles) {
   uint32_t* words = (uint32_t*)ws;
-  for (uint32_t i = threadIdx.x; i < sizeof(SelectWs) / 4; i += kWG) words[i] = 0;
-  __syncthreads();
-  if (threadIdx.x == 0) ws->state[0].k_rem = k;
+  const uint32_t tid = blockIdx.x * kWG + threadIdx.x, nthreads = gridDim.x * kWG;
+  for (uint32_t i = tid; i < ws_words; i += nthreads)
+    words[i] = (i == offsetof(SelectWs, state[0].k_rem) / 4) ? k : 0u;
+  for (uint32_t t = tid; t < n_tiles; t += nthreads) tile_state[t] = 0ull;
 }
 
 // Given the finished histogram of one digit and the state before that digit, walk the
@@ -221,11 +245,11 @@ __global__ __launch_bounds__(kWG) void k_select_hist(const KeyArgs scores, uint3
   if (tile < n_tiles) load_tile(tile, key);
   SelectState cur = ws->state[pass == 0 ? 0 : pass - 1];
   if (pass > 0) {
-    cur = next_state(ws->hist[pass - 1], K::bits(pass - 1), cur, scratch, &shared_state);
+    cur = next_state(ws->hist[pass - 1], K::bits(scores, pass - 1), cur, scratch, &shared_state);
     if (blockIdx.x == 0 && threadIdx.x == 0) ws->state[pass] = cur;
   }
   __syncthreads();
-  const int shift = K::shift(pass), bits = K::bits(pass);
+  const int shift = K::shift(scores, pass), bits = K::bits(scores, pass);
   const uint32_t mask = (1u << bits) - 1;
   while (tile < n_tiles) {
     const uint64_t base = (uint64_t)tile * kHistTileKeys + threadIdx.x;
@@ -261,6 +285,102 @@ __global__ __launch_bounds__(kWG) void k_select_hist(const KeyArgs scores, uint3
     if (lh[b]) atomicAdd(&gh[b], lh[b]);
 }
 
+// ---- ordered compaction in one kernel ---------------------------------------------------
+// Workgroup t classifies tile t of kTileKeys keys, counts its keys above and equal to the
+// threshold, publishes the counts in the tile's 64-bit word and adds up the words of the
+// tiles before it, a workgroup's width at a time, until it meets a tile that already knows
+// its own running total (a chained scan with look-back).  A word carries its own validity:
+// bits 63-62 say what it holds (0 nothing yet, 1 the tile's own counts, 2 the running total up
+// to and including the tile), bits 61-31 the keys equal to the threshold, bits 30-0 the keys
+// above it.  It is written and read with single relaxed device-scope atomic accesses; nothing
+// else has to be ordered, so there is no fence.  The words are zeroed by k_select_clear.
+//
+// A workgroup only ever waits for tiles with lower numbers, and the hardware starts the
+// workgroups of a grid in the order of their numbers (per XCD), so the tiles waited for are
+// running or done.  (Handing tiles out by a ticket - one atomic counter - would not depend on
+// that order, but 512 adds to one address cost 8 us on 2^20 keys.)  The kernel's end does not
+// depend on it either: the wait is bounded.  After `spin_limit` polls a workgroup stops
+// waiting and counts the keys of all earlier tiles itself - slow, but it always ends, and the
+// result is the same.
+constexpr unsigned long long kTileOwn = 1ull << 62, kTileRunning = 2ull << 62, kTileFlags = 3ull << 62;
+constexpr unsigned long long kTilePayload = ~kTileFlags;
+constexpr int kEqualShift = 31;
+constexpr uint32_t kFieldMask = 0x7fffffffu;
+
+__device__ __forceinline__ unsigned long long tile_word_load(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void tile_word_store(unsigned long long* p, unsigned long long v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+  for (int m = kWave / 2; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+  return v;
+}
+
+// Called by the whole workgroup: publishes `own` (the payload of tile `tile`) and returns the
+// summed payloads of tiles 0 .. tile-1 in every thread.  Each of the four wavefronts polls 64
+// of the 256 tiles of a window; the nearest tile with a running total ends the walk.
+// *gave_up (LDS) is set if a predecessor's word did not appear within spin_limit polls (the
+// return value is then void).  `part`, `found`: LDS for one value per wavefront.
+__device__ __forceinline__ unsigned long long look_back(unsigned long long* __restrict__ tile_state,
+                                                        uint32_t tile, unsigned long long own,
+                                                        uint32_t spin_limit, int* gave_up,
+                                                        unsigned long long* part, int* found) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  if (threadIdx.x == 0) {
+    *gave_up = 0;
+    tile_word_store(&tile_state[tile], (tile == 0 ? kTileRunning : kTileOwn) | own);
+  }
+  __syncthreads();
+  if (tile == 0) return 0;
+  unsigned long long running = 0;
+  long long top = (long long)tile - 1;  // highest tile of the window still to be added
+  for (;;) {
+    const long long t = top - wave * kWave - lane;
+    unsigned long long w;
+    uint32_t polls = 0;
+    bool timed_out = false;
+    for (;;) {
+      // tiles before the first count as a running total of nothing
+      w = t >= 0 ? tile_word_load(&tile_state[t]) : kTileRunning;
+      if (__ballot((w & kTileFlags) == 0) == 0) break;
+      if (++polls > spin_limit) {
+        timed_out = true;
+        break;
+      }
+      __builtin_amdgcn_s_sleep(1);
+    }
+    const unsigned long long has_total = __ballot((w & kTileFlags) == kTileRunning);
+    const int first = has_total ? __ffsll((long long)has_total) - 1 : kWave;
+    const unsigned long long sum = wave_sum(lane <= first ? (w & kTilePayload) : 0ull);
+    if (lane == 0) {
+      part[wave] = sum;
+      found[wave] = has_total != 0;
+      if (timed_out) *gave_up = 1;
+    }
+    __syncthreads();
+    bool done = false;
+    unsigned long long add = 0;
+#pragma unroll
+    for (int v = 0; v < kWG / kWave; ++v) {
+      if (!done) add += part[v];
+      done = done || found[v];
+    }
+    const int stop = *gave_up;
+    __syncthreads();  // the slots are rewritten in the next round
+    if (stop) return 0;
+    running += add;
+    if (done) break;
+    top -= kWG;
+  }
+  if (threadIdx.x == 0) tile_word_store(&tile_state[tile], kTileRunning | (running + own));
+  return running;
+}
+
 // 0 = not selected on its own, 1 = above the threshold, 2 = equal to the threshold.
 template <int SRC>
 __device__ __forceinline__ int classify(const KeyArgs& src, uint64_t i, typename Key<SRC>::type T) {
@@ -269,115 +389,83 @@ __device__ __forceinline__ int classify(const KeyArgs& src, uint64_t i, typename
   return key > T ? 1 : (key == T ? 2 : 0);
 }
 
-// Per-tile counts of (above, equal), packed as low / high 32 bits.  For a selection the
-// threshold is first derived from the last pass's histogram, as in k_select_hist.
+// Writes the selected indices at their final, ascending positions; grid = n_tiles.  For a
+// selection the threshold is first derived from the last pass's histogram, as in
+// k_select_hist.  out_count (mask compaction): receives the number of indices written.
 template <int SRC>
-__global__ __launch_bounds__(kWG) void k_compact_count(const KeyArgs src, uint32_t n,
-                                                       uint32_t n_tiles, int passes,
-                                                       SelectWs* __restrict__ ws,
-                                                       unsigned long long* __restrict__ tile_cnt) {
-  using key_t = typename Key<SRC>::type;
-  __shared__ unsigned long long slots[kWG / kWave];
-  __shared__ uint32_t scratch[kWG / kWave + 1];
-  __shared__ SelectState shared_state;
-  key_t T = 0;
-  if constexpr (SRC != SRC_MASK) {
-    const SelectState fin = next_state(ws->hist[passes - 1], Key<SRC>::bits(passes - 1),
-                                       ws->state[passes - 1], scratch, &shared_state);
-    if (blockIdx.x == 0 && threadIdx.x == 0) ws->state[passes] = fin;
-    T = (key_t)fin.prefix;
-  }
-  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-    const uint64_t base = (uint64_t)tile * kTileKeys + threadIdx.x * kKeysPerThread;
-    unsigned long long cnt = 0;
-#pragma unroll
-    for (int j = 0; j < kKeysPerThread; ++j) {
-      if (base + j < n) {
-        const int cls = classify<SRC>(src, base + j, T);
-        cnt += cls == 1 ? 1ull : (cls == 2 ? (1ull << 32) : 0ull);
-      }
-    }
-    cnt = workgroup_sum(cnt, slots);
-    if (threadIdx.x == 0) tile_cnt[tile] = cnt;
-  }
-}
-
-// Exclusive prefix sums of the per-tile counts, in place, by one workgroup; used when
-// there are too many tiles for every writer to add up its predecessors itself.
-__global__ __launch_bounds__(kWG) void k_compact_scan(unsigned long long* __restrict__ tile_cnt,
-                                                      uint32_t n_tiles, uint32_t* __restrict__ out_count) {
-  __shared__ unsigned long long slots[kWG / kWave + 1];
-  unsigned long long running = 0;
-  for (uint32_t t0 = 0; t0 < n_tiles; t0 += kWG) {
-    const uint32_t t = t0 + threadIdx.x;
-    const unsigned long long v = t < n_tiles ? tile_cnt[t] : 0;
-    unsigned long long total;
-    const unsigned long long ex = workgroup_exclusive_scan(v, slots, &total);
-    if (t < n_tiles) tile_cnt[t] = running + ex;
-    running += total;
-  }
-  if (out_count && threadIdx.x == 0) *out_count = (uint32_t)running;
-}
-
-// Writes the selected indices of each tile at their final, ascending positions.
-//   SCANNED: tile_cnt already holds exclusive prefix sums (k_compact_scan ran); otherwise
-//   it holds raw counts and each workgroup adds up the tiles before its own (few tiles).
-template <int SRC, bool SCANNED>
-__global__ __launch_bounds__(kWG) void k_compact_write(const KeyArgs src, uint32_t n,
-                                                       uint32_t n_tiles, int passes,
-                                                       const SelectWs* __restrict__ ws,
-                                                       const unsigned long long* __restrict__ tile_cnt,
-                                                       uint32_t* __restrict__ out_idx, uint32_t out_cap,
-                                                       uint32_t* __restrict__ out_count) {
+__global__ __launch_bounds__(kWG) void k_compact(const KeyArgs src, uint32_t n, uint32_t n_tiles,
+                                                 int passes, SelectWs* __restrict__ ws,
+                                                 unsigned long long* __restrict__ tile_state,
+                                                 uint32_t* __restrict__ out_idx, uint32_t out_cap,
+                                                 uint32_t* __restrict__ out_count, uint32_t spin_limit) {
   using key_t = typename Key<SRC>::type;
   __shared__ uint32_t slots[kWG / kWave + 1];
   __shared__ unsigned long long wide[kWG / kWave];
-  const key_t T = SRC == SRC_MASK ? 0 : (key_t)ws->state[passes].prefix;
-  const uint32_t take = SRC == SRC_MASK ? 0 : ws->state[passes].k_rem;
-  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-    unsigned long long off;
-    if constexpr (SCANNED) {
-      off = tile_cnt[tile];
-    } else {
-      unsigned long long before = 0, all = 0;
-      for (uint32_t t = threadIdx.x; t < n_tiles; t += kWG) {
-        const unsigned long long v = tile_cnt[t];
-        all += v;
-        if (t < tile) before += v;
-      }
-      off = workgroup_sum(before, wide);
-      if (out_count && tile == 0) {
-        all = workgroup_sum(all, wide);
-        if (threadIdx.x == 0) *out_count = (uint32_t)all;
+  __shared__ SelectState shared_state;
+  __shared__ unsigned long long s_before;
+  __shared__ int s_gave_up;
+  __shared__ int s_found[kWG / kWave];
+  key_t T = 0;
+  uint32_t take = 0;
+  if constexpr (SRC != SRC_MASK) {
+    const SelectState fin = next_state(ws->hist[passes - 1], Key<SRC>::bits(src, passes - 1),
+                                       ws->state[passes - 1], slots, &shared_state);
+    T = (key_t)fin.prefix;
+    take = fin.k_rem;
+  }
+  const uint32_t tile = blockIdx.x;
+  if (tile >= n_tiles) return;  // cannot happen with grid == n_tiles; keeps every access in range
+
+  const uint64_t base = (uint64_t)tile * kTileKeys + threadIdx.x * kKeysPerThread;
+  int cls[kKeysPerThread];
+  uint32_t cnt = 0;  // low half: above, high half: equal (a tile holds 2048 keys)
+#pragma unroll
+  for (int j = 0; j < kKeysPerThread; ++j) {
+    cls[j] = base + j < n ? classify<SRC>(src, base + j, T) : 0;
+    cnt += cls[j] == 1 ? 1u : (cls[j] == 2 ? (1u << 16) : 0u);
+  }
+  uint32_t total;
+  const uint32_t ex = workgroup_exclusive_scan(cnt, slots, &total);
+  const unsigned long long own = (unsigned long long)(total & 0xffffu) |
+                                 ((unsigned long long)(total >> 16) << kEqualShift);
+  unsigned long long before = look_back(tile_state, tile, own, spin_limit, &s_gave_up, wide, s_found);
+  if (s_gave_up) {  // count the keys of the earlier tiles directly
+    unsigned long long c2 = 0;
+    for (uint32_t t = 0; t < tile; ++t) {
+      const uint64_t b2 = (uint64_t)t * kTileKeys + threadIdx.x * kKeysPerThread;
+#pragma unroll
+      for (int j = 0; j < kKeysPerThread; ++j) {
+        const int c = b2 + j < n ? classify<SRC>(src, b2 + j, T) : 0;
+        c2 += c == 1 ? 1ull : (c == 2 ? (1ull << kEqualShift) : 0ull);
       }
     }
-    const uint64_t base = (uint64_t)tile * kTileKeys + threadIdx.x * kKeysPerThread;
-    int cls[kKeysPerThread];
-    uint32_t cnt = 0;  // low half: above, high half: equal (a tile holds 2048 keys)
-#pragma unroll
-    for (int j = 0; j < kKeysPerThread; ++j) {
-      cls[j] = base + j < n ? classify<SRC>(src, base + j, T) : 0;
-      cnt += cls[j] == 1 ? 1u : (cls[j] == 2 ? (1u << 16) : 0u);
+    before = workgroup_sum(c2, wide);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      s_before = before;
+      tile_word_store(&tile_state[tile], kTileRunning | (before + own));  // later tiles may stop here
     }
-    uint32_t total;
-    const uint32_t ex = workgroup_exclusive_scan(cnt, slots, &total);
-    uint32_t n_above = (uint32_t)off + (ex & 0xffffu);
-    uint32_t n_equal = (uint32_t)(off >> 32) + (ex >> 16);
+    __syncthreads();
+    before = s_before;
+  }
+  uint32_t n_above = (uint32_t)(before & kFieldMask) + (ex & 0xffffu);
+  uint32_t n_equal = (uint32_t)((before >> kEqualShift) & kFieldMask) + (ex >> 16);
 #pragma unroll
-    for (int j = 0; j < kKeysPerThread; ++j) {
-      if (cls[j] == 1) {
-        const uint32_t pos = n_above + (n_equal < take ? n_equal : take);
+  for (int j = 0; j < kKeysPerThread; ++j) {
+    if (cls[j] == 1) {
+      const uint32_t pos = n_above + (n_equal < take ? n_equal : take);
+      if (pos < out_cap) out_idx[pos] = (uint32_t)(base + j);
+      ++n_above;
+    } else if (cls[j] == 2) {
+      if (n_equal < take) {
+        const uint32_t pos = n_above + n_equal;
         if (pos < out_cap) out_idx[pos] = (uint32_t)(base + j);
-        ++n_above;
-      } else if (cls[j] == 2) {
-        if (n_equal < take) {
-          const uint32_t pos = n_above + n_equal;
-          if (pos < out_cap) out_idx[pos] = (uint32_t)(base + j);
-        }
-        ++n_equal;
       }
+      ++n_equal;
     }
   }
+  if (out_count && tile == n_tiles - 1 && threadIdx.x == 0)
+    *out_count = (uint32_t)(before & kFieldMask) + (total & 0xffffu);
 }
 
 // Whole selection in one workgroup of 1,024 threads for small stores (n <= kSmallSelect):
@@ -407,10 +495,11 @@ __global__ __launch_bounds__(kSmallWG) void k_select_small(const KeyArgs scores,
 
   SelectState cur;
   cur.prefix = 0, cur.k_rem = k, cur.pad = 0;
-  for (int pass = 0; pass < K::passes; ++pass) {
+  const int n_passes = K::passes(scores);
+  for (int pass = 0; pass < n_passes; ++pass) {
     for (int b = threadIdx.x; b < kMaxBins; b += kSmallWG) lh[b] = 0;
     __syncthreads();
-    const int shift = K::shift(pass), bits = K::bits(pass);
+    const int shift = K::shift(scores, pass), bits = K::bits(scores, pass);
     const uint32_t mask = (1u << bits) - 1;
 #pragma unroll
     for (int j = 0; j < kSmallKeys; ++j) {
@@ -465,27 +554,25 @@ __global__ __launch_bounds__(kSmallWG) void k_select_small(const KeyArgs scores,
   }
 }
 
-constexpr uint32_t kSelfScanTiles = 2048;  // up to here writers add up their predecessors
+// Polls a workgroup of the compaction spends on one window of predecessors before it counts
+// the earlier tiles itself (each poll is a load from device memory plus a short sleep, about a
+// microsecond).  A host-side setting so that a test can force the fallback.
+static uint32_t g_spin_limit = 1u << 16;
 
-// count -> (scan) -> write, shared by selection and mask compaction.
+static uint32_t clear_grid(uint32_t n_tiles) {
+  const uint32_t words = (uint32_t)(sizeof(SelectWs) / 4) + n_tiles;
+  const uint32_t g = (words + kWG * 8 - 1) / (kWG * 8);
+  return g < 1 ? 1 : (g > 256 ? 256 : g);
+}
+
+// The ordered write, shared by selection and mask compaction.  k_select_clear must have run.
 template <int SRC>
 static void run_compaction(const KeyArgs src, uint32_t n, int passes, SelectWs* ws,
                            unsigned long long* tiles, uint32_t* out_idx, uint32_t out_cap,
                            uint32_t* out_count, hipStream_t st) {
   const uint32_t n_tiles = (uint32_t)n_tiles_of(n);
-  const uint32_t tgrid = n_tiles < kTileGridCap ? n_tiles : kTileGridCap;
-  launch((k_compact_count<SRC>), dim3(tgrid), dim3(kWG), 0, st, src, n, n_tiles, passes,
-                     ws, tiles);
-  if (n_tiles <= kSelfScanTiles) {
-    launch((k_compact_write<SRC, false>), dim3(tgrid), dim3(kWG), 0, st, src, n, n_tiles,
-                       passes, (const SelectWs*)ws, (const unsigned long long*)tiles, out_idx, out_cap,
-                       out_count);
-  } else {
-    launch(k_compact_scan, dim3(1), dim3(kWG), 0, st, tiles, n_tiles, out_count);
-    launch((k_compact_write<SRC, true>), dim3(tgrid), dim3(kWG), 0, st, src, n, n_tiles,
-                       passes, (const SelectWs*)ws, (const unsigned long long*)tiles, out_idx, out_cap,
-                       (uint32_t*)nullptr);
-  }
+  launch((k_compact<SRC>), dim3(n_tiles), dim3(kWG), 0, st, src, n, n_tiles, passes, ws, tiles, out_idx,
+         out_cap, out_count, g_spin_limit);
 }
 
 template <int SRC>
@@ -500,7 +587,9 @@ static void run_select(const KeyArgs scores, uint32_t n, uint32_t k, uint32_t* o
   }
   SelectWs* ws = (SelectWs*)workspace;
   unsigned long long* tiles = (unsigned long long*)((char*)workspace + kWsTileOffset);
-  launch(k_select_clear, dim3(1), dim3(kWG), 0, st, ws, k);
+  const uint32_t n_tiles = (uint32_t)n_tiles_of(n);
+  launch(k_select_clear, dim3(clear_grid(n_tiles)), dim3(kWG), 0, st, ws, (uint32_t)(sizeof(SelectWs) / 4), k,
+         tiles, n_tiles);
   const uint32_t n_htiles = (uint32_t)(((uint64_t)n + kHistTileKeys - 1) / kHistTileKeys);
   // Every workgroup ends a pass with one global add per non-empty bin, so beyond a few
   // hundred workgroups more of them only add flush traffic: an eighth of the tiles, between
@@ -509,10 +598,13 @@ static void run_select(const KeyArgs scores, uint32_t n, uint32_t k, uint32_t* o
   uint32_t hgrid = n_htiles / 8;
   hgrid = hgrid < 256 ? 256 : (hgrid > 2048 ? 2048 : hgrid);
   if (hgrid > n_htiles) hgrid = n_htiles;
-  for (int p = 0; p < Key<SRC>::passes; ++p)
+  const int passes = Key<SRC>::passes(scores);
+  for (int p = 0; p < passes; ++p)
     launch((k_select_hist<SRC>), dim3(hgrid), dim3(kWG), 0, st, scores, n, n_htiles, p, ws);
-  run_compaction<SRC>(scores, n, Key<SRC>::passes, ws, tiles, out_idx, k, nullptr, st);
+  run_compaction<SRC>(scores, n, passes, ws, tiles, out_idx, k, nullptr, st);
 }
+
+__global__ void k_store_u32(uint32_t* __restrict__ p, uint32_t v) { *p = v; }
 
 // Round-robin strategy: the k blocks start, start+1, ... (mod n), written ascending.  When
 // the run wraps, its wrapped head (blocks 0 .. wrap-1) comes first.
@@ -527,18 +619,29 @@ __global__ __launch_bounds__(kWG) void k_select_round(uint32_t n, uint32_t k, ui
 
 using namespace scar;
 
-// Body of scar_select_topk and scar_select_topk_static once the workspace is known.
+// Body of the scar_select_topk family once the arguments and the workspace are known.
+// bounded: 64-bit integer scores are taken into [0, score_max].
 static int select_topk_checked(int32_t score_type, const void* scores, uint32_t n_blocks, uint32_t k,
-                               uint32_t* out_idx, void* workspace, hipStream_t st) {
+                               bool bounded, uint64_t score_max, uint32_t* out_idx, void* workspace,
+                               hipStream_t st) {
   if (k == n_blocks) {  // a full checkpoint: every block, whatever the scores
     const uint32_t grid = (k + kWG - 1) / kWG < 4096 ? (k + kWG - 1) / kWG : 4096;
     launch(k_select_round, dim3(grid), dim3(kWG), 0, st, n_blocks, k, 0u, out_idx);
     return launch_status();
   }
-  if (score_type == SCAR_SCORE_F32)
-    run_select<SRC_F32>(KeyArgs{scores, 0, 0}, n_blocks, k, out_idx, workspace, st);
-  else
-    run_select<SRC_I64>(KeyArgs{scores, 0, 0}, n_blocks, k, out_idx, workspace, st);
+  if (score_type == SCAR_SCORE_F32) {
+    run_select<SRC_F32>(key_args(scores), n_blocks, k, out_idx, workspace, st);
+    return launch_status();
+  }
+  KeyArgs a = key_args(scores);
+  if (bounded) {  // keys in [0, score_max]: as many digits as score_max has
+    int bits = 1;
+    while (bits < 64 && (score_max >> bits) != 0) ++bits;
+    a.passes = (bits + 10) / 11;
+    a.bounded = 1;
+    a.cap = score_max;
+  }
+  run_select<SRC_I64>(a, n_blocks, k, out_idx, workspace, st);
   return launch_status();
 }
 
@@ -560,8 +663,22 @@ extern "C" int scar_select_topk(int32_t score_type, const void* scores, uint32_t
   if (rc || k == 0) return rc;
   rc = check_workspace(workspace, workspace_bytes, n_blocks);
   if (rc) return rc;
-  return select_topk_checked(score_type, scores, n_blocks, k, out_idx, workspace, (hipStream_t)stream);
+  return select_topk_checked(score_type, scores, n_blocks, k, false, 0, out_idx, workspace,
+                             (hipStream_t)stream);
 }
+
+extern "C" int scar_select_topk_bounded(int32_t score_type, const void* scores, uint32_t n_blocks,
+                                        uint32_t k, uint64_t score_max, uint32_t* out_idx,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = select_topk_args(score_type, scores, n_blocks, k, out_idx);
+  if (rc || k == 0) return rc;
+  rc = check_workspace(workspace, workspace_bytes, n_blocks);
+  if (rc) return rc;
+  return select_topk_checked(score_type, scores, n_blocks, k, true, score_max, out_idx, workspace,
+                             (hipStream_t)stream);
+}
+
+extern "C" void scar_set_lookback_spin_limit(uint32_t polls) { g_spin_limit = polls; }
 
 // ---- the selection for callers that cannot allocate -------------------------------------
 // The scratch of scar_select_topk_static: one array per GPU, part of the loaded code object,
@@ -594,7 +711,7 @@ extern "C" int scar_select_topk_static(int32_t score_type, const void* scores, u
   if (k == 0) return SCAR_OK;
   void* ws = scratch_of_current_device();
   if (!ws) return SCAR_ERR_DEVICE;
-  return select_topk_checked(score_type, scores, n_blocks, k, out_idx, ws, (hipStream_t)stream);
+  return select_topk_checked(score_type, scores, n_blocks, k, false, 0, out_idx, ws, (hipStream_t)stream);
 }
 
 extern "C" int scar_mask_to_indices(const uint8_t* mask, uint32_t n_blocks, uint32_t* out_idx,
@@ -605,12 +722,16 @@ extern "C" int scar_mask_to_indices(const uint8_t* mask, uint32_t n_blocks, uint
   const int rc = check_workspace(workspace, workspace_bytes, n_blocks);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;
+  SelectWs* ws = (SelectWs*)workspace;
   unsigned long long* tiles = (unsigned long long*)((char*)workspace + kWsTileOffset);
-  if (n_blocks == 0)  // nothing to scan: the one-workgroup scan of zero tiles writes *out_count = 0
-    launch(k_compact_scan, dim3(1), dim3(kWG), 0, st, tiles, 0u, out_count);
-  else
-    run_compaction<SRC_MASK>(KeyArgs{mask, 0, 0}, n_blocks, 0, (SelectWs*)workspace, tiles, out_idx, n_blocks,
-                             out_count, st);
+  const uint32_t n_tiles = (uint32_t)n_tiles_of(n_blocks);
+  if (n_blocks == 0) {  // nothing to scan
+    launch(k_store_u32, dim3(1), dim3(1), 0, st, out_count, 0u);
+    return launch_status();
+  }
+  launch(k_select_clear, dim3(clear_grid(n_tiles)), dim3(kWG), 0, st, ws, (uint32_t)(sizeof(SelectWs) / 4), 0u,
+         tiles, n_tiles);
+  run_compaction<SRC_MASK>(key_args(mask), n_blocks, 0, ws, tiles, out_idx, n_blocks, out_count, st);
   return launch_status();
 }
 
@@ -633,7 +754,7 @@ extern "C" int scar_select_random(uint32_t n_blocks, uint32_t k, uint64_t seed, 
   if (!out_idx || !aligned(out_idx, 4)) return SCAR_ERR_INVALID_ARG;
   const int rc = check_workspace(workspace, workspace_bytes, n_blocks);
   if (rc) return rc;
-  run_select<SRC_RANDOM>(KeyArgs{nullptr, seed, draw}, n_blocks, k, out_idx, workspace,
+  run_select<SRC_RANDOM>(key_args(nullptr, seed, draw), n_blocks, k, out_idx, workspace,
                          (hipStream_t)stream);
   return launch_status();
 }

@@ -68,6 +68,10 @@ def lib():
         L.scar_block_scores_rows.restype = ctypes.c_int
         L.scar_select_topk.argtypes = [i32, vp, u32, u32, vp, vp, sz, vp]
         L.scar_checkpoint_commit.argtypes = [lp, vp, vp, vp, u32, vp, vp]
+        L.scar_select_topk_bounded.argtypes = [i32, vp, u32, u32, u64, vp, vp, sz, vp]
+        L.scar_select_topk_bounded.restype = ctypes.c_int
+        L.scar_set_lookback_spin_limit.argtypes = [u32]
+        L.scar_set_lookback_spin_limit.restype = None
         L.scar_select_topk_static.argtypes = [i32, vp, u32, u32, vp, vp]
         L.scar_select_topk_static.restype = ctypes.c_int
         L.scar_partial_recover.argtypes = [lp, vp, vp, vp, u32, vp, vp, sz, vp]
@@ -224,6 +228,29 @@ def select_topk(scores, k, workspace, out=None):
         raise ValueError("out must hold k indices")
     _check(lib().scar_select_topk(st, _p(scores), scores.numel(), int(k), _p(out), _p(workspace), _bytes(workspace), _stream()), "scar_select_topk")
     return out
+
+
+def select_topk_bounded(scores, k, score_max, workspace, out=None):
+    """scar_select_topk_bounded: scar_select_topk for int64 scores known to lie in [0, score_max]."""
+    _dev(scores, "scores"), _dev(workspace, "workspace")
+    if scores.dtype == torch.float32:
+        st = SCORE_F32
+    elif scores.dtype == torch.int64:
+        st = SCORE_I64
+    else:
+        raise TypeError("scores must be float32 or int64")
+    if out is None:
+        out = torch.empty(int(k), dtype=torch.int32, device=scores.device)
+    elif _idx(out, "out").numel() < int(k):
+        raise ValueError("out must hold k indices")
+    _check(lib().scar_select_topk_bounded(st, _p(scores), scores.numel(), int(k), int(score_max), _p(out),
+                                          _p(workspace), _bytes(workspace), _stream()),
+           "scar_select_topk_bounded")
+    return out
+
+
+def set_lookback_spin_limit(polls: int) -> None:
+    lib().scar_set_lookback_spin_limit(int(polls))
 
 
 STATIC_MAX_BLOCKS = 1 << 24

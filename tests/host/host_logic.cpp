@@ -41,6 +41,23 @@ int main() {
       CHECK(gy >= 1 && gy <= pieces && gy <= 65535);
       CHECK(gy == 1 || (uint64_t)gx * gy <= kMaxNormGrid);
     }
+  // grids of the row kernels: long lists pad x to the XCDs and keep x * y within the cap; a
+  // short list of rows in pieces is not padded in x, has a y that is a multiple of 8 (the
+  // device renumbers the whole grid in eighths) and still stays within the cap
+  for (uint64_t cap : {(uint64_t)kMaxNormGrid, kCopyGridCap})
+    for (uint32_t pieces : {1u, 2u, 5u, 8u, 17u, 4096u, 65536u, 100000u})
+      for (uint64_t need : {1ull, 2ull, 7ull, 100ull, 255ull, 256ull, 5000ull, 1ull << 20}) {
+        const RowGrid rg = row_grid(need, pieces, cap);
+        CHECK(rg.x >= 1 && rg.y >= 1 && rg.y <= 65535);
+        if (pieces > 1 && need < kRowSpreadBelow) {
+          CHECK(rg.x == need && rg.y % 8 == 0);
+          CHECK((uint64_t)rg.x * rg.y <= cap);
+          CHECK(rg.y <= (pieces + 7) / 8 * 8);
+        } else {
+          CHECK(rg.x % 8 == 0 && rg.y <= pieces);
+          CHECK(rg.y == 1 || (uint64_t)rg.x * rg.y <= cap);
+        }
+      }
   // workgroups per compute unit of the streaming reads: none asked for on short launches or
   // when eight fit anyway; otherwise exactly the wanted number fits the 160 KiB
   CHECK(stream_lds_bytes(kStreamFromGrid - 1, 32 * 1024) == 0);

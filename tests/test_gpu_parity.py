@@ -9,7 +9,7 @@ import torch
 import oracle
 from paper_1810_07354_amd import scar
 from paper_1810_07354_amd import workloads as wl
-from gpu_util import (DEV, DeviceStore, assert_norm_matches, assert_scores_match,
+from gpu_util import (DEV, REL_TOL, DeviceStore, assert_norm_matches, assert_scores_match,
                       assert_selection_matches, idx_dev, idx_host, to_dev, to_host)
 
 pytestmark = pytest.mark.gpu
@@ -156,6 +156,138 @@ def test_block_scores_of_rows_shorter_than_16_bytes(dtype, L):
         assert torch.equal(s, listed)
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16, I32])
+@pytest.mark.parametrize("nb,L,off", [(16, 1 << 20, 0), (5, 700_001, 0), (3, 1 << 18, 1), (40, 65_536 + 24, 4),
+                                      (2048, 1 << 16, 0)])
+def test_block_scores_of_a_few_very_long_blocks(dtype, nb, L, off):
+    # fewer blocks than the chip has room for workgroups: scored in pieces, many workgroups per
+    # block (a ragged last block, bases off the 16-byte grid, rows that are not whole steps),
+    # and the listed call must give the same bits
+    if dtype == BF16 and L * 2 < 256 * 1024:
+        L *= 2
+    n = L * nb - L // 3
+    hx, hc = make_store(dtype, n, seed=nb + L)
+    x = to_dev(np.concatenate([np.zeros(off, dtype=hx.dtype), hx]), dtype)[off:]
+    c = to_dev(np.concatenate([np.zeros(off, dtype=hc.dtype), hc]), dtype)[off:]
+    print("giant blocks dtype=%d nb=%d L=%d off=%d" % (dtype, nb, L, off), flush=True)
+    oracle.set_num_threads(8)
+    try:
+        want = oracle.block_scores(dtype, hx, hc, L)
+    finally:
+        oracle.set_num_threads(1)
+    s = scar.block_scores(x, c, L)
+    assert_scores_match(s, want, dtype)
+    listed = torch.full_like(s, -1)
+    order = torch.randperm(nb, device=DEV).to(torch.int32)
+    scar.block_scores_rows(x, c, L, order, listed)
+    assert torch.equal(s, listed)
+    some = torch.full_like(s, -7)
+    scar.block_scores_rows(x, c, L, order[: max(1, nb // 3)], some)
+    chosen = order[: max(1, nb // 3)].long()
+    assert torch.equal(some[chosen], s[chosen])
+    rest = torch.ones(nb, dtype=torch.bool, device=DEV)
+    rest[chosen] = False
+    assert bool((some[rest] == -7).all())
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16, wl.F32_BF16C])
+@pytest.mark.parametrize("L,nb", [(8, 3000), (100, 2000), (1024, 600), (5000, 40_000 // 100)])
+def test_nan_inf_and_negative_zero_in_the_store(dtype, L, nb):
+    # NaN, +-Inf and -0 as *elements of x and c*: scores follow IEEE (NaN or Inf), the selection
+    # ranks NaN above Inf above every number, commit and recovery move the bit patterns as they
+    # are (a bfloat16 checkpoint rounds: NaN stays NaN, Inf stays Inf), norms become NaN or Inf
+    r = np.random.default_rng(L + nb + dtype)
+    n = L * nb - L // 2
+    hx, hc = make_store(F32, n, seed=L)
+    specials = np.array([np.nan, np.inf, -np.inf, -0.0, 0.0], dtype=np.float32)
+    for arr in (hx, hc):
+        where = r.choice(n, size=nb // 4, replace=False)
+        arr[where] = r.choice(specials, size=where.size)
+    both = r.choice(n, size=nb // 8, replace=False)          # Inf - Inf = NaN, Inf - (-Inf) = Inf
+    hx[both], hc[both] = np.inf, r.choice(np.array([np.inf, -np.inf], dtype=np.float32), size=both.size)
+    if dtype == BF16:
+        hx, hc = wl.f32_to_bf16_bits(hx), wl.f32_to_bf16_bits(hc)
+        x, c = to_dev(hx, BF16), to_dev(hc, BF16)
+    elif dtype == wl.F32_BF16C:
+        hc = wl.f32_to_bf16_bits(hc)
+        x, c = to_dev(hx, F32), to_dev(hc, BF16)
+    else:
+        x, c = to_dev(hx, F32), to_dev(hc, F32)
+    nbk = oracle.n_blocks_of(n, L)
+    ws = scar.new_workspace(nbk, DEV)
+    print("non-finite store dtype=%d L=%d nb=%d" % (dtype, L, nbk), flush=True)
+
+    s = scar.block_scores(x, c, L)
+    s_ref = oracle.block_scores(dtype, hx, hc, L)
+    s_h = s.cpu().numpy()
+    assert np.isnan(s_ref).sum() > 0 and np.isinf(s_ref).sum() > 0
+    np.testing.assert_array_equal(np.isnan(s_h), np.isnan(s_ref))
+    np.testing.assert_array_equal(np.isposinf(s_h), np.isposinf(s_ref))
+    fin = np.isfinite(s_ref)
+    np.testing.assert_allclose(s_h[fin].astype(np.float64), s_ref[fin], rtol=REL_TOL, atol=0)
+
+    n_nan, n_big = int(np.isnan(s_ref).sum()), int((~fin).sum())
+    for k in sorted({1, n_nan, n_nan + 1, n_big, n_big + 5, nbk // 2}):
+        idx = scar.select_topk(s, k, ws)
+        np.testing.assert_array_equal(idx_host(idx), oracle.select_topk(s_h.astype(np.float64), k))
+        if k in (n_nan, n_big):       # exactly the NaN blocks / the non-finite blocks: the same in float64
+            np.testing.assert_array_equal(idx_host(idx), oracle.select_topk(s_ref, k))
+
+    def as_bits(a):
+        return a.view(np.uint32) if a.dtype == np.float32 else a
+
+    scar.checkpoint_commit(x, c, L, idx)
+    oracle.checkpoint_commit(dtype, hx, hc, L, idx_host(idx))
+    np.testing.assert_array_equal(as_bits(to_host(c)), as_bits(hc))
+    np.testing.assert_array_equal(as_bits(to_host(x)), as_bits(hx))
+
+    lost = np.sort(r.choice(nbk, size=nbk // 3, replace=False)).astype(np.uint32)
+    got = scar.read_norm(scar.partial_recover(x, c, L, idx_dev(lost), ws))
+    want = oracle.partial_recover(dtype, hx, hc, L, lost)
+    for g, w in zip(got[:2], want[:2]):
+        assert (np.isnan(w) and np.isnan(g)) or (np.isinf(w) and g == w) or abs(g - w) <= REL_TOL * abs(w)
+    np.testing.assert_array_equal(as_bits(to_host(x)), as_bits(hx))
+    # a list without the poisoned blocks gives a finite norm again
+    clean = np.nonzero(np.isfinite(oracle.block_scores(dtype, hx, hc, L)))[0].astype(np.uint32)
+    got = scar.read_norm(scar.perturbation_norm(x, c, L, idx_dev(clean), ws))
+    assert_norm_matches(got, oracle.perturbation_norm(dtype, hx, hc, L, clean), F32)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16, I32, wl.F32_BF16C])
+@pytest.mark.parametrize("nb,L,n_list", [(16, 1 << 20, 2), (5, 700_001, 1), (9, 300_000, 9), (300, 20_000, 70)])
+def test_commit_and_recover_of_a_few_very_long_rows(dtype, nb, L, n_list):
+    # a short list of rows that are cut into thousands of 4 KiB pieces: the pieces, not the list,
+    # are spread over the chip; every byte against the oracle, norm alone = norm with recovery
+    r = np.random.default_rng(nb + L)
+    n = L * nb - L // 3
+    xdt = F32 if dtype == wl.F32_BF16C else dtype
+    hx, hc = make_store(xdt, n, seed=nb + L + 1)
+    if dtype == wl.F32_BF16C:
+        hc = wl.f32_to_bf16_bits(hc)
+    x, c = to_dev(hx, xdt), to_dev(hc, BF16 if dtype == wl.F32_BF16C else dtype)
+    ws = scar.new_workspace(nb, DEV)
+    norm_kind = I32 if dtype == I32 else F32
+    print("long rows dtype=%d nb=%d L=%d list=%d" % (dtype, nb, L, n_list), flush=True)
+    K = np.sort(np.unique(np.append(r.choice(nb, size=n_list, replace=False), nb - 1))).astype(np.uint32)
+    st = torch.zeros(K.size * L, dtype=c.dtype, device=DEV)
+    scar.checkpoint_commit(x, c, L, idx_dev(K), st)
+    hst = np.zeros(K.size * L, dtype=hc.dtype)
+    oracle.checkpoint_commit(dtype, hx, hc, L, K, hst)
+    np.testing.assert_array_equal(to_host(c), hc)
+    np.testing.assert_array_equal(to_host(st), hst)
+    S = np.sort(np.unique(np.append(r.choice(nb, size=n_list, replace=False), nb - 1))).astype(np.uint32)
+    hx2 = hx.copy()
+    hx2[: n // 2] += hx2.dtype.type(1)        # move x away from c again, so the lost rows differ
+    x = to_dev(hx2, xdt)
+    pre = scar.read_norm(scar.perturbation_norm(x, c, L, idx_dev(S), ws))
+    got = scar.read_norm(scar.partial_recover(x, c, L, idx_dev(S), ws))
+    want = oracle.partial_recover(dtype, hx2, hc, L, S)
+    assert_norm_matches(got, want, norm_kind)
+    assert pre == got
+    np.testing.assert_array_equal(to_host(x), hx2)
+    np.testing.assert_array_equal(to_host(c), hc)
+
+
 def test_block_scores_int_extremes():
     hi = np.full(2048, np.iinfo(np.int32).max, dtype=np.int32)
     lo = np.full(2048, np.iinfo(np.int32).min, dtype=np.int32)
@@ -213,8 +345,7 @@ def test_select_topk_int(n, hi):
 
 @pytest.mark.parametrize("n,k", [(5_000_000, 1234), (5_000_000, 2_500_000), (33_554_432 + 5000, 40_000)])
 def test_select_topk_many_tiles(n, k):
-    # more tiles than one workgroup sums on its own (separate scan kernel) and, for the
-    # largest case, more tiles than the grid (every workgroup strides over several)
+    # thousands of tiles: long chains of look-back windows in the ordered write
     r = np.random.default_rng(n + k)
     s = r.integers(0, 1 << 20, size=n).astype(np.float32)       # many ties
     d = torch.from_numpy(s).to(DEV)
@@ -228,6 +359,54 @@ def test_select_topk_many_tiles(n, k):
     want = oracle.mask_to_indices(m)
     assert int(cnt.item()) == want.size
     np.testing.assert_array_equal(idx_host(out)[: want.size], want)
+
+
+@pytest.mark.parametrize("n,hi,bound", [(100_000, 50, 49), (100_000, 50, 1000 * 2 ** 32), (30_000, 2 ** 21, 2 ** 21),
+                                        (30_000, 2 ** 40, 2 ** 33 - 1), (20_000, 2 ** 40, 2 ** 54), (16_000, 300, 10 ** 6),
+                                        (250_000, 2 ** 62, 2 ** 62), (1_200_000, 5000, 2 ** 22 - 1), (70_000, 100, 20)])
+def test_select_topk_bounded(n, hi, bound):
+    # 64-bit integer scores with an upper bound known on the host: fewer digit passes, the same
+    # choice as the oracle makes on the scores taken into [0, bound] (a negative score counts
+    # as 0 and one above the bound as the bound)
+    r = np.random.default_rng(n + 3)
+    s = r.integers(0, hi, size=n).astype(np.int64)
+    s[::11] = -s[::11]
+    d = torch.from_numpy(s).to(DEV)
+    ws = scar.new_workspace(n, DEV)
+    clamped = np.clip(s, 0, bound)
+    for k in sorted({1, n // 20, n // 2, n - 1}):
+        print("select bounded n=%d hi=%d bound=%d k=%d" % (n, hi, bound, k), flush=True)
+        got = idx_host(scar.select_topk_bounded(d, k, bound, ws))
+        np.testing.assert_array_equal(got, oracle.select_topk(clamped, k))
+    # float scores ignore the bound
+    f = r.random(n).astype(np.float32)
+    got = idx_host(scar.select_topk_bounded(torch.from_numpy(f).to(DEV), n // 3, 5, ws))
+    np.testing.assert_array_equal(got, oracle.select_topk(f.astype(np.float64), n // 3))
+
+
+@pytest.mark.parametrize("limit", [0, 1])
+def test_ordered_write_when_no_workgroup_waits_for_another(limit):
+    # the chained scan's bounded wait, forced from the host to give up at once: every workgroup
+    # then counts the tiles before its own itself; results must not change
+    r = np.random.default_rng(limit)
+    scar.set_lookback_spin_limit(limit)
+    try:
+        for n, k in ((300_000, 30_000), (1_000_000, 999_999), (20_000, 1)):
+            print("forced fallback limit=%d n=%d k=%d" % (limit, n, k), flush=True)
+            s = r.integers(0, 30, size=n).astype(np.float32)
+            ws = scar.new_workspace(n, DEV)
+            got = idx_host(scar.select_topk(torch.from_numpy(s).to(DEV), k, ws))
+            np.testing.assert_array_equal(got, oracle.select_topk(s.astype(np.float64), k))
+            m = (s > 20).astype(np.uint8)
+            out, cnt = scar.mask_to_indices(torch.from_numpy(m).to(DEV), ws)
+            want = oracle.mask_to_indices(m)
+            assert int(cnt.item()) == want.size
+            np.testing.assert_array_equal(idx_host(out)[: want.size], want)
+            si = r.integers(0, 5, size=n).astype(np.int64)
+            got = idx_host(scar.select_topk(torch.from_numpy(si).to(DEV), k, ws))
+            np.testing.assert_array_equal(got, oracle.select_topk(si, k))
+    finally:
+        scar.set_lookback_spin_limit(1 << 16)
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16, I32])
