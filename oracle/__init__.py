@@ -50,7 +50,8 @@ def lib():
         L.oracle_partial_recover.argtypes = [i32, vp, vp, u64, u32, vp, u32, ctypes.POINTER(Norm)]
         L.oracle_mask_to_indices.argtypes = [vp, u32, vp, ctypes.POINTER(u32)]
         L.oracle_var_block_scores.argtypes = [i32, vp, vp, vp, u32, vp]
-        L.oracle_var_checkpoint_commit.argtypes = [i32, vp, vp, vp, u32, vp, u32]
+        L.oracle_var_checkpoint_commit.argtypes = [i32, vp, vp, vp, u32, vp, u32, vp, vp]
+        L.oracle_var_partial_recover_rows.argtypes = [i32, vp, vp, vp, vp, u32, vp, u32, ctypes.POINTER(Norm)]
         L.oracle_var_perturbation_norm.argtypes = [i32, vp, vp, vp, u32, vp, u32, ctypes.POINTER(Norm)]
         L.oracle_var_partial_recover.argtypes = [i32, vp, vp, vp, u32, vp, u32, ctypes.POINTER(Norm)]
         L.oracle_tv_block_scores.argtypes = [i32, vp, vp, u64, u32, vp, vp]
@@ -246,10 +247,36 @@ def var_block_scores(dtype, x, c, offsets):
     return out
 
 
-def var_checkpoint_commit(dtype, x, c, offsets, idx):
+def var_checkpoint_commit(dtype, x, c, offsets, idx, staging=None):
+    """c_b <- x_b for the listed blocks of unequal length.  With staging (a flat array of c's
+    type with room for the listed blocks) the blocks are also packed into it in list order;
+    returns the uint64 element offsets of the packed blocks (n_idx + 1 entries) or None."""
     x, c, off, idx = _flat_x(x, dtype), _flat_c(c, dtype), _offsets(offsets), _idx(idx)
+    st_off = None
+    if staging is not None:
+        staging = _flat_c(staging, dtype)
+        need = int(sum(int(off[b + 1] - off[b]) for b in idx))
+        if staging.size < need:
+            raise ValueError("staging too small")
+        st_off = np.zeros(idx.size + 1, dtype=np.uint64)
     _check(lib().oracle_var_checkpoint_commit(dtype, _ptr(x), _ptr(c), _ptr(off), off.size - 1,
-                                              _ptr(idx), idx.size), "oracle_var_checkpoint_commit")
+                                              _ptr(idx), idx.size, _ptr(staging),
+                                              ctypes.c_void_p(st_off.ctypes.data) if st_off is not None
+                                              else ctypes.c_void_p(0)), "oracle_var_checkpoint_commit")
+    return st_off
+
+
+def var_partial_recover_rows(dtype, x, rows, row_offsets, offsets, lost):
+    """x_b <- the packed row of block b for the lost blocks; (sum, norm, isum) of rows - x_S
+    measured before the overwrite."""
+    x, rows, off, lost = _flat_x(x, dtype), _flat_c(rows, dtype), _offsets(offsets), _idx(lost)
+    row_offsets = np.ascontiguousarray(row_offsets, dtype=np.uint64)
+    out = Norm()
+    _check(lib().oracle_var_partial_recover_rows(dtype, _ptr(x), _ptr(rows),
+                                                 ctypes.c_void_p(row_offsets.ctypes.data), _ptr(off),
+                                                 off.size - 1, _ptr(lost), lost.size, ctypes.byref(out)),
+           "oracle_var_partial_recover_rows")
+    return out.sum, out.norm, out.isum
 
 
 def var_perturbation_norm(dtype, x, c, offsets, idx=None):

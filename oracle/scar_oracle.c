@@ -473,16 +473,31 @@ int oracle_var_block_scores(int dtype, const void *x, const void *c, const uint6
   return ORACLE_OK;
 }
 
+/* Checkpoint step 4 of Section 4.3 for blocks of unequal length (Section 5.1, by-layer):
+ * c_b <- x_b for the listed blocks.  If staging is given, the listed blocks are also packed
+ * into it one after the other in the order of the list - the bytes that go to persistent
+ * storage - and staging_offsets[i] receives the element offset of block idx[i] within staging
+ * (the lengths of the blocks listed before it, added up), staging_offsets[n_idx] the total. */
 int oracle_var_checkpoint_commit(int dtype, const void *x, void *c, const uint64_t *offsets,
-                                 uint32_t n_blocks, const uint32_t *idx, uint32_t n_idx) {
+                                 uint32_t n_blocks, const uint32_t *idx, uint32_t n_idx,
+                                 void *staging, uint64_t *staging_offsets) {
   if (!dtype_ok(dtype) || dtype == ORACLE_F32_BF16C || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
+  if (staging && !staging_offsets) return ORACLE_ERR_ARG;
+  if (staging_offsets) staging_offsets[0] = 0;
   if (n_idx == 0) return ORACLE_OK;
   int rc = check_indices(idx, n_idx, n_blocks);
   if (rc) return rc;
   size_t es = elem_size(dtype);
+  uint64_t packed = 0; /* elements already in staging */
   for (uint32_t i = 0; i < n_idx; ++i) {
     uint64_t lo = offsets[idx[i]], hi = offsets[idx[i] + 1];
     if (hi > lo) memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo) * es);
+    if (staging_offsets) {
+      staging_offsets[i] = packed;
+      if (staging && hi > lo) memcpy((char *)staging + packed * es, (const char *)x + lo * es, (hi - lo) * es);
+      packed += hi - lo;
+      staging_offsets[i + 1] = packed;
+    }
   }
   return ORACLE_OK;
 }
@@ -538,6 +553,51 @@ int oracle_var_partial_recover(int dtype, void *x, const void *c, const uint64_t
   for (uint32_t i = 0; i < n_lost; ++i) {
     uint64_t lo = offsets[lost[i]], hi = offsets[lost[i] + 1];
     if (hi > lo) memcpy((char *)x + lo * es, (const char *)c + lo * es, (hi - lo) * es);
+  }
+  return ORACLE_OK;
+}
+
+/* Recovery from storage for blocks of unequal length (Section 4.3, recovery step 2): the
+ * checkpoint values of the lost blocks come as packed rows - block lost[i] at element
+ * row_offsets[i] of rows, as oracle_var_checkpoint_commit packs them - instead of from c.
+ * norm_out, if given, receives || rows - x_S || measured before x is overwritten. */
+int oracle_var_partial_recover_rows(int dtype, void *x, const void *rows, const uint64_t *row_offsets,
+                                    const uint64_t *offsets, uint32_t n_blocks, const uint32_t *lost,
+                                    uint32_t n_lost, oracle_norm *norm_out) {
+  if (!dtype_ok(dtype) || dtype == ORACLE_F32_BF16C || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
+  oracle_norm zero = {0.0, 0.0, 0};
+  if (norm_out) *norm_out = zero;
+  if (n_lost == 0) return ORACLE_OK;
+  if (!row_offsets || !rows || !x) return ORACLE_ERR_ARG;
+  int rc = check_indices(lost, n_lost, n_blocks);
+  if (rc) return rc;
+  size_t es = elem_size(dtype);
+  if (norm_out) {
+    double fs = 0.0;
+    int64_t is = 0;
+    for (uint32_t i = 0; i < n_lost; ++i) {
+      uint64_t lo = offsets[lost[i]], len = offsets[lost[i] + 1] - lo, r0 = row_offsets[i];
+      for (uint64_t t = 0; t < len; ++t) {
+        if (dtype == ORACLE_I32) {
+          int64_t d = (int64_t)((const int32_t *)rows)[r0 + t] - (int64_t)((const int32_t *)x)[lo + t];
+          is += d < 0 ? -d : d;
+        } else {
+          double d = load_real(dtype, rows, r0 + t) - load_real(dtype, x, lo + t);
+          fs += d * d;
+        }
+      }
+    }
+    if (dtype == ORACLE_I32) {
+      norm_out->isum = is;
+      norm_out->sum = norm_out->norm = (double)is;
+    } else {
+      norm_out->sum = fs;
+      norm_out->norm = sqrt(fs);
+    }
+  }
+  for (uint32_t i = 0; i < n_lost; ++i) {
+    uint64_t lo = offsets[lost[i]], len = offsets[lost[i] + 1] - lo;
+    if (len) memcpy((char *)x + lo * es, (const char *)rows + row_offsets[i] * es, len * es);
   }
   return ORACLE_OK;
 }

@@ -67,6 +67,13 @@ MUTANTS = [
     ("document length of the list position", "    total += (weights ? (double)weights[b] : 1.0) * block_tv(dtype, x, c, lo, hi);",
      "    total += (weights ? (double)weights[i] : 1.0) * block_tv(dtype, x, c, lo, hi);"),
     ("scaled norm as a root", "  out->sum = out->norm = total;", "  out->sum = total; out->norm = sqrt(total);"),
+    ("unequal blocks: staging offsets include the block itself", "      staging_offsets[i] = packed;\n", "      staging_offsets[i] = packed + (hi - lo);\n"),
+    ("unequal blocks: staging packed by block position", "memcpy((char *)staging + packed * es, (const char *)x + lo * es, (hi - lo) * es);",
+     "memcpy((char *)staging + lo * es, (const char *)x + lo * es, (hi - lo) * es);"),
+    ("unequal blocks: rows read from the block's own offset", "memcpy((char *)x + lo * es, (const char *)rows + row_offsets[i] * es, len * es);",
+     "memcpy((char *)x + lo * es, (const char *)rows + lo * es, len * es);"),
+    ("unequal blocks: norm of the rows after the overwrite", "double d = load_real(dtype, rows, r0 + t) - load_real(dtype, x, lo + t);",
+     "double d = load_real(dtype, rows, r0 + t) - load_real(dtype, rows, r0 + t);"),
     ("unequal blocks: commit one element short", "    if (hi > lo) memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo) * es);",
      "    if (hi > lo) memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo - 1) * es);"),
 ]

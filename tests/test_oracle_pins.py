@@ -569,6 +569,64 @@ def test_var_commit_and_recover_touch_only_their_blocks():
         oracle.var_block_scores(F32, x, c, np.array([0, 5, 4], dtype=np.uint64))
 
 
+def test_var_staging_layout_by_hand():
+    # lengths 3 0 5 2 4; listed 2, 0, 3, 1: packed offsets 0 5 8 10 10 (an empty block takes no
+    # room), packed content = the blocks of x one after the other in list order
+    off = np.array([0, 3, 3, 8, 10, 14], dtype=np.uint64)
+    x = np.arange(100, 114, dtype=np.float32)
+    c = np.zeros(14, dtype=np.float32)
+    st = np.full(12, -1, dtype=np.float32)
+    got = oracle.var_checkpoint_commit(F32, x, c, off, [2, 0, 3, 1], st)
+    np.testing.assert_array_equal(got, [0, 5, 8, 10, 10])
+    np.testing.assert_array_equal(st, [103, 104, 105, 106, 107, 100, 101, 102, 108, 109, -1, -1])
+    np.testing.assert_array_equal(c, [100, 101, 102, 103, 104, 105, 106, 107, 108, 109, 0, 0, 0, 0])
+    # nothing listed: offsets = [0], nothing written
+    st[:] = -1
+    np.testing.assert_array_equal(oracle.var_checkpoint_commit(F32, x, c, off, [], st), [0])
+    assert (st == -1).all()
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16, I32])
+def test_var_staging_with_equal_blocks_is_the_fixed_layouts_staging(dtype):
+    x, c = small_store(56, n_elems=240, dtype=dtype)
+    L = 10
+    off = np.arange(0, 241, L, dtype=np.uint64)
+    idx = np.array([7, 23, 0, 11], dtype=np.uint32)
+    c1, c2 = c.copy(), c.copy()
+    st1, st2 = np.zeros(idx.size * L, dtype=x.dtype), np.zeros(idx.size * L, dtype=x.dtype)
+    st_off = oracle.var_checkpoint_commit(dtype, x, c1, off, idx, st1)
+    oracle.checkpoint_commit(dtype, x, c2, L, idx, st2)
+    np.testing.assert_array_equal(st_off, np.arange(idx.size + 1) * L)
+    np.testing.assert_array_equal(st1, st2)
+    np.testing.assert_array_equal(c1, c2)
+
+
+@pytest.mark.parametrize("dtype", [F32, I32])
+def test_var_recovery_from_packed_rows_is_recovery_from_the_checkpoint(dtype):
+    # rows packed by a commit hold c's values of those blocks; recovering the same blocks from
+    # the rows must equal recovering them from c, norm and bytes, and touch nothing else
+    off = ragged_offsets(57, 40, 23)
+    n = int(off[-1])
+    x, c = small_store(58, n_elems=n, dtype=dtype)
+    K = np.array([31, 2, 17, 9, 38], dtype=np.uint32)
+    st = np.zeros(n, dtype=x.dtype)
+    st_off = oracle.var_checkpoint_commit(dtype, x, c, off, K, st)
+    x_new, _ = small_store(59, n_elems=n, dtype=dtype)          # training moved on
+    xa, xb = x_new.copy(), x_new.copy()
+    want = oracle.var_partial_recover(dtype, xa, c, off, K)
+    got = oracle.var_partial_recover_rows(dtype, xb, st, st_off[:-1], off, K)
+    assert want[1] > 0 and got[2] == want[2]
+    assert math.isclose(got[0], want[0], rel_tol=1e-12) and math.isclose(got[1], want[1], rel_tol=1e-12)
+    np.testing.assert_array_equal(xa, xb)
+    # by hand on one block: x <- row, norm = |row - x|
+    o2 = np.array([0, 2, 5], dtype=np.uint64)
+    if dtype == F32:
+        xs = np.array([1, 2, 3, 4, 5], dtype=np.float32)
+        rows = np.array([9, 9, 9, 6, 8, 5], dtype=np.float32)      # block 1 packed at offset 3
+        assert oracle.var_partial_recover_rows(F32, xs, rows, [3], o2, [1]) == (9.0 + 16.0, 5.0, 0)
+        np.testing.assert_array_equal(xs, [1, 2, 6, 8, 5])
+
+
 # --------------------------------------------------------------------------- reduced-precision checkpoint
 
 MIX = oracle.F32_BF16C
