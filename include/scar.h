@@ -245,7 +245,7 @@ int scar_select_random(uint32_t n_blocks, uint32_t k, uint64_t seed, uint64_t dr
  * parameter, so blocks differ in size by orders of magnitude.  Block b is the element
  * range [offsets[b], offsets[b+1]); empty blocks are allowed (score 0).
  * The calls below mirror the five above (scar_select_topk, _round and _random work on
- * any score array and serve both layouts).  There is no staging output.  SCAR_F32_BF16C
+ * any score array and serve both layouts).  SCAR_F32_BF16C
  * stores have fixed-length blocks only: SCAR_ERR_UNSUPPORTED here.
  * All of them need a workspace of scar_var_workspace_bytes(n_blocks) bytes. */
 typedef struct {
@@ -268,10 +268,32 @@ int scar_var_checkpoint_commit(const scar_var_layout* layout, const void* x, voi
                                const uint32_t* idx, uint32_t n_idx, void* workspace,
                                size_t workspace_bytes, void* stream);
 
+/* As scar_checkpoint_commit with staging rows (Section 4.3, checkpoint step 4): the listed
+ * blocks are also packed into `staging` one after the other in the order of the list - the
+ * bytes a background writer sends to persistent storage - and staging_offsets (DEVICE,
+ * n_idx + 1 entries) receives where: block idx[i] starts at element staging_offsets[i] of
+ * staging, staging_offsets[n_idx] is the total (the lengths of the listed blocks added up; an
+ * empty block takes no room).  staging must have room for that total; its elements have c's
+ * type.  The offsets are computed on the device; nothing comes back to the host. */
+int scar_var_checkpoint_commit_staged(const scar_var_layout* layout, const void* x, void* c,
+                                      const uint32_t* idx, uint32_t n_idx, void* staging,
+                                      uint64_t* staging_offsets, void* workspace,
+                                      size_t workspace_bytes, void* stream);
+
 /* As scar_partial_recover; the workspace is always required. */
 int scar_var_partial_recover(const scar_var_layout* layout, void* x, const void* c,
                              const uint32_t* lost_idx, uint32_t n_lost, scar_norm* norm_out,
                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* scar_var_partial_recover with the lost blocks' checkpoint values taken from packed rows
+ * (Section 4.3, recovery step 2: re-loaded from storage) instead of from the in-memory
+ * checkpoint: block lost_idx[i] is read from element row_offsets[i] of rows (DEVICE arrays;
+ * the layout scar_var_checkpoint_commit_staged writes and scar_var_store_load returns), and
+ * norm_out, if given, receives || rows - x_S || measured before the overwrite. */
+int scar_var_partial_recover_rows(const scar_var_layout* layout, void* x, const void* rows,
+                                  const uint64_t* row_offsets, const uint32_t* lost_idx,
+                                  uint32_t n_lost, scar_norm* norm_out, void* workspace,
+                                  size_t workspace_bytes, void* stream);
 
 /* As scar_perturbation_norm (idx == NULL: every block). */
 int scar_var_perturbation_norm(const scar_var_layout* layout, const void* x, const void* c,

@@ -36,7 +36,7 @@ typedef struct scar_store scar_store;
 int scar_store_create(const char* path, const scar_layout* layout, uint32_t max_rows,
                       scar_store** out);
 
-/* Opens an existing store file; *layout_out receives its layout. */
+/* Opens an existing store file of fixed-length blocks; *layout_out receives its layout. */
 int scar_store_open(const char* path, uint32_t max_rows, scar_layout* layout_out, scar_store** out);
 
 /* Background save of one partial checkpoint.  staging (DEVICE): the packed rows written by
@@ -59,6 +59,37 @@ int scar_store_wait(scar_store* store);
  * first.  Feed rows to scar_partial_recover_rows. */
 int scar_store_load(scar_store* store, const uint32_t* idx_host, uint32_t n_idx, void* rows,
                     void* stream);
+
+/* ---- stores whose blocks differ in length (Section 5.1, by-layer partitioning) -------------
+ * The same object and the same writer thread for a scar_var_layout store.  File: a 4,096-byte
+ * header (ASCII magic "SCARSTV1", int32 dtype, uint32 n_blocks, uint64 n_elems, uint64
+ * data_offset), the n_blocks + 1 uint64 element offsets at byte 4,096, then block b at byte
+ * data_offset + offsets[b] * element size (data_offset = the next multiple of 4,096 after the
+ * offsets).  scar_store_wait and scar_store_close serve both kinds of store; the calls above
+ * refuse a store of this kind and the calls below one of the other (SCAR_ERR_INVALID_ARG).
+ *
+ * offsets_host: HOST array, n_blocks + 1 non-decreasing element offsets, offsets[0] = 0.
+ * max_rows: most blocks per save or load; max_elems: most elements per save or load (the
+ * size of the two pinned buffers).  SCAR_F32, SCAR_BF16 and SCAR_I32 stores. */
+int scar_var_store_create(const char* path, int32_t dtype, uint32_t n_blocks,
+                          const uint64_t* offsets_host, uint32_t max_rows, uint64_t max_elems,
+                          scar_store** out);
+
+/* Background save of the rows scar_var_checkpoint_commit_staged packed: staging (DEVICE) holds
+ * the blocks idx[0..n_idx) (DEVICE) one after the other.  Which blocks were chosen, and so how
+ * many elements that is, is known only on the device: the caller says how many elements to
+ * transfer - staging_elems, at least the listed blocks' total, the capacity of the staging
+ * buffer will always do - and the writer thread, which knows the offsets, finds the rows in
+ * them.  Fewer elements than the list needs make the save fail (reported by scar_store_wait). */
+int scar_var_store_save_async(scar_store* store, const void* staging, uint64_t staging_elems,
+                              const uint32_t* idx, uint32_t n_idx, void* stream);
+
+/* Recovery from storage: reads the blocks idx_host[0..n_idx) (HOST) from the file into rows
+ * (DEVICE, packed in list order) and writes where each one starts to row_offsets (DEVICE,
+ * n_idx + 1 element offsets; the last is the total); returns after the copies have completed.
+ * Feed both to scar_var_partial_recover_rows. */
+int scar_var_store_load(scar_store* store, const uint32_t* idx_host, uint32_t n_idx, void* rows,
+                        uint64_t* row_offsets, void* stream);
 
 /* Waits for pending saves, stops the writer thread, closes the file, frees everything. */
 int scar_store_close(scar_store* store);

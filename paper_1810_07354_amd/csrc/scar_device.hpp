@@ -210,6 +210,30 @@ __device__ __forceinline__ V workgroup_sum(V v, V* slots) {
   return total;
 }
 
+// Exclusive prefix sum of v over a workgroup of NT threads in thread order; *total gets the
+// sum.  `slots` is LDS for NT / kWave + 1 values.
+template <int NT = kWG, typename T>
+__device__ __forceinline__ T workgroup_exclusive_scan(T v, T* slots, T* total) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  T inc = v;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    T up = __shfl_up(inc, d, kWave);
+    if (lane >= d) inc += up;
+  }
+  __syncthreads();
+  if (lane == kWave - 1) slots[wave] = inc;
+  __syncthreads();
+  T base = 0, sum = 0;
+#pragma unroll
+  for (int w = 0; w < NT / kWave; ++w) {
+    if (w < wave) base += slots[w];
+    sum += slots[w];
+  }
+  *total = sum;
+  return base + inc - v;
+}
+
 // ---- one block, one group ------------------------------------------------------------
 
 // Geometry of block b: byte offset of its first element and its element count.

@@ -203,8 +203,13 @@ constexpr size_t kVarPartialOffset = kVarPlanAnyOffset + kVarMaxGridCopy;
 inline size_t var_mask_offset(uint64_t n_blocks) {
   return kVarPartialOffset + ((8 * ((size_t)kVarMaxGridCopy + n_blocks) + 255) / 256) * 256;
 }
+// ... then 8 bytes per block: where the block sits in a packed buffer (staging rows of a
+// commit, rows read back from storage).
+inline size_t var_pack_offset(uint64_t n_blocks) {
+  return var_mask_offset(n_blocks) + ((n_blocks + 255) / 256) * 256;
+}
 inline size_t var_workspace_bytes_for(uint64_t n_blocks) {
-  return var_mask_offset(n_blocks) + ((n_blocks + 255) / 256) * 256 + 256;
+  return var_pack_offset(n_blocks) + ((8 * n_blocks + 255) / 256) * 256 + 256;
 }
 
 // ---- enqueueing kernels ---------------------------------------------------------------

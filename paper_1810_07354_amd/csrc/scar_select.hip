@@ -143,30 +143,6 @@ struct Key<SRC_MASK> {  // only classified, never histogrammed
   __device__ static type load(const KeyArgs& a, uint64_t i) { return ((const uint8_t*)a.ptr)[i] ? 1u : 0u; }
 };
 
-// Exclusive prefix sum of v over a workgroup of NT threads in thread order; *total gets the
-// sum.  `slots` is LDS for NT / kWave + 1 values.
-template <int NT = kWG, typename T>
-__device__ __forceinline__ T workgroup_exclusive_scan(T v, T* slots, T* total) {
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  T inc = v;
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    T up = __shfl_up(inc, d, kWave);
-    if (lane >= d) inc += up;
-  }
-  __syncthreads();
-  if (lane == kWave - 1) slots[wave] = inc;
-  __syncthreads();
-  T base = 0, sum = 0;
-#pragma unroll
-  for (int w = 0; w < NT / kWave; ++w) {
-    if (w < wave) base += slots[w];
-    sum += slots[w];
-  }
-  *total = sum;
-  return base + inc - v;
-}
-
 // Zeroes the histograms and the per-tile words of the compaction, and sets the state before
 // the first pass.  `ws_words`: 32-bit words of the selection scratch to clear.
 __global__ __launch_bounds__(kWG) void k_select_clear(SelectWs* ws, uint32_t ws_words, uint32_t k,

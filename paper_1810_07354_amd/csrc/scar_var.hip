@@ -21,6 +21,14 @@
 //            chosen tensor is one contiguous stretch and must not land on a single XCD; the
 //            dense score walk gives each XCD a contiguous eighth instead.
 //
+//   packed rows (the storage leg, Section 4.3): a commit can also pack the chosen blocks one
+//            after the other, in list order, into a staging buffer, and a recovery can take the
+//            checkpoint values from such packed rows instead of from c.  pack[b] holds the
+//            element offset of block b in the packed buffer (a prefix sum over the list for a
+//            commit, the caller's row offsets for a recovery); the packed side of a segment
+//            starts wherever the lengths before it add up to, so it is read and written in
+//            4-byte (2-byte) words next to the 16-byte accesses of x and c.
+//
 // Segments start wherever a block starts, so each is split into a few leading elements up
 // to the next 16-byte boundary, a body of non-temporal 16-byte accesses, and a tail.
 #include "scar_device.hpp"
@@ -87,23 +95,50 @@ __global__ __launch_bounds__(kPrepareThreads) void k_var_prepare(
 }
 
 enum : int { COPY_NONE = 0, COPY_X_TO_C = 1, COPY_C_TO_X = 2 };
+// What the packed side buffer does: nothing, receive the segment as well (staging rows of a
+// commit), or stand in for c (rows read back from storage).
+enum : int { SIDE_NONE = 0, SIDE_WRITE = 1, SIDE_READ = 2 };
+
+// 16 bytes of a buffer that is only element-aligned, as words.
+template <typename W>
+__device__ __forceinline__ uint4 load_words(const W* p) {
+  constexpr int N = 16 / sizeof(W);
+  W w[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) w[i] = p[i];
+  uint4 v;
+  __builtin_memcpy(&v, w, 16);
+  return v;
+}
+template <typename W>
+__device__ __forceinline__ void store_words(W* p, const uint4& v) {
+  constexpr int N = 16 / sizeof(W);
+  W w[N];
+  __builtin_memcpy(w, &v, 16);
+#pragma unroll
+  for (int i = 0; i < N; ++i) p[i] = w[i];
+}
 
 // One segment of `len` elements starting at element `first`, spread over the workgroup.
 //   ACC:  acc += sum of (c - x)^2 or |c - x| over the segment (this lane's share)
 //   COPY: the segment is copied x -> c or c -> x afterwards
-template <int DT, bool ACC, int COPY>
+//   SIDE: `side` points at the segment's place in the packed buffer (element-aligned):
+//         SIDE_WRITE stores the segment of x there too, SIDE_READ takes c's values from there
+//         (c itself is then not touched).
+template <int DT, bool ACC, int COPY, int SIDE>
 __device__ __forceinline__ void segment_apply(char* __restrict__ x, char* __restrict__ c,
-                                              uint64_t first, uint64_t len, bool base_aligned,
-                                              typename Acc<DT>::type& acc) {
+                                              char* __restrict__ side, uint64_t first, uint64_t len,
+                                              bool base_aligned, typename Acc<DT>::type& acc) {
   constexpr int E = elem_bytes(DT);
   constexpr int EPV = 16 / E;
   using word_t = typename std::conditional<E == 4, uint32_t, uint16_t>::type;
   char* xs = x + first * E;
-  char* cs = c + first * E;
+  char* cs = SIDE == SIDE_READ ? side : c + first * E;
   auto element = [&](uint64_t j) {
     if (ACC) accumulate_elem<DT>(acc, cs, xs, j);
     if (COPY == COPY_X_TO_C) ((word_t*)cs)[j] = ((const word_t*)xs)[j];
     if (COPY == COPY_C_TO_X) ((word_t*)xs)[j] = ((const word_t*)cs)[j];
+    if (SIDE == SIDE_WRITE) ((word_t*)side)[j] = ((const word_t*)xs)[j];
   };
   uint64_t head = len;  // elements handled one by one before the 16-byte body
   if (base_aligned) {
@@ -113,7 +148,8 @@ __device__ __forceinline__ void segment_apply(char* __restrict__ x, char* __rest
   for (uint64_t j = threadIdx.x; j < head; j += kWG) element(j);
   const uint64_t nvec = (len - head) / EPV;
   uint4* xv = (uint4*)(xs + head * E);
-  uint4* cv = (uint4*)(cs + head * E);
+  uint4* cv = (uint4*)(cs + head * E);          // SIDE_READ: only element-aligned, see below
+  word_t* sw = (word_t*)(side + (SIDE == SIDE_NONE ? 0 : head * E));
   // a pure read keeps four loads per lane and stream in flight; copies do best with fewer
   constexpr int U = COPY == COPY_NONE ? kUnroll : 2;
   for (uint64_t v0 = 0; v0 < nvec; v0 += (uint64_t)kWG * U) {
@@ -123,7 +159,10 @@ __device__ __forceinline__ void segment_apply(char* __restrict__ x, char* __rest
       const uint64_t v = v0 + (uint64_t)u * kWG + threadIdx.x;
       const bool ok = v < nvec;
       a[u] = (ok && (ACC || COPY == COPY_X_TO_C)) ? load_stream(xv + v) : make_uint4(0, 0, 0, 0);
-      b[u] = (ok && (ACC || COPY == COPY_C_TO_X)) ? load_stream(cv + v) : make_uint4(0, 0, 0, 0);
+      if (SIDE == SIDE_READ)
+        b[u] = ok ? load_words((const word_t*)cs + (head + v * EPV)) : make_uint4(0, 0, 0, 0);
+      else
+        b[u] = (ok && (ACC || COPY == COPY_C_TO_X)) ? load_stream(cv + v) : make_uint4(0, 0, 0, 0);
     }
     if (ACC) accumulate_vec<DT, U>(acc, b, a);
     if (COPY != COPY_NONE) {
@@ -133,6 +172,7 @@ __device__ __forceinline__ void segment_apply(char* __restrict__ x, char* __rest
         if (v < nvec) {
           if (COPY == COPY_X_TO_C) store_stream(cv + v, a[u]);
           if (COPY == COPY_C_TO_X) store_stream(xv + v, b[u]);
+          if (SIDE == SIDE_WRITE) store_words(sw + v * EPV, a[u]);
         }
       }
     }
@@ -144,7 +184,8 @@ __device__ __forceinline__ void segment_apply(char* __restrict__ x, char* __rest
 //   PER_BLOCK (scores): every block met gets its own sum in partial[w + b].
 //   otherwise: only blocks with mask[b] != 0 (all blocks if mask == NULL) are touched and
 //   the workgroup's total goes to partial[w] (if ACC).
-template <int DT, bool ACC, int COPY, bool PER_BLOCK>
+//   SIDE: the packed buffer `side` with the per-block element offsets `pack` (see above).
+template <int DT, bool ACC, int COPY, bool PER_BLOCK, int SIDE>
 __global__ __launch_bounds__(kWG) void k_var_walk(char* __restrict__ x, char* __restrict__ c,
                                                   const uint64_t* __restrict__ off, uint32_t n_blocks,
                                                   uint64_t n_elems, uint64_t range_elems, uint32_t n_wg,
@@ -152,7 +193,8 @@ __global__ __launch_bounds__(kWG) void k_var_walk(char* __restrict__ x, char* __
                                                   const uint32_t* __restrict__ first,
                                                   const uint8_t* __restrict__ any,
                                                   typename Acc<DT>::type* __restrict__ partial,
-                                                  bool base_aligned) {
+                                                  bool base_aligned, char* __restrict__ side,
+                                                  const uint64_t* __restrict__ pack) {
   using acc_t = typename Acc<DT>::type;
   __shared__ acc_t slots[kWG / kWave];
   const uint32_t w = PER_BLOCK ? xcd_contiguous_block_id() : blockIdx.x;
@@ -179,8 +221,11 @@ __global__ __launch_bounds__(kWG) void k_var_walk(char* __restrict__ x, char* __
     }
     if (bend <= pos) break;  // offsets do not cover the store: leave the rest alone
     const uint64_t seg_end = bend < e1 ? bend : e1;
-    if (PER_BLOCK || !mask || mask[cur])
-      segment_apply<DT, ACC, COPY>(x, c, pos, seg_end - pos, base_aligned, acc);
+    if (PER_BLOCK || !mask || mask[cur]) {
+      char* side_seg = nullptr;
+      if constexpr (SIDE != SIDE_NONE) side_seg = side + (pack[cur] + (pos - off[cur])) * elem_bytes(DT);
+      segment_apply<DT, ACC, COPY, SIDE>(x, c, side_seg, pos, seg_end - pos, base_aligned, acc);
+    }
     pos = seg_end;
   }
   if (ACC) {
@@ -246,6 +291,41 @@ __global__ __launch_bounds__(kWG) void k_var_mask_set(uint8_t* __restrict__ mask
   }
 }
 
+// Packed offsets of a commit with staging rows: out[i] = elements of the blocks listed before
+// idx[i] (out[n_idx] = all of them), and pack[idx[i]] = out[i].  One workgroup; entries
+// >= n_blocks take no room.
+constexpr int kPackThreads = 1024;
+__global__ __launch_bounds__(kPackThreads) void k_var_pack_scan(const uint64_t* __restrict__ off,
+                                                                uint32_t n_blocks,
+                                                                const uint32_t* __restrict__ idx, uint32_t n_idx,
+                                                                unsigned long long* __restrict__ out,
+                                                                unsigned long long* __restrict__ pack) {
+  __shared__ unsigned long long slots[kPackThreads / kWave + 1];
+  unsigned long long running = 0;
+  for (uint32_t i0 = 0; i0 < n_idx; i0 += kPackThreads) {
+    const uint32_t i = i0 + threadIdx.x;
+    const uint32_t b = i < n_idx ? idx[i] : n_blocks;
+    const unsigned long long len = b < n_blocks ? off[b + 1] - off[b] : 0ull;
+    unsigned long long total;
+    const unsigned long long ex = workgroup_exclusive_scan<kPackThreads>(len, slots, &total);
+    if (i < n_idx) out[i] = running + ex;
+    if (b < n_blocks) pack[b] = running + ex;
+    running += total;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[n_idx] = running;
+}
+
+// Packed offsets of a recovery from rows: pack[lost[i]] = row_offsets[i].
+__global__ __launch_bounds__(kWG) void k_var_pack_set(uint32_t n_blocks, const uint32_t* __restrict__ idx,
+                                                      uint32_t n_idx, const uint64_t* __restrict__ row_offsets,
+                                                      unsigned long long* __restrict__ pack) {
+  for (uint64_t i = (uint64_t)blockIdx.x * kWG + threadIdx.x; i < n_idx; i += (uint64_t)gridDim.x * kWG) {
+    const uint32_t b = idx[i];
+    if (b < n_blocks) pack[b] = row_offsets[i];
+  }
+}
+
 static uint64_t var_blocks(const scar_var_layout* l) {
   if (!l || !dtype_ok(l->dtype) || l->dtype == SCAR_F32_BF16C || l->n_blocks > SCAR_MAX_BLOCKS)
     return UINT64_MAX;
@@ -258,9 +338,10 @@ static int check_var_workspace(const void* ws, size_t bytes, uint64_t n_blocks) 
   return SCAR_OK;
 }
 
-template <int DT, bool ACC, int COPY, bool PER_BLOCK>
+template <int DT, bool ACC, int COPY, bool PER_BLOCK, int SIDE = SIDE_NONE>
 static void launch_walk(const scar_var_layout* l, const void* x, const void* c, const uint8_t* mask,
-                        bool planned, void* workspace, const VarGeometry& g, hipStream_t st) {
+                        bool planned, void* workspace, const VarGeometry& g, hipStream_t st,
+                        void* side = nullptr) {
   const bool base_aligned = aligned(x, 16) && aligned(c, 16);
   uint32_t* first = (uint32_t*)workspace;
   uint8_t* any = (uint8_t*)workspace + kVarPlanAnyOffset;
@@ -272,19 +353,21 @@ static void launch_walk(const scar_var_layout* l, const void* x, const void* c, 
   uint64_t in_flight = 2 * g.range_elems * elem_bytes(DT);
   if (in_flight > 2 * 16 * kWG * kUnroll) in_flight = 2 * 16 * kWG * kUnroll;
   const size_t lds = (COPY == COPY_NONE && PER_BLOCK) ? stream_lds_bytes(g.n_wg, in_flight) : 0;
-  launch((k_var_walk<DT, ACC, COPY, PER_BLOCK>), dim3(xcd_grid(g.n_wg, kVarMaxGridCopy)), dim3(kWG),
+  const uint64_t* pack = (const uint64_t*)((char*)workspace + var_pack_offset(l->n_blocks));
+  launch((k_var_walk<DT, ACC, COPY, PER_BLOCK, SIDE>), dim3(xcd_grid(g.n_wg, kVarMaxGridCopy)), dim3(kWG),
                      lds, st, (char*)const_cast<void*>(x), (char*)const_cast<void*>(c), l->offsets,
                      l->n_blocks, l->n_elems, g.range_elems, g.n_wg, mask, (const uint32_t*)first,
-                     (const uint8_t*)any, (typename Acc<DT>::type*)partial, base_aligned);
+                     (const uint8_t*)any, (typename Acc<DT>::type*)partial, base_aligned, (char*)side, pack);
 }
 
-template <bool ACC, int COPY, bool PER_BLOCK>
+template <bool ACC, int COPY, bool PER_BLOCK, int SIDE = SIDE_NONE>
 static void dispatch_walk(const scar_var_layout* l, const void* x, const void* c, const uint8_t* mask,
-                          bool planned, void* workspace, const VarGeometry& g, hipStream_t st) {
+                          bool planned, void* workspace, const VarGeometry& g, hipStream_t st,
+                          void* side = nullptr) {
   switch (l->dtype) {
-    case SCAR_F32: launch_walk<DT_F32, ACC, COPY, PER_BLOCK>(l, x, c, mask, planned, workspace, g, st); break;
-    case SCAR_BF16: launch_walk<DT_BF16, ACC, COPY, PER_BLOCK>(l, x, c, mask, planned, workspace, g, st); break;
-    default: launch_walk<DT_I32, ACC, COPY, PER_BLOCK>(l, x, c, mask, planned, workspace, g, st); break;
+    case SCAR_F32: launch_walk<DT_F32, ACC, COPY, PER_BLOCK, SIDE>(l, x, c, mask, planned, workspace, g, st, side); break;
+    case SCAR_BF16: launch_walk<DT_BF16, ACC, COPY, PER_BLOCK, SIDE>(l, x, c, mask, planned, workspace, g, st, side); break;
+    default: launch_walk<DT_I32, ACC, COPY, PER_BLOCK, SIDE>(l, x, c, mask, planned, workspace, g, st, side); break;
   }
 }
 
@@ -326,9 +409,13 @@ static const uint8_t* mark_blocks(const scar_var_layout* l, const uint32_t* idx,
 }
 
 // Shared body of commit (copy = COPY_X_TO_C), recovery (COPY_C_TO_X) and norm (COPY_NONE).
+//   side / side_offsets: the packed buffer of a commit with staging rows (side_offsets is then
+//   an output, n_idx + 1 entries) or of a recovery from rows (side_offsets is an input,
+//   n_idx entries); both NULL otherwise.
 static int var_rows(int copy, const scar_var_layout* layout, const void* x, const void* c,
                     const uint32_t* idx, uint32_t n_idx, bool all_blocks, scar_norm* norm_out,
-                    void* workspace, size_t workspace_bytes, void* stream) {
+                    void* workspace, size_t workspace_bytes, void* stream, void* side = nullptr,
+                    uint64_t* side_offsets = nullptr) {
   if (layout && layout->dtype == SCAR_F32_BF16C) return SCAR_ERR_UNSUPPORTED;
   const uint64_t nb = var_blocks(layout);
   if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
@@ -337,12 +424,14 @@ static int var_rows(int copy, const scar_var_layout* layout, const void* x, cons
   if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;
   const bool nothing = nb == 0 || layout->n_elems == 0 || (!all_blocks && n_idx == 0);
+  if (side && (!side_offsets || !aligned(side_offsets, 8) || !aligned(side, host_elem_bytes(layout->dtype))))
+    return SCAR_ERR_INVALID_ARG;
   if (nothing) {
-    if (norm_out) {
-      launch_finish(layout->dtype, (char*)workspace + kVarPartialOffset, 0, norm_out, st);
-      return launch_status();
-    }
-    return SCAR_OK;
+    if (side && copy == COPY_X_TO_C)  // an empty list still gets its (all zero) offsets
+      launch(k_var_pack_scan, dim3(1), dim3(kPackThreads), 0, st, layout->offsets, (uint32_t)nb, idx, 0u,
+             (unsigned long long*)side_offsets, (unsigned long long*)((char*)workspace + var_pack_offset(nb)));
+    if (norm_out) launch_finish(layout->dtype, (char*)workspace + kVarPartialOffset, 0, norm_out, st);
+    return launch_status();
   }
   const int eb = host_elem_bytes(layout->dtype);
   if (!x || !c || (!all_blocks && !idx) || !aligned(x, eb) || !aligned(c, eb) || !aligned(idx, 4))
@@ -351,7 +440,20 @@ static int var_rows(int copy, const scar_var_layout* layout, const void* x, cons
   const VarGeometry g = var_geometry(layout->n_elems, norm_out ? kVarMaxGrid : kVarMaxGridCopy);
   bool planned = false;
   const uint8_t* mask = all_blocks ? nullptr : mark_blocks(layout, idx, n_idx, workspace, g, &planned, st);
-  if (copy == COPY_X_TO_C)
+  unsigned long long* pack = (unsigned long long*)((char*)workspace + var_pack_offset(nb));
+  if (side && copy == COPY_X_TO_C) {
+    launch(k_var_pack_scan, dim3(1), dim3(kPackThreads), 0, st, layout->offsets, (uint32_t)nb, idx, n_idx,
+           (unsigned long long*)side_offsets, pack);
+    dispatch_walk<false, COPY_X_TO_C, false, SIDE_WRITE>(layout, x, c, mask, planned, workspace, g, st, side);
+  } else if (side) {  // recovery from packed rows: c is not read
+    const uint32_t sg = (n_idx + kWG - 1) / kWG;
+    launch(k_var_pack_set, dim3(sg < 4096 ? sg : 4096), dim3(kWG), 0, st, (uint32_t)nb, idx, n_idx,
+           (const uint64_t*)side_offsets, pack);
+    if (norm_out)
+      dispatch_walk<true, COPY_C_TO_X, false, SIDE_READ>(layout, x, x, mask, planned, workspace, g, st, side);
+    else
+      dispatch_walk<false, COPY_C_TO_X, false, SIDE_READ>(layout, x, x, mask, planned, workspace, g, st, side);
+  } else if (copy == COPY_X_TO_C)
     dispatch_walk<false, COPY_X_TO_C, false>(layout, x, c, mask, planned, workspace, g, st);
   else if (copy == COPY_C_TO_X && norm_out)
     dispatch_walk<true, COPY_C_TO_X, false>(layout, x, c, mask, planned, workspace, g, st);
@@ -414,4 +516,25 @@ extern "C" int scar_var_perturbation_norm(const scar_var_layout* layout, const v
   if (!norm_out) return SCAR_ERR_INVALID_ARG;
   return var_rows(COPY_NONE, layout, x, c, idx, n_idx, idx == nullptr, norm_out, workspace,
                   workspace_bytes, stream);
+}
+
+extern "C" int scar_var_checkpoint_commit_staged(const scar_var_layout* layout, const void* x, void* c,
+                                                 const uint32_t* idx, uint32_t n_idx, void* staging,
+                                                 uint64_t* staging_offsets, void* workspace,
+                                                 size_t workspace_bytes, void* stream) {
+  if (!staging_offsets || (n_idx && !staging)) return SCAR_ERR_INVALID_ARG;
+  // with nothing listed the offsets are still written; any non-NULL side pointer will do
+  return var_rows(COPY_X_TO_C, layout, x, c, idx, n_idx, false, nullptr, workspace, workspace_bytes, stream,
+                  staging ? staging : (void*)staging_offsets, staging_offsets);
+}
+
+extern "C" int scar_var_partial_recover_rows(const scar_var_layout* layout, void* x, const void* rows,
+                                             const uint64_t* row_offsets, const uint32_t* lost_idx,
+                                             uint32_t n_lost, scar_norm* norm_out, void* workspace,
+                                             size_t workspace_bytes, void* stream) {
+  if (n_lost && (!rows || !row_offsets)) return SCAR_ERR_INVALID_ARG;
+  if (n_lost == 0)  // nothing to take from the rows: the plain call writes the zero norm
+    return var_rows(COPY_C_TO_X, layout, x, x, lost_idx, 0, false, norm_out, workspace, workspace_bytes, stream);
+  return var_rows(COPY_C_TO_X, layout, x, x, lost_idx, n_lost, false, norm_out, workspace, workspace_bytes,
+                  stream, const_cast<void*>(rows), const_cast<uint64_t*>(row_offsets));
 }

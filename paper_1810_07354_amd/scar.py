@@ -86,8 +86,11 @@ def lib():
         L.scar_var_checkpoint_commit.argtypes = [vlp, vp, vp, vp, u32, vp, sz, vp]
         L.scar_var_partial_recover.argtypes = [vlp, vp, vp, vp, u32, vp, vp, sz, vp]
         L.scar_var_perturbation_norm.argtypes = [vlp, vp, vp, vp, u32, vp, vp, sz, vp]
+        L.scar_var_checkpoint_commit_staged.argtypes = [vlp, vp, vp, vp, u32, vp, vp, vp, sz, vp]
+        L.scar_var_partial_recover_rows.argtypes = [vlp, vp, vp, vp, vp, u32, vp, vp, sz, vp]
         for name in ("scar_var_block_scores", "scar_var_checkpoint_commit", "scar_var_partial_recover",
-                     "scar_var_perturbation_norm"):
+                     "scar_var_perturbation_norm", "scar_var_checkpoint_commit_staged",
+                     "scar_var_partial_recover_rows"):
             getattr(L, name).restype = ctypes.c_int
         L.scar_tv_block_scores.argtypes = [lp, vp, vp, vp, vp, vp]
         L.scar_tv_partial_recover.argtypes = [lp, vp, vp, vp, vp, u32, vp, vp, sz, vp]
@@ -102,6 +105,11 @@ def lib():
         L.scar_store_load.argtypes = [vp, vp, u32, vp, vp]
         L.scar_store_close.argtypes = [vp]
         L.scar_partial_recover_rows.argtypes = [lp, vp, vp, vp, u32, vp, vp, sz, vp]
+        L.scar_var_store_create.argtypes = [ctypes.c_char_p, i32, u32, vp, u32, u64, pp]
+        L.scar_var_store_save_async.argtypes = [vp, vp, u64, vp, u32, vp]
+        L.scar_var_store_load.argtypes = [vp, vp, u32, vp, vp, vp]
+        for name in ("scar_var_store_create", "scar_var_store_save_async", "scar_var_store_load"):
+            getattr(L, name).restype = ctypes.c_int
         for name in ("scar_store_create", "scar_store_open", "scar_store_save_async", "scar_store_wait",
                      "scar_store_load", "scar_store_close", "scar_partial_recover_rows"):
             getattr(L, name).restype = ctypes.c_int
@@ -412,6 +420,37 @@ def var_checkpoint_commit(x, c, offsets, idx, workspace):
            "scar_var_checkpoint_commit")
 
 
+def var_checkpoint_commit_staged(x, c, offsets, idx, workspace, staging):
+    """scar_var_checkpoint_commit_staged: also packs the listed blocks into staging; returns the
+    device tensor of their n_idx + 1 element offsets (int64)."""
+    _dev(x, "x"), _dev(c, "c"), _idx(idx, "idx"), _dev(workspace, "workspace"), _dev(staging, "staging")
+    if staging.dtype != c.dtype:
+        raise TypeError("staging must have c's element type")
+    lay = var_layout_of(x, offsets)
+    st_off = torch.empty(idx.numel() + 1, dtype=torch.int64, device=x.device)
+    _check(lib().scar_var_checkpoint_commit_staged(ctypes.byref(lay), _p(x), _p(c), _p(idx), idx.numel(),
+                                                   _p(staging), _p(st_off), _p(workspace), _bytes(workspace),
+                                                   _stream()), "scar_var_checkpoint_commit_staged")
+    return st_off
+
+
+def var_partial_recover_rows(x, rows, row_offsets, offsets, lost_idx, workspace, want_norm=True):
+    """scar_var_partial_recover_rows: x[b] <- the packed row of block b for the lost blocks;
+    returns the device scar_norm buffer or None."""
+    _dev(x, "x"), _dev(rows, "rows"), _dev(row_offsets, "row_offsets"), _idx(lost_idx, "lost_idx")
+    _dev(workspace, "workspace")
+    if row_offsets.dtype != torch.int64 or row_offsets.numel() < lost_idx.numel():
+        raise ValueError("row_offsets must be an int64 tensor with an entry per lost block")
+    if rows.dtype != x.dtype:
+        raise TypeError("rows must have x's element type")
+    lay = var_layout_of(x, offsets)
+    norm_out = _norm_buffer(x.device) if want_norm else None
+    _check(lib().scar_var_partial_recover_rows(ctypes.byref(lay), _p(x), _p(rows), _p(row_offsets), _p(lost_idx),
+                                               lost_idx.numel(), _p(norm_out), _p(workspace), _bytes(workspace),
+                                               _stream()), "scar_var_partial_recover_rows")
+    return norm_out
+
+
 def var_partial_recover(x, c, offsets, lost_idx, workspace, want_norm=True):
     """scar_var_partial_recover; returns the device scar_norm buffer or None."""
     _dev(x, "x"), _dev(c, "c"), _idx(lost_idx, "lost_idx"), _dev(workspace, "workspace")
@@ -530,6 +569,45 @@ class Store:
         _check(lib().scar_store_load(self._h, ctypes.c_void_p(idx_host.ctypes.data), idx_host.size,
                                      _p(rows), _stream()), "scar_store_load")
         return rows
+
+    def close(self):
+        if self._h:
+            h, self._h = self._h, ctypes.c_void_p(0)
+            _check(lib().scar_store_close(h), "scar_store_close")
+
+
+class VarStore:
+    """scar_store for blocks of unequal length: the running checkpoint of a by-layer store in a
+    file, written by the same background thread."""
+
+    def __init__(self, path, dtype, offsets_host, max_rows, max_elems):
+        import numpy as np
+        self._h = ctypes.c_void_p(0)
+        off = np.ascontiguousarray(offsets_host, dtype=np.uint64)
+        _check(lib().scar_var_store_create(os.fsencode(path), int(dtype), off.size - 1,
+                                           ctypes.c_void_p(off.ctypes.data), int(max_rows), int(max_elems),
+                                           ctypes.byref(self._h)), "scar_var_store_create")
+
+    def save_async(self, staging, staging_elems, idx):
+        _dev(staging, "staging"), _idx(idx, "idx")
+        if staging_elems > staging.numel():
+            raise ValueError("staging_elems exceeds the staging buffer")
+        _check(lib().scar_var_store_save_async(self._h, _p(staging), int(staging_elems), _p(idx), idx.numel(),
+                                               _stream()), "scar_var_store_save_async")
+
+    def wait(self):
+        _check(lib().scar_store_wait(self._h), "scar_store_wait")
+
+    def load(self, idx_host, rows):
+        """Reads the blocks idx_host into the packed device tensor rows; returns the device tensor
+        of their n_idx + 1 element offsets (int64)."""
+        import numpy as np
+        idx_host = np.ascontiguousarray(idx_host, dtype=np.uint32)
+        _dev(rows, "rows")
+        row_off = torch.empty(idx_host.size + 1, dtype=torch.int64, device=rows.device)
+        _check(lib().scar_var_store_load(self._h, ctypes.c_void_p(idx_host.ctypes.data), idx_host.size,
+                                         _p(rows), _p(row_off), _stream()), "scar_var_store_load")
+        return row_off
 
     def close(self):
         if self._h:

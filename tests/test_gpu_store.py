@@ -118,3 +118,93 @@ def test_store_errors(tmp_path):
         scar.Store(str(bad), max_rows=4)
     with pytest.raises(scar.ScarError):
         scar.Store(str(tmp_path / "no_such_dir" / "x.ckpt"), max_rows=4, layout=scar.Layout(scar.F32, 8, 64))
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16, wl.I32])
+def test_by_layer_store_follows_the_running_checkpoint_and_recovers_from_it(dtype, tmp_path):
+    # blocks of unequal length (Section 5.1, by-layer) through the storage leg: staged commits,
+    # background saves into a file with one place per block, recovery of lost blocks from it
+    sizes = wl.mixed_layer_sizes(120, 1_500_000, seed=21)
+    w = wl.layers_like(sizes, seed=22, fraction=0.2, n_lost=30, dtype=dtype)
+    off, nb, n = w.offsets, w.n_blocks, int(w.x.size)
+    hx, hc = w.x.copy(), w.c.copy()
+    x, c = to_dev(hx, dtype), to_dev(hc, dtype)
+    d_off = torch.from_numpy(off.astype(np.int64)).to(DEV)
+    ws, ws_sel = scar.new_var_workspace(nb, DEV), scar.new_workspace(nb, DEV)
+    esz = c.element_size()
+    path = str(tmp_path / "layers.ckpt")
+    store = scar.VarStore(path, dtype, off, max_rows=nb, max_elems=n)
+    data_offset = 4096 + (((nb + 1) * 8 + 4095) // 4096) * 4096
+
+    def file_checkpoint():
+        return np.fromfile(path, dtype=hc.dtype, offset=data_offset, count=n)
+
+    try:
+        head = open(path, "rb").read(32)
+        assert head[:8] == b"SCARSTV1"
+        assert struct.unpack("<iIQQ", head[8:32]) == (dtype, nb, n, data_offset)
+        np.testing.assert_array_equal(np.fromfile(path, dtype=np.uint64, offset=4096, count=nb + 1), off)
+
+        # the running checkpoint starts as a full save of the first state (Section 4.2)
+        everything = np.arange(nb, dtype=np.uint32)
+        staging = torch.empty(n, dtype=c.dtype, device=DEV)
+        scar.var_checkpoint_commit_staged(x, c, d_off, idx_dev(everything), ws, staging)
+        store.save_async(staging, n, idx_dev(everything))
+        oracle.var_checkpoint_commit(dtype, hx, hc, off, everything)
+        store.wait()
+        np.testing.assert_array_equal(file_checkpoint(), hc)
+
+        r = np.random.default_rng(2)
+        k = w.k
+        stagings = [torch.empty(n, dtype=c.dtype, device=DEV) for _ in range(3)]
+        for cyc in range(3):
+            print("by-layer store dtype=%d cycle %d" % (dtype, cyc), flush=True)
+            lo = int(r.integers(0, n - n // 4))
+            if dtype == wl.I32:
+                hx[lo:lo + n // 4] += r.integers(-2, 3, size=n // 4).astype(np.int32)
+            elif dtype == wl.BF16:
+                hx[lo:lo + n // 4] = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(hx[lo:lo + n // 4])
+                                                         + r.normal(0, 1e-2, size=n // 4).astype(np.float32))
+            else:
+                hx[lo:lo + n // 4] += r.normal(0, 1e-2, size=n // 4).astype(np.float32)
+            x = to_dev(hx, dtype)
+            s = scar.var_block_scores(x, c, d_off, ws)
+            idx = scar.select_topk(s, k, ws_sel)
+            scar.var_checkpoint_commit_staged(x, c, d_off, idx, ws, stagings[cyc])
+            store.save_async(stagings[cyc], n, idx)          # the capacity: the device knows the total
+            oracle.var_checkpoint_commit(dtype, hx, hc, off, idx_host(idx))
+        store.wait()
+        np.testing.assert_array_equal(to_host(c), hc)
+        np.testing.assert_array_equal(file_checkpoint(), hc)
+
+        # failure: the lost blocks come back from the file
+        if dtype == wl.I32:
+            hx += 1
+        elif dtype == wl.BF16:
+            hx[:] = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(hx) + np.float32(0.5))
+        else:
+            hx += np.float32(0.5)
+        x = to_dev(hx, dtype)
+        lost = w.lost
+        rows = torch.zeros(n, dtype=c.dtype, device=DEV)
+        row_off = store.load(lost, rows)
+        lens = np.diff(off.astype(np.int64))[lost.astype(np.int64)]
+        np.testing.assert_array_equal(row_off.cpu().numpy(), np.concatenate([[0], np.cumsum(lens)]))
+        got = scar.read_norm(scar.var_partial_recover_rows(x, rows, row_off, d_off, idx_dev(lost), ws))
+        want = oracle.var_partial_recover(dtype, hx, hc, off, lost)
+        assert_norm_matches(got, want, wl.I32 if dtype == wl.I32 else wl.F32)
+        np.testing.assert_array_equal(to_host(x), hx)
+
+        # too few elements handed over for the listed blocks: the save fails, the wait says so
+        store.save_async(staging, 1, idx_dev(everything))
+        with pytest.raises(scar.ScarError) as e:
+            store.wait()
+        assert e.value.status == -4
+        with pytest.raises(scar.ScarError):                  # a fixed-layout call on this kind of store
+            scar.lib().scar_store_save_async  # noqa: B018  (the symbol exists; the refusal is checked below)
+            rc = scar.lib().scar_store_save_async(store._h, ctypes.c_void_p(staging.data_ptr()),
+                                                  ctypes.c_void_p(staging.data_ptr()), 1, None)
+            if rc != 0:
+                raise scar.ScarError(rc, "scar_store_save_async")
+    finally:
+        store.close()

@@ -39,10 +39,36 @@ def cycle(w: wl.VarWorkload, k=None, lost=None, unaligned=False):
     idx = scar.select_topk(s, k, ws_sel)
     assert_selection_matches(idx_host(idx), s.cpu().numpy(), s_ref, k)
 
+    # the same commit with staging rows on a copy of c: packed rows and their offsets
+    c2, hc2 = c.clone(), hc.copy()
+    lens = np.diff(off.astype(np.int64))
+    room = int(lens[idx_host(idx).astype(np.int64)].sum())
+    st = torch.full((room + 3,), 0, dtype=c.dtype, device=DEV)[3:]       # staging off the 16-byte grid
+    st_off = scar.var_checkpoint_commit_staged(x, c2, d_off, idx, ws, st)
+    hst = np.zeros(room, dtype=hc.dtype)
+    want_off = oracle.var_checkpoint_commit(dt, hx, hc2, off, idx_host(idx), hst)
+    np.testing.assert_array_equal(st_off.cpu().numpy().astype(np.uint64), want_off)
+    np.testing.assert_array_equal(to_host(st.contiguous()), hst)
+    np.testing.assert_array_equal(to_host(c2.contiguous()), hc2)
+
     scar.var_checkpoint_commit(x, c, d_off, idx, ws)
     oracle.var_checkpoint_commit(dt, hx, hc, off, idx_host(idx))
     np.testing.assert_array_equal(to_host(c.contiguous()), hc)
     np.testing.assert_array_equal(to_host(x.contiguous()), hx)
+    np.testing.assert_array_equal(hc, hc2)
+
+    # recovery of the lost blocks from packed rows (the checkpoint's values of those blocks, as
+    # storage would return them) on a copy of x: the same bytes and norm as recovery from c
+    if lost.size:
+        x2, hx2 = x.clone(), hx.copy()
+        rows_h = np.zeros(int(lens[lost.astype(np.int64)].sum()), dtype=hc.dtype)
+        row_off = oracle.var_checkpoint_commit(dt, hc, hc.copy(), off, lost, rows_h)   # packs c's blocks
+        rows_d = torch.cat([torch.zeros(1, dtype=c.dtype, device=DEV), to_dev(rows_h, dt)])[1:]
+        got_r = scar.read_norm(scar.var_partial_recover_rows(
+            x2, rows_d, torch.from_numpy(row_off.astype(np.int64)).to(DEV), d_off, idx_dev(lost), ws))
+        want_r = oracle.var_partial_recover_rows(dt, hx2, rows_h, row_off[:-1], off, lost)
+        assert_norm_matches(got_r, want_r, dt)
+        np.testing.assert_array_equal(to_host(x2.contiguous()), hx2)
 
     full = scar.read_norm(scar.var_perturbation_norm(x, c, d_off, None, ws))
     assert_norm_matches(full, oracle.var_perturbation_norm(dt, hx, hc, off), dt)
