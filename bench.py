@@ -72,12 +72,54 @@ def stored_traffic(workload):
     return int(fields["traffic_bytes_per_launch"])
 
 
+SHAPE = {"dtype": "f32", "block_len": 1024, "n_blocks": 1 << 18}   # of --workload shape (set by main)
+
+
+def make_shape(dev):
+    """A store of any shape for `--workload shape`: n_blocks blocks of block_len elements (f32,
+    bf16, i32, or f32 with a bf16 checkpoint), c ~ N(0, 0.02) (counts: uniform 0..999), x = c plus
+    a small move of every element; k = 10 % of the blocks, an eighth of them lost."""
+    import torch
+    from paper_1810_07354_amd import workloads as wl
+    dt, L, nb = SHAPE["dtype"], SHAPE["block_len"], SHAPE["n_blocks"]
+    n = L * nb
+    g = torch.Generator(device=dev)
+    g.manual_seed(12)
+    if dt == "i32":
+        c = torch.randint(0, 1000, (n,), generator=g, device=dev, dtype=torch.int32)
+        x = c + torch.randint(-2, 3, (n,), generator=g, device=dev, dtype=torch.int32)
+    else:
+        c = torch.empty(n, device=dev).normal_(0.0, 0.02, generator=g)
+        x = c + 1e-3 * torch.empty(n, device=dev).normal_(generator=g)
+        if dt == "bf16":
+            x, c = x.to(torch.bfloat16), c.to(torch.bfloat16)
+        elif dt == "mixed":
+            c = c.to(torch.bfloat16)
+    k, n_lost = wl.k_of_fraction(0.10, nb), max(1, nb // 8)
+
+    def lost_of(cycle):
+        return wl.random_lost_blocks(nb, n_lost, 1000 + cycle)
+
+    def drift(cycle):
+        m = max(1, n // 10)
+        if x.dtype == torch.int32:
+            x[:m] += torch.randint(-2, 3, (m,), generator=g, device=dev, dtype=torch.int32)
+        else:
+            x[:m] = (x[:m].float() + 1e-3 * torch.empty(m, device=dev).normal_(generator=g)).to(x.dtype)
+
+    label = "%d blocks of %d x %s, k=10%%, lost=1/8" % (nb, L, dt)
+    return x, c, L, k, n_lost, lost_of, drift, label, None
+
+
 def make_workload(name, dev):
     """Returns (x, c, block_len, k, n_lost, lost_of(cycle), drift(cycle), label, weights);
     weights is None except for the total-variation workload (document lengths, on the device)."""
     import numpy as np
     import torch
     from paper_1810_07354_amd import workloads as wl
+
+    if name == "shape":
+        return make_shape(dev)
 
     def up(a, dtype):
         if dtype == wl.BF16:
@@ -561,7 +603,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="flat_f32",
                     choices=["flat_f32", "flat_bf16", "flat_mixed", "mlr", "mf", "lda", "cnn", "cnn@1", "cnn@10",
-                             "cnn@50", "layers", "doctopic", "giant"])
+                             "cnn@50", "layers", "doctopic", "giant", "shape"])
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16", "i32", "mixed"],
+                    help="--workload shape: element type (mixed = f32 with a bf16 checkpoint)")
+    ap.add_argument("--block-len", type=int, default=1024, help="--workload shape: elements per block")
+    ap.add_argument("--n-blocks", type=int, default=1 << 18, help="--workload shape: number of blocks")
     ap.add_argument("--strategy", default="priority", choices=STRATEGIES,
                     help="how K is chosen: the method (priority) or a comparison set-up of Section 5.4; "
                          "full = every block saved and every block recovered (traditional checkpointing)")
@@ -599,6 +645,7 @@ def main():
 
     if args.workload == "layers":
         return main_layers(args)
+    SHAPE.update(dtype=args.dtype, block_len=args.block_len, n_blocks=args.n_blocks)
 
     if args.calibrate_copy:
         # A plain copy of known size (1 GiB read, 1 GiB written per launch) so that a

@@ -123,9 +123,9 @@ size_t scar_workspace_bytes(uint64_t n_blocks);
  *   I32:        scores = int64_t[n_blocks], s_b = sum_j |x_j - c_j|, exact (for a row of
  *               topic counts this is twice the document-length-scaled total variation of
  *               Appendix C).
- * Reads x and c once; writes scores.  Stores of at most 2,048 blocks of 256 KiB or more (a
+ * Reads x and c once; writes scores.  Stores of at most 16,384 blocks of 64 KiB or more (a
  * tensor cut into a few large shards) are scored in pieces by many workgroups per block; the
- * pieces' sums wait in a fixed 512 KiB array inside the library (this call takes no workspace),
+ * pieces' sums wait in a fixed 2 MiB array inside the library (this call takes no workspace),
  * so two calls of that kind must not overlap on one GPU.  SCAR_F32_BF16C stores keep one
  * workgroup per block.  The copy calls below hand long rows out in 4 KiB pieces. */
 int scar_block_scores(const scar_layout* layout, const void* x, const void* c, void* scores,

@@ -393,14 +393,14 @@ static bool dispatch_scores_flat(int g, bool split, const scar_layout* l, const 
 // block's pieces in a fixed order (reproducible, no atomics).  The pieces depend only on the
 // layout, so listed blocks (scar_block_scores_rows) get bit for bit the scores of the full scan.
 //
-// The partial sums live in a fixed array inside the library's code object (512 KiB per GPU;
+// The partial sums live in a fixed array inside the library's code object (2 MiB per GPU;
 // scar_block_scores takes no workspace): calls of this kind on one GPU share it and must not
 // overlap.  In host code the array's name is only a handle; its device address is asked for
 // once per device and kept.
-constexpr uint32_t kGiantMaxPartials = 65536;
-constexpr uint32_t kGiantMaxBlocks = 2048;            // more blocks than this fill the chip by themselves
-constexpr uint64_t kGiantMinRowBytes = 256 * 1024;    // shorter rows: a workgroup per row is fine
-constexpr uint32_t kGiantPieceBytes = 64 * 1024;      // per stream and workgroup, at least
+constexpr uint32_t kGiantMaxPartials = 262144;
+constexpr uint32_t kGiantMaxBlocks = 16384;           // more blocks than this fill the chip by themselves
+constexpr uint64_t kGiantMinRowBytes = 64 * 1024;     // shorter rows: a workgroup per row is fine
+constexpr uint32_t kGiantPieceBytes = 16 * 1024;      // per stream and workgroup, at least: one round of loads
 static __device__ __align__(256) unsigned long long giant_partials[kGiantMaxPartials];
 
 constexpr int kGiantMaxDevices = 64;
@@ -437,9 +437,17 @@ __global__ __launch_bounds__(kWG) void k_giant_pieces(const char* __restrict__ x
       const BlockSpan sp = block_span(b, n_elems, block_len, elem_bytes(DT));
       const uint64_t lo = (uint64_t)piece * piece_elems;
       if (lo < sp.len) {
+        // each wavefront walks a contiguous quarter of the piece, as the wavefronts of the
+        // scan of 4 KiB blocks each walk a block (measured faster than the four striding
+        // through the whole piece together)
         const uint32_t len = (uint32_t)(sp.len - lo < piece_elems ? sp.len - lo : piece_elems);
-        const uint64_t off = sp.byte_off + lo * elem_bytes(DT);
-        acc = block_distance<DT, 256, VEC>(x + off, c + off, len, threadIdx.x);
+        const uint32_t quarter = piece_elems / (kWG / kWave);
+        const uint32_t q0 = (threadIdx.x / kWave) * quarter;
+        if (q0 < len) {
+          const uint32_t qlen = len - q0 < quarter ? len - q0 : quarter;
+          const uint64_t off = sp.byte_off + (lo + q0) * elem_bytes(DT);
+          acc = block_distance<DT, kWave, VEC>(x + off, c + off, qlen, threadIdx.x & (kWave - 1));
+        }
       }
     }
     acc = workgroup_sum(acc, slots);
@@ -478,7 +486,7 @@ static bool giant_geometry(const scar_layout* l, int eb, uint32_t n_blocks, uint
   const uint64_t room = kGiantMaxPartials / n_blocks;
   if (pieces > room) pieces = room;
   // whole 16-byte steps per piece, so that every piece starts as aligned as its block does
-  const uint64_t per = 16 / eb;
+  const uint64_t per = (uint64_t)(kWG / kWave) * 16 / eb;  // and each wavefront's quarter as well
   uint64_t pe = ((uint64_t)l->block_len + pieces - 1) / pieces;
   pe = (pe + per - 1) / per * per;
   *piece_elems = (uint32_t)pe;

@@ -158,12 +158,12 @@ def test_block_scores_of_rows_shorter_than_16_bytes(dtype, L):
 
 @pytest.mark.parametrize("dtype", [F32, BF16, I32])
 @pytest.mark.parametrize("nb,L,off", [(16, 1 << 20, 0), (5, 700_001, 0), (3, 1 << 18, 1), (40, 65_536 + 24, 4),
-                                      (2048, 1 << 16, 0)])
+                                      (2048, 1 << 16, 0), (16_384, 1 << 14, 0), (9000, 16_390, 3)])
 def test_block_scores_of_a_few_very_long_blocks(dtype, nb, L, off):
     # fewer blocks than the chip has room for workgroups: scored in pieces, many workgroups per
     # block (a ragged last block, bases off the 16-byte grid, rows that are not whole steps),
     # and the listed call must give the same bits
-    if dtype == BF16 and L * 2 < 256 * 1024:
+    if dtype == BF16 and L * 2 < 64 * 1024:
         L *= 2
     n = L * nb - L // 3
     hx, hc = make_store(dtype, n, seed=nb + L)
