@@ -57,6 +57,9 @@ def lib():
         L.oracle_tv_block_scores.argtypes = [i32, vp, vp, u64, u32, vp, vp]
         L.oracle_tv_perturbation_norm.argtypes = [i32, vp, vp, u64, u32, vp, vp, u32, ctypes.POINTER(Norm)]
         L.oracle_tv_partial_recover.argtypes = [i32, vp, vp, u64, u32, vp, vp, u32, ctypes.POINTER(Norm)]
+        L.oracle_var_tv_block_scores.argtypes = [i32, vp, vp, vp, u32, vp, vp]
+        L.oracle_var_tv_perturbation_norm.argtypes = [i32, vp, vp, vp, u32, vp, vp, u32, ctypes.POINTER(Norm)]
+        L.oracle_var_tv_partial_recover.argtypes = [i32, vp, vp, vp, u32, vp, vp, u32, ctypes.POINTER(Norm)]
         L.oracle_select_round.argtypes = [u32, u32, u64, vp]
         L.oracle_select_random.argtypes = [u32, u32, u64, u64, vp]
         L.oracle_philox4x32_10.argtypes = [vp, vp, vp]
@@ -338,3 +341,35 @@ def tv_partial_recover(dtype, x, c, block_len, lost, weights=None):
                                            lost.size, ctypes.byref(out)), "oracle_tv_partial_recover")
     return out.sum, out.norm, out.isum
 
+
+# ---- scaled total variation over blocks of unequal length -------------------------------------
+
+def var_tv_block_scores(dtype, x, c, offsets, weights=None):
+    x, c, off, w = _flat_x(x, dtype), _flat_c(c, dtype), _offsets(offsets), _weights(weights)
+    out = np.zeros(off.size - 1, dtype=np.float64)
+    _check(lib().oracle_var_tv_block_scores(dtype, _ptr(x), _ptr(c), _ptr(off), off.size - 1, _ptr(w), _ptr(out)),
+           "oracle_var_tv_block_scores")
+    return out
+
+
+def var_tv_perturbation_norm(dtype, x, c, offsets, weights=None, idx=None):
+    x, c, off, w = _flat_x(x, dtype), _flat_c(c, dtype), _offsets(offsets), _weights(weights)
+    out = Norm()
+    if idx is None:
+        ptr, n = ctypes.c_void_p(0), 0
+    else:
+        idx = _idx(idx)
+        keep = idx if idx.size else np.zeros(1, dtype=np.uint32)
+        ptr, n = ctypes.c_void_p(keep.ctypes.data), idx.size
+    _check(lib().oracle_var_tv_perturbation_norm(dtype, _ptr(x), _ptr(c), _ptr(off), off.size - 1, _ptr(w), ptr, n,
+                                                 ctypes.byref(out)), "oracle_var_tv_perturbation_norm")
+    return out.sum, out.norm, out.isum
+
+
+def var_tv_partial_recover(dtype, x, c, offsets, lost, weights=None):
+    x, c, off, w, lost = _flat_x(x, dtype), _flat_c(c, dtype), _offsets(offsets), _weights(weights), _idx(lost)
+    out = Norm()
+    _check(lib().oracle_var_tv_partial_recover(dtype, _ptr(x), _ptr(c), _ptr(off), off.size - 1, _ptr(w),
+                                               _ptr(lost), lost.size, ctypes.byref(out)),
+           "oracle_var_tv_partial_recover")
+    return out.sum, out.norm, out.isum

@@ -675,3 +675,51 @@ int oracle_tv_partial_recover(int dtype, void *x, const void *c, uint64_t n_elem
   return oracle_partial_recover(dtype, x, c, n_elems, block_len, lost, n_lost, NULL);
 }
 
+/* The same three in the scaled total variation for blocks of unequal length (rows that are
+ * distributions over vocabularies or topic sets of different sizes; Section 5.1, Appendix C):
+ * block b is [offsets[b], offsets[b+1]), its distance w_b * 1/2 * sum |x - c|. */
+int oracle_var_tv_block_scores(int dtype, const void *x, const void *c, const uint64_t *offsets,
+                               uint32_t n_blocks, const float *weights, double *scores) {
+  if (!tv_dtype_ok(dtype) || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
+  if (n_blocks == 0) return ORACLE_OK;
+  if (!scores || (offsets[n_blocks] && (!x || !c))) return ORACLE_ERR_ARG;
+  for (uint32_t b = 0; b < n_blocks; ++b)
+    scores[b] = (weights ? (double)weights[b] : 1.0) * block_tv(dtype, x, c, offsets[b], offsets[b + 1]);
+  return ORACLE_OK;
+}
+
+int oracle_var_tv_perturbation_norm(int dtype, const void *x, const void *c, const uint64_t *offsets,
+                                    uint32_t n_blocks, const float *weights, const uint32_t *idx,
+                                    uint32_t n_idx, oracle_norm *out) {
+  if (!tv_dtype_ok(dtype) || !offsets_ok(offsets, n_blocks) || !out) return ORACLE_ERR_ARG;
+  out->sum = out->norm = 0.0;
+  out->isum = 0;
+  uint32_t m = idx ? n_idx : n_blocks;
+  if (idx) {
+    int rc = check_indices(idx, n_idx, n_blocks);
+    if (rc) return rc;
+  }
+  double total = 0.0;
+  for (uint32_t i = 0; i < m; ++i) {
+    uint32_t b = idx ? idx[i] : i;
+    total += (weights ? (double)weights[b] : 1.0) * block_tv(dtype, x, c, offsets[b], offsets[b + 1]);
+  }
+  out->sum = out->norm = total;
+  return ORACLE_OK;
+}
+
+int oracle_var_tv_partial_recover(int dtype, void *x, const void *c, const uint64_t *offsets,
+                                  uint32_t n_blocks, const float *weights, const uint32_t *lost,
+                                  uint32_t n_lost, oracle_norm *norm_out) {
+  if (!tv_dtype_ok(dtype)) return ORACLE_ERR_ARG;
+  if (norm_out) {
+    oracle_norm zero = {0.0, 0.0, 0};
+    *norm_out = zero;
+    if (n_lost) {
+      int rc = oracle_var_tv_perturbation_norm(dtype, x, c, offsets, n_blocks, weights, lost, n_lost, norm_out);
+      if (rc) return rc;
+    }
+  }
+  return oracle_var_partial_recover(dtype, x, c, offsets, n_blocks, lost, n_lost, NULL);
+}
+

@@ -74,6 +74,12 @@ MUTANTS = [
      "memcpy((char *)x + lo * es, (const char *)rows + lo * es, len * es);"),
     ("unequal blocks: norm of the rows after the overwrite", "double d = load_real(dtype, rows, r0 + t) - load_real(dtype, x, lo + t);",
      "double d = load_real(dtype, rows, r0 + t) - load_real(dtype, rows, r0 + t);"),
+    ("unequal rows: document length ignored in the scaled score",
+     "    scores[b] = (weights ? (double)weights[b] : 1.0) * block_tv(dtype, x, c, offsets[b], offsets[b + 1]);",
+     "    scores[b] = block_tv(dtype, x, c, offsets[b], offsets[b + 1]);"),
+    ("unequal rows: scaled norm weighs by list position",
+     "    total += (weights ? (double)weights[b] : 1.0) * block_tv(dtype, x, c, offsets[b], offsets[b + 1]);",
+     "    total += (weights ? (double)weights[i] : 1.0) * block_tv(dtype, x, c, offsets[b], offsets[b + 1]);"),
     ("unequal blocks: commit one element short", "    if (hi > lo) memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo) * es);",
      "    if (hi > lo) memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo - 1) * es);"),
 ]

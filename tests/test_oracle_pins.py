@@ -847,3 +847,33 @@ def test_rescoring_listed_blocks_equals_rescoring_everything(dtype):
         oracle.block_scores_rows(dtype, x, c, L, np.array([40], dtype=np.uint32), stale)
     with pytest.raises(oracle.OracleError):
         oracle.block_scores_rows(dtype, x, c, L, np.array([3, 3], dtype=np.uint32), stale)
+
+
+def test_var_tv_closed_forms_and_reduction_to_equal_rows():
+    # rows of unequal length: disjoint one-hot rows have TV 1, equal rows 0, an empty row 0;
+    # x = c + a on t entries => t * a / 2; weights multiply; equal rows reduce to the fixed layout
+    off = np.array([0, 3, 3, 8, 10], dtype=np.uint64)                     # lengths 3 0 5 2
+    c = np.concatenate([one_hot(3, 0), one_hot(5, 1), np.array([0.5, 0.5], dtype=np.float32)])
+    x = np.concatenate([one_hot(3, 2), one_hot(5, 1), np.array([0.75, 0.25], dtype=np.float32)])
+    np.testing.assert_array_equal(oracle.var_tv_block_scores(F32, x, c, off), [1.0, 0.0, 0.0, 0.25])
+    w = np.array([40, 9, 7, 8], dtype=np.float32)
+    np.testing.assert_array_equal(oracle.var_tv_block_scores(F32, x, c, off, w), [40.0, 0.0, 0.0, 2.0])
+    assert oracle.var_tv_perturbation_norm(F32, x, c, off, w) == (42.0, 42.0, 0)
+    assert oracle.var_tv_perturbation_norm(F32, x, c, off, w, [3, 1]) == (2.0, 2.0, 0)
+    assert oracle.var_tv_perturbation_norm(F32, x, c, off, w, []) == (0.0, 0.0, 0)
+    x1 = x.copy()
+    assert oracle.var_tv_partial_recover(F32, x1, c, off, [0], w) == (40.0, 40.0, 0)
+    np.testing.assert_array_equal(x1[:3], c[:3])
+    np.testing.assert_array_equal(x1[3:], x[3:])
+    r = np.random.default_rng(8)
+    L, nb = 12, 25
+    xe = r.dirichlet(np.full(L, 0.5), size=nb).astype(np.float32).ravel()
+    ce = r.dirichlet(np.full(L, 0.5), size=nb).astype(np.float32).ravel()
+    we = r.integers(1, 300, size=nb).astype(np.float32)
+    offe = np.arange(0, L * nb + 1, L, dtype=np.uint64)
+    np.testing.assert_array_equal(oracle.var_tv_block_scores(F32, xe, ce, offe, we), oracle.tv_block_scores(F32, xe, ce, L, we))
+    S = np.array([7, 0, 19], dtype=np.uint32)
+    assert oracle.var_tv_perturbation_norm(F32, xe, ce, offe, we, S) == oracle.tv_perturbation_norm(F32, xe, ce, L, we, S)
+    xa, xb = xe.copy(), xe.copy()
+    assert oracle.var_tv_partial_recover(F32, xa, ce, offe, S, we) == oracle.tv_partial_recover(F32, xb, ce, L, S, we)
+    np.testing.assert_array_equal(xa, xb)
