@@ -327,6 +327,24 @@ int scar_tv_perturbation_norm(const scar_layout* layout, const void* x, const vo
                               scar_norm* norm_out, void* workspace, size_t workspace_bytes,
                               void* stream);
 
+/* The same three for blocks of unequal length (rows that are distributions over sets of
+ * different sizes): scar_var_block_scores, scar_var_partial_recover and
+ * scar_var_perturbation_norm in the scaled total variation.  weights: float[n_blocks] in DEVICE
+ * memory or NULL.  SCAR_F32 and SCAR_BF16 stores; the workspace is that of the scar_var_* calls. */
+int scar_var_tv_block_scores(const scar_var_layout* layout, const void* x, const void* c,
+                             const float* weights, float* scores, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+int scar_var_tv_partial_recover(const scar_var_layout* layout, void* x, const void* c,
+                                const float* weights, const uint32_t* lost_idx, uint32_t n_lost,
+                                scar_norm* norm_out, void* workspace, size_t workspace_bytes,
+                                void* stream);
+
+int scar_var_tv_perturbation_norm(const scar_var_layout* layout, const void* x, const void* c,
+                                  const float* weights, const uint32_t* idx, uint32_t n_idx,
+                                  scar_norm* norm_out, void* workspace, size_t workspace_bytes,
+                                  void* stream);
+
 /* Static, never NULL. */
 const char* scar_strerror(int status);
 

@@ -158,6 +158,9 @@ inline RowGrid row_grid(uint64_t need_x, uint32_t pieces, uint64_t cap) {
 // (double, or uint64 for SCAR_I32) in a fixed order and writes *out.
 void launch_finish(int32_t dtype, const void* partial, uint32_t n_partial, scar_norm* out,
                    hipStream_t st);
+// The same for the scaled total variation: double partial sums of w_b * sum |c - x|; the norm
+// is half their sum.
+void launch_finish_tv(const void* partial, uint32_t n_partial, scar_norm* out, hipStream_t st);
 
 // ---- reduced-precision checkpoint (SCAR_F32_BF16C: x float32, c bfloat16) ---------------
 // Bodies of the entry points for that store type (defined with its kernels); arguments are

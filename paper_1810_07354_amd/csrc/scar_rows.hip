@@ -484,7 +484,7 @@ static uint32_t dispatch_recover(int dt, int g, const scar_layout* l, void* x, c
   }
 }
 
-static void launch_finish_tv(const void* partial, uint32_t n_partial, scar_norm* out, hipStream_t st) {
+void launch_finish_tv(const void* partial, uint32_t n_partial, scar_norm* out, hipStream_t st) {
   launch((k_norm_finish<DT_F32_TV>), dim3(1), dim3(kFinishThreads), 0, st, (const double*)partial,
                      n_partial, out);
 }

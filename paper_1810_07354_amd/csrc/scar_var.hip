@@ -194,7 +194,8 @@ __global__ __launch_bounds__(kWG) void k_var_walk(char* __restrict__ x, char* __
                                                   const uint8_t* __restrict__ any,
                                                   typename Acc<DT>::type* __restrict__ partial,
                                                   bool base_aligned, char* __restrict__ side,
-                                                  const uint64_t* __restrict__ pack) {
+                                                  const uint64_t* __restrict__ pack,
+                                                  const float* __restrict__ weights) {
   using acc_t = typename Acc<DT>::type;
   __shared__ acc_t slots[kWG / kWave];
   const uint32_t w = PER_BLOCK ? xcd_contiguous_block_id() : blockIdx.x;
@@ -224,7 +225,14 @@ __global__ __launch_bounds__(kWG) void k_var_walk(char* __restrict__ x, char* __
     if (PER_BLOCK || !mask || mask[cur]) {
       char* side_seg = nullptr;
       if constexpr (SIDE != SIDE_NONE) side_seg = side + (pack[cur] + (pos - off[cur])) * elem_bytes(DT);
-      segment_apply<DT, ACC, COPY, SIDE>(x, c, side_seg, pos, seg_end - pos, base_aligned, acc);
+      if constexpr (is_tv(DT) && ACC && !PER_BLOCK) {  // a row's share counts with the row's weight
+        const float w = weights ? weights[cur] : 1.f;
+        acc_t seg = 0;
+        segment_apply<DT, ACC, COPY, SIDE>(x, c, side_seg, pos, seg_end - pos, base_aligned, seg);
+        acc += (double)w * seg;
+      } else {
+        segment_apply<DT, ACC, COPY, SIDE>(x, c, side_seg, pos, seg_end - pos, base_aligned, acc);
+      }
     }
     pos = seg_end;
   }
@@ -240,7 +248,8 @@ template <int DT, int G, int T>
 __global__ __launch_bounds__(T) void k_var_scores_finish(const typename Acc<DT>::type* __restrict__ partial,
                                                          const uint64_t* __restrict__ off,
                                                          uint32_t n_blocks, uint64_t n_elems,
-                                                         uint64_t range_elems, void* __restrict__ scores) {
+                                                         uint64_t range_elems, void* __restrict__ scores,
+                                                         const float* __restrict__ weights) {
   using acc_t = typename Acc<DT>::type;
   constexpr int GPW = T / G;
   __shared__ acc_t slots[T / kWave];
@@ -272,6 +281,8 @@ __global__ __launch_bounds__(T) void k_var_scores_finish(const typename Acc<DT>:
     if (lane == 0) {
       if constexpr (DT == DT_I32)
         ((long long*)scores)[b] = (long long)acc;
+      else if constexpr (is_tv(DT))  // w_b * 1/2 * sum |x - c|
+        ((float*)scores)[b] = (float)(0.5 * acc * (double)(weights ? weights[b] : 1.f));
       else
         ((float*)scores)[b] = (float)acc;
     }
@@ -341,7 +352,7 @@ static int check_var_workspace(const void* ws, size_t bytes, uint64_t n_blocks) 
 template <int DT, bool ACC, int COPY, bool PER_BLOCK, int SIDE = SIDE_NONE>
 static void launch_walk(const scar_var_layout* l, const void* x, const void* c, const uint8_t* mask,
                         bool planned, void* workspace, const VarGeometry& g, hipStream_t st,
-                        void* side = nullptr) {
+                        void* side = nullptr, const float* weights = nullptr) {
   const bool base_aligned = aligned(x, 16) && aligned(c, 16);
   uint32_t* first = (uint32_t*)workspace;
   uint8_t* any = (uint8_t*)workspace + kVarPlanAnyOffset;
@@ -357,7 +368,7 @@ static void launch_walk(const scar_var_layout* l, const void* x, const void* c, 
   launch((k_var_walk<DT, ACC, COPY, PER_BLOCK, SIDE>), dim3(xcd_grid(g.n_wg, kVarMaxGridCopy)), dim3(kWG),
                      lds, st, (char*)const_cast<void*>(x), (char*)const_cast<void*>(c), l->offsets,
                      l->n_blocks, l->n_elems, g.range_elems, g.n_wg, mask, (const uint32_t*)first,
-                     (const uint8_t*)any, (typename Acc<DT>::type*)partial, base_aligned, (char*)side, pack);
+                     (const uint8_t*)any, (typename Acc<DT>::type*)partial, base_aligned, (char*)side, pack, weights);
 }
 
 template <bool ACC, int COPY, bool PER_BLOCK, int SIDE = SIDE_NONE>
@@ -371,19 +382,30 @@ static void dispatch_walk(const scar_var_layout* l, const void* x, const void* c
   }
 }
 
+// The total-variation kinds (float stores only; always measuring).
+template <int COPY, bool PER_BLOCK>
+static void dispatch_walk_tv(const scar_var_layout* l, const void* x, const void* c, const uint8_t* mask,
+                             bool planned, void* workspace, const VarGeometry& g, const float* weights,
+                             hipStream_t st) {
+  if (l->dtype == SCAR_F32)
+    launch_walk<DT_F32_TV, true, COPY, PER_BLOCK>(l, x, c, mask, planned, workspace, g, st, nullptr, weights);
+  else
+    launch_walk<DT_BF16_TV, true, COPY, PER_BLOCK>(l, x, c, mask, planned, workspace, g, st, nullptr, weights);
+}
+
 template <int DT>
 static void launch_scores_finish(const scar_var_layout* l, const void* workspace, const VarGeometry& g,
-                                 void* scores, hipStream_t st) {
+                                 void* scores, hipStream_t st, const float* weights = nullptr) {
   using acc_t = typename Acc<DT>::type;
   const void* partial = (const char*)workspace + kVarPartialOffset;
   if (l->n_blocks <= 16384) {  // few blocks, possibly huge: a whole workgroup adds each one's slots
     launch((k_var_scores_finish<DT, 1024, 1024>), dim3(l->n_blocks), dim3(1024), 0, st,
-                       (const acc_t*)partial, l->offsets, l->n_blocks, l->n_elems, g.range_elems, scores);
+                       (const acc_t*)partial, l->offsets, l->n_blocks, l->n_elems, g.range_elems, scores, weights);
   } else {
     const uint64_t need = ((uint64_t)l->n_blocks + 3) / 4;
     launch((k_var_scores_finish<DT, kWave, kWG>), dim3((uint32_t)(need < 65536 ? need : 65536)),
                        dim3(kWG), 0, st, (const acc_t*)partial, l->offsets, l->n_blocks, l->n_elems,
-                       g.range_elems, scores);
+                       g.range_elems, scores, weights);
   }
 }
 
@@ -415,8 +437,10 @@ static const uint8_t* mark_blocks(const scar_var_layout* l, const uint32_t* idx,
 static int var_rows(int copy, const scar_var_layout* layout, const void* x, const void* c,
                     const uint32_t* idx, uint32_t n_idx, bool all_blocks, scar_norm* norm_out,
                     void* workspace, size_t workspace_bytes, void* stream, void* side = nullptr,
-                    uint64_t* side_offsets = nullptr) {
+                    uint64_t* side_offsets = nullptr, bool tv = false, const float* weights = nullptr) {
   if (layout && layout->dtype == SCAR_F32_BF16C) return SCAR_ERR_UNSUPPORTED;
+  if (tv && layout && layout->dtype == SCAR_I32) return SCAR_ERR_UNSUPPORTED;
+  if (!aligned(weights, 4)) return SCAR_ERR_INVALID_ARG;
   const uint64_t nb = var_blocks(layout);
   if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
   if (norm_out && !aligned(norm_out, 8)) return SCAR_ERR_INVALID_ARG;
@@ -430,7 +454,12 @@ static int var_rows(int copy, const scar_var_layout* layout, const void* x, cons
     if (side && copy == COPY_X_TO_C)  // an empty list still gets its (all zero) offsets
       launch(k_var_pack_scan, dim3(1), dim3(kPackThreads), 0, st, layout->offsets, (uint32_t)nb, idx, 0u,
              (unsigned long long*)side_offsets, (unsigned long long*)((char*)workspace + var_pack_offset(nb)));
-    if (norm_out) launch_finish(layout->dtype, (char*)workspace + kVarPartialOffset, 0, norm_out, st);
+    if (norm_out) {
+      if (tv)
+        launch_finish_tv((char*)workspace + kVarPartialOffset, 0, norm_out, st);
+      else
+        launch_finish(layout->dtype, (char*)workspace + kVarPartialOffset, 0, norm_out, st);
+    }
     return launch_status();
   }
   const int eb = host_elem_bytes(layout->dtype);
@@ -453,7 +482,11 @@ static int var_rows(int copy, const scar_var_layout* layout, const void* x, cons
       dispatch_walk<true, COPY_C_TO_X, false, SIDE_READ>(layout, x, x, mask, planned, workspace, g, st, side);
     else
       dispatch_walk<false, COPY_C_TO_X, false, SIDE_READ>(layout, x, x, mask, planned, workspace, g, st, side);
-  } else if (copy == COPY_X_TO_C)
+  } else if (tv && norm_out && copy == COPY_C_TO_X)
+    dispatch_walk_tv<COPY_C_TO_X, false>(layout, x, c, mask, planned, workspace, g, weights, st);
+  else if (tv && norm_out)
+    dispatch_walk_tv<COPY_NONE, false>(layout, x, c, mask, planned, workspace, g, weights, st);
+  else if (copy == COPY_X_TO_C)
     dispatch_walk<false, COPY_X_TO_C, false>(layout, x, c, mask, planned, workspace, g, st);
   else if (copy == COPY_C_TO_X && norm_out)
     dispatch_walk<true, COPY_C_TO_X, false>(layout, x, c, mask, planned, workspace, g, st);
@@ -461,7 +494,9 @@ static int var_rows(int copy, const scar_var_layout* layout, const void* x, cons
     dispatch_walk<false, COPY_C_TO_X, false>(layout, x, c, mask, planned, workspace, g, st);
   else
     dispatch_walk<true, COPY_NONE, false>(layout, x, c, mask, planned, workspace, g, st);
-  if (norm_out)
+  if (norm_out && tv)
+    launch_finish_tv((char*)workspace + kVarPartialOffset, g.n_wg, norm_out, st);
+  else if (norm_out)
     launch_finish(layout->dtype, (char*)workspace + kVarPartialOffset, g.n_wg, norm_out, st);
   return launch_status();
 }
@@ -474,26 +509,65 @@ extern "C" size_t scar_var_workspace_bytes(uint64_t n_blocks) {
   return n_blocks > SCAR_MAX_BLOCKS ? 0 : var_workspace_bytes_for(n_blocks);
 }
 
-extern "C" int scar_var_block_scores(const scar_var_layout* layout, const void* x, const void* c,
-                                     void* scores, void* workspace, size_t workspace_bytes,
-                                     void* stream) {
+// Shared body of scar_var_block_scores and scar_var_tv_block_scores.
+static int var_scores(bool tv, const scar_var_layout* layout, const void* x, const void* c,
+                      const float* weights, void* scores, void* workspace, size_t workspace_bytes,
+                      void* stream) {
   if (layout && layout->dtype == SCAR_F32_BF16C) return SCAR_ERR_UNSUPPORTED;
+  if (tv && layout && layout->dtype == SCAR_I32) return SCAR_ERR_UNSUPPORTED;
   const uint64_t nb = var_blocks(layout);
   if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
   if (nb == 0) return SCAR_OK;
   const int eb = host_elem_bytes(layout->dtype);
-  if (!scores || !aligned(scores, layout->dtype == SCAR_I32 ? 8 : 4)) return SCAR_ERR_INVALID_ARG;
+  if (!scores || !aligned(scores, layout->dtype == SCAR_I32 ? 8 : 4) || !aligned(weights, 4)) return SCAR_ERR_INVALID_ARG;
   if (layout->n_elems && (!x || !c || !aligned(x, eb) || !aligned(c, eb))) return SCAR_ERR_INVALID_ARG;
   const int rc = check_var_workspace(workspace, workspace_bytes, nb);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;
   const VarGeometry g = var_geometry(layout->n_elems, kVarMaxGridCopy);
+  if (tv) {
+    if (layout->n_elems) dispatch_walk_tv<COPY_NONE, true>(layout, x, c, nullptr, false, workspace, g, weights, st);
+    if (layout->dtype == SCAR_F32)
+      launch_scores_finish<DT_F32_TV>(layout, workspace, g, scores, st, weights);
+    else
+      launch_scores_finish<DT_BF16_TV>(layout, workspace, g, scores, st, weights);
+    return launch_status();
+  }
   if (layout->n_elems) dispatch_walk<true, COPY_NONE, true>(layout, x, c, nullptr, false, workspace, g, st);
   switch (layout->dtype) {
     case SCAR_I32: launch_scores_finish<DT_I32>(layout, workspace, g, scores, st); break;
     default: launch_scores_finish<DT_F32>(layout, workspace, g, scores, st); break;
   }
   return launch_status();
+}
+
+extern "C" int scar_var_block_scores(const scar_var_layout* layout, const void* x, const void* c,
+                                     void* scores, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+  return var_scores(false, layout, x, c, nullptr, scores, workspace, workspace_bytes, stream);
+}
+
+extern "C" int scar_var_tv_block_scores(const scar_var_layout* layout, const void* x, const void* c,
+                                        const float* weights, float* scores, void* workspace,
+                                        size_t workspace_bytes, void* stream) {
+  return var_scores(true, layout, x, c, weights, scores, workspace, workspace_bytes, stream);
+}
+
+extern "C" int scar_var_tv_partial_recover(const scar_var_layout* layout, void* x, const void* c,
+                                           const float* weights, const uint32_t* lost_idx, uint32_t n_lost,
+                                           scar_norm* norm_out, void* workspace, size_t workspace_bytes,
+                                           void* stream) {
+  return var_rows(COPY_C_TO_X, layout, x, c, lost_idx, n_lost, false, norm_out, workspace, workspace_bytes,
+                  stream, nullptr, nullptr, true, weights);
+}
+
+extern "C" int scar_var_tv_perturbation_norm(const scar_var_layout* layout, const void* x, const void* c,
+                                             const float* weights, const uint32_t* idx, uint32_t n_idx,
+                                             scar_norm* norm_out, void* workspace, size_t workspace_bytes,
+                                             void* stream) {
+  if (!norm_out) return SCAR_ERR_INVALID_ARG;
+  return var_rows(COPY_NONE, layout, x, c, idx, n_idx, idx == nullptr, norm_out, workspace, workspace_bytes,
+                  stream, nullptr, nullptr, true, weights);
 }
 
 extern "C" int scar_var_checkpoint_commit(const scar_var_layout* layout, const void* x, void* c,

@@ -86,6 +86,11 @@ def lib():
         L.scar_var_checkpoint_commit.argtypes = [vlp, vp, vp, vp, u32, vp, sz, vp]
         L.scar_var_partial_recover.argtypes = [vlp, vp, vp, vp, u32, vp, vp, sz, vp]
         L.scar_var_perturbation_norm.argtypes = [vlp, vp, vp, vp, u32, vp, vp, sz, vp]
+        L.scar_var_tv_block_scores.argtypes = [vlp, vp, vp, vp, vp, vp, sz, vp]
+        L.scar_var_tv_partial_recover.argtypes = [vlp, vp, vp, vp, vp, u32, vp, vp, sz, vp]
+        L.scar_var_tv_perturbation_norm.argtypes = [vlp, vp, vp, vp, vp, u32, vp, vp, sz, vp]
+        for name in ("scar_var_tv_block_scores", "scar_var_tv_partial_recover", "scar_var_tv_perturbation_norm"):
+            getattr(L, name).restype = ctypes.c_int
         L.scar_var_checkpoint_commit_staged.argtypes = [vlp, vp, vp, vp, u32, vp, vp, vp, sz, vp]
         L.scar_var_partial_recover_rows.argtypes = [vlp, vp, vp, vp, vp, u32, vp, vp, sz, vp]
         for name in ("scar_var_block_scores", "scar_var_checkpoint_commit", "scar_var_partial_recover",
@@ -532,6 +537,48 @@ def tv_perturbation_norm(x, c, block_len, idx, workspace, weights=None):
     _check(lib().scar_tv_perturbation_norm(ctypes.byref(lay), _p(x), _p(c), _p(w), ptr, n, _p(norm_out),
                                            _p(workspace), _bytes(workspace), _stream()),
            "scar_tv_perturbation_norm")
+    return norm_out
+
+
+def var_tv_block_scores(x, c, offsets, workspace, weights=None, out=None):
+    """scar_var_tv_block_scores: w_b * TV(x_b, c_b) per block of unequal length (float32)."""
+    _dev(x, "x"), _dev(c, "c"), _dev(workspace, "workspace")
+    lay = var_layout_of(x, offsets)
+    w = _weights(weights, lay.n_blocks, x.device)
+    if out is None:
+        out = torch.empty(lay.n_blocks, dtype=torch.float32, device=x.device)
+    _check(lib().scar_var_tv_block_scores(ctypes.byref(lay), _p(x), _p(c), _p(w), _p(out), _p(workspace),
+                                          _bytes(workspace), _stream()), "scar_var_tv_block_scores")
+    return out
+
+
+def var_tv_partial_recover(x, c, offsets, lost_idx, workspace, weights=None, want_norm=True):
+    """scar_var_tv_partial_recover; returns the device scar_norm buffer or None."""
+    _dev(x, "x"), _dev(c, "c"), _idx(lost_idx, "lost_idx"), _dev(workspace, "workspace")
+    lay = var_layout_of(x, offsets)
+    w = _weights(weights, lay.n_blocks, x.device)
+    norm_out = _norm_buffer(x.device) if want_norm else None
+    _check(lib().scar_var_tv_partial_recover(ctypes.byref(lay), _p(x), _p(c), _p(w), _p(lost_idx),
+                                             lost_idx.numel(), _p(norm_out), _p(workspace), _bytes(workspace),
+                                             _stream()), "scar_var_tv_partial_recover")
+    return norm_out
+
+
+def var_tv_perturbation_norm(x, c, offsets, idx, workspace, weights=None):
+    """scar_var_tv_perturbation_norm (idx None = every block)."""
+    _dev(x, "x"), _dev(c, "c"), _dev(workspace, "workspace")
+    lay = var_layout_of(x, offsets)
+    w = _weights(weights, lay.n_blocks, x.device)
+    norm_out = _norm_buffer(x.device)
+    if idx is None:
+        ptr, n = ctypes.c_void_p(0), 0
+    else:
+        _idx(idx, "idx")
+        n = idx.numel()
+        ptr = _p(idx) if n else _p(norm_out)
+    _check(lib().scar_var_tv_perturbation_norm(ctypes.byref(lay), _p(x), _p(c), _p(w), ptr, n, _p(norm_out),
+                                               _p(workspace), _bytes(workspace), _stream()),
+           "scar_var_tv_perturbation_norm")
     return norm_out
 
 

@@ -211,3 +211,56 @@ def test_tv_random_layouts(seed):
         norm_close(got, oracle.tv_partial_recover(dtype, hx, hc, L, S, hw))
         assert pre == got
         np.testing.assert_array_equal(to_host(x.contiguous()), hx)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("case", ["short_rows", "mixed", "few_giant"])
+@pytest.mark.parametrize("weighted", [False, True])
+def test_tv_calls_on_rows_of_unequal_length(dtype, case, weighted):
+    # the scaled total variation over blocks of unequal length (scar_var_tv_*): scores, the norm
+    # of all blocks and of a list, recovery with the fused norm, and the selection on the scores
+    r = np.random.default_rng(len(case) + dtype)
+    if case == "short_rows":
+        sizes = r.integers(0, 60, size=20_000)
+    elif case == "mixed":
+        sizes = wl.mixed_layer_sizes(300, 3_000_000, seed=31)
+    else:
+        sizes = np.array([5_000_000, 3, 0, 2_500_000, 700_001])
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.uint64)
+    nb, n = sizes.size, int(off[-1])
+    c = r.random(n, dtype=np.float32)
+    x = np.where(r.random(n) < 0.3, c + r.normal(0, 0.01, size=n).astype(np.float32), c).astype(np.float32)
+    hx, hc = (wl.f32_to_bf16_bits(x), wl.f32_to_bf16_bits(c)) if dtype == BF16 else (x, c)
+    hw = r.integers(5, 3000, size=nb).astype(np.float32) if weighted else None
+    w = torch.from_numpy(hw).to(DEV) if weighted else None
+    print("var tv dtype=%d case=%s weighted=%s blocks=%d elems=%d" % (dtype, case, weighted, nb, n), flush=True)
+    xd, cd = to_dev(hx, dtype), to_dev(hc, dtype)
+    d_off = torch.from_numpy(off.astype(np.int64)).to(DEV)
+    ws, ws_sel = scar.new_var_workspace(nb, DEV), scar.new_workspace(nb, DEV)
+
+    s = scar.var_tv_block_scores(xd, cd, d_off, ws, w)
+    s_ref = oracle.var_tv_block_scores(dtype, hx, hc, off, hw)
+    np.testing.assert_allclose(s.cpu().numpy().astype(np.float64), s_ref, rtol=REL_TOL, atol=0)
+    k = max(1, nb // 5)
+    idx = scar.select_topk(s, k, ws_sel)
+    assert_selection_matches(idx_host(idx), s.cpu().numpy(), s_ref, k)
+
+    full = scar.read_norm(scar.var_tv_perturbation_norm(xd, cd, d_off, None, ws, w))
+    norm_close(full, oracle.var_tv_perturbation_norm(dtype, hx, hc, off, hw))
+    S = np.sort(r.choice(nb, size=max(1, nb // 3), replace=False)).astype(np.uint32)
+    pre = scar.read_norm(scar.var_tv_perturbation_norm(xd, cd, d_off, idx_dev(S), ws, w))
+    got = scar.read_norm(scar.var_tv_partial_recover(xd, cd, d_off, idx_dev(S), ws, w))
+    want = oracle.var_tv_partial_recover(dtype, hx, hc, off, S, hw)
+    norm_close(got, want)
+    norm_close(pre, want)
+    assert got[1] <= full[1] * (1 + REL_TOL)
+    np.testing.assert_array_equal(to_host(xd), hx)
+    np.testing.assert_array_equal(to_host(cd), hc)
+    # without a norm it is the plain recovery
+    scar.var_tv_partial_recover(xd, cd, d_off, idx_dev(S), ws, w, want_norm=False)
+    np.testing.assert_array_equal(to_host(xd), hx)
+    # integer tables are scored by the plain calls (L1 = twice this norm): not built here
+    xi = torch.zeros(8, dtype=torch.int32, device=DEV)
+    with pytest.raises(scar.ScarError) as e:
+        scar.var_tv_block_scores(xi, xi.clone(), torch.tensor([0, 8], device=DEV), ws)
+    assert e.value.status == -5
