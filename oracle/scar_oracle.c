@@ -459,7 +459,7 @@ static int offsets_ok(const uint64_t *offsets, uint32_t n_blocks) {
 
 int oracle_var_block_scores(int dtype, const void *x, const void *c, const uint64_t *offsets,
                             uint32_t n_blocks, void *scores) {
-  if (!dtype_ok(dtype) || dtype == ORACLE_F32_BF16C || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
+  if (!dtype_ok(dtype) || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
   if (n_blocks == 0) return ORACLE_OK;
   if (!scores || (offsets[n_blocks] && (!x || !c))) return ORACLE_ERR_ARG;
 #pragma omp parallel for schedule(dynamic, 1) num_threads(g_threads)
@@ -481,20 +481,25 @@ int oracle_var_block_scores(int dtype, const void *x, const void *c, const uint6
 int oracle_var_checkpoint_commit(int dtype, const void *x, void *c, const uint64_t *offsets,
                                  uint32_t n_blocks, const uint32_t *idx, uint32_t n_idx,
                                  void *staging, uint64_t *staging_offsets) {
-  if (!dtype_ok(dtype) || dtype == ORACLE_F32_BF16C || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
+  if (!dtype_ok(dtype) || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
   if (staging && !staging_offsets) return ORACLE_ERR_ARG;
   if (staging_offsets) staging_offsets[0] = 0;
   if (n_idx == 0) return ORACLE_OK;
   int rc = check_indices(idx, n_idx, n_blocks);
   if (rc) return rc;
-  size_t es = elem_size(dtype);
+  size_t es = elem_size(c_type(dtype));
   uint64_t packed = 0; /* elements already in staging */
   for (uint32_t i = 0; i < n_idx; ++i) {
     uint64_t lo = offsets[idx[i]], hi = offsets[idx[i] + 1];
-    if (hi > lo) memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo) * es);
+    if (dtype == ORACLE_F32_BF16C) { /* what is saved is x rounded to the checkpoint's precision */
+      for (uint64_t j = lo; j < hi; ++j) ((uint16_t *)c)[j] = round_to_bf16(((const float *)x)[j]);
+    } else if (hi > lo) {
+      memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo) * es);
+    }
     if (staging_offsets) {
       staging_offsets[i] = packed;
-      if (staging && hi > lo) memcpy((char *)staging + packed * es, (const char *)x + lo * es, (hi - lo) * es);
+      /* the saved rows, in the checkpoint's element type */
+      if (staging && hi > lo) memcpy((char *)staging + packed * es, (const char *)c + lo * es, (hi - lo) * es);
       packed += hi - lo;
       staging_offsets[i + 1] = packed;
     }
@@ -506,7 +511,7 @@ int oracle_var_checkpoint_commit(int dtype, const void *x, void *c, const uint64
 int oracle_var_perturbation_norm(int dtype, const void *x, const void *c, const uint64_t *offsets,
                                  uint32_t n_blocks, const uint32_t *idx, uint32_t n_idx,
                                  oracle_norm *out) {
-  if (!dtype_ok(dtype) || dtype == ORACLE_F32_BF16C || !offsets_ok(offsets, n_blocks) || !out) return ORACLE_ERR_ARG;
+  if (!dtype_ok(dtype) || !offsets_ok(offsets, n_blocks) || !out) return ORACLE_ERR_ARG;
   out->sum = out->norm = 0.0;
   out->isum = 0;
   uint32_t m = idx ? n_idx : n_blocks;
@@ -536,7 +541,7 @@ int oracle_var_perturbation_norm(int dtype, const void *x, const void *c, const 
 int oracle_var_partial_recover(int dtype, void *x, const void *c, const uint64_t *offsets,
                                uint32_t n_blocks, const uint32_t *lost, uint32_t n_lost,
                                oracle_norm *norm_out) {
-  if (!dtype_ok(dtype) || dtype == ORACLE_F32_BF16C || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
+  if (!dtype_ok(dtype) || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
   oracle_norm zero = {0.0, 0.0, 0};
   if (n_lost == 0) {
     if (norm_out) *norm_out = zero;
@@ -549,10 +554,14 @@ int oracle_var_partial_recover(int dtype, void *x, const void *c, const uint64_t
     int rc = check_indices(lost, n_lost, n_blocks);
     if (rc) return rc;
   }
-  size_t es = elem_size(dtype);
+  size_t es = elem_size(x_type(dtype));
   for (uint32_t i = 0; i < n_lost; ++i) {
     uint64_t lo = offsets[lost[i]], hi = offsets[lost[i] + 1];
-    if (hi > lo) memcpy((char *)x + lo * es, (const char *)c + lo * es, (hi - lo) * es);
+    if (dtype == ORACLE_F32_BF16C) {
+      for (uint64_t j = lo; j < hi; ++j) ((float *)x)[j] = (float)load_real(ORACLE_BF16, c, j);
+    } else if (hi > lo) {
+      memcpy((char *)x + lo * es, (const char *)c + lo * es, (hi - lo) * es);
+    }
   }
   return ORACLE_OK;
 }
@@ -564,7 +573,7 @@ int oracle_var_partial_recover(int dtype, void *x, const void *c, const uint64_t
 int oracle_var_partial_recover_rows(int dtype, void *x, const void *rows, const uint64_t *row_offsets,
                                     const uint64_t *offsets, uint32_t n_blocks, const uint32_t *lost,
                                     uint32_t n_lost, oracle_norm *norm_out) {
-  if (!dtype_ok(dtype) || dtype == ORACLE_F32_BF16C || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
+  if (!dtype_ok(dtype) || !offsets_ok(offsets, n_blocks)) return ORACLE_ERR_ARG;
   oracle_norm zero = {0.0, 0.0, 0};
   if (norm_out) *norm_out = zero;
   if (n_lost == 0) return ORACLE_OK;
@@ -582,7 +591,7 @@ int oracle_var_partial_recover_rows(int dtype, void *x, const void *rows, const 
           int64_t d = (int64_t)((const int32_t *)rows)[r0 + t] - (int64_t)((const int32_t *)x)[lo + t];
           is += d < 0 ? -d : d;
         } else {
-          double d = load_real(dtype, rows, r0 + t) - load_real(dtype, x, lo + t);
+          double d = load_real(c_type(dtype), rows, r0 + t) - load_real(x_type(dtype), x, lo + t);
           fs += d * d;
         }
       }
@@ -597,7 +606,11 @@ int oracle_var_partial_recover_rows(int dtype, void *x, const void *rows, const 
   }
   for (uint32_t i = 0; i < n_lost; ++i) {
     uint64_t lo = offsets[lost[i]], len = offsets[lost[i] + 1] - lo;
-    if (len) memcpy((char *)x + lo * es, (const char *)rows + row_offsets[i] * es, len * es);
+    if (dtype == ORACLE_F32_BF16C) {
+      for (uint64_t t = 0; t < len; ++t) ((float *)x)[lo + t] = (float)load_real(ORACLE_BF16, rows, row_offsets[i] + t);
+    } else if (len) {
+      memcpy((char *)x + lo * es, (const char *)rows + row_offsets[i] * es, len * es);
+    }
   }
   return ORACLE_OK;
 }

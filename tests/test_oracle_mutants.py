@@ -68,20 +68,22 @@ MUTANTS = [
      "    total += (weights ? (double)weights[i] : 1.0) * block_tv(dtype, x, c, lo, hi);"),
     ("scaled norm as a root", "  out->sum = out->norm = total;", "  out->sum = total; out->norm = sqrt(total);"),
     ("unequal blocks: staging offsets include the block itself", "      staging_offsets[i] = packed;\n", "      staging_offsets[i] = packed + (hi - lo);\n"),
-    ("unequal blocks: staging packed by block position", "memcpy((char *)staging + packed * es, (const char *)x + lo * es, (hi - lo) * es);",
-     "memcpy((char *)staging + lo * es, (const char *)x + lo * es, (hi - lo) * es);"),
+    ("unequal blocks: staging packed by block position", "memcpy((char *)staging + packed * es, (const char *)c + lo * es, (hi - lo) * es);",
+     "memcpy((char *)staging + lo * es, (const char *)c + lo * es, (hi - lo) * es);"),
+    ("unequal blocks: bfloat16 checkpoint truncated on commit", "for (uint64_t j = lo; j < hi; ++j) ((uint16_t *)c)[j] = round_to_bf16(((const float *)x)[j]);\n    } else if (hi > lo) {",
+     "for (uint64_t j = lo; j < hi; ++j) ((uint16_t *)c)[j] = (uint16_t)(((const uint32_t *)x)[j] >> 16);\n    } else if (hi > lo) {"),
     ("unequal blocks: rows read from the block's own offset", "memcpy((char *)x + lo * es, (const char *)rows + row_offsets[i] * es, len * es);",
      "memcpy((char *)x + lo * es, (const char *)rows + lo * es, len * es);"),
-    ("unequal blocks: norm of the rows after the overwrite", "double d = load_real(dtype, rows, r0 + t) - load_real(dtype, x, lo + t);",
-     "double d = load_real(dtype, rows, r0 + t) - load_real(dtype, rows, r0 + t);"),
+    ("unequal blocks: norm of the rows after the overwrite", "double d = load_real(c_type(dtype), rows, r0 + t) - load_real(x_type(dtype), x, lo + t);",
+     "double d = load_real(c_type(dtype), rows, r0 + t) - load_real(c_type(dtype), rows, r0 + t);"),
     ("unequal rows: document length ignored in the scaled score",
      "    scores[b] = (weights ? (double)weights[b] : 1.0) * block_tv(dtype, x, c, offsets[b], offsets[b + 1]);",
      "    scores[b] = block_tv(dtype, x, c, offsets[b], offsets[b + 1]);"),
     ("unequal rows: scaled norm weighs by list position",
      "    total += (weights ? (double)weights[b] : 1.0) * block_tv(dtype, x, c, offsets[b], offsets[b + 1]);",
      "    total += (weights ? (double)weights[i] : 1.0) * block_tv(dtype, x, c, offsets[b], offsets[b + 1]);"),
-    ("unequal blocks: commit one element short", "    if (hi > lo) memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo) * es);",
-     "    if (hi > lo) memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo - 1) * es);"),
+    ("unequal blocks: commit one element short", "    } else if (hi > lo) {\n      memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo) * es);\n    }\n    if (staging_offsets) {",
+     "    } else if (hi > lo) {\n      memcpy((char *)c + lo * es, (const char *)x + lo * es, (hi - lo - 1) * es);\n    }\n    if (staging_offsets) {"),
 ]
 
 

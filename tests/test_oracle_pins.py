@@ -701,8 +701,10 @@ def test_mixed_equals_float_store_when_values_are_representable():
     x1, x2 = xf.copy(), xf.copy()
     assert oracle.partial_recover(MIX, x1, cb, 7, [0, 42]) == oracle.partial_recover(F32, x2, cf, 7, [0, 42])
     np.testing.assert_array_equal(x1, x2)
-    with pytest.raises(oracle.OracleError):
-        oracle.var_block_scores(MIX, xf, cb, np.array([0, 300], dtype=np.uint64))
+    one = np.array([0, 300], dtype=np.uint64)                            # the same in one block of unequal-length kind
+    np.testing.assert_array_equal(oracle.var_block_scores(MIX, xf, cb, one), oracle.var_block_scores(F32, xf, cf, one))
+    with pytest.raises(oracle.OracleError):                               # the total variation has no such store
+        oracle.var_tv_block_scores(MIX, xf, cb, one)
 
 
 # ------------------------------------------- scaled total variation (Section 5.1, Appendix C)
@@ -877,3 +879,39 @@ def test_var_tv_closed_forms_and_reduction_to_equal_rows():
     xa, xb = xe.copy(), xe.copy()
     assert oracle.var_tv_partial_recover(F32, xa, ce, offe, S, we) == oracle.tv_partial_recover(F32, xb, ce, L, S, we)
     np.testing.assert_array_equal(xa, xb)
+
+
+def test_var_layout_with_a_bfloat16_checkpoint_reduces_to_the_fixed_layout_and_rounds_by_hand():
+    # float32 x against a bfloat16 c in blocks of unequal length: with equal blocks every call
+    # equals its fixed-layout twin; by hand: a commit stores x rounded to nearest even, the
+    # staging rows hold those rounded values, recovery widens them
+    r = rng_of(60)
+    L, nb = 10, 24
+    x = r.normal(0, 1, size=L * nb).astype(np.float32)
+    c = (r.normal(0, 1, size=L * nb).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    off = np.arange(0, L * nb + 1, L, dtype=np.uint64)
+    np.testing.assert_array_equal(oracle.var_block_scores(MIX, x, c, off), oracle.block_scores(MIX, x, c, L))
+    idx = np.array([5, 23, 0, 11], dtype=np.uint32)
+    assert oracle.var_perturbation_norm(MIX, x, c, off, idx) == oracle.perturbation_norm(MIX, x, c, L, idx)
+    c1, c2 = c.copy(), c.copy()
+    st1, st2 = np.zeros(idx.size * L, dtype=np.uint16), np.zeros(idx.size * L, dtype=np.uint16)
+    oracle.var_checkpoint_commit(MIX, x, c1, off, idx, st1)
+    oracle.checkpoint_commit(MIX, x, c2, L, idx, st2)
+    np.testing.assert_array_equal(c1, c2)
+    np.testing.assert_array_equal(st1, st2)
+    x1, x2 = x.copy(), x.copy()
+    assert oracle.var_partial_recover(MIX, x1, c1, off, idx) == oracle.partial_recover(MIX, x2, c2, L, idx)
+    np.testing.assert_array_equal(x1, x2)
+    # by hand, lengths 2 and 3: 1 + 2^-8 is a tie and rounds to even (1.0), 1 + 3 * 2^-8 rounds up
+    o2 = np.array([0, 2, 5], dtype=np.uint64)
+    xs = np.array([9.0, 9.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -2.5], dtype=np.float32)
+    cs = bf16_of([0, 0, 0, 0, 0])
+    st = np.zeros(3, dtype=np.uint16)
+    np.testing.assert_array_equal(oracle.var_checkpoint_commit(MIX, xs, cs, o2, [1], st), [0, 3])
+    want = bf16_of([1.0, 1.0 + 2.0 ** -6, -2.5])
+    np.testing.assert_array_equal(st, want)
+    np.testing.assert_array_equal(cs, np.concatenate([bf16_of([0, 0]), want]))
+    xr = np.zeros(5, dtype=np.float32)
+    got = oracle.var_partial_recover_rows(MIX, xr, st, [0], o2, [1])
+    np.testing.assert_array_equal(xr, [0, 0, 1.0, 1.0 + 2.0 ** -6, -2.5])
+    assert got[0] == 1.0 + (1.0 + 2.0 ** -6) ** 2 + 6.25
