@@ -68,7 +68,7 @@ typedef enum {
                         bfloat16.  Scores and norms use c widened exactly; a commit stores x
                         rounded to nearest even (so a freshly saved block keeps a rounding
                         distance of at most 2^-8 |x| per element); recovery widens c into x.
-                        staging rows are bfloat16.  Fixed-length blocks only. */
+                        staging rows are bfloat16. */
 } scar_dtype;
 
 /* Element type of a score array. */
@@ -85,7 +85,7 @@ typedef enum {
   SCAR_ERR_DEVICE = -3,      /* HIP reported an error when a kernel was enqueued */
   /* -4 is SCAR_ERR_IO of scar_store.h */
   SCAR_ERR_UNSUPPORTED = -5  /* every argument is valid, but this combination of store type
-                                and call is not built (e.g. the total-variation calls on
+                                and call is not built (the total-variation calls on
                                 SCAR_I32 or SCAR_F32_BF16C stores) */
 } scar_status;
 
@@ -245,8 +245,8 @@ int scar_select_random(uint32_t n_blocks, uint32_t k, uint64_t seed, uint64_t dr
  * parameter, so blocks differ in size by orders of magnitude.  Block b is the element
  * range [offsets[b], offsets[b+1]); empty blocks are allowed (score 0).
  * The calls below mirror the five above (scar_select_topk, _round and _random work on
- * any score array and serve both layouts).  SCAR_F32_BF16C
- * stores have fixed-length blocks only: SCAR_ERR_UNSUPPORTED here.
+ * any score array and serve both layouts).  Every store type is served, SCAR_F32_BF16C
+ * included (staging rows and packed rows are then bfloat16, like c).
  * All of them need a workspace of scar_var_workspace_bytes(n_blocks) bytes. */
 typedef struct {
   int32_t dtype;           /* scar_dtype */
@@ -330,7 +330,8 @@ int scar_tv_perturbation_norm(const scar_layout* layout, const void* x, const vo
 /* The same three for blocks of unequal length (rows that are distributions over sets of
  * different sizes): scar_var_block_scores, scar_var_partial_recover and
  * scar_var_perturbation_norm in the scaled total variation.  weights: float[n_blocks] in DEVICE
- * memory or NULL.  SCAR_F32 and SCAR_BF16 stores; the workspace is that of the scar_var_* calls. */
+ * memory or NULL.  SCAR_F32 and SCAR_BF16 stores (others: SCAR_ERR_UNSUPPORTED); the workspace is
+ * that of the scar_var_* calls. */
 int scar_var_tv_block_scores(const scar_var_layout* layout, const void* x, const void* c,
                              const float* weights, float* scores, void* workspace,
                              size_t workspace_bytes, void* stream);

@@ -70,7 +70,7 @@ int scar_store_load(scar_store* store, const uint32_t* idx_host, uint32_t n_idx,
  *
  * offsets_host: HOST array, n_blocks + 1 non-decreasing element offsets, offsets[0] = 0.
  * max_rows: most blocks per save or load; max_elems: most elements per save or load (the
- * size of the two pinned buffers).  SCAR_F32, SCAR_BF16 and SCAR_I32 stores. */
+ * size of the two pinned buffers).  Every store type; elements in the file have c's type. */
 int scar_var_store_create(const char* path, int32_t dtype, uint32_t n_blocks,
                           const uint64_t* offsets_host, uint32_t max_rows, uint64_t max_elems,
                           scar_store** out);

@@ -18,9 +18,12 @@ constexpr int kUnroll = 4;  // 16-byte loads per lane and stream kept in flight
 
 // What a kernel measures: squared L2 on float32 / bfloat16, exact L1 on int32 counts, or
 // (the *_TV kinds) the total variation 1/2 * sum |x - c| of float rows that are distributions.
-enum : int { DT_F32 = 0, DT_BF16 = 1, DT_I32 = 2, DT_F32_TV = 3, DT_BF16_TV = 4 };
+// DT_MIXED (only in the walk over blocks of unequal length): float32 x against a bfloat16 c.
+enum : int { DT_F32 = 0, DT_BF16 = 1, DT_I32 = 2, DT_F32_TV = 3, DT_BF16_TV = 4, DT_MIXED = 5 };
 
+// Element size of x, and of c (they differ for DT_MIXED only).
 __host__ __device__ constexpr int elem_bytes(int dt) { return (dt == DT_BF16 || dt == DT_BF16_TV) ? 2 : 4; }
+__host__ __device__ constexpr int c_elem_bytes(int dt) { return dt == DT_MIXED ? 2 : elem_bytes(dt); }
 __host__ __device__ constexpr bool is_tv(int dt) { return dt == DT_F32_TV || dt == DT_BF16_TV; }
 
 // ---- streaming memory access ---------------------------------------------------------

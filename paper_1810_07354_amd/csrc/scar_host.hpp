@@ -17,7 +17,8 @@ constexpr uint32_t kMaxBlockLen = 1u << 28;
 inline bool dtype_ok(int32_t dt) {
   return dt == SCAR_F32 || dt == SCAR_BF16 || dt == SCAR_I32 || dt == SCAR_F32_BF16C;
 }
-inline int host_elem_bytes(int32_t dt) { return dt == SCAR_BF16 ? 2 : 4; }
+inline int host_elem_bytes(int32_t dt) { return dt == SCAR_BF16 ? 2 : 4; }  // of x
+inline int host_c_elem_bytes(int32_t dt) { return (dt == SCAR_BF16 || dt == SCAR_F32_BF16C) ? 2 : 4; }  // of c
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 

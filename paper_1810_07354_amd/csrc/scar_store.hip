@@ -336,7 +336,7 @@ extern "C" int scar_var_store_create(const char* path, int32_t dtype, uint32_t n
                                      const uint64_t* offsets_host, uint32_t max_rows, uint64_t max_elems,
                                      scar_store** out) {
   if (!path || !out || !offsets_host || n_blocks == 0 || n_blocks > SCAR_MAX_BLOCKS || max_rows == 0 ||
-      max_elems == 0 || !scar::dtype_ok(dtype) || dtype == SCAR_F32_BF16C || offsets_host[0] != 0)
+      max_elems == 0 || !scar::dtype_ok(dtype) || offsets_host[0] != 0)
     return SCAR_ERR_INVALID_ARG;
   for (uint32_t b = 0; b < n_blocks; ++b)
     if (offsets_host[b + 1] < offsets_host[b]) return SCAR_ERR_INVALID_ARG;

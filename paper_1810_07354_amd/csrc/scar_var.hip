@@ -33,6 +33,7 @@
 // to the next 16-byte boundary, a body of non-temporal 16-byte accesses, and a tail.
 #include "scar_device.hpp"
 #include "scar_host.hpp"
+#include "scar_mixed_device.hpp"
 
 namespace scar {
 
@@ -119,6 +120,79 @@ __device__ __forceinline__ void store_words(W* p, const uint4& v) {
   for (int i = 0; i < N; ++i) p[i] = w[i];
 }
 
+// A segment of a float32 store with a bfloat16 checkpoint (SCAR_F32_BF16C): the unit is 4
+// elements, 16 bytes of x against 8 bytes of c; a commit stores x rounded to nearest even (and
+// the same rounded values in the staging rows), a recovery widens.  `side` is only 2-byte
+// aligned and is read and written in halfwords.
+template <bool ACC, int COPY, int SIDE>
+__device__ __forceinline__ void segment_apply_mixed(float* __restrict__ x, uint16_t* __restrict__ c,
+                                                    uint16_t* __restrict__ side, uint64_t first, uint64_t len,
+                                                    bool base_aligned, double& acc) {
+  float* xs = x + first;
+  uint16_t* cs = SIDE == SIDE_READ ? side : c + first;
+  auto element = [&](uint64_t j) {
+    if (ACC) acc += (double)sq(xs[j] - widen_elem(cs, j));
+    if (COPY == COPY_X_TO_C) {
+      const uint16_t r = (uint16_t)round_bf16(__float_as_uint(xs[j]));
+      cs[j] = r;
+      if (SIDE == SIDE_WRITE) side[j] = r;
+    }
+    if (COPY == COPY_C_TO_X) xs[j] = widen_elem(cs, j);
+  };
+  uint64_t head = len;  // elements handled one by one before the whole units
+  if (base_aligned) {
+    head = (kMixUnit - (first & (kMixUnit - 1))) & (kMixUnit - 1);
+    if (head > len) head = len;
+  }
+  for (uint64_t j = threadIdx.x; j < head; j += kWG) element(j);
+  const uint64_t nunit = (len - head) / kMixUnit;
+  uint4* xv = (uint4*)(xs + head);
+  uint2* cv = (uint2*)(cs + head);  // SIDE_READ: only 2-byte aligned, read in halfwords below
+  constexpr int U = COPY == COPY_NONE ? kMixU : 2;
+  for (uint64_t v0 = 0; v0 < nunit; v0 += (uint64_t)kWG * U) {
+    uint4 a[U];
+    uint2 b[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint64_t v = v0 + (uint64_t)u * kWG + threadIdx.x;
+      const bool ok = v < nunit;
+      a[u] = (ok && (ACC || COPY == COPY_X_TO_C)) ? load_stream(xv + v) : make_uint4(0, 0, 0, 0);
+      b[u] = make_uint2(0, 0);
+      if (ok && (ACC || COPY == COPY_C_TO_X)) {
+        if (SIDE == SIDE_READ) {
+          const uint16_t* h = cs + head + v * kMixUnit;
+          b[u] = make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
+        } else {
+          b[u] = load_stream2(cv + v);
+        }
+      }
+    }
+    if (ACC) {
+      float part = 0.f;
+#pragma unroll
+      for (int u = 0; u < U; ++u) part += sqdiff_unit(a[u], b[u]);
+      acc += (double)part;
+    }
+    if (COPY != COPY_NONE) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint64_t v = v0 + (uint64_t)u * kWG + threadIdx.x;
+        if (v >= nunit) continue;
+        if (COPY == COPY_X_TO_C) {
+          const uint2 r = round_unit(a[u]);
+          store_stream2(cv + v, r);
+          if (SIDE == SIDE_WRITE) {
+            uint16_t* h = side + head + v * kMixUnit;
+            h[0] = (uint16_t)r.x, h[1] = (uint16_t)(r.x >> 16), h[2] = (uint16_t)r.y, h[3] = (uint16_t)(r.y >> 16);
+          }
+        }
+        if (COPY == COPY_C_TO_X) store_stream(xv + v, widen_unit(b[u]));
+      }
+    }
+  }
+  for (uint64_t j = head + nunit * kMixUnit + threadIdx.x; j < len; j += kWG) element(j);
+}
+
 // One segment of `len` elements starting at element `first`, spread over the workgroup.
 //   ACC:  acc += sum of (c - x)^2 or |c - x| over the segment (this lane's share)
 //   COPY: the segment is copied x -> c or c -> x afterwards
@@ -129,6 +203,10 @@ template <int DT, bool ACC, int COPY, int SIDE>
 __device__ __forceinline__ void segment_apply(char* __restrict__ x, char* __restrict__ c,
                                               char* __restrict__ side, uint64_t first, uint64_t len,
                                               bool base_aligned, typename Acc<DT>::type& acc) {
+  if constexpr (DT == DT_MIXED) {
+    segment_apply_mixed<ACC, COPY, SIDE>((float*)x, (uint16_t*)c, (uint16_t*)side, first, len, base_aligned, acc);
+    return;
+  }
   constexpr int E = elem_bytes(DT);
   constexpr int EPV = 16 / E;
   using word_t = typename std::conditional<E == 4, uint32_t, uint16_t>::type;
@@ -224,7 +302,7 @@ __global__ __launch_bounds__(kWG) void k_var_walk(char* __restrict__ x, char* __
     const uint64_t seg_end = bend < e1 ? bend : e1;
     if (PER_BLOCK || !mask || mask[cur]) {
       char* side_seg = nullptr;
-      if constexpr (SIDE != SIDE_NONE) side_seg = side + (pack[cur] + (pos - off[cur])) * elem_bytes(DT);
+      if constexpr (SIDE != SIDE_NONE) side_seg = side + (pack[cur] + (pos - off[cur])) * c_elem_bytes(DT);
       if constexpr (is_tv(DT) && ACC && !PER_BLOCK) {  // a row's share counts with the row's weight
         const float w = weights ? weights[cur] : 1.f;
         acc_t seg = 0;
@@ -338,8 +416,7 @@ __global__ __launch_bounds__(kWG) void k_var_pack_set(uint32_t n_blocks, const u
 }
 
 static uint64_t var_blocks(const scar_var_layout* l) {
-  if (!l || !dtype_ok(l->dtype) || l->dtype == SCAR_F32_BF16C || l->n_blocks > SCAR_MAX_BLOCKS)
-    return UINT64_MAX;
+  if (!l || !dtype_ok(l->dtype) || l->n_blocks > SCAR_MAX_BLOCKS) return UINT64_MAX;
   if (l->n_blocks && (!l->offsets || !aligned(l->offsets, 8))) return UINT64_MAX;
   return l->n_blocks;
 }
@@ -353,7 +430,7 @@ template <int DT, bool ACC, int COPY, bool PER_BLOCK, int SIDE = SIDE_NONE>
 static void launch_walk(const scar_var_layout* l, const void* x, const void* c, const uint8_t* mask,
                         bool planned, void* workspace, const VarGeometry& g, hipStream_t st,
                         void* side = nullptr, const float* weights = nullptr) {
-  const bool base_aligned = aligned(x, 16) && aligned(c, 16);
+  const bool base_aligned = aligned(x, 16) && aligned(c, DT == DT_MIXED ? 8 : 16);
   uint32_t* first = (uint32_t*)workspace;
   uint8_t* any = (uint8_t*)workspace + kVarPlanAnyOffset;
   void* partial = (char*)workspace + kVarPartialOffset;
@@ -378,6 +455,7 @@ static void dispatch_walk(const scar_var_layout* l, const void* x, const void* c
   switch (l->dtype) {
     case SCAR_F32: launch_walk<DT_F32, ACC, COPY, PER_BLOCK, SIDE>(l, x, c, mask, planned, workspace, g, st, side); break;
     case SCAR_BF16: launch_walk<DT_BF16, ACC, COPY, PER_BLOCK, SIDE>(l, x, c, mask, planned, workspace, g, st, side); break;
+    case SCAR_F32_BF16C: launch_walk<DT_MIXED, ACC, COPY, PER_BLOCK, SIDE>(l, x, c, mask, planned, workspace, g, st, side); break;
     default: launch_walk<DT_I32, ACC, COPY, PER_BLOCK, SIDE>(l, x, c, mask, planned, workspace, g, st, side); break;
   }
 }
@@ -438,8 +516,7 @@ static int var_rows(int copy, const scar_var_layout* layout, const void* x, cons
                     const uint32_t* idx, uint32_t n_idx, bool all_blocks, scar_norm* norm_out,
                     void* workspace, size_t workspace_bytes, void* stream, void* side = nullptr,
                     uint64_t* side_offsets = nullptr, bool tv = false, const float* weights = nullptr) {
-  if (layout && layout->dtype == SCAR_F32_BF16C) return SCAR_ERR_UNSUPPORTED;
-  if (tv && layout && layout->dtype == SCAR_I32) return SCAR_ERR_UNSUPPORTED;
+  if (tv && layout && (layout->dtype == SCAR_I32 || layout->dtype == SCAR_F32_BF16C)) return SCAR_ERR_UNSUPPORTED;
   if (!aligned(weights, 4)) return SCAR_ERR_INVALID_ARG;
   const uint64_t nb = var_blocks(layout);
   if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
@@ -448,7 +525,7 @@ static int var_rows(int copy, const scar_var_layout* layout, const void* x, cons
   if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;
   const bool nothing = nb == 0 || layout->n_elems == 0 || (!all_blocks && n_idx == 0);
-  if (side && (!side_offsets || !aligned(side_offsets, 8) || !aligned(side, host_elem_bytes(layout->dtype))))
+  if (side && (!side_offsets || !aligned(side_offsets, 8) || !aligned(side, host_c_elem_bytes(layout->dtype))))
     return SCAR_ERR_INVALID_ARG;
   if (nothing) {
     if (side && copy == COPY_X_TO_C)  // an empty list still gets its (all zero) offsets
@@ -462,8 +539,9 @@ static int var_rows(int copy, const scar_var_layout* layout, const void* x, cons
     }
     return launch_status();
   }
-  const int eb = host_elem_bytes(layout->dtype);
-  if (!x || !c || (!all_blocks && !idx) || !aligned(x, eb) || !aligned(c, eb) || !aligned(idx, 4))
+  const int eb = host_elem_bytes(layout->dtype), ceb = host_c_elem_bytes(layout->dtype);
+  if (!x || !c || (!all_blocks && !idx) || !aligned(x, eb) || !aligned(c, side && copy == COPY_C_TO_X ? eb : ceb) ||
+      !aligned(idx, 4))
     return SCAR_ERR_INVALID_ARG;
   // walks that add nothing up take the finer cut
   const VarGeometry g = var_geometry(layout->n_elems, norm_out ? kVarMaxGrid : kVarMaxGridCopy);
@@ -513,14 +591,13 @@ extern "C" size_t scar_var_workspace_bytes(uint64_t n_blocks) {
 static int var_scores(bool tv, const scar_var_layout* layout, const void* x, const void* c,
                       const float* weights, void* scores, void* workspace, size_t workspace_bytes,
                       void* stream) {
-  if (layout && layout->dtype == SCAR_F32_BF16C) return SCAR_ERR_UNSUPPORTED;
-  if (tv && layout && layout->dtype == SCAR_I32) return SCAR_ERR_UNSUPPORTED;
+  if (tv && layout && (layout->dtype == SCAR_I32 || layout->dtype == SCAR_F32_BF16C)) return SCAR_ERR_UNSUPPORTED;
   const uint64_t nb = var_blocks(layout);
   if (nb == UINT64_MAX) return SCAR_ERR_INVALID_ARG;
   if (nb == 0) return SCAR_OK;
-  const int eb = host_elem_bytes(layout->dtype);
+  const int eb = host_elem_bytes(layout->dtype), ceb = host_c_elem_bytes(layout->dtype);
   if (!scores || !aligned(scores, layout->dtype == SCAR_I32 ? 8 : 4) || !aligned(weights, 4)) return SCAR_ERR_INVALID_ARG;
-  if (layout->n_elems && (!x || !c || !aligned(x, eb) || !aligned(c, eb))) return SCAR_ERR_INVALID_ARG;
+  if (layout->n_elems && (!x || !c || !aligned(x, eb) || !aligned(c, ceb))) return SCAR_ERR_INVALID_ARG;
   const int rc = check_var_workspace(workspace, workspace_bytes, nb);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;

@@ -385,14 +385,13 @@ def select_random(n_blocks_, k, seed, draw, workspace, out=None):
 
 # ---- blocks of unequal length -------------------------------------------------------------
 
-def var_layout_of(x, offsets) -> VarLayout:
-    """offsets: int64 device tensor of n_blocks + 1 element offsets (offsets[0] = 0)."""
+def var_layout_of(x, offsets, c=None) -> VarLayout:
+    """offsets: int64 device tensor of n_blocks + 1 element offsets (offsets[0] = 0).  c (or
+    packed rows of c's type) decides between a plain store and float32 x with a bfloat16 c."""
     _dev(offsets, "offsets")
     if offsets.dtype != torch.int64:
         raise TypeError("offsets must be an int64 tensor")
-    if x.dtype not in _DTYPE_OF:
-        raise TypeError("unsupported element type %s" % x.dtype)
-    return VarLayout(_DTYPE_OF[x.dtype], offsets.numel() - 1, x.numel(), offsets.data_ptr())
+    return VarLayout(store_type(x, c), offsets.numel() - 1, x.numel(), offsets.data_ptr())
 
 
 def var_workspace_bytes(n_blocks_: int) -> int:
@@ -406,9 +405,9 @@ def new_var_workspace(n_blocks_: int, device) -> torch.Tensor:
 def var_block_scores(x, c, offsets, workspace, out=None):
     """scar_var_block_scores."""
     _dev(x, "x"), _dev(c, "c"), _dev(workspace, "workspace")
-    if x.dtype != c.dtype or x.numel() != c.numel():
-        raise ValueError("x and c must have the same element type and size")
-    lay = var_layout_of(x, offsets)
+    if x.numel() != c.numel():
+        raise ValueError("x and c must have the same size")
+    lay = var_layout_of(x, offsets, c)
     if out is None:
         out = torch.empty(lay.n_blocks, dtype=torch.int64 if x.dtype == torch.int32 else torch.float32,
                           device=x.device)
@@ -419,7 +418,7 @@ def var_block_scores(x, c, offsets, workspace, out=None):
 def var_checkpoint_commit(x, c, offsets, idx, workspace):
     """scar_var_checkpoint_commit."""
     _dev(x, "x"), _dev(c, "c"), _idx(idx, "idx"), _dev(workspace, "workspace")
-    lay = var_layout_of(x, offsets)
+    lay = var_layout_of(x, offsets, c)
     _check(lib().scar_var_checkpoint_commit(ctypes.byref(lay), _p(x), _p(c), _p(idx), idx.numel(),
                                             _p(workspace), _bytes(workspace), _stream()),
            "scar_var_checkpoint_commit")
@@ -431,7 +430,7 @@ def var_checkpoint_commit_staged(x, c, offsets, idx, workspace, staging):
     _dev(x, "x"), _dev(c, "c"), _idx(idx, "idx"), _dev(workspace, "workspace"), _dev(staging, "staging")
     if staging.dtype != c.dtype:
         raise TypeError("staging must have c's element type")
-    lay = var_layout_of(x, offsets)
+    lay = var_layout_of(x, offsets, c)
     st_off = torch.empty(idx.numel() + 1, dtype=torch.int64, device=x.device)
     _check(lib().scar_var_checkpoint_commit_staged(ctypes.byref(lay), _p(x), _p(c), _p(idx), idx.numel(),
                                                    _p(staging), _p(st_off), _p(workspace), _bytes(workspace),
@@ -446,9 +445,7 @@ def var_partial_recover_rows(x, rows, row_offsets, offsets, lost_idx, workspace,
     _dev(workspace, "workspace")
     if row_offsets.dtype != torch.int64 or row_offsets.numel() < lost_idx.numel():
         raise ValueError("row_offsets must be an int64 tensor with an entry per lost block")
-    if rows.dtype != x.dtype:
-        raise TypeError("rows must have x's element type")
-    lay = var_layout_of(x, offsets)
+    lay = var_layout_of(x, offsets, rows)
     norm_out = _norm_buffer(x.device) if want_norm else None
     _check(lib().scar_var_partial_recover_rows(ctypes.byref(lay), _p(x), _p(rows), _p(row_offsets), _p(lost_idx),
                                                lost_idx.numel(), _p(norm_out), _p(workspace), _bytes(workspace),
@@ -459,7 +456,7 @@ def var_partial_recover_rows(x, rows, row_offsets, offsets, lost_idx, workspace,
 def var_partial_recover(x, c, offsets, lost_idx, workspace, want_norm=True):
     """scar_var_partial_recover; returns the device scar_norm buffer or None."""
     _dev(x, "x"), _dev(c, "c"), _idx(lost_idx, "lost_idx"), _dev(workspace, "workspace")
-    lay = var_layout_of(x, offsets)
+    lay = var_layout_of(x, offsets, c)
     norm_out = _norm_buffer(x.device) if want_norm else None
     _check(lib().scar_var_partial_recover(ctypes.byref(lay), _p(x), _p(c), _p(lost_idx), lost_idx.numel(),
                                           _p(norm_out), _p(workspace), _bytes(workspace), _stream()),
@@ -470,7 +467,7 @@ def var_partial_recover(x, c, offsets, lost_idx, workspace, want_norm=True):
 def var_perturbation_norm(x, c, offsets, idx, workspace):
     """scar_var_perturbation_norm (idx None = every block)."""
     _dev(x, "x"), _dev(c, "c"), _dev(workspace, "workspace")
-    lay = var_layout_of(x, offsets)
+    lay = var_layout_of(x, offsets, c)
     norm_out = _norm_buffer(x.device)
     if idx is None:
         ptr, n = ctypes.c_void_p(0), 0

@@ -120,15 +120,18 @@ def test_store_errors(tmp_path):
         scar.Store(str(tmp_path / "no_such_dir" / "x.ckpt"), max_rows=4, layout=scar.Layout(scar.F32, 8, 64))
 
 
-@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16, wl.I32])
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16, wl.I32, MIX])
 def test_by_layer_store_follows_the_running_checkpoint_and_recovers_from_it(dtype, tmp_path):
     # blocks of unequal length (Section 5.1, by-layer) through the storage leg: staged commits,
     # background saves into a file with one place per block, recovery of lost blocks from it
     sizes = wl.mixed_layer_sizes(120, 1_500_000, seed=21)
-    w = wl.layers_like(sizes, seed=22, fraction=0.2, n_lost=30, dtype=dtype)
+    xt, ct = (wl.F32, wl.BF16) if dtype == MIX else (dtype, dtype)
+    w = wl.layers_like(sizes, seed=22, fraction=0.2, n_lost=30, dtype=xt)
     off, nb, n = w.offsets, w.n_blocks, int(w.x.size)
     hx, hc = w.x.copy(), w.c.copy()
-    x, c = to_dev(hx, dtype), to_dev(hc, dtype)
+    if dtype == MIX:
+        hc = wl.f32_to_bf16_bits(hc)
+    x, c = to_dev(hx, xt), to_dev(hc, ct)
     d_off = torch.from_numpy(off.astype(np.int64)).to(DEV)
     ws, ws_sel = scar.new_var_workspace(nb, DEV), scar.new_workspace(nb, DEV)
     esz = c.element_size()
@@ -160,14 +163,14 @@ def test_by_layer_store_follows_the_running_checkpoint_and_recovers_from_it(dtyp
         for cyc in range(3):
             print("by-layer store dtype=%d cycle %d" % (dtype, cyc), flush=True)
             lo = int(r.integers(0, n - n // 4))
-            if dtype == wl.I32:
+            if xt == wl.I32:
                 hx[lo:lo + n // 4] += r.integers(-2, 3, size=n // 4).astype(np.int32)
-            elif dtype == wl.BF16:
+            elif xt == wl.BF16:
                 hx[lo:lo + n // 4] = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(hx[lo:lo + n // 4])
                                                          + r.normal(0, 1e-2, size=n // 4).astype(np.float32))
             else:
                 hx[lo:lo + n // 4] += r.normal(0, 1e-2, size=n // 4).astype(np.float32)
-            x = to_dev(hx, dtype)
+            x = to_dev(hx, xt)
             s = scar.var_block_scores(x, c, d_off, ws)
             idx = scar.select_topk(s, k, ws_sel)
             scar.var_checkpoint_commit_staged(x, c, d_off, idx, ws, stagings[cyc])
@@ -178,13 +181,13 @@ def test_by_layer_store_follows_the_running_checkpoint_and_recovers_from_it(dtyp
         np.testing.assert_array_equal(file_checkpoint(), hc)
 
         # failure: the lost blocks come back from the file
-        if dtype == wl.I32:
+        if xt == wl.I32:
             hx += 1
-        elif dtype == wl.BF16:
+        elif xt == wl.BF16:
             hx[:] = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(hx) + np.float32(0.5))
         else:
             hx += np.float32(0.5)
-        x = to_dev(hx, dtype)
+        x = to_dev(hx, xt)
         lost = w.lost
         rows = torch.zeros(n, dtype=c.dtype, device=DEV)
         row_off = store.load(lost, rows)

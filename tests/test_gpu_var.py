@@ -17,16 +17,24 @@ def off_dev(off):
     return torch.from_numpy(off.astype(np.int64)).to(DEV)
 
 
-def cycle(w: wl.VarWorkload, k=None, lost=None, unaligned=False):
+MIX = wl.F32_BF16C
+
+
+def cycle(w: wl.VarWorkload, k=None, lost=None, unaligned=False, bf16_checkpoint=False):
     dt, off = w.dtype, w.offsets
     k = w.k if k is None else k
     lost = w.lost if lost is None else lost
     hx, hc = w.x.copy(), w.c.copy()
+    xdt = cdt = dt
+    if bf16_checkpoint:                   # float32 x with a bfloat16 checkpoint (SCAR_F32_BF16C)
+        assert dt == wl.F32
+        hc, dt, cdt = wl.f32_to_bf16_bits(hc), MIX, wl.BF16
     if unaligned:                         # views that start one element into their allocation
-        pad = np.zeros(1, dtype=hx.dtype)
-        x, c = to_dev(np.concatenate([pad, hx]), dt)[1:], to_dev(np.concatenate([pad, hc]), dt)[1:]
+        x = to_dev(np.concatenate([np.zeros(1, dtype=hx.dtype), hx]), xdt)[1:]
+        c = to_dev(np.concatenate([np.zeros(1, dtype=hc.dtype), hc]), cdt)[1:]
     else:
-        x, c = to_dev(hx, dt), to_dev(hc, dt)
+        x, c = to_dev(hx, xdt), to_dev(hc, cdt)
+    kind = wl.F32 if dt == MIX else dt    # what scores and norms are compared as
     d_off = off_dev(off)
     nb = w.n_blocks
     ws = scar.new_var_workspace(nb, DEV)
@@ -34,7 +42,7 @@ def cycle(w: wl.VarWorkload, k=None, lost=None, unaligned=False):
 
     s = scar.var_block_scores(x, c, d_off, ws)
     s_ref = oracle.var_block_scores(dt, hx, hc, off)
-    assert_scores_match(s, s_ref, dt)
+    assert_scores_match(s, s_ref, kind)
 
     idx = scar.select_topk(s, k, ws_sel)
     assert_selection_matches(idx_host(idx), s.cpu().numpy(), s_ref, k)
@@ -62,21 +70,21 @@ def cycle(w: wl.VarWorkload, k=None, lost=None, unaligned=False):
     if lost.size:
         x2, hx2 = x.clone(), hx.copy()
         rows_h = np.zeros(int(lens[lost.astype(np.int64)].sum()), dtype=hc.dtype)
-        row_off = oracle.var_checkpoint_commit(dt, hc, hc.copy(), off, lost, rows_h)   # packs c's blocks
-        rows_d = torch.cat([torch.zeros(1, dtype=c.dtype, device=DEV), to_dev(rows_h, dt)])[1:]
+        row_off = oracle.var_checkpoint_commit(cdt, hc, hc.copy(), off, lost, rows_h)  # packs c's blocks
+        rows_d = torch.cat([torch.zeros(1, dtype=c.dtype, device=DEV), to_dev(rows_h, cdt)])[1:]
         got_r = scar.read_norm(scar.var_partial_recover_rows(
             x2, rows_d, torch.from_numpy(row_off.astype(np.int64)).to(DEV), d_off, idx_dev(lost), ws))
         want_r = oracle.var_partial_recover_rows(dt, hx2, rows_h, row_off[:-1], off, lost)
-        assert_norm_matches(got_r, want_r, dt)
+        assert_norm_matches(got_r, want_r, kind)
         np.testing.assert_array_equal(to_host(x2.contiguous()), hx2)
 
     full = scar.read_norm(scar.var_perturbation_norm(x, c, d_off, None, ws))
-    assert_norm_matches(full, oracle.var_perturbation_norm(dt, hx, hc, off), dt)
+    assert_norm_matches(full, oracle.var_perturbation_norm(dt, hx, hc, off), kind)
     part = scar.read_norm(scar.var_perturbation_norm(x, c, d_off, idx_dev(lost), ws))
     got = scar.read_norm(scar.var_partial_recover(x, c, d_off, idx_dev(lost), ws))
     want = oracle.var_partial_recover(dt, hx, hc, off, lost)
-    assert_norm_matches(got, want, dt)
-    assert_norm_matches(part, want, dt)
+    assert_norm_matches(got, want, kind)
+    assert_norm_matches(part, want, kind)
     assert got[1] <= full[1] * (1 + REL_TOL)
     np.testing.assert_array_equal(to_host(x.contiguous()), hx)
     np.testing.assert_array_equal(to_host(c.contiguous()), hc)
@@ -98,6 +106,21 @@ def test_mixed_layers(dtype, unaligned):
     w = wl.layers_like(sizes, seed=9, fraction=0.2, n_lost=50, dtype=dtype)
     print("mixed layers dtype=%d unaligned=%s n=%d" % (dtype, unaligned, w.x.size), flush=True)
     cycle(w, unaligned=unaligned)
+
+
+@pytest.mark.parametrize("unaligned", [False, True])
+def test_by_layer_stores_with_a_bfloat16_checkpoint(unaligned):
+    # SCAR_F32_BF16C through the walk over blocks of unequal length: scores against the widened
+    # checkpoint, commits that round to nearest even (staging rows too), recovery that widens
+    print("by-layer CNN with a bf16 checkpoint, unaligned=%s" % unaligned, flush=True)
+    cycle(wl.layers_like(dtype=wl.F32), unaligned=unaligned, bf16_checkpoint=True)
+    sizes = wl.mixed_layer_sizes(200, 6_000_000)
+    w = wl.layers_like(sizes, seed=9, fraction=0.2, n_lost=50, dtype=wl.F32)
+    print("mixed layers with a bf16 checkpoint n=%d" % w.x.size, flush=True)
+    cycle(w, unaligned=unaligned, bf16_checkpoint=True)
+    r = np.random.default_rng(5)
+    cycle(wl.layers_like(r.integers(0, 40, size=100_000), seed=12, fraction=0.1, n_lost=20_000), unaligned=unaligned,
+          bf16_checkpoint=True)
 
 
 def test_many_small_unequal_blocks_and_long_ranges():
