@@ -222,6 +222,15 @@ int scar_mask_to_indices(const uint8_t* mask, uint32_t n_blocks, uint32_t* out_i
                          uint32_t* out_count, void* workspace, size_t workspace_bytes,
                          void* stream);
 
+/* A debugging aid for the one precondition on index lists that no call checks: counts
+ * (DEVICE, two uint32) receives how many entries of idx are >= n_blocks (the calls skip
+ * those) and how many repeat an earlier entry (the norm would count such a block twice).
+ * workspace: scar_check_workspace_bytes(n_blocks) bytes of device scratch (a bit per block),
+ * 256-byte aligned.  Enqueues two small kernels; the list is not modified. */
+size_t scar_check_workspace_bytes(uint64_t n_blocks);
+int scar_check_indices(const uint32_t* idx, uint32_t n_idx, uint32_t n_blocks, uint32_t* counts,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
 /* The comparison strategies of Section 5.4 for choosing K; their output feeds
  * scar_checkpoint_commit exactly like scar_select_topk's.
  *

@@ -582,6 +582,35 @@ static void run_select(const KeyArgs scores, uint32_t n, uint32_t k, uint32_t* o
 
 __global__ void k_store_u32(uint32_t* __restrict__ p, uint32_t v) { *p = v; }
 
+// Checking an index list (a debugging aid): one bit per block; an entry whose bit is already
+// set is a repeat, an entry >= n_blocks is out of range.  counts[0] = out of range, counts[1] =
+// repeats.
+__global__ __launch_bounds__(kWG) void k_check_clear(uint32_t* __restrict__ bits, uint32_t n_words,
+                                                     uint32_t* __restrict__ counts) {
+  const uint32_t tid = blockIdx.x * kWG + threadIdx.x;
+  for (uint32_t i = tid; i < n_words; i += gridDim.x * kWG) bits[i] = 0;
+  if (tid < 2) counts[tid] = 0;
+}
+__global__ __launch_bounds__(kWG) void k_check_mark(const uint32_t* __restrict__ idx, uint32_t n_idx,
+                                                    uint32_t n_blocks, uint32_t* __restrict__ bits,
+                                                    uint32_t* __restrict__ counts) {
+  uint32_t outside = 0, repeated = 0;
+  for (uint64_t i = (uint64_t)blockIdx.x * kWG + threadIdx.x; i < n_idx; i += (uint64_t)gridDim.x * kWG) {
+    const uint32_t b = idx[i];
+    if (b >= n_blocks) {
+      ++outside;
+    } else {
+      const uint32_t bit = 1u << (b & 31);
+      if (atomicOr(&bits[b >> 5], bit) & bit) ++repeated;
+    }
+  }
+  outside = wave_sum(outside), repeated = wave_sum(repeated);
+  if ((threadIdx.x & (kWave - 1)) == 0) {
+    if (outside) atomicAdd(&counts[0], outside);
+    if (repeated) atomicAdd(&counts[1], repeated);
+  }
+}
+
 // Round-robin strategy: the k blocks start, start+1, ... (mod n), written ascending.  When
 // the run wraps, its wrapped head (blocks 0 .. wrap-1) comes first.
 __global__ __launch_bounds__(kWG) void k_select_round(uint32_t n, uint32_t k, uint32_t start,
@@ -732,5 +761,28 @@ extern "C" int scar_select_random(uint32_t n_blocks, uint32_t k, uint64_t seed, 
   if (rc) return rc;
   run_select<SRC_RANDOM>(key_args(nullptr, seed, draw), n_blocks, k, out_idx, workspace,
                          (hipStream_t)stream);
+  return launch_status();
+}
+
+extern "C" size_t scar_check_workspace_bytes(uint64_t n_blocks) {
+  return n_blocks > SCAR_MAX_BLOCKS ? 0 : ((n_blocks + 31) / 32 * 4 + 255) / 256 * 256 + 256;
+}
+
+extern "C" int scar_check_indices(const uint32_t* idx, uint32_t n_idx, uint32_t n_blocks, uint32_t* counts,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (n_blocks > SCAR_MAX_BLOCKS || !counts || !aligned(counts, 4) || (n_idx && (!idx || !aligned(idx, 4))))
+    return SCAR_ERR_INVALID_ARG;
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < scar_check_workspace_bytes(n_blocks))
+    return SCAR_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const uint32_t n_words = (n_blocks + 31) / 32;
+  const uint32_t cg = (n_words + kWG * 8 - 1) / (kWG * 8);
+  launch(k_check_clear, dim3(cg < 1 ? 1 : (cg > 1024 ? 1024 : cg)), dim3(kWG), 0, st, (uint32_t*)workspace, n_words,
+         counts);
+  if (n_idx) {
+    const uint32_t mg = (n_idx + kWG * 4 - 1) / (kWG * 4);
+    launch(k_check_mark, dim3(mg > 4096 ? 4096 : mg), dim3(kWG), 0, st, idx, n_idx, n_blocks, (uint32_t*)workspace,
+           counts);
+  }
   return launch_status();
 }

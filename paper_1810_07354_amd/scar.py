@@ -68,6 +68,10 @@ def lib():
         L.scar_block_scores_rows.restype = ctypes.c_int
         L.scar_select_topk.argtypes = [i32, vp, u32, u32, vp, vp, sz, vp]
         L.scar_checkpoint_commit.argtypes = [lp, vp, vp, vp, u32, vp, vp]
+        L.scar_check_workspace_bytes.argtypes = [u64]
+        L.scar_check_workspace_bytes.restype = sz
+        L.scar_check_indices.argtypes = [vp, u32, u32, vp, vp, sz, vp]
+        L.scar_check_indices.restype = ctypes.c_int
         L.scar_select_topk_bounded.argtypes = [i32, vp, u32, u32, u64, vp, vp, sz, vp]
         L.scar_select_topk_bounded.restype = ctypes.c_int
         L.scar_set_lookback_spin_limit.argtypes = [u32]
@@ -260,6 +264,17 @@ def select_topk_bounded(scores, k, score_max, workspace, out=None):
                                           _p(workspace), _bytes(workspace), _stream()),
            "scar_select_topk_bounded")
     return out
+
+
+def check_indices(idx, n_blocks_):
+    """scar_check_indices: (entries out of range, repeated entries) of an index list; synchronises."""
+    _idx(idx, "idx")
+    ws = torch.empty(int(lib().scar_check_workspace_bytes(int(n_blocks_))), dtype=torch.uint8, device=idx.device)
+    counts = torch.empty(2, dtype=torch.int32, device=idx.device)
+    _check(lib().scar_check_indices(_p(idx), idx.numel(), int(n_blocks_), _p(counts), _p(ws), _bytes(ws),
+                                    _stream()), "scar_check_indices")
+    host = counts.cpu()
+    return int(host[0]), int(host[1])
 
 
 def set_lookback_spin_limit(polls: int) -> None:

@@ -699,6 +699,26 @@ def test_misaligned_bases_whole_cycles(dtype, off_x, off_c):
         np.testing.assert_array_equal(to_host(c.contiguous()), hc)
 
 
+def test_index_list_checker_counts_repeats_and_entries_out_of_range():
+    r = np.random.default_rng(3)
+    for nb, n in ((1, 1), (50, 50), (100_000, 60_000), (3_000_000, 1_500_000)):
+        good = r.permutation(nb)[:n].astype(np.uint32)
+        assert scar.check_indices(idx_dev(good), nb) == (0, 0)
+        bad = good.copy()
+        n_rep, n_out = min(7, n // 2), min(5, n // 3)
+        if n_rep:
+            bad[-n_rep:] = bad[:n_rep]                      # repeats of the first entries
+        if n_out:
+            bad[n_rep:n_rep + n_out] = nb + np.arange(n_out, dtype=np.uint32)
+        print("check indices nb=%d n=%d" % (nb, n), flush=True)
+        assert scar.check_indices(idx_dev(bad), nb) == (n_out, n_rep)
+    assert scar.check_indices(torch.zeros(0, dtype=torch.int32, device=DEV), 10) == (0, 0)
+    # the selection's own output always passes
+    s = torch.rand(200_000, device=DEV)
+    idx = scar.select_topk(s, 77_777, scar.new_workspace(200_000, DEV))
+    assert scar.check_indices(idx, 200_000) == (0, 0)
+
+
 @pytest.mark.parametrize("dtype", [F32, I32])
 def test_out_of_range_list_entries_are_skipped(dtype):
     # documented device-side behaviour: an index >= n_blocks in a list is ignored
