@@ -455,19 +455,30 @@ __global__ __launch_bounds__(kWG) void k_giant_pieces(const char* __restrict__ x
   }
 }
 
+constexpr int kGiantFinishThreads = 1024;
 template <int DT>
-__global__ __launch_bounds__(kWG) void k_giant_finish(const typename Acc<DT>::type* __restrict__ partial,
-                                                      uint32_t ppb, uint32_t n_blocks,
-                                                      const uint32_t* __restrict__ idx, uint32_t first_entry,
-                                                      const float* __restrict__ weights, void* __restrict__ scores) {
+__global__ __launch_bounds__(kGiantFinishThreads) void k_giant_finish(
+    const typename Acc<DT>::type* __restrict__ partial, uint32_t ppb, uint32_t n_blocks,
+    const uint32_t* __restrict__ idx, uint32_t first_entry, const float* __restrict__ weights,
+    void* __restrict__ scores) {
   using acc_t = typename Acc<DT>::type;
-  __shared__ acc_t slots[kWG / kWave];
+  constexpr int T = kGiantFinishThreads;
+  __shared__ acc_t slots[T / kWave];
   const uint32_t e = blockIdx.x;
   const uint64_t b = idx ? idx[first_entry + e] : first_entry + e;
   if (b >= n_blocks) return;
+  const acc_t* mine = partial + (uint64_t)e * ppb;
   acc_t acc = 0;
-  for (uint32_t p = threadIdx.x; p < ppb; p += kWG) acc += partial[(uint64_t)e * ppb + p];
-  acc = workgroup_sum(acc, slots);
+  uint32_t p = threadIdx.x;
+  for (; p + 7 * T < ppb; p += 8 * T) {  // eight loads in flight, added in index order
+    acc_t t[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) t[u] = mine[p + u * T];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += t[u];
+  }
+  for (; p < ppb; p += T) acc += mine[p];
+  acc = workgroup_sum<T>(acc, slots);
   if (threadIdx.x == 0) {
     if constexpr (DT == DT_I32)
       ((long long*)scores)[b] = (long long)acc;
@@ -514,7 +525,7 @@ static int launch_giant(const scar_layout* l, const void* x, const void* c, void
     else
       launch((k_giant_pieces<DT, false>), dim3(grid), dim3(kWG), lds, st, (const char*)x, (const char*)c,
              l->n_elems, l->block_len, n_blocks, ppb, piece_elems, idx, first, n_entries, partial);
-    launch((k_giant_finish<DT>), dim3(n_entries), dim3(kWG), 0, st, (const acc_t*)partial, ppb, n_blocks, idx,
+    launch((k_giant_finish<DT>), dim3(n_entries), dim3(kGiantFinishThreads), 0, st, (const acc_t*)partial, ppb, n_blocks, idx,
            first, weights, scores);
   }
   return launch_status();
