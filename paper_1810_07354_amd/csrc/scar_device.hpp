@@ -307,7 +307,10 @@ __device__ __forceinline__ typename Acc<DT>::type block_distance(const char* xb,
     uint4 a[kUnroll], b[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-      const uint32_t v = v0 + u * G + lane;
+      // a whole workgroup on a row: each wavefront takes kUnroll consecutive KiB of a round
+      // rather than a KiB out of every fourth (measured faster, as for the scan of 4 KiB blocks)
+      const uint32_t v = G == 256 ? v0 + ((lane / kWave) * kUnroll + u) * kWave + (lane & (kWave - 1))
+                                  : v0 + u * G + lane;
       if (v < nvec) {
         a[u] = load_stream(xv + v);
         b[u] = load_stream(cv + v);
