@@ -738,7 +738,8 @@ def test_out_of_range_list_entries_are_skipped(dtype):
     np.testing.assert_array_equal(to_host(x), hx)
 
 
-@pytest.mark.parametrize("kind", ["by_layer", "total_variation", "bf16_checkpoint"])
+@pytest.mark.parametrize("kind", ["by_layer", "total_variation", "bf16_checkpoint", "few_long_blocks",
+                                  "counts_bounded_static"])
 def test_other_cycles_replay_correctly_from_a_hip_graph(kind):
     # the by-layer, total-variation and reduced-precision paths are kernels only as well
     r = np.random.default_rng(5)
@@ -768,6 +769,34 @@ def test_other_cycles_replay_correctly_from_a_hip_graph(kind):
             idx = scar.select_topk(s, k, ws)
             scar.checkpoint_commit(x_, c_, L, idx)
             return s, idx, scar.tv_partial_recover(x_, c_, L, lost, ws, wts)
+    elif kind == "few_long_blocks":
+        # scored in pieces through the library's fixed array, copied in pieces spread over the XCDs
+        L, nb = 1 << 20, 12
+        hx, hc = make_store(F32, L * nb - 77, seed=8)
+        x, c = to_dev(hx, F32), to_dev(hc, F32)
+        k, lost = 3, idx_dev(np.array([1, 7, 11], dtype=np.uint32))
+        ws = scar.new_workspace(nb, DEV)
+
+        def cycle(x_, c_):
+            s = scar.block_scores(x_, c_, L)
+            idx = scar.select_topk(s, k, ws)
+            scar.checkpoint_commit(x_, c_, L, idx)
+            return s, idx, scar.partial_recover(x_, c_, L, lost, ws)
+    elif kind == "counts_bounded_static":
+        # an int32 count table: bounded 64-bit selection, and the selection on the library's own scratch
+        L, nb = 200, 60_000
+        hx, hc = make_store(I32, L * nb, seed=8)
+        x, c = to_dev(hx, I32), to_dev(hc, I32)
+        k, lost = nb // 10, idx_dev(wl.random_lost_blocks(nb, nb // 8, 9))
+        ws = scar.new_workspace(nb, DEV)
+        idx_static = torch.empty(k, dtype=torch.int32, device=DEV)
+
+        def cycle(x_, c_):
+            s = scar.block_scores(x_, c_, L)
+            idx = scar.select_topk_bounded(s, k, L * (2 ** 32 - 1), ws)
+            scar.select_topk_static(s, k, out=idx_static)
+            scar.checkpoint_commit(x_, c_, L, idx_static)
+            return s, idx, scar.partial_recover(x_, c_, L, lost, ws)
     else:
         L, nb = 1024, 4096
         hx, hc = make_store(F32, L * nb, seed=8)
@@ -810,6 +839,8 @@ def test_other_cycles_replay_correctly_from_a_hip_graph(kind):
         noise = 1e-3 * torch.empty(x2.numel(), device=DEV).normal_(generator=g)
         state_x, state_c = (x2 + noise.to(x2.dtype)).contiguous(), c2
         torch.cuda.synchronize()
+        if kind == "counts_bounded_static":
+            assert torch.equal(idx_g, idx_static)
 
 
 @pytest.mark.parametrize("seed", range(6))
