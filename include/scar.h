@@ -23,7 +23,10 @@
  * Conventions for every call
  *   - Every data pointer (x, c, scores, idx, out_idx, staging, norm_out, mask, workspace)
  *     is DEVICE memory owned by the caller.  The library allocates nothing and keeps no
- *     state.  scar_layout and scalar arguments are host values.
+ *     state between calls, with two exceptions that are fixed arrays inside its code object
+ *     (one copy per GPU, nothing to free): the scratch of scar_select_topk_static and the
+ *     piece sums of scar_block_scores on a few very long blocks; calls that use the same one
+ *     must not overlap on one GPU.  scar_layout and scalar arguments are host values.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call
  *     validates its arguments on the host, enqueues its kernels on `stream` and returns;
  *     it never synchronises.  Results are in device memory once the stream reaches them.
