@@ -66,7 +66,10 @@ MUTANTS = [
      "    scores[b] = block_tv(dtype, x, c, lo, hi);"),
     ("document length of the list position", "    total += (weights ? (double)weights[b] : 1.0) * block_tv(dtype, x, c, lo, hi);",
      "    total += (weights ? (double)weights[i] : 1.0) * block_tv(dtype, x, c, lo, hi);"),
-    ("scaled norm as a root", "  out->sum = out->norm = total;", "  out->sum = total; out->norm = sqrt(total);"),
+    ("scaled norm as a root", "block_tv(dtype, x, c, lo, hi);\n  }\n  out->sum = out->norm = total;",
+     "block_tv(dtype, x, c, lo, hi);\n  }\n  out->sum = total; out->norm = sqrt(total);"),
+    ("unequal blocks: scaled norm as a root", "offsets[b + 1]);\n  }\n  out->sum = out->norm = total;",
+     "offsets[b + 1]);\n  }\n  out->sum = total; out->norm = sqrt(total);"),
     ("unequal blocks: staging offsets include the block itself", "      staging_offsets[i] = packed;\n", "      staging_offsets[i] = packed + (hi - lo);\n"),
     ("unequal blocks: staging packed by block position", "memcpy((char *)staging + packed * es, (const char *)c + lo * es, (hi - lo) * es);",
      "memcpy((char *)staging + lo * es, (const char *)c + lo * es, (hi - lo) * es);"),
