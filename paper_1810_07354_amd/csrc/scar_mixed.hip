@@ -16,14 +16,27 @@
 
 namespace scar {
 
-// Squared distance of one block (len elements at xb / cb), this lane's share.
+// Elements of a row before its first whole unit.  With x on a 16-byte and c on an 8-byte
+// boundary, element e of the store starts a unit of both streams exactly when e is a multiple
+// of 4, so a row that starts at element `off` has (-off) mod 4 leading elements, whatever its
+// length.  Rows of a store that is not aligned like that are walked element by element: all
+// of the row is "head".
+__device__ __forceinline__ uint32_t mixed_head(uint64_t off, uint32_t len, bool vec) {
+  if (!vec) return len;
+  const uint32_t head = (uint32_t)(0 - off) & (kMixUnit - 1);
+  return head < len ? head : len;
+}
+
+// Squared distance of one block (len elements at xb / cb, the first `head` of them before the
+// first whole unit), this lane's share: the whole units, then the elements around them.
 template <int G>
 __device__ __forceinline__ double mixed_distance(const float* xb, const uint16_t* cb, uint32_t len,
-                                                 int lane, bool vec) {
+                                                 uint32_t head, int lane) {
   double acc = 0;
-  const uint32_t nunit = vec ? len / kMixUnit : 0;
-  const uint4* xv = (const uint4*)xb;
-  const uint2* cv = (const uint2*)cb;
+  const uint32_t nunit = (len - head) / kMixUnit;
+  const uint32_t tail0 = head + nunit * kMixUnit;
+  const uint4* xv = (const uint4*)(xb + head);
+  const uint2* cv = (const uint2*)(cb + head);
   for (uint32_t u0 = 0; u0 < nunit; u0 += G * kMixU) {
     uint4 a[kMixU];
     uint2 b[kMixU];
@@ -43,7 +56,10 @@ __device__ __forceinline__ double mixed_distance(const float* xb, const uint16_t
     for (int u = 0; u < kMixU; ++u) part += sqdiff_unit(a[u], b[u]);
     acc += (double)part;
   }
-  for (uint32_t j = nunit * kMixUnit + lane; j < len; j += G) acc += (double)sq(xb[j] - widen_elem(cb, j));
+  for (uint32_t e = lane; e < len - nunit * kMixUnit; e += G) {
+    const uint32_t j = e < head ? e : tail0 + (e - head);
+    acc += (double)sq(xb[j] - widen_elem(cb, j));
+  }
   return acc;
 }
 
@@ -68,7 +84,8 @@ __global__ __launch_bounds__(kWG) void k_mixed_scores(const float* __restrict__ 
       if (b >= n_blocks) continue;
     }
     const BlockSpan sp = block_span(b, n_elems, block_len, 1);  // byte_off = element offset
-    double acc = mixed_distance<G>(x + sp.byte_off, c + sp.byte_off, sp.len, lane, vec);
+    double acc = mixed_distance<G>(x + sp.byte_off, c + sp.byte_off, sp.len,
+                                   mixed_head(sp.byte_off, sp.len, vec), lane);
     if constexpr (G == 256)
       acc = workgroup_sum(acc, slots);
     else
@@ -199,19 +216,41 @@ __global__ __launch_bounds__(kWG) void k_mixed_commit(const float* __restrict__ 
       const float* xb = x + off;
       uint16_t* cb = c + off;
       uint16_t* sb = staging ? staging + i * (uint64_t)block_len + first : nullptr;
-      const uint32_t nunit = vec ? len / kMixUnit : 0;
-      for (uint32_t u = lane; u < nunit; u += G) {
-        const uint2 r = round_unit(load_stream((const uint4*)xb + u));
-        store_stream2((uint2*)cb + u, r);
-        if (sb && vec_staging) store_stream2((uint2*)sb + u, r);
-      }
-      for (uint32_t j = nunit * kMixUnit + lane; j < len; j += G) {
+      const uint32_t head = mixed_head(off, len, vec);
+      const uint32_t nunit = (len - head) / kMixUnit, tail0 = head + nunit * kMixUnit;
+      // the few elements around the whole units are asked for together with the first units when
+      // the group has a lane for each of them; a row walked element by element loops instead
+      const bool ends_in_lanes = G >= kMixUnit && head < (uint32_t)kMixUnit;
+      const bool has_head = ends_in_lanes && (uint32_t)lane < head, has_tail = ends_in_lanes && tail0 + lane < len;
+      uint32_t hx = 0, tx = 0;
+      if (has_head) hx = __float_as_uint(xb[lane]);
+      if (has_tail) tx = __float_as_uint(xb[tail0 + lane]);
+      auto element = [&](uint32_t j) {
         const uint16_t r = (uint16_t)round_bf16(__float_as_uint(xb[j]));
         cb[j] = r;
         if (sb) sb[j] = r;
+      };
+      if (!ends_in_lanes)
+        for (uint32_t j = lane; j < head; j += G) element(j);
+      for (uint32_t u = lane; u < nunit; u += G) {
+        const uint2 r = round_unit(load_stream((const uint4*)(xb + head) + u));
+        store_stream2((uint2*)(cb + head) + u, r);
+        if (sb && vec_staging) store_stream2((uint2*)(sb + head) + u, r);
       }
-      if (sb && !vec_staging)
-        for (uint32_t j = lane; j < nunit * kMixUnit; j += G) sb[j] = (uint16_t)round_bf16(__float_as_uint(xb[j]));
+      if (has_head) {
+        const uint16_t r = (uint16_t)round_bf16(hx);
+        cb[lane] = r;
+        if (sb) sb[lane] = r;
+      }
+      if (has_tail) {
+        const uint16_t r = (uint16_t)round_bf16(tx);
+        cb[tail0 + lane] = r;
+        if (sb) sb[tail0 + lane] = r;
+      }
+      if (!ends_in_lanes)
+        for (uint32_t j = tail0 + lane; j < len; j += G) element(j);
+      if (sb && !vec_staging)  // staging rows that do not share the phase of c's rows
+        for (uint32_t j = head + lane; j < tail0; j += G) sb[j] = (uint16_t)round_bf16(__float_as_uint(xb[j]));
     }
   }
 }
@@ -240,17 +279,39 @@ __global__ __launch_bounds__(T) void k_mixed_recover(float* __restrict__ x, cons
         continue;
       float* xb = x + off;
       const uint16_t* cb = packed ? c + i * (uint64_t)block_len + first : c + off;
-      const uint32_t nunit = vec ? len / kMixUnit : 0;
-      for (uint32_t u = lane; u < nunit; u += G) {
-        const uint2 cv = load_stream2((const uint2*)cb + u);
-        if (NORM) acc += (double)sqdiff_unit(load_stream((const uint4*)xb + u), cv);
-        if (STORE) store_stream((uint4*)xb + u, widen_unit(cv));
+      const uint32_t head = mixed_head(off, len, vec);
+      const uint32_t nunit = (len - head) / kMixUnit, tail0 = head + nunit * kMixUnit;
+      const bool ends_in_lanes = G >= kMixUnit && head < (uint32_t)kMixUnit;  // as in k_mixed_commit
+      const bool has_head = ends_in_lanes && (uint32_t)lane < head, has_tail = ends_in_lanes && tail0 + lane < len;
+      float hc = 0, hx = 0, tc = 0, tx = 0;
+      if (has_head) {
+        hc = widen_elem(cb, lane);
+        if (NORM) hx = xb[lane];
       }
-      for (uint32_t j = nunit * kMixUnit + lane; j < len; j += G) {
+      if (has_tail) {
+        tc = widen_elem(cb, tail0 + lane);
+        if (NORM) tx = xb[tail0 + lane];
+      }
+      auto element = [&](uint32_t j) {
         const float w = widen_elem(cb, j);
         if (NORM) acc += (double)sq(xb[j] - w);
         if (STORE) xb[j] = w;
+      };
+      if (!ends_in_lanes)
+        for (uint32_t j = lane; j < head; j += G) element(j);
+      if (NORM && has_head) acc += (double)sq(hx - hc);
+      for (uint32_t u = lane; u < nunit; u += G) {
+        const uint2 cv = load_stream2((const uint2*)(cb + head) + u);
+        if (NORM) acc += (double)sqdiff_unit(load_stream((const uint4*)(xb + head) + u), cv);
+        if (STORE) store_stream((uint4*)(xb + head) + u, widen_unit(cv));
       }
+      if (NORM && has_tail) acc += (double)sq(tx - tc);
+      if (STORE) {
+        if (has_head) xb[lane] = hc;
+        if (has_tail) xb[tail0 + lane] = tc;
+      }
+      if (!ends_in_lanes)
+        for (uint32_t j = tail0 + lane; j < len; j += G) element(j);
     }
   }
   if (NORM) {
@@ -272,8 +333,18 @@ __global__ __launch_bounds__(T) void k_mixed_recover(float* __restrict__ x, cons
     default: CALL(256); break;   \
   }
 
-static bool mixed_vec(const scar_layout* l, const void* x, const void* c) {
-  return aligned(x, 16) && aligned(c, 8) && l->block_len % kMixUnit == 0;
+// Both streams can be walked in whole units (mixed_head): x on a 16-byte, c on an 8-byte boundary.
+static bool mixed_vec(const void* x, const void* c) { return aligned(x, 16) && aligned(c, 8); }
+
+// Rows of whole units: packed rows (staging, rows read back) then share the phase of the store's rows.
+static bool unit_rows(const scar_layout* l) { return l->block_len % kMixUnit == 0; }
+
+// Lanes per row of the copy kernels: one per unit, and at least 4 for rows that are not whole
+// units, so that the elements around the units each find a lane.
+static int mixed_copy_group(const scar_layout* l, bool vec) {
+  if (!vec) return pick_group_units(l->block_len, 1, true);
+  const int g = pick_group_units((l->block_len + kMixUnit - 1) / kMixUnit, 1, true);
+  return (!unit_rows(l) && g < kMixUnit) ? kMixUnit : g;
 }
 
 // Pieces per row for the copy kernels (1 unless the store is aligned and rows exceed a piece).
@@ -285,7 +356,9 @@ int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, c
                        const uint32_t* idx, uint32_t n_idx, void* scores, hipStream_t st) {
   if (!x || !c || !scores || !aligned(x, 4) || !aligned(c, 2) || !aligned(scores, 4))
     return SCAR_ERR_INVALID_ARG;
-  const bool vec = mixed_vec(l, x, c);
+  // Rows that are not whole units are walked in units too once they are too long for the scan
+  // over runs of whole rows below, whose sums follow the element-wise walk
+  const bool vec = mixed_vec(x, c) && (unit_rows(l) || l->block_len > kMixFlatSplitRowElems);
   // loads in flight: one 16-byte step of x and 8 bytes of c per unit (element-wise: 4 + 2)
   const uint64_t units = vec ? l->block_len / kMixUnit : l->block_len;
   const int g = pick_group_units(units, vec ? kMixU : 4, false);
@@ -359,10 +432,10 @@ int mixed_commit(const scar_layout* l, uint32_t n_blocks, const void* x, void* c
   if (!x || !c || !idx || !aligned(x, 4) || !aligned(c, 2) || !aligned(idx, 4) ||
       (staging && !aligned(staging, 2)))
     return SCAR_ERR_INVALID_ARG;
-  const bool vec = mixed_vec(l, x, c);
-  const bool vec_st = vec && staging && aligned(staging, 8);
+  const bool vec = mixed_vec(x, c);
+  const bool vec_st = vec && unit_rows(l) && staging && aligned(staging, 8);
   const uint32_t pieces = mixed_pieces(l, vec);
-  const int g = pieces > 1 ? 256 : pick_group_units(vec ? l->block_len / kMixUnit : l->block_len, 1, true);
+  const int g = pieces > 1 ? 256 : mixed_copy_group(l, vec);
 #define CALL(G)                                                                                     \
   {                                                                                                 \
     constexpr int GPW = (G == 256) ? 1 : kWG / G;                                                   \
@@ -441,9 +514,9 @@ int mixed_recover_or_norm(bool store, bool packed, const scar_layout* l, uint32_
                           const uint32_t* idx, uint32_t n_idx, scar_norm* norm_out, void* partial,
                           hipStream_t st) {
   if (!aligned(x, 4) || !aligned(c, 2)) return SCAR_ERR_INVALID_ARG;
-  const bool vec = mixed_vec(l, x, c);
+  const bool vec = mixed_vec(x, c) && (!packed || unit_rows(l));  // c = packed rows: their own phase
   const uint32_t pieces = mixed_pieces(l, vec);
-  const int g = pieces > 1 ? 256 : pick_group_units(vec ? l->block_len / kMixUnit : l->block_len, 1, true);
+  const int g = pieces > 1 ? 256 : mixed_copy_group(l, vec);
   uint32_t n_partial = 0;
   if (!store && norm_out && !idx && !packed && aligned(x, 16) && aligned(c, 8)) {  // the whole store
     const uint64_t chunks = (l->n_elems / kMixUnit + kWG * kMixU - 1) / (kWG * kMixU);

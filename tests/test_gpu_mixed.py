@@ -26,7 +26,7 @@ def scores_match(got, want):
     np.testing.assert_allclose(got.cpu().numpy().astype(np.float64), want, rtol=REL_TOL, atol=0)
 
 
-@pytest.mark.parametrize("L", [1, 8, 24, 100, 784, 1024, 4096, 5000, 70000])
+@pytest.mark.parametrize("L", [1, 5, 8, 24, 100, 101, 257, 784, 1001, 1024, 4001, 4096, 5000, 70000, 70001])
 @pytest.mark.parametrize("unaligned", [False, True])
 def test_mixed_calls(L, unaligned):
     n = min(max(L * 37 + L // 3, 4099), 3_000_000)
@@ -120,7 +120,7 @@ def test_mixed_recover_over_long_index_lists(L, nb):
 
 
 @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16, wl.I32, MIX])
-@pytest.mark.parametrize("L", [24, 5000, 70000])
+@pytest.mark.parametrize("L", [24, 37, 4001, 5000, 70000])
 def test_recover_from_packed_rows_of_any_length(dtype, L):
     # rows read back from storage (Section 4.3, recovery step 2): row i of `rows` is block
     # lost[i]; long rows are walked in pieces, the last block of the store is short
@@ -193,7 +193,7 @@ def test_mixed_random_layouts(seed):
         np.testing.assert_array_equal(to_host(x.contiguous()), hx)
 
 
-@pytest.mark.parametrize("L,nb", [(1, 5000), (24, 3000), (100, 9000), (1024, 700), (5000, 60)])
+@pytest.mark.parametrize("L,nb", [(1, 5000), (24, 3000), (100, 9000), (257, 5000), (1001, 300), (1024, 700), (4001, 70), (5000, 60)])
 def test_mixed_scores_of_listed_blocks(L, nb):
     # scores[b] for b in idx equal the full scan's bit for bit, the other entries stay; the
     # list is unsorted, holds the short last block and two entries out of range (skipped)
