@@ -911,3 +911,52 @@ def test_block_scores_of_very_many_short_rows(dtype, L, nb):
         oracle.set_num_threads(1)
     s = scar.block_scores(to_dev(x, dtype), to_dev(c, dtype), L)
     assert_scores_match(s, want, dtype)
+
+
+def test_two_streams_run_their_cycles_side_by_side():
+    # two stores, each with its own workspace, go through three cycles on two streams with no
+    # wait between them, so kernels of the two interleave on the device (the ordered write of
+    # the selection included, whose workgroups wait for lower-numbered tiles of their own
+    # launch only); every result must equal the one the same calls give one after the other
+    specs = [(F32, 256, (1 << 25) - 77, 0.10), (I32, 1000, 40_000 * 1000, 0.05)]
+    stores = []
+    for dtype, L, n, frac in specs:
+        hx, hc = make_store(dtype, n, seed=700 + L)
+        if dtype == I32:          # few distinct scores: the selection is decided by its tie rule
+            hx = (hc + (np.arange(n) % 997 == 0)).astype(np.int32)
+        nb = oracle.n_blocks_of(n, L)
+        lost = [idx_dev(wl.random_lost_blocks(nb, nb // 8, 900 + cyc)) for cyc in range(3)]
+        stores.append(dict(dtype=dtype, L=L, nb=nb, k=wl.k_of_fraction(frac, nb), lost=lost,
+                           x0=to_dev(hx, dtype), c0=to_dev(hc, dtype)))
+
+    def run(st, x, c, out):
+        ws = st["ws"]
+        for cyc in range(3):
+            s = scar.block_scores(x, c, st["L"])
+            idx = scar.select_topk(s, st["k"], ws)
+            scar.checkpoint_commit(x, c, st["L"], idx)
+            norm = scar.partial_recover(x, c, st["L"], st["lost"][cyc], ws)
+            out.append((s, idx, norm))
+
+    serial = []
+    for st in stores:                                  # one after the other on the current stream
+        st["ws"] = scar.new_workspace(st["nb"], DEV)
+        x, c, out = st["x0"].clone(), st["c0"].clone(), []
+        run(st, x, c, out)
+        torch.cuda.synchronize()
+        serial.append((x, c, out))
+
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    side = []
+    for st in stores:
+        side.append((st["x0"].clone(), st["c0"].clone(), []))
+    torch.cuda.synchronize()
+    for st, sm, (x, c, out) in zip(stores, streams, side):
+        print("stream for dtype=%d L=%d blocks=%d" % (st["dtype"], st["L"], st["nb"]), flush=True)
+        with torch.cuda.stream(sm):                    # enqueued without waiting for the other
+            run(st, x, c, out)
+    torch.cuda.synchronize()
+    for (x1, c1, o1), (x2, c2, o2) in zip(serial, side):
+        assert torch.equal(x1, x2) and torch.equal(c1, c2)
+        for (s1, i1, n1), (s2, i2, n2) in zip(o1, o2):
+            assert torch.equal(s1, s2) and torch.equal(i1, i2) and torch.equal(n1, n2)
