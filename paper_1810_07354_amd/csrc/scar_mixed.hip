@@ -16,14 +16,19 @@
 
 namespace scar {
 
-// Elements of a row before its first whole unit.  With x on a 16-byte and c on an 8-byte
-// boundary, element e of the store starts a unit of both streams exactly when e is a multiple
-// of 4, so a row that starts at element `off` has (-off) mod 4 leading elements, whatever its
-// length.  Rows of a store that is not aligned like that are walked element by element: all
-// of the row is "head".
-__device__ __forceinline__ uint32_t mixed_head(uint64_t off, uint32_t len, bool vec) {
-  if (!vec) return len;
-  const uint32_t head = (uint32_t)(0 - off) & (kMixUnit - 1);
+// Elements of a row before its first whole unit (4 elements: 16 bytes of x on a 16-byte
+// boundary, 8 bytes of c on an 8-byte boundary).  Both streams reach such boundaries at the same
+// elements exactly when the two row addresses have the same phase, counted in elements modulo
+// 4; then the row is walked in units between (-phase) mod 4 leading and a few trailing
+// elements, whatever its length.  Rows whose phases differ (views that start at unrelated
+// offsets, packed rows of a length that is no multiple of 4) are walked element by element: all
+// of the row is "head".  Decided per row from the addresses, so every kernel splits a given row
+// in the same way.
+__device__ __forceinline__ uint32_t mixed_head(const float* xb, const uint16_t* cb, uint32_t len) {
+  const uint32_t px = (uint32_t)((uintptr_t)xb >> 2) & (kMixUnit - 1);
+  const uint32_t pc = (uint32_t)((uintptr_t)cb >> 1) & (kMixUnit - 1);
+  if (px != pc) return len;
+  const uint32_t head = (0u - px) & (kMixUnit - 1);
   return head < len ? head : len;
 }
 
@@ -69,7 +74,7 @@ template <int G, bool LISTED>
 __global__ __launch_bounds__(kWG) void k_mixed_scores(const float* __restrict__ x,
                                                       const uint16_t* __restrict__ c,
                                                       float* __restrict__ scores, uint64_t n_elems,
-                                                      uint32_t block_len, uint32_t n_blocks, bool vec,
+                                                      uint32_t block_len, uint32_t n_blocks,
                                                       const uint32_t* __restrict__ idx, uint32_t n_idx) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
@@ -84,8 +89,9 @@ __global__ __launch_bounds__(kWG) void k_mixed_scores(const float* __restrict__ 
       if (b >= n_blocks) continue;
     }
     const BlockSpan sp = block_span(b, n_elems, block_len, 1);  // byte_off = element offset
-    double acc = mixed_distance<G>(x + sp.byte_off, c + sp.byte_off, sp.len,
-                                   mixed_head(sp.byte_off, sp.len, vec), lane);
+    const float* xb = x + sp.byte_off;
+    const uint16_t* cb = c + sp.byte_off;
+    double acc = mixed_distance<G>(xb, cb, sp.len, mixed_head(xb, cb, sp.len), lane);
     if constexpr (G == 256)
       acc = workgroup_sum(acc, slots);
     else
@@ -97,15 +103,16 @@ __global__ __launch_bounds__(kWG) void k_mixed_scores(const float* __restrict__ 
 // Many short rows of an aligned store, read as runs of whole rows (the reduced-precision twin
 // of k_block_scores_flat): a workgroup loads a chunk of `chunk_rows` whole rows - at most
 // kMixFlatUnits units per stream, every lane kMixU of them, fully coalesced - and leaves in LDS
-// one partial sum per unit or, SPLIT (rows that are not whole units, which k_mixed_scores walks
-// element by element), one term per element.  The groups then add each row's values in the
-// order in which mixed_distance adds them from memory, so the scores are bit for bit those of
+// one partial sum per unit and, SPLIT (rows that are not whole units: a row then starts inside
+// a unit and has leading and trailing elements of its own), one term per element as well.  The
+// groups then add each row's values in the order in which mixed_distance adds them from memory
+// (units, then the elements around them), so the scores are bit for bit those of
 // k_mixed_scores, which still serves listed blocks and a short last block of the store.
 // Chunks start on 16-byte boundaries of x (8-byte boundaries of c); the host sizes chunk_rows
 // for that.
 constexpr uint32_t kMixFlatUnits = kWG * kMixU;
 constexpr uint32_t kMixFlatRowElems = 128;       // longest row of whole units taken (512 bytes of x)
-constexpr uint32_t kMixFlatSplitRowElems = 256;  // longest row that is not (G <= 64 element-wise)
+constexpr uint32_t kMixFlatSplitRowElems = 256;  // longest row that is not
 constexpr uint32_t kMixFlatMinRows = 4096;
 
 template <int G, bool SPLIT>
@@ -115,7 +122,8 @@ __global__ __launch_bounds__(kWG) void k_mixed_scores_flat(const float* __restri
                                                            uint32_t n_rows, uint32_t chunk_rows,
                                                            uint32_t n_chunks) {
   constexpr int GPW = kWG / G;
-  __shared__ __align__(16) float vals[SPLIT ? kMixFlatUnits * kMixUnit : kMixFlatUnits];
+  __shared__ float unit_sums[kMixFlatUnits];
+  __shared__ __align__(16) float terms[SPLIT ? kMixFlatUnits * kMixUnit : 1];
   const int lane = threadIdx.x & (G - 1);
   const uint32_t grp = threadIdx.x / G;
   for (uint32_t chunk = xcd_contiguous_block_id(); chunk < n_chunks; chunk += gridDim.x) {
@@ -139,42 +147,44 @@ __global__ __launch_bounds__(kWG) void k_mixed_scores_flat(const float* __restri
     for (int u = 0; u < kMixU; ++u) {
       const uint32_t i = u * kWG + threadIdx.x;
       if (i >= nunit) continue;
+      unit_sums[i] = sqdiff_unit(a[u], b[u]);
       if constexpr (SPLIT) {
         float4 t;  // the terms of the element-wise walk
         t.x = sq(__uint_as_float(a[u].x) - widen_lo(b[u].x));
         t.y = sq(__uint_as_float(a[u].y) - widen_hi(b[u].x));
         t.z = sq(__uint_as_float(a[u].z) - widen_lo(b[u].y));
         t.w = sq(__uint_as_float(a[u].w) - widen_hi(b[u].y));
-        ((float4*)vals)[i] = t;
-      } else {
-        vals[i] = sqdiff_unit(a[u], b[u]);
+        ((float4*)terms)[i] = t;
       }
     }
     if constexpr (SPLIT)  // the elements after the last whole unit (last chunk only)
-      for (uint32_t j = nunit * kMixUnit + threadIdx.x; j < n_el; j += kWG) vals[j] = sq(xc[j] - widen_elem(cc, j));
+      for (uint32_t j = nunit * kMixUnit + threadIdx.x; j < n_el; j += kWG) terms[j] = sq(xc[j] - widen_elem(cc, j));
     __syncthreads();
     for (uint32_t r = grp; r < rows; r += GPW) {
       double acc = 0;
-      if constexpr (SPLIT) {
-        const float* p = vals + r * block_len;
-        for (uint32_t j = lane; j < block_len; j += G) acc += (double)p[j];
-      } else {
-        const uint32_t row_units = block_len / kMixUnit;
-        const float* p = vals + r * row_units;
-        for (uint32_t u0 = 0; u0 < row_units; u0 += G * kMixU) {  // the order of mixed_distance
-          float part = 0.f;
+      // the row's own split, as mixed_head makes it: chunks start on whole units
+      const uint32_t e_lo = r * block_len;
+      uint32_t head = SPLIT ? (uint32_t)(0 - e_lo) & (kMixUnit - 1) : 0;
+      if (head > block_len) head = block_len;
+      const uint32_t row_units = (block_len - head) / kMixUnit, tail0 = head + row_units * kMixUnit;
+      const float* p = unit_sums + (e_lo + head) / kMixUnit;
+      for (uint32_t u0 = 0; u0 < row_units; u0 += G * kMixU) {  // the order of mixed_distance
+        float part = 0.f;
 #pragma unroll
-          for (int u = 0; u < kMixU; ++u) {
-            const uint32_t i = u0 + u * G + lane;
-            part += i < row_units ? p[i] : 0.f;
-          }
-          acc += (double)part;
+        for (int u = 0; u < kMixU; ++u) {
+          const uint32_t i = u0 + u * G + lane;
+          part += i < row_units ? p[i] : 0.f;
         }
+        acc += (double)part;
+      }
+      if constexpr (SPLIT) {
+        for (uint32_t e = lane; e < block_len - row_units * kMixUnit; e += G)
+          acc += (double)terms[e_lo + (e < head ? e : tail0 + (e - head))];
       }
       acc = group_sum<G>(acc);
       if (lane == 0) scores[row0 + r] = (float)acc;
     }
-    __syncthreads();  // the next chunk overwrites vals
+    __syncthreads();  // the next chunk overwrites the sums and terms
   }
 }
 
@@ -201,8 +211,7 @@ template <int G>
 __global__ __launch_bounds__(kWG) void k_mixed_commit(const float* __restrict__ x, uint16_t* __restrict__ c,
                                                       const uint32_t* __restrict__ idx, uint32_t n_idx,
                                                       uint16_t* __restrict__ staging, uint64_t n_elems,
-                                                      uint32_t block_len, uint32_t n_blocks, uint32_t pieces,
-                                                      bool vec, bool vec_staging) {
+                                                      uint32_t block_len, uint32_t n_blocks, uint32_t pieces) {
   constexpr int GPW = (G == 256) ? 1 : kWG / G;
   const int lane = (G == 256) ? threadIdx.x : (threadIdx.x & (G - 1));
   const uint32_t grp = (G == 256) ? 0 : threadIdx.x / G;
@@ -216,7 +225,9 @@ __global__ __launch_bounds__(kWG) void k_mixed_commit(const float* __restrict__ 
       const float* xb = x + off;
       uint16_t* cb = c + off;
       uint16_t* sb = staging ? staging + i * (uint64_t)block_len + first : nullptr;
-      const uint32_t head = mixed_head(off, len, vec);
+      const uint32_t head = mixed_head(xb, cb, len);
+      // the staging row takes whole units too if it has the phase of c's row
+      const bool vec_staging = sb && (((uintptr_t)sb ^ (uintptr_t)cb) & 7) == 0;
       const uint32_t nunit = (len - head) / kMixUnit, tail0 = head + nunit * kMixUnit;
       // the few elements around the whole units are asked for together with the first units when
       // the group has a lane for each of them; a row walked element by element loops instead
@@ -249,7 +260,7 @@ __global__ __launch_bounds__(kWG) void k_mixed_commit(const float* __restrict__ 
       }
       if (!ends_in_lanes)
         for (uint32_t j = tail0 + lane; j < len; j += G) element(j);
-      if (sb && !vec_staging)  // staging rows that do not share the phase of c's rows
+      if (sb && !vec_staging)
         for (uint32_t j = head + lane; j < tail0; j += G) sb[j] = (uint16_t)round_bf16(__float_as_uint(xb[j]));
     }
   }
@@ -261,7 +272,7 @@ template <int G, int T, bool STORE, bool NORM>
 __global__ __launch_bounds__(T) void k_mixed_recover(float* __restrict__ x, const uint16_t* __restrict__ c,
                                                      const uint32_t* __restrict__ idx, uint32_t n_idx,
                                                      uint64_t n_elems, uint32_t block_len,
-                                                     uint32_t n_blocks, uint32_t pieces, bool vec, bool packed,
+                                                     uint32_t n_blocks, uint32_t pieces, bool packed,
                                                      double* __restrict__ partial) {
   constexpr int GPW = T / G;
   const int lane = threadIdx.x & (G - 1);
@@ -279,7 +290,7 @@ __global__ __launch_bounds__(T) void k_mixed_recover(float* __restrict__ x, cons
         continue;
       float* xb = x + off;
       const uint16_t* cb = packed ? c + i * (uint64_t)block_len + first : c + off;
-      const uint32_t head = mixed_head(off, len, vec);
+      const uint32_t head = mixed_head(xb, cb, len);
       const uint32_t nunit = (len - head) / kMixUnit, tail0 = head + nunit * kMixUnit;
       const bool ends_in_lanes = G >= kMixUnit && head < (uint32_t)kMixUnit;  // as in k_mixed_commit
       const bool has_head = ends_in_lanes && (uint32_t)lane < head, has_tail = ends_in_lanes && tail0 + lane < len;
@@ -333,8 +344,11 @@ __global__ __launch_bounds__(T) void k_mixed_recover(float* __restrict__ x, cons
     default: CALL(256); break;   \
   }
 
-// Both streams can be walked in whole units (mixed_head): x on a 16-byte, c on an 8-byte boundary.
-static bool mixed_vec(const void* x, const void* c) { return aligned(x, 16) && aligned(c, 8); }
+// x and c start at the same phase (mixed_head), so the rows of the store are walked in whole
+// units: what the launches are sized for.  The kernels decide row by row.
+static bool mixed_vec(const void* x, const void* c) {
+  return ((reinterpret_cast<uintptr_t>(x) >> 2) & (kMixUnit - 1)) == ((reinterpret_cast<uintptr_t>(c) >> 1) & (kMixUnit - 1));
+}
 
 // Rows of whole units: packed rows (staging, rows read back) then share the phase of the store's rows.
 static bool unit_rows(const scar_layout* l) { return l->block_len % kMixUnit == 0; }
@@ -347,7 +361,7 @@ static int mixed_copy_group(const scar_layout* l, bool vec) {
   return (!unit_rows(l) && g < kMixUnit) ? kMixUnit : g;
 }
 
-// Pieces per row for the copy kernels (1 unless the store is aligned and rows exceed a piece).
+// Pieces per row for the copy kernels (1 unless the rows are walked in units and exceed a piece).
 static uint32_t mixed_pieces(const scar_layout* l, bool vec) {
   return (vec && l->block_len > kMixPieceElems) ? (l->block_len + kMixPieceElems - 1) / kMixPieceElems : 1;
 }
@@ -356,15 +370,13 @@ int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, c
                        const uint32_t* idx, uint32_t n_idx, void* scores, hipStream_t st) {
   if (!x || !c || !scores || !aligned(x, 4) || !aligned(c, 2) || !aligned(scores, 4))
     return SCAR_ERR_INVALID_ARG;
-  // Rows that are not whole units are walked in units too once they are too long for the scan
-  // over runs of whole rows below, whose sums follow the element-wise walk
-  const bool vec = mixed_vec(x, c) && (unit_rows(l) || l->block_len > kMixFlatSplitRowElems);
+  const bool vec = mixed_vec(x, c);
   // loads in flight: one 16-byte step of x and 8 bytes of c per unit (element-wise: 4 + 2)
-  const uint64_t units = vec ? l->block_len / kMixUnit : l->block_len;
+  const uint64_t units = vec ? (l->block_len + kMixUnit - 1) / kMixUnit : l->block_len;
   const int g = pick_group_units(units, vec ? kMixU : 4, false);
   // many short rows of an aligned store: read as runs of whole rows, added up in the order of
   // the group walk with the same g
-  const bool split = l->block_len % kMixUnit != 0;
+  const bool split = !unit_rows(l);
   if (!idx && aligned(x, 16) && aligned(c, 8) && n_blocks >= kMixFlatMinRows && g <= 64 &&
       l->block_len <= (split ? kMixFlatSplitRowElems : kMixFlatRowElems) &&
       run_chunk_rows((uint64_t)l->block_len * 4, kMixFlatUnits) > 0) {
@@ -373,7 +385,7 @@ int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, c
     const uint32_t n_chunks = (n_rows + chunk_rows - 1) / chunk_rows;
     const uint32_t grid = xcd_grid(n_chunks, kScoreGridCap);
     // four workgroups per compute unit: 40 KiB of LDS each, part of it unused
-    const size_t used = (split ? kMixFlatUnits * kMixUnit : kMixFlatUnits) * sizeof(float) + 256;
+    const size_t used = (split ? kMixFlatUnits * (kMixUnit + 1) : kMixFlatUnits) * sizeof(float) + 256;
     const size_t lds = 40 * 1024 - used;
 #define FLAT(G)                                                                                        \
   case G:                                                                                              \
@@ -407,11 +419,11 @@ int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, c
     if (idx)                                                                                         \
       launch((k_mixed_scores<G, true>), dim3(grid), dim3(kWG), lds, st, (const float*)x, \
                          (const uint16_t*)c, (float*)scores, l->n_elems, l->block_len, n_blocks,     \
-                         vec, idx, n_idx);                                                           \
+                         idx, n_idx);                                                                \
     else                                                                                             \
       launch((k_mixed_scores<G, false>), dim3(grid), dim3(kWG), lds, st,                 \
                          (const float*)x, (const uint16_t*)c, (float*)scores, l->n_elems,            \
-                         l->block_len, n_blocks, vec, idx, n_idx);                                   \
+                         l->block_len, n_blocks, idx, n_idx);                                        \
   }
   switch (g) {  // the score kernel reduces inside a wavefront or a whole workgroup
     case 1: CALL(1) break;
@@ -433,7 +445,6 @@ int mixed_commit(const scar_layout* l, uint32_t n_blocks, const void* x, void* c
       (staging && !aligned(staging, 2)))
     return SCAR_ERR_INVALID_ARG;
   const bool vec = mixed_vec(x, c);
-  const bool vec_st = vec && unit_rows(l) && staging && aligned(staging, 8);
   const uint32_t pieces = mixed_pieces(l, vec);
   const int g = pieces > 1 ? 256 : mixed_copy_group(l, vec);
 #define CALL(G)                                                                                     \
@@ -442,7 +453,7 @@ int mixed_commit(const scar_layout* l, uint32_t n_blocks, const void* x, void* c
     const RowGrid rg = row_grid(((uint64_t)n_idx + GPW - 1) / GPW, pieces, kCopyGridCap);           \
     launch((k_mixed_commit<G>), dim3(rg.x, rg.y),                                                   \
                        dim3(kWG), 0, st, (const float*)x, (uint16_t*)c, idx, n_idx,                 \
-                       (uint16_t*)staging, l->n_elems, l->block_len, n_blocks, pieces, vec, vec_st); \
+                       (uint16_t*)staging, l->n_elems, l->block_len, n_blocks, pieces);             \
   }
   SCAR_FOR_GROUP(g, CALL)
 #undef CALL
@@ -452,7 +463,7 @@ int mixed_commit(const scar_layout* l, uint32_t n_blocks, const void* x, void* c
 template <bool STORE, bool NORM>
 static uint32_t launch_mixed_recover(int g, const scar_layout* l, uint32_t n_blocks, void* x,
                                      const void* c, const uint32_t* idx, uint32_t n_idx, uint32_t pieces,
-                                     bool vec, bool packed, void* partial, hipStream_t st) {
+                                     bool packed, void* partial, hipStream_t st) {
   uint32_t grid = 0, grid_y = 1;
   constexpr int kWide = 1024;
 #define LAUNCH(G, T)                                                                                  \
@@ -461,7 +472,7 @@ static uint32_t launch_mixed_recover(int g, const scar_layout* l, uint32_t n_blo
     grid = rg.x, grid_y = rg.y;                                                                       \
     launch((k_mixed_recover<G, T, STORE, NORM>), dim3(grid, grid_y), dim3(T), 0, st,      \
                        (float*)x, (const uint16_t*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, \
-                       pieces, vec, packed, (double*)partial);                                        \
+                       pieces, packed, (double*)partial);                                             \
   }
 #define CALL(G)                                                       \
   if (n_idx >= 64 && ((uint64_t)n_idx * pieces * G + kWG - 1) / kWG >= 8192) \
@@ -527,11 +538,11 @@ int mixed_recover_or_norm(bool store, bool packed, const scar_layout* l, uint32_
     return launch_status();
   }
   if (store && norm_out)
-    n_partial = launch_mixed_recover<true, true>(g, l, n_blocks, x, c, idx, n_idx, pieces, vec, packed, partial, st);
+    n_partial = launch_mixed_recover<true, true>(g, l, n_blocks, x, c, idx, n_idx, pieces, packed, partial, st);
   else if (store)
-    launch_mixed_recover<true, false>(g, l, n_blocks, x, c, idx, n_idx, pieces, vec, packed, nullptr, st);
+    launch_mixed_recover<true, false>(g, l, n_blocks, x, c, idx, n_idx, pieces, packed, nullptr, st);
   else
-    n_partial = launch_mixed_recover<false, true>(g, l, n_blocks, x, c, idx, n_idx, pieces, vec, packed, partial, st);
+    n_partial = launch_mixed_recover<false, true>(g, l, n_blocks, x, c, idx, n_idx, pieces, packed, partial, st);
   if (norm_out) launch_finish(l->dtype, partial, n_partial, norm_out, st);
   return launch_status();
 }
