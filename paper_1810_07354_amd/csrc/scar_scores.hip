@@ -489,6 +489,36 @@ __global__ __launch_bounds__(kGiantFinishThreads) void k_giant_finish(
   }
 }
 
+// The same sums for blocks of few pieces (up to kGiantWavePieces): a wavefront per block instead
+// of a workgroup of 1,024 threads, which 16,384 blocks of four pieces each would keep busy for
+// longer than the scan of their data.  Which of the two kernels adds a block's pieces depends on
+// the layout alone, so listed and full scans still agree bit for bit.
+constexpr uint32_t kGiantWavePieces = 512;
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_giant_finish_wave(
+    const typename Acc<DT>::type* __restrict__ partial, uint32_t ppb, uint32_t n_blocks,
+    const uint32_t* __restrict__ idx, uint32_t first_entry, uint32_t n_entries,
+    const float* __restrict__ weights, void* __restrict__ scores) {
+  using acc_t = typename Acc<DT>::type;
+  const uint32_t e = blockIdx.x * (kWG / kWave) + threadIdx.x / kWave;
+  if (e >= n_entries) return;
+  const uint64_t b = idx ? idx[first_entry + e] : first_entry + e;
+  if (b >= n_blocks) return;
+  const acc_t* mine = partial + (uint64_t)e * ppb;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  acc_t acc = 0;
+  for (uint32_t p = lane; p < ppb; p += kWave) acc += mine[p];
+  acc = group_sum<kWave>(acc);
+  if (lane == 0) {
+    if constexpr (DT == DT_I32)
+      ((long long*)scores)[b] = (long long)acc;
+    else if constexpr (is_tv(DT))
+      ((float*)scores)[b] = (float)(0.5 * acc * (double)(weights ? weights[b] : 1.f));
+    else
+      ((float*)scores)[b] = (float)acc;
+  }
+}
+
 // True if the layout is scored by pieces; ppb / piece_elems receive the cut.
 static bool giant_geometry(const scar_layout* l, int eb, uint32_t n_blocks, uint32_t* ppb, uint32_t* piece_elems) {
   const uint64_t row_bytes = (uint64_t)l->block_len * eb;
@@ -525,8 +555,12 @@ static int launch_giant(const scar_layout* l, const void* x, const void* c, void
     else
       launch((k_giant_pieces<DT, false>), dim3(grid), dim3(kWG), lds, st, (const char*)x, (const char*)c,
              l->n_elems, l->block_len, n_blocks, ppb, piece_elems, idx, first, n_entries, partial);
-    launch((k_giant_finish<DT>), dim3(n_entries), dim3(kGiantFinishThreads), 0, st, (const acc_t*)partial, ppb, n_blocks, idx,
-           first, weights, scores);
+    if (ppb <= kGiantWavePieces)
+      launch((k_giant_finish_wave<DT>), dim3((n_entries + kWG / kWave - 1) / (kWG / kWave)), dim3(kWG), 0, st,
+             (const acc_t*)partial, ppb, n_blocks, idx, first, n_entries, weights, scores);
+    else
+      launch((k_giant_finish<DT>), dim3(n_entries), dim3(kGiantFinishThreads), 0, st, (const acc_t*)partial, ppb,
+             n_blocks, idx, first, weights, scores);
   }
   return launch_status();
 }

@@ -158,7 +158,8 @@ def test_block_scores_of_rows_shorter_than_16_bytes(dtype, L):
 
 @pytest.mark.parametrize("dtype", [F32, BF16, I32])
 @pytest.mark.parametrize("nb,L,off", [(16, 1 << 20, 0), (5, 700_001, 0), (3, 1 << 18, 1), (40, 65_536 + 24, 4),
-                                      (2048, 1 << 16, 0), (16_384, 1 << 14, 0), (9000, 16_390, 3)])
+                                      (2048, 1 << 16, 0), (16_384, 1 << 14, 0), (9000, 16_390, 3),
+                                      (2, 5_000_001, 0)])
 def test_block_scores_of_a_few_very_long_blocks(dtype, nb, L, off):
     # fewer blocks than the chip has room for workgroups: scored in pieces, many workgroups per
     # block (a ragged last block, bases off the 16-byte grid, rows that are not whole steps),
