@@ -262,10 +262,11 @@ __global__ __launch_bounds__(kWG) void k_select_hist(const KeyArgs scores, uint3
 }
 
 // ---- ordered compaction in one kernel ---------------------------------------------------
-// Workgroup t classifies tile t of kTileKeys keys, counts its keys above and equal to the
-// threshold, publishes the counts in the tile's 64-bit word and adds up the words of the
-// tiles before it, a workgroup's width at a time, until it meets a tile that already knows
-// its own running total (a chained scan with look-back).  A word carries its own validity:
+// Workgroup t classifies tile t of kTileKeys keys (a span of consecutive tiles when there are
+// more tiles than kCompactMaxGroups; "tile" below then reads "span"), counts its keys above and
+// equal to the threshold, publishes the counts in the tile's 64-bit word and adds up the words
+// of the tiles before it, a workgroup's width at a time, until it meets a tile that already
+// knows its own running total (a chained scan with look-back).  A word carries its own validity:
 // bits 63-62 say what it holds (0 nothing yet, 1 the tile's own counts, 2 the running total up
 // to and including the tile), bits 61-31 the keys equal to the threshold, bits 30-0 the keys
 // above it.  It is written and read with single relaxed device-scope atomic accesses; nothing
@@ -357,30 +358,40 @@ __device__ __forceinline__ unsigned long long look_back(unsigned long long* __re
   return running;
 }
 
-// 0 = not selected on its own, 1 = above the threshold, 2 = equal to the threshold.
-template <int SRC>
-__device__ __forceinline__ int classify(const KeyArgs& src, uint64_t i, typename Key<SRC>::type T) {
-  const typename Key<SRC>::type key = Key<SRC>::load(src, i);
-  if constexpr (SRC == SRC_MASK) return key ? 1 : 0;
-  return key > T ? 1 : (key == T ? 2 : 0);
+// Writes the selected indices at their final, ascending positions.  For a selection the
+// threshold is first derived from the last pass's histogram, as in k_select_hist.  out_count
+// (mask compaction): receives the number of indices written.
+//
+// Workgroup w owns the `span` consecutive tiles from w * span on and word w of tile_state; grid =
+// ceil(n_tiles / span).  span = 1 (up to kCompactMaxGroups tiles): the tile's keys are
+// classified once and stay in registers across the look-back.  Longer key arrays would put
+// more tiles in flight than a look-back can cross quickly - every workgroup would walk back
+// over all the tiles that run beside it, a window and a round trip across the chip at a time
+// (67 M keys: 435 us, a seventh of what the memory allows) - so there a workgroup first counts
+// all the keys of its span, publishes one word, adds up the words of the at most
+// kCompactMaxGroups - 1 workgroups before it, all of which count at the same time, and then reads
+// its keys a second time to place them.
+constexpr uint32_t kCompactMaxGroups = 2048;
+
+__device__ __forceinline__ unsigned long long pack_counts(uint32_t above_equal16) {
+  return (unsigned long long)(above_equal16 & 0xffffu) | ((unsigned long long)(above_equal16 >> 16) << kEqualShift);
 }
 
-// Writes the selected indices at their final, ascending positions; grid = n_tiles.  For a
-// selection the threshold is first derived from the last pass's histogram, as in
-// k_select_hist.  out_count (mask compaction): receives the number of indices written.
 template <int SRC>
-__global__ __launch_bounds__(kWG) void k_compact(const KeyArgs src, uint32_t n, uint32_t n_tiles,
+__global__ __launch_bounds__(kWG) void k_compact(const KeyArgs src, uint32_t n, uint32_t n_tiles, uint32_t span,
                                                  int passes, SelectWs* __restrict__ ws,
                                                  unsigned long long* __restrict__ tile_state,
                                                  uint32_t* __restrict__ out_idx, uint32_t out_cap,
                                                  uint32_t* __restrict__ out_count, uint32_t spin_limit) {
   using key_t = typename Key<SRC>::type;
-  __shared__ uint32_t slots[kWG / kWave + 1];
-  __shared__ unsigned long long wide[kWG / kWave];
+  constexpr int kWaves = kWG / kWave;
+  __shared__ uint32_t slots[kWaves + 1];
+  __shared__ unsigned long long wide[kWaves];
   __shared__ SelectState shared_state;
   __shared__ unsigned long long s_before;
   __shared__ int s_gave_up;
-  __shared__ int s_found[kWG / kWave];
+  __shared__ int s_found[kWaves];
+  __shared__ uint32_t wave_cnt[kKeysPerThread][kWaves];
   key_t T = 0;
   uint32_t take = 0;
   if constexpr (SRC != SRC_MASK) {
@@ -389,59 +400,120 @@ __global__ __launch_bounds__(kWG) void k_compact(const KeyArgs src, uint32_t n, 
     T = (key_t)fin.prefix;
     take = fin.k_rem;
   }
-  const uint32_t tile = blockIdx.x;
-  if (tile >= n_tiles) return;  // cannot happen with grid == n_tiles; keeps every access in range
+  const uint32_t group = blockIdx.x;
+  const uint64_t first64 = (uint64_t)group * span;
+  if (first64 >= n_tiles) return;  // cannot happen with the grid above; keeps every access in range
+  const uint32_t first = (uint32_t)first64;
+  const uint32_t last = n_tiles - first < span ? n_tiles : first + span;  // one past the span's last tile
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const unsigned long long below = (1ull << lane) - 1;  // the lanes before this one
 
-  const uint64_t base = (uint64_t)tile * kTileKeys + threadIdx.x * kKeysPerThread;
+  // A tile is read as kKeysPerThread rows of kWG consecutive keys, thread i taking key i of every
+  // row: coalesced, and in index order when rows are taken one after the other and threads in
+  // order.  Counts are kept in pairs: low half above the threshold, high half equal to it (a
+  // tile holds 2,048 keys).  Key j of this thread in tile t:
+  auto key_index = [&](uint32_t t, int j) { return (uint64_t)t * kTileKeys + (uint32_t)j * kWG + threadIdx.x; };
+  auto load_tile = [&](uint32_t t, key_t (&key)[kKeysPerThread]) {
+#pragma unroll
+    for (int j = 0; j < kKeysPerThread; ++j) {
+      const uint64_t i = key_index(t, j);
+      key[j] = Key<SRC>::load(src, i < n ? i : n - 1);
+    }
+  };
+  // 0 = not selected on its own, 1 = above the threshold, 2 = equal to it
+  auto class_of = [&](key_t key, uint64_t i) {
+    if (i >= n) return 0;
+    if constexpr (SRC == SRC_MASK) return key ? 1 : 0;
+    return key > T ? 1 : (key == T ? 2 : 0);
+  };
+  auto count_tile = [&](uint32_t t) {  // this thread's share of the tile's counts
+    key_t key[kKeysPerThread];
+    load_tile(t, key);
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int j = 0; j < kKeysPerThread; ++j) {
+      const int c = class_of(key[j], key_index(t, j));
+      cnt += c == 1 ? 1u : (c == 2 ? (1u << 16) : 0u);
+    }
+    return cnt;
+  };
+  // Classes of this thread's keys of tile t, the counts of the lanes before it in each row, and
+  // (returned) the counts of the whole tile; before_in_tile[j] then holds the counts of
+  // everything in the tile that precedes key j of this thread.
   int cls[kKeysPerThread];
-  uint32_t cnt = 0;  // low half: above, high half: equal (a tile holds 2048 keys)
+  uint32_t before_in_tile[kKeysPerThread];
+  auto classify_tile = [&](uint32_t t, const key_t (&key)[kKeysPerThread]) {
 #pragma unroll
-  for (int j = 0; j < kKeysPerThread; ++j) {
-    cls[j] = base + j < n ? classify<SRC>(src, base + j, T) : 0;
-    cnt += cls[j] == 1 ? 1u : (cls[j] == 2 ? (1u << 16) : 0u);
-  }
-  uint32_t total;
-  const uint32_t ex = workgroup_exclusive_scan(cnt, slots, &total);
-  const unsigned long long own = (unsigned long long)(total & 0xffffu) |
-                                 ((unsigned long long)(total >> 16) << kEqualShift);
-  unsigned long long before = look_back(tile_state, tile, own, spin_limit, &s_gave_up, wide, s_found);
-  if (s_gave_up) {  // count the keys of the earlier tiles directly
-    unsigned long long c2 = 0;
-    for (uint32_t t = 0; t < tile; ++t) {
-      const uint64_t b2 = (uint64_t)t * kTileKeys + threadIdx.x * kKeysPerThread;
+    for (int j = 0; j < kKeysPerThread; ++j) cls[j] = class_of(key[j], key_index(t, j));
+    __syncthreads();  // wave_cnt may still be read from the tile before
 #pragma unroll
-      for (int j = 0; j < kKeysPerThread; ++j) {
-        const int c = b2 + j < n ? classify<SRC>(src, b2 + j, T) : 0;
-        c2 += c == 1 ? 1ull : (c == 2 ? (1ull << kEqualShift) : 0ull);
+    for (int j = 0; j < kKeysPerThread; ++j) {
+      const unsigned long long above = __ballot(cls[j] == 1), equal = __ballot(cls[j] == 2);
+      before_in_tile[j] = (uint32_t)__popcll(above & below) | ((uint32_t)__popcll(equal & below) << 16);
+      if (lane == 0) wave_cnt[j][wave] = (uint32_t)__popcll(above) | ((uint32_t)__popcll(equal) << 16);
+    }
+    __syncthreads();
+    uint32_t running = 0;
+#pragma unroll
+    for (int j = 0; j < kKeysPerThread; ++j) {
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        if (w == wave) before_in_tile[j] += running;
+        running += wave_cnt[j][w];
       }
     }
+    return running;
+  };
+
+  uint32_t total = 0;
+  unsigned long long own;
+  key_t cur[kKeysPerThread] = {}, nxt[kKeysPerThread] = {};
+  if (span == 1) {
+    load_tile(first, cur);
+    total = classify_tile(first, cur);
+    own = pack_counts(total);
+  } else {
+    unsigned long long mine = 0;
+#pragma unroll 2
+    for (uint32_t t = first; t < last; ++t) mine += pack_counts(count_tile(t));
+    own = workgroup_sum(mine, wide);
+    load_tile(first, cur);  // on its way during the look-back
+  }
+  unsigned long long before = look_back(tile_state, group, own, spin_limit, &s_gave_up, wide, s_found);
+  if (s_gave_up) {  // count the keys of the earlier tiles directly
+    unsigned long long c2 = 0;
+    for (uint32_t t = 0; t < first; ++t) c2 += pack_counts(count_tile(t));
     before = workgroup_sum(c2, wide);
     __syncthreads();
     if (threadIdx.x == 0) {
       s_before = before;
-      tile_word_store(&tile_state[tile], kTileRunning | (before + own));  // later tiles may stop here
+      tile_word_store(&tile_state[group], kTileRunning | (before + own));  // later workgroups may stop here
     }
     __syncthreads();
     before = s_before;
   }
-  uint32_t n_above = (uint32_t)(before & kFieldMask) + (ex & 0xffffu);
-  uint32_t n_equal = (uint32_t)((before >> kEqualShift) & kFieldMask) + (ex >> 16);
-#pragma unroll
-  for (int j = 0; j < kKeysPerThread; ++j) {
-    if (cls[j] == 1) {
-      const uint32_t pos = n_above + (n_equal < take ? n_equal : take);
-      if (pos < out_cap) out_idx[pos] = (uint32_t)(base + j);
-      ++n_above;
-    } else if (cls[j] == 2) {
-      if (n_equal < take) {
-        const uint32_t pos = n_above + n_equal;
-        if (pos < out_cap) out_idx[pos] = (uint32_t)(base + j);
-      }
-      ++n_equal;
+  for (uint32_t t = first; t < last; ++t) {
+    if (span != 1) {  // the next tile's keys are asked for before this tile is placed
+      if (t + 1 < last) load_tile(t + 1, nxt);
+      total = classify_tile(t, cur);
     }
+    const uint32_t above0 = (uint32_t)(before & kFieldMask), equal0 = (uint32_t)((before >> kEqualShift) & kFieldMask);
+#pragma unroll
+    for (int j = 0; j < kKeysPerThread; ++j) {
+      const uint32_t n_above = above0 + (before_in_tile[j] & 0xffffu), n_equal = equal0 + (before_in_tile[j] >> 16);
+      if (cls[j] == 1) {
+        const uint32_t pos = n_above + (n_equal < take ? n_equal : take);
+        if (pos < out_cap) out_idx[pos] = (uint32_t)key_index(t, j);
+      } else if (cls[j] == 2 && n_equal < take) {
+        const uint32_t pos = n_above + n_equal;
+        if (pos < out_cap) out_idx[pos] = (uint32_t)key_index(t, j);
+      }
+    }
+    before += pack_counts(total);
+#pragma unroll
+    for (int j = 0; j < kKeysPerThread; ++j) cur[j] = nxt[j];
   }
-  if (out_count && tile == n_tiles - 1 && threadIdx.x == 0)
-    *out_count = (uint32_t)(before & kFieldMask) + (total & 0xffffu);
+  if (out_count && last == n_tiles && threadIdx.x == 0) *out_count = (uint32_t)(before & kFieldMask);
 }
 
 // Whole selection in one workgroup of 1,024 threads for small stores (n <= kSmallSelect):
@@ -547,8 +619,10 @@ static void run_compaction(const KeyArgs src, uint32_t n, int passes, SelectWs* 
                            unsigned long long* tiles, uint32_t* out_idx, uint32_t out_cap,
                            uint32_t* out_count, hipStream_t st) {
   const uint32_t n_tiles = (uint32_t)n_tiles_of(n);
-  launch((k_compact<SRC>), dim3(n_tiles), dim3(kWG), 0, st, src, n, n_tiles, passes, ws, tiles, out_idx,
-         out_cap, out_count, g_spin_limit);
+  uint32_t span = (n_tiles + kCompactMaxGroups - 1) / kCompactMaxGroups;  // 1 up to kCompactMaxGroups tiles
+  if (span == 0) span = 1;
+  launch((k_compact<SRC>), dim3((n_tiles + span - 1) / span), dim3(kWG), 0, st, src, n, n_tiles, span, passes, ws,
+         tiles, out_idx, out_cap, out_count, g_spin_limit);
 }
 
 template <int SRC>

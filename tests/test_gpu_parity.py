@@ -392,7 +392,8 @@ def test_ordered_write_when_no_workgroup_waits_for_another(limit):
     r = np.random.default_rng(limit)
     scar.set_lookback_spin_limit(limit)
     try:
-        for n, k in ((300_000, 30_000), (1_000_000, 999_999), (20_000, 1)):
+        # 4.3 M keys: more tiles than workgroups, so each workgroup owns two tiles and counts them first
+        for n, k in ((300_000, 30_000), (1_000_000, 999_999), (20_000, 1), (4_300_000, 500_000)):
             print("forced fallback limit=%d n=%d k=%d" % (limit, n, k), flush=True)
             s = r.integers(0, 30, size=n).astype(np.float32)
             ws = scar.new_workspace(n, DEV)
