@@ -176,6 +176,14 @@ int scar_select_topk_bounded(int32_t score_type, const void* scores, uint32_t n_
  * to be changed while calls are being made on other threads. */
 void scar_set_lookback_spin_limit(uint32_t polls);
 
+/* Testing aid.  The ordered write gives every workgroup one tile of 2,048 keys up to 2,048
+ * tiles and a span of consecutive tiles beyond (longer key arrays), whose first 32 tiles are
+ * placed from classes kept while counting and whose further tiles are read again.  A smaller
+ * number of workgroups makes short key arrays take those paths: `groups` in [1, 2048]; 0 or a
+ * larger value restores the default.  Results never depend on it.  Process-wide, host-side;
+ * not to be changed while calls are being made on other threads. */
+void scar_set_compaction_groups(uint32_t groups);
+
 /* scar_select_topk for callers that cannot allocate device memory or hand over a workspace:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, same result (index for index) as scar_select_topk, but the scratch is a fixed

@@ -369,9 +369,11 @@ __device__ __forceinline__ unsigned long long look_back(unsigned long long* __re
 // over all the tiles that run beside it, a window and a round trip across the chip at a time
 // (67 M keys: 435 us, a seventh of what the memory allows) - so there a workgroup first counts
 // all the keys of its span, publishes one word, adds up the words of the at most
-// kCompactMaxGroups - 1 workgroups before it, all of which count at the same time, and then reads
-// its keys a second time to place them.
+// kCompactMaxGroups - 1 workgroups before it, all of which count at the same time, and then
+// places its keys: those of the first kCompactKeptTiles tiles from the classes it kept in LDS while
+// counting (two bits per key), those of further tiles (beyond 134 M keys) by reading them again.
 constexpr uint32_t kCompactMaxGroups = 2048;
+constexpr uint32_t kCompactKeptTiles = 32;  // tiles of a span whose classes wait in LDS (16 KiB)
 
 __device__ __forceinline__ unsigned long long pack_counts(uint32_t above_equal16) {
   return (unsigned long long)(above_equal16 & 0xffffu) | ((unsigned long long)(above_equal16 >> 16) << kEqualShift);
@@ -392,6 +394,7 @@ __global__ __launch_bounds__(kWG) void k_compact(const KeyArgs src, uint32_t n, 
   __shared__ int s_gave_up;
   __shared__ int s_found[kWaves];
   __shared__ uint32_t wave_cnt[kKeysPerThread][kWaves];
+  __shared__ uint16_t codes[kCompactKeptTiles][kWG];
   key_t T = 0;
   uint32_t take = 0;
   if constexpr (SRC != SRC_MASK) {
@@ -426,25 +429,26 @@ __global__ __launch_bounds__(kWG) void k_compact(const KeyArgs src, uint32_t n, 
     if constexpr (SRC == SRC_MASK) return key ? 1 : 0;
     return key > T ? 1 : (key == T ? 2 : 0);
   };
-  auto count_tile = [&](uint32_t t) {  // this thread's share of the tile's counts
+  // This thread's share of the counts of tile t; *code gets the classes of its keys, two bits each.
+  auto count_tile = [&](uint32_t t, uint16_t* code) {
     key_t key[kKeysPerThread];
     load_tile(t, key);
-    uint32_t cnt = 0;
+    uint32_t cnt = 0, packed = 0;
 #pragma unroll
     for (int j = 0; j < kKeysPerThread; ++j) {
       const int c = class_of(key[j], key_index(t, j));
       cnt += c == 1 ? 1u : (c == 2 ? (1u << 16) : 0u);
+      packed |= (uint32_t)c << (2 * j);
     }
+    *code = (uint16_t)packed;
     return cnt;
   };
-  // Classes of this thread's keys of tile t, the counts of the lanes before it in each row, and
-  // (returned) the counts of the whole tile; before_in_tile[j] then holds the counts of
-  // everything in the tile that precedes key j of this thread.
+  // cls: classes of this thread's keys of a tile.  rank_tile returns the counts of the whole tile
+  // and leaves in before_in_tile[j] the counts of everything in the tile that precedes key j of
+  // this thread.
   int cls[kKeysPerThread];
   uint32_t before_in_tile[kKeysPerThread];
-  auto classify_tile = [&](uint32_t t, const key_t (&key)[kKeysPerThread]) {
-#pragma unroll
-    for (int j = 0; j < kKeysPerThread; ++j) cls[j] = class_of(key[j], key_index(t, j));
+  auto rank_tile = [&]() {  // from cls[]
     __syncthreads();  // wave_cnt may still be read from the tile before
 #pragma unroll
     for (int j = 0; j < kKeysPerThread; ++j) {
@@ -465,24 +469,37 @@ __global__ __launch_bounds__(kWG) void k_compact(const KeyArgs src, uint32_t n, 
     return running;
   };
 
+  auto classes_from_keys = [&](uint32_t t, const key_t (&key)[kKeysPerThread]) {
+#pragma unroll
+    for (int j = 0; j < kKeysPerThread; ++j) cls[j] = class_of(key[j], key_index(t, j));
+  };
   uint32_t total = 0;
   unsigned long long own;
   key_t cur[kKeysPerThread] = {}, nxt[kKeysPerThread] = {};
+  const uint32_t kept = last - first < kCompactKeptTiles ? last - first : kCompactKeptTiles;  // tiles with codes in LDS
   if (span == 1) {
     load_tile(first, cur);
-    total = classify_tile(first, cur);
+    classes_from_keys(first, cur);
+    total = rank_tile();
     own = pack_counts(total);
   } else {
     unsigned long long mine = 0;
 #pragma unroll 2
-    for (uint32_t t = first; t < last; ++t) mine += pack_counts(count_tile(t));
+    for (uint32_t t = first; t < last; ++t) {
+      uint16_t code;
+      mine += pack_counts(count_tile(t, &code));
+      if (t - first < kCompactKeptTiles) codes[t - first][threadIdx.x] = code;  // read back by the same thread
+    }
     own = workgroup_sum(mine, wide);
-    load_tile(first, cur);  // on its way during the look-back
+    if (first + kept < last) load_tile(first + kept, cur);  // on its way during the look-back
   }
   unsigned long long before = look_back(tile_state, group, own, spin_limit, &s_gave_up, wide, s_found);
   if (s_gave_up) {  // count the keys of the earlier tiles directly
     unsigned long long c2 = 0;
-    for (uint32_t t = 0; t < first; ++t) c2 += pack_counts(count_tile(t));
+    for (uint32_t t = 0; t < first; ++t) {
+      uint16_t code;
+      c2 += pack_counts(count_tile(t, &code));
+    }
     before = workgroup_sum(c2, wide);
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -493,9 +510,16 @@ __global__ __launch_bounds__(kWG) void k_compact(const KeyArgs src, uint32_t n, 
     before = s_before;
   }
   for (uint32_t t = first; t < last; ++t) {
-    if (span != 1) {  // the next tile's keys are asked for before this tile is placed
-      if (t + 1 < last) load_tile(t + 1, nxt);
-      total = classify_tile(t, cur);
+    if (span != 1) {
+      if (t - first < kept) {  // classes kept from the count
+        const uint32_t code = codes[t - first][threadIdx.x];
+#pragma unroll
+        for (int j = 0; j < kKeysPerThread; ++j) cls[j] = (int)((code >> (2 * j)) & 3u);
+      } else {  // read again, the next tile's keys asked for before this tile is placed
+        if (t + 1 < last) load_tile(t + 1, nxt);
+        classes_from_keys(t, cur);
+      }
+      total = rank_tile();
     }
     const uint32_t above0 = (uint32_t)(before & kFieldMask), equal0 = (uint32_t)((before >> kEqualShift) & kFieldMask);
 #pragma unroll
@@ -510,8 +534,10 @@ __global__ __launch_bounds__(kWG) void k_compact(const KeyArgs src, uint32_t n, 
       }
     }
     before += pack_counts(total);
+    if (t - first >= kept) {
 #pragma unroll
-    for (int j = 0; j < kKeysPerThread; ++j) cur[j] = nxt[j];
+      for (int j = 0; j < kKeysPerThread; ++j) cur[j] = nxt[j];
+    }
   }
   if (out_count && last == n_tiles && threadIdx.x == 0) *out_count = (uint32_t)(before & kFieldMask);
 }
@@ -606,6 +632,7 @@ __global__ __launch_bounds__(kSmallWG) void k_select_small(const KeyArgs scores,
 // the earlier tiles itself (each poll is a load from device memory plus a short sleep, about a
 // microsecond).  A host-side setting so that a test can force the fallback.
 static uint32_t g_spin_limit = 1u << 16;
+static uint32_t g_compact_groups = kCompactMaxGroups;
 
 static uint32_t clear_grid(uint32_t n_tiles) {
   const uint32_t words = (uint32_t)(sizeof(SelectWs) / 4) + n_tiles;
@@ -619,7 +646,7 @@ static void run_compaction(const KeyArgs src, uint32_t n, int passes, SelectWs* 
                            unsigned long long* tiles, uint32_t* out_idx, uint32_t out_cap,
                            uint32_t* out_count, hipStream_t st) {
   const uint32_t n_tiles = (uint32_t)n_tiles_of(n);
-  uint32_t span = (n_tiles + kCompactMaxGroups - 1) / kCompactMaxGroups;  // 1 up to kCompactMaxGroups tiles
+  uint32_t span = (n_tiles + g_compact_groups - 1) / g_compact_groups;  // 1 up to kCompactMaxGroups tiles
   if (span == 0) span = 1;
   launch((k_compact<SRC>), dim3((n_tiles + span - 1) / span), dim3(kWG), 0, st, src, n, n_tiles, span, passes, ws,
          tiles, out_idx, out_cap, out_count, g_spin_limit);
@@ -758,6 +785,10 @@ extern "C" int scar_select_topk_bounded(int32_t score_type, const void* scores, 
 }
 
 extern "C" void scar_set_lookback_spin_limit(uint32_t polls) { g_spin_limit = polls; }
+
+extern "C" void scar_set_compaction_groups(uint32_t groups) {
+  g_compact_groups = (groups == 0 || groups > kCompactMaxGroups) ? kCompactMaxGroups : groups;
+}
 
 // ---- the selection for callers that cannot allocate -------------------------------------
 // The scratch of scar_select_topk_static: one array per GPU, part of the loaded code object,

@@ -76,6 +76,8 @@ def lib():
         L.scar_select_topk_bounded.restype = ctypes.c_int
         L.scar_set_lookback_spin_limit.argtypes = [u32]
         L.scar_set_lookback_spin_limit.restype = None
+        L.scar_set_compaction_groups.argtypes = [u32]
+        L.scar_set_compaction_groups.restype = None
         L.scar_select_topk_static.argtypes = [i32, vp, u32, u32, vp, vp]
         L.scar_select_topk_static.restype = ctypes.c_int
         L.scar_partial_recover.argtypes = [lp, vp, vp, vp, u32, vp, vp, sz, vp]
@@ -279,6 +281,11 @@ def check_indices(idx, n_blocks_):
 
 def set_lookback_spin_limit(polls: int) -> None:
     lib().scar_set_lookback_spin_limit(int(polls))
+
+
+def set_compaction_groups(groups: int) -> None:
+    """scar_set_compaction_groups (testing aid): at most `groups` workgroups in the ordered write."""
+    lib().scar_set_compaction_groups(int(groups))
 
 
 STATIC_MAX_BLOCKS = 1 << 24

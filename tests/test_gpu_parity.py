@@ -411,6 +411,38 @@ def test_ordered_write_when_no_workgroup_waits_for_another(limit):
         scar.set_lookback_spin_limit(1 << 16)
 
 
+@pytest.mark.parametrize("groups,limit", [(1, 1 << 16), (3, 1 << 16), (7, 1 << 16), (64, 1 << 16), (5, 0)])
+def test_ordered_write_over_spans_of_tiles(groups, limit):
+    # long key arrays give every workgroup a span of tiles; a small number of workgroups, set
+    # from the host, makes short arrays take the same paths: spans of up to 489 tiles, the first
+    # 32 of them placed from classes kept while counting, the rest read again; with and without
+    # a look-back that gives up at once
+    r = np.random.default_rng(groups)
+    scar.set_compaction_groups(groups)
+    scar.set_lookback_spin_limit(limit)
+    try:
+        for n, k in ((1_000_000, 100_000), (300_001, 300_000), (70_000, 1)):
+            print("spans groups=%d limit=%d n=%d k=%d" % (groups, limit, n, k), flush=True)
+            s = r.integers(0, 50, size=n).astype(np.float32)
+            ws = scar.new_workspace(n, DEV)
+            got = idx_host(scar.select_topk(torch.from_numpy(s).to(DEV), k, ws))
+            np.testing.assert_array_equal(got, oracle.select_topk(s.astype(np.float64), k))
+            f = r.random(n).astype(np.float32)
+            got = idx_host(scar.select_topk(torch.from_numpy(f).to(DEV), k, ws))
+            np.testing.assert_array_equal(got, oracle.select_topk(f.astype(np.float64), k))
+            m = (s > 30).astype(np.uint8)
+            out, cnt = scar.mask_to_indices(torch.from_numpy(m).to(DEV), ws)
+            want = oracle.mask_to_indices(m)
+            assert int(cnt.item()) == want.size
+            np.testing.assert_array_equal(idx_host(out)[: want.size], want)
+            si = r.integers(0, 5, size=n).astype(np.int64)
+            got = idx_host(scar.select_topk(torch.from_numpy(si).to(DEV), k, ws))
+            np.testing.assert_array_equal(got, oracle.select_topk(si, k))
+    finally:
+        scar.set_compaction_groups(0)
+        scar.set_lookback_spin_limit(1 << 16)
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16, I32])
 @pytest.mark.parametrize("L", [1, 6, 100, 1024, 4100, 20000])
 def test_commit_and_recover(dtype, L):
