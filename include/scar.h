@@ -129,8 +129,8 @@ size_t scar_workspace_bytes(uint64_t n_blocks);
  * Reads x and c once; writes scores.  Stores of at most 16,384 blocks of 64 KiB or more (a
  * tensor cut into a few large shards) are scored in pieces by many workgroups per block; the
  * pieces' sums wait in a fixed 2 MiB array inside the library (this call takes no workspace),
- * so two calls of that kind must not overlap on one GPU.  SCAR_F32_BF16C stores keep one
- * workgroup per block.  The copy calls below hand long rows out in 4 KiB pieces. */
+ * so two calls of that kind must not overlap on one GPU.  The copy calls below hand long rows
+ * out in 4 KiB pieces. */
 int scar_block_scores(const scar_layout* layout, const void* x, const void* c, void* scores,
                       void* stream);
 

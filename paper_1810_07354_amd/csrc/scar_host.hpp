@@ -166,6 +166,8 @@ void launch_finish_tv(const void* partial, uint32_t n_partial, scar_norm* out, h
 // ---- reduced-precision checkpoint (SCAR_F32_BF16C: x float32, c bfloat16) ---------------
 // Bodies of the entry points for that store type (defined with its kernels); arguments are
 // as in the entry points and the layout has already been checked.
+bool mixed_giant_scores(const scar_layout* l, uint32_t n_blocks, const void* x, const void* c,
+                        const uint32_t* idx, uint32_t n_idx, void* scores, hipStream_t st, int* status);
 int mixed_block_scores(const scar_layout* l, uint32_t n_blocks, const void* x, const void* c,
                        const uint32_t* idx, uint32_t n_idx, void* scores, hipStream_t st);
 int mixed_commit(const scar_layout* l, uint32_t n_blocks, const void* x, void* c, const uint32_t* idx,

@@ -54,4 +54,56 @@ __device__ __forceinline__ float widen_elem(const uint16_t* c, uint64_t j) {
   return __uint_as_float((uint32_t)c[j] << 16);
 }
 
+// Elements of a row before its first whole unit (4 elements: 16 bytes of x on a 16-byte
+// boundary, 8 bytes of c on an 8-byte boundary).  Both streams reach such boundaries at the same
+// elements exactly when the two row addresses have the same phase, counted in elements modulo
+// 4; then the row is walked in units between (-phase) mod 4 leading and a few trailing
+// elements, whatever its length.  Rows whose phases differ (views that start at unrelated
+// offsets, packed rows of a length that is no multiple of 4) are walked element by element: all
+// of the row is "head".  Decided per row from the addresses, so every kernel splits a given row
+// in the same way.
+__device__ __forceinline__ uint32_t mixed_head(const float* xb, const uint16_t* cb, uint32_t len) {
+  const uint32_t px = (uint32_t)((uintptr_t)xb >> 2) & (kMixUnit - 1);
+  const uint32_t pc = (uint32_t)((uintptr_t)cb >> 1) & (kMixUnit - 1);
+  if (px != pc) return len;
+  const uint32_t head = (0u - px) & (kMixUnit - 1);
+  return head < len ? head : len;
+}
+
+// Squared distance of one block (len elements at xb / cb, the first `head` of them before the
+// first whole unit), this lane's share: the whole units, then the elements around them.
+template <int G>
+__device__ __forceinline__ double mixed_distance(const float* xb, const uint16_t* cb, uint32_t len,
+                                                 uint32_t head, int lane) {
+  double acc = 0;
+  const uint32_t nunit = (len - head) / kMixUnit;
+  const uint32_t tail0 = head + nunit * kMixUnit;
+  const uint4* xv = (const uint4*)(xb + head);
+  const uint2* cv = (const uint2*)(cb + head);
+  for (uint32_t u0 = 0; u0 < nunit; u0 += G * kMixU) {
+    uint4 a[kMixU];
+    uint2 b[kMixU];
+#pragma unroll
+    for (int u = 0; u < kMixU; ++u) {
+      const uint32_t i = u0 + u * G + lane;
+      if (i < nunit) {
+        a[u] = load_stream(xv + i);
+        b[u] = load_stream2(cv + i);
+      } else {
+        a[u] = make_uint4(0, 0, 0, 0);
+        b[u] = make_uint2(0, 0);
+      }
+    }
+    float part = 0.f;
+#pragma unroll
+    for (int u = 0; u < kMixU; ++u) part += sqdiff_unit(a[u], b[u]);
+    acc += (double)part;
+  }
+  for (uint32_t e = lane; e < len - nunit * kMixUnit; e += G) {
+    const uint32_t j = e < head ? e : tail0 + (e - head);
+    acc += (double)sq(xb[j] - widen_elem(cb, j));
+  }
+  return acc;
+}
+
 }  // namespace scar

@@ -10,6 +10,7 @@
 
 #include "scar_device.hpp"
 #include "scar_host.hpp"
+#include "scar_mixed_device.hpp"
 
 namespace scar {
 
@@ -455,6 +456,40 @@ __global__ __launch_bounds__(kWG) void k_giant_pieces(const char* __restrict__ x
   }
 }
 
+// The same pieces for the reduced-precision store (float32 x, bfloat16 c): offsets count
+// elements, each wavefront's quarter is split into units by its own addresses (mixed_head).
+__global__ __launch_bounds__(kWG) void k_giant_pieces_mixed(const float* __restrict__ x,
+                                                            const uint16_t* __restrict__ c, uint64_t n_elems,
+                                                            uint32_t block_len, uint32_t n_blocks, uint32_t ppb,
+                                                            uint32_t piece_elems, const uint32_t* __restrict__ idx,
+                                                            uint32_t first_entry, uint32_t n_entries,
+                                                            double* __restrict__ partial) {
+  __shared__ double slots[kWG / kWave];
+  const uint64_t total = (uint64_t)n_entries * ppb;
+  for (uint64_t w = xcd_contiguous_block_id(); w < total; w += gridDim.x) {
+    const uint32_t e = (uint32_t)(w / ppb), piece = (uint32_t)(w % ppb);
+    const uint64_t b = idx ? idx[first_entry + e] : first_entry + e;
+    double acc = 0;
+    if (b < n_blocks) {
+      const BlockSpan sp = block_span(b, n_elems, block_len, 1);  // byte_off = element offset
+      const uint64_t lo = (uint64_t)piece * piece_elems;
+      if (lo < sp.len) {
+        const uint32_t len = (uint32_t)(sp.len - lo < piece_elems ? sp.len - lo : piece_elems);
+        const uint32_t quarter = piece_elems / (kWG / kWave);
+        const uint32_t q0 = (threadIdx.x / kWave) * quarter;
+        if (q0 < len) {
+          const uint32_t qlen = len - q0 < quarter ? len - q0 : quarter;
+          const float* xb = x + sp.byte_off + lo + q0;
+          const uint16_t* cb = c + sp.byte_off + lo + q0;
+          acc = mixed_distance<kWave>(xb, cb, qlen, mixed_head(xb, cb, qlen), threadIdx.x & (kWave - 1));
+        }
+      }
+    }
+    acc = workgroup_sum(acc, slots);
+    if (threadIdx.x == 0) partial[w] = acc;
+  }
+}
+
 constexpr int kGiantFinishThreads = 1024;
 template <int DT>
 __global__ __launch_bounds__(kGiantFinishThreads) void k_giant_finish(
@@ -535,7 +570,8 @@ static bool giant_geometry(const scar_layout* l, int eb, uint32_t n_blocks, uint
   return true;
 }
 
-template <int DT>
+// MIXED: float32 x against a bfloat16 c (DT = DT_F32 for the sums and the scores).
+template <int DT, bool MIXED = false>
 static int launch_giant(const scar_layout* l, const void* x, const void* c, void* scores, uint32_t n_blocks,
                         bool vec, const float* weights, const uint32_t* idx, uint32_t n_idx, uint32_t ppb,
                         uint32_t piece_elems, hipStream_t st) {
@@ -548,8 +584,11 @@ static int launch_giant(const scar_layout* l, const void* x, const void* c, void
     const uint32_t n_entries = n_items - first < per_launch ? n_items - first : per_launch;
     const uint64_t total = (uint64_t)n_entries * ppb;
     const uint32_t grid = xcd_grid(total, kScoreGridCap);
-    const size_t lds = stream_lds_bytes(total, 2 * 16 * kWG * kUnroll);
-    if (vec)
+    const size_t lds = stream_lds_bytes(total, (MIXED ? 24 : 2 * 16) * kWG * kUnroll);
+    if constexpr (MIXED)
+      launch(k_giant_pieces_mixed, dim3(grid), dim3(kWG), lds, st, (const float*)x, (const uint16_t*)c, l->n_elems,
+             l->block_len, n_blocks, ppb, piece_elems, idx, first, n_entries, (double*)partial);
+    else if (vec)
       launch((k_giant_pieces<DT, true>), dim3(grid), dim3(kWG), lds, st, (const char*)x, (const char*)c,
              l->n_elems, l->block_len, n_blocks, ppb, piece_elems, idx, first, n_entries, partial);
     else
@@ -563,6 +602,16 @@ static int launch_giant(const scar_layout* l, const void* x, const void* c, void
              n_blocks, idx, first, weights, scores);
   }
   return launch_status();
+}
+
+// Scores of a reduced-precision store that is a few very long blocks; false if the layout is
+// not of that kind (then nothing has been enqueued and *status is untouched).
+bool mixed_giant_scores(const scar_layout* l, uint32_t n_blocks, const void* x, const void* c,
+                        const uint32_t* idx, uint32_t n_idx, void* scores, hipStream_t st, int* status) {
+  uint32_t ppb = 0, piece_elems = 0;
+  if (!giant_geometry(l, 4, n_blocks, &ppb, &piece_elems)) return false;
+  *status = launch_giant<DT_F32, true>(l, x, c, scores, n_blocks, false, nullptr, idx, n_idx, ppb, piece_elems, st);
+  return true;
 }
 
 template <int DT>

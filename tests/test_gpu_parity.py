@@ -156,7 +156,7 @@ def test_block_scores_of_rows_shorter_than_16_bytes(dtype, L):
         assert torch.equal(s, listed)
 
 
-@pytest.mark.parametrize("dtype", [F32, BF16, I32])
+@pytest.mark.parametrize("dtype", [F32, BF16, I32, wl.F32_BF16C])
 @pytest.mark.parametrize("nb,L,off", [(16, 1 << 20, 0), (5, 700_001, 0), (3, 1 << 18, 1), (40, 65_536 + 24, 4),
                                       (2048, 1 << 16, 0), (16_384, 1 << 14, 0), (9000, 16_390, 3),
                                       (2, 5_000_001, 0)])
@@ -167,9 +167,14 @@ def test_block_scores_of_a_few_very_long_blocks(dtype, nb, L, off):
     if dtype == BF16 and L * 2 < 64 * 1024:
         L *= 2
     n = L * nb - L // 3
-    hx, hc = make_store(dtype, n, seed=nb + L)
-    x = to_dev(np.concatenate([np.zeros(off, dtype=hx.dtype), hx]), dtype)[off:]
-    c = to_dev(np.concatenate([np.zeros(off, dtype=hc.dtype), hc]), dtype)[off:]
+    xdt = cdt = dtype
+    if dtype == wl.F32_BF16C:             # float32 x against a bfloat16 checkpoint
+        xdt, cdt = F32, BF16
+    hx, hc = make_store(xdt, n, seed=nb + L)
+    if dtype == wl.F32_BF16C:
+        hc = wl.f32_to_bf16_bits(hc)
+    x = to_dev(np.concatenate([np.zeros(off, dtype=hx.dtype), hx]), xdt)[off:]
+    c = to_dev(np.concatenate([np.zeros(off, dtype=hc.dtype), hc]), cdt)[off:]
     print("giant blocks dtype=%d nb=%d L=%d off=%d" % (dtype, nb, L, off), flush=True)
     oracle.set_num_threads(8)
     try:
