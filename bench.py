@@ -322,13 +322,19 @@ def measure_ceilings(dev, bytes_per_stream, reps=10):
 
 
 def main_layers(args):
+    print(json.dumps(run_layers("cuda:0", args.steps, args.warmup)), flush=True)
+
+
+def run_layers(dev, steps, warmup):
     """The by-layer variant: the 2^30-element f32 store cut into 96 tensors of very unequal
-    size (blocks of unequal length), through the scar_var_* entry points."""
+    size (blocks of unequal length), through the scar_var_* entry points.  Returns the JSON
+    fields of the run."""
+    import types
     import numpy as np
     import torch
     from paper_1810_07354_amd import scar, workloads as wl
 
-    dev = "cuda:0"
+    args = types.SimpleNamespace(steps=steps, warmup=warmup)
     n_elems, seed = 1 << 30, 4
     sizes = wl.mixed_layer_sizes(96, n_elems, seed=6)
     sizes[np.argmax(sizes)] += n_elems - sizes.sum()          # make the sizes add up exactly
@@ -373,7 +379,7 @@ def main_layers(args):
     recover_bytes = sum(m[1] for m in moved) / len(moved)
     cycle_bytes = score_bytes + commit_bytes + recover_bytes
     achieved = score_bytes / (score_ms * 1e-3) / 1e9
-    print(json.dumps({
+    return {
         "metric": "params scanned GB/s per checkpoint+recovery cycle",
         "value": round(n_elems * 4 / (ms_step * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
@@ -389,11 +395,12 @@ def main_layers(args):
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                      "avg_ms": round(score_ms, 4), "algorithmic_bytes_per_launch": score_bytes},
-        "cpu_baseline": None}), flush=True)
+        "cpu_baseline": None}
 
 
 STRATEGIES = ("priority", "round", "random", "full")
-OTHER_WORKLOADS = ("flat_bf16", "mlr", "mf", "lda", "cnn@1", "cnn@10", "cnn@50")
+OTHER_WORKLOADS = ("flat_bf16", "flat_mixed", "giant", "doctopic", "mlr", "mf", "lda", "cnn@1", "cnn@10", "cnn@50")
+LAUNCH_BOUND_WORKLOADS = ("mlr", "mf", "lda", "cnn@1", "cnn@10", "cnn@50")   # also timed as HIP-graph replays
 
 
 def run_workload(name, dev, steps, warmup, strategy="priority", hip_graph=False):
@@ -695,7 +702,7 @@ def main():
             entry = brief(o)
             del st
             torch.cuda.empty_cache()
-            if name != "flat_bf16":
+            if name in LAUNCH_BOUND_WORKLOADS:
                 # the small stores are bound by launch and host-call latency: the same cycle
                 # replayed from a captured HIP graph, as a caller with such a store would run it
                 g, st = run_workload(name, dev, 20, 3, hip_graph=True)
@@ -704,6 +711,14 @@ def main():
                 del st
                 torch.cuda.empty_cache()
             others.append(entry)
+        lay = run_layers(dev, 20, 3)   # blocks of unequal length (scar_var_*), the same 2^30 elements
+        r = lay["roofline"]
+        others.append({"workload": "layers", "label": lay["config"]["workload"], "dtype": lay["dtype"],
+                       "strategy": "priority", "steps": lay["steps"], "ms_per_step": lay["ms_per_step"],
+                       "value": lay["value"], "unit": lay["unit"], "pct_of_hbm_peak": lay["pct_of_hbm_peak"],
+                       "roofline": {"kernel": r["kernel"], "achieved": r["achieved"], "frac": r["frac"],
+                                    "avg_ms": r["avg_ms"]}})
+        torch.cuda.empty_cache()
         out["other_workloads"] = others
     print(json.dumps(out), flush=True)
 
