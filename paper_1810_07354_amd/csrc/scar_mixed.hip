@@ -155,7 +155,10 @@ __device__ __forceinline__ bool mixed_piece(uint32_t b, uint32_t piece, uint32_t
 }
 
 // c_b <- round(x_b) (and staging row i <- the same bfloat16 values) for b = idx[i].
-template <int G>
+// WHOLE: every row starts on a unit boundary of both streams and is a whole number of units
+// (but for a short last block) - x 16-byte, c 8-byte aligned, block_len a multiple of 4 -
+// so no row has leading elements and the split by addresses is skipped.
+template <int G, bool WHOLE>
 __global__ __launch_bounds__(kWG) void k_mixed_commit(const float* __restrict__ x, uint16_t* __restrict__ c,
                                                       const uint32_t* __restrict__ idx, uint32_t n_idx,
                                                       uint16_t* __restrict__ staging, uint64_t n_elems,
@@ -173,13 +176,13 @@ __global__ __launch_bounds__(kWG) void k_mixed_commit(const float* __restrict__ 
       const float* xb = x + off;
       uint16_t* cb = c + off;
       uint16_t* sb = staging ? staging + i * (uint64_t)block_len + first : nullptr;
-      const uint32_t head = mixed_head(xb, cb, len);
+      const uint32_t head = WHOLE ? 0 : mixed_head(xb, cb, len);
       // the staging row takes whole units too if it has the phase of c's row
       const bool vec_staging = sb && (((uintptr_t)sb ^ (uintptr_t)cb) & 7) == 0;
       const uint32_t nunit = (len - head) / kMixUnit, tail0 = head + nunit * kMixUnit;
       // the few elements around the whole units are asked for together with the first units when
       // the group has a lane for each of them; a row walked element by element loops instead
-      const bool ends_in_lanes = G >= kMixUnit && head < (uint32_t)kMixUnit;
+      const bool ends_in_lanes = !WHOLE && G >= kMixUnit && head < (uint32_t)kMixUnit;
       const bool has_head = ends_in_lanes && (uint32_t)lane < head, has_tail = ends_in_lanes && tail0 + lane < len;
       uint32_t hx = 0, tx = 0;
       if (has_head) hx = __float_as_uint(xb[lane]);
@@ -216,7 +219,7 @@ __global__ __launch_bounds__(kWG) void k_mixed_commit(const float* __restrict__ 
 
 // Recovery and/or norm over the blocks idx[0..n_idx) (idx == NULL: blocks 0..n_idx), with T
 // threads per workgroup (1,024 for long index lists, so that no group takes a second entry).
-template <int G, int T, bool STORE, bool NORM>
+template <int G, int T, bool STORE, bool NORM, bool WHOLE>
 __global__ __launch_bounds__(T) void k_mixed_recover(float* __restrict__ x, const uint16_t* __restrict__ c,
                                                      const uint32_t* __restrict__ idx, uint32_t n_idx,
                                                      uint64_t n_elems, uint32_t block_len,
@@ -238,9 +241,9 @@ __global__ __launch_bounds__(T) void k_mixed_recover(float* __restrict__ x, cons
         continue;
       float* xb = x + off;
       const uint16_t* cb = packed ? c + i * (uint64_t)block_len + first : c + off;
-      const uint32_t head = mixed_head(xb, cb, len);
+      const uint32_t head = WHOLE ? 0 : mixed_head(xb, cb, len);
       const uint32_t nunit = (len - head) / kMixUnit, tail0 = head + nunit * kMixUnit;
-      const bool ends_in_lanes = G >= kMixUnit && head < (uint32_t)kMixUnit;  // as in k_mixed_commit
+      const bool ends_in_lanes = !WHOLE && G >= kMixUnit && head < (uint32_t)kMixUnit;  // as in k_mixed_commit
       const bool has_head = ends_in_lanes && (uint32_t)lane < head, has_tail = ends_in_lanes && tail0 + lane < len;
       float hc = 0, hx = 0, tc = 0, tx = 0;
       if (has_head) {
@@ -300,6 +303,11 @@ static bool mixed_vec(const void* x, const void* c) {
 
 // Rows of whole units: packed rows (staging, rows read back) then share the phase of the store's rows.
 static bool unit_rows(const scar_layout* l) { return l->block_len % kMixUnit == 0; }
+
+// Every row starts on a unit boundary of both streams and is made of whole units.
+static bool mixed_whole(const scar_layout* l, const void* x, const void* c) {
+  return aligned(x, 16) && aligned(c, 8) && unit_rows(l);
+}
 
 // Lanes per row of the copy kernels: one per unit, and at least 4 for rows that are not whole
 // units, so that the elements around the units each find a lane.
@@ -395,22 +403,26 @@ int mixed_commit(const scar_layout* l, uint32_t n_blocks, const void* x, void* c
       (staging && !aligned(staging, 2)))
     return SCAR_ERR_INVALID_ARG;
   const bool vec = mixed_vec(x, c);
+  const bool whole = mixed_whole(l, x, c);
   const uint32_t pieces = mixed_pieces(l, vec);
   const int g = pieces > 1 ? 256 : mixed_copy_group(l, vec);
 #define CALL(G)                                                                                     \
   {                                                                                                 \
     constexpr int GPW = (G == 256) ? 1 : kWG / G;                                                   \
     const RowGrid rg = row_grid(((uint64_t)n_idx + GPW - 1) / GPW, pieces, kCopyGridCap);           \
-    launch((k_mixed_commit<G>), dim3(rg.x, rg.y),                                                   \
-                       dim3(kWG), 0, st, (const float*)x, (uint16_t*)c, idx, n_idx,                 \
-                       (uint16_t*)staging, l->n_elems, l->block_len, n_blocks, pieces);             \
+    if (whole)                                                                                      \
+      launch((k_mixed_commit<G, true>), dim3(rg.x, rg.y), dim3(kWG), 0, st, (const float*)x, (uint16_t*)c, idx, \
+             n_idx, (uint16_t*)staging, l->n_elems, l->block_len, n_blocks, pieces);                \
+    else                                                                                            \
+      launch((k_mixed_commit<G, false>), dim3(rg.x, rg.y), dim3(kWG), 0, st, (const float*)x, (uint16_t*)c, idx, \
+             n_idx, (uint16_t*)staging, l->n_elems, l->block_len, n_blocks, pieces);                \
   }
   SCAR_FOR_GROUP(g, CALL)
 #undef CALL
   return launch_status();
 }
 
-template <bool STORE, bool NORM>
+template <bool STORE, bool NORM, bool WHOLE>
 static uint32_t launch_mixed_recover(int g, const scar_layout* l, uint32_t n_blocks, void* x,
                                      const void* c, const uint32_t* idx, uint32_t n_idx, uint32_t pieces,
                                      bool packed, void* partial, hipStream_t st) {
@@ -420,7 +432,7 @@ static uint32_t launch_mixed_recover(int g, const scar_layout* l, uint32_t n_blo
   {                                                                                                   \
     const RowGrid rg = row_grid(((uint64_t)n_idx + (T / G) - 1) / (T / G), pieces, kMaxNormGrid);     \
     grid = rg.x, grid_y = rg.y;                                                                       \
-    launch((k_mixed_recover<G, T, STORE, NORM>), dim3(grid, grid_y), dim3(T), 0, st,      \
+    launch((k_mixed_recover<G, T, STORE, NORM, WHOLE>), dim3(grid, grid_y), dim3(T), 0, st, \
                        (float*)x, (const uint16_t*)c, idx, n_idx, l->n_elems, l->block_len, n_blocks, \
                        pieces, packed, (double*)partial);                                             \
   }
@@ -487,12 +499,17 @@ int mixed_recover_or_norm(bool store, bool packed, const scar_layout* l, uint32_
     launch_finish(l->dtype, partial, grid, norm_out, st);
     return launch_status();
   }
+  const bool whole = mixed_whole(l, x, c);  // c = packed rows included: rows of whole units keep its phase
+#define RUN(STORE, NORM, PARTIAL)                                                                              \
+  (whole ? launch_mixed_recover<STORE, NORM, true>(g, l, n_blocks, x, c, idx, n_idx, pieces, packed, PARTIAL, st) \
+         : launch_mixed_recover<STORE, NORM, false>(g, l, n_blocks, x, c, idx, n_idx, pieces, packed, PARTIAL, st))
   if (store && norm_out)
-    n_partial = launch_mixed_recover<true, true>(g, l, n_blocks, x, c, idx, n_idx, pieces, packed, partial, st);
+    n_partial = RUN(true, true, partial);
   else if (store)
-    launch_mixed_recover<true, false>(g, l, n_blocks, x, c, idx, n_idx, pieces, packed, nullptr, st);
+    RUN(true, false, nullptr);
   else
-    n_partial = launch_mixed_recover<false, true>(g, l, n_blocks, x, c, idx, n_idx, pieces, packed, partial, st);
+    n_partial = RUN(false, true, partial);
+#undef RUN
   if (norm_out) launch_finish(l->dtype, partial, n_partial, norm_out, st);
   return launch_status();
 }
