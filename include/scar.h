@@ -41,9 +41,10 @@
  *     are 16-byte aligned and block_len * element size is a multiple of 16 the kernels
  *     use 16-byte accesses throughout (fastest).  Otherwise every row is walked as a few
  *     leading elements, a 16-byte body and a tail, which needs x and c at the same offset
- *     within their 16-byte lines; if they are not, rows are walked element by element.
- *     Copies and integer results are identical in every case, float sums up to the order
- *     of the additions.
+ *     within their 16-byte lines; if they are not, rows are walked element by element
+ *     (SCAR_F32_BF16C: 16 bytes of x against 8 bytes of c; the two addresses, counted in
+ *     elements, must agree modulo 4).  Copies and integer results are identical in every
+ *     case, float sums up to the order of the additions.
  *   - Index lists (idx, lost_idx) hold block numbers < n_blocks without repeats, in any
  *     order (ascending is fastest).  This is not checked on the host (the lists live in
  *     device memory); on the device an entry >= n_blocks is skipped, and a repeated
